@@ -1,0 +1,434 @@
+/*
+ * CPU oracle of the CCL-D decision analyzer's cross-rank anomaly computation.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, single-threaded
+ * statement of what the analyzer computes; tests and the benchmark's CPU
+ * baseline call it, the GPU library never does, and the two share no code.
+ *
+ * Every step below follows the paper's decision analyzer (Section 4.2):
+ * metrics are grouped by communicator and by Trace ID (communicator id,
+ * operation counter; Section 5.1), each round's per-rank Duration Time
+ * (Section 4.1.2) gives T_max and T_min, Eq. 1-3 detect a slow communicator,
+ * Eq. 4 attributes it, and the hang rules of Sections 4.2.1 / 4.2.2 raise and
+ * classify hang alerts.  The cross-rank arrival/completion statistics (lower
+ * median, median absolute deviation, per-rank lag) are the statistical test
+ * that stands in for the paper's "theta determined statistically".
+ *
+ * All arithmetic is 64-bit integer; products are compared in 128 bits, so no
+ * ratio is ever materialised.  Medians are found by fully sorting a copy.
+ *
+ * Pinned by tests/test_oracle_*.py (closed forms of Eq. 1-4, brute force,
+ * invariants, injected-fault recovery).  The choices the paper leaves open
+ * (segment usability, detection groups by operation type and size class,
+ * watermarks under re-analysis, tie rules) are this build's definitions and
+ * are "parity unpinned" by the paper itself.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_INFLIGHT INT64_MAX
+#define ORC_NO_RANK 0xFFFFFFFFll
+
+enum { ORC_OK = 0, ORC_E_UNKNOWN_COMM = -1, ORC_E_RANK_NOT_MEMBER = -2, ORC_E_RANGE = -3,
+       ORC_E_DUPLICATE_KEY = -4, ORC_E_SNAPSHOT_GAP = -5, ORC_E_BAD_ARG = -6 };
+
+/* parameter vector (int64 each) */
+enum { P_HANG_THRESHOLD_NS, P_TBASE_INIT_NS, P_TBASE_ROUNDS, P_TBASE_WARMUP_NS, P_THETA_NUM, P_THETA_DEN,
+       P_ALPHA_NUM, P_BETA_NUM, P_AB_DEN, P_REPEAT_THRESHOLD, P_BARRIER_BYTES, P_KMAD_NUM, P_KMAD_DEN,
+       P_LAG_FLOOR_NS, P_STALL_SNAPSHOTS, P_FIFO_DEPTH, P_COUNT };
+
+enum { OP_ALLREDUCE = 0, OP_MAX = 16, CLS_MAX = 64 };
+
+/* segment state bits */
+enum { SEG_COMPLETE = 1, SEG_CONSISTENT = 2, SEG_BARRIER = 4, SEG_USABLE = 8 };
+enum { FLAG_LATE_ENTER = 1, FLAG_LATE_EXIT = 2 };
+
+/* table layouts: every table is a row-major int64 matrix */
+enum { SEG_COMM, SEG_SEQ, SEG_N, SEG_INFLIGHT, SEG_STATE, SEG_OP, SEG_BYTES,
+       SEG_ENTER_MIN, SEG_ENTER_MED, SEG_ENTER_MAX, SEG_ENTER_MAD,
+       SEG_EXIT_MIN, SEG_EXIT_MED, SEG_EXIT_MAX, SEG_EXIT_MAD,
+       SEG_DUR_MIN, SEG_DUR_MAX, SEG_ARGMIN_RANK, SEG_ARGMAX_RANK, SEG_INFLIGHT_ENTER_MIN, SEG_NCOL };
+enum { FLG_COMM, FLG_SEQ, FLG_RANK, FLG_KIND, FLG_LAG_ENTER, FLG_LAG_EXIT, FLG_NCOL };
+enum { GRP_COMM, GRP_OP, GRP_CLS, GRP_N_USABLE, GRP_RSTAR_SEQ, GRP_TMAX, GRP_TMIN, GRP_TBASE, GRP_STATIC,
+       GRP_FROZEN, GRP_M, GRP_SLOW, GRP_CLASS, GRP_ROOT_S1, GRP_ROOT_S2, GRP_REPEATS, GRP_LOCATE, GRP_NCOL };
+enum { ALR_COMM, ALR_SEQ, ALR_AGE, ALR_CLASS, ALR_NCAND, ALR_CAND_OFF, ALR_NCOL };
+enum { BLM_N_LATE_ENTER, BLM_N_LATE_EXIT, BLM_SUM_LAG_ENTER, BLM_SUM_LAG_EXIT, BLM_N_RECORDS, BLM_NCOL };
+enum { REC_LAG_ENTER, REC_LAG_EXIT, REC_FLAG, REC_NCOL };
+
+typedef struct {
+  uint32_t n_ranks, n_comms;
+  const uint8_t *algo;
+  const uint32_t *size, *member_off, *members;
+  const int32_t *tree_parent;
+} orc_topology;
+
+typedef struct {
+  int32_t status;
+  uint64_t n, n_seg, n_flag, n_group, n_alert, n_cand, n_ranks;
+  uint64_t *perm;     /* [n]  input index of the j-th record in (comm, seq, rank) order */
+  int64_t *rec;       /* [n][REC_NCOL]  per sorted record */
+  int64_t *seg;       /* [n_seg][SEG_NCOL] */
+  int64_t *flag;      /* [n_flag][FLG_NCOL]  ordered by (comm, seq, rank) */
+  int64_t *group;     /* [n_group][GRP_NCOL] ordered by (comm, op, cls) */
+  int64_t *alert;     /* [n_alert][ALR_NCOL] ordered by (comm, seq) */
+  int64_t *cand;      /* [n_cand] candidate ranks of the alerts, ascending per alert */
+  int64_t *blame;     /* [n_ranks][BLM_NCOL] */
+  int64_t *order;     /* [n_ranks] ranks by (n_flags desc, sum_lag desc, rank asc) */
+} orc_window_result;
+
+/* per detection group (communicator, operation, size class): Eq. 1 state and the repetition counter */
+typedef struct {
+  uint32_t cnt, frozen, repeats, pad;
+  int64_t sum, t0, tbase_dyn;
+  uint64_t baselined_wm;      /* seq+1 of the last round visited for Eq. 1 (0 = none) */
+  uint64_t baseline_last_seq; /* seq of the last round summed into the baseline */
+  uint64_t detected_wm;       /* seq+1 of the last round counted as a slow detection */
+} orc_group_state;
+
+typedef struct {
+  uint32_t n_comms;
+  orc_group_state *g;         /* [n_comms][OP_MAX][CLS_MAX] */
+} orc_state;
+
+/* ------------------------------------------------------------------ */
+orc_state *orc_state_create(uint32_t n_comms) {
+  orc_state *s = (orc_state *)calloc(1, sizeof(orc_state));
+  if (!s) return NULL;
+  s->n_comms = n_comms;
+  s->g = (orc_group_state *)calloc((size_t)n_comms * OP_MAX * CLS_MAX, sizeof(orc_group_state));
+  if (!s->g) { free(s); return NULL; }
+  return s;
+}
+void orc_state_destroy(orc_state *s) { if (s) { free(s->g); free(s); } }
+
+void orc_window_result_free(orc_window_result *r) {
+  if (!r) return;
+  free(r->perm); free(r->rec); free(r->seg); free(r->flag); free(r->group);
+  free(r->alert); free(r->cand); free(r->blame); free(r->order);
+  memset(r, 0, sizeof(*r));
+}
+
+/* ------------------------------------------------------------------ */
+typedef struct {
+  const uint32_t *rank, *comm; const uint64_t *seq;
+} key_cols;
+static key_cols g_kc;   /* comparison context for qsort (the oracle is single-threaded) */
+
+static int cmp_record(const void *pa, const void *pb) {
+  uint64_t a = *(const uint64_t *)pa, b = *(const uint64_t *)pb;
+  if (g_kc.comm[a] != g_kc.comm[b]) return g_kc.comm[a] < g_kc.comm[b] ? -1 : 1;
+  if (g_kc.seq[a] != g_kc.seq[b]) return g_kc.seq[a] < g_kc.seq[b] ? -1 : 1;
+  if (g_kc.rank[a] != g_kc.rank[b]) return g_kc.rank[a] < g_kc.rank[b] ? -1 : 1;
+  return 0;
+}
+static int cmp_i64(const void *pa, const void *pb) {
+  int64_t a = *(const int64_t *)pa, b = *(const int64_t *)pb;
+  return a < b ? -1 : (a > b ? 1 : 0);
+}
+
+/* lower median: element floor((n-1)/2) of the ascending order */
+static int64_t lower_median(const int64_t *v, size_t n, int64_t *scratch) {
+  memcpy(scratch, v, n * sizeof(int64_t));
+  qsort(scratch, n, sizeof(int64_t), cmp_i64);
+  return scratch[(n - 1) / 2];
+}
+static int64_t abs_diff(int64_t a, int64_t b) { return a >= b ? a - b : b - a; }
+
+static int is_member(const orc_topology *t, uint32_t comm, uint32_t rank) {
+  uint32_t o = t->member_off[comm];
+  for (uint32_t i = 0; i < t->size[comm]; ++i) if (t->members[o + i] == rank) return 1;
+  return 0;
+}
+static int floor_log2_u64(uint64_t b) { int c = 0; if (b == 0) b = 1; while (b >>= 1) ++c; return c; }
+
+typedef struct { uint32_t comm, op, cls; uint64_t seq, seg; } grp_item;
+static int cmp_grp_item(const void *pa, const void *pb) {
+  const grp_item *a = (const grp_item *)pa, *b = (const grp_item *)pb;
+  if (a->comm != b->comm) return a->comm < b->comm ? -1 : 1;
+  if (a->op != b->op) return a->op < b->op ? -1 : 1;
+  if (a->cls != b->cls) return a->cls < b->cls ? -1 : 1;
+  if (a->seq != b->seq) return a->seq < b->seq ? -1 : 1;
+  return 0;
+}
+
+static const int64_t *g_blame;
+static int cmp_blame_order(const void *pa, const void *pb) {
+  int64_t a = *(const int64_t *)pa, b = *(const int64_t *)pb;
+  const int64_t *ba = g_blame + a * BLM_NCOL, *bb = g_blame + b * BLM_NCOL;
+  int64_t na = ba[BLM_N_LATE_ENTER] + ba[BLM_N_LATE_EXIT], nb = bb[BLM_N_LATE_ENTER] + bb[BLM_N_LATE_EXIT];
+  if (na != nb) return na > nb ? -1 : 1;
+  int64_t sa = (int64_t)((uint64_t)ba[BLM_SUM_LAG_ENTER] + (uint64_t)ba[BLM_SUM_LAG_EXIT]);
+  int64_t sb = (int64_t)((uint64_t)bb[BLM_SUM_LAG_ENTER] + (uint64_t)bb[BLM_SUM_LAG_EXIT]);
+  if (sa != sb) return sa > sb ? -1 : 1;
+  return a < b ? -1 : (a > b ? 1 : 0);
+}
+
+/* ------------------------------------------------------------------ */
+int orc_analyze_window(const int64_t *P, const orc_topology *T, uint64_t n,
+                       const uint32_t *rank, const uint32_t *comm, const uint64_t *seq, const uint8_t *op,
+                       const uint64_t *bytes, const int64_t *t_enter, const int64_t *t_exit,
+                       int64_t now_ns, orc_state *st, orc_window_result *R) {
+  memset(R, 0, sizeof(*R));
+  R->n = n; R->n_ranks = T->n_ranks;
+  if (!st || st->n_comms != T->n_comms || P[P_TBASE_ROUNDS] < 1 || P[P_THETA_DEN] < 1 || P[P_AB_DEN] < 1 ||
+      P[P_KMAD_DEN] < 1) { R->status = ORC_E_BAD_ARG; return R->status; }
+
+  /* ---- validation: the status does not depend on the order of the records ---- */
+  int bad_comm = 0, bad_member = 0, bad_range = 0;
+  for (uint64_t i = 0; i < n; ++i) {
+    if (comm[i] >= T->n_comms) { bad_comm = 1; continue; }
+    if (rank[i] >= T->n_ranks || !is_member(T, comm[i], rank[i])) bad_member = 1;
+    if (op[i] >= OP_MAX || t_enter[i] < 0 || t_enter[i] == ORC_INFLIGHT || t_exit[i] < t_enter[i]) bad_range = 1;
+  }
+  if (bad_comm) { R->status = ORC_E_UNKNOWN_COMM; return R->status; }
+  if (bad_member) { R->status = ORC_E_RANK_NOT_MEMBER; return R->status; }
+  if (bad_range) { R->status = ORC_E_RANGE; return R->status; }
+
+  /* ---- group by Trace ID (communicator, operation counter), ranks ascending inside a round ---- */
+  uint64_t *perm = (uint64_t *)malloc((n ? n : 1) * sizeof(uint64_t));
+  for (uint64_t i = 0; i < n; ++i) perm[i] = i;
+  g_kc.rank = rank; g_kc.comm = comm; g_kc.seq = seq;
+  qsort(perm, n, sizeof(uint64_t), cmp_record);
+  R->perm = perm;
+  for (uint64_t j = 1; j < n; ++j)
+    if (cmp_record(&perm[j - 1], &perm[j]) == 0) { R->status = ORC_E_DUPLICATE_KEY; return R->status; }
+
+  uint64_t n_seg = 0;
+  for (uint64_t j = 0; j < n; ++j)
+    if (j == 0 || comm[perm[j]] != comm[perm[j - 1]] || seq[perm[j]] != seq[perm[j - 1]]) ++n_seg;
+  R->n_seg = n_seg;
+  R->seg = (int64_t *)calloc((n_seg ? n_seg : 1) * SEG_NCOL, sizeof(int64_t));
+  R->rec = (int64_t *)calloc((n ? n : 1) * REC_NCOL, sizeof(int64_t));
+  R->blame = (int64_t *)calloc((size_t)(T->n_ranks ? T->n_ranks : 1) * BLM_NCOL, sizeof(int64_t));
+  R->order = (int64_t *)calloc(T->n_ranks ? T->n_ranks : 1, sizeof(int64_t));
+  uint64_t *seg_first = (uint64_t *)malloc((n_seg + 1) * sizeof(uint64_t));
+
+  uint32_t max_size = 1;
+  for (uint64_t j = 0, s = 0; j < n; ++j)
+    if (j == 0 || comm[perm[j]] != comm[perm[j - 1]] || seq[perm[j]] != seq[perm[j - 1]]) seg_first[s++] = j;
+  seg_first[n_seg] = n;
+  for (uint64_t s = 0; s < n_seg; ++s)
+    if (seg_first[s + 1] - seg_first[s] > max_size) max_size = (uint32_t)(seg_first[s + 1] - seg_first[s]);
+  int64_t *va = (int64_t *)malloc(max_size * sizeof(int64_t));
+  int64_t *vb = (int64_t *)malloc(max_size * sizeof(int64_t));
+  int64_t *vs = (int64_t *)malloc(max_size * sizeof(int64_t));
+
+  uint64_t n_flag = 0, n_alert = 0, n_cand = 0;
+  /* ---- per-round state and statistics ---- */
+  for (uint64_t s = 0; s < n_seg; ++s) {
+    int64_t *S = R->seg + s * SEG_NCOL;
+    uint64_t a = seg_first[s], b = seg_first[s + 1];
+    uint64_t i0 = perm[a];
+    uint32_t c = comm[i0];
+    uint64_t nn = b - a, n_infl = 0, n_done = 0;
+    int consistent = 1;
+    int64_t infl_enter_min = ORC_INFLIGHT;
+    for (uint64_t j = a; j < b; ++j) {
+      uint64_t i = perm[j];
+      if (op[i] != op[i0] || bytes[i] != bytes[i0]) consistent = 0;
+      if (t_exit[i] == ORC_INFLIGHT) { ++n_infl; if (t_enter[i] < infl_enter_min) infl_enter_min = t_enter[i]; }
+    }
+    int complete = (nn == T->size[c]) && n_infl == 0;
+    int barrier = (op[i0] == OP_ALLREDUCE) && (bytes[i0] < (uint64_t)P[P_BARRIER_BYTES]);
+    int usable = complete && consistent && !barrier;
+    S[SEG_COMM] = c; S[SEG_SEQ] = (int64_t)seq[i0]; S[SEG_N] = (int64_t)nn; S[SEG_INFLIGHT] = (int64_t)n_infl;
+    S[SEG_STATE] = (complete ? SEG_COMPLETE : 0) | (consistent ? SEG_CONSISTENT : 0) |
+                   (barrier ? SEG_BARRIER : 0) | (usable ? SEG_USABLE : 0);
+    S[SEG_OP] = op[i0]; S[SEG_BYTES] = (int64_t)bytes[i0];
+    S[SEG_INFLIGHT_ENTER_MIN] = infl_enter_min;
+    S[SEG_ARGMIN_RANK] = ORC_NO_RANK; S[SEG_ARGMAX_RANK] = ORC_NO_RANK;
+    /* statistics over the records of this round that have completed */
+    int64_t dmin = 0, dmax = 0;
+    for (uint64_t j = a; j < b; ++j) {
+      uint64_t i = perm[j];
+      if (t_exit[i] == ORC_INFLIGHT) continue;
+      va[n_done] = t_enter[i]; vb[n_done] = t_exit[i];
+      int64_t d = t_exit[i] - t_enter[i];               /* Duration Time of this rank */
+      if (n_done == 0 || d < dmin) { dmin = d; S[SEG_ARGMIN_RANK] = rank[i]; }   /* tie -> smallest rank */
+      if (n_done == 0 || d > dmax) { dmax = d; S[SEG_ARGMAX_RANK] = rank[i]; }
+      ++n_done;
+    }
+    if (n_done > 0) {
+      int64_t emin = va[0], emax = va[0], xmin = vb[0], xmax = vb[0];
+      for (uint64_t k = 1; k < n_done; ++k) {
+        if (va[k] < emin) emin = va[k];
+        if (va[k] > emax) emax = va[k];
+        if (vb[k] < xmin) xmin = vb[k];
+        if (vb[k] > xmax) xmax = vb[k];
+      }
+      int64_t emed = lower_median(va, n_done, vs), xmed = lower_median(vb, n_done, vs);
+      for (uint64_t k = 0; k < n_done; ++k) { va[k] = abs_diff(va[k], emed); vb[k] = abs_diff(vb[k], xmed); }
+      int64_t emad = lower_median(va, n_done, vs), xmad = lower_median(vb, n_done, vs);
+      S[SEG_ENTER_MIN] = emin; S[SEG_ENTER_MED] = emed; S[SEG_ENTER_MAX] = emax; S[SEG_ENTER_MAD] = emad;
+      S[SEG_EXIT_MIN] = xmin; S[SEG_EXIT_MED] = xmed; S[SEG_EXIT_MAX] = xmax; S[SEG_EXIT_MAD] = xmad;
+      S[SEG_DUR_MIN] = dmin; S[SEG_DUR_MAX] = dmax;
+    }
+    /* per-rank lag and slow-rank flags, on usable rounds only */
+    if (usable) {
+      for (uint64_t j = a; j < b; ++j) {
+        uint64_t i = perm[j];
+        int64_t le = t_enter[i] - S[SEG_ENTER_MED], lx = t_exit[i] - S[SEG_EXIT_MED];
+        int f = 0;
+        if (le > P[P_LAG_FLOOR_NS] &&
+            (__int128)le * (__int128)P[P_KMAD_DEN] > (__int128)P[P_KMAD_NUM] * (__int128)S[SEG_ENTER_MAD])
+          f |= FLAG_LATE_ENTER;
+        if (lx > P[P_LAG_FLOOR_NS] &&
+            (__int128)lx * (__int128)P[P_KMAD_DEN] > (__int128)P[P_KMAD_NUM] * (__int128)S[SEG_EXIT_MAD])
+          f |= FLAG_LATE_EXIT;
+        R->rec[j * REC_NCOL + REC_LAG_ENTER] = le;
+        R->rec[j * REC_NCOL + REC_LAG_EXIT] = lx;
+        R->rec[j * REC_NCOL + REC_FLAG] = f;
+        if (f) ++n_flag;
+      }
+    }
+    /* hang alert: an operation still in flight for longer than the threshold, barriers excepted */
+    if (n_infl > 0 && !barrier && now_ns - infl_enter_min > P[P_HANG_THRESHOLD_NS]) {
+      ++n_alert;
+      if (nn < T->size[c]) n_cand += T->size[c] - nn; else n_cand += n_done;
+    }
+  }
+  for (uint64_t i = 0; i < n; ++i) R->blame[(size_t)rank[i] * BLM_NCOL + BLM_N_RECORDS] += 1;
+
+  /* ---- flag list (already in (comm, seq, rank) order) and per-rank blame ---- */
+  R->n_flag = n_flag;
+  R->flag = (int64_t *)calloc((n_flag ? n_flag : 1) * FLG_NCOL, sizeof(int64_t));
+  for (uint64_t j = 0, k = 0; j < n; ++j) {
+    int64_t f = R->rec[j * REC_NCOL + REC_FLAG];
+    if (!f) continue;
+    uint64_t i = perm[j];
+    int64_t *F = R->flag + k * FLG_NCOL; ++k;
+    F[FLG_COMM] = comm[i]; F[FLG_SEQ] = (int64_t)seq[i]; F[FLG_RANK] = rank[i]; F[FLG_KIND] = f;
+    F[FLG_LAG_ENTER] = R->rec[j * REC_NCOL + REC_LAG_ENTER];
+    F[FLG_LAG_EXIT] = R->rec[j * REC_NCOL + REC_LAG_EXIT];
+    int64_t *B = R->blame + (size_t)rank[i] * BLM_NCOL;
+    if (f & FLAG_LATE_ENTER) {
+      B[BLM_N_LATE_ENTER] += 1;
+      B[BLM_SUM_LAG_ENTER] = (int64_t)((uint64_t)B[BLM_SUM_LAG_ENTER] + (uint64_t)F[FLG_LAG_ENTER]);
+    }
+    if (f & FLAG_LATE_EXIT) {
+      B[BLM_N_LATE_EXIT] += 1;
+      B[BLM_SUM_LAG_EXIT] = (int64_t)((uint64_t)B[BLM_SUM_LAG_EXIT] + (uint64_t)F[FLG_LAG_EXIT]);
+    }
+  }
+  for (uint32_t r = 0; r < T->n_ranks; ++r) R->order[r] = r;
+  g_blame = R->blame;
+  qsort(R->order, T->n_ranks, sizeof(int64_t), cmp_blame_order);
+
+  /* ---- hang alerts with the first two branches of the hang decision tree ---- */
+  R->n_alert = n_alert; R->n_cand = n_cand;
+  R->alert = (int64_t *)calloc((n_alert ? n_alert : 1) * ALR_NCOL, sizeof(int64_t));
+  R->cand = (int64_t *)calloc(n_cand ? n_cand : 1, sizeof(int64_t));
+  {
+    uint64_t ka = 0, kc = 0;
+    int64_t *tmp = (int64_t *)malloc((size_t)(T->n_ranks ? T->n_ranks : 1) * sizeof(int64_t));
+    for (uint64_t s = 0; s < n_seg; ++s) {
+      int64_t *S = R->seg + s * SEG_NCOL;
+      if (!(S[SEG_INFLIGHT] > 0 && !(S[SEG_STATE] & SEG_BARRIER) &&
+            now_ns - S[SEG_INFLIGHT_ENTER_MIN] > P[P_HANG_THRESHOLD_NS])) continue;
+      uint64_t a = seg_first[s], b = seg_first[s + 1];
+      uint32_t c = (uint32_t)S[SEG_COMM];
+      int64_t *A = R->alert + ka * ALR_NCOL; ++ka;
+      A[ALR_COMM] = c; A[ALR_SEQ] = S[SEG_SEQ]; A[ALR_AGE] = now_ns - S[SEG_INFLIGHT_ENTER_MIN];
+      A[ALR_CAND_OFF] = (int64_t)kc;
+      uint64_t m = 0;
+      if ((uint64_t)S[SEG_N] < T->size[c]) {
+        /* a member with no record for this operation counter has not entered: Not-Entered-Hang */
+        A[ALR_CLASS] = 1;
+        for (uint32_t q = 0; q < T->size[c]; ++q) {
+          uint32_t r = T->members[T->member_off[c] + q];
+          int present = 0;
+          for (uint64_t j = a; j < b; ++j) if (rank[perm[j]] == r) { present = 1; break; }
+          if (!present) tmp[m++] = r;
+        }
+      } else if ((uint64_t)S[SEG_INFLIGHT] < (uint64_t)S[SEG_N]) {
+        /* everyone entered and some ranks are not hung: Inconsistent-Hang, the non-hang ranks are the root */
+        A[ALR_CLASS] = 2;
+        for (uint64_t j = a; j < b; ++j) if (t_exit[perm[j]] != ORC_INFLIGHT) tmp[m++] = rank[perm[j]];
+      } else {
+        A[ALR_CLASS] = 3;   /* all ranks hung: needs the Send/Recv counters (orc_locate_hang) */
+      }
+      qsort(tmp, m, sizeof(int64_t), cmp_i64);
+      for (uint64_t q = 0; q < m; ++q) R->cand[kc++] = tmp[q];
+      A[ALR_NCAND] = (int64_t)m;
+    }
+    free(tmp);
+  }
+
+  /* ---- slow detection and location per detection group (Eq. 1-4) ---- */
+  uint64_t n_us = 0;
+  for (uint64_t s = 0; s < n_seg; ++s) if (R->seg[s * SEG_NCOL + SEG_STATE] & SEG_USABLE) ++n_us;
+  grp_item *items = (grp_item *)malloc((n_us ? n_us : 1) * sizeof(grp_item));
+  for (uint64_t s = 0, k = 0; s < n_seg; ++s) {
+    const int64_t *S = R->seg + s * SEG_NCOL;
+    if (!(S[SEG_STATE] & SEG_USABLE)) continue;
+    items[k].comm = (uint32_t)S[SEG_COMM]; items[k].op = (uint32_t)S[SEG_OP];
+    items[k].cls = (uint32_t)floor_log2_u64((uint64_t)S[SEG_BYTES]);
+    items[k].seq = (uint64_t)S[SEG_SEQ]; items[k].seg = s; ++k;
+  }
+  qsort(items, n_us, sizeof(grp_item), cmp_grp_item);
+  uint64_t n_group = 0;
+  for (uint64_t k = 0; k < n_us; ++k)
+    if (k == 0 || items[k].comm != items[k - 1].comm || items[k].op != items[k - 1].op ||
+        items[k].cls != items[k - 1].cls) ++n_group;
+  R->n_group = n_group;
+  R->group = (int64_t *)calloc((n_group ? n_group : 1) * GRP_NCOL, sizeof(int64_t));
+  for (uint64_t k0 = 0, gi = 0; k0 < n_us; ++gi) {
+    uint64_t k1 = k0 + 1;
+    while (k1 < n_us && items[k1].comm == items[k0].comm && items[k1].op == items[k0].op &&
+           items[k1].cls == items[k0].cls) ++k1;
+    orc_group_state *G = st->g + ((size_t)items[k0].comm * OP_MAX + items[k0].op) * CLS_MAX + items[k0].cls;
+    /* Eq. 1: average T_max of the first m rounds; m = min(tbase_rounds, rounds inside the warm-up span) */
+    for (uint64_t k = k0; k < k1; ++k) {
+      const int64_t *S = R->seg + items[k].seg * SEG_NCOL;
+      if (items[k].seq + 1 <= G->baselined_wm) continue;
+      if (!G->frozen) {
+        if (G->cnt == 0) G->t0 = S[SEG_ENTER_MIN];
+        if (G->cnt < (uint64_t)P[P_TBASE_ROUNDS] && S[SEG_ENTER_MIN] - G->t0 <= P[P_TBASE_WARMUP_NS]) {
+          G->sum += S[SEG_DUR_MAX]; G->cnt += 1; G->baseline_last_seq = items[k].seq;
+        } else {
+          G->frozen = 1; G->tbase_dyn = G->sum / (int64_t)G->cnt;
+        }
+      }
+      G->baselined_wm = items[k].seq + 1;
+    }
+    /* Eq. 2: the round of this window with the largest intra-round range (tie -> smallest seq) */
+    uint64_t kstar = k0;
+    int64_t best = 0;
+    for (uint64_t k = k0; k < k1; ++k) {
+      const int64_t *S = R->seg + items[k].seg * SEG_NCOL;
+      int64_t range = S[SEG_DUR_MAX] - S[SEG_DUR_MIN];
+      if (k == k0 || range > best) { best = range; kstar = k; }
+    }
+    const int64_t *Sx = R->seg + items[kstar].seg * SEG_NCOL;
+    int64_t tmax = Sx[SEG_DUR_MAX], tmin = Sx[SEG_DUR_MIN];
+    /* Eq. 1 case split: the configured baseline applies while the round is among the first m */
+    int dynamic = G->frozen && items[kstar].seq > G->baseline_last_seq;
+    int64_t tbase = dynamic ? G->tbase_dyn : P[P_TBASE_INIT_NS];
+    /* Eq. 3: R = (T_max - T_base)/T_base > theta, cross-multiplied */
+    int slow = (__int128)(tmax - tbase) * (__int128)P[P_THETA_DEN] > (__int128)P[P_THETA_NUM] * (__int128)tbase;
+    int cls = 0;
+    int64_t root1 = ORC_NO_RANK;
+    if (slow) {
+      /* Eq. 4: P = (T_max - T_min)/(T_max - T_base); P > beta: computation-slow, P < alpha: communication-slow */
+      __int128 num = (__int128)(tmax - tmin) * (__int128)P[P_AB_DEN];
+      __int128 den = (__int128)(tmax - tbase);
+      if (num > (__int128)P[P_BETA_NUM] * den) cls = 1;
+      else if (num < (__int128)P[P_ALPHA_NUM] * den) cls = 2;
+      else cls = 3;
+      if (cls != 2) root1 = Sx[SEG_ARGMIN_RANK];   /* the rank with minimal communication time */
+      if (items[kstar].seq + 1 > G->detected_wm) { G->repeats += 1; G->detected_wm = items[kstar].seq + 1; }
+    }
+    int64_t *O = R->group + gi * GRP_NCOL;
+    O[GRP_COMM] = items[k0].comm; O[GRP_OP] = items[k0].op; O[GRP_CLS] = items[k0].cls;
+    O[GRP_N_USABLE] = (int64_t)(k1 - k0); O[GRP_RSTAR_SEQ] = (int64_t)items[kstar].seq;
+    O[GRP_TMAX] = tmax; O[GRP_TMIN] = tmin; O[GRP_TBASE] = tbase; O[GRP_STATIC] = !dynamic;
+    O[GRP_FROZEN] = G->frozen; O[GRP_M] = G->cnt; O[GRP_SLOW] = slow; O[GRP_CLASS] = cls;
+    O[GRP_ROOT_S1] = root1; O[GRP_ROOT_S2] = ORC_NO_RANK; O[GRP_REPEATS] = G->repeats;
+    O[GRP_LOCATE] = slow && G->repeats >= (uint64_t)P[P_REPEAT_THRESHOLD];
+    k0 = k1;
+  }
+  free(items); free(seg_first); free(va); free(vb); free(vs);
+  R->status = ORC_OK;
+  return ORC_OK;
+}

@@ -1,0 +1,182 @@
+"""ctypes wrapper of the CPU oracle (oracle/ccld_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  It never imports the GPU library's binding.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ccld_oracle.c")
+_LIB = os.path.join(_HERE, "libccld_oracle.so")
+
+INFLIGHT = np.iinfo(np.int64).max
+NO_RANK = 0xFFFFFFFF
+
+STATUS = {0: "OK", -1: "E_UNKNOWN_COMM", -2: "E_RANK_NOT_MEMBER", -3: "E_RANGE", -4: "E_DUPLICATE_KEY",
+          -5: "E_SNAPSHOT_GAP", -6: "E_BAD_ARG"}
+
+PARAM_NAMES = ("hang_threshold_ns", "tbase_init_ns", "tbase_rounds", "tbase_warmup_ns", "theta_num", "theta_den",
+               "alpha_num", "beta_num", "ab_den", "repeat_threshold", "barrier_bytes", "kmad_num", "kmad_den",
+               "lag_floor_ns", "stall_snapshots", "fifo_depth")
+DEFAULT_PARAMS: Dict[str, int] = dict(
+    hang_threshold_ns=300_000_000_000, tbase_init_ns=(2**63 - 1) // 4, tbase_rounds=100,
+    tbase_warmup_ns=120_000_000_000, theta_num=3, theta_den=1, alpha_num=4, beta_num=6, ab_den=10,
+    repeat_threshold=2, barrier_bytes=4, kmad_num=9, kmad_den=2, lag_floor_ns=300_000,
+    stall_snapshots=30, fifo_depth=8)
+
+SEG_COLS = ("comm", "seq", "n", "inflight", "state", "op", "bytes", "enter_min", "enter_med", "enter_max",
+            "enter_mad", "exit_min", "exit_med", "exit_max", "exit_mad", "dur_min", "dur_max", "argmin_rank",
+            "argmax_rank", "inflight_enter_min")
+FLAG_COLS = ("comm", "seq", "rank", "kind", "lag_enter", "lag_exit")
+GROUP_COLS = ("comm", "op", "cls", "n_usable", "rstar_seq", "tmax", "tmin", "tbase", "static", "frozen", "m",
+              "slow", "class", "root_s1", "root_s2", "repeats", "locate")
+ALERT_COLS = ("comm", "seq", "age", "class", "n_cand", "cand_off")
+BLAME_COLS = ("n_late_enter", "n_late_exit", "sum_lag_enter", "sum_lag_exit", "n_records")
+REC_COLS = ("lag_enter", "lag_exit", "flag")
+SEG_COMPLETE, SEG_CONSISTENT, SEG_BARRIER, SEG_USABLE = 1, 2, 4, 8
+FLAG_LATE_ENTER, FLAG_LATE_EXIT = 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, -O2)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC])
+    return _LIB
+
+
+class _Topo(C.Structure):
+    _fields_ = [("n_ranks", C.c_uint32), ("n_comms", C.c_uint32), ("algo", C.c_void_p), ("size", C.c_void_p),
+                ("member_off", C.c_void_p), ("members", C.c_void_p), ("tree_parent", C.c_void_p)]
+
+
+class _WinRes(C.Structure):
+    _fields_ = [("status", C.c_int32), ("n", C.c_uint64), ("n_seg", C.c_uint64), ("n_flag", C.c_uint64),
+                ("n_group", C.c_uint64), ("n_alert", C.c_uint64), ("n_cand", C.c_uint64), ("n_ranks", C.c_uint64),
+                ("perm", C.c_void_p), ("rec", C.c_void_p), ("seg", C.c_void_p), ("flag", C.c_void_p),
+                ("group", C.c_void_p), ("alert", C.c_void_p), ("cand", C.c_void_p), ("blame", C.c_void_p),
+                ("order", C.c_void_p)]
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        L.orc_state_create.restype = C.c_void_p
+        L.orc_state_create.argtypes = [C.c_uint32]
+        L.orc_state_destroy.argtypes = [C.c_void_p]
+        L.orc_window_result_free.argtypes = [C.c_void_p]
+        L.orc_analyze_window.restype = C.c_int
+        L.orc_analyze_window.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64] + [C.c_void_p] * 7 + \
+            [C.c_int64, C.c_void_p, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _table(ptr, n, ncol) -> np.ndarray:
+    if n == 0 or not ptr:
+        return np.zeros((0, ncol), dtype=np.int64)
+    buf = (C.c_int64 * (n * ncol)).from_address(ptr)
+    return np.frombuffer(buf, dtype=np.int64).reshape(n, ncol).copy()
+
+
+@dataclass
+class WindowResult:
+    status: str
+    perm: np.ndarray                 # [n] input index of the j-th record in (comm, seq, rank) order
+    rec: Dict[str, np.ndarray]       # per sorted record
+    seg: Dict[str, np.ndarray]
+    flag: Dict[str, np.ndarray]
+    group: Dict[str, np.ndarray]
+    alert: Dict[str, np.ndarray]
+    cand: np.ndarray
+    blame: Dict[str, np.ndarray]
+    order: np.ndarray
+
+
+def _cols(tab: np.ndarray, names) -> Dict[str, np.ndarray]:
+    return {nm: np.ascontiguousarray(tab[:, i]) for i, nm in enumerate(names)}
+
+
+class Oracle:
+    """Holds the topology, the parameters and the per-group detection state
+    that persists from one analysed window to the next."""
+
+    def __init__(self, topo, params: Optional[Dict[str, int]] = None):
+        self.L = lib()
+        self.params = dict(DEFAULT_PARAMS)
+        if params:
+            self.params.update(params)
+        self._p = np.asarray([self.params[k] for k in PARAM_NAMES], dtype=np.int64)
+        self._algo = np.ascontiguousarray(topo.algo, dtype=np.uint8)
+        self._size = np.ascontiguousarray(topo.size, dtype=np.uint32)
+        self._off = np.ascontiguousarray(topo.member_off, dtype=np.uint32)
+        self._members = np.ascontiguousarray(topo.members, dtype=np.uint32)
+        self._tp = None if topo.tree_parent is None else np.ascontiguousarray(topo.tree_parent, dtype=np.int32)
+        self._topo = _Topo(int(topo.n_ranks), int(self._size.shape[0]), _ptr(self._algo), _ptr(self._size),
+                           _ptr(self._off), _ptr(self._members), _ptr(self._tp))
+        self.n_ranks = int(topo.n_ranks)
+        self._state = self.L.orc_state_create(int(self._size.shape[0]))
+        if not self._state:
+            raise MemoryError("oracle state")
+
+    def close(self):
+        if self._state:
+            self.L.orc_state_destroy(self._state)
+            self._state = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def analyze_window(self, cols: Dict[str, np.ndarray], now_ns: int) -> WindowResult:
+        rank = np.ascontiguousarray(cols["rank"], dtype=np.uint32)
+        comm = np.ascontiguousarray(cols["comm"], dtype=np.uint32)
+        seq = np.ascontiguousarray(cols["seq"], dtype=np.uint64)
+        op = np.ascontiguousarray(cols["op"], dtype=np.uint8)
+        nbytes = np.ascontiguousarray(cols["bytes"], dtype=np.uint64)
+        te = np.ascontiguousarray(cols["t_enter"], dtype=np.int64)
+        tx = np.ascontiguousarray(cols["t_exit"], dtype=np.int64)
+        n = int(rank.shape[0])
+        res = _WinRes()
+        self.L.orc_analyze_window(_ptr(self._p), C.addressof(self._topo), n, _ptr(rank), _ptr(comm), _ptr(seq),
+                                  _ptr(op), _ptr(nbytes), _ptr(te), _ptr(tx), int(now_ns), self._state,
+                                  C.addressof(res))
+        try:
+            status = STATUS[res.status]
+            if res.status != 0:
+                z = np.zeros((0,), np.int64)
+                e = lambda names: {k: z.copy() for k in names}
+                return WindowResult(status, z.astype(np.uint64), e(REC_COLS), e(SEG_COLS), e(FLAG_COLS),
+                                    e(GROUP_COLS), e(ALERT_COLS), z, e(BLAME_COLS), z)
+            perm = _table(res.perm, n, 1).reshape(-1).astype(np.uint64)
+            out = WindowResult(
+                status, perm,
+                _cols(_table(res.rec, n, len(REC_COLS)), REC_COLS),
+                _cols(_table(res.seg, res.n_seg, len(SEG_COLS)), SEG_COLS),
+                _cols(_table(res.flag, res.n_flag, len(FLAG_COLS)), FLAG_COLS),
+                _cols(_table(res.group, res.n_group, len(GROUP_COLS)), GROUP_COLS),
+                _cols(_table(res.alert, res.n_alert, len(ALERT_COLS)), ALERT_COLS),
+                _table(res.cand, res.n_cand, 1).reshape(-1),
+                _cols(_table(res.blame, self.n_ranks, len(BLAME_COLS)), BLAME_COLS),
+                _table(res.order, self.n_ranks, 1).reshape(-1))
+            return out
+        finally:
+            self.L.orc_window_result_free(C.addressof(res))

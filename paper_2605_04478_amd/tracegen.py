@@ -1,0 +1,444 @@
+"""Seeded synthetic inputs: a simulated training cluster that emits per-rank
+collective-communication trace records and progress-counter snapshots.
+
+This module only *produces inputs* (and the list of faults it injected).  It
+holds none of the analyzer's arithmetic and is the one piece of code that both
+the GPU library's tests and the CPU oracle's tests are allowed to share.
+
+Record schema (one row per rank per collective, SoA numpy arrays):
+    rank u32, comm u32, seq u64, op u8, bytes u64, t_enter i64 ns, t_exit i64 ns
+A collective that has not completed on a rank carries t_exit == INFLIGHT.
+
+All random numbers come from a counter-based generator (a 64-bit mixing hash of
+(seed, stream, a, b)), so any slice of a trace can be generated independently
+and in parallel, and the same (spec, seed) always yields the same arrays.
+Floating point appears only here; every emitted time is an int64 nanosecond.
+"""
+from __future__ import annotations
+
+import os
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+INFLIGHT = np.iinfo(np.int64).max
+NO_RANK = 0xFFFFFFFF
+
+OP_ALLREDUCE = 0
+OP_ALLGATHER = 1
+OP_REDUCESCATTER = 2
+OP_ALLTOALL = 3
+OP_SENDRECV = 4
+OP_BROADCAST = 5
+
+ALGO_RING = 0
+ALGO_TREE = 1
+
+T_EPOCH_NS = 1_700_000_000 * 1_000_000_000  # traces start at a wall-clock-like origin
+
+_U = np.uint64
+_GOLD = _U(0x9E3779B97F4A7C15)
+_M1 = _U(0xBF58476D1CE4E5B9)
+_M2 = _U(0x94D049BB133111EB)
+
+
+# --------------------------------------------------------------------------
+# counter-based random numbers
+# --------------------------------------------------------------------------
+def _mix(x: np.ndarray) -> np.ndarray:
+    x = (x ^ (x >> _U(30))) * _M1
+    x = (x ^ (x >> _U(27))) * _M2
+    return x ^ (x >> _U(31))
+
+
+def rand_u64(seed: int, stream: int, a, b=0) -> np.ndarray:
+    """64 random bits for every element of broadcast(a, b)."""
+    with np.errstate(over="ignore"):
+        a = np.asarray(a).astype(np.uint64, copy=False)
+        b = np.asarray(b).astype(np.uint64, copy=False)
+        s = _mix(np.asarray([(seed * 0x632BE59BD9B4E019 + stream * 0x9E3779B97F4A7C15 + 1) & (2**64 - 1)],
+                            dtype=np.uint64))[0]
+        h = _mix((a + s) * _GOLD + _U(0x2545F4914F6CDD1D))
+        h = _mix(h ^ ((b + _U(1)) * _M1))
+    return h
+
+
+def rand_unit(seed, stream, a, b=0) -> np.ndarray:
+    """Uniform doubles in [0, 1)."""
+    return (rand_u64(seed, stream, a, b) >> _U(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+
+
+def rand_normal(seed, stream, a, b=0) -> np.ndarray:
+    u1 = rand_unit(seed, stream, a, b)
+    u2 = rand_unit(seed, stream + 7919, a, b)
+    return np.sqrt(-2.0 * np.log1p(-u1)) * np.cos(2.0 * np.pi * u2)
+
+
+# --------------------------------------------------------------------------
+# topology
+# --------------------------------------------------------------------------
+@dataclass
+class Topology:
+    """Communicator table: CSR member lists in ring order (successor = next,
+    cyclic) or, for tree communicators, in BFS order with a parent slot per
+    member (-1 for the root)."""
+    n_ranks: int
+    algo: np.ndarray          # u8  [n_comms]
+    size: np.ndarray          # u32 [n_comms]
+    member_off: np.ndarray    # u32 [n_comms]
+    members: np.ndarray       # u32 [sum size]
+    tree_parent: Optional[np.ndarray] = None   # i32 [sum size], member-slot index within the comm
+    names: List[str] = field(default_factory=list)
+
+    @property
+    def n_comms(self) -> int:
+        return int(self.size.shape[0])
+
+    def members_of(self, c: int) -> np.ndarray:
+        o = int(self.member_off[c])
+        return self.members[o:o + int(self.size[c])]
+
+
+def make_topology(n_ranks: int, comms: Sequence[Sequence[int]], algo: Optional[Sequence[int]] = None,
+                  tree_parent: Optional[Sequence[Optional[Sequence[int]]]] = None,
+                  names: Optional[List[str]] = None) -> Topology:
+    size = np.asarray([len(c) for c in comms], dtype=np.uint32)
+    off = np.zeros(len(comms), dtype=np.uint32)
+    if len(comms) > 1:
+        off[1:] = np.cumsum(size[:-1], dtype=np.uint64).astype(np.uint32)
+    members = (np.concatenate([np.asarray(c, dtype=np.uint32) for c in comms])
+               if len(comms) else np.zeros(0, np.uint32))
+    al = np.zeros(len(comms), dtype=np.uint8) if algo is None else np.asarray(algo, dtype=np.uint8)
+    tp = None
+    if tree_parent is not None:
+        tp = np.full(members.shape[0], -1, dtype=np.int32)
+        for c, par in enumerate(tree_parent):
+            if par is not None:
+                tp[int(off[c]):int(off[c]) + int(size[c])] = np.asarray(par, dtype=np.int32)
+    return Topology(n_ranks, al, size, off, members, tp, names or [])
+
+
+@dataclass
+class Layout3D:
+    """rank = pp*(DP*TP) + dp*TP + tp; a TP group is 8 consecutive ranks (one
+    node).  Communicator ids: all TP groups, then all PP groups, then all DP
+    groups, then (optionally) one world communicator."""
+    tp: int
+    pp: int
+    dp: int
+    world: bool = False
+
+    @property
+    def n_ranks(self) -> int:
+        return self.tp * self.pp * self.dp
+
+    @property
+    def n_tp(self) -> int:
+        return self.pp * self.dp
+
+    @property
+    def n_pp(self) -> int:
+        return self.dp * self.tp
+
+    @property
+    def n_dp(self) -> int:
+        return self.pp * self.tp
+
+    def coords(self, rank):
+        rank = np.asarray(rank)
+        return rank // (self.dp * self.tp), (rank // self.tp) % self.dp, rank % self.tp
+
+    def comm_of(self, kind: str, rank) -> np.ndarray:
+        p, d, t = self.coords(rank)
+        if kind == "tp":
+            return p * self.dp + d
+        if kind == "pp":
+            return self.n_tp + d * self.tp + t
+        if kind == "dp":
+            return self.n_tp + self.n_pp + p * self.tp + t
+        if kind == "world":
+            return np.zeros_like(np.asarray(rank)) + (self.n_tp + self.n_pp + self.n_dp)
+        raise ValueError(kind)
+
+    def topology(self) -> Topology:
+        r = np.arange(self.n_ranks).reshape(self.pp, self.dp, self.tp)
+        comms: List[np.ndarray] = []
+        names: List[str] = []
+        for p in range(self.pp):
+            for d in range(self.dp):
+                comms.append(r[p, d, :]); names.append("tp")
+        for d in range(self.dp):
+            for t in range(self.tp):
+                comms.append(r[:, d, t]); names.append("pp")
+        for p in range(self.pp):
+            for t in range(self.tp):
+                comms.append(r[p, :, t]); names.append("dp")
+        if self.world:
+            comms.append(r.reshape(-1)); names.append("world")
+        return make_topology(self.n_ranks, comms, names=names)
+
+
+# --------------------------------------------------------------------------
+# trace specification
+# --------------------------------------------------------------------------
+CYCLE_3D: Tuple[Tuple[str, int], ...] = (
+    ("tp", OP_ALLREDUCE), ("tp", OP_ALLREDUCE), ("tp", OP_ALLREDUCE), ("pp", OP_SENDRECV),
+    ("tp", OP_ALLREDUCE), ("tp", OP_ALLREDUCE), ("tp", OP_ALLREDUCE), ("pp", OP_SENDRECV),
+    ("dp", OP_ALLGATHER), ("dp", OP_ALLREDUCE),
+)
+CYCLE_WORLD: Tuple[Tuple[str, int], ...] = (("world", OP_ALLREDUCE),)
+
+
+@dataclass
+class SlowRank:
+    rank: int
+    prob: float                      # probability that an op of this rank is delayed
+    dist: Tuple                      # ("const", ns) | ("uniform", lo_ns, hi_ns) | ("exp", mean_ns)
+
+
+@dataclass
+class SlowGroup:
+    ranks: Tuple[int, ...]           # ranks whose transfers are stretched
+    factor: float                    # multiplier on the transfer time of those ranks
+    kind: str                        # communicator kind the fault applies to ("pp", "dp", ...)
+    comm: Optional[int] = None       # restrict to one communicator id (slow link); None = all of that kind
+
+
+@dataclass
+class TraceSpec:
+    layout: Layout3D
+    cycle: Tuple[Tuple[str, int], ...]
+    n_slots: int                     # collectives per rank
+    bytes_dist: Tuple                # ("pow2", lo_exp, hi_exp) | ("loguniform", lo_exp, hi_exp)
+    sigma: float = 0.1               # lognormal jitter of the transfer time, one draw per collective
+    skew_ns: int = 50_000            # per-rank clock offset, uniform in [-skew, +skew]
+    slot_ns: int = 100_000_000       # spacing of successive collectives on a rank
+    bandwidth_b_per_ns: float = 20.0
+    enter_jitter_ns: int = 20_000
+    exit_jitter_ns: int = 5_000
+    slow_ranks: List[SlowRank] = field(default_factory=list)
+    slow_groups: List[SlowGroup] = field(default_factory=list)
+    seed: int = 0
+    name: str = "trace"
+
+    @property
+    def n_records(self) -> int:
+        return self.n_slots * self.layout.n_ranks
+
+
+# streams of the counter-based generator
+_S_BYTES, _S_JIT, _S_ENTER, _S_EXIT, _S_SKEW, _S_INJP, _S_INJV, _S_PICK = 11, 12, 13, 14, 15, 16, 17, 18
+
+
+def _slot_seq_tables(cycle) -> Tuple[np.ndarray, Dict[str, int]]:
+    """Ordinal of each cycle position among the positions of its kind, and the
+    number of positions of each kind per cycle."""
+    cnt: Dict[str, int] = {}
+    ordinal = np.zeros(len(cycle), dtype=np.int64)
+    for i, (kind, _) in enumerate(cycle):
+        ordinal[i] = cnt.get(kind, 0)
+        cnt[kind] = cnt.get(kind, 0) + 1
+    return ordinal, cnt
+
+
+def _delay(dist: Tuple, u: np.ndarray) -> np.ndarray:
+    if dist[0] == "const":
+        return np.full(u.shape, float(dist[1]))
+    if dist[0] == "uniform":
+        return dist[1] + (dist[2] - dist[1]) * u
+    if dist[0] == "exp":
+        return -float(dist[1]) * np.log1p(-u)
+    raise ValueError(dist)
+
+
+def _gen_slots(spec: TraceSpec, k0: int, k1: int, out: Dict[str, np.ndarray]) -> None:
+    """Fill rows [k0*n_ranks, k1*n_ranks) of the output columns (slot-major)."""
+    L = spec.layout
+    R = L.n_ranks
+    cyc = spec.cycle
+    ordinal, per_cycle = _slot_seq_tables(cyc)
+    ranks = np.arange(R, dtype=np.int64)
+    skew = np.rint((rand_unit(spec.seed, _S_SKEW, ranks) * 2.0 - 1.0) * spec.skew_ns).astype(np.int64)
+    view = {k: v.reshape(-1, R) for k, v in out.items()}
+    ks_all = np.arange(k0, k1, dtype=np.int64)
+    for kind in sorted(per_cycle):
+        pos = [i for i, (kd, _) in enumerate(cyc) if kd == kind]
+        sel = np.isin(ks_all % len(cyc), pos)
+        ks = ks_all[sel]
+        if ks.size == 0:
+            continue
+        m = ks.size
+        comm_r = L.comm_of(kind, ranks).astype(np.int64)              # [R]
+        seq_k = (ks // len(cyc)) * per_cycle[kind] + ordinal[ks % len(cyc)]   # [m]
+        op_k = np.asarray([cyc[int(i)][1] for i in (ks % len(cyc))], dtype=np.uint8)
+        # one draw per collective (comm, seq): message size and transfer jitter
+        ucomm, inv = np.unique(comm_r, return_inverse=True)
+        ub = rand_unit(spec.seed, _S_BYTES, ucomm[None, :], seq_k[:, None])
+        if spec.bytes_dist[0] == "pow2":
+            lo, hi = spec.bytes_dist[1], spec.bytes_dist[2]
+            nbytes_c = np.left_shift(np.int64(1), (lo + np.floor(ub * (hi - lo + 1))).astype(np.int64))
+        else:
+            lo, hi = spec.bytes_dist[1], spec.bytes_dist[2]
+            nbytes_c = np.floor(np.exp2(lo + (hi - lo) * ub)).astype(np.int64)
+        jit_c = np.exp(spec.sigma * rand_normal(spec.seed, _S_JIT, ucomm[None, :], seq_k[:, None]))
+        nbytes = nbytes_c[:, inv]                                    # [m, R]
+        jit = jit_c[:, inv]
+        # per-record draws
+        inject = np.zeros((m, R), dtype=np.float64)
+        for sr in spec.slow_ranks:
+            hit = rand_unit(spec.seed, _S_INJP, np.int64(sr.rank), ks) < sr.prob
+            val = _delay(sr.dist, rand_unit(spec.seed, _S_INJV, np.int64(sr.rank), ks))
+            inject[:, sr.rank] += np.where(hit, np.maximum(np.rint(val), 1.0), 0.0)
+        enter = (ks[:, None] * spec.slot_ns
+                 + np.floor(rand_unit(spec.seed, _S_ENTER, ranks[None, :], ks[:, None]) * spec.enter_jitter_ns)
+                 + inject)
+        e4 = enter.reshape(m, L.pp, L.dp, L.tp)
+        if kind == "tp":
+            start = np.broadcast_to(e4.max(axis=3, keepdims=True), e4.shape)
+        elif kind == "pp":
+            start = np.broadcast_to(e4.max(axis=1, keepdims=True), e4.shape)
+        elif kind == "dp":
+            start = np.broadcast_to(e4.max(axis=2, keepdims=True), e4.shape)
+        else:
+            start = np.broadcast_to(e4.max(axis=(1, 2, 3), keepdims=True), e4.shape)
+        start = start.reshape(m, R)
+        factor = np.ones(R, dtype=np.float64)
+        fac2d = None
+        for sg in spec.slow_groups:
+            if sg.kind != kind:
+                continue
+            if sg.comm is None:
+                factor[list(sg.ranks)] *= sg.factor
+            else:
+                if fac2d is None:
+                    fac2d = np.ones((1, R), dtype=np.float64)
+                on = np.zeros(R, dtype=bool)
+                on[list(sg.ranks)] = True
+                fac2d = fac2d * np.where(on & (comm_r == sg.comm), sg.factor, 1.0)[None, :]
+        f = factor[None, :] if fac2d is None else factor[None, :] * fac2d
+        dur = np.rint(nbytes.astype(np.float64) / spec.bandwidth_b_per_ns * jit * f)
+        exit_ = (start + dur
+                 + np.floor(rand_unit(spec.seed, _S_EXIT, ranks[None, :], ks[:, None]) * spec.exit_jitter_ns))
+        r0 = ks - k0          # row of each slot inside this chunk's [slots, R] view
+        view["rank"][r0, :] = ranks.astype(np.uint32)[None, :]
+        view["comm"][r0, :] = comm_r.astype(np.uint32)[None, :]
+        view["seq"][r0, :] = seq_k.astype(np.uint64)[:, None]
+        view["op"][r0, :] = op_k[:, None]
+        view["bytes"][r0, :] = nbytes.astype(np.uint64)
+        view["t_enter"][r0, :] = T_EPOCH_NS + enter.astype(np.int64) + skew[None, :]
+        view["t_exit"][r0, :] = T_EPOCH_NS + exit_.astype(np.int64) + skew[None, :]
+        view["inj_delay"][r0, :] = inject.astype(np.int64)
+        view["stretched"][r0, :] = np.broadcast_to(f != 1.0, (m, R))
+
+
+COLUMNS = ("rank", "comm", "seq", "op", "bytes", "t_enter", "t_exit")
+_DTYPES = {"rank": np.uint32, "comm": np.uint32, "seq": np.uint64, "op": np.uint8, "bytes": np.uint64,
+           "t_enter": np.int64, "t_exit": np.int64, "inj_delay": np.int64, "stretched": np.bool_}
+
+
+@dataclass
+class Trace:
+    spec: TraceSpec
+    topo: Topology
+    cols: Dict[str, np.ndarray]          # the seven record columns
+    inj_delay: np.ndarray                # ns added to this record's entry (0 = none)   [ground truth]
+    stretched: np.ndarray                # this record's transfer was stretched          [ground truth]
+
+    @property
+    def n(self) -> int:
+        return int(self.cols["rank"].shape[0])
+
+    def take(self, index: np.ndarray) -> "Trace":
+        return Trace(self.spec, self.topo, {k: v[index] for k, v in self.cols.items()},
+                     self.inj_delay[index], self.stretched[index])
+
+    def shuffled(self, seed: int) -> "Trace":
+        perm = np.random.Generator(np.random.PCG64(seed)).permutation(self.n)
+        return self.take(perm)
+
+
+def generate(spec: TraceSpec, chunk_slots: int = 0, workers: int = 0) -> Trace:
+    R = spec.layout.n_ranks
+    n = spec.n_records
+    out = {k: np.empty(n, dtype=_DTYPES[k]) for k in _DTYPES}
+    if chunk_slots <= 0:
+        chunk_slots = max(1, (1 << 20) // R)
+    if workers <= 0:
+        workers = min(16, os.cpu_count() or 1)
+    chunks = [(k, min(k + chunk_slots, spec.n_slots)) for k in range(0, spec.n_slots, chunk_slots)]
+
+    def work(c):
+        sub = {k: v[c[0] * R:c[1] * R] for k, v in out.items()}
+        _gen_slots(spec, c[0], c[1], sub)
+
+    if workers == 1 or len(chunks) == 1:
+        for c in chunks:
+            work(c)
+    else:
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(work, chunks))
+    cols = {k: out[k] for k in COLUMNS}
+    return Trace(spec, spec.layout.topology(), cols, out["inj_delay"], out["stretched"])
+
+
+# --------------------------------------------------------------------------
+# the benchmark configurations
+# --------------------------------------------------------------------------
+def _pick_distinct(seed: int, stream: int, n_pick: int, n_total: int, exclude=()) -> List[int]:
+    order = np.argsort(rand_u64(seed, stream, np.arange(n_total)), kind="stable")
+    ex = set(int(x) for x in exclude)
+    outl: List[int] = []
+    for r in order:
+        if int(r) not in ex:
+            outl.append(int(r))
+            if len(outl) == n_pick:
+                break
+    return outl
+
+
+def config1(n_slots: int = 1000, seed: int = 0, faults: bool = True) -> TraceSpec:
+    """16 ranks, one world ring, all-reduce only; rank 5 enters 2 ms late on 5 % of its ops."""
+    lay = Layout3D(tp=16, pp=1, dp=1, world=False)
+    # a single communicator: use the TP communicator of the 16x1x1 layout as the world ring
+    return TraceSpec(layout=lay, cycle=(("tp", OP_ALLREDUCE),), n_slots=n_slots, bytes_dist=("pow2", 20, 28),
+                     sigma=0.1, skew_ns=50_000, slot_ns=100_000_000,
+                     slow_ranks=[SlowRank(5, 0.05, ("const", 2_000_000))] if faults else [],
+                     seed=seed, name="config1")
+
+
+def config2(n_cycles: int = 1000, seed: int = 0, faults: bool = True) -> TraceSpec:
+    """512 ranks = TP8 x PP4 x DP16; 3 slow ranks and one slow pipeline link."""
+    lay = Layout3D(tp=8, pp=4, dp=16)
+    slow, groups = [], []
+    if faults:
+        for r in _pick_distinct(seed, _S_PICK, 3, lay.n_ranks):
+            slow.append(SlowRank(r, 0.10, ("uniform", 500_000, 5_000_000)))
+        # one PP communicator, one adjacent stage pair
+        ex = [s.rank for s in slow]
+        a = _pick_distinct(seed, _S_PICK + 1, 1, lay.n_ranks - lay.dp * lay.tp, exclude=ex)[0]
+        b = a + lay.dp * lay.tp
+        groups.append(SlowGroup((a, b), 1.5, "pp", comm=int(lay.comm_of("pp", a))))
+    return TraceSpec(layout=lay, cycle=CYCLE_3D, n_slots=10 * n_cycles, bytes_dist=("pow2", 20, 28),
+                     sigma=0.1, skew_ns=50_000, slot_ns=100_000_000, slow_ranks=slow, slow_groups=groups,
+                     seed=seed, name="config2")
+
+
+def config3(n_cycles: int = 2000, seed: int = 0, faults: bool = True,
+            layout: Optional[Layout3D] = None) -> TraceSpec:
+    """4,096 ranks = TP8 x PP8 x DP64; 8 slow ranks (every op, Exp(1 ms)) and two
+    nodes whose DP transfers run 1.3x slower."""
+    lay = layout or Layout3D(tp=8, pp=8, dp=64)
+    slow, groups = [], []
+    if faults:
+        n_nodes = lay.n_ranks // lay.tp
+        nodes = _pick_distinct(seed, _S_PICK + 2, min(2, n_nodes), n_nodes)
+        node_ranks = [r for nd in nodes for r in range(nd * lay.tp, (nd + 1) * lay.tp)]
+        for r in _pick_distinct(seed, _S_PICK, min(8, lay.n_ranks // 4), lay.n_ranks, exclude=node_ranks):
+            slow.append(SlowRank(r, 1.0, ("exp", 1_000_000)))
+        for nd in nodes:
+            groups.append(SlowGroup(tuple(range(nd * lay.tp, (nd + 1) * lay.tp)), 1.3, "dp"))
+    return TraceSpec(layout=lay, cycle=CYCLE_3D, n_slots=10 * n_cycles, bytes_dist=("loguniform", 16.0, 29.0),
+                     sigma=0.2, skew_ns=100_000, slot_ns=250_000_000, slow_ranks=slow, slow_groups=groups,
+                     seed=seed, name="config3")
