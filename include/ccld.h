@@ -1,0 +1,214 @@
+/*
+ * ccld.h - C ABI of the MI355X decision-analyzer hot path of CCL-D.
+ *
+ * The library analyses per-rank collective-communication trace records on one
+ * GPU: it groups them by Trace ID (communicator id, operation counter), computes
+ * cross-rank statistics per collective, flags slow ranks, evaluates the paper's
+ * slow-detection and slow-location rules, raises hang alerts, locates a hang's
+ * root rank from Send/Recv progress counters, and accumulates per-rank blame.
+ *
+ * Conventions
+ *  - "device" pointers are HIP device memory owned by the caller (for example a
+ *    PyTorch tensor's data_ptr()); "host" pointers are ordinary host memory.
+ *  - The library allocates no device memory: everything it needs lives in the
+ *    caller's workspace (ccld_query_workspace / ccld_create).  It never frees or
+ *    keeps caller memory other than that workspace.
+ *  - All work is enqueued on the HIP stream given to ccld_create.  Calls that
+ *    return counts (analyze, locate, blame) synchronise that stream before they
+ *    return; ccld_ingest does not.
+ *  - Every function returns a ccld_status: 0 = CCLD_OK, negative = error,
+ *    positive = warning.  Nothing throws, aborts or prints.
+ *  - Output tables are column-major int64 matrices: column c of a table with
+ *    capacity CAP starts at table + c*CAP.  Unsigned fields (seq, bytes) are
+ *    stored bit-for-bit.  When a table is too small its list is truncated, its
+ *    count is still exact, and the status is CCLD_W_TRUNCATED.
+ *  - All arithmetic is 64-bit integer; products are compared in 128 bits.
+ */
+#ifndef CCLD_H
+#define CCLD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ccld_ctx ccld_ctx;
+typedef int32_t ccld_status;
+
+enum {
+  CCLD_OK = 0,
+  CCLD_E_UNKNOWN_COMM = -1,     /* a record names a communicator that is not in the topology        */
+  CCLD_E_RANK_NOT_MEMBER = -2,  /* a record's rank is not a member of its communicator              */
+  CCLD_E_RANGE = -3,            /* op >= 16, t_enter < 0 or == CCLD_T_INFLIGHT, t_exit < t_enter    */
+  CCLD_E_DUPLICATE_KEY = -4,    /* two records (or snapshot rows) with the same key                 */
+  CCLD_E_SNAPSHOT_GAP = -5,     /* a (snapshot, rank, communicator, channel) row is missing         */
+  CCLD_E_BAD_ARG = -6,          /* parameter out of range                                           */
+  CCLD_E_NULL = -7,             /* required pointer is NULL                                         */
+  CCLD_E_CAPACITY = -8,         /* batch or window larger than the capacity given at create         */
+  CCLD_E_KEY_WIDTH = -9,        /* communicator + sequence + rank bits do not fit in 64 bits        */
+  CCLD_E_BAD_TOPOLOGY = -10,    /* malformed communicator table                                     */
+  CCLD_E_HIP = -11,             /* a HIP runtime call failed                                        */
+  CCLD_E_WORKSPACE = -12,       /* workspace too small or misaligned                                */
+  CCLD_W_TRUNCATED = 1          /* an output list did not fit its table                             */
+};
+
+#define CCLD_T_INFLIGHT INT64_MAX     /* t_exit of an operation that has not completed              */
+#define CCLD_NO_RANK 0xFFFFFFFFll
+#define CCLD_OP_MAX 16                /* operation codes are 0..15                                  */
+
+/* operation codes (Operation Type Set, Section 4.1.2); only ALLREDUCE has a meaning to the
+ * analyzer (barrier filter), the others are labels */
+enum { CCLD_OP_ALLREDUCE = 0, CCLD_OP_ALLGATHER = 1, CCLD_OP_REDUCESCATTER = 2, CCLD_OP_ALLTOALL = 3,
+       CCLD_OP_SENDRECV = 4, CCLD_OP_BROADCAST = 5 };
+enum { CCLD_ALGO_RING = 0, CCLD_ALGO_TREE = 1 };   /* Section 4.2.1: ring vs tree comparison groups */
+
+/* Analyzer parameters; all integer, ratios as numerator/denominator.  Defaults in brackets. */
+typedef struct {
+  int64_t hang_threshold_ns;   /* [300e9] an operation in flight longer than this raises a hang alert (Sec. 4.2.1, 6.1) */
+  int64_t tbase_init_ns;       /* [INT64_MAX/4] administrator-set initial baseline T_base^(init) (Eq. 1)    */
+  uint32_t tbase_rounds;       /* [100] cap of m, the rounds averaged into the baseline (Eq. 1)             */
+  uint32_t repeat_threshold;   /* [2] slow detections needed before location is triggered (Sec. 4.2.1)      */
+  int64_t tbase_warmup_ns;     /* [120e9] rounds later than this after the first one end the warm-up (Eq. 1) */
+  uint32_t theta_num, theta_den;          /* [3,1] slowdown threshold theta_slow (Eq. 3)                    */
+  uint32_t alpha_num, beta_num, ab_den;   /* [4,6,10] boundaries alpha, beta of P (Eq. 4)                   */
+  uint32_t barrier_bytes;      /* [4] an ALLREDUCE smaller than this is a barrier and is ignored (Sec. 4.2.1) */
+  uint32_t kmad_num, kmad_den; /* [9,2] a rank is late when its lag exceeds kmad * MAD ...                  */
+  int64_t lag_floor_ns;        /* [300000] ... and this floor (must exceed twice the clock skew)            */
+  uint32_t stall_snapshots;    /* [30] a counter unchanged over this many snapshots is stalled              */
+  uint32_t fifo_depth;         /* [8] ring back-pressure depth used by the wait-for edges                   */
+  uint32_t window_batches;     /* [1] the window holds the last this-many ingested batches                  */
+  uint32_t reserved;
+} ccld_params;
+
+/* Communicator table (host pointers, copied by ccld_create). */
+typedef struct {
+  uint32_t n_ranks, n_comms;
+  const uint8_t *algo;          /* [n_comms] CCLD_ALGO_*                                          */
+  const uint32_t *size;         /* [n_comms] members per communicator                             */
+  const uint32_t *member_off;   /* [n_comms] first slot of each communicator in members[]         */
+  const uint32_t *members;      /* ranks; ring order (successor = next slot, cyclic) or BFS order */
+  const int32_t *tree_parent;   /* per slot: parent's slot index inside the communicator, -1 = root; may be NULL */
+} ccld_topology;
+
+/* One batch of trace records, SoA (Section 5.1: Trace ID = communicator id + operation counter;
+ * Section 4.1.2: Operation Type Set = op, bytes; Duration Time = t_exit - t_enter). */
+typedef struct {
+  const uint32_t *rank, *comm;
+  const uint64_t *seq;
+  const uint8_t *op;
+  const uint64_t *bytes;
+  const int64_t *t_enter, *t_exit;   /* ns; t_exit == CCLD_T_INFLIGHT while the operation runs   */
+  int32_t on_device;                 /* 1: device pointers, 0: host pointers (copied synchronously) */
+} ccld_records;
+
+/* Progress-counter snapshots (Section 4.1.2 SendCount/RecvCount, per channel), SoA. */
+typedef struct {
+  const uint32_t *snap, *rank, *comm, *channel;
+  const uint64_t *seq_posted;        /* operation counter of the operation the counters describe  */
+  const uint32_t *chunks_sent, *chunks_recv;
+  int32_t on_device;
+} ccld_snapshots;
+
+/* ---- table layouts ------------------------------------------------------------------------- */
+/* segment table: one row per collective (communicator, operation counter), ordered by (comm, seq) */
+enum { CCLD_SEG_COMM, CCLD_SEG_SEQ, CCLD_SEG_N, CCLD_SEG_INFLIGHT, CCLD_SEG_STATE, CCLD_SEG_OP, CCLD_SEG_BYTES,
+       CCLD_SEG_ENTER_MIN, CCLD_SEG_ENTER_MED, CCLD_SEG_ENTER_MAX, CCLD_SEG_ENTER_MAD,
+       CCLD_SEG_EXIT_MIN, CCLD_SEG_EXIT_MED, CCLD_SEG_EXIT_MAX, CCLD_SEG_EXIT_MAD,
+       CCLD_SEG_DUR_MIN, CCLD_SEG_DUR_MAX, CCLD_SEG_ARGMIN_RANK, CCLD_SEG_ARGMAX_RANK,
+       CCLD_SEG_INFLIGHT_ENTER_MIN, CCLD_SEG_FIRST, CCLD_SEG_NCOL };
+/* CCLD_SEG_STATE bits */
+enum { CCLD_SEG_COMPLETE = 1,    /* every member has a record and none is in flight              */
+       CCLD_SEG_CONSISTENT = 2,  /* all records carry the same op and bytes                      */
+       CCLD_SEG_BARRIER = 4,     /* ALLREDUCE of fewer than barrier_bytes bytes                  */
+       CCLD_SEG_USABLE = 8 };    /* complete, consistent and not a barrier                       */
+/* flag list: one row per late record, ordered by (comm, seq, rank) */
+enum { CCLD_FLG_COMM, CCLD_FLG_SEQ, CCLD_FLG_RANK, CCLD_FLG_KIND, CCLD_FLG_LAG_ENTER, CCLD_FLG_LAG_EXIT,
+       CCLD_FLG_NCOL };
+enum { CCLD_FLAG_LATE_ENTER = 1, CCLD_FLAG_LATE_EXIT = 2 };
+/* detection groups (communicator, op, floor(log2 bytes)), ordered by that triple */
+enum { CCLD_GRP_COMM, CCLD_GRP_OP, CCLD_GRP_CLS, CCLD_GRP_N_USABLE, CCLD_GRP_RSTAR_SEQ, CCLD_GRP_TMAX,
+       CCLD_GRP_TMIN, CCLD_GRP_TBASE, CCLD_GRP_STATIC, CCLD_GRP_FROZEN, CCLD_GRP_M, CCLD_GRP_SLOW,
+       CCLD_GRP_CLASS, CCLD_GRP_ROOT_S1, CCLD_GRP_ROOT_S2, CCLD_GRP_REPEATS, CCLD_GRP_LOCATE, CCLD_GRP_NCOL };
+enum { CCLD_SLOW_NONE = 0, CCLD_SLOW_S1_COMPUTATION = 1, CCLD_SLOW_S2_COMMUNICATION = 2, CCLD_SLOW_S3_MIXED = 3 };
+/* hang alerts, ordered by (comm, seq); candidates of alert a are cand[off .. off+n) */
+enum { CCLD_ALR_COMM, CCLD_ALR_SEQ, CCLD_ALR_AGE, CCLD_ALR_CLASS, CCLD_ALR_NCAND, CCLD_ALR_CAND_OFF,
+       CCLD_ALR_NCOL };
+enum { CCLD_HANG_H1_NOT_ENTERED = 1, CCLD_HANG_H2_INCONSISTENT = 2, CCLD_HANG_H3_HARDWARE = 3 };
+/* per-rank blame */
+enum { CCLD_BLM_N_LATE_ENTER, CCLD_BLM_N_LATE_EXIT, CCLD_BLM_SUM_LAG_ENTER, CCLD_BLM_SUM_LAG_EXIT,
+       CCLD_BLM_N_RECORDS, CCLD_BLM_NCOL };
+
+/* Result of ccld_analyze_window.  The caller fills capacities and device pointers; the
+ * library fills the tables and, on return, the host-side counts and status. */
+typedef struct {
+  uint64_t seg_cap, flag_cap, group_cap, alert_cap, cand_cap;   /* in: rows                     */
+  int64_t *seg;        /* device [CCLD_SEG_NCOL][seg_cap]                                        */
+  int64_t *flag;       /* device [CCLD_FLG_NCOL][flag_cap]                                       */
+  int64_t *group;      /* device [CCLD_GRP_NCOL][group_cap]                                      */
+  int64_t *alert;      /* device [CCLD_ALR_NCOL][alert_cap]                                      */
+  int64_t *cand;       /* device [cand_cap]                                                      */
+  int64_t *lag_enter;  /* device [n_records] or NULL: t_enter - median, in sorted order, 0 on unusable rounds */
+  int64_t *lag_exit;   /* device [n_records] or NULL                                             */
+  uint8_t *rec_flag;   /* device [n_records] or NULL: CCLD_FLAG_* bits, in sorted order          */
+  uint32_t *perm;      /* device [n_records] or NULL: window index of the j-th record in (comm, seq, rank) order */
+  uint64_t n_records, n_seg, n_flag, n_group, n_alert, n_cand;  /* out (host)                   */
+  ccld_status status;  /* out (host): CCLD_OK, a data error (no tables written), or CCLD_W_TRUNCATED */
+  int32_t reserved;
+} ccld_window_result;
+
+/* ---- entry points ---------------------------------------------------------------------------- */
+
+/* Fills *params with the defaults listed above. */
+ccld_status ccld_default_params(ccld_params *params);
+
+/* Bytes of device workspace needed for windows of up to max_window_records records, batches of
+ * up to max_batch_records and hang analyses of up to max_snapshot_rows rows. */
+ccld_status ccld_query_workspace(const ccld_params *params, const ccld_topology *topo,
+                                 uint64_t max_window_records, uint64_t max_batch_records,
+                                 uint64_t max_snapshot_rows, uint64_t *bytes);
+
+/* Creates an analyzer.  workspace: device memory of at least the queried size, 256-byte aligned,
+ * owned by the caller and reserved for this context until ccld_destroy.  hip_stream: a hipStream_t
+ * (NULL = the default stream).  The topology is copied. */
+ccld_status ccld_create(const ccld_params *params, const ccld_topology *topo,
+                        uint64_t max_window_records, uint64_t max_batch_records, uint64_t max_snapshot_rows,
+                        void *workspace, uint64_t workspace_bytes, void *hip_stream, ccld_ctx **out);
+ccld_status ccld_destroy(ccld_ctx *ctx);
+
+/* Appends one batch of n records to the window (the analyzer "periodically processes metrics from
+ * all ranks", Section 3); when the window already holds window_batches batches the oldest batch is
+ * dropped first.  The records are validated, keyed by Trace ID (communicator id, operation counter;
+ * Section 5.1) plus rank, and stored on the device.  Asynchronous for device input; data errors
+ * found on the device are reported by the next ccld_analyze_window. */
+ccld_status ccld_ingest(ccld_ctx *ctx, const ccld_records *batch, uint64_t n);
+
+/* Drops every batch from the window; the per-group detection state (Eq. 1 baseline, repetition
+ * counters) is kept. */
+ccld_status ccld_reset_window(ccld_ctx *ctx);
+
+/* Analyses the resident window (Sections 4.2.1 and 4.2.2): sorts the records by (communicator,
+ * operation counter, rank); per collective computes earliest / lower-median / latest arrival and
+ * completion, their median absolute deviations, T_min / T_max of the per-rank Duration Time with
+ * the ranks attaining them, consistency of the Operation Type Set; flags late ranks; per detection
+ * group applies Eq. 1 (baseline), Eq. 2 (round of largest range), Eq. 3 (slowdown ratio against
+ * theta), Eq. 4 (P against alpha/beta, root = rank of minimal communication time) and the
+ * repetition counter; raises hang alerts for operations in flight longer than the hang threshold
+ * (barriers excepted) with the not-entered / inconsistent / hardware branch of the hang decision
+ * tree.  now_ns is the analyzer's clock.  Per-rank blame of this window is kept for
+ * ccld_rank_blame.  Returns out->status. */
+ccld_status ccld_analyze_window(ccld_ctx *ctx, int64_t now_ns, ccld_window_result *out);
+
+/* Per-rank blame of the most recent ccld_analyze_window: blame = device [CCLD_BLM_NCOL][n_ranks]
+ * (late-entry and late-exit counts, their summed lags, records seen); order = device [n_ranks]
+ * ranks sorted by (number of flags descending, summed lag descending, rank ascending).  Either
+ * pointer may be NULL.  The first entries of order[] name the faulty rank(s) (Section 1: "precisely
+ * identifying the faulty GPU rank"). */
+ccld_status ccld_rank_blame(ccld_ctx *ctx, int64_t *blame, uint32_t *order);
+
+const char *ccld_status_str(ccld_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CCLD_H */

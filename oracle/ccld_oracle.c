@@ -48,7 +48,7 @@ enum { FLAG_LATE_ENTER = 1, FLAG_LATE_EXIT = 2 };
 enum { SEG_COMM, SEG_SEQ, SEG_N, SEG_INFLIGHT, SEG_STATE, SEG_OP, SEG_BYTES,
        SEG_ENTER_MIN, SEG_ENTER_MED, SEG_ENTER_MAX, SEG_ENTER_MAD,
        SEG_EXIT_MIN, SEG_EXIT_MED, SEG_EXIT_MAX, SEG_EXIT_MAD,
-       SEG_DUR_MIN, SEG_DUR_MAX, SEG_ARGMIN_RANK, SEG_ARGMAX_RANK, SEG_INFLIGHT_ENTER_MIN, SEG_NCOL };
+       SEG_DUR_MIN, SEG_DUR_MAX, SEG_ARGMIN_RANK, SEG_ARGMAX_RANK, SEG_INFLIGHT_ENTER_MIN, SEG_FIRST, SEG_NCOL };
 enum { FLG_COMM, FLG_SEQ, FLG_RANK, FLG_KIND, FLG_LAG_ENTER, FLG_LAG_EXIT, FLG_NCOL };
 enum { GRP_COMM, GRP_OP, GRP_CLS, GRP_N_USABLE, GRP_RSTAR_SEQ, GRP_TMAX, GRP_TMIN, GRP_TBASE, GRP_STATIC,
        GRP_FROZEN, GRP_M, GRP_SLOW, GRP_CLASS, GRP_ROOT_S1, GRP_ROOT_S2, GRP_REPEATS, GRP_LOCATE, GRP_NCOL };
@@ -237,6 +237,7 @@ int orc_analyze_window(const int64_t *P, const orc_topology *T, uint64_t n,
                    (barrier ? SEG_BARRIER : 0) | (usable ? SEG_USABLE : 0);
     S[SEG_OP] = op[i0]; S[SEG_BYTES] = (int64_t)bytes[i0];
     S[SEG_INFLIGHT_ENTER_MIN] = infl_enter_min;
+    S[SEG_FIRST] = (int64_t)a;   /* position of the round's first record in the sorted order */
     S[SEG_ARGMIN_RANK] = ORC_NO_RANK; S[SEG_ARGMAX_RANK] = ORC_NO_RANK;
     /* statistics over the records of this round that have completed */
     int64_t dmin = 0, dmax = 0;

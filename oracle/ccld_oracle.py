@@ -34,7 +34,7 @@ DEFAULT_PARAMS: Dict[str, int] = dict(
 
 SEG_COLS = ("comm", "seq", "n", "inflight", "state", "op", "bytes", "enter_min", "enter_med", "enter_max",
             "enter_mad", "exit_min", "exit_med", "exit_max", "exit_mad", "dur_min", "dur_max", "argmin_rank",
-            "argmax_rank", "inflight_enter_min")
+            "argmax_rank", "inflight_enter_min", "first")
 FLAG_COLS = ("comm", "seq", "rank", "kind", "lag_enter", "lag_exit")
 GROUP_COLS = ("comm", "op", "cls", "n_usable", "rstar_seq", "tmax", "tmin", "tbase", "static", "frozen", "m",
               "slow", "class", "root_s1", "root_s2", "repeats", "locate")

@@ -1,0 +1,472 @@
+// extern "C" entry points: context set-up, workspace carving, ingest, window analysis, blame.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "ccld_internal.h"
+#include "window_kernels.h"
+
+using namespace ccld;
+
+#define HIP_TRY(x) do { if ((x) != hipSuccess) { (void)hipGetLastError(); return CCLD_E_HIP; } } while (0)
+
+static int bits_for_host(uint64_t v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
+
+namespace {
+
+// Bump allocator over the caller's workspace; with base == nullptr it only measures.
+struct Carver {
+  uint8_t* base; uint64_t off;
+  template <class T> T* take(uint64_t count) {
+    off = (off + 255) & ~(uint64_t)255;
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+struct TopoCounts { uint64_t n_members; };
+
+void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint64_t n_members) {
+  const uint64_t N = std::max<uint64_t>(c->cap, 1), B = std::max<uint64_t>(c->batch_cap, 1);
+  // topology
+  c->topo.algo = w.take<uint8_t>(n_comms);
+  c->topo.size = w.take<uint32_t>(n_comms);
+  c->topo.member_off = w.take<uint32_t>(n_comms);
+  c->topo.members = w.take<uint32_t>(n_members);
+  c->topo.members_sorted = w.take<uint32_t>(n_members);
+  c->topo.tree_parent = w.take<int32_t>(n_members);
+  c->topo.rank_comm_off = w.take<uint32_t>((uint64_t)n_ranks + 1);
+  c->topo.rank_comms = w.take<uint32_t>(n_members);
+  // window
+  c->win_key = w.take<uint64_t>(N);
+  c->win_row = w.take<Row>(N);
+  c->batch_meta = w.take<BatchMeta>((uint64_t)c->p.window_batches + 2);
+  // sort
+  const uint64_t tw = sort_table_words(N);
+  for (int i = 0; i < 2; ++i) { c->sb.key[i] = w.take<uint64_t>(N); c->sb.idx[i] = w.take<uint32_t>(N); }
+  c->sb.table = w.take<uint32_t>(tw);
+  c->sb.totals = w.take<uint32_t>(SORT_RADIX);
+  c->keyC = w.take<uint64_t>(N); c->idxC = w.take<uint32_t>(N);
+  c->table2 = w.take<uint32_t>(tw);
+  c->totals2 = w.take<uint32_t>(SORT_RADIX);
+  // analysis scratch
+  const uint64_t seg_tiles = (N + SEG_TILE - 1) / SEG_TILE, sel_tiles = (N + SEL_TILE - 1) / SEL_TILE;
+  c->tile_heads = w.take<uint32_t>(seg_tiles + 2);
+  c->tile_flags = w.take<uint32_t>(sel_tiles + 2);
+  c->rec_flag = w.take<uint8_t>(N);
+  c->flag_pos = w.take<uint32_t>(N);
+  c->flag_lag = w.take<int64_t>(2 * N);
+  c->big_list = w.take<uint32_t>(2 * (seg_tiles + 2));
+  c->big_ex = w.take<int64_t>(2 * N);
+  c->rank_partial = w.take<uint32_t>((uint64_t)RANKCOUNT_BLOCKS * n_ranks);
+  c->blame = w.take<int64_t>((uint64_t)CCLD_BLM_NCOL * n_ranks);
+  c->usable_list = w.take<uint32_t>(N);
+  c->group_first = w.take<uint32_t>(N + 1);
+  c->alert_list = w.take<uint32_t>(N);
+  c->alert_ncand = w.take<uint32_t>(N + 2);
+  c->gstate = w.take<GroupState>((uint64_t)n_comms * GROUP_SLOTS);
+  c->counters = w.take<uint64_t>(CNT_COUNT);
+  c->stage = w.take<uint8_t>(B * 48);
+}
+
+ccld_status check_params(const ccld_params* p) {
+  if (!p) return CCLD_E_NULL;
+  if (p->tbase_rounds < 1 || p->theta_den < 1 || p->ab_den < 1 || p->kmad_den < 1 || p->tbase_warmup_ns < 0 ||
+      p->window_batches < 1 || p->window_batches > 4096 || p->hang_threshold_ns < 0)
+    return CCLD_E_BAD_ARG;
+  return CCLD_OK;
+}
+
+ccld_status check_topology(const ccld_topology* t, uint64_t* n_members) {
+  if (!t) return CCLD_E_NULL;
+  if (t->n_ranks == 0 || t->n_comms == 0) return CCLD_E_BAD_TOPOLOGY;
+  if (!t->algo || !t->size || !t->member_off || !t->members) return CCLD_E_NULL;
+  uint64_t total = 0;
+  for (uint32_t c = 0; c < t->n_comms; ++c) {
+    if (t->size[c] == 0 || t->algo[c] > CCLD_ALGO_TREE) return CCLD_E_BAD_TOPOLOGY;
+    if (t->member_off[c] != total) return CCLD_E_BAD_TOPOLOGY;     // packed CSR
+    total += t->size[c];
+    if (total > 0xFFFFFFFFull) return CCLD_E_BAD_TOPOLOGY;
+  }
+  for (uint32_t c = 0; c < t->n_comms; ++c) {
+    std::vector<uint32_t> m(t->members + t->member_off[c], t->members + t->member_off[c] + t->size[c]);
+    std::sort(m.begin(), m.end());
+    for (size_t i = 0; i < m.size(); ++i)
+      if (m[i] >= t->n_ranks || (i > 0 && m[i] == m[i - 1])) return CCLD_E_BAD_TOPOLOGY;
+    if (t->algo[c] == CCLD_ALGO_TREE) {
+      if (!t->tree_parent) return CCLD_E_BAD_TOPOLOGY;
+      int roots = 0;
+      for (uint32_t q = 0; q < t->size[c]; ++q) {
+        int32_t par = t->tree_parent[t->member_off[c] + q];
+        if (par < 0) ++roots;
+        else if ((uint32_t)par >= q) return CCLD_E_BAD_TOPOLOGY;   // BFS order: parents come first
+      }
+      if (roots != 1) return CCLD_E_BAD_TOPOLOGY;
+    }
+  }
+  *n_members = total;
+  return CCLD_OK;
+}
+
+ccld_status data_status(uint64_t bits) {
+  if (bits & DS_UNKNOWN_COMM) return CCLD_E_UNKNOWN_COMM;
+  if (bits & DS_NOT_MEMBER) return CCLD_E_RANK_NOT_MEMBER;
+  if (bits & DS_RANGE) return CCLD_E_RANGE;
+  if (bits & DS_KEY_WIDTH) return CCLD_E_KEY_WIDTH;
+  if (bits & DS_DUPLICATE) return CCLD_E_DUPLICATE_KEY;
+  if (bits & DS_SNAPSHOT_GAP) return CCLD_E_SNAPSHOT_GAP;
+  return CCLD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ccld_status ccld_default_params(ccld_params* p) {
+  if (!p) return CCLD_E_NULL;
+  std::memset(p, 0, sizeof(*p));
+  p->hang_threshold_ns = 300000000000ll;
+  p->tbase_init_ns = INT64_MAX / 4;
+  p->tbase_rounds = 100;
+  p->repeat_threshold = 2;
+  p->tbase_warmup_ns = 120000000000ll;
+  p->theta_num = 3; p->theta_den = 1;
+  p->alpha_num = 4; p->beta_num = 6; p->ab_den = 10;
+  p->barrier_bytes = 4;
+  p->kmad_num = 9; p->kmad_den = 2;
+  p->lag_floor_ns = 300000;
+  p->stall_snapshots = 30;
+  p->fifo_depth = 8;
+  p->window_batches = 1;
+  return CCLD_OK;
+}
+
+ccld_status ccld_query_workspace(const ccld_params* params, const ccld_topology* topo, uint64_t max_window_records,
+                                 uint64_t max_batch_records, uint64_t max_snapshot_rows, uint64_t* bytes) {
+  if (!bytes) return CCLD_E_NULL;
+  ccld_status s = check_params(params);
+  if (s != CCLD_OK) return s;
+  uint64_t n_members = 0;
+  s = check_topology(topo, &n_members);
+  if (s != CCLD_OK) return s;
+  if (max_window_records >= (1ull << 31) || max_batch_records > max_window_records ||
+      max_snapshot_rows >= (1ull << 31))
+    return CCLD_E_CAPACITY;
+  ccld_ctx tmp;
+  tmp.p = *params; tmp.cap = max_window_records; tmp.batch_cap = max_batch_records; tmp.snap_cap = max_snapshot_rows;
+  Carver w{nullptr, 0};
+  carve_all(&tmp, w, topo->n_ranks, topo->n_comms, n_members);
+  *bytes = w.off + 256;
+  return CCLD_OK;
+}
+
+ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, uint64_t max_window_records,
+                        uint64_t max_batch_records, uint64_t max_snapshot_rows, void* workspace,
+                        uint64_t workspace_bytes, void* hip_stream, ccld_ctx** out) {
+  if (!out || !workspace) return CCLD_E_NULL;
+  *out = nullptr;
+  uint64_t need = 0;
+  ccld_status s = ccld_query_workspace(params, topo, max_window_records, max_batch_records, max_snapshot_rows, &need);
+  if (s != CCLD_OK) return s;
+  if (workspace_bytes < need || ((uintptr_t)workspace & 255) != 0) return CCLD_E_WORKSPACE;
+  const int rb = bits_for_host(topo->n_ranks - 1), cb = bits_for_host(topo->n_comms - 1);
+  if (rb + cb > 63) return CCLD_E_KEY_WIDTH;
+  ccld_ctx* c = new (std::nothrow) ccld_ctx();
+  if (!c) return CCLD_E_BAD_ARG;
+  c->p = *params;
+  c->stream = (hipStream_t)hip_stream;
+  c->cap = max_window_records; c->batch_cap = max_batch_records; c->snap_cap = max_snapshot_rows;
+  c->kf.rb = rb; c->kf.cb = cb; c->kf.sb = 64 - rb - cb;
+  c->head = 0; c->count = 0; c->next_slot = 0;
+  c->sorted_buf = 0; c->last_n = 0; c->blame_valid = false;
+  c->sf.rb = rb; c->sf.ws = 0;
+  uint64_t n_members = 0;
+  check_topology(topo, &n_members);
+  Carver w{(uint8_t*)workspace, 0};
+  carve_all(c, w, topo->n_ranks, topo->n_comms, n_members);
+  c->topo.n_ranks = topo->n_ranks; c->topo.n_comms = topo->n_comms;
+  c->h_size.assign(topo->size, topo->size + topo->n_comms);
+  c->h_pinned = nullptr;
+
+  // derived host tables: sorted member lists, rank -> communicators CSR
+  std::vector<uint32_t> sorted(topo->members, topo->members + n_members);
+  std::vector<uint32_t> rc_off((size_t)topo->n_ranks + 1, 0), rc(n_members);
+  std::vector<int32_t> parent(n_members, -1);
+  for (uint32_t k = 0; k < topo->n_comms; ++k) {
+    std::sort(sorted.begin() + topo->member_off[k], sorted.begin() + topo->member_off[k] + topo->size[k]);
+    for (uint32_t q = 0; q < topo->size[k]; ++q) rc_off[topo->members[topo->member_off[k] + q] + 1] += 1;
+  }
+  for (uint32_t r = 0; r < topo->n_ranks; ++r) rc_off[r + 1] += rc_off[r];
+  {
+    std::vector<uint32_t> fill(rc_off.begin(), rc_off.end() - 1);
+    for (uint32_t k = 0; k < topo->n_comms; ++k)
+      for (uint32_t q = 0; q < topo->size[k]; ++q) rc[fill[topo->members[topo->member_off[k] + q]]++] = k;
+  }
+  if (topo->tree_parent) parent.assign(topo->tree_parent, topo->tree_parent + n_members);
+
+  ccld_status rs = CCLD_OK;
+  auto up = [&](const void* dst, const void* src, size_t bytes) {
+    if (bytes && hipMemcpyAsync(const_cast<void*>(dst), src, bytes, hipMemcpyHostToDevice, c->stream) != hipSuccess)
+      rs = CCLD_E_HIP;
+  };
+  up(c->topo.algo, topo->algo, topo->n_comms);
+  up(c->topo.size, topo->size, 4ull * topo->n_comms);
+  up(c->topo.member_off, topo->member_off, 4ull * topo->n_comms);
+  up(c->topo.members, topo->members, 4ull * n_members);
+  up(c->topo.members_sorted, sorted.data(), 4ull * n_members);
+  up(c->topo.tree_parent, parent.data(), 4ull * n_members);
+  up(c->topo.rank_comm_off, rc_off.data(), 4ull * rc_off.size());
+  up(c->topo.rank_comms, rc.data(), 4ull * n_members);
+  if (hipMemsetAsync(c->gstate, 0, sizeof(GroupState) * (uint64_t)topo->n_comms * GROUP_SLOTS, c->stream) != hipSuccess) rs = CCLD_E_HIP;
+  if (hipMemsetAsync(c->batch_meta, 0, sizeof(BatchMeta) * ((uint64_t)c->p.window_batches + 2), c->stream) != hipSuccess) rs = CCLD_E_HIP;
+  if (hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, c->stream) != hipSuccess) rs = CCLD_E_HIP;
+  if (hipMemsetAsync(c->blame, 0, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)topo->n_ranks, c->stream) != hipSuccess) rs = CCLD_E_HIP;
+  if (hipHostMalloc((void**)&c->h_pinned, 4096 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) rs = CCLD_E_HIP;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) rs = CCLD_E_HIP;   // host vectors above die at return
+  if (rs != CCLD_OK) { (void)hipGetLastError(); if (c->h_pinned) (void)hipHostFree(c->h_pinned); delete c; return rs; }
+  *out = c;
+  return CCLD_OK;
+}
+
+ccld_status ccld_destroy(ccld_ctx* c) {
+  if (!c) return CCLD_E_NULL;
+  (void)hipStreamSynchronize(c->stream);
+  if (c->h_pinned) (void)hipHostFree(c->h_pinned);
+  delete c;
+  return CCLD_OK;
+}
+
+ccld_status ccld_reset_window(ccld_ctx* c) {
+  if (!c) return CCLD_E_NULL;
+  c->head = 0; c->count = 0; c->batch_n.clear(); c->batch_slot.clear();
+  return CCLD_OK;
+}
+
+ccld_status ccld_ingest(ccld_ctx* c, const ccld_records* b, uint64_t n) {
+  if (!c || !b) return CCLD_E_NULL;
+  if (n && (!b->rank || !b->comm || !b->seq || !b->op || !b->bytes || !b->t_enter || !b->t_exit)) return CCLD_E_NULL;
+  if (n > c->batch_cap) return CCLD_E_CAPACITY;
+  // drop the oldest batch once the window holds window_batches of them
+  uint64_t head = c->head, count = c->count;
+  size_t drop = 0;
+  if (c->batch_n.size() >= c->p.window_batches) {
+    drop = c->batch_n.size() - c->p.window_batches + 1;
+    for (size_t i = 0; i < drop; ++i) { head = (head + c->batch_n[i]) % std::max<uint64_t>(c->cap, 1); count -= c->batch_n[i]; }
+  }
+  if (count + n > c->cap) return CCLD_E_CAPACITY;
+  IngestArgs a;
+  std::memset(&a, 0, sizeof(a));
+  const uint32_t slot = c->next_slot;
+  a.meta = c->batch_meta + slot;
+  HIP_TRY(hipMemsetAsync(a.meta, 0, sizeof(BatchMeta), c->stream));
+  if (b->on_device) {
+    a.rank = b->rank; a.comm = b->comm; a.seq = b->seq; a.op = b->op; a.bytes = b->bytes;
+    a.t_enter = b->t_enter; a.t_exit = b->t_exit;
+  } else if (n) {
+    // host batch: copy the seven columns into the staging area, 8-byte columns first
+    uint8_t* s = c->stage;
+    uint64_t* d_seq = (uint64_t*)s; uint64_t* d_bytes = d_seq + n; int64_t* d_te = (int64_t*)(d_bytes + n);
+    int64_t* d_tx = d_te + n; uint32_t* d_rank = (uint32_t*)(d_tx + n); uint32_t* d_comm = d_rank + n;
+    uint8_t* d_op = (uint8_t*)(d_comm + n);
+    HIP_TRY(hipMemcpyAsync(d_seq, b->seq, 8 * n, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(d_bytes, b->bytes, 8 * n, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(d_te, b->t_enter, 8 * n, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(d_tx, b->t_exit, 8 * n, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(d_rank, b->rank, 4 * n, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(d_comm, b->comm, 4 * n, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(d_op, b->op, n, hipMemcpyHostToDevice, c->stream));
+    a.rank = d_rank; a.comm = d_comm; a.seq = d_seq; a.op = d_op; a.bytes = d_bytes; a.t_enter = d_te; a.t_exit = d_tx;
+  }
+  a.n = n; a.win_key = c->win_key; a.win_row = c->win_row;
+  a.tail = (uint32_t)((head + count) % std::max<uint64_t>(c->cap, 1));
+  a.cap = (uint32_t)c->cap;
+  launch_ingest(c->stream, a, c->topo, c->kf);
+  HIP_TRY(hipGetLastError());
+  if (!b->on_device && n) HIP_TRY(hipStreamSynchronize(c->stream));   // the host buffers may go away on return
+  c->batch_n.erase(c->batch_n.begin(), c->batch_n.begin() + drop);
+  c->batch_slot.erase(c->batch_slot.begin(), c->batch_slot.begin() + drop);
+  c->batch_n.push_back(n);
+  c->batch_slot.push_back(slot);
+  c->next_slot = (slot + 1) % (c->p.window_batches + 2);
+  c->head = head; c->count = count + n;
+  return CCLD_OK;
+}
+
+static void zero_counts(ccld_window_result* o) {
+  o->n_records = o->n_seg = o->n_flag = o->n_group = o->n_alert = o->n_cand = 0;
+}
+
+ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result* o) {
+  if (!c || !o) return CCLD_E_NULL;
+  zero_counts(o);
+  o->status = CCLD_OK;
+  c->blame_valid = false;
+  if (!o->seg || o->seg_cap == 0) return o->status = CCLD_E_NULL;
+  if ((o->flag_cap && !o->flag) || (o->group_cap && !o->group) || (o->alert_cap && !o->alert) ||
+      (o->cand_cap && !o->cand))
+    return o->status = CCLD_E_NULL;
+  hipStream_t st = c->stream;
+  const uint32_t n = (uint32_t)c->count;
+  const uint32_t n_ranks = c->topo.n_ranks;
+
+  // 1. data errors found at ingest, and the widest sequence number in the window
+  const size_t nb = c->batch_slot.size();
+  uint64_t bits = 0, max_seq = 0;
+  if (nb) {
+    const uint32_t n_meta = c->p.window_batches + 2;
+    HIP_TRY(hipMemcpyAsync(c->h_pinned, c->batch_meta, sizeof(BatchMeta) * n_meta, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    const BatchMeta* hm = (const BatchMeta*)c->h_pinned;
+    for (size_t i = 0; i < nb; ++i) { bits |= hm[c->batch_slot[i]].status; max_seq = std::max(max_seq, hm[c->batch_slot[i]].max_seq); }
+  }
+  if (bits) return o->status = data_status(bits);
+  o->n_records = n;
+  HIP_TRY(hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st));
+  HIP_TRY(hipMemsetAsync(c->blame, 0, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)n_ranks, st));
+  c->last_n = n;
+  if (n == 0) { HIP_TRY(hipStreamSynchronize(st)); c->blame_valid = true; return o->status; }
+
+  // 2. sort by (communicator, operation counter, rank) on the significant bits only
+  const int rb = c->kf.rb, cb = c->kf.cb, ws = bits_for_host(max_seq);
+  c->sf.rb = rb; c->sf.ws = ws;
+  KeySource src;
+  src.key = c->win_key; src.head = (uint32_t)c->head; src.cap = (uint32_t)c->cap;
+  src.squeeze = cb > 0 ? 1 : 0;
+  src.hi_shift = cb > 0 ? 64 - cb : 0;
+  src.lo_bits = rb + ws;
+  src.lo_mask = (rb + ws) >= 64 ? ~0ull : (((uint64_t)1 << (rb + ws)) - 1);
+  const int sorted = radix_sort_pairs(st, src, n, c->sb, rb + ws + cb);
+  if (sorted < 0) return o->status = CCLD_E_HIP;
+  c->sorted_buf = sorted;
+  const uint64_t* skey = c->sb.key[sorted];
+  const uint32_t* sidx = c->sb.idx[sorted];
+
+  // 3. collectives: heads per tile, their scan, statistics, flags
+  SegArgs sa;
+  std::memset(&sa, 0, sizeof(sa));
+  sa.key = skey; sa.idx = sidx; sa.row = c->win_row; sa.n = n; sa.sf = c->sf; sa.comm_size = c->topo.size;
+  sa.tile_heads = c->tile_heads; sa.seg = o->seg; sa.seg_cap = o->seg_cap;
+  sa.rec_flag = o->rec_flag ? o->rec_flag : c->rec_flag;
+  sa.lag_e = o->lag_enter; sa.lag_x = o->lag_exit; sa.flag_lag = c->flag_lag; sa.cap_n = c->cap;
+  sa.big_list = c->big_list; sa.big_ex = c->big_ex; sa.counters = c->counters;
+  sa.lag_floor = c->p.lag_floor_ns; sa.kmad_num = c->p.kmad_num; sa.kmad_den = c->p.kmad_den;
+  sa.barrier_bytes = c->p.barrier_bytes;
+  const uint32_t seg_tiles = (n + SEG_TILE - 1) / SEG_TILE;
+  launch_seg_count(st, sa);
+  launch_scan_tiles(st, c->tile_heads, seg_tiles, &c->counters[CNT_NSEG]);
+  launch_rank_count(st, skey, n, rb, n_ranks, c->rank_partial, c->blame);
+  launch_seg_analyze(st, sa);
+  FlagArgs fa;
+  std::memset(&fa, 0, sizeof(fa));
+  fa.key = skey; fa.rec_flag = sa.rec_flag; fa.flag_lag = c->flag_lag; fa.cap_n = c->cap; fa.n = n; fa.sf = c->sf;
+  fa.tile_flags = c->tile_flags; fa.flag_pos = c->flag_pos; fa.flag = o->flag; fa.flag_cap = o->flag_cap;
+  fa.counters = c->counters;
+  launch_flag_compact(st, fa);
+  if (o->perm) launch_perm(st, sidx, n, (uint32_t)c->head, (uint32_t)c->cap, o->perm);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (c->h_pinned[CNT_STATUS]) { zero_counts(o); return o->status = data_status(c->h_pinned[CNT_STATUS]); }
+  o->n_seg = c->h_pinned[CNT_NSEG];
+  o->n_flag = c->h_pinned[CNT_NFLAG];
+  const uint32_t n_flag = (uint32_t)o->n_flag;
+  const uint32_t seg_rows = (uint32_t)std::min<uint64_t>(o->n_seg, o->seg_cap);
+  if (o->n_seg > o->seg_cap || o->n_flag > o->flag_cap) o->status = CCLD_W_TRUNCATED;
+
+  // 4. blame: flags keyed by rank, sorted, one wavefront per rank sums its run
+  SortBuffers sb2;
+  sb2.key[0] = c->sb.key[1 - sorted]; sb2.idx[0] = c->sb.idx[1 - sorted];
+  sb2.key[1] = c->keyC; sb2.idx[1] = c->idxC; sb2.table = c->table2; sb2.totals = c->totals2;
+  if (n_flag) {
+    uint64_t* bk = c->keyC;       // keys are written to C, first pass sorts C -> buffer 0 of sb2
+    launch_blame_keys(st, skey, c->flag_pos, n_flag, rb, bk);
+    KeySource bs; bs.key = bk; bs.head = 0; bs.cap = n_flag; bs.squeeze = 0; bs.hi_shift = 0; bs.lo_bits = 0; bs.lo_mask = 0;
+    const int r2 = radix_sort_pairs(st, bs, n_flag, sb2, rb);
+    if (r2 < 0) return o->status = CCLD_E_HIP;
+    launch_blame_reduce(st, sb2.key[r2], sb2.idx[r2], n_flag, c->flag_pos, sa.rec_flag, c->flag_lag, c->cap, n_ranks, c->blame);
+  }
+
+  // 5. slow detection and location per detection group (Eq. 1-4)
+  GroupArgs ga;
+  std::memset(&ga, 0, sizeof(ga));
+  ga.seg = o->seg; ga.seg_cap = o->seg_cap; ga.n_seg = seg_rows; ga.ws = ws; ga.cb = cb;
+  ga.usable_list = c->usable_list; ga.tile_counts = c->tile_flags; ga.counters = c->counters;
+  ga.gstate = c->gstate; ga.group = o->group; ga.group_cap = o->group_cap; ga.p = c->p;
+  launch_usable_select(st, ga);
+  // 6. hang alerts
+  AlertArgs aa;
+  std::memset(&aa, 0, sizeof(aa));
+  aa.seg = o->seg; aa.seg_cap = o->seg_cap; aa.n_seg = seg_rows; aa.now_ns = now_ns;
+  aa.hang_threshold_ns = c->p.hang_threshold_ns; aa.key = skey; aa.idx = sidx; aa.row = c->win_row; aa.n = n;
+  aa.sf = c->sf; aa.topo = c->topo; aa.tile_counts = c->tile_heads; aa.alert_list = c->alert_list;
+  aa.alert_ncand = c->alert_ncand; aa.alert = o->alert; aa.alert_cap = o->alert_cap; aa.cand = o->cand;
+  aa.cand_cap = o->cand_cap; aa.counters = c->counters;
+  launch_alert_select(st, aa);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  const uint32_t n_usable = (uint32_t)c->h_pinned[CNT_NUSABLE];
+  o->n_alert = c->h_pinned[CNT_NALERT];
+  if (n_usable) {
+    if (cb + 10 + ws > 64) return o->status = CCLD_E_KEY_WIDTH;
+    ga.gkey = c->keyC;            // blame's sort is done with C by stream order
+    launch_group_keys(st, ga, n_usable);
+    KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = n_usable; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0;
+    // sort C -> buffers {other main, C}: the first pass reads C and writes buffer 0, so C is free again for pass 2
+    const int r3 = radix_sort_pairs(st, gs, n_usable, sb2, cb + 10 + ws);
+    if (r3 < 0) return o->status = CCLD_E_HIP;
+    launch_group_heads(st, sb2.key[r3], n_usable, ws, c->tile_flags, c->group_first, c->counters);
+    HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    o->n_group = c->h_pinned[CNT_NGROUP];
+    launch_group_eval(st, ga, sb2.key[r3], sb2.idx[r3], n_usable, c->group_first, (uint32_t)o->n_group);
+    if (o->n_group > o->group_cap) o->status = CCLD_W_TRUNCATED;
+  }
+  if (o->n_alert) {
+    launch_alert_candidates(st, aa, (uint32_t)o->n_alert);
+    HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    o->n_cand = c->h_pinned[CNT_NCAND];
+    if (o->n_alert > o->alert_cap || o->n_cand > o->cand_cap) o->status = CCLD_W_TRUNCATED;
+  }
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(st));
+  c->blame_valid = true;
+  return o->status;
+}
+
+ccld_status ccld_rank_blame(ccld_ctx* c, int64_t* blame, uint32_t* order) {
+  if (!c) return CCLD_E_NULL;
+  if (!c->blame_valid) return CCLD_E_BAD_ARG;
+  const uint32_t n_ranks = c->topo.n_ranks;
+  if (blame)
+    HIP_TRY(hipMemcpyAsync(blame, c->blame, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)n_ranks,
+                           hipMemcpyDeviceToDevice, c->stream));
+  if (order) launch_blame_order(c->stream, c->blame, n_ranks, order);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  return CCLD_OK;
+}
+
+const char* ccld_status_str(ccld_status s) {
+  switch (s) {
+    case CCLD_OK: return "OK";
+    case CCLD_E_UNKNOWN_COMM: return "E_UNKNOWN_COMM";
+    case CCLD_E_RANK_NOT_MEMBER: return "E_RANK_NOT_MEMBER";
+    case CCLD_E_RANGE: return "E_RANGE";
+    case CCLD_E_DUPLICATE_KEY: return "E_DUPLICATE_KEY";
+    case CCLD_E_SNAPSHOT_GAP: return "E_SNAPSHOT_GAP";
+    case CCLD_E_BAD_ARG: return "E_BAD_ARG";
+    case CCLD_E_NULL: return "E_NULL";
+    case CCLD_E_CAPACITY: return "E_CAPACITY";
+    case CCLD_E_KEY_WIDTH: return "E_KEY_WIDTH";
+    case CCLD_E_BAD_TOPOLOGY: return "E_BAD_TOPOLOGY";
+    case CCLD_E_HIP: return "E_HIP";
+    case CCLD_E_WORKSPACE: return "E_WORKSPACE";
+    case CCLD_W_TRUNCATED: return "W_TRUNCATED";
+    default: return "E_UNKNOWN";
+  }
+}
+
+}  // extern "C"

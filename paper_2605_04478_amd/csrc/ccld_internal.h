@@ -1,0 +1,117 @@
+// Context layout and kernel-launcher declarations shared by the translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "ccld.h"
+#include "radix_sort.h"
+
+namespace ccld {
+
+// One stored record: the payload the analysis gathers by sorted position (32 bytes, one
+// aligned access); rank, communicator and sequence number live in the key.
+struct __attribute__((aligned(32))) Row {
+  int64_t t_enter, t_exit;
+  uint64_t bytes;
+  uint32_t op, pad;
+};
+
+// Key layout at ingest: comm << (64 - cb) | seq << rb | rank, with rb / cb the bit widths of
+// the largest rank / communicator id.  The sort squeezes the unused middle bits out.
+struct KeyFormat {
+  int rb, cb;          // rank bits, communicator bits
+  int sb;              // bits available to the sequence number: 64 - rb - cb
+};
+
+// Squeezed key used from the sort onwards: comm << (rb + ws) | seq << rb | rank.
+struct SqueezedFormat {
+  int rb, ws;          // rank bits, sequence bits actually present in this window
+};
+
+struct DeviceTopology {
+  uint32_t n_ranks, n_comms;
+  const uint8_t* algo;
+  const uint32_t* size;
+  const uint32_t* member_off;
+  const uint32_t* members;
+  const uint32_t* members_sorted;   // each communicator's members in ascending rank order
+  const int32_t* tree_parent;
+  const uint32_t* rank_comm_off;    // [n_ranks + 1] CSR: communicators each rank belongs to
+  const uint32_t* rank_comms;
+};
+
+// Eq. 1 state and repetition counter of one detection group (communicator, op, size class).
+struct GroupState {
+  uint32_t cnt, frozen, repeats, pad;
+  int64_t sum, t0, tbase_dyn;
+  uint64_t baselined_wm, baseline_last_seq, detected_wm;
+};
+constexpr int GROUP_CLS = 64;
+constexpr int GROUP_SLOTS = CCLD_OP_MAX * GROUP_CLS;
+
+// status bits accumulated on the device
+enum { DS_UNKNOWN_COMM = 1, DS_NOT_MEMBER = 2, DS_RANGE = 4, DS_KEY_WIDTH = 8, DS_DUPLICATE = 16,
+       DS_SNAPSHOT_GAP = 32 };
+
+struct BatchSlot { uint64_t n; };
+
+// device-side header of per-batch results: [status bits, max sequence number]
+struct BatchMeta { uint64_t status; uint64_t max_seq; };
+
+constexpr int SEG_TILE = 1024;       // sorted records owned by one workgroup of the segment kernels
+constexpr int SEG_HALO = 256;        // records past the tile a workgroup may read to finish its last collective
+constexpr int SEG_THREADS = 256;
+constexpr int SEL_TILE = 2048;       // records per workgroup of the compaction kernels
+constexpr int RANKCOUNT_BLOCKS = 256;
+
+// device counters written by kernels and read back by the host
+enum { CNT_NSEG, CNT_NFLAG, CNT_NBIG, CNT_NUSABLE, CNT_NGROUP, CNT_NALERT, CNT_NCAND, CNT_STATUS, CNT_COUNT = 16 };
+
+}  // namespace ccld
+
+struct ccld_ctx {
+  ccld_params p;
+  hipStream_t stream;
+  uint64_t cap, batch_cap, snap_cap;
+  ccld::KeyFormat kf;
+  // topology
+  std::vector<uint32_t> h_size;
+  ccld::DeviceTopology topo;
+  // window (circular)
+  uint64_t head, count;
+  std::vector<uint64_t> batch_n;      // sizes of the resident batches, oldest first
+  std::vector<uint32_t> batch_slot;   // meta slot of each resident batch
+  uint32_t next_slot;
+  uint64_t* win_key;
+  ccld::Row* win_row;
+  ccld::BatchMeta* batch_meta;        // [window_batches + 1]
+  // sort
+  ccld::SortBuffers sb;               // main sort
+  uint64_t* keyC; uint32_t* idxC;     // third pair for the small sorts
+  uint32_t* table2; uint32_t* totals2;
+  // analysis scratch
+  uint32_t* tile_heads;               // [seg tiles + 1]
+  uint32_t* tile_flags;               // [sel tiles + 1]
+  uint8_t* rec_flag;                  // [cap]
+  uint32_t* flag_pos;                 // [cap] sorted position of the k-th flagged record
+  int64_t* flag_lag;                  // [2][cap]
+  uint32_t* big_list;                 // [cap / SEG_HALO + 2][2]  (segment ordinal, first position)
+  int64_t* big_ex;                    // [2][cap]
+  uint32_t* rank_partial;             // [RANKCOUNT_BLOCKS][n_ranks]
+  int64_t* blame;                     // [CCLD_BLM_NCOL][n_ranks]
+  uint32_t* usable_list;              // [cap]
+  uint32_t* group_first;              // [cap + 1]
+  uint32_t* alert_list;               // [cap]
+  uint32_t* alert_ncand;              // [cap + 1]
+  ccld::GroupState* gstate;           // [n_comms][GROUP_SLOTS]
+  uint64_t* counters;                 // [CNT_COUNT] device
+  uint64_t* h_pinned;                 // pinned host staging
+  // staging for host-resident batches
+  uint8_t* stage;                     // [batch_cap * 41] device
+  // last analysis
+  int sorted_buf;                     // which ping-pong buffer holds the sorted window
+  uint64_t last_n;
+  ccld::SqueezedFormat sf;
+  bool blame_valid;
+};

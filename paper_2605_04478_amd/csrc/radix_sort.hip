@@ -1,0 +1,199 @@
+// LSD radix sort of (u64 key, u32 index) pairs for gfx950.
+//
+// One pass = three kernels: per-tile digit histograms in LDS, an exclusive scan of
+// every digit's row of tile counts, and a scatter that ranks the tile's keys with
+// wavefront ballots (stable), regroups them by digit in LDS and writes each digit's
+// run to its place with consecutive lanes on consecutive addresses.
+#include "radix_sort.h"
+#include "device_utils.h"
+
+namespace ccld {
+
+__device__ __forceinline__ u64 load_key(const KeySource& s, u32 j, u32* phys) {
+  u32 p = s.head + j;                       // head < cap and j < cap, no overflow below 2^32 (cap <= 2^31)
+  if (p >= s.cap) p -= s.cap;
+  *phys = p;
+  u64 k = s.key[p];
+  if (s.squeeze) k = ((k >> s.hi_shift) << s.lo_bits) | (k & s.lo_mask);
+  return k;
+}
+
+// ---- per-tile digit histogram --------------------------------------------------------------
+template <bool FIRST>
+__global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, const u64* __restrict__ key_in,
+                                                             u32* __restrict__ table, u32 n, u32 n_tiles,
+                                                             int shift, u32 dmask) {
+  __shared__ u32 s_hist[SORT_RADIX];
+  const u32 tid = threadIdx.x, tile = blockIdx.x;
+  for (u32 i = tid; i < SORT_RADIX; i += SORT_THREADS) s_hist[i] = 0;
+  __syncthreads();
+  const u32 base = tile * SORT_TILE;
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; ++it) {
+    u32 j = base + it * SORT_THREADS + tid;
+    if (j < n) {
+      u64 k;
+      if (FIRST) { u32 ph; k = load_key(src, j, &ph); } else k = key_in[j];
+      atomicAdd(&s_hist[(u32)(k >> shift) & dmask], 1u);
+    }
+  }
+  __syncthreads();
+  for (u32 d = tid; d <= dmask; d += SORT_THREADS) table[(u64)d * n_tiles + tile] = s_hist[d];
+}
+
+// ---- exclusive scan of each digit's row of tile counts ------------------------------------
+__global__ __launch_bounds__(SORT_THREADS) void k_radix_scan(u32* __restrict__ table, u32* __restrict__ totals,
+                                                             u32 n_tiles) {
+  __shared__ u32 s_wave[SORT_THREADS / CCLD_WAVE];
+  u32* row = table + (u64)blockIdx.x * n_tiles;
+  u32 carry = 0;
+  for (u32 base = 0; base < n_tiles; base += SORT_THREADS) {
+    u32 i = base + threadIdx.x;
+    u32 v = i < n_tiles ? row[i] : 0u, tot;
+    u32 ex = block_exclusive_sum<SORT_THREADS>(v, s_wave, &tot);
+    if (i < n_tiles) row[i] = carry + ex;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) totals[blockIdx.x] = carry;
+}
+
+// ---- rank, regroup in LDS, scatter --------------------------------------------------------------
+template <bool FIRST>
+__global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, const u64* __restrict__ key_in,
+                                                                const u32* __restrict__ idx_in,
+                                                                u64* __restrict__ key_out, u32* __restrict__ idx_out,
+                                                                const u32* __restrict__ table,
+                                                                const u32* __restrict__ totals, u32 n, u32 n_tiles,
+                                                                int shift, int nbits) {
+  constexpr int NW = SORT_THREADS / CCLD_WAVE;
+  __shared__ u32 s_cnt[NW][SORT_RADIX];   // per-wavefront digit counters, then each wavefront's base inside the digit
+  __shared__ u32 s_dstart[SORT_RADIX];    // first tile-local position of each digit
+  __shared__ u32 s_gbase[SORT_RADIX];     // global position of tile-local position 0 of each digit (minus dstart)
+  __shared__ u32 s_wave[NW];
+  __shared__ u64 s_key[SORT_TILE];
+  __shared__ u32 s_idx[SORT_TILE];
+
+  const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE, tile = blockIdx.x;
+  const u32 dmask = (1u << nbits) - 1u;
+  const u32 base = tile * SORT_TILE;
+  const u32 valid = (n - base) < (u32)SORT_TILE ? (n - base) : (u32)SORT_TILE;
+
+  for (u32 i = tid; i < NW * SORT_RADIX; i += SORT_THREADS) (&s_cnt[0][0])[i] = 0;
+
+  // wavefront w owns tile elements [w*64*ITEMS, (w+1)*64*ITEMS); item `it` of lane l is element
+  // w*64*ITEMS + it*64 + l, so (wavefront, item, lane) order is input order
+  u64 k[SORT_ITEMS];
+  u32 v[SORT_ITEMS], dig[SORT_ITEMS], pre[SORT_ITEMS];
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; ++it) {
+    u32 e = wave * (CCLD_WAVE * SORT_ITEMS) + it * CCLD_WAVE + lane;
+    if (e < valid) {
+      if (FIRST) { k[it] = load_key(src, base + e, &v[it]); }
+      else { k[it] = key_in[base + e]; v[it] = idx_in[base + e]; }
+      dig[it] = (u32)(k[it] >> shift) & dmask;
+    } else {
+      k[it] = 0; v[it] = 0; dig[it] = dmask;   // padding sorts after every real key of the last digit
+    }
+  }
+  __syncthreads();
+
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; ++it) {
+    const u32 d = dig[it];
+    u64 same = ~0ull;                      // lanes of this wavefront holding the same digit
+#pragma unroll
+    for (int b = 0; b < SORT_RBITS; ++b) {
+      if (b < nbits) {
+        const bool bit = (d >> b) & 1u;
+        const u64 bal = ballot64(bit);
+        same &= bit ? bal : ~bal;
+      }
+    }
+    const u32 below = mbcnt64(same), cnt = (u32)__popcll(same);
+    const u32 old = s_cnt[wave][d];
+    __builtin_amdgcn_wave_barrier();
+    if (below == cnt - 1) s_cnt[wave][d] = old + cnt;
+    __builtin_amdgcn_wave_barrier();
+    pre[it] = old + below;
+  }
+  __syncthreads();
+
+  // per digit: base of each wavefront inside the digit, tile total; then digit starts
+  {
+    u32 tot = 0;
+    u32 gtot = 0;
+    if (tid < SORT_RADIX) {
+#pragma unroll
+      for (int w = 0; w < NW; ++w) { u32 c = s_cnt[w][tid]; s_cnt[w][tid] = tot; tot += c; }
+      gtot = tid <= dmask ? totals[tid] : 0u;
+    }
+    u32 t0, t1;
+    u32 dstart = block_exclusive_sum<SORT_THREADS>(tot, s_wave, &t0);
+    u32 gbase = block_exclusive_sum<SORT_THREADS>(gtot, s_wave, &t1);
+    if (tid < SORT_RADIX) {
+      s_dstart[tid] = dstart;
+      u32 toff = tid <= dmask ? table[(u64)tid * n_tiles + tile] : 0u;
+      s_gbase[tid] = gbase + toff - dstart;
+    }
+  }
+  __syncthreads();
+
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; ++it) {
+    const u32 d = dig[it];
+    const u32 pos = s_dstart[d] + s_cnt[wave][d] + pre[it];
+    s_key[pos] = k[it];
+    s_idx[pos] = v[it];
+  }
+  __syncthreads();
+
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; ++it) {
+    const u32 pos = it * SORT_THREADS + tid;
+    if (pos < valid) {
+      const u64 kk = s_key[pos];
+      const u32 g = s_gbase[(u32)(kk >> shift) & dmask] + pos;
+      key_out[g] = kk;
+      idx_out[g] = s_idx[pos];
+    }
+  }
+}
+
+static_assert(SORT_RADIX <= SORT_THREADS, "one thread per digit in the scatter prologue");
+
+int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const SortBuffers& buf, int bits) {
+  if (n == 0) return 0;
+  const u32 n_tiles = sort_tiles(n);
+  int passes = bits <= 0 ? 1 : (bits + SORT_RBITS - 1) / SORT_RBITS;
+  int done_bits = 0, cur = -1;
+  for (int p = 0; p < passes; ++p) {
+    // spread the bits evenly over the passes
+    int left = bits - done_bits, nb = bits <= 0 ? 1 : (left + (passes - p) - 1) / (passes - p);
+    if (nb < 1) nb = 1;
+    const u32 dmask = (1u << nb) - 1u;
+    const int out = cur < 0 ? 0 : 1 - cur;
+    if (p == 0) {
+      hipLaunchKernelGGL(k_radix_hist<true>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
+                         (const u64*)nullptr, buf.table, n, n_tiles, done_bits, dmask);
+    } else {
+      hipLaunchKernelGGL(k_radix_hist<false>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
+                         (const u64*)buf.key[cur], buf.table, n, n_tiles, done_bits, dmask);
+    }
+    hipLaunchKernelGGL(k_radix_scan, dim3(dmask + 1), dim3(SORT_THREADS), 0, stream, buf.table, buf.totals, n_tiles);
+    if (p == 0) {
+      hipLaunchKernelGGL(k_radix_scatter<true>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
+                         (const u64*)nullptr, (const u32*)nullptr, buf.key[out], buf.idx[out],
+                         (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, done_bits, nb);
+    } else {
+      hipLaunchKernelGGL(k_radix_scatter<false>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
+                         (const u64*)buf.key[cur], (const u32*)buf.idx[cur], buf.key[out], buf.idx[out],
+                         (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, done_bits, nb);
+    }
+    if (hipGetLastError() != hipSuccess) return -1;
+    done_bits += nb;
+    cur = out;
+  }
+  return cur;
+}
+
+}  // namespace ccld

@@ -1,0 +1,942 @@
+// Window analysis kernels for gfx950: ingest, per-collective statistics with exact integer
+// lower median / MAD by rank-counting in LDS, late-rank flags and their compaction, per-rank
+// blame, the slow-detection rules (Eq. 1-4) per detection group, and hang alerts.
+#include "window_kernels.h"
+#include "device_utils.h"
+
+namespace ccld {
+
+constexpr i64 T_INFLIGHT = INT64_MAX;
+
+__device__ __forceinline__ void atomic_or_u64(u64* p, u64 v) { atomicOr((unsigned long long*)p, (unsigned long long)v); }
+__device__ __forceinline__ u64 atomic_add_u64(u64* p, u64 v) {
+  return atomicAdd((unsigned long long*)p, (unsigned long long)v);
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_fill_u64(u64* p, u64 n, u64 v) {
+  for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < n; i += (u64)gridDim.x * 256) p[i] = v;
+}
+void launch_fill_u64(hipStream_t st, uint64_t* p, uint64_t n, uint64_t v) {
+  if (n == 0) return;
+  u32 g = (u32)((n + 255) / 256); if (g > 4096) g = 4096;
+  hipLaunchKernelGGL(k_fill_u64, dim3(g), dim3(256), 0, st, p, n, v);
+}
+
+// ------------------------------------------------------------------------------------------
+// Ingest: validate each record, key it by Trace ID (communicator id, operation counter) plus
+// rank, store key and payload row at the window's tail.
+__global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, KeyFormat kf) {
+  __shared__ u64 s_status[4], s_max[4];
+  u64 status = 0, maxseq = 0;
+  for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < a.n; i += (u64)gridDim.x * 256) {
+    const u32 r = a.rank[i], c = a.comm[i];
+    const u64 s = a.seq[i];
+    const u32 op = a.op[i];
+    const i64 te = a.t_enter[i], tx = a.t_exit[i];
+    u64 key = 0;
+    if (c >= T.n_comms) {
+      status |= DS_UNKNOWN_COMM;
+    } else {
+      bool member = false;
+      if (r < T.n_ranks)
+        for (u32 q = T.rank_comm_off[r]; q < T.rank_comm_off[r + 1]; ++q) member |= (T.rank_comms[q] == c);
+      if (!member) status |= DS_NOT_MEMBER;
+      if (op >= CCLD_OP_MAX || te < 0 || te == T_INFLIGHT || tx < te) status |= DS_RANGE;
+      if (kf.sb < 64 && (s >> kf.sb) != 0) {
+        status |= DS_KEY_WIDTH;
+      } else {
+        key = (kf.cb ? ((u64)c << (64 - kf.cb)) : 0ull) | (s << kf.rb) | (u64)r;
+        maxseq = s > maxseq ? s : maxseq;
+      }
+    }
+    u64 p = (u64)a.tail + i;
+    if (p >= a.cap) p -= a.cap;
+    a.win_key[p] = key;
+    Row rw;
+    rw.t_enter = te; rw.t_exit = tx; rw.bytes = a.bytes[i]; rw.op = op; rw.pad = 0;
+    a.win_row[p] = rw;
+  }
+  // one pair of atomics per workgroup
+  u64 st = status;
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) st |= shfl_xor_u64(st, m);
+  u64 mx = wave_max_u64(maxseq);
+  const u32 lane = lane_id(), wave = threadIdx.x / CCLD_WAVE;
+  if (lane == 0) { s_status[wave] = st; s_max[wave] = mx; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    u64 S = 0, M = 0;
+    for (int w = 0; w < 4; ++w) { S |= s_status[w]; M = s_max[w] > M ? s_max[w] : M; }
+    if (S) atomic_or_u64(&a.meta->status, S);
+    if (M) atomicMax((unsigned long long*)&a.meta->max_seq, (unsigned long long)M);
+  }
+}
+void launch_ingest(hipStream_t st, const IngestArgs& a, const DeviceTopology& T, const KeyFormat& kf) {
+  if (a.n == 0) return;
+  u64 g = (a.n + 255) / 256;
+  if (g > 2048) g = 2048;
+  hipLaunchKernelGGL(k_ingest, dim3((u32)g), dim3(256), 0, st, a, T, kf);
+}
+
+// ------------------------------------------------------------------------------------------
+// Collective (segment) heads per tile of the sorted keys; equal neighbours are duplicates.
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_count(SegArgs a) {
+  __shared__ u32 s_wave[SEG_THREADS / CCLD_WAVE];
+  const u32 base = blockIdx.x * SEG_TILE;
+  u32 cnt = 0;
+  bool dup = false;
+#pragma unroll
+  for (int r = 0; r < SEG_TILE / SEG_THREADS; ++r) {
+    const u32 j = base + r * SEG_THREADS + threadIdx.x;
+    if (j < a.n) {
+      const u64 k = a.key[j];
+      if (j == 0) cnt += 1;
+      else {
+        const u64 kp = a.key[j - 1];
+        cnt += ((k >> a.sf.rb) != (kp >> a.sf.rb));
+        dup |= (k == kp);
+      }
+    }
+  }
+  u32 tot;
+  block_exclusive_sum<SEG_THREADS>(cnt, s_wave, &tot);
+  if (threadIdx.x == 0) a.tile_heads[blockIdx.x] = tot;
+  if (dup) atomic_or_u64(&a.counters[CNT_STATUS], DS_DUPLICATE);
+}
+void launch_seg_count(hipStream_t st, const SegArgs& a) {
+  if (a.n == 0) return;
+  hipLaunchKernelGGL(k_seg_count, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
+}
+
+// In-place exclusive scan of per-tile counts by one workgroup; counts[n_tiles] and *total_out
+// receive the total.
+__global__ __launch_bounds__(1024) void k_scan_tiles(u32* counts, u32 n_tiles, u64* total_out) {
+  __shared__ u32 s_wave[1024 / CCLD_WAVE];
+  u32 carry = 0;
+  for (u32 b = 0; b < n_tiles; b += 1024) {
+    const u32 i = b + threadIdx.x;
+    const u32 v = i < n_tiles ? counts[i] : 0u;
+    u32 tot;
+    const u32 ex = block_exclusive_sum<1024>(v, s_wave, &tot);
+    if (i < n_tiles) counts[i] = carry + ex;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) { counts[n_tiles] = carry; *total_out = carry; }
+}
+void launch_scan_tiles(hipStream_t st, uint32_t* counts, uint32_t n_tiles, uint64_t* total_out) {
+  hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(1024), 0, st, counts, n_tiles, total_out);
+}
+
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void seg_put(const SegArgs& a, int col, u32 srow, i64 v) {
+  if (srow < a.seg_cap) a.seg[(u64)col * a.seg_cap + srow] = v;
+}
+__device__ __forceinline__ i64 absdiff(i64 a, i64 b) { return a >= b ? a - b : b - a; }
+__device__ __forceinline__ bool is_late(i64 lag, i64 floor_ns, u32 knum, u32 kden, i64 mad) {
+  return lag > floor_ns && (i128)lag * (i128)kden > (i128)knum * (i128)mad;
+}
+__device__ __forceinline__ void seg_put_empty_stats(const SegArgs& a, u32 srow) {
+  for (int c = CCLD_SEG_ENTER_MIN; c <= CCLD_SEG_DUR_MAX; ++c) seg_put(a, c, srow, 0);
+  seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, CCLD_NO_RANK);
+  seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, CCLD_NO_RANK);
+}
+
+// Per-collective statistics for every collective whose first record lies in this workgroup's
+// tile of the sorted window.  The tile plus a halo is staged in LDS; each record's rank among
+// its collective's completed records is found by counting, which yields the exact lower
+// median (order statistic floor((n-1)/2)), the extremes, and then the MAD the same way.
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_analyze(SegArgs a) {
+  constexpr int L = SEG_TILE + SEG_HALO, PER = L / SEG_THREADS, OWN = SEG_TILE / SEG_THREADS;
+  constexpr int MAXSEG = 256;
+  constexpr int NW = SEG_THREADS / CCLD_WAVE;
+  __shared__ i64 s_e[L], s_x[L];
+  __shared__ unsigned short s_sl[L];               // collective number inside the tile, 0xFFFF = not ours
+  __shared__ unsigned short s_head[SEG_TILE + 2];  // first position of each collective, then the end
+  __shared__ i64 s_med_e[MAXSEG], s_med_x[MAXSEG], s_mad_e[MAXSEG], s_mad_x[MAXSEG];
+  __shared__ u32 s_incons[MAXSEG];
+  __shared__ u64 s_bnd_bytes[PER][NW];
+  __shared__ u32 s_bnd_op[PER][NW];
+  __shared__ u32 s_wave[NW];
+  __shared__ u32 s_halo_head;
+
+  const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE;
+  const u32 tile = blockIdx.x, base = tile * SEG_TILE;
+  const u32 Lv = (a.n - base) < (u32)L ? (a.n - base) : (u32)L;
+  const bool more = (u64)base + L < a.n;
+  const int rb = a.sf.rb;
+  const u64 rmask = ((u64)1 << rb) - 1;
+  const u64 smask = ((u64)1 << a.sf.ws) - 1;
+
+  if (tid == 0) s_halo_head = Lv;
+
+  u64 kreg[PER], nb[PER];
+  i64 e[PER], x[PER];
+  u32 op[PER];
+  bool head[PER];
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    const u32 pos = r * SEG_THREADS + tid;
+    head[r] = false; kreg[r] = 0; nb[r] = 0; op[r] = 0; e[r] = 0; x[r] = 0;
+    if (pos < Lv) {
+      const u32 j = base + pos;
+      const u64 k = a.key[j];
+      const Row rw = a.row[a.idx[j]];
+      kreg[r] = k; e[r] = rw.t_enter; x[r] = rw.t_exit; nb[r] = rw.bytes; op[r] = rw.op;
+      head[r] = (j == 0) || ((a.key[j - 1] >> rb) != (k >> rb));
+      s_e[pos] = e[r]; s_x[pos] = x[r];
+    }
+  }
+  __syncthreads();
+
+  // number the collectives that start in the tile proper, in position order
+  u32 carry = 0, incl[PER];
+#pragma unroll
+  for (int r = 0; r < OWN; ++r) {
+    const u32 pos = r * SEG_THREADS + tid;
+    const u32 h = head[r] ? 1u : 0u;
+    u32 tot;
+    const u32 ex = block_exclusive_sum<SEG_THREADS>(h, s_wave, &tot);
+    if (h) s_head[carry + ex] = (unsigned short)pos;
+    incl[r] = carry + ex + h;
+    carry += tot;
+  }
+  const u32 nheads = carry;
+#pragma unroll
+  for (int r = OWN; r < PER; ++r) {
+    const u32 pos = r * SEG_THREADS + tid;
+    if (head[r]) atomicMin(&s_halo_head, pos);
+  }
+  // previous record's operation type, for the consistency test
+  u64 pbytes[PER];
+  u32 pop[PER];
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    pbytes[r] = shfl_up_u64(nb[r], 1);
+    pop[r] = __shfl_up(op[r], 1, CCLD_WAVE);
+    if (lane == CCLD_WAVE - 1) { s_bnd_bytes[r][wave] = nb[r]; s_bnd_op[r][wave] = op[r]; }
+  }
+  __syncthreads();
+  const u32 end_last = s_halo_head;     // first collective head in the halo, or the end of what was loaded
+  const bool last_big = nheads > 0 && end_last == Lv && more;   // the last collective runs past the halo
+  const u32 n_own = last_big ? nheads - 1 : nheads;
+  if (tid == 0) s_head[nheads] = (unsigned short)end_last;
+  bool mism[PER];
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    const u32 pos = r * SEG_THREADS + tid;
+    if (lane == 0) {
+      if (wave > 0) { pbytes[r] = s_bnd_bytes[r][wave - 1]; pop[r] = s_bnd_op[r][wave - 1]; }
+      else if (r > 0) { pbytes[r] = s_bnd_bytes[r - 1][NW - 1]; pop[r] = s_bnd_op[r - 1][NW - 1]; }
+    }
+    mism[r] = pos < Lv && pos > 0 && !head[r] && (nb[r] != pbytes[r] || op[r] != pop[r]);
+    if (pos < Lv) {
+      u32 sl;
+      if (r < OWN) sl = incl[r] == 0 ? 0xFFFFu : incl[r] - 1;
+      else sl = (nheads > 0 && pos < end_last) ? nheads - 1 : 0xFFFFu;
+      s_sl[pos] = (unsigned short)sl;
+    }
+  }
+  __syncthreads();
+  const u32 seg0 = a.tile_heads[tile];
+  if (last_big && tid == 0) {
+    const u64 slot = atomic_add_u64(&a.counters[CNT_NBIG], 1);
+    a.big_list[2 * slot] = seg0 + nheads - 1;
+    a.big_list[2 * slot + 1] = base + s_head[nheads - 1];
+  }
+
+  for (u32 sbase = 0; sbase < n_own; sbase += MAXSEG) {
+    s_incons[tid] = 0;
+    __syncthreads();
+    u32 ndone[PER], ninfl[PER];
+    // ---- ranks of arrival, completion and duration; minimum, median, maximum -------------
+#pragma unroll
+    for (int r = 0; r < PER; ++r) {
+      const u32 pos = r * SEG_THREADS + tid;
+      ndone[r] = 0; ninfl[r] = 0;
+      const u32 sl = pos < Lv ? s_sl[pos] : 0xFFFFu;
+      if (sl == 0xFFFFu || sl < sbase || sl >= sbase + MAXSEG || sl >= n_own) continue;
+      const u32 slot = sl - sbase, srow = seg0 + sl;
+      if (mism[r]) atomicOr(&s_incons[slot], 1u);
+      const u32 a0 = s_head[sl], b0 = s_head[sl + 1];
+      const i64 ei = e[r], xi = x[r], di = xi - ei;
+      u32 re = 0, rx = 0, cmin = 0, cmax = 0, nd = 0, ni = 0;
+      i64 imin = T_INFLIGHT;
+      for (u32 j = a0; j < b0; ++j) {
+        const i64 ej = s_e[j], xj = s_x[j];
+        if (xj != T_INFLIGHT) {
+          const i64 dj = xj - ej;
+          const bool before = j < pos;
+          ++nd;
+          re += (ej < ei) || (ej == ei && before);
+          rx += (xj < xi) || (xj == xi && before);
+          cmin += (dj < di) || (dj == di && before);
+          cmax += (dj > di) || (dj == di && before);
+        } else {
+          ++ni;
+          imin = ej < imin ? ej : imin;
+        }
+      }
+      ndone[r] = nd; ninfl[r] = ni;
+      if (xi != T_INFLIGHT) {
+        const u32 km = (nd - 1) / 2;
+        if (re == km) { s_med_e[slot] = ei; seg_put(a, CCLD_SEG_ENTER_MED, srow, ei); }
+        if (re == 0) seg_put(a, CCLD_SEG_ENTER_MIN, srow, ei);
+        if (re == nd - 1) seg_put(a, CCLD_SEG_ENTER_MAX, srow, ei);
+        if (rx == km) { s_med_x[slot] = xi; seg_put(a, CCLD_SEG_EXIT_MED, srow, xi); }
+        if (rx == 0) seg_put(a, CCLD_SEG_EXIT_MIN, srow, xi);
+        if (rx == nd - 1) seg_put(a, CCLD_SEG_EXIT_MAX, srow, xi);
+        if (cmin == 0) { seg_put(a, CCLD_SEG_DUR_MIN, srow, di); seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)(kreg[r] & rmask)); }
+        if (cmax == 0) { seg_put(a, CCLD_SEG_DUR_MAX, srow, di); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)(kreg[r] & rmask)); }
+      }
+      if (pos == a0) {
+        seg_put(a, CCLD_SEG_COMM, srow, (i64)(kreg[r] >> (rb + a.sf.ws)));
+        seg_put(a, CCLD_SEG_SEQ, srow, (i64)((kreg[r] >> rb) & smask));
+        seg_put(a, CCLD_SEG_N, srow, (i64)(b0 - a0));
+        seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ni);
+        seg_put(a, CCLD_SEG_OP, srow, (i64)op[r]);
+        seg_put(a, CCLD_SEG_BYTES, srow, (i64)nb[r]);
+        seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
+        seg_put(a, CCLD_SEG_FIRST, srow, (i64)(base + pos));
+        if (nd == 0) seg_put_empty_stats(a, srow);
+      }
+    }
+    __syncthreads();
+    // ---- median absolute deviations ------------------------------------------------------
+#pragma unroll
+    for (int r = 0; r < PER; ++r) {
+      const u32 pos = r * SEG_THREADS + tid;
+      const u32 sl = pos < Lv ? s_sl[pos] : 0xFFFFu;
+      if (sl == 0xFFFFu || sl < sbase || sl >= sbase + MAXSEG || sl >= n_own) continue;
+      if (x[r] == T_INFLIGHT) continue;
+      const u32 slot = sl - sbase, srow = seg0 + sl;
+      const u32 a0 = s_head[sl], b0 = s_head[sl + 1];
+      const i64 me = s_med_e[slot], mx = s_med_x[slot];
+      const i64 dei = absdiff(e[r], me), dxi = absdiff(x[r], mx);
+      u32 rde = 0, rdx = 0;
+      for (u32 j = a0; j < b0; ++j) {
+        const i64 xj = s_x[j];
+        if (xj == T_INFLIGHT) continue;
+        const i64 dej = absdiff(s_e[j], me), dxj = absdiff(xj, mx);
+        const bool before = j < pos;
+        rde += (dej < dei) || (dej == dei && before);
+        rdx += (dxj < dxi) || (dxj == dxi && before);
+      }
+      const u32 km = (ndone[r] - 1) / 2;
+      if (rde == km) { s_mad_e[slot] = dei; seg_put(a, CCLD_SEG_ENTER_MAD, srow, dei); }
+      if (rdx == km) { s_mad_x[slot] = dxi; seg_put(a, CCLD_SEG_EXIT_MAD, srow, dxi); }
+    }
+    __syncthreads();
+    // ---- state of the collective, per-rank lag, late flags ----------------------------------
+#pragma unroll
+    for (int r = 0; r < PER; ++r) {
+      const u32 pos = r * SEG_THREADS + tid;
+      const u32 sl = pos < Lv ? s_sl[pos] : 0xFFFFu;
+      if (sl == 0xFFFFu || sl < sbase || sl >= sbase + MAXSEG || sl >= n_own) continue;
+      const u32 slot = sl - sbase, srow = seg0 + sl;
+      const u32 a0 = s_head[sl], b0 = s_head[sl + 1];
+      const u32 comm = (u32)(kreg[r] >> (rb + a.sf.ws));
+      const bool complete = (b0 - a0) == a.comm_size[comm] && ninfl[r] == 0;
+      const bool consistent = s_incons[slot] == 0;
+      const bool barrier = op[r] == CCLD_OP_ALLREDUCE && nb[r] < (u64)a.barrier_bytes;
+      const bool usable = complete && consistent && !barrier;
+      if (pos == a0)
+        seg_put(a, CCLD_SEG_STATE, srow,
+                (complete ? CCLD_SEG_COMPLETE : 0) | (consistent ? CCLD_SEG_CONSISTENT : 0) |
+                    (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+      i64 le = 0, lx = 0;
+      u32 f = 0;
+      if (usable) {
+        le = e[r] - s_med_e[slot];
+        lx = x[r] - s_med_x[slot];
+        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, s_mad_e[slot])) f |= CCLD_FLAG_LATE_ENTER;
+        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, s_mad_x[slot])) f |= CCLD_FLAG_LATE_EXIT;
+      }
+      const u32 j = base + pos;
+      a.rec_flag[j] = (uint8_t)f;
+      if (a.lag_e) a.lag_e[j] = le;
+      if (a.lag_x) a.lag_x[j] = lx;
+      if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
+    }
+    __syncthreads();
+  }
+}
+
+// Collectives too long for a tile plus halo: one workgroup per collective, values staged in
+// global scratch, the same counting selection with all reads broadcast across the workgroup.
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
+  __shared__ u32 s_end, s_ninfl, s_incons;
+  __shared__ unsigned long long s_imin;
+  __shared__ i64 s_stat[4];      // med_e, med_x, mad_e, mad_x
+  const u32 tid = threadIdx.x;
+  const int rb = a.sf.rb;
+  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  i64* big_e = a.big_ex;
+  i64* big_x = a.big_ex + a.cap_n;
+  const u32 nbig = (u32)a.counters[CNT_NBIG];
+  for (u32 ent = blockIdx.x; ent < nbig; ent += gridDim.x) {
+    const u32 srow = a.big_list[2 * ent], a0 = a.big_list[2 * ent + 1];
+    const u64 k0 = a.key[a0];
+    const u64 pref = k0 >> rb;
+    if (tid == 0) { s_end = a.n; s_ninfl = 0; s_incons = 0; s_imin = (unsigned long long)T_INFLIGHT; }
+    __syncthreads();
+    for (u64 j0 = (u64)a0 + 1;; j0 += SEG_THREADS) {
+      const u64 j = j0 + tid;
+      if (j < a.n && (a.key[j] >> rb) != pref) atomicMin(&s_end, (u32)j);
+      __syncthreads();
+      const bool stop = s_end != a.n || j0 + SEG_THREADS >= a.n;
+      __syncthreads();
+      if (stop) break;
+    }
+    const u32 b0 = s_end, nn = b0 - a0;
+    const Row h = a.row[a.idx[a0]];
+    {
+      u32 ni = 0; bool inc = false; i64 imin = T_INFLIGHT;
+      for (u32 j = a0 + tid; j < b0; j += SEG_THREADS) {
+        const Row rw = a.row[a.idx[j]];
+        big_e[j] = rw.t_enter; big_x[j] = rw.t_exit;
+        if (rw.t_exit == T_INFLIGHT) { ++ni; imin = rw.t_enter < imin ? rw.t_enter : imin; }
+        inc |= (rw.op != h.op || rw.bytes != h.bytes);
+      }
+      if (ni) { atomicAdd(&s_ninfl, ni); atomicMin(&s_imin, (unsigned long long)imin); }
+      if (inc) atomicOr(&s_incons, 1u);
+    }
+    __threadfence_block();
+    __syncthreads();
+    const u32 ninfl = s_ninfl, nd = nn - ninfl, km = nd ? (nd - 1) / 2 : 0;
+    if (tid == 0) {
+      seg_put(a, CCLD_SEG_COMM, srow, (i64)(k0 >> (rb + a.sf.ws)));
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> rb) & smask));
+      seg_put(a, CCLD_SEG_N, srow, (i64)nn);
+      seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
+      seg_put(a, CCLD_SEG_OP, srow, (i64)h.op);
+      seg_put(a, CCLD_SEG_BYTES, srow, (i64)h.bytes);
+      seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, (i64)s_imin);
+      seg_put(a, CCLD_SEG_FIRST, srow, (i64)a0);
+      if (nd == 0) seg_put_empty_stats(a, srow);
+    }
+    for (u32 i = a0 + tid; i < b0; i += SEG_THREADS) {
+      const i64 ei = big_e[i], xi = big_x[i];
+      if (xi == T_INFLIGHT) continue;
+      const i64 di = xi - ei;
+      u32 re = 0, rx = 0, cmin = 0, cmax = 0;
+      for (u32 j = a0; j < b0; ++j) {
+        const i64 ej = big_e[j], xj = big_x[j];
+        if (xj == T_INFLIGHT) continue;
+        const i64 dj = xj - ej;
+        const bool before = j < i;
+        re += (ej < ei) || (ej == ei && before);
+        rx += (xj < xi) || (xj == xi && before);
+        cmin += (dj < di) || (dj == di && before);
+        cmax += (dj > di) || (dj == di && before);
+      }
+      if (re == km) { s_stat[0] = ei; seg_put(a, CCLD_SEG_ENTER_MED, srow, ei); }
+      if (re == 0) seg_put(a, CCLD_SEG_ENTER_MIN, srow, ei);
+      if (re == nd - 1) seg_put(a, CCLD_SEG_ENTER_MAX, srow, ei);
+      if (rx == km) { s_stat[1] = xi; seg_put(a, CCLD_SEG_EXIT_MED, srow, xi); }
+      if (rx == 0) seg_put(a, CCLD_SEG_EXIT_MIN, srow, xi);
+      if (rx == nd - 1) seg_put(a, CCLD_SEG_EXIT_MAX, srow, xi);
+      const i64 rk = (i64)(a.key[i] & rmask);
+      if (cmin == 0) { seg_put(a, CCLD_SEG_DUR_MIN, srow, di); seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, rk); }
+      if (cmax == 0) { seg_put(a, CCLD_SEG_DUR_MAX, srow, di); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, rk); }
+    }
+    __syncthreads();
+    const i64 me = s_stat[0], mx = s_stat[1];
+    for (u32 i = a0 + tid; i < b0; i += SEG_THREADS) {
+      const i64 xi = big_x[i];
+      if (xi == T_INFLIGHT) continue;
+      const i64 dei = absdiff(big_e[i], me), dxi = absdiff(xi, mx);
+      u32 rde = 0, rdx = 0;
+      for (u32 j = a0; j < b0; ++j) {
+        const i64 xj = big_x[j];
+        if (xj == T_INFLIGHT) continue;
+        const i64 dej = absdiff(big_e[j], me), dxj = absdiff(xj, mx);
+        const bool before = j < i;
+        rde += (dej < dei) || (dej == dei && before);
+        rdx += (dxj < dxi) || (dxj == dxi && before);
+      }
+      if (rde == km) { s_stat[2] = dei; seg_put(a, CCLD_SEG_ENTER_MAD, srow, dei); }
+      if (rdx == km) { s_stat[3] = dxi; seg_put(a, CCLD_SEG_EXIT_MAD, srow, dxi); }
+    }
+    __syncthreads();
+    const u32 comm = (u32)(k0 >> (rb + a.sf.ws));
+    const bool complete = nn == a.comm_size[comm] && ninfl == 0;
+    const bool consistent = s_incons == 0;
+    const bool barrier = h.op == CCLD_OP_ALLREDUCE && h.bytes < (u64)a.barrier_bytes;
+    const bool usable = complete && consistent && !barrier;
+    if (tid == 0)
+      seg_put(a, CCLD_SEG_STATE, srow,
+              (complete ? CCLD_SEG_COMPLETE : 0) | (consistent ? CCLD_SEG_CONSISTENT : 0) |
+                  (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+    for (u32 i = a0 + tid; i < b0; i += SEG_THREADS) {
+      i64 le = 0, lx = 0;
+      u32 f = 0;
+      if (usable) {
+        le = big_e[i] - me; lx = big_x[i] - mx;
+        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, s_stat[2])) f |= CCLD_FLAG_LATE_ENTER;
+        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, s_stat[3])) f |= CCLD_FLAG_LATE_EXIT;
+      }
+      a.rec_flag[i] = (uint8_t)f;
+      if (a.lag_e) a.lag_e[i] = le;
+      if (a.lag_x) a.lag_x[i] = lx;
+      if (f) { a.flag_lag[i] = le; a.flag_lag[a.cap_n + i] = lx; }
+    }
+    __syncthreads();
+  }
+}
+
+void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
+  if (a.n == 0) return;
+  hipLaunchKernelGGL(k_seg_analyze, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
+  hipLaunchKernelGGL(k_seg_big, dim3(128), dim3(SEG_THREADS), 0, st, a);
+}
+
+// ------------------------------------------------------------------------------------------
+// Ordered compaction of the flagged records into the flag list.
+__global__ __launch_bounds__(256) void k_flag_count(FlagArgs a) {
+  __shared__ u32 s_wave[4];
+  const u32 base = blockIdx.x * SEL_TILE;
+  u32 c = 0;
+#pragma unroll
+  for (int r = 0; r < SEL_TILE / 256; ++r) {
+    const u32 j = base + r * 256 + threadIdx.x;
+    if (j < a.n) c += a.rec_flag[j] != 0;
+  }
+  u32 tot;
+  block_exclusive_sum<256>(c, s_wave, &tot);
+  if (threadIdx.x == 0) a.tile_flags[blockIdx.x] = tot;
+}
+__global__ __launch_bounds__(256) void k_flag_emit(FlagArgs a) {
+  __shared__ u32 s_wave[4];
+  const u32 base = blockIdx.x * SEL_TILE;
+  u32 carry = a.tile_flags[blockIdx.x];
+  const int rb = a.sf.rb;
+  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+#pragma unroll 1
+  for (int r = 0; r < SEL_TILE / 256; ++r) {
+    const u32 j = base + r * 256 + threadIdx.x;
+    const u32 f = j < a.n ? a.rec_flag[j] : 0u;
+    u32 tot;
+    const u32 ex = block_exclusive_sum<256>(f != 0, s_wave, &tot);
+    if (f) {
+      const u32 k = carry + ex;
+      a.flag_pos[k] = j;
+      if (a.flag && k < a.flag_cap) {
+        const u64 key = a.key[j];
+        a.flag[(u64)CCLD_FLG_COMM * a.flag_cap + k] = (i64)(key >> (rb + a.sf.ws));
+        a.flag[(u64)CCLD_FLG_SEQ * a.flag_cap + k] = (i64)((key >> rb) & smask);
+        a.flag[(u64)CCLD_FLG_RANK * a.flag_cap + k] = (i64)(key & rmask);
+        a.flag[(u64)CCLD_FLG_KIND * a.flag_cap + k] = (i64)f;
+        a.flag[(u64)CCLD_FLG_LAG_ENTER * a.flag_cap + k] = a.flag_lag[j];
+        a.flag[(u64)CCLD_FLG_LAG_EXIT * a.flag_cap + k] = a.flag_lag[a.cap_n + j];
+      }
+    }
+    carry += tot;
+  }
+}
+void launch_flag_compact(hipStream_t st, const FlagArgs& a) {
+  const u32 nt = (a.n + SEL_TILE - 1) / SEL_TILE;
+  if (a.n) hipLaunchKernelGGL(k_flag_count, dim3(nt), dim3(256), 0, st, a);
+  launch_scan_tiles(st, a.tile_flags, nt, &a.counters[CNT_NFLAG]);
+  if (a.n) hipLaunchKernelGGL(k_flag_emit, dim3(nt), dim3(256), 0, st, a);
+}
+
+// ------------------------------------------------------------------------------------------
+// Records per rank: privatised LDS histograms, per-workgroup partial tables, then a reduction.
+constexpr int RC_CHUNK = 8192;
+__global__ __launch_bounds__(256) void k_rank_count(const u64* __restrict__ key, u32 n, int rb, u32 n_ranks,
+                                                    u32* __restrict__ partial) {
+  __shared__ u32 s_h[RC_CHUNK];
+  const u64 rmask = ((u64)1 << rb) - 1;
+  const u64 per = ((u64)n + gridDim.x - 1) / gridDim.x;
+  const u64 lo = per * blockIdx.x, hi = (lo + per) < n ? (lo + per) : n;
+  for (u32 r0 = 0; r0 < n_ranks; r0 += RC_CHUNK) {
+    for (u32 i = threadIdx.x; i < RC_CHUNK; i += 256) s_h[i] = 0;
+    __syncthreads();
+    for (u64 j = lo + threadIdx.x; j < hi; j += 256) {
+      const u32 r = (u32)(key[j] & rmask);
+      if (r >= r0 && r < r0 + RC_CHUNK) atomicAdd(&s_h[r - r0], 1u);
+    }
+    __syncthreads();
+    for (u32 i = threadIdx.x; i < RC_CHUNK && r0 + i < n_ranks; i += 256)
+      partial[(u64)blockIdx.x * n_ranks + r0 + i] = s_h[i];
+    __syncthreads();
+  }
+}
+__global__ __launch_bounds__(256) void k_rank_reduce(const u32* __restrict__ partial, u32 n_blocks, u32 n_ranks,
+                                                     i64* __restrict__ blame) {
+  const u32 r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= n_ranks) return;
+  u64 s = 0;
+  for (u32 b = 0; b < n_blocks; ++b) s += partial[(u64)b * n_ranks + r];
+  blame[(u64)CCLD_BLM_N_RECORDS * n_ranks + r] = (i64)s;
+}
+void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, int rb, uint32_t n_ranks,
+                       uint32_t* partial, int64_t* blame) {
+  hipLaunchKernelGGL(k_rank_count, dim3(RANKCOUNT_BLOCKS), dim3(256), 0, st, key, n, rb, n_ranks, partial);
+  hipLaunchKernelGGL(k_rank_reduce, dim3((n_ranks + 255) / 256), dim3(256), 0, st, (const u32*)partial,
+                     (u32)RANKCOUNT_BLOCKS, n_ranks, blame);
+}
+
+// Blame: key every flag by its rank, sort, then one wavefront per rank sums its run.
+__global__ __launch_bounds__(256) void k_blame_keys(const u64* __restrict__ key, const u32* __restrict__ flag_pos,
+                                                    u32 n_flag, int rb, u64* __restrict__ out_key) {
+  const u32 k = blockIdx.x * 256 + threadIdx.x;
+  if (k < n_flag) out_key[k] = key[flag_pos[k]] & (((u64)1 << rb) - 1);
+}
+void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag_pos, uint32_t n_flag, int rb,
+                       uint64_t* out_key) {
+  if (n_flag) hipLaunchKernelGGL(k_blame_keys, dim3((n_flag + 255) / 256), dim3(256), 0, st, key, flag_pos, n_flag, rb, out_key);
+}
+__global__ __launch_bounds__(256) void k_blame_reduce(const u64* __restrict__ skey, const u32* __restrict__ sidx,
+                                                      u32 n_flag, const u32* __restrict__ flag_pos,
+                                                      const uint8_t* __restrict__ rec_flag,
+                                                      const i64* __restrict__ flag_lag, u64 cap_n, u32 n_ranks,
+                                                      i64* __restrict__ blame) {
+  const u32 r = blockIdx.x * 4 + threadIdx.x / CCLD_WAVE;
+  if (r >= n_ranks) return;
+  const u32 lane = lane_id();
+  // run of this rank in the sorted keys: [lower_bound(r), lower_bound(r + 1))
+  u32 lo = 0, hi = n_flag;
+  while (lo < hi) { const u32 m = (lo + hi) / 2; if (skey[m] < (u64)r) lo = m + 1; else hi = m; }
+  const u32 first = lo;
+  hi = n_flag;
+  while (lo < hi) { const u32 m = (lo + hi) / 2; if (skey[m] <= (u64)r) lo = m + 1; else hi = m; }
+  const u32 last = lo;
+  u64 ne = 0, nx = 0, se = 0, sx = 0;
+  for (u32 q = first + lane; q < last; q += CCLD_WAVE) {
+    const u32 j = flag_pos[sidx[q]];
+    const u32 f = rec_flag[j];
+    if (f & CCLD_FLAG_LATE_ENTER) { ne += 1; se += (u64)flag_lag[j]; }
+    if (f & CCLD_FLAG_LATE_EXIT) { nx += 1; sx += (u64)flag_lag[cap_n + j]; }
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    ne += shfl_xor_u64(ne, m); nx += shfl_xor_u64(nx, m); se += shfl_xor_u64(se, m); sx += shfl_xor_u64(sx, m);
+  }
+  if (lane == 0) {
+    blame[(u64)CCLD_BLM_N_LATE_ENTER * n_ranks + r] = (i64)ne;
+    blame[(u64)CCLD_BLM_N_LATE_EXIT * n_ranks + r] = (i64)nx;
+    blame[(u64)CCLD_BLM_SUM_LAG_ENTER * n_ranks + r] = (i64)se;
+    blame[(u64)CCLD_BLM_SUM_LAG_EXIT * n_ranks + r] = (i64)sx;
+  }
+}
+void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* sidx, uint32_t n_flag,
+                         const uint32_t* flag_pos, const uint8_t* rec_flag, const int64_t* flag_lag,
+                         uint64_t cap_n, uint32_t n_ranks, int64_t* blame) {
+  hipLaunchKernelGGL(k_blame_reduce, dim3((n_ranks + 3) / 4), dim3(256), 0, st, skey, sidx, n_flag, flag_pos,
+                     rec_flag, flag_lag, cap_n, n_ranks, blame);
+}
+
+// order[] = ranks by (flags descending, summed lag descending, rank ascending): each rank counts
+// the ranks that precede it, the table staged through LDS in tiles.
+__global__ __launch_bounds__(256) void k_blame_order(const i64* __restrict__ blame, u32 n_ranks,
+                                                     u32* __restrict__ order) {
+  __shared__ i64 s_n[256], s_s[256];
+  const u32 r = blockIdx.x * 256 + threadIdx.x;
+  const bool live = r < n_ranks;
+  i64 myn = 0, mys = 0;
+  if (live) {
+    myn = blame[(u64)CCLD_BLM_N_LATE_ENTER * n_ranks + r] + blame[(u64)CCLD_BLM_N_LATE_EXIT * n_ranks + r];
+    mys = (i64)((u64)blame[(u64)CCLD_BLM_SUM_LAG_ENTER * n_ranks + r] + (u64)blame[(u64)CCLD_BLM_SUM_LAG_EXIT * n_ranks + r]);
+  }
+  u32 before = 0;
+  for (u32 t0 = 0; t0 < n_ranks; t0 += 256) {
+    const u32 q = t0 + threadIdx.x;
+    __syncthreads();
+    if (q < n_ranks) {
+      s_n[threadIdx.x] = blame[(u64)CCLD_BLM_N_LATE_ENTER * n_ranks + q] + blame[(u64)CCLD_BLM_N_LATE_EXIT * n_ranks + q];
+      s_s[threadIdx.x] = (i64)((u64)blame[(u64)CCLD_BLM_SUM_LAG_ENTER * n_ranks + q] + (u64)blame[(u64)CCLD_BLM_SUM_LAG_EXIT * n_ranks + q]);
+    }
+    __syncthreads();
+    const u32 lim = (n_ranks - t0) < 256u ? (n_ranks - t0) : 256u;
+    for (u32 i = 0; i < lim; ++i) {
+      const i64 on = s_n[i], os = s_s[i];
+      const u32 o = t0 + i;
+      before += (on > myn) || (on == myn && (os > mys || (os == mys && o < r)));
+    }
+  }
+  if (live) order[before] = r;
+}
+void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, uint32_t* order) {
+  hipLaunchKernelGGL(k_blame_order, dim3((n_ranks + 255) / 256), dim3(256), 0, st, blame, n_ranks, order);
+}
+
+// ------------------------------------------------------------------------------------------
+// generic ordered selection of indices i in [0, n) with pred(i)
+template <class Pred>
+__global__ __launch_bounds__(256) void k_select_count(Pred pred, u32 n, u32* tile_counts) {
+  __shared__ u32 s_wave[4];
+  const u32 base = blockIdx.x * SEL_TILE;
+  u32 c = 0;
+#pragma unroll 1
+  for (int r = 0; r < SEL_TILE / 256; ++r) {
+    const u32 i = base + r * 256 + threadIdx.x;
+    if (i < n) c += pred(i) ? 1u : 0u;
+  }
+  u32 tot;
+  block_exclusive_sum<256>(c, s_wave, &tot);
+  if (threadIdx.x == 0) tile_counts[blockIdx.x] = tot;
+}
+template <class Pred>
+__global__ __launch_bounds__(256) void k_select_emit(Pred pred, u32 n, const u32* tile_counts, u32* out) {
+  __shared__ u32 s_wave[4];
+  const u32 base = blockIdx.x * SEL_TILE;
+  u32 carry = tile_counts[blockIdx.x];
+#pragma unroll 1
+  for (int r = 0; r < SEL_TILE / 256; ++r) {
+    const u32 i = base + r * 256 + threadIdx.x;
+    const bool p = i < n && pred(i);
+    u32 tot;
+    const u32 ex = block_exclusive_sum<256>(p ? 1u : 0u, s_wave, &tot);
+    if (p) out[carry + ex] = i;
+    carry += tot;
+  }
+}
+template <class Pred>
+static void run_select(hipStream_t st, Pred pred, u32 n, u32* tile_counts, u32* out, u64* total_out) {
+  const u32 nt = (n + SEL_TILE - 1) / SEL_TILE;
+  if (n) hipLaunchKernelGGL(k_select_count<Pred>, dim3(nt), dim3(256), 0, st, pred, n, tile_counts);
+  launch_scan_tiles(st, tile_counts, nt, total_out);
+  if (n) hipLaunchKernelGGL(k_select_emit<Pred>, dim3(nt), dim3(256), 0, st, pred, n, (const u32*)tile_counts, out);
+}
+
+struct PredUsable {
+  const i64* state;
+  __device__ bool operator()(u32 s) const { return (state[s] & CCLD_SEG_USABLE) != 0; }
+};
+void launch_usable_select(hipStream_t st, const GroupArgs& a) {
+  PredUsable p{a.seg + (u64)CCLD_SEG_STATE * a.seg_cap};
+  run_select(st, p, a.n_seg, a.tile_counts, a.usable_list, &a.counters[CNT_NUSABLE]);
+}
+
+// detection-group key of a usable collective: (communicator, op, floor(log2 bytes)) then the
+// operation counter, so that a stable sort lists every group's rounds in ascending order
+__global__ __launch_bounds__(256) void k_group_keys(GroupArgs a, u32 n_usable) {
+  const u32 q = blockIdx.x * 256 + threadIdx.x;
+  if (q >= n_usable) return;
+  const u32 s = a.usable_list[q];
+  const u64 comm = (u64)a.seg[(u64)CCLD_SEG_COMM * a.seg_cap + s];
+  const u64 op = (u64)a.seg[(u64)CCLD_SEG_OP * a.seg_cap + s];
+  const u64 nb = (u64)a.seg[(u64)CCLD_SEG_BYTES * a.seg_cap + s];
+  const u64 seq = (u64)a.seg[(u64)CCLD_SEG_SEQ * a.seg_cap + s];
+  const u64 cls = 63 - __clzll((long long)(nb | 1));
+  a.gkey[q] = (((comm * CCLD_OP_MAX + op) * GROUP_CLS + cls) << a.ws) | seq;
+}
+void launch_group_keys(hipStream_t st, const GroupArgs& a, uint32_t n_usable) {
+  if (n_usable) hipLaunchKernelGGL(k_group_keys, dim3((n_usable + 255) / 256), dim3(256), 0, st, a, n_usable);
+}
+
+struct PredGroupHead {
+  const u64* skey; int ws;
+  __device__ bool operator()(u32 i) const { return i == 0 || (skey[i] >> ws) != (skey[i - 1] >> ws); }
+};
+void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_usable, int ws, uint32_t* tile_counts,
+                        uint32_t* group_first, uint64_t* counters) {
+  PredGroupHead p{skey, ws};
+  run_select(st, p, n_usable, tile_counts, group_first, &counters[CNT_NGROUP]);
+}
+
+// One workgroup per detection group.  Eq. 1: baseline = mean of T_max over the first m rounds
+// (m = min(tbase_rounds, rounds within the warm-up span)); Eq. 2: the window's round of largest
+// T_max - T_min; Eq. 3: slow iff (T_max - T_base)/T_base > theta; Eq. 4: P = (T_max - T_min)/
+// (T_max - T_base) against alpha / beta; repetition counter.  All ratios cross-multiplied.
+__global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __restrict__ skey,
+                                                    const u32* __restrict__ sidx, u32 n_usable,
+                                                    const u32* __restrict__ group_first, u32 n_group) {
+  __shared__ u32 s_i0, s_istar, s_kstar;
+  __shared__ unsigned long long s_sum, s_best;
+  const u32 g = blockIdx.x, tid = threadIdx.x;
+  const u32 f = group_first[g], e = (g + 1 < n_group) ? group_first[g + 1] : n_usable;
+  const u64 smask = ((u64)1 << a.ws) - 1;
+  const u64 gid = skey[f] >> a.ws;                       // (comm*OP_MAX + op)*CLS + cls
+  GroupState* G = a.gstate + gid;
+  const i64* EMIN = a.seg + (u64)CCLD_SEG_ENTER_MIN * a.seg_cap;
+  const i64* DMAX = a.seg + (u64)CCLD_SEG_DUR_MAX * a.seg_cap;
+  const i64* DMIN = a.seg + (u64)CCLD_SEG_DUR_MIN * a.seg_cap;
+  const GroupState g0 = *G;
+  if (tid == 0) { s_i0 = e; s_istar = e; s_kstar = e; s_sum = 0; s_best = 0; }
+  __syncthreads();
+  // rounds not yet visited by Eq. 1 form a suffix (ascending operation counters)
+  for (u32 i = f + tid; i < e; i += 256)
+    if ((skey[i] & smask) + 1 > g0.baselined_wm) atomicMin(&s_i0, i);
+  // Eq. 2 needs the largest range
+  for (u32 i = f + tid; i < e; i += 256) {
+    const u32 s = a.usable_list[sidx[i]];
+    atomicMax(&s_best, (unsigned long long)(DMAX[s] - DMIN[s]));
+  }
+  __syncthreads();
+  const u32 i0 = s_i0;
+  const i64 t0 = (g0.cnt == 0 && i0 < e) ? EMIN[a.usable_list[sidx[i0]]] : g0.t0;
+  if (!g0.frozen) {
+    for (u32 i = i0 + tid; i < e; i += 256) {
+      const u32 s = a.usable_list[sidx[i]];
+      const u64 q = i - i0;
+      if ((u64)g0.cnt + q >= (u64)a.p.tbase_rounds || EMIN[s] - t0 > a.p.tbase_warmup_ns) atomicMin(&s_istar, i);
+    }
+  }
+  const unsigned long long best = s_best;
+  for (u32 i = f + tid; i < e; i += 256) {
+    const u32 s = a.usable_list[sidx[i]];
+    if ((unsigned long long)(DMAX[s] - DMIN[s]) == best) atomicMin(&s_kstar, i);
+  }
+  __syncthreads();
+  const u32 istar = s_istar;
+  if (!g0.frozen) {
+    unsigned long long part = 0;
+    for (u32 i = i0 + tid; i < istar; i += 256) part += (unsigned long long)DMAX[a.usable_list[sidx[i]]];
+    if (part) atomicAdd(&s_sum, part);
+  }
+  __syncthreads();
+  if (tid != 0) return;
+  GroupState n = g0;
+  if (!g0.frozen && i0 < e) {
+    n.t0 = t0;
+    n.sum = (i64)((u64)g0.sum + (u64)s_sum);
+    n.cnt = g0.cnt + (istar - i0);
+    if (istar > i0) n.baseline_last_seq = skey[istar - 1] & smask;
+    if (istar < e) { n.frozen = 1; n.tbase_dyn = n.sum / (i64)n.cnt; }
+  }
+  if (i0 < e) n.baselined_wm = (skey[e - 1] & smask) + 1;
+  const u32 ks = s_kstar;
+  const u32 sx = a.usable_list[sidx[ks]];
+  const u64 rseq = skey[ks] & smask;
+  const i64 tmax = DMAX[sx], tmin = DMIN[sx];
+  const bool dynamic = n.frozen && rseq > n.baseline_last_seq;
+  const i64 tbase = dynamic ? n.tbase_dyn : a.p.tbase_init_ns;
+  const bool slow = (i128)(tmax - tbase) * (i128)a.p.theta_den > (i128)a.p.theta_num * (i128)tbase;
+  int cls = CCLD_SLOW_NONE;
+  i64 root1 = CCLD_NO_RANK;
+  if (slow) {
+    const i128 num = (i128)(tmax - tmin) * (i128)a.p.ab_den, den = (i128)(tmax - tbase);
+    if (num > (i128)a.p.beta_num * den) cls = CCLD_SLOW_S1_COMPUTATION;
+    else if (num < (i128)a.p.alpha_num * den) cls = CCLD_SLOW_S2_COMMUNICATION;
+    else cls = CCLD_SLOW_S3_MIXED;
+    if (cls != CCLD_SLOW_S2_COMMUNICATION) root1 = a.seg[(u64)CCLD_SEG_ARGMIN_RANK * a.seg_cap + sx];
+    if (rseq + 1 > n.detected_wm) { n.repeats += 1; n.detected_wm = rseq + 1; }
+  }
+  *G = n;
+  if (g < a.group_cap) {
+    i64* O = a.group;
+    const u64 C = a.group_cap;
+    O[CCLD_GRP_COMM * C + g] = (i64)(gid / (CCLD_OP_MAX * GROUP_CLS));
+    O[CCLD_GRP_OP * C + g] = (i64)((gid / GROUP_CLS) % CCLD_OP_MAX);
+    O[CCLD_GRP_CLS * C + g] = (i64)(gid % GROUP_CLS);
+    O[CCLD_GRP_N_USABLE * C + g] = (i64)(e - f);
+    O[CCLD_GRP_RSTAR_SEQ * C + g] = (i64)rseq;
+    O[CCLD_GRP_TMAX * C + g] = tmax;
+    O[CCLD_GRP_TMIN * C + g] = tmin;
+    O[CCLD_GRP_TBASE * C + g] = tbase;
+    O[CCLD_GRP_STATIC * C + g] = dynamic ? 0 : 1;
+    O[CCLD_GRP_FROZEN * C + g] = n.frozen;
+    O[CCLD_GRP_M * C + g] = n.cnt;
+    O[CCLD_GRP_SLOW * C + g] = slow ? 1 : 0;
+    O[CCLD_GRP_CLASS * C + g] = cls;
+    O[CCLD_GRP_ROOT_S1 * C + g] = root1;
+    O[CCLD_GRP_ROOT_S2 * C + g] = CCLD_NO_RANK;
+    O[CCLD_GRP_REPEATS * C + g] = n.repeats;
+    O[CCLD_GRP_LOCATE * C + g] = (slow && n.repeats >= a.p.repeat_threshold) ? 1 : 0;
+  }
+}
+void launch_group_eval(hipStream_t st, const GroupArgs& a, const uint64_t* skey, const uint32_t* sidx,
+                       uint32_t n_usable, const uint32_t* group_first, uint32_t n_group) {
+  if (n_group) hipLaunchKernelGGL(k_group_eval, dim3(n_group), dim3(256), 0, st, a, skey, sidx, n_usable, group_first, n_group);
+}
+
+// ------------------------------------------------------------------------------------------
+// Hang alerts: a collective with an operation in flight longer than the threshold, barriers
+// excepted; class by the first two questions of the hang decision tree.
+struct PredAlert {
+  const i64 *inflight, *state, *imin;
+  i64 now, thr;
+  __device__ bool operator()(u32 s) const {
+    return inflight[s] > 0 && !(state[s] & CCLD_SEG_BARRIER) && now - imin[s] > thr;
+  }
+};
+void launch_alert_select(hipStream_t st, const AlertArgs& a) {
+  PredAlert p{a.seg + (u64)CCLD_SEG_INFLIGHT * a.seg_cap, a.seg + (u64)CCLD_SEG_STATE * a.seg_cap,
+              a.seg + (u64)CCLD_SEG_INFLIGHT_ENTER_MIN * a.seg_cap, a.now_ns, a.hang_threshold_ns};
+  run_select(st, p, a.n_seg, a.tile_counts, a.alert_list, &a.counters[CNT_NALERT]);
+}
+
+// candidates of one alert, in ascending rank order; EMIT = false only counts them
+template <bool EMIT>
+__global__ __launch_bounds__(256) void k_alert_cand(AlertArgs a, u32 n_alert) {
+  __shared__ u32 s_wave[4];
+  const u32 al = blockIdx.x, tid = threadIdx.x;
+  const u32 s = a.alert_list[al];
+  const u64 C = a.seg_cap;
+  const u32 comm = (u32)a.seg[CCLD_SEG_COMM * C + s];
+  const u32 nn = (u32)a.seg[CCLD_SEG_N * C + s], ninfl = (u32)a.seg[CCLD_SEG_INFLIGHT * C + s];
+  const u32 first = (u32)a.seg[CCLD_SEG_FIRST * C + s];
+  const u32 size = a.topo.size[comm], moff = a.topo.member_off[comm];
+  const u64 rmask = ((u64)1 << a.sf.rb) - 1;
+  const u32 off = EMIT ? a.alert_ncand[al] : 0u;
+  int cls;
+  u32 total = 0;
+  if (nn < size) {
+    cls = CCLD_HANG_H1_NOT_ENTERED;          // members with no record for this operation counter
+    for (u32 q0 = 0; q0 < size; q0 += 256) {
+      const u32 q = q0 + tid;
+      bool miss = false;
+      u32 r = 0;
+      if (q < size) {
+        r = a.topo.members_sorted[moff + q];
+        u32 lo = first, hi = first + nn;
+        while (lo < hi) { const u32 m = (lo + hi) / 2; if ((u32)(a.key[m] & rmask) < r) lo = m + 1; else hi = m; }
+        miss = !(lo < first + nn && (u32)(a.key[lo] & rmask) == r);
+      }
+      u32 tot;
+      const u32 ex = block_exclusive_sum<256>(miss ? 1u : 0u, s_wave, &tot);
+      if (EMIT && miss && (u64)off + total + ex < a.cand_cap) a.cand[off + total + ex] = (i64)r;
+      total += tot;
+    }
+  } else if (ninfl < nn) {
+    cls = CCLD_HANG_H2_INCONSISTENT;         // everyone entered; the ranks that completed are the root
+    for (u32 j0 = 0; j0 < nn; j0 += 256) {
+      const u32 j = j0 + tid;
+      bool done = false;
+      u32 r = 0;
+      if (j < nn) {
+        r = (u32)(a.key[first + j] & rmask);
+        done = a.row[a.idx[first + j]].t_exit != T_INFLIGHT;
+      }
+      u32 tot;
+      const u32 ex = block_exclusive_sum<256>(done ? 1u : 0u, s_wave, &tot);
+      if (EMIT && done && (u64)off + total + ex < a.cand_cap) a.cand[off + total + ex] = (i64)r;
+      total += tot;
+    }
+  } else {
+    cls = CCLD_HANG_H3_HARDWARE;             // all hung: needs the Send/Recv counters
+  }
+  if (tid != 0) return;
+  if (!EMIT) { a.alert_ncand[al] = total; return; }
+  if (al < a.alert_cap) {
+    const u64 A = a.alert_cap;
+    a.alert[CCLD_ALR_COMM * A + al] = comm;
+    a.alert[CCLD_ALR_SEQ * A + al] = a.seg[CCLD_SEG_SEQ * C + s];
+    a.alert[CCLD_ALR_AGE * A + al] = a.now_ns - a.seg[CCLD_SEG_INFLIGHT_ENTER_MIN * C + s];
+    a.alert[CCLD_ALR_CLASS * A + al] = cls;
+    a.alert[CCLD_ALR_NCAND * A + al] = total;
+    a.alert[CCLD_ALR_CAND_OFF * A + al] = off;
+  }
+}
+void launch_alert_candidates(hipStream_t st, const AlertArgs& a, uint32_t n_alert) {
+  if (n_alert == 0) return;
+  hipLaunchKernelGGL(k_alert_cand<false>, dim3(n_alert), dim3(256), 0, st, a, n_alert);
+  launch_scan_tiles(st, a.alert_ncand, n_alert, &a.counters[CNT_NCAND]);
+  hipLaunchKernelGGL(k_alert_cand<true>, dim3(n_alert), dim3(256), 0, st, a, n_alert);
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_perm(const u32* __restrict__ idx, u32 n, u32 head, u32 cap, u32* perm) {
+  const u32 j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= n) return;
+  const u32 p = idx[j];
+  perm[j] = p >= head ? p - head : p + (cap - head);
+}
+void launch_perm(hipStream_t st, const uint32_t* idx, uint32_t n, uint32_t head, uint32_t cap, uint32_t* perm) {
+  if (n) hipLaunchKernelGGL(k_perm, dim3((n + 255) / 256), dim3(256), 0, st, idx, n, head, cap, perm);
+}
+
+}  // namespace ccld

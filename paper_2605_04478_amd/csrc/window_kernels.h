@@ -1,0 +1,116 @@
+// Host-callable launchers of the window-analysis kernels (defined in window.hip).
+#pragma once
+#include "ccld_internal.h"
+
+namespace ccld {
+
+struct IngestArgs {
+  const uint32_t *rank, *comm;
+  const uint64_t* seq;
+  const uint8_t* op;
+  const uint64_t* bytes;
+  const int64_t *t_enter, *t_exit;
+  uint64_t n;
+  uint64_t* win_key;
+  Row* win_row;
+  uint32_t tail, cap;
+  BatchMeta* meta;
+};
+void launch_ingest(hipStream_t st, const IngestArgs& a, const DeviceTopology& T, const KeyFormat& kf);
+void launch_fill_u64(hipStream_t st, uint64_t* p, uint64_t n, uint64_t v);
+
+struct SegArgs {
+  const uint64_t* key;       // sorted squeezed keys
+  const uint32_t* idx;       // window slot of each sorted record
+  const Row* row;
+  uint32_t n;
+  SqueezedFormat sf;
+  const uint32_t* comm_size;
+  uint32_t* tile_heads;      // [tiles + 1] head counts, then (after the scan) first segment ordinal of each tile
+  int64_t* seg;
+  uint64_t seg_cap;
+  uint8_t* rec_flag;
+  int64_t *lag_e, *lag_x;    // optional per-record outputs
+  int64_t* flag_lag;         // [2][cap_n] lags of flagged records by sorted position
+  uint64_t cap_n;
+  uint32_t* big_list;
+  int64_t* big_ex;           // [2][cap_n]
+  uint64_t* counters;
+  int64_t lag_floor;
+  uint32_t kmad_num, kmad_den, barrier_bytes;
+};
+void launch_seg_count(hipStream_t st, const SegArgs& a);          // fills tile_heads, flags duplicates
+void launch_scan_tiles(hipStream_t st, uint32_t* counts, uint32_t n_tiles, uint64_t* total_out);
+void launch_seg_analyze(hipStream_t st, const SegArgs& a);        // small collectives, then the oversized ones
+
+struct FlagArgs {
+  const uint64_t* key;
+  const uint8_t* rec_flag;
+  const int64_t* flag_lag;
+  uint64_t cap_n;
+  uint32_t n;
+  SqueezedFormat sf;
+  uint32_t* tile_flags;      // [tiles + 1]
+  uint32_t* flag_pos;
+  int64_t* flag;             // caller's table (may be NULL)
+  uint64_t flag_cap;
+  uint64_t* counters;
+};
+void launch_flag_compact(hipStream_t st, const FlagArgs& a);
+
+void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, int rb, uint32_t n_ranks,
+                       uint32_t* partial, int64_t* blame);
+void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag_pos, uint32_t n_flag, int rb,
+                       uint64_t* out_key);
+void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* sidx, uint32_t n_flag,
+                         const uint32_t* flag_pos, const uint8_t* rec_flag, const int64_t* flag_lag,
+                         uint64_t cap_n, uint32_t n_ranks, int64_t* blame);
+void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, uint32_t* order);
+
+struct GroupArgs {
+  const int64_t* seg;
+  uint64_t seg_cap;
+  uint32_t n_seg;            // rows present in the table
+  int ws, cb;
+  uint32_t* usable_list;
+  uint32_t* tile_counts;
+  uint64_t* counters;
+  uint64_t* gkey;            // [n_usable]
+  GroupState* gstate;
+  int64_t* group;
+  uint64_t group_cap;
+  ccld_params p;
+};
+void launch_usable_select(hipStream_t st, const GroupArgs& a);
+void launch_group_keys(hipStream_t st, const GroupArgs& a, uint32_t n_usable);
+void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_usable, int ws, uint32_t* tile_counts,
+                        uint32_t* group_first, uint64_t* counters);
+void launch_group_eval(hipStream_t st, const GroupArgs& a, const uint64_t* skey, const uint32_t* sidx,
+                       uint32_t n_usable, const uint32_t* group_first, uint32_t n_group);
+
+struct AlertArgs {
+  const int64_t* seg;
+  uint64_t seg_cap;
+  uint32_t n_seg;
+  int64_t now_ns, hang_threshold_ns;
+  const uint64_t* key;
+  const uint32_t* idx;
+  const Row* row;
+  uint32_t n;
+  SqueezedFormat sf;
+  DeviceTopology topo;
+  uint32_t* tile_counts;
+  uint32_t* alert_list;
+  uint32_t* alert_ncand;
+  int64_t* alert;
+  uint64_t alert_cap;
+  int64_t* cand;
+  uint64_t cand_cap;
+  uint64_t* counters;
+};
+void launch_alert_select(hipStream_t st, const AlertArgs& a);
+void launch_alert_candidates(hipStream_t st, const AlertArgs& a, uint32_t n_alert);
+
+void launch_perm(hipStream_t st, const uint32_t* idx, uint32_t n, uint32_t head, uint32_t cap, uint32_t* perm);
+
+}  // namespace ccld

@@ -1,0 +1,231 @@
+"""GPU parity: ccld_ingest / ccld_analyze_window / ccld_rank_blame through the C ABI
+against the CPU oracle, element by element and bit-exact (everything is int64)."""
+import numpy as np
+import pytest
+
+from oracle import ccld_oracle as orc
+from paper_2605_04478_amd import tracegen as tg
+from tests.helpers import INFLIGHT, T0, ring_topology, rounds_with_durations, toy_cols
+
+pytestmark = pytest.mark.gpu
+
+FAR = T0 + 10**15
+
+
+def _analyzer(topo, n, **params):
+    from paper_2605_04478_amd import ccld
+    return ccld.Analyzer(topo, max_window_records=max(n, 1), **params)
+
+
+def compare(g, o, blame=None, order=None, per_record=True, what=""):
+    """g: ccld.WindowResult, o: oracle WindowResult."""
+    assert g.status == o.status, (what, g.status, o.status)
+    if o.status != "OK":
+        return
+    assert g.n_seg == len(o.seg["comm"]), what
+    assert g.n_flag == len(o.flag["comm"]), what
+    assert g.n_group == len(o.group["comm"]), what
+    assert g.n_alert == len(o.alert["comm"]), what
+    assert g.n_cand == len(o.cand), what
+    for name in ("seg", "flag", "group", "alert"):
+        gt, ot = getattr(g, name), getattr(o, name)
+        for k in ot:
+            assert np.array_equal(gt[k], ot[k]), (what, name, k, np.nonzero(gt[k] != ot[k])[0][:5])
+    assert np.array_equal(g.cand, o.cand), what
+    if per_record:
+        pr = g.per_record()
+        assert np.array_equal(pr["perm"].astype(np.uint64), o.perm), what
+        assert np.array_equal(pr["lag_enter"], o.rec["lag_enter"]), what
+        assert np.array_equal(pr["lag_exit"], o.rec["lag_exit"]), what
+        assert np.array_equal(pr["rec_flag"].astype(np.int64), o.rec["flag"]), what
+    if blame is not None:
+        for k in o.blame:
+            assert np.array_equal(blame[k], o.blame[k]), (what, "blame", k)
+        assert np.array_equal(order, o.order), (what, "order")
+
+
+def run_both(topo, cols, now=FAR, on_device=True, what="", **params):
+    n = int(cols["rank"].shape[0])
+    an = _analyzer(topo, n, **params)
+    an.ingest(an.to_device(cols) if on_device else cols)
+    g = an.analyze_window(now, n_records=n, per_record=True)
+    o = orc.Oracle(topo, params).analyze_window(cols, now)
+    blame = order = None
+    if o.status == "OK":
+        blame, order = an.rank_blame()
+    compare(g, o, blame, order, what=what)
+    an.close()
+    return g, o
+
+
+def test_config1_parity():
+    tr = tg.generate(tg.config1()).shuffled(1)
+    g, o = run_both(tr.topo, tr.cols, what="config1")
+    assert g.n_flag == int((tr.inj_delay > 0).sum()) and g.n_seg == 1000
+
+
+def test_config1_host_batch_parity():
+    tr = tg.generate(tg.config1(n_slots=300)).shuffled(2)
+    run_both(tr.topo, tr.cols, on_device=False, what="config1-host")
+
+
+def _disturb(tr):
+    """In-flight operations, a missing member, inconsistent and barrier rounds, early exits."""
+    c = {k: v.copy() for k, v in tr.cols.items()}
+    topo = tr.topo
+    last70 = c["seq"][c["comm"] == 70].max()
+    c["t_exit"][(c["comm"] == 70) & (c["seq"] == last70)] = INFLIGHT                      # all hung
+    m = (c["comm"] == 71) & (c["seq"] == c["seq"][c["comm"] == 71].max())
+    idx = np.nonzero(m)[0]
+    c["t_exit"][idx[: len(idx) // 2]] = INFLIGHT                                          # some completed
+    keep = ~((c["comm"] == 3) & (c["seq"] == c["seq"][c["comm"] == 3].max()) &
+             (c["rank"] == topo.members_of(3)[2]))
+    m2 = (c["comm"] == 3) & (c["seq"] == c["seq"][c["comm"] == 3].max())
+    c["t_exit"][m2] = INFLIGHT                                                            # one member never entered
+    c["bytes"][(c["comm"] == 5) & (c["seq"] == 4) & (c["rank"] == topo.members_of(5)[1])] += 1
+    c["op"][(c["comm"] == 6) & (c["seq"] == 2) & (c["rank"] == topo.members_of(6)[0])] = tg.OP_BROADCAST
+    c["bytes"][(c["comm"] == 7) & (c["seq"] == 9)] = 2                                    # a barrier
+    c["t_exit"][(c["comm"] == 7) & (c["seq"] == 11)] = INFLIGHT
+    c["bytes"][(c["comm"] == 7) & (c["seq"] == 11)] = 0                                   # a hung barrier
+    return {k: v[keep] for k, v in c.items()}
+
+
+def test_config2_parity_with_disturbances():
+    tr = tg.generate(tg.config2(n_cycles=100)).shuffled(4)
+    cols = _disturb(tr)
+    now = int(cols["t_enter"].max()) + 10_000_000
+    g, o = run_both(tr.topo, cols, now=now, what="config2", hang_threshold_ns=1_000_000)
+    assert g.n_alert >= 3 and g.n_flag > 100 and g.n_group > 100
+    assert sorted(set(o.alert["class"].tolist())) == [1, 2, 3]
+
+
+def test_config3_layout_parity():
+    tr = tg.generate(tg.config3(n_cycles=40, layout=tg.Layout3D(tp=8, pp=4, dp=64))).shuffled(5)
+    g, o = run_both(tr.topo, tr.cols, what="config3-small")
+    assert g.n_flag > 0
+
+
+def test_random_partial_rounds_with_ties():
+    rng = np.random.default_rng(3)
+    R = 70
+    topo = ring_topology(R, comms=[list(range(R)), list(range(0, R, 2)), [1, 3, 5]])
+    rows = []
+    for c, members in enumerate([list(range(R)), list(range(0, R, 2)), [1, 3, 5]]):
+        for s in range(400):
+            n = int(rng.integers(1, len(members) + 1)) if rng.random() < 0.5 else len(members)
+            ranks = rng.choice(members, n, replace=False)
+            te = T0 + s * 1000 + rng.integers(0, 6, n)
+            tx = te + rng.integers(0, 5, n)
+            infl = rng.random(n) < 0.05
+            for r, a, b, f in zip(ranks, te, tx, infl):
+                rows.append((int(r), c, s, int(rng.integers(0, 2)) if rng.random() < 0.01 else 0,
+                             64 << int(rng.integers(0, 3)), int(a), INFLIGHT if f else int(b)))
+    cols = toy_cols(rows)
+    run_both(topo, cols, now=T0 + 10**6, what="ties", hang_threshold_ns=500_000, lag_floor_ns=1,
+             tbase_init_ns=2, kmad_num=1, kmad_den=1)
+
+
+@pytest.mark.parametrize("size,rounds", [(257, 9), (1500, 5), (3000, 3)])
+def test_large_communicators_cross_tiles(size, rounds):
+    """Collectives larger than a wavefront, than the halo and than a whole tile."""
+    rng = np.random.default_rng(size)
+    topo = ring_topology(size, comms=[list(range(size)), [0, 1, 2, 3]])
+    rows = []
+    for s in range(rounds):
+        te = T0 + s * 10**7 + rng.integers(0, 2000, size)
+        tx = te + 10**6 + rng.integers(0, 3000, size)
+        late = rng.choice(size, 3, replace=False)
+        te[late] += 5_000_000
+        tx[late] = np.maximum(tx[late], te[late] + 10)
+        for r in range(size):
+            if s == rounds - 1 and r % 97 == 5:
+                continue            # last round incomplete
+            rows.append((r, 0, s, 0, 4096, int(te[r]), int(tx[r])))
+        for r in range(4):
+            rows.append((r, 1, s, 0, 1 << 20, int(te[r]), int(tx[r])))
+    cols = toy_cols(rows)
+    p = np.random.default_rng(1).permutation(len(rows))
+    cols = {k: v[p] for k, v in cols.items()}
+    g, o = run_both(topo, cols, what=f"large{size}", tbase_init_ns=1000)
+    assert g.n_flag >= 3 * (rounds - 1)
+
+
+def test_edge_sizes():
+    topo = ring_topology(4)
+    run_both(topo, toy_cols([]), what="empty")
+    run_both(topo, toy_cols([(2, 0, 0, 0, 8, T0, T0 + 5)]), what="single")
+    run_both(topo, toy_cols([(r, 0, 0, 0, 8, T0 + r, T0 + 5 + r) for r in range(4)]), what="one-round")
+    # exact multiples of the tile sizes and one more
+    for n_rounds in (256, 257, 512, 513):
+        rows = rounds_with_durations([[100, 200, 300, 400 + j] for j in range(n_rounds)])
+        run_both(topo, toy_cols(rows), what=f"rounds{n_rounds}", tbase_init_ns=10)
+
+
+def test_validation_parity():
+    topo = ring_topology(4, comms=[[0, 1], [2, 3]])
+    ok = [(0, 0, 0, 0, 8, T0, T0 + 1), (1, 0, 0, 0, 8, T0, T0 + 1)]
+    cases = {"unknown": ok + [(0, 2, 0, 0, 8, T0, T0 + 1)],
+             "member": ok + [(2, 0, 1, 0, 8, T0, T0 + 1)],
+             "dup": ok + [(1, 0, 0, 0, 8, T0 + 5, T0 + 9)],
+             "range": ok + [(1, 0, 1, 0, 8, T0 + 5, T0 + 4)],
+             "op": ok + [(1, 0, 1, 16, 8, T0 + 5, T0 + 9)],
+             "both": ok + [(0, 2, 0, 0, 8, T0, T0 + 1), (2, 0, 1, 0, 8, T0, T0 + 1)]}
+    want = {"unknown": "E_UNKNOWN_COMM", "member": "E_RANK_NOT_MEMBER", "dup": "E_DUPLICATE_KEY",
+            "range": "E_RANGE", "op": "E_RANGE", "both": "E_UNKNOWN_COMM"}
+    for name, rows in cases.items():
+        g, o = run_both(topo, toy_cols(rows), what=name)
+        assert g.status == want[name] and g.n_seg == 0
+
+
+def test_state_across_windows_matches_oracle():
+    """Eq. 1 baseline, watermarks and the repetition counter persist from window to window."""
+    spec = tg.config1(n_slots=600)
+    tr = tg.generate(spec)
+    from paper_2605_04478_amd import ccld
+    an = ccld.Analyzer(tr.topo, max_window_records=tr.n, tbase_rounds=20)
+    o = orc.Oracle(tr.topo, dict(tbase_rounds=20))
+    R = spec.layout.n_ranks
+    for w, (a, b) in enumerate([(0, 150), (100, 300), (300, 450), (450, 600)]):     # overlapping, then disjoint
+        sl = {k: v[a * R:b * R] for k, v in tr.cols.items()}
+        an.reset_window()
+        an.ingest(an.to_device(sl))
+        g = an.analyze_window(FAR, n_records=(b - a) * R, per_record=True)
+        ref = o.analyze_window(sl, FAR)
+        blame, order = an.rank_blame()
+        compare(g, ref, blame, order, what=f"window{w}")
+    assert ref.group["frozen"].max() == 1 and ref.group["repeats"].max() >= 2
+
+
+def test_sliding_window_of_batches():
+    """window_batches = 3: each ingest drops the oldest batch; the analysis covers the last three."""
+    spec = tg.config2(n_cycles=30)
+    tr = tg.generate(spec)
+    R = spec.layout.n_ranks
+    per = 40 * R
+    batches = [{k: v[i:i + per] for k, v in tr.cols.items()} for i in range(0, tr.n, per)]
+    from paper_2605_04478_amd import ccld
+    an = ccld.Analyzer(tr.topo, max_window_records=3 * per + 17, max_batch_records=per, window_batches=3)
+    o = orc.Oracle(tr.topo)
+    for i, b in enumerate(batches):
+        an.ingest(an.to_device(b))
+        win = batches[max(0, i - 2): i + 1]
+        cols = {k: np.concatenate([w[k] for w in win]) for k in b}
+        g = an.analyze_window(FAR, n_records=3 * per, per_record=True)
+        ref = o.analyze_window(cols, FAR)
+        blame, order = an.rank_blame()
+        compare(g, ref, blame, order, what=f"step{i}")
+
+
+def test_truncated_tables_keep_exact_counts():
+    tr = tg.generate(tg.config1(n_slots=400))
+    from paper_2605_04478_amd import ccld
+    an = ccld.Analyzer(tr.topo, max_window_records=tr.n)
+    an.ingest(an.to_device(tr.cols))
+    ref = orc.Oracle(tr.topo).analyze_window(tr.cols, FAR)
+    g = an.analyze_window(FAR, n_records=tr.n, flag_cap=5, group_cap=2)
+    assert g.status == "W_TRUNCATED"
+    assert g.n_flag == len(ref.flag["comm"]) and g.n_group == len(ref.group["comm"])
+    assert np.array_equal(g.flag["rank"], ref.flag["rank"][:5])
+    assert np.array_equal(g.group["tmax"], ref.group["tmax"][:2])
+    blame, order = an.rank_blame()
+    assert np.array_equal(blame["n_late_enter"], ref.blame["n_late_enter"])
