@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Throughput of the analyzer hot path on one MI355X.
+
+A step = one pass of the whole path over one synthetic trace that is already
+resident in HBM: ccld_ingest (device columns -> keyed window), ccld_analyze_window
+(sort, per-collective statistics, flags, blame, Eq. 1-4 groups, hang alerts) and
+ccld_rank_blame.  The default workload is the 4,096-rank trace (TP8 x PP8 x DP64,
+20,000 collectives per rank, about 82M records) in a seeded random order.
+
+Prints ONE JSON line with the records/s of the whole step, the roofline figures
+of the dominant kernel (the radix-sort scatter pass, timed with HIP events on the
+library's stream inside the timed region) and the CPU oracle's rate on a bounded
+sample of the same trace.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--cycles", type=int, default=2000, help="10-op cycles per rank (2000 = the 82M-record trace)")
+    ap.add_argument("--no-shuffle", action="store_true", help="keep the generator's time-major record order")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-cycles", type=int, default=2000, help="cycles of the trace given to the CPU oracle")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this analyzer runs on ONE GPU (no sharding, no collectives); run it with --gpus 1")
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2605_04478_amd import ccld, tracegen as tg
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU")
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    spec = tg.config3(n_cycles=args.cycles, seed=args.seed)
+    t0 = time.time()
+    tr = tg.generate(spec)
+    n = tr.n
+    log(f"generated {n} records ({spec.layout.n_ranks} ranks, {tr.topo.n_comms} communicators) in {time.time() - t0:.1f}s")
+
+    an = ccld.Analyzer(tr.topo, max_window_records=n, device="cuda:0")
+    cols = an.to_device(tr.cols)
+    if not args.no_shuffle:
+        g = torch.Generator(device=dev)
+        g.manual_seed(args.seed + 1)
+        perm = torch.randperm(n, device=dev, generator=g)
+        cols = {k: v[perm].contiguous() for k, v in cols.items()}
+        del perm
+    torch.cuda.synchronize()
+    now = int(tr.cols["t_exit"].max()) + 1
+    n_seg_expected = n // 4 + 1024
+    buffers = an.alloc_window_result(n, seg_cap=n_seg_expected, flag_cap=max(n // 8, 1 << 16),
+                                     group_cap=min(an.n_comms * 1024, 1 << 22))
+    log(f"workspace {an.workspace_bytes / 2**30:.2f} GiB; inputs resident in HBM")
+
+    def step():
+        an.reset_window()
+        an.ingest(cols)
+        res = an.analyze_window(now, buffers=buffers)
+        an.rank_blame()
+        return res
+
+    res = None
+    for _ in range(args.warmup):
+        res = step()
+    torch.cuda.synchronize()
+    an.profile_enable(True)
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        res = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t_start
+    prof, passes = an.profile_read()
+    an.profile_enable(False)
+    assert res is not None and res.status == "OK", res
+    ms_per_step = dt / args.steps * 1e3
+    value = n / (dt / args.steps)
+
+    # Algorithmic HBM bytes per step of each kernel class (what the method has to move):
+    #  ingest   reads the 41-byte SoA record, writes an 8-byte key and a 32-byte payload row
+    #  hist     reads the 8-byte key once per pass
+    #  scatter  pass 1 reads the key and writes key + index (20 B); later passes move key + index (24 B)
+    #  segments reads key (twice: heads, then analysis) + index, gathers the 32-byte row, writes a
+    #           21-column int64 row per collective and one flag byte per record
+    n_seg = int(res.n_seg)
+    alg = {"ingest": n * 81.0, "sort_hist": n * 8.0 * passes, "sort_scatter": n * (20.0 + 24.0 * (passes - 1)),
+           "segments": n * (8.0 + 12.0 + 32.0 + 1.0) + n_seg * 21 * 8.0}
+    kernels = {k: {"ms_per_step": round(v[0] / args.steps, 4), "launches_per_step": v[1] / args.steps}
+               for k, v in prof.items() if v[1]}
+    for k, b in alg.items():
+        if k in kernels and kernels[k]["ms_per_step"] > 0:
+            kernels[k]["algorithmic_GBps"] = round(b / (kernels[k]["ms_per_step"] * 1e-3) / 1e9, 1)
+    dominant = max(alg, key=lambda k: prof[k][0])
+    d_ms, d_cnt = prof[dominant]
+    launches_per_step = max(d_cnt // args.steps, 1)
+    alg_bytes_per_launch = alg[dominant] / launches_per_step
+    d_avg_ms = d_ms / max(d_cnt, 1)
+    achieved = alg_bytes_per_launch / (d_avg_ms * 1e-3) / 1e9 if d_avg_ms > 0 else 0.0
+    kname = {"ingest": "k_ingest", "sort_hist": "k_radix_hist", "sort_scatter": "k_radix_scatter",
+             "segments": "k_seg_analyze"}[dominant]
+
+    cpu = None
+    if not args.no_cpu:
+        from oracle import ccld_oracle as orc
+        R = spec.layout.n_ranks
+        m = min(args.cpu_cycles, args.cycles) * 10 * R
+        sample = {k: v[:m] for k, v in tr.cols.items()}
+        o = orc.Oracle(tr.topo)
+        t1 = time.perf_counter()
+        ro = o.analyze_window(sample, now)
+        t_cpu = time.perf_counter() - t1
+        assert ro.status == "OK"
+        cpu = {"value": m / t_cpu, "unit": "records/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {min(args.cpu_cycles, args.cycles)} cycles of the same trace "
+                         f"({m} records, {len(ro.seg['comm'])} collectives), {t_cpu:.1f} s single-threaded"}
+
+    out = {
+        "metric": "trace records analyzed/sec (and HBM GB/s, % peak) at 4,096 ranks; 1 MI355X",
+        "value": value, "unit": "records/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64", "data": "synthetic",
+        "config": {"workload": f"config 3: 4,096 ranks TP8xPP8xDP64, {args.cycles * 10} collectives/rank, "
+                               f"{n} records, {'shuffled' if not args.no_shuffle else 'time-major'} order; "
+                               "step = ingest + analyze_window + rank_blame",
+                   "records": n, "collectives": int(res.n_seg), "flags": int(res.n_flag),
+                   "groups": int(res.n_group), "sort_passes": passes},
+        "roofline": {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_ms": d_avg_ms, "launches": d_cnt,
+                     "algorithmic_bytes_per_launch": alg_bytes_per_launch},
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    an.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

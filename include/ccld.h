@@ -206,6 +206,16 @@ ccld_status ccld_analyze_window(ccld_ctx *ctx, int64_t now_ns, ccld_window_resul
  * identifying the faulty GPU rank"). */
 ccld_status ccld_rank_blame(ccld_ctx *ctx, int64_t *blame, uint32_t *order);
 
+/* Optional timing of the library's kernels with HIP events recorded on the context's stream, by
+ * kernel class.  ccld_profile_enable(ctx, 1) clears the accumulators and starts timing every
+ * following call; ccld_profile_read copies the accumulated milliseconds and launch counts
+ * (host arrays of CCLD_PROF_NCLASS entries). */
+enum { CCLD_PROF_INGEST, CCLD_PROF_SORT_HIST, CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER, CCLD_PROF_SEGMENTS,
+       CCLD_PROF_FLAGS, CCLD_PROF_BLAME, CCLD_PROF_GROUPS, CCLD_PROF_ALERTS, CCLD_PROF_HANG,
+       CCLD_PROF_NCLASS = 16 };
+ccld_status ccld_profile_enable(ccld_ctx *ctx, int32_t on);
+ccld_status ccld_profile_read(ccld_ctx *ctx, double *ms, uint64_t *launches, uint64_t *sort_passes);
+
 const char *ccld_status_str(ccld_status s);
 
 #ifdef __cplusplus

@@ -80,7 +80,11 @@ class _HangResult(C.Structure):
 
 _lib: Optional[C.CDLL] = None
 
-EXPORTS = ("ccld_default_params", "ccld_query_workspace", "ccld_create", "ccld_destroy", "ccld_ingest",
+PROF_CLASSES = ("ingest", "sort_hist", "sort_scan", "sort_scatter", "segments", "flags", "blame", "groups", "alerts",
+                "hang")
+PROF_NCLASS = 16
+
+EXPORTS = ("ccld_profile_enable", "ccld_profile_read", "ccld_default_params", "ccld_query_workspace", "ccld_create", "ccld_destroy", "ccld_ingest",
            "ccld_reset_window", "ccld_analyze_window", "ccld_rank_blame", "ccld_locate_hang", "ccld_status_str")
 
 
@@ -103,6 +107,8 @@ def lib() -> C.CDLL:
         L.ccld_rank_blame.argtypes = [vp, vp, vp]
         if hasattr(L, "ccld_locate_hang"):
             L.ccld_locate_hang.argtypes = [vp, vp, u64, vp]
+        L.ccld_profile_enable.argtypes = [vp, C.c_int32]
+        L.ccld_profile_read.argtypes = [vp, vp, vp, vp]
         L.ccld_status_str.argtypes = [C.c_int32]
         L.ccld_status_str.restype = C.c_char_p
         for name in EXPORTS:
@@ -315,6 +321,19 @@ class Analyzer:
         b = blame.view(len(BLAME_COLS), self.n_ranks).cpu().numpy()
         return ({nm: np.ascontiguousarray(b[i]) for i, nm in enumerate(BLAME_COLS)},
                 order.cpu().numpy().astype(np.int64))
+
+    # ---- kernel timing ------------------------------------------------------------------
+    def profile_enable(self, on: bool = True) -> None:
+        self._check(self.L.ccld_profile_enable(self._ctx, 1 if on else 0), "ccld_profile_enable")
+
+    def profile_read(self):
+        """-> ({class: (milliseconds, launches)}, passes of the last main sort)"""
+        ms = (C.c_double * PROF_NCLASS)()
+        cnt = (C.c_uint64 * PROF_NCLASS)()
+        passes = C.c_uint64(0)
+        self._check(self.L.ccld_profile_read(self._ctx, C.addressof(ms), C.addressof(cnt), C.addressof(passes)),
+                    "ccld_profile_read")
+        return {nm: (ms[i], int(cnt[i])) for i, nm in enumerate(PROF_CLASSES)}, int(passes.value)
 
     # ---- hang location ----------------------------------------------------------------------
     def snapshots_to_device(self, cols: Dict[str, np.ndarray]) -> Dict[str, "object"]:

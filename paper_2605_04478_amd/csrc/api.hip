@@ -179,7 +179,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   c->cap = max_window_records; c->batch_cap = max_batch_records; c->snap_cap = max_snapshot_rows;
   c->kf.rb = rb; c->kf.cb = cb; c->kf.sb = 64 - rb - cb;
   c->head = 0; c->count = 0; c->next_slot = 0;
-  c->sorted_buf = 0; c->last_n = 0; c->blame_valid = false;
+  c->sorted_buf = 0; c->last_n = 0; c->blame_valid = false; c->sort_passes = 0;
   c->sf.rb = rb; c->sf.ws = 0;
   uint64_t n_members = 0;
   check_topology(topo, &n_members);
@@ -233,6 +233,7 @@ ccld_status ccld_destroy(ccld_ctx* c) {
   if (!c) return CCLD_E_NULL;
   (void)hipStreamSynchronize(c->stream);
   if (c->h_pinned) (void)hipHostFree(c->h_pinned);
+  c->prof.destroy();
   delete c;
   return CCLD_OK;
 }
@@ -281,7 +282,9 @@ ccld_status ccld_ingest(ccld_ctx* c, const ccld_records* b, uint64_t n) {
   a.n = n; a.win_key = c->win_key; a.win_row = c->win_row;
   a.tail = (uint32_t)((head + count) % std::max<uint64_t>(c->cap, 1));
   a.cap = (uint32_t)c->cap;
+  c->prof.begin();
   launch_ingest(c->stream, a, c->topo, c->kf);
+  c->prof.end(CCLD_PROF_INGEST);
   HIP_TRY(hipGetLastError());
   if (!b->on_device && n) HIP_TRY(hipStreamSynchronize(c->stream));   // the host buffers may go away on return
   c->batch_n.erase(c->batch_n.begin(), c->batch_n.begin() + drop);
@@ -336,7 +339,9 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   src.hi_shift = cb > 0 ? 64 - cb : 0;
   src.lo_bits = rb + ws;
   src.lo_mask = (rb + ws) >= 64 ? ~0ull : (((uint64_t)1 << (rb + ws)) - 1);
-  const int sorted = radix_sort_pairs(st, src, n, c->sb, rb + ws + cb);
+  const int sorted = radix_sort_pairs(st, src, n, c->sb, rb + ws + cb, &c->prof, CCLD_PROF_SORT_HIST,
+                                      CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER);
+  c->sort_passes = (rb + ws + cb) <= 0 ? 1 : (rb + ws + cb + SORT_RBITS - 1) / SORT_RBITS;
   if (sorted < 0) return o->status = CCLD_E_HIP;
   c->sorted_buf = sorted;
   const uint64_t* skey = c->sb.key[sorted];
@@ -353,16 +358,22 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   sa.lag_floor = c->p.lag_floor_ns; sa.kmad_num = c->p.kmad_num; sa.kmad_den = c->p.kmad_den;
   sa.barrier_bytes = c->p.barrier_bytes;
   const uint32_t seg_tiles = (n + SEG_TILE - 1) / SEG_TILE;
+  c->prof.begin();
   launch_seg_count(st, sa);
   launch_scan_tiles(st, c->tile_heads, seg_tiles, &c->counters[CNT_NSEG]);
-  launch_rank_count(st, skey, n, rb, n_ranks, c->rank_partial, c->blame);
   launch_seg_analyze(st, sa);
+  c->prof.end(CCLD_PROF_SEGMENTS);
+  c->prof.begin();
+  launch_rank_count(st, skey, n, rb, n_ranks, c->rank_partial, c->blame);
+  c->prof.end(CCLD_PROF_BLAME);
   FlagArgs fa;
   std::memset(&fa, 0, sizeof(fa));
   fa.key = skey; fa.rec_flag = sa.rec_flag; fa.flag_lag = c->flag_lag; fa.cap_n = c->cap; fa.n = n; fa.sf = c->sf;
   fa.tile_flags = c->tile_flags; fa.flag_pos = c->flag_pos; fa.flag = o->flag; fa.flag_cap = o->flag_cap;
   fa.counters = c->counters;
+  c->prof.begin();
   launch_flag_compact(st, fa);
+  c->prof.end(CCLD_PROF_FLAGS);
   if (o->perm) launch_perm(st, sidx, n, (uint32_t)c->head, (uint32_t)c->cap, o->perm);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
@@ -380,11 +391,13 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   sb2.key[1] = c->keyC; sb2.idx[1] = c->idxC; sb2.table = c->table2; sb2.totals = c->totals2;
   if (n_flag) {
     uint64_t* bk = c->keyC;       // keys are written to C, first pass sorts C -> buffer 0 of sb2
+    c->prof.begin();
     launch_blame_keys(st, skey, c->flag_pos, n_flag, rb, bk);
     KeySource bs; bs.key = bk; bs.head = 0; bs.cap = n_flag; bs.squeeze = 0; bs.hi_shift = 0; bs.lo_bits = 0; bs.lo_mask = 0;
     const int r2 = radix_sort_pairs(st, bs, n_flag, sb2, rb);
     if (r2 < 0) return o->status = CCLD_E_HIP;
     launch_blame_reduce(st, sb2.key[r2], sb2.idx[r2], n_flag, c->flag_pos, sa.rec_flag, c->flag_lag, c->cap, n_ranks, c->blame);
+    c->prof.end(CCLD_PROF_BLAME);
   }
 
   // 5. slow detection and location per detection group (Eq. 1-4)
@@ -393,7 +406,9 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   ga.seg = o->seg; ga.seg_cap = o->seg_cap; ga.n_seg = seg_rows; ga.ws = ws; ga.cb = cb;
   ga.usable_list = c->usable_list; ga.tile_counts = c->tile_flags; ga.counters = c->counters;
   ga.gstate = c->gstate; ga.group = o->group; ga.group_cap = o->group_cap; ga.p = c->p;
+  c->prof.begin();
   launch_usable_select(st, ga);
+  c->prof.end(CCLD_PROF_GROUPS);
   // 6. hang alerts
   AlertArgs aa;
   std::memset(&aa, 0, sizeof(aa));
@@ -402,7 +417,9 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   aa.sf = c->sf; aa.topo = c->topo; aa.tile_counts = c->tile_heads; aa.alert_list = c->alert_list;
   aa.alert_ncand = c->alert_ncand; aa.alert = o->alert; aa.alert_cap = o->alert_cap; aa.cand = o->cand;
   aa.cand_cap = o->cand_cap; aa.counters = c->counters;
+  c->prof.begin();
   launch_alert_select(st, aa);
+  c->prof.end(CCLD_PROF_ALERTS);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
@@ -411,20 +428,26 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   if (n_usable) {
     if (cb + 10 + ws > 64) return o->status = CCLD_E_KEY_WIDTH;
     ga.gkey = c->keyC;            // blame's sort is done with C by stream order
+    c->prof.begin();
     launch_group_keys(st, ga, n_usable);
     KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = n_usable; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0;
     // sort C -> buffers {other main, C}: the first pass reads C and writes buffer 0, so C is free again for pass 2
     const int r3 = radix_sort_pairs(st, gs, n_usable, sb2, cb + 10 + ws);
     if (r3 < 0) return o->status = CCLD_E_HIP;
     launch_group_heads(st, sb2.key[r3], n_usable, ws, c->tile_flags, c->group_first, c->counters);
+    c->prof.end(CCLD_PROF_GROUPS);
     HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     o->n_group = c->h_pinned[CNT_NGROUP];
+    c->prof.begin();
     launch_group_eval(st, ga, sb2.key[r3], sb2.idx[r3], n_usable, c->group_first, (uint32_t)o->n_group);
+    c->prof.end(CCLD_PROF_GROUPS);
     if (o->n_group > o->group_cap) o->status = CCLD_W_TRUNCATED;
   }
   if (o->n_alert) {
+    c->prof.begin();
     launch_alert_candidates(st, aa, (uint32_t)o->n_alert);
+    c->prof.end(CCLD_PROF_ALERTS);
     HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     o->n_cand = c->h_pinned[CNT_NCAND];
@@ -432,6 +455,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipStreamSynchronize(st));
+  c->prof.collect();
   c->blame_valid = true;
   return o->status;
 }
@@ -446,6 +470,24 @@ ccld_status ccld_rank_blame(ccld_ctx* c, int64_t* blame, uint32_t* order) {
   if (order) launch_blame_order(c->stream, c->blame, n_ranks, order);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipStreamSynchronize(c->stream));
+  return CCLD_OK;
+}
+
+ccld_status ccld_profile_enable(ccld_ctx* c, int32_t on) {
+  if (!c) return CCLD_E_NULL;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  return c->prof.enable(c->stream, on != 0) ? CCLD_OK : CCLD_E_HIP;
+}
+
+ccld_status ccld_profile_read(ccld_ctx* c, double* ms, uint64_t* launches, uint64_t* sort_passes) {
+  if (!c) return CCLD_E_NULL;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  c->prof.collect();
+  for (int i = 0; i < CCLD_PROF_NCLASS; ++i) {
+    if (ms) ms[i] = c->prof.ms[i];
+    if (launches) launches[i] = c->prof.cnt[i];
+  }
+  if (sort_passes) *sort_passes = (uint64_t)c->sort_passes;
   return CCLD_OK;
 }
 

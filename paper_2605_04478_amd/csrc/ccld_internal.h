@@ -6,6 +6,7 @@
 
 #include "ccld.h"
 #include "radix_sort.h"
+#include "profiler.h"
 
 namespace ccld {
 
@@ -114,4 +115,6 @@ struct ccld_ctx {
   uint64_t last_n;
   ccld::SqueezedFormat sf;
   bool blame_valid;
+  ccld::Profiler prof;
+  int sort_passes;                    // passes of the last main sort
 };

@@ -35,6 +35,9 @@ inline uint64_t sort_table_words(uint64_t n_max) { return (uint64_t)SORT_RADIX *
 // Sorts n pairs stably by the low `bits` bits of the (squeezed) key.  The first pass reads
 // src; the result lands in buf.key[r], buf.idx[r] where r is the return value (0 or 1), or
 // a negative value if a launch failed.  bits == 0 still performs one copying pass.
-int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const SortBuffers& buf, int bits);
+// prof (optional) times the launches: class ids for the histogram, scan and scatter kernels.
+struct Profiler;
+int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const SortBuffers& buf, int bits,
+                     Profiler* prof = nullptr, int cls_hist = 0, int cls_scan = 0, int cls_scatter = 0);
 
 }  // namespace ccld

@@ -6,6 +6,7 @@
 // run to its place with consecutive lanes on consecutive addresses.
 #include "radix_sort.h"
 #include "device_utils.h"
+#include "profiler.h"
 
 namespace ccld {
 
@@ -161,7 +162,8 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, c
 
 static_assert(SORT_RADIX <= SORT_THREADS, "one thread per digit in the scatter prologue");
 
-int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const SortBuffers& buf, int bits) {
+int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const SortBuffers& buf, int bits,
+                     Profiler* prof, int cls_hist, int cls_scan, int cls_scatter) {
   if (n == 0) return 0;
   const u32 n_tiles = sort_tiles(n);
   int passes = bits <= 0 ? 1 : (bits + SORT_RBITS - 1) / SORT_RBITS;
@@ -172,6 +174,7 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const
     if (nb < 1) nb = 1;
     const u32 dmask = (1u << nb) - 1u;
     const int out = cur < 0 ? 0 : 1 - cur;
+    if (prof) prof->begin();
     if (p == 0) {
       hipLaunchKernelGGL(k_radix_hist<true>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
                          (const u64*)nullptr, buf.table, n, n_tiles, done_bits, dmask);
@@ -179,7 +182,9 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const
       hipLaunchKernelGGL(k_radix_hist<false>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
                          (const u64*)buf.key[cur], buf.table, n, n_tiles, done_bits, dmask);
     }
+    if (prof) { prof->end(cls_hist); prof->begin(); }
     hipLaunchKernelGGL(k_radix_scan, dim3(dmask + 1), dim3(SORT_THREADS), 0, stream, buf.table, buf.totals, n_tiles);
+    if (prof) { prof->end(cls_scan); prof->begin(); }
     if (p == 0) {
       hipLaunchKernelGGL(k_radix_scatter<true>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
                          (const u64*)nullptr, (const u32*)nullptr, buf.key[out], buf.idx[out],
@@ -189,6 +194,7 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const
                          (const u64*)buf.key[cur], (const u32*)buf.idx[cur], buf.key[out], buf.idx[out],
                          (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, done_bits, nb);
     }
+    if (prof) prof->end(cls_scatter);
     if (hipGetLastError() != hipSuccess) return -1;
     done_bits += nb;
     cur = out;
