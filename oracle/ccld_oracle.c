@@ -433,3 +433,256 @@ int orc_analyze_window(const int64_t *P, const orc_topology *T, uint64_t n,
   R->status = ORC_OK;
   return ORC_OK;
 }
+
+/* ==================================================================================================
+ * Hang location from progress-counter snapshots (Section 4.2.2, hang decision tree; Section 4.1.2,
+ * SendCount / RecvCount per channel; Section 4.2.1, ring vs tree comparison groups).
+ *
+ * Rows: one per (snapshot, rank, communicator, channel) with the operation counter the counters
+ * describe and the chunks sent / received so far.  Every cell of the grid
+ * [0, n_snap) x members x [0, n_ch) must be present exactly once.
+ *
+ * The three questions of the paper's tree are asked per communicator:
+ *   a rank whose operation counter lags has not entered        -> Not-Entered-Hang, that rank
+ *   all entered, some ranks still progressing ("non-hang")     -> Inconsistent-Hang, those ranks
+ *   all entered, all hung                                      -> Hardware-Fault, the rank with the
+ *                                                                 fewest SendCount/RecvCount
+ * The operational definitions below (stall test over stall_snapshots snapshots, idle test, ring
+ * wait-for edges with a FIFO depth, the filter for ranks that are blocked inside another hung
+ * communicator) are this build's reading and are "parity unpinned" by the paper; the tests pin
+ * them by brute force on small rings and by the recovery of injected roots.
+ * ================================================================================================== */
+enum { PAIR_RANK, PAIR_COMM, PAIR_STALLED, PAIR_ENTERED, PAIR_SEQ, PAIR_SENT, PAIR_RECV, PAIR_WAITS_ON,
+       PAIR_HOPS, PAIR_ONSET, PAIR_NCOL };
+enum { HC_COMM, HC_HUNG, HC_CLASS, HC_SEQ_MAX, HC_ROOT_BY_COUNT, HC_NCAND, HC_NCOL };
+enum { ROOT_RANK, ROOT_COMM, ROOT_CLASS, ROOT_NCOL };
+
+typedef struct {
+  int32_t status;
+  uint64_t n_root, n_pair, n_comm;
+  int64_t *root;   /* [n_root][ROOT_NCOL] ordered by (rank, comm) */
+  int64_t *pair;   /* [n_pair][PAIR_NCOL] one row per member slot of every communicator, in table order */
+  int64_t *comm;   /* [n_comm][HC_NCOL]   one row per communicator */
+} orc_hang_result;
+
+void orc_hang_result_free(orc_hang_result *r) {
+  if (!r) return;
+  free(r->root); free(r->pair); free(r->comm);
+  memset(r, 0, sizeof(*r));
+}
+
+typedef struct { uint64_t seq; uint32_t sent, recv; } cell_t;
+
+static int cmp_root(const void *pa, const void *pb) {
+  const int64_t *a = (const int64_t *)pa, *b = (const int64_t *)pb;
+  if (a[ROOT_RANK] != b[ROOT_RANK]) return a[ROOT_RANK] < b[ROOT_RANK] ? -1 : 1;
+  if (a[ROOT_COMM] != b[ROOT_COMM]) return a[ROOT_COMM] < b[ROOT_COMM] ? -1 : 1;
+  return 0;
+}
+
+int orc_locate_hang(const int64_t *P, const orc_topology *T, uint64_t n_rows, uint32_t n_snap, uint32_t n_ch,
+                    const uint32_t *snap, const uint32_t *rank, const uint32_t *comm, const uint32_t *channel,
+                    const uint64_t *seq_posted, const uint32_t *chunks_sent, const uint32_t *chunks_recv,
+                    orc_hang_result *R) {
+  memset(R, 0, sizeof(*R));
+  if (n_snap == 0 || n_ch == 0) { R->status = ORC_E_BAD_ARG; return R->status; }
+  uint64_t n_pair = 0;
+  for (uint32_t c = 0; c < T->n_comms; ++c) n_pair += T->size[c];
+  const uint64_t n_cell = n_pair * n_ch * n_snap;
+
+  /* ---- validation ---- */
+  int bad_comm = 0, bad_member = 0, bad_range = 0;
+  for (uint64_t i = 0; i < n_rows; ++i) {
+    if (comm[i] >= T->n_comms) { bad_comm = 1; continue; }
+    if (rank[i] >= T->n_ranks || !is_member(T, comm[i], rank[i])) bad_member = 1;
+    if (snap[i] >= n_snap || channel[i] >= n_ch) bad_range = 1;
+  }
+  if (bad_comm) { R->status = ORC_E_UNKNOWN_COMM; return R->status; }
+  if (bad_member) { R->status = ORC_E_RANK_NOT_MEMBER; return R->status; }
+  if (bad_range) { R->status = ORC_E_RANGE; return R->status; }
+
+  /* ---- place every row in its cell [pair][channel][snapshot] ---- */
+  cell_t *cell = (cell_t *)calloc(n_cell ? n_cell : 1, sizeof(cell_t));
+  uint8_t *seen = (uint8_t *)calloc(n_cell ? n_cell : 1, 1);
+  int dup = 0, gap = 0;
+  for (uint64_t i = 0; i < n_rows; ++i) {
+    uint32_t c = comm[i], slot = 0;
+    while (T->members[T->member_off[c] + slot] != rank[i]) ++slot;
+    uint64_t k = (((uint64_t)T->member_off[c] + slot) * n_ch + channel[i]) * n_snap + snap[i];
+    if (seen[k]) dup = 1;
+    seen[k] = 1;
+    cell[k].seq = seq_posted[i]; cell[k].sent = chunks_sent[i]; cell[k].recv = chunks_recv[i];
+  }
+  for (uint64_t k = 0; k < n_cell; ++k) if (!seen[k]) gap = 1;
+  free(seen);
+  if (dup) { free(cell); R->status = ORC_E_DUPLICATE_KEY; return R->status; }
+  if (gap) { free(cell); R->status = ORC_E_SNAPSHOT_GAP; return R->status; }
+
+  const uint32_t L = n_snap - 1;
+  const int64_t W = P[P_STALL_SNAPSHOTS];
+  const int can_stall = W >= 0 && (int64_t)L >= W;     /* too few snapshots: nothing can be called stalled */
+
+  R->n_pair = n_pair; R->n_comm = T->n_comms;
+  R->pair = (int64_t *)calloc((n_pair ? n_pair : 1) * PAIR_NCOL, sizeof(int64_t));
+  R->comm = (int64_t *)calloc((size_t)T->n_comms * HC_NCOL, sizeof(int64_t));
+
+  /* ---- per (rank, communicator): stalled, operation counter, chunk totals, onset ---- */
+  for (uint32_t c = 0; c < T->n_comms; ++c) {
+    for (uint32_t q = 0; q < T->size[c]; ++q) {
+      uint64_t p = (uint64_t)T->member_off[c] + q;
+      int64_t *Q = R->pair + p * PAIR_NCOL;
+      int stalled = can_stall;
+      uint64_t seq = 0, S = 0, Rv = 0;
+      uint32_t onset = 0;
+      for (uint32_t ch = 0; ch < n_ch; ++ch) {
+        const cell_t *s = cell + (p * n_ch + ch) * n_snap;
+        if (can_stall) {
+          const cell_t *o = s + (L - (uint32_t)W);
+          if (!(o->seq == s[L].seq && o->sent == s[L].sent && o->recv == s[L].recv)) stalled = 0;
+        }
+        uint32_t on = L;       /* smallest snapshot from which this channel's state stays constant */
+        while (on > 0 && s[on - 1].seq == s[L].seq && s[on - 1].sent == s[L].sent && s[on - 1].recv == s[L].recv) --on;
+        if (on > onset) onset = on;
+        if (s[L].seq > seq) seq = s[L].seq;
+        S += s[L].sent; Rv += s[L].recv;
+      }
+      Q[PAIR_RANK] = T->members[p]; Q[PAIR_COMM] = c; Q[PAIR_STALLED] = stalled; Q[PAIR_SEQ] = (int64_t)seq;
+      Q[PAIR_SENT] = (int64_t)S; Q[PAIR_RECV] = (int64_t)Rv; Q[PAIR_WAITS_ON] = ORC_NO_RANK; Q[PAIR_HOPS] = -1;
+      Q[PAIR_ONSET] = onset;
+    }
+  }
+  free(cell);
+
+  /* ---- per communicator: entered, idle test, the decision tree, wait-for edges ---- */
+  uint8_t *is_cand = (uint8_t *)calloc(n_pair ? n_pair : 1, 1);
+  for (uint32_t c = 0; c < T->n_comms; ++c) {
+    const uint32_t n = T->size[c], off = T->member_off[c];
+    int64_t *H = R->comm + (size_t)c * HC_NCOL;
+    int64_t *Q = R->pair + (uint64_t)off * PAIR_NCOL;
+#define PQ(q, col) Q[(uint64_t)(q) * PAIR_NCOL + (col)]
+    uint64_t seq_max = 0;
+    for (uint32_t q = 0; q < n; ++q) if ((uint64_t)PQ(q, PAIR_SEQ) > seq_max) seq_max = (uint64_t)PQ(q, PAIR_SEQ);
+    int all_entered = 1, any_stalled = 0, all_stalled = 1;
+    for (uint32_t q = 0; q < n; ++q) {
+      PQ(q, PAIR_ENTERED) = ((uint64_t)PQ(q, PAIR_SEQ) == seq_max);
+      if (!PQ(q, PAIR_ENTERED)) all_entered = 0;
+      if (PQ(q, PAIR_STALLED)) any_stalled = 1; else all_stalled = 0;
+    }
+    /* a completed collective leaves comparable ranks with identical counts: the whole ring, or each
+       layer of the tree */
+    int *depth = (int *)calloc(n, sizeof(int));
+    if (T->algo[c] == 1 && T->tree_parent)
+      for (uint32_t q = 0; q < n; ++q) { int32_t par = T->tree_parent[off + q]; depth[q] = par < 0 ? 0 : depth[par] + 1; }
+    int idle_ok = all_entered;
+    for (uint32_t q = 0; q < n && idle_ok; ++q)
+      for (uint32_t r2 = 0; r2 < q; ++r2)
+        if (depth[r2] == depth[q]) {
+          if (PQ(r2, PAIR_SENT) != PQ(q, PAIR_SENT) || PQ(r2, PAIR_RECV) != PQ(q, PAIR_RECV)) idle_ok = 0;
+          break;      /* comparing with the first member of the layer is enough */
+        }
+    const int hung = !idle_ok && any_stalled;
+    /* the rank with the fewest SendCount/RecvCount: minimal S+R, then minimal R, then minimal rank */
+    uint32_t best = 0;
+    for (uint32_t q = 1; q < n; ++q) {
+      int64_t a = PQ(q, PAIR_SENT) + PQ(q, PAIR_RECV), b = PQ(best, PAIR_SENT) + PQ(best, PAIR_RECV);
+      if (a < b || (a == b && (PQ(q, PAIR_RECV) < PQ(best, PAIR_RECV) ||
+                               (PQ(q, PAIR_RECV) == PQ(best, PAIR_RECV) && PQ(q, PAIR_RANK) < PQ(best, PAIR_RANK)))))
+        best = q;
+    }
+    H[HC_COMM] = c; H[HC_HUNG] = hung; H[HC_SEQ_MAX] = (int64_t)seq_max;
+    H[HC_ROOT_BY_COUNT] = hung ? PQ(best, PAIR_RANK) : ORC_NO_RANK; H[HC_CLASS] = 0;
+    if (hung) {
+      if (!all_entered) {
+        H[HC_CLASS] = 1;
+        for (uint32_t q = 0; q < n; ++q) if (!PQ(q, PAIR_ENTERED)) is_cand[off + q] = 1;
+      } else if (!all_stalled) {
+        H[HC_CLASS] = 2;
+        for (uint32_t q = 0; q < n; ++q) if (!PQ(q, PAIR_STALLED)) is_cand[off + q] = 1;
+      } else {
+        H[HC_CLASS] = 3;
+        uint32_t n_c = 0;
+        if (T->algo[c] == 0) {
+          /* ring: a rank that has consumed everything its predecessor sent waits on the predecessor;
+             a rank whose successor has fifo_depth unconsumed chunks waits on the successor */
+          for (uint32_t q = 0; q < n; ++q) {
+            uint32_t pred = (q + n - 1) % n, succ = (q + 1) % n;
+            if (n > 1 && PQ(q, PAIR_RECV) >= PQ(pred, PAIR_SENT)) PQ(q, PAIR_WAITS_ON) = PQ(pred, PAIR_RANK);
+            else if (n > 1 && PQ(q, PAIR_SENT) - PQ(succ, PAIR_RECV) >= P[P_FIFO_DEPTH]) PQ(q, PAIR_WAITS_ON) = PQ(succ, PAIR_RANK);
+            else { is_cand[off + q] = 1; ++n_c; }
+          }
+        } else {
+          /* tree: inside a layer, the ranks furthest behind the layer's best */
+          int64_t worst = 0;
+          int64_t *def = (int64_t *)calloc(n, sizeof(int64_t));
+          for (uint32_t q = 0; q < n; ++q) {
+            int64_t mx = 0;
+            for (uint32_t r2 = 0; r2 < n; ++r2)
+              if (depth[r2] == depth[q] && PQ(r2, PAIR_SENT) + PQ(r2, PAIR_RECV) > mx) mx = PQ(r2, PAIR_SENT) + PQ(r2, PAIR_RECV);
+            def[q] = mx - (PQ(q, PAIR_SENT) + PQ(q, PAIR_RECV));
+            if (def[q] > worst) worst = def[q];
+          }
+          if (worst > 0) for (uint32_t q = 0; q < n; ++q) if (def[q] == worst) { is_cand[off + q] = 1; ++n_c; }
+          free(def);
+        }
+        if (n_c == 0) is_cand[off + best] = 1;      /* a pure cycle: fall back to the fewest counts */
+      }
+    }
+    free(depth);
+#undef PQ
+  }
+
+  /* ---- a not-entered rank that is itself blocked inside another hung communicator is a victim ---- */
+  uint8_t *drop = (uint8_t *)calloc(n_pair ? n_pair : 1, 1);
+  for (uint32_t c = 0; c < T->n_comms; ++c) {
+    if (R->comm[(size_t)c * HC_NCOL + HC_CLASS] != 1) continue;
+    for (uint32_t q = 0; q < T->size[c]; ++q) {
+      uint64_t p = (uint64_t)T->member_off[c] + q;
+      if (!is_cand[p]) continue;
+      uint32_t r = T->members[p];
+      for (uint32_t c2 = 0; c2 < T->n_comms && !drop[p]; ++c2) {
+        if (c2 == c || !R->comm[(size_t)c2 * HC_NCOL + HC_HUNG]) continue;
+        for (uint32_t q2 = 0; q2 < T->size[c2]; ++q2) {
+          uint64_t p2 = (uint64_t)T->member_off[c2] + q2;
+          if (T->members[p2] == r && R->pair[p2 * PAIR_NCOL + PAIR_ENTERED]) { drop[p] = 1; break; }
+        }
+      }
+    }
+  }
+  uint64_t n_root = 0;
+  for (uint64_t p = 0; p < n_pair; ++p) { if (drop[p]) is_cand[p] = 0; if (is_cand[p]) ++n_root; }
+  free(drop);
+
+  /* ---- hops along the wait-for edges to a root; roots listed by (rank, communicator) ---- */
+  R->n_root = n_root;
+  R->root = (int64_t *)calloc((n_root ? n_root : 1) * ROOT_NCOL, sizeof(int64_t));
+  uint64_t kr = 0;
+  for (uint32_t c = 0; c < T->n_comms; ++c) {
+    const uint32_t n = T->size[c], off = T->member_off[c];
+    int64_t *H = R->comm + (size_t)c * HC_NCOL;
+    uint32_t nc = 0;
+    for (uint32_t q = 0; q < n; ++q) if (is_cand[off + q]) {
+      ++nc;
+      int64_t *O = R->root + kr * ROOT_NCOL; ++kr;
+      O[ROOT_RANK] = T->members[off + q]; O[ROOT_COMM] = c; O[ROOT_CLASS] = H[HC_CLASS];
+    }
+    H[HC_NCAND] = nc;
+    if (!H[HC_HUNG]) continue;
+    for (uint32_t q = 0; q < n; ++q) {
+      uint32_t cur = q;
+      int64_t hops = 0;
+      while (1) {
+        if (is_cand[off + cur]) break;
+        int64_t w = R->pair[((uint64_t)off + cur) * PAIR_NCOL + PAIR_WAITS_ON];
+        if (w == ORC_NO_RANK || hops >= (int64_t)n) { hops = -1; break; }
+        uint32_t nxt = 0;
+        while (T->members[off + nxt] != (uint32_t)w) ++nxt;
+        cur = nxt; ++hops;
+      }
+      R->pair[((uint64_t)off + q) * PAIR_NCOL + PAIR_HOPS] = hops;
+    }
+  }
+  qsort(R->root, n_root, ROOT_NCOL * sizeof(int64_t), cmp_root);
+  free(is_cand);
+  R->status = ORC_OK;
+  return ORC_OK;
+}

@@ -65,6 +65,24 @@ class _WinRes(C.Structure):
                 ("order", C.c_void_p)]
 
 
+class _HangRes(C.Structure):
+    _fields_ = [("status", C.c_int32), ("n_root", C.c_uint64), ("n_pair", C.c_uint64), ("n_comm", C.c_uint64),
+                ("root", C.c_void_p), ("pair", C.c_void_p), ("comm", C.c_void_p)]
+
+
+HANG_ROOT_COLS = ("rank", "comm", "class")
+HANG_PAIR_COLS = ("rank", "comm", "stalled", "entered", "seq", "sent", "recv", "waits_on", "hops", "onset")
+HANG_COMM_COLS = ("comm", "hung", "class", "seq_max", "root_by_count", "n_cand")
+
+
+@dataclass
+class HangResult:
+    status: str
+    root: Dict[str, np.ndarray]
+    pair: Dict[str, np.ndarray]
+    comm: Dict[str, np.ndarray]
+
+
 _lib: Optional[C.CDLL] = None
 
 
@@ -80,6 +98,10 @@ def lib() -> C.CDLL:
         L.orc_analyze_window.restype = C.c_int
         L.orc_analyze_window.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64] + [C.c_void_p] * 7 + \
             [C.c_int64, C.c_void_p, C.c_void_p]
+        L.orc_hang_result_free.argtypes = [C.c_void_p]
+        L.orc_locate_hang.restype = C.c_int
+        L.orc_locate_hang.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32] + \
+            [C.c_void_p] * 7 + [C.c_void_p]
         _lib = L
     return _lib
 
@@ -180,3 +202,26 @@ class Oracle:
             return out
         finally:
             self.L.orc_window_result_free(C.addressof(res))
+
+    def locate_hang(self, cols: Dict[str, np.ndarray], n_snapshots: int, n_channels: int) -> HangResult:
+        dt = {"snap": np.uint32, "rank": np.uint32, "comm": np.uint32, "channel": np.uint32,
+              "seq_posted": np.uint64, "chunks_sent": np.uint32, "chunks_recv": np.uint32}
+        a = {k: np.ascontiguousarray(cols[k], dtype=dt[k]) for k in dt}
+        n = int(a["snap"].shape[0])
+        res = _HangRes()
+        self.L.orc_locate_hang(_ptr(self._p), C.addressof(self._topo), n, int(n_snapshots), int(n_channels),
+                               _ptr(a["snap"]), _ptr(a["rank"]), _ptr(a["comm"]), _ptr(a["channel"]),
+                               _ptr(a["seq_posted"]), _ptr(a["chunks_sent"]), _ptr(a["chunks_recv"]),
+                               C.addressof(res))
+        try:
+            status = STATUS[res.status]
+            if res.status != 0:
+                z = np.zeros((0,), np.int64)
+                e = lambda names: {k: z.copy() for k in names}
+                return HangResult(status, e(HANG_ROOT_COLS), e(HANG_PAIR_COLS), e(HANG_COMM_COLS))
+            return HangResult(status,
+                              _cols(_table(res.root, res.n_root, len(HANG_ROOT_COLS)), HANG_ROOT_COLS),
+                              _cols(_table(res.pair, res.n_pair, len(HANG_PAIR_COLS)), HANG_PAIR_COLS),
+                              _cols(_table(res.comm, res.n_comm, len(HANG_COMM_COLS)), HANG_COMM_COLS))
+        finally:
+            self.L.orc_hang_result_free(C.addressof(res))

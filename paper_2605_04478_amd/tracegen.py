@@ -442,3 +442,151 @@ def config3(n_cycles: int = 2000, seed: int = 0, faults: bool = True,
     return TraceSpec(layout=lay, cycle=CYCLE_3D, n_slots=10 * n_cycles, bytes_dist=("loguniform", 16.0, 29.0),
                      sigma=0.2, skew_ns=100_000, slot_ns=250_000_000, slow_ranks=slow, slow_groups=groups,
                      seed=seed, name="config3")
+
+
+# --------------------------------------------------------------------------
+# progress-counter snapshots (hang location)
+# --------------------------------------------------------------------------
+SNAP_COLUMNS = ("snap", "rank", "comm", "channel", "seq_posted", "chunks_sent", "chunks_recv")
+_S_HROOT, _S_HC0, _S_HTOT = 31, 32, 33
+
+
+def ring_steady_state(n: int, frozen: int, c0: np.ndarray, total: int, depth: int):
+    """Chunk counters of an n-rank ring in which member slot `frozen` stopped after sending and
+    receiving c0 chunks (one value per channel) and everybody else ran until blocked.
+
+    The ring is simulated step by step: a rank may send chunk S when it has received the chunks
+    before it (S <= R) and its successor has fewer than `depth` unconsumed chunks (S - R_succ <
+    depth); it may receive when its predecessor has sent more than it has received (R < S_pred)
+    and it is not already ahead of its own sends (R <= S).  Returns (S, R), each [n, channels]."""
+    c0 = np.asarray(c0, dtype=np.int64)
+    S = np.zeros((n, c0.shape[0]), dtype=np.int64)
+    R = np.zeros_like(S)
+    S[frozen] = c0
+    R[frozen] = c0
+    live = np.ones(n, dtype=bool)
+    live[frozen] = False
+    for _ in range(4 * (int(c0.max()) + n * (depth + 2)) + 16):
+        pred_S = np.roll(S, 1, axis=0)
+        succ_R = np.roll(R, -1, axis=0)
+        can_recv = (R < pred_S) & (R <= S) & (R < total) & live[:, None]
+        R = R + can_recv
+        can_send = (S <= R) & (S - succ_R < depth) & (S < total) & live[:, None]
+        S2 = S + can_send
+        if not can_recv.any() and not can_send.any():
+            break
+        S = S2
+    return S, R
+
+
+@dataclass
+class HangSpec:
+    layout: Layout3D
+    n_snapshots: int = 64
+    n_channels: int = 16
+    hang_snapshot: int = 20            # first snapshot that shows the frozen state (None = healthy run)
+    hang_seq: int = 12_345
+    fifo_depth: int = 8
+    seed: int = 0
+
+
+@dataclass
+class HangTrace:
+    spec: HangSpec
+    topo: Topology
+    cols: Dict[str, np.ndarray]
+    root_rank: int                     # ground truth (or -1 for a healthy run)
+    root_comm: int
+
+    @property
+    def n(self) -> int:
+        return int(self.cols["snap"].shape[0])
+
+
+def generate_hang(spec: HangSpec, shuffle: bool = True) -> HangTrace:
+    """Snapshots of every (rank, communicator, channel) at 1 s intervals.
+
+    Healthy snapshots show completed operations: every member of a communicator reports the same
+    operation counter and S = R = the operation's chunk count per channel, and the counter advances
+    from snapshot to snapshot.  From `hang_snapshot` on, one seeded rank of one DP ring is frozen
+    in the middle of operation `hang_seq`; the ring's other members run until blocked
+    (ring_steady_state); the ring's members post nothing further on their other communicators;
+    every other rank posts one more operation on each communicator it shares with a ring member
+    (the world communicator included), sends its first chunk and blocks; communicators without a
+    ring member stay idle after their last completed operation."""
+    L = spec.layout
+    topo = L.topology()
+    R = L.n_ranks
+    nch, nsn = spec.n_channels, spec.n_snapshots
+    kinds = ["tp", "pp", "dp"] + (["world"] if L.world else [])
+    ranks = np.arange(R, dtype=np.int64)
+    seed = spec.seed
+    hang = spec.hang_snapshot is not None
+    root_rank = root_comm = -1
+    ring = np.zeros(0, dtype=np.int64)
+    if hang:
+        root_rank = int(rand_u64(seed, _S_HROOT, 0) % np.uint64(R))
+        root_comm = int(L.comm_of("dp", root_rank))
+        ring = topo.members_of(root_comm).astype(np.int64)
+    in_ring = np.zeros(R, dtype=bool)
+    in_ring[ring] = True
+    out = {k: [] for k in SNAP_COLUMNS}
+    ch = np.arange(nch, dtype=np.int64)
+    Sx = Rx = None
+    if hang:
+        c0 = 100 + (rand_u64(seed, _S_HC0, ch) % np.uint64(900)).astype(np.int64)
+        slot = int(np.nonzero(ring == root_rank)[0][0])
+        Sx, Rx = ring_steady_state(len(ring), slot, c0, 1 << 20, spec.fifo_depth)
+    for kind in kinds:
+        comm_r = L.comm_of(kind, ranks).astype(np.int64)                      # [R]
+        # chunks per channel of a completed operation (same for all members) and the counter's pace
+        pace = 1 + (rand_u64(seed, _S_HTOT, comm_r, 7) % np.uint64(5)).astype(np.int64)
+        base = spec.hang_seq - pace * (spec.hang_snapshot if hang else 0) if kind == "dp" else \
+            1000 + (rand_u64(seed, _S_HTOT, comm_r, 8) % np.uint64(9000)).astype(np.int64)
+        base = np.broadcast_to(base, (R,)).astype(np.int64)
+        touched = np.zeros(R, dtype=bool)          # communicator has a member of the frozen ring
+        if hang:
+            has = np.zeros(topo.n_comms + 1, dtype=bool)
+            has[np.unique(comm_r[ring])] = True
+            touched = has[comm_r]
+        for s in range(nsn):
+            frozen_now = hang and s >= spec.hang_snapshot
+            s_eff = min(s, spec.hang_snapshot - 1) if frozen_now else s
+            seq = base + pace * s_eff                                           # [R] last completed op
+            tot = 64 + (rand_u64(seed, _S_HTOT, comm_r[:, None] * 131071 + seq[:, None], ch[None, :])
+                        % np.uint64(1984)).astype(np.int64)                     # [R, ch]
+            sent = tot.copy()
+            recv = tot.copy()
+            seqp = np.broadcast_to(seq[:, None], (R, nch)).copy()
+            if frozen_now:
+                if kind == "dp":
+                    # the frozen ring: mid-operation hang_seq
+                    sent[ring] = Sx
+                    recv[ring] = Rx
+                    seqp[ring] = spec.hang_seq
+                else:
+                    # everybody outside the ring posted the next operation where a ring member is awaited
+                    blocked = touched & ~in_ring
+                    seqp[blocked] = seq[blocked, None] + 1
+                    sent[blocked] = 1
+                    recv[blocked] = 0
+            n_rows = R * nch
+            out["snap"].append(np.full(n_rows, s, dtype=np.uint32))
+            out["rank"].append(np.repeat(ranks, nch).astype(np.uint32))
+            out["comm"].append(np.repeat(comm_r, nch).astype(np.uint32))
+            out["channel"].append(np.tile(ch, R).astype(np.uint32))
+            out["seq_posted"].append(seqp.reshape(-1).astype(np.uint64))
+            out["chunks_sent"].append(sent.reshape(-1).astype(np.uint32))
+            out["chunks_recv"].append(recv.reshape(-1).astype(np.uint32))
+    cols = {k: np.concatenate(v) for k, v in out.items()}
+    if shuffle:
+        perm = np.random.Generator(np.random.PCG64(seed + 17)).permutation(cols["snap"].shape[0])
+        cols = {k: v[perm] for k, v in cols.items()}
+    return HangTrace(spec, topo, cols, root_rank, root_comm)
+
+
+def config4(seed: int = 0, layout: Optional[Layout3D] = None, healthy: bool = False, **kw) -> HangSpec:
+    """4,096 ranks, {TP, PP, DP, world} x 16 channels x 64 snapshots (about 17M rows); one rank of
+    one DP ring stops at operation 12,345 from snapshot 20 on."""
+    lay = layout or Layout3D(tp=8, pp=8, dp=64, world=True)
+    return HangSpec(layout=lay, hang_snapshot=None if healthy else kw.pop("hang_snapshot", 20), seed=seed, **kw)
