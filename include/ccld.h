@@ -108,6 +108,8 @@ typedef struct {
   const uint64_t *seq_posted;        /* operation counter of the operation the counters describe  */
   const uint32_t *chunks_sent, *chunks_recv;
   int32_t on_device;
+  uint32_t n_snapshots;              /* snapshots are numbered 0 .. n_snapshots-1                   */
+  uint32_t n_channels;               /* channels are numbered 0 .. n_channels-1                     */
 } ccld_snapshots;
 
 /* ---- table layouts ------------------------------------------------------------------------- */
@@ -157,6 +159,26 @@ typedef struct {
   int32_t reserved;
 } ccld_window_result;
 
+/* hang location tables */
+/* roots, ordered by (rank, communicator) */
+enum { CCLD_HROOT_RANK, CCLD_HROOT_COMM, CCLD_HROOT_CLASS, CCLD_HROOT_NCOL };
+/* one row per member slot of every communicator, in the order of the topology's members[] */
+enum { CCLD_HPAIR_RANK, CCLD_HPAIR_COMM, CCLD_HPAIR_STALLED, CCLD_HPAIR_ENTERED, CCLD_HPAIR_SEQ, CCLD_HPAIR_SENT,
+       CCLD_HPAIR_RECV, CCLD_HPAIR_WAITS_ON, CCLD_HPAIR_HOPS, CCLD_HPAIR_ONSET, CCLD_HPAIR_NCOL };
+/* one row per communicator */
+enum { CCLD_HCOMM_COMM, CCLD_HCOMM_HUNG, CCLD_HCOMM_CLASS, CCLD_HCOMM_SEQ_MAX, CCLD_HCOMM_ROOT_BY_COUNT,
+       CCLD_HCOMM_NCAND, CCLD_HCOMM_NCOL };
+
+typedef struct {
+  uint64_t root_cap, pair_cap, comm_cap;   /* in: rows                                             */
+  int64_t *root;       /* device [CCLD_HROOT_NCOL][root_cap]                                        */
+  int64_t *pair;       /* device [CCLD_HPAIR_NCOL][pair_cap] or NULL                                */
+  int64_t *comm;       /* device [CCLD_HCOMM_NCOL][comm_cap] or NULL                                */
+  uint64_t n_root, n_pair, n_hung_comm;    /* out (host)                                           */
+  ccld_status status;  /* out (host)                                                                */
+  int32_t reserved;
+} ccld_hang_result;
+
 /* ---- entry points ---------------------------------------------------------------------------- */
 
 /* Fills *params with the defaults listed above. */
@@ -198,6 +220,24 @@ ccld_status ccld_reset_window(ccld_ctx *ctx);
  * tree.  now_ns is the analyzer's clock.  Per-rank blame of this window is kept for
  * ccld_rank_blame.  Returns out->status. */
 ccld_status ccld_analyze_window(ccld_ctx *ctx, int64_t now_ns, ccld_window_result *out);
+
+/* Locates the root of a hang from progress-counter snapshots (Section 4.2.2, hang decision tree;
+ * Section 4.1.2, SendCount / RecvCount; Section 4.2.1, ring vs tree comparison groups).  The n_rows
+ * rows must fill the grid snapshots x (communicator, member) x channels exactly once, in any order
+ * (otherwise CCLD_E_SNAPSHOT_GAP / CCLD_E_DUPLICATE_KEY; the grid must fit max_snapshot_rows).
+ * Per (rank, communicator): stalled iff every channel's (operation counter, sent, received) is the
+ * same at the last snapshot and stall_snapshots earlier; entered iff its operation counter equals
+ * the communicator's largest.  A communicator is hung iff a member is stalled and it is not idle
+ * (all entered with identical totals across the ring, or inside each layer of the tree).  Per hung
+ * communicator the paper's tree is applied: members that have not entered are the root
+ * (Not-Entered-Hang); else members that are not stalled (Inconsistent-Hang); else (Hardware-Fault)
+ * the ring's wait-for edges are walked (a rank that consumed all its predecessor sent waits on the
+ * predecessor, a rank whose successor holds fifo_depth unconsumed chunks waits on the successor)
+ * and the ranks that wait on nobody are the root, or in a tree the ranks furthest behind their
+ * layer; with no such rank, the rank with the fewest SendCount + RecvCount.  A not-entered rank
+ * that has entered another hung communicator is a victim and is dropped. */
+ccld_status ccld_locate_hang(ccld_ctx *ctx, const ccld_snapshots *snapshots, uint64_t n_rows,
+                             ccld_hang_result *out);
 
 /* Per-rank blame of the most recent ccld_analyze_window: blame = device [CCLD_BLM_NCOL][n_ranks]
  * (late-entry and late-exit counts, their summed lags, records seen); order = device [n_ranks]

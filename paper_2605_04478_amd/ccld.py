@@ -33,7 +33,7 @@ ALERT_COLS = ("comm", "seq", "age", "class", "n_cand", "cand_off")
 BLAME_COLS = ("n_late_enter", "n_late_exit", "sum_lag_enter", "sum_lag_exit", "n_records")
 HANG_ROOT_COLS = ("rank", "comm", "class")
 HANG_PAIR_COLS = ("rank", "comm", "stalled", "entered", "seq", "sent", "recv", "waits_on", "hops", "onset")
-HANG_COMM_COLS = ("comm", "hung", "class", "seq_max", "root_by_count", "n_candidates")
+HANG_COMM_COLS = ("comm", "hung", "class", "seq_max", "root_by_count", "n_cand")
 
 
 class Params(C.Structure):
@@ -58,7 +58,7 @@ class _Records(C.Structure):
 class _Snapshots(C.Structure):
     _fields_ = [("snap", C.c_void_p), ("rank", C.c_void_p), ("comm", C.c_void_p), ("channel", C.c_void_p),
                 ("seq_posted", C.c_void_p), ("chunks_sent", C.c_void_p), ("chunks_recv", C.c_void_p),
-                ("on_device", C.c_int32)]
+                ("on_device", C.c_int32), ("n_snapshots", C.c_uint32), ("n_channels", C.c_uint32)]
 
 
 class _WindowResult(C.Structure):
@@ -186,7 +186,7 @@ class HangResult:
     @property
     def pair(self): return _table(self.dev["pair"], HANG_PAIR_COLS, self.caps["pair"], self.n_pair)
     @property
-    def comm(self): return _table(self.dev["comm"], HANG_COMM_COLS, self.caps["comm"], self.n_hung_comm)
+    def comm(self): return _table(self.dev["comm"], HANG_COMM_COLS, self.caps["comm"], self.caps["comm"])
 
 
 class Analyzer:
@@ -342,8 +342,8 @@ class Analyzer:
                 "chunks_sent": np.int32, "chunks_recv": np.int32}
         return {k: t.from_numpy(np.ascontiguousarray(cols[k]).view(sign[k])).to(self.device) for k in sign}
 
-    def locate_hang(self, cols, root_cap: int = 4096, pair_cap: Optional[int] = None,
-                    comm_cap: Optional[int] = None) -> HangResult:
+    def locate_hang(self, cols, n_snapshots: int, n_channels: int, root_cap: int = 4096,
+                    pair_cap: Optional[int] = None, comm_cap: Optional[int] = None) -> HangResult:
         t = self.torch
         first = cols["snap"]
         on_device = not isinstance(first, np.ndarray)
@@ -356,7 +356,8 @@ class Analyzer:
             keep = {k: np.ascontiguousarray(cols[k], dtype=dt[k]) for k in dt}
             ptr = lambda k: keep[k].ctypes.data_as(C.c_void_p)
         sn = _Snapshots(ptr("snap"), ptr("rank"), ptr("comm"), ptr("channel"), ptr("seq_posted"),
-                        ptr("chunks_sent"), ptr("chunks_recv"), 1 if on_device else 0)
+                        ptr("chunks_sent"), ptr("chunks_recv"), 1 if on_device else 0, int(n_snapshots),
+                        int(n_channels))
         caps = {"root": int(root_cap), "pair": int(pair_cap or int(self._size.sum())),
                 "comm": int(comm_cap or self.n_comms)}
         i64 = dict(dtype=t.int64, device=self.device)

@@ -35,6 +35,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->topo.member_off = w.take<uint32_t>(n_comms);
   c->topo.members = w.take<uint32_t>(n_members);
   c->topo.members_sorted = w.take<uint32_t>(n_members);
+  c->topo.sorted_slot = w.take<uint32_t>(n_members);
   c->topo.tree_parent = w.take<int32_t>(n_members);
   c->topo.rank_comm_off = w.take<uint32_t>((uint64_t)n_ranks + 1);
   c->topo.rank_comms = w.take<uint32_t>(n_members);
@@ -51,7 +52,8 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->table2 = w.take<uint32_t>(tw);
   c->totals2 = w.take<uint32_t>(SORT_RADIX);
   // analysis scratch
-  const uint64_t seg_tiles = (N + SEG_TILE - 1) / SEG_TILE, sel_tiles = (N + SEL_TILE - 1) / SEL_TILE;
+  const uint64_t NT = std::max<uint64_t>(N, std::max<uint64_t>(n_members, n_comms));   // the tile-count scratch also serves the hang pass
+  const uint64_t seg_tiles = (NT + SEG_TILE - 1) / SEG_TILE, sel_tiles = (NT + SEL_TILE - 1) / SEL_TILE;
   c->tile_heads = w.take<uint32_t>(seg_tiles + 2);
   c->tile_flags = w.take<uint32_t>(sel_tiles + 2);
   c->rec_flag = w.take<uint8_t>(N);
@@ -63,11 +65,23 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->blame = w.take<int64_t>((uint64_t)CCLD_BLM_NCOL * n_ranks);
   c->usable_list = w.take<uint32_t>(N);
   c->group_first = w.take<uint32_t>(N + 1);
-  c->alert_list = w.take<uint32_t>(N);
+  c->alert_list = w.take<uint32_t>(NT);
   c->alert_ncand = w.take<uint32_t>(N + 2);
   c->gstate = w.take<GroupState>((uint64_t)n_comms * GROUP_SLOTS);
   c->counters = w.take<uint64_t>(CNT_COUNT);
   c->stage = w.take<uint8_t>(B * 48);
+  // hang location
+  const uint64_t SN = std::max<uint64_t>(c->snap_cap, 1);
+  c->n_members = n_members;
+  c->h_cell = w.take<uint64_t>(2 * SN);
+  c->h_cnt = w.take<uint32_t>(SN);
+  c->h_pair = w.take<int64_t>((uint64_t)CCLD_HPAIR_NCOL * n_members);
+  c->h_comm = w.take<int64_t>((uint64_t)CCLD_HCOMM_NCOL * n_comms);
+  c->h_wait_slot = w.take<int32_t>(n_members);
+  c->h_cand = w.take<uint8_t>(n_members);
+  c->h_layer_max = w.take<uint64_t>(n_members);
+  c->h_root_list = w.take<uint32_t>(n_members + 1);
+  c->h_stage = w.take<uint8_t>(SN * 32);
 }
 
 ccld_status check_params(const ccld_params* p) {
@@ -102,7 +116,12 @@ ccld_status check_topology(const ccld_topology* t, uint64_t* n_members) {
         if (par < 0) ++roots;
         else if ((uint32_t)par >= q) return CCLD_E_BAD_TOPOLOGY;   // BFS order: parents come first
       }
-      if (roots != 1) return CCLD_E_BAD_TOPOLOGY;
+      if (roots != 1 || t->tree_parent[t->member_off[c]] >= 0) return CCLD_E_BAD_TOPOLOGY;
+      std::vector<uint32_t> depth(t->size[c], 0);                  // BFS order: layers are contiguous
+      for (uint32_t q = 1; q < t->size[c]; ++q) {
+        depth[q] = depth[t->tree_parent[t->member_off[c] + q]] + 1;
+        if (depth[q] < depth[q - 1]) return CCLD_E_BAD_TOPOLOGY;
+      }
     }
   }
   *n_members = total;
@@ -190,11 +209,20 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   c->h_pinned = nullptr;
 
   // derived host tables: sorted member lists, rank -> communicators CSR
-  std::vector<uint32_t> sorted(topo->members, topo->members + n_members);
+  std::vector<uint32_t> sorted(topo->members, topo->members + n_members), sslot(n_members);
   std::vector<uint32_t> rc_off((size_t)topo->n_ranks + 1, 0), rc(n_members);
   std::vector<int32_t> parent(n_members, -1);
   for (uint32_t k = 0; k < topo->n_comms; ++k) {
-    std::sort(sorted.begin() + topo->member_off[k], sorted.begin() + topo->member_off[k] + topo->size[k]);
+    {
+      std::vector<uint32_t> ord(topo->size[k]);
+      for (uint32_t q = 0; q < topo->size[k]; ++q) ord[q] = q;
+      const uint32_t* mem = topo->members + topo->member_off[k];
+      std::sort(ord.begin(), ord.end(), [mem](uint32_t a, uint32_t b) { return mem[a] < mem[b]; });
+      for (uint32_t q = 0; q < topo->size[k]; ++q) {
+        sorted[topo->member_off[k] + q] = mem[ord[q]];
+        sslot[topo->member_off[k] + q] = ord[q];
+      }
+    }
     for (uint32_t q = 0; q < topo->size[k]; ++q) rc_off[topo->members[topo->member_off[k] + q] + 1] += 1;
   }
   for (uint32_t r = 0; r < topo->n_ranks; ++r) rc_off[r + 1] += rc_off[r];
@@ -215,6 +243,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   up(c->topo.member_off, topo->member_off, 4ull * topo->n_comms);
   up(c->topo.members, topo->members, 4ull * n_members);
   up(c->topo.members_sorted, sorted.data(), 4ull * n_members);
+  up(c->topo.sorted_slot, sslot.data(), 4ull * n_members);
   up(c->topo.tree_parent, parent.data(), 4ull * n_members);
   up(c->topo.rank_comm_off, rc_off.data(), 4ull * rc_off.size());
   up(c->topo.rank_comms, rc.data(), 4ull * n_members);

@@ -37,6 +37,7 @@ struct DeviceTopology {
   const uint32_t* member_off;
   const uint32_t* members;
   const uint32_t* members_sorted;   // each communicator's members in ascending rank order
+  const uint32_t* sorted_slot;      // slot (position in members[]) of each entry of members_sorted
   const int32_t* tree_parent;
   const uint32_t* rank_comm_off;    // [n_ranks + 1] CSR: communicators each rank belongs to
   const uint32_t* rank_comms;
@@ -110,6 +111,17 @@ struct ccld_ctx {
   uint64_t* h_pinned;                 // pinned host staging
   // staging for host-resident batches
   uint8_t* stage;                     // [batch_cap * 41] device
+  // hang location
+  uint64_t n_members;                 // member slots over all communicators
+  uint64_t* h_cell;                   // [snap_cap][2]  (operation counter, sent | recv << 32)
+  uint32_t* h_cnt;                    // [snap_cap] rows seen per cell
+  int64_t* h_pair;                    // [CCLD_HPAIR_NCOL][n_members]
+  int64_t* h_comm;                    // [CCLD_HCOMM_NCOL][n_comms]
+  int32_t* h_wait_slot;               // [n_members] slot waited on, -1 = none
+  uint8_t* h_cand;                    // [n_members]
+  uint64_t* h_layer_max;              // [n_members]
+  uint32_t* h_root_list;              // [n_members]
+  uint8_t* h_stage;                   // [snap_cap * 32] device staging for host-resident snapshots
   // last analysis
   int sorted_buf;                     // which ping-pong buffer holds the sorted window
   uint64_t last_n;

@@ -1,0 +1,404 @@
+// Hang location from progress-counter snapshots for gfx950: rows are placed into a dense grid
+// [member slot][channel][snapshot], one wavefront per (rank, communicator) scans its channels'
+// time series, one workgroup per communicator applies the hang decision tree and builds the
+// ring / tree wait-for edges, victims are filtered across communicators, and the edges are
+// walked to the roots.
+#include <algorithm>
+#include <cstring>
+
+#include "ccld_internal.h"
+#include "device_utils.h"
+#include "select.h"
+#include "window_kernels.h"
+
+using namespace ccld;
+
+namespace ccld {
+
+struct HangArgs {
+  // rows
+  const u32 *snap, *rank, *comm, *channel;
+  const u64* seq_posted;
+  const u32 *sent, *recv;
+  u64 n_rows;
+  u32 n_snap, n_ch;
+  DeviceTopology T;
+  u64 n_members;
+  // grid
+  u64* cell;          // [n_members * n_ch * n_snap][2]
+  u32* cnt;
+  // tables
+  i64* pair;          // [CCLD_HPAIR_NCOL][n_members]
+  i64* hcomm;         // [CCLD_HCOMM_NCOL][n_comms]
+  int* wait_slot;
+  uint8_t* cand;
+  u64* layer_max;
+  u64* counters;
+  u32 stall_snapshots, fifo_depth;
+};
+
+#define PAIR(a, col, p) (a.pair[(u64)(col) * a.n_members + (p)])
+#define HCOMM(a, col, c) (a.hcomm[(u64)(col) * a.T.n_comms + (c)])
+
+// slot of rank r inside communicator c, or -1
+__device__ __forceinline__ int slot_of(const DeviceTopology& T, u32 c, u32 r) {
+  const u32 off = T.member_off[c], n = T.size[c];
+  u32 lo = 0, hi = n;
+  while (lo < hi) { const u32 m = (lo + hi) / 2; if (T.members_sorted[off + m] < r) lo = m + 1; else hi = m; }
+  if (lo < n && T.members_sorted[off + lo] == r) return (int)T.sorted_slot[off + lo];
+  return -1;
+}
+
+// ---- place every row in its cell ------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_hang_place(HangArgs a) {
+  u64 status = 0;
+  for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < a.n_rows; i += (u64)gridDim.x * 256) {
+    const u32 c = a.comm[i], r = a.rank[i], ch = a.channel[i], s = a.snap[i];
+    if (c >= a.T.n_comms) { status |= DS_UNKNOWN_COMM; continue; }
+    const int slot = r < a.T.n_ranks ? slot_of(a.T, c, r) : -1;
+    if (slot < 0) { status |= DS_NOT_MEMBER; continue; }
+    if (ch >= a.n_ch || s >= a.n_snap) { status |= DS_RANGE; continue; }
+    const u64 k = (((u64)a.T.member_off[c] + (u32)slot) * a.n_ch + ch) * a.n_snap + s;
+    a.cell[2 * k] = a.seq_posted[i];
+    a.cell[2 * k + 1] = (u64)a.sent[i] | ((u64)a.recv[i] << 32);
+    atomicAdd(&a.cnt[k], 1u);
+  }
+  u64 st = status;
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) st |= shfl_xor_u64(st, m);
+  if (lane_id() == 0 && st) atomicOr((unsigned long long*)&a.counters[CNT_STATUS], (unsigned long long)st);
+}
+
+// ---- per (rank, communicator): stalled, operation counter, chunk totals, onset -------------------
+// One wavefront per member slot; lanes read consecutive snapshots of one channel.
+__global__ __launch_bounds__(256) void k_hang_pairs(HangArgs a) {
+  const u32 lane = lane_id();
+  const u64 p = (u64)blockIdx.x * 4 + threadIdx.x / CCLD_WAVE;
+  if (p >= a.n_members) return;
+  const u32 L = a.n_snap - 1, W = a.stall_snapshots;
+  const bool can_stall = L >= W;
+  bool stalled = can_stall;
+  u64 seq = 0, S = 0, R = 0;
+  u32 onset = 0;
+  u64 status = 0;
+  for (u32 ch = 0; ch < a.n_ch; ++ch) {
+    const u64 base = (p * a.n_ch + ch) * a.n_snap;
+    const u64 sL0 = a.cell[2 * (base + L)], sL1 = a.cell[2 * (base + L) + 1];
+    if (can_stall) {
+      const u64 o0 = a.cell[2 * (base + L - W)], o1 = a.cell[2 * (base + L - W) + 1];
+      if (o0 != sL0 || o1 != sL1) stalled = false;
+    }
+    u32 last_diff = 0;        // 1 + the last snapshot whose state differs from the final one
+    for (u32 s0 = 0; s0 < a.n_snap; s0 += CCLD_WAVE) {
+      const u32 s = s0 + lane;
+      bool diff = false;
+      if (s < a.n_snap) {
+        diff = a.cell[2 * (base + s)] != sL0 || a.cell[2 * (base + s) + 1] != sL1;
+        const u32 seen = a.cnt[base + s];
+        if (seen == 0) status |= DS_SNAPSHOT_GAP;
+        if (seen > 1) status |= DS_DUPLICATE;
+      }
+      const u64 m = ballot64(diff);
+      if (m) last_diff = s0 + (64 - (u32)__clzll((long long)m));
+    }
+    onset = last_diff > onset ? last_diff : onset;
+    seq = sL0 > seq ? sL0 : seq;
+    S += sL1 & 0xFFFFFFFFull;
+    R += sL1 >> 32;
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) status |= shfl_xor_u64(status, m);
+  if (lane == 0) {
+    if (status) atomicOr((unsigned long long*)&a.counters[CNT_STATUS], (unsigned long long)status);
+    // communicator of this slot: the last one whose offset is <= p
+    u32 lo = 0, hi = a.T.n_comms;
+    while (hi - lo > 1) { const u32 m = (lo + hi) / 2; if (a.T.member_off[m] <= p) lo = m; else hi = m; }
+    PAIR(a, CCLD_HPAIR_RANK, p) = a.T.members[p];
+    PAIR(a, CCLD_HPAIR_COMM, p) = lo;
+    PAIR(a, CCLD_HPAIR_STALLED, p) = stalled ? 1 : 0;
+    PAIR(a, CCLD_HPAIR_ENTERED, p) = 0;
+    PAIR(a, CCLD_HPAIR_SEQ, p) = (i64)seq;
+    PAIR(a, CCLD_HPAIR_SENT, p) = (i64)S;
+    PAIR(a, CCLD_HPAIR_RECV, p) = (i64)R;
+    PAIR(a, CCLD_HPAIR_WAITS_ON, p) = CCLD_NO_RANK;
+    PAIR(a, CCLD_HPAIR_HOPS, p) = -1;
+    PAIR(a, CCLD_HPAIR_ONSET, p) = onset;
+    a.wait_slot[p] = -1;
+    a.cand[p] = 0;
+    a.layer_max[p] = 0;
+  }
+}
+
+// ---- per communicator: entered, idle test, decision tree, wait-for edges ------------------------
+__global__ __launch_bounds__(256) void k_hang_comm(HangArgs a) {
+  __shared__ unsigned long long s_seqmax, s_minsum, s_minrecv, s_worst;
+  __shared__ u32 s_flags, s_best, s_ncand;      // flags: 1 not all entered, 2 any stalled, 4 not all stalled, 8 not idle
+  const u32 c = blockIdx.x, tid = threadIdx.x;
+  const u32 n = a.T.size[c], off = a.T.member_off[c];
+  const bool tree = a.T.algo[c] == CCLD_ALGO_TREE;
+  if (tid == 0) { s_seqmax = 0; s_minsum = ~0ull; s_minrecv = ~0ull; s_worst = 0; s_flags = 0; s_best = 0xFFFFFFFFu; s_ncand = 0; }
+  __syncthreads();
+  for (u32 q = tid; q < n; q += 256) atomicMax(&s_seqmax, (unsigned long long)PAIR(a, CCLD_HPAIR_SEQ, off + q));
+  __syncthreads();
+  const u64 seq_max = s_seqmax;
+  // depth of a slot in the tree (layers are contiguous in BFS order)
+  auto depth_of = [&](u32 q) -> u32 {
+    u32 d = 0;
+    if (tree) { int cur = (int)q; while (a.T.tree_parent[off + cur] >= 0) { cur = a.T.tree_parent[off + cur]; ++d; } }
+    return d;
+  };
+  for (u32 q = tid; q < n; q += 256) {
+    const u64 p = off + q;
+    const bool entered = (u64)PAIR(a, CCLD_HPAIR_SEQ, p) == seq_max;
+    PAIR(a, CCLD_HPAIR_ENTERED, p) = entered ? 1 : 0;
+    u32 f = 0;
+    if (!entered) f |= 1 | 8;
+    if (PAIR(a, CCLD_HPAIR_STALLED, p)) f |= 2; else f |= 4;
+    // identical totals across comparable ranks: every adjacent pair of the same layer
+    if (q > 0 && (!tree || depth_of(q) == depth_of(q - 1)) &&
+        (PAIR(a, CCLD_HPAIR_SENT, p) != PAIR(a, CCLD_HPAIR_SENT, p - 1) ||
+         PAIR(a, CCLD_HPAIR_RECV, p) != PAIR(a, CCLD_HPAIR_RECV, p - 1)))
+      f |= 8;
+    if (f) atomicOr(&s_flags, f);
+    atomicMin(&s_minsum, (unsigned long long)(PAIR(a, CCLD_HPAIR_SENT, p) + PAIR(a, CCLD_HPAIR_RECV, p)));
+    if (tree) atomicMax((unsigned long long*)&a.layer_max[off + depth_of(q)],
+                        (unsigned long long)(PAIR(a, CCLD_HPAIR_SENT, p) + PAIR(a, CCLD_HPAIR_RECV, p)));
+  }
+  __syncthreads();
+  // fewest SendCount + RecvCount, then fewest received, then smallest rank
+  for (u32 q = tid; q < n; q += 256)
+    if ((u64)(PAIR(a, CCLD_HPAIR_SENT, off + q) + PAIR(a, CCLD_HPAIR_RECV, off + q)) == s_minsum)
+      atomicMin(&s_minrecv, (unsigned long long)PAIR(a, CCLD_HPAIR_RECV, off + q));
+  __syncthreads();
+  for (u32 q = tid; q < n; q += 256)
+    if ((u64)(PAIR(a, CCLD_HPAIR_SENT, off + q) + PAIR(a, CCLD_HPAIR_RECV, off + q)) == s_minsum &&
+        (u64)PAIR(a, CCLD_HPAIR_RECV, off + q) == s_minrecv)
+      atomicMin(&s_best, (u32)PAIR(a, CCLD_HPAIR_RANK, off + q));
+  __syncthreads();
+  const u32 flags = s_flags;
+  const bool all_entered = !(flags & 1), any_stalled = flags & 2, all_stalled = !(flags & 4), idle_ok = !(flags & 8);
+  const bool hung = !idle_ok && any_stalled;
+  int cls = 0;
+  if (hung) cls = !all_entered ? CCLD_HANG_H1_NOT_ENTERED : (!all_stalled ? CCLD_HANG_H2_INCONSISTENT : CCLD_HANG_H3_HARDWARE);
+  if (tid == 0) {
+    HCOMM(a, CCLD_HCOMM_COMM, c) = c;
+    HCOMM(a, CCLD_HCOMM_HUNG, c) = hung ? 1 : 0;
+    HCOMM(a, CCLD_HCOMM_CLASS, c) = cls;
+    HCOMM(a, CCLD_HCOMM_SEQ_MAX, c) = (i64)seq_max;
+    HCOMM(a, CCLD_HCOMM_ROOT_BY_COUNT, c) = hung ? (i64)s_best : CCLD_NO_RANK;
+    HCOMM(a, CCLD_HCOMM_NCAND, c) = 0;
+  }
+  if (!hung) return;
+  if (cls == CCLD_HANG_H1_NOT_ENTERED) {
+    for (u32 q = tid; q < n; q += 256) if (!PAIR(a, CCLD_HPAIR_ENTERED, off + q)) a.cand[off + q] = 1;
+    return;
+  }
+  if (cls == CCLD_HANG_H2_INCONSISTENT) {
+    for (u32 q = tid; q < n; q += 256) if (!PAIR(a, CCLD_HPAIR_STALLED, off + q)) a.cand[off + q] = 1;
+    return;
+  }
+  // all entered, all hung
+  if (!tree) {
+    for (u32 q = tid; q < n; q += 256) {
+      const u32 pred = (q + n - 1) % n, succ = (q + 1) % n;
+      const i64 Rq = PAIR(a, CCLD_HPAIR_RECV, off + q), Sq = PAIR(a, CCLD_HPAIR_SENT, off + q);
+      if (n > 1 && Rq >= PAIR(a, CCLD_HPAIR_SENT, off + pred)) {
+        PAIR(a, CCLD_HPAIR_WAITS_ON, off + q) = PAIR(a, CCLD_HPAIR_RANK, off + pred);
+        a.wait_slot[off + q] = (int)pred;
+      } else if (n > 1 && Sq - PAIR(a, CCLD_HPAIR_RECV, off + succ) >= (i64)a.fifo_depth) {
+        PAIR(a, CCLD_HPAIR_WAITS_ON, off + q) = PAIR(a, CCLD_HPAIR_RANK, off + succ);
+        a.wait_slot[off + q] = (int)succ;
+      } else {
+        a.cand[off + q] = 1;
+        atomicAdd(&s_ncand, 1u);
+      }
+    }
+  } else {
+    for (u32 q = tid; q < n; q += 256) {
+      const u64 def = a.layer_max[off + depth_of(q)] - (u64)(PAIR(a, CCLD_HPAIR_SENT, off + q) + PAIR(a, CCLD_HPAIR_RECV, off + q));
+      atomicMax(&s_worst, (unsigned long long)def);
+    }
+    __syncthreads();
+    const u64 worst = s_worst;
+    if (worst > 0)
+      for (u32 q = tid; q < n; q += 256) {
+        const u64 def = a.layer_max[off + depth_of(q)] - (u64)(PAIR(a, CCLD_HPAIR_SENT, off + q) + PAIR(a, CCLD_HPAIR_RECV, off + q));
+        if (def == worst) { a.cand[off + q] = 1; atomicAdd(&s_ncand, 1u); }
+      }
+  }
+  __syncthreads();
+  if (s_ncand == 0)      // a pure cycle: the rank with the fewest counts
+    for (u32 q = tid; q < n; q += 256) if ((u32)PAIR(a, CCLD_HPAIR_RANK, off + q) == s_best) a.cand[off + q] = 1;
+}
+
+// ---- a not-entered rank that has entered another hung communicator is a victim --------------------
+__global__ __launch_bounds__(256) void k_hang_filter(HangArgs a) {
+  const u64 p = (u64)blockIdx.x * 256 + threadIdx.x;
+  if (p >= a.n_members || !a.cand[p]) return;
+  const u32 c = (u32)PAIR(a, CCLD_HPAIR_COMM, p), r = (u32)PAIR(a, CCLD_HPAIR_RANK, p);
+  if (HCOMM(a, CCLD_HCOMM_CLASS, c) != CCLD_HANG_H1_NOT_ENTERED) return;
+  for (u32 k = a.T.rank_comm_off[r]; k < a.T.rank_comm_off[r + 1]; ++k) {
+    const u32 c2 = a.T.rank_comms[k];
+    if (c2 == c || !HCOMM(a, CCLD_HCOMM_HUNG, c2)) continue;
+    const int q2 = slot_of(a.T, c2, r);
+    if (q2 >= 0 && PAIR(a, CCLD_HPAIR_ENTERED, (u64)a.T.member_off[c2] + q2)) { a.cand[p] = 2; return; }   // 2 = dropped
+  }
+}
+
+// ---- hops along the wait-for edges to a root; candidates per communicator ---------------------------
+__global__ __launch_bounds__(256) void k_hang_hops(HangArgs a) {
+  const u64 p = (u64)blockIdx.x * 256 + threadIdx.x;
+  if (p >= a.n_members) return;
+  const u32 c = (u32)PAIR(a, CCLD_HPAIR_COMM, p);
+  if (a.cand[p] == 1) atomicAdd((unsigned long long*)&HCOMM(a, CCLD_HCOMM_NCAND, c), 1ull);
+  if (!HCOMM(a, CCLD_HCOMM_HUNG, c)) return;
+  const u32 off = a.T.member_off[c], n = a.T.size[c];
+  u32 cur = (u32)(p - off);
+  i64 hops = 0;
+  while (true) {
+    if (a.cand[off + cur] == 1) break;
+    const int w = a.wait_slot[off + cur];
+    if (w < 0 || hops >= (i64)n) { hops = -1; break; }
+    cur = (u32)w;
+    ++hops;
+  }
+  PAIR(a, CCLD_HPAIR_HOPS, p) = hops;
+}
+
+struct PredRoot {
+  const uint8_t* cand;
+  __device__ bool operator()(u32 p) const { return cand[p] == 1; }
+};
+struct PredHung {
+  const i64* hung;
+  __device__ bool operator()(u32 c) const { return hung[c] != 0; }
+};
+
+__global__ __launch_bounds__(256) void k_hang_root_keys(HangArgs a, const u32* list, u32 n_root, int cb, u64* key) {
+  const u32 k = blockIdx.x * 256 + threadIdx.x;
+  if (k >= n_root) return;
+  const u32 p = list[k];
+  key[k] = ((u64)PAIR(a, CCLD_HPAIR_RANK, p) << cb) | (u64)PAIR(a, CCLD_HPAIR_COMM, p);
+}
+__global__ __launch_bounds__(256) void k_hang_root_emit(HangArgs a, const u32* list, const u32* sidx, u32 n_root,
+                                                        i64* root, u64 root_cap) {
+  const u32 k = blockIdx.x * 256 + threadIdx.x;
+  if (k >= n_root || k >= root_cap) return;
+  const u32 p = list[sidx[k]];
+  const u32 c = (u32)PAIR(a, CCLD_HPAIR_COMM, p);
+  root[CCLD_HROOT_RANK * root_cap + k] = PAIR(a, CCLD_HPAIR_RANK, p);
+  root[CCLD_HROOT_COMM * root_cap + k] = c;
+  root[CCLD_HROOT_CLASS * root_cap + k] = HCOMM(a, CCLD_HCOMM_CLASS, c);
+}
+
+// copy the first `rows` rows of every column of a column-major table into a table of another capacity
+__global__ __launch_bounds__(256) void k_copy_table(const i64* src, u64 src_cap, i64* dst, u64 dst_cap, u64 rows, int ncol) {
+  const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * (u64)ncol) return;
+  const u64 col = i / rows, r = i % rows;
+  dst[col * dst_cap + r] = src[col * src_cap + r];
+}
+
+}  // namespace ccld
+
+#define HIP_TRY(x) do { if ((x) != hipSuccess) { (void)hipGetLastError(); return CCLD_E_HIP; } } while (0)
+
+static ccld_status hang_status(uint64_t bits) {
+  if (bits & DS_UNKNOWN_COMM) return CCLD_E_UNKNOWN_COMM;
+  if (bits & DS_NOT_MEMBER) return CCLD_E_RANK_NOT_MEMBER;
+  if (bits & DS_RANGE) return CCLD_E_RANGE;
+  if (bits & DS_DUPLICATE) return CCLD_E_DUPLICATE_KEY;
+  if (bits & DS_SNAPSHOT_GAP) return CCLD_E_SNAPSHOT_GAP;
+  return CCLD_OK;
+}
+
+extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, ccld_hang_result* o) {
+  if (!c || !sn || !o) return CCLD_E_NULL;
+  o->n_root = o->n_pair = o->n_hung_comm = 0;
+  o->status = CCLD_OK;
+  if (!o->root && o->root_cap) return o->status = CCLD_E_NULL;
+  if (n_rows && (!sn->snap || !sn->rank || !sn->comm || !sn->channel || !sn->seq_posted || !sn->chunks_sent || !sn->chunks_recv))
+    return o->status = CCLD_E_NULL;
+  if (sn->n_snapshots == 0 || sn->n_channels == 0) return o->status = CCLD_E_BAD_ARG;
+  const uint64_t n_cell = c->n_members * sn->n_channels * sn->n_snapshots;
+  if (n_cell > c->snap_cap || n_rows > c->snap_cap) return o->status = CCLD_E_CAPACITY;
+  hipStream_t st = c->stream;
+
+  HangArgs a;
+  std::memset(&a, 0, sizeof(a));
+  if (sn->on_device) {
+    a.snap = sn->snap; a.rank = sn->rank; a.comm = sn->comm; a.channel = sn->channel;
+    a.seq_posted = sn->seq_posted; a.sent = sn->chunks_sent; a.recv = sn->chunks_recv;
+  } else if (n_rows) {
+    uint64_t* d_seq = (uint64_t*)c->h_stage;
+    uint32_t* d32 = (uint32_t*)(d_seq + n_rows);
+    const uint32_t* src[6] = {sn->snap, sn->rank, sn->comm, sn->channel, sn->chunks_sent, sn->chunks_recv};
+    HIP_TRY(hipMemcpyAsync(d_seq, sn->seq_posted, 8 * n_rows, hipMemcpyHostToDevice, st));
+    for (int i = 0; i < 6; ++i) HIP_TRY(hipMemcpyAsync(d32 + i * n_rows, src[i], 4 * n_rows, hipMemcpyHostToDevice, st));
+    a.seq_posted = d_seq; a.snap = d32; a.rank = d32 + n_rows; a.comm = d32 + 2 * n_rows; a.channel = d32 + 3 * n_rows;
+    a.sent = d32 + 4 * n_rows; a.recv = d32 + 5 * n_rows;
+  }
+  a.n_rows = n_rows; a.n_snap = sn->n_snapshots; a.n_ch = sn->n_channels; a.T = c->topo; a.n_members = c->n_members;
+  a.cell = c->h_cell; a.cnt = c->h_cnt; a.pair = c->h_pair; a.hcomm = c->h_comm; a.wait_slot = c->h_wait_slot;
+  a.cand = c->h_cand; a.layer_max = c->h_layer_max; a.counters = c->counters;
+  a.stall_snapshots = c->p.stall_snapshots; a.fifo_depth = c->p.fifo_depth;
+
+  c->prof.begin();
+  HIP_TRY(hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st));
+  HIP_TRY(hipMemsetAsync(c->h_cnt, 0, sizeof(uint32_t) * n_cell, st));
+  if (n_rows) {
+    uint64_t g = (n_rows + 255) / 256; if (g > 4096) g = 4096;
+    hipLaunchKernelGGL(k_hang_place, dim3((uint32_t)g), dim3(256), 0, st, a);
+  }
+  const uint32_t nm = (uint32_t)c->n_members;
+  hipLaunchKernelGGL(k_hang_pairs, dim3((nm + 3) / 4), dim3(256), 0, st, a);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (c->h_pinned[CNT_STATUS]) { c->prof.end(CCLD_PROF_HANG); c->prof.collect(); return o->status = hang_status(c->h_pinned[CNT_STATUS]); }
+
+  hipLaunchKernelGGL(k_hang_comm, dim3(c->topo.n_comms), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(k_hang_filter, dim3((nm + 255) / 256), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(k_hang_hops, dim3((nm + 255) / 256), dim3(256), 0, st, a);
+  // roots in (rank, communicator) order
+  PredRoot pr{c->h_cand};
+  run_select(st, pr, nm, c->tile_flags, c->h_root_list, &c->counters[CNT_NCAND]);
+  PredHung ph{c->h_comm + (uint64_t)CCLD_HCOMM_HUNG * c->topo.n_comms};
+  run_select(st, ph, c->topo.n_comms, c->tile_heads, c->alert_list, &c->counters[CNT_NALERT]);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  const uint32_t n_root = (uint32_t)c->h_pinned[CNT_NCAND];
+  o->n_root = n_root;
+  o->n_hung_comm = c->h_pinned[CNT_NALERT];
+  o->n_pair = c->n_members;
+  if (n_root && o->root_cap) {
+    SortBuffers sb2;
+    sb2.key[0] = c->sb.key[0]; sb2.idx[0] = c->sb.idx[0]; sb2.key[1] = c->sb.key[1]; sb2.idx[1] = c->sb.idx[1];
+    sb2.table = c->table2; sb2.totals = c->totals2;
+    if (n_root > c->cap) return o->status = CCLD_E_CAPACITY;
+    hipLaunchKernelGGL(k_hang_root_keys, dim3((n_root + 255) / 256), dim3(256), 0, st, a, (const u32*)c->h_root_list, n_root, c->kf.cb, c->keyC);
+    KeySource ks; ks.key = c->keyC; ks.head = 0; ks.cap = n_root; ks.squeeze = 0; ks.hi_shift = 0; ks.lo_bits = 0; ks.lo_mask = 0;
+    const int r = radix_sort_pairs(st, ks, n_root, sb2, c->kf.cb + c->kf.rb);
+    if (r < 0) return o->status = CCLD_E_HIP;
+    hipLaunchKernelGGL(k_hang_root_emit, dim3((n_root + 255) / 256), dim3(256), 0, st, a, (const u32*)c->h_root_list,
+                       (const u32*)sb2.idx[r], n_root, o->root, o->root_cap);
+  }
+  if (o->pair && o->pair_cap) {
+    const uint64_t rows = std::min<uint64_t>(o->pair_cap, c->n_members);
+    hipLaunchKernelGGL(k_copy_table, dim3((uint32_t)((rows * CCLD_HPAIR_NCOL + 255) / 256)), dim3(256), 0, st,
+                       (const i64*)c->h_pair, c->n_members, o->pair, o->pair_cap, rows, (int)CCLD_HPAIR_NCOL);
+  }
+  if (o->comm && o->comm_cap) {
+    const uint64_t rows = std::min<uint64_t>(o->comm_cap, c->topo.n_comms);
+    hipLaunchKernelGGL(k_copy_table, dim3((uint32_t)((rows * CCLD_HCOMM_NCOL + 255) / 256)), dim3(256), 0, st,
+                       (const i64*)c->h_comm, (uint64_t)c->topo.n_comms, o->comm, o->comm_cap, rows, (int)CCLD_HCOMM_NCOL);
+  }
+  c->prof.end(CCLD_PROF_HANG);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(st));
+  c->prof.collect();
+  if (o->n_root > o->root_cap || (o->pair && o->pair_cap < c->n_members) || (o->comm && o->comm_cap < c->topo.n_comms))
+    o->status = CCLD_W_TRUNCATED;
+  return o->status;
+}

@@ -585,6 +585,75 @@ def generate_hang(spec: HangSpec, shuffle: bool = True) -> HangTrace:
     return HangTrace(spec, topo, cols, root_rank, root_comm)
 
 
+def generate_slots(spec: TraceSpec, k0: int, k1: int) -> Trace:
+    """The records of collectives k0 .. k1-1 of every rank (one slice of the trace)."""
+    R = spec.layout.n_ranks
+    k1 = min(k1, spec.n_slots)
+    n = max(k1 - k0, 0) * R
+    out = {k: np.empty(n, dtype=_DTYPES[k]) for k in _DTYPES}
+    if n:
+        _gen_slots(spec, k0, k1, out)
+    return Trace(spec, spec.layout.topology(), {k: out[k] for k in COLUMNS}, out["inj_delay"], out["stretched"])
+
+
+@dataclass
+class StreamSpec:
+    """A trace delivered in one-second batches, with a slow rank that changes every
+    `epoch_steps` batches and (optionally) one rank that stops entering one DP communicator."""
+    layout: Layout3D
+    n_steps: int = 600
+    slots_per_step: int = 122                 # 1 s / 8.192 ms
+    slot_ns: int = 8_192_000
+    epoch_steps: int = 30
+    hang_step: Optional[int] = 300
+    seed: int = 0
+
+    def base(self) -> TraceSpec:
+        return TraceSpec(layout=self.layout, cycle=CYCLE_3D, n_slots=self.n_steps * self.slots_per_step,
+                         bytes_dist=("loguniform", 16.0, 25.0), sigma=0.2, skew_ns=100_000, slot_ns=self.slot_ns,
+                         seed=self.seed, name="config5")
+
+    def slow_rank(self, step: int) -> int:
+        return int(rand_u64(self.seed, _S_PICK + 5, step // self.epoch_steps) % np.uint64(self.layout.n_ranks))
+
+    def hang_site(self) -> Tuple[int, int, int]:
+        """(rank that stops entering, its DP communicator, first operation counter it misses)"""
+        r = int(rand_u64(self.seed, _S_PICK + 6, 0) % np.uint64(self.layout.n_ranks))
+        comm = int(self.layout.comm_of("dp", r))
+        first_slot = self.hang_step * self.slots_per_step
+        cyc = len(CYCLE_3D)
+        k = first_slot
+        while CYCLE_3D[k % cyc][0] != "dp":
+            k += 1
+        seq = (k // cyc) * 2 + (0 if k % cyc == 8 else 1)
+        return r, comm, seq
+
+    def now_ns(self, step: int) -> int:
+        return T_EPOCH_NS + (step + 1) * self.slots_per_step * self.slot_ns
+
+
+def stream_batch(ss: StreamSpec, step: int) -> Trace:
+    """Batch `step`: the collectives that start in second `step`.  From the hang on, the hung
+    communicator shows its peers in flight on the missed operation and nothing after it; every
+    other communicator carries on."""
+    spec = ss.base()
+    spec.slow_ranks = [SlowRank(ss.slow_rank(step), 1.0, ("exp", 1_000_000))]
+    tr = generate_slots(spec, step * ss.slots_per_step, (step + 1) * ss.slots_per_step)
+    if ss.hang_step is not None and step >= ss.hang_step:
+        r, comm, seq = ss.hang_site()
+        c = tr.cols
+        on = c["comm"] == comm
+        keep = ~(on & ((c["seq"] > seq) | ((c["seq"] == seq) & (c["rank"] == r))))
+        c["t_exit"][on & (c["seq"] == seq)] = INFLIGHT
+        tr = tr.take(np.nonzero(keep)[0])
+    return tr
+
+
+def config5(n_steps: int = 600, seed: int = 0, layout: Optional[Layout3D] = None, **kw) -> StreamSpec:
+    """16,384 ranks = TP8 x PP16 x DP128, about 2M records per one-second batch."""
+    return StreamSpec(layout=layout or Layout3D(tp=8, pp=16, dp=128), n_steps=n_steps, seed=seed, **kw)
+
+
 def config4(seed: int = 0, layout: Optional[Layout3D] = None, healthy: bool = False, **kw) -> HangSpec:
     """4,096 ranks, {TP, PP, DP, world} x 16 channels x 64 snapshots (about 17M rows); one rank of
     one DP ring stops at operation 12,345 from snapshot 20 on."""

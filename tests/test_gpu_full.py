@@ -1,0 +1,72 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times."""
+import numpy as np
+import pytest
+
+from oracle import ccld_oracle as orc
+from paper_2605_04478_amd import tracegen as tg
+from tests.test_gpu_window import compare
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(tr, seed):
+    import torch
+    from paper_2605_04478_amd import ccld
+    an = ccld.Analyzer(tr.topo, max_window_records=tr.n)
+    cols = an.to_device(tr.cols)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    perm = torch.randperm(tr.n, device="cuda", generator=g)
+    cols = {k: v[perm].contiguous() for k, v in cols.items()}
+    an.ingest(cols)
+    now = int(tr.cols["t_exit"].max()) + 1
+    res = an.analyze_window(now, n_records=tr.n, seg_cap=tr.n // 4 + 1024, flag_cap=tr.n // 8 + 1024)
+    blame, order = an.rank_blame()
+    return an, res, blame, order, now
+
+
+def test_config2_full_size():
+    spec = tg.config2()
+    tr = tg.generate(spec)
+    assert tr.n == 5_120_000
+    an, res, blame, order, now = _run(tr, 2)
+    ref = orc.Oracle(tr.topo).analyze_window(tr.cols, now)
+    compare(res, ref, blame, order, per_record=False, what="config2-full")
+    slow = sorted(s.rank for s in spec.slow_ranks)
+    link = sorted(spec.slow_groups[0].ranks)
+    assert sorted(np.nonzero(blame["n_late_enter"])[0].tolist()) == slow
+    assert sorted(np.nonzero(blame["n_late_exit"])[0].tolist()) == link
+    assert set(order[:5].tolist()) == set(slow + link)
+    an.close()
+
+
+def test_config3_full_size_82m_records():
+    spec = tg.config3()
+    tr = tg.generate(spec)
+    assert tr.n == 81_920_000 and tr.topo.n_comms == 1088
+    an, res, blame, order, now = _run(tr, 3)
+    assert res.status == "OK" and res.n_seg == 8_448_000
+    ref = orc.Oracle(tr.topo).analyze_window(tr.cols, now)
+    compare(res, ref, blame, order, per_record=False, what="config3-full")
+    slow = sorted(s.rank for s in spec.slow_ranks)
+    nic = sorted(x for g in spec.slow_groups for x in g.ranks)
+    assert set(order[:8].tolist()) == set(slow)                     # the 8 slow ranks lead the blame
+    assert set(np.nonzero(blame["n_late_exit"] >= 20)[0].tolist()) == set(nic)
+    an.close()
+
+
+def test_config4_full_size_hang_locate():
+    from paper_2605_04478_amd import ccld
+    ht = tg.generate_hang(tg.config4())
+    assert ht.n == 16_777_216
+    an = ccld.Analyzer(ht.topo, max_window_records=1024, max_snapshot_rows=ht.n)
+    g = an.locate_hang(an.snapshots_to_device(ht.cols), 64, 16)
+    assert g.status == "OK"
+    assert list(g.root["rank"]) == [ht.root_rank] and list(g.root["comm"]) == [ht.root_comm]
+    assert list(g.root["class"]) == [3]
+    o = orc.Oracle(ht.topo).locate_hang(ht.cols, 64, 16)
+    for name in ("root", "pair", "comm"):
+        gt, ot = getattr(g, name), getattr(o, name)
+        for k in ot:
+            assert np.array_equal(gt[k], ot[k]), (name, k)
+    an.close()
