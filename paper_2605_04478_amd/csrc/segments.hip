@@ -1,0 +1,396 @@
+// Per-collective statistics for gfx950.  Collectives of up to 64 records are packed side by side
+// into the lanes of a wavefront and sorted there with a bitonic network whose exchanges are DPP
+// row operations wherever the lane pattern allows, which yields minimum, exact lower median
+// (order statistic floor((n-1)/2)), maximum, and then the median absolute deviation; longer
+// collectives take a workgroup each.
+#include "window_kernels.h"
+#include "device_utils.h"
+
+#ifndef CCLD_USE_DPP
+#define CCLD_USE_DPP 1
+#endif
+
+namespace ccld {
+
+constexpr i64 T_INFLIGHT = INT64_MAX;
+constexpr int SEG_WAVE_MAX = 64;     // longest collective handled inside one wavefront
+
+__device__ __forceinline__ u64 atomic_add_u64(u64* p, u64 v) {
+  return atomicAdd((unsigned long long*)p, (unsigned long long)v);
+}
+
+__device__ __forceinline__ void seg_put(const SegArgs& a, int col, u32 srow, i64 v) {
+  if (srow < a.seg_cap) a.seg[(u64)col * a.seg_cap + srow] = v;
+}
+__device__ __forceinline__ i64 absdiff(i64 a, i64 b) { return a >= b ? a - b : b - a; }
+__device__ __forceinline__ bool is_late(i64 lag, i64 floor_ns, u32 knum, u32 kden, i64 mad) {
+  return lag > floor_ns && (i128)lag * (i128)kden > (i128)knum * (i128)mad;
+}
+__device__ __forceinline__ void seg_put_empty_stats(const SegArgs& a, u32 srow) {
+  for (int c = CCLD_SEG_ENTER_MIN; c <= CCLD_SEG_DUR_MAX; ++c) seg_put(a, c, srow, 0);
+  seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, CCLD_NO_RANK);
+  seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, CCLD_NO_RANK);
+}
+
+
+// ---- lane exchanges ------------------------------------------------------------------------
+// value held by lane (lane ^ M)
+template <int M>
+__device__ __forceinline__ u32 xor_lane_u32(u32 v) {
+#if CCLD_USE_DPP
+  const int s = (int)v;
+  if constexpr (M == 1) return (u32)__builtin_amdgcn_update_dpp(s, s, 0xB1, 0xF, 0xF, false);        // quad_perm [1,0,3,2]
+  else if constexpr (M == 2) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+  else if constexpr (M == 3) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x1B, 0xF, 0xF, false);   // quad_perm [3,2,1,0]
+  else if constexpr (M == 7) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x141, 0xF, 0xF, false);  // row_half_mirror
+  else if constexpr (M == 15) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x140, 0xF, 0xF, false); // row_mirror
+  else if constexpr (M == 8) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x128, 0xF, 0xF, false);  // row_ror:8
+  else if constexpr (M == 4) {
+    int t = __builtin_amdgcn_update_dpp(s, s, 0x104, 0xF, 0x5, false);    // banks 0,2 read lane + 4 (row_shl:4)
+    t = __builtin_amdgcn_update_dpp(t, s, 0x114, 0xF, 0xA, false);        // banks 1,3 read lane - 4 (row_shr:4)
+    return (u32)t;
+  } else
+#endif
+    return __shfl_xor(v, M, CCLD_WAVE);
+}
+template <int M>
+__device__ __forceinline__ i64 xor_lane_i64(i64 v) {
+  const u32 lo = xor_lane_u32<M>((u32)(u64)v), hi = xor_lane_u32<M>((u32)((u64)v >> 32));
+  return (i64)(((u64)hi << 32) | lo);
+}
+__device__ __forceinline__ i64 shfl_i64(i64 v, int src) { return (i64)shfl_u64((u64)v, src); }
+
+constexpr int high_bit(int m) { int b = 1; while (b * 2 <= m) b *= 2; return b; }
+
+// compare-exchange with lane ^ M: the lane whose top bit of M is clear keeps the smaller value
+template <int M>
+__device__ __forceinline__ i64 cmpx(i64 v, u32 lane) {
+  const i64 p = xor_lane_i64<M>(v);
+  const bool upper = (lane & high_bit(M)) != 0;
+  return ((p < v) != upper) ? p : v;
+}
+
+// ascending sort inside every aligned group of G lanes (bitonic merges: mirror, then halving strides)
+template <int G>
+__device__ __forceinline__ i64 sort_groups(i64 v, u32 lane) {
+  if constexpr (G >= 2) { v = cmpx<1>(v, lane); }
+  if constexpr (G >= 4) { v = cmpx<3>(v, lane); v = cmpx<1>(v, lane); }
+  if constexpr (G >= 8) { v = cmpx<7>(v, lane); v = cmpx<2>(v, lane); v = cmpx<1>(v, lane); }
+  if constexpr (G >= 16) { v = cmpx<15>(v, lane); v = cmpx<4>(v, lane); v = cmpx<2>(v, lane); v = cmpx<1>(v, lane); }
+  if constexpr (G >= 32) {
+    v = cmpx<31>(v, lane); v = cmpx<8>(v, lane); v = cmpx<4>(v, lane); v = cmpx<2>(v, lane); v = cmpx<1>(v, lane);
+  }
+  if constexpr (G >= 64) {
+    v = cmpx<63>(v, lane); v = cmpx<16>(v, lane); v = cmpx<8>(v, lane); v = cmpx<4>(v, lane);
+    v = cmpx<2>(v, lane); v = cmpx<1>(v, lane);
+  }
+  return v;
+}
+
+// all-reduce inside a group: smallest (d, r) / largest d with the smallest r among equals
+template <int G, bool MAXIMUM>
+__device__ __forceinline__ void reduce_dur(i64& d, u32& r) {
+#define CCLD_DUR_STEP(M)                                                        \
+  if constexpr (G > M) {                                                        \
+    const i64 od = xor_lane_i64<M>(d);                                          \
+    const u32 orr = xor_lane_u32<M>(r);                                         \
+    const bool better = MAXIMUM ? (od > d) : (od < d);                          \
+    if (better || (od == d && orr < r)) { d = od; r = orr; }                    \
+  }
+  CCLD_DUR_STEP(1) CCLD_DUR_STEP(2) CCLD_DUR_STEP(4) CCLD_DUR_STEP(8) CCLD_DUR_STEP(16) CCLD_DUR_STEP(32)
+#undef CCLD_DUR_STEP
+}
+template <int G>
+__device__ __forceinline__ i64 reduce_min(i64 v) {
+#define CCLD_MIN_STEP(M) if constexpr (G > M) { const i64 o = xor_lane_i64<M>(v); v = o < v ? o : v; }
+  CCLD_MIN_STEP(1) CCLD_MIN_STEP(2) CCLD_MIN_STEP(4) CCLD_MIN_STEP(8) CCLD_MIN_STEP(16) CCLD_MIN_STEP(32)
+#undef CCLD_MIN_STEP
+  return v;
+}
+
+// ---- collectives of up to 64 records, 64/G of them per wavefront pass --------------------------
+template <int G>
+__device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32 seg0, u32 nheads,
+                                                 const unsigned short* s_head, u32 lane, u32 wave) {
+  constexpr int SPW = CCLD_WAVE / G, NW = SEG_THREADS / CCLD_WAVE;
+  const int rb = a.sf.rb;
+  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  const u32 q = lane / G, l = lane % G, gbase = q * G;
+  const u64 gmask = (G == 64 ? ~0ull : (((u64)1 << (G & 63)) - 1)) << gbase;
+  for (u32 b = wave; b * SPW < nheads; b += NW) {
+    const u32 sl = b * SPW + q;
+    u32 a0 = 0, n = 0;
+    if (sl < nheads) { a0 = s_head[sl]; n = (u32)s_head[sl + 1] - a0; }
+    const bool small = n >= 1 && n <= (u32)SEG_WAVE_MAX;
+    const bool valid = small && l < n;
+    if (n > (u32)SEG_WAVE_MAX && l == 0) {            // too long for a wavefront: leave it to k_seg_big
+      const u64 slot = atomic_add_u64(&a.counters[CNT_NBIG], 1);
+      a.big_list[2 * slot] = seg0 + sl;
+      a.big_list[2 * slot + 1] = base + a0;
+    }
+    u64 key = 0, nb = 0;
+    i64 e = 0, x = T_INFLIGHT;
+    u32 op = 0, j = 0;
+    if (valid) {
+      j = base + a0 + l;
+      key = a.key[j];
+      const Row rw = a.row[a.idx[j]];
+      e = rw.t_enter; x = rw.t_exit; nb = rw.bytes; op = rw.op;
+    }
+    const bool done = valid && x != T_INFLIGHT;
+    const u64 m_infl = ballot64(valid && !done);
+    const u32 nd = (u32)__popcll(ballot64(done) & gmask);
+    const u32 ninfl = (u32)__popcll(m_infl & gmask);
+    const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
+    // arrival and completion: sorted inside the group, lane k of the group holds the k-th smallest
+    const i64 se = sort_groups<G>(done ? e : T_INFLIGHT, lane);
+    const i64 sx = sort_groups<G>(done ? x : T_INFLIGHT, lane);
+    const i64 med_e = shfl_i64(se, gbase + km), med_x = shfl_i64(sx, gbase + km);
+    const i64 min_e = shfl_i64(se, gbase), max_e = shfl_i64(se, gbase + kl);
+    const i64 min_x = shfl_i64(sx, gbase), max_x = shfl_i64(sx, gbase + kl);
+    const i64 sde = sort_groups<G>(done ? (e >= med_e ? e - med_e : med_e - e) : T_INFLIGHT, lane);
+    const i64 sdx = sort_groups<G>(done ? (x >= med_x ? x - med_x : med_x - x) : T_INFLIGHT, lane);
+    const i64 mad_e = shfl_i64(sde, gbase + km), mad_x = shfl_i64(sdx, gbase + km);
+    // T_min / T_max of the Duration Time with the ranks attaining them (ties: smallest rank)
+    const u32 rank = (u32)(key & rmask);
+    i64 dmin = done ? x - e : INT64_MAX, dmax = done ? x - e : INT64_MIN;
+    u32 rmin = done ? rank : 0xFFFFFFFFu, rmax = rmin;
+    reduce_dur<G, false>(dmin, rmin);
+    reduce_dur<G, true>(dmax, rmax);
+    // Operation Type Set must agree across the collective
+    const u64 hb = shfl_u64(nb, gbase);
+    const u32 hop = __shfl(op, gbase, CCLD_WAVE);
+    const bool incons = (ballot64(valid && (nb != hb || op != hop)) & gmask) != 0;
+    i64 imin = T_INFLIGHT;
+    if (m_infl) imin = reduce_min<G>((valid && !done) ? e : T_INFLIGHT);
+    const u32 comm = (u32)(key >> (rb + a.sf.ws));
+    bool usable = false;
+    if (valid) {
+      const bool complete = n == a.comm_size[comm] && ninfl == 0;
+      const bool barrier = op == CCLD_OP_ALLREDUCE && nb < (u64)a.barrier_bytes;
+      usable = complete && !incons && !barrier;
+      if (l == 0) {
+        const u32 srow = seg0 + sl;
+        seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
+        seg_put(a, CCLD_SEG_SEQ, srow, (i64)((key >> rb) & smask));
+        seg_put(a, CCLD_SEG_N, srow, (i64)n);
+        seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
+        seg_put(a, CCLD_SEG_STATE, srow,
+                (complete ? CCLD_SEG_COMPLETE : 0) | (!incons ? CCLD_SEG_CONSISTENT : 0) |
+                    (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+        seg_put(a, CCLD_SEG_OP, srow, (i64)op);
+        seg_put(a, CCLD_SEG_BYTES, srow, (i64)nb);
+        seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
+        seg_put(a, CCLD_SEG_FIRST, srow, (i64)j);
+        if (nd == 0) {
+          seg_put_empty_stats(a, srow);
+        } else {
+          seg_put(a, CCLD_SEG_ENTER_MIN, srow, min_e); seg_put(a, CCLD_SEG_ENTER_MED, srow, med_e);
+          seg_put(a, CCLD_SEG_ENTER_MAX, srow, max_e); seg_put(a, CCLD_SEG_ENTER_MAD, srow, mad_e);
+          seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
+          seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
+          seg_put(a, CCLD_SEG_DUR_MIN, srow, dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, dmax);
+          seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)rmax);
+        }
+      }
+      i64 le = 0, lx = 0;
+      u32 f = 0;
+      if (usable) {
+        le = e - med_e; lx = x - med_x;
+        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
+        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
+      }
+      a.rec_flag[j] = (uint8_t)f;
+      if (a.lag_e) a.lag_e[j] = le;
+      if (a.lag_x) a.lag_x[j] = lx;
+      if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
+    }
+  }
+}
+
+// One workgroup per tile of SEG_TILE sorted records: finds the collectives that start in the
+// tile, then its wavefronts take them 64/G at a time (G = the tile's widest short collective,
+// rounded up to a power of two).
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
+  constexpr int OWN = SEG_TILE / SEG_THREADS, NW = SEG_THREADS / CCLD_WAVE;
+  __shared__ unsigned short s_head[SEG_TILE + 2];
+  __shared__ u32 s_wave[NW];
+  __shared__ u32 s_halo_head, s_gmax;
+  const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE;
+  const u32 tile = blockIdx.x, base = tile * SEG_TILE;
+  const u32 rem = a.n - base;                                     // records from the tile's start to the end
+  const u32 own = rem < (u32)SEG_TILE ? rem : (u32)SEG_TILE;
+  const int rb = a.sf.rb;
+  if (tid == 0) { s_halo_head = rem <= (u32)(SEG_TILE + SEG_WAVE_MAX) ? rem : 0xFFFFu; s_gmax = 0; }
+  bool head[OWN];
+#pragma unroll
+  for (int r = 0; r < OWN; ++r) {
+    const u32 pos = r * SEG_THREADS + tid, j = base + pos;
+    head[r] = pos < own && (j == 0 || (a.key[j - 1] >> rb) != (a.key[j] >> rb));
+  }
+  __syncthreads();
+  u32 carry = 0;
+#pragma unroll
+  for (int r = 0; r < OWN; ++r) {
+    const u32 h = head[r] ? 1u : 0u;
+    u32 tot;
+    const u32 ex = block_exclusive_sum<SEG_THREADS>(h, s_wave, &tot);
+    if (h) s_head[carry + ex] = (unsigned short)(r * SEG_THREADS + tid);
+    carry += tot;
+  }
+  const u32 nheads = carry;
+  // where the tile's last collective ends: the first head within 64 records past the tile
+  if (tid <= (u32)SEG_WAVE_MAX) {
+    const u32 pos = SEG_TILE + tid;
+    if (pos < rem) {
+      const u32 j = base + pos;
+      if ((a.key[j - 1] >> rb) != (a.key[j] >> rb)) atomicMin(&s_halo_head, pos);
+    }
+  }
+  __syncthreads();
+  if (tid == 0) s_head[nheads] = (unsigned short)s_halo_head;
+  __syncthreads();
+  for (u32 s = tid; s < nheads; s += SEG_THREADS) {
+    const u32 n = (u32)s_head[s + 1] - (u32)s_head[s];
+    if (n <= (u32)SEG_WAVE_MAX) atomicMax(&s_gmax, n);
+  }
+  __syncthreads();
+  const u32 gmax = s_gmax, seg0 = a.tile_heads[tile];
+  if (gmax <= 2) seg_wave_batches<2>(a, base, seg0, nheads, s_head, lane, wave);
+  else if (gmax <= 4) seg_wave_batches<4>(a, base, seg0, nheads, s_head, lane, wave);
+  else if (gmax <= 8) seg_wave_batches<8>(a, base, seg0, nheads, s_head, lane, wave);
+  else if (gmax <= 16) seg_wave_batches<16>(a, base, seg0, nheads, s_head, lane, wave);
+  else if (gmax <= 32) seg_wave_batches<32>(a, base, seg0, nheads, s_head, lane, wave);
+  else seg_wave_batches<64>(a, base, seg0, nheads, s_head, lane, wave);
+}
+
+// Collectives too long for a tile plus halo: one workgroup per collective, values staged in
+// global scratch, the same counting selection with all reads broadcast across the workgroup.
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
+  __shared__ u32 s_end, s_ninfl, s_incons;
+  __shared__ unsigned long long s_imin;
+  __shared__ i64 s_stat[4];      // med_e, med_x, mad_e, mad_x
+  const u32 tid = threadIdx.x;
+  const int rb = a.sf.rb;
+  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  i64* big_e = a.big_ex;
+  i64* big_x = a.big_ex + a.cap_n;
+  const u32 nbig = (u32)a.counters[CNT_NBIG];
+  for (u32 ent = blockIdx.x; ent < nbig; ent += gridDim.x) {
+    const u32 srow = a.big_list[2 * ent], a0 = a.big_list[2 * ent + 1];
+    const u64 k0 = a.key[a0];
+    const u64 pref = k0 >> rb;
+    if (tid == 0) { s_end = a.n; s_ninfl = 0; s_incons = 0; s_imin = (unsigned long long)T_INFLIGHT; }
+    __syncthreads();
+    for (u64 j0 = (u64)a0 + 1;; j0 += SEG_THREADS) {
+      const u64 j = j0 + tid;
+      if (j < a.n && (a.key[j] >> rb) != pref) atomicMin(&s_end, (u32)j);
+      __syncthreads();
+      const bool stop = s_end != a.n || j0 + SEG_THREADS >= a.n;
+      __syncthreads();
+      if (stop) break;
+    }
+    const u32 b0 = s_end, nn = b0 - a0;
+    const Row h = a.row[a.idx[a0]];
+    {
+      u32 ni = 0; bool inc = false; i64 imin = T_INFLIGHT;
+      for (u32 j = a0 + tid; j < b0; j += SEG_THREADS) {
+        const Row rw = a.row[a.idx[j]];
+        big_e[j] = rw.t_enter; big_x[j] = rw.t_exit;
+        if (rw.t_exit == T_INFLIGHT) { ++ni; imin = rw.t_enter < imin ? rw.t_enter : imin; }
+        inc |= (rw.op != h.op || rw.bytes != h.bytes);
+      }
+      if (ni) { atomicAdd(&s_ninfl, ni); atomicMin(&s_imin, (unsigned long long)imin); }
+      if (inc) atomicOr(&s_incons, 1u);
+    }
+    __threadfence_block();
+    __syncthreads();
+    const u32 ninfl = s_ninfl, nd = nn - ninfl, km = nd ? (nd - 1) / 2 : 0;
+    if (tid == 0) {
+      seg_put(a, CCLD_SEG_COMM, srow, (i64)(k0 >> (rb + a.sf.ws)));
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> rb) & smask));
+      seg_put(a, CCLD_SEG_N, srow, (i64)nn);
+      seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
+      seg_put(a, CCLD_SEG_OP, srow, (i64)h.op);
+      seg_put(a, CCLD_SEG_BYTES, srow, (i64)h.bytes);
+      seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, (i64)s_imin);
+      seg_put(a, CCLD_SEG_FIRST, srow, (i64)a0);
+      if (nd == 0) seg_put_empty_stats(a, srow);
+    }
+    for (u32 i = a0 + tid; i < b0; i += SEG_THREADS) {
+      const i64 ei = big_e[i], xi = big_x[i];
+      if (xi == T_INFLIGHT) continue;
+      const i64 di = xi - ei;
+      u32 re = 0, rx = 0, cmin = 0, cmax = 0;
+      for (u32 j = a0; j < b0; ++j) {
+        const i64 ej = big_e[j], xj = big_x[j];
+        if (xj == T_INFLIGHT) continue;
+        const i64 dj = xj - ej;
+        const bool before = j < i;
+        re += (ej < ei) || (ej == ei && before);
+        rx += (xj < xi) || (xj == xi && before);
+        cmin += (dj < di) || (dj == di && before);
+        cmax += (dj > di) || (dj == di && before);
+      }
+      if (re == km) { s_stat[0] = ei; seg_put(a, CCLD_SEG_ENTER_MED, srow, ei); }
+      if (re == 0) seg_put(a, CCLD_SEG_ENTER_MIN, srow, ei);
+      if (re == nd - 1) seg_put(a, CCLD_SEG_ENTER_MAX, srow, ei);
+      if (rx == km) { s_stat[1] = xi; seg_put(a, CCLD_SEG_EXIT_MED, srow, xi); }
+      if (rx == 0) seg_put(a, CCLD_SEG_EXIT_MIN, srow, xi);
+      if (rx == nd - 1) seg_put(a, CCLD_SEG_EXIT_MAX, srow, xi);
+      const i64 rk = (i64)(a.key[i] & rmask);
+      if (cmin == 0) { seg_put(a, CCLD_SEG_DUR_MIN, srow, di); seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, rk); }
+      if (cmax == 0) { seg_put(a, CCLD_SEG_DUR_MAX, srow, di); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, rk); }
+    }
+    __syncthreads();
+    const i64 me = s_stat[0], mx = s_stat[1];
+    for (u32 i = a0 + tid; i < b0; i += SEG_THREADS) {
+      const i64 xi = big_x[i];
+      if (xi == T_INFLIGHT) continue;
+      const i64 dei = absdiff(big_e[i], me), dxi = absdiff(xi, mx);
+      u32 rde = 0, rdx = 0;
+      for (u32 j = a0; j < b0; ++j) {
+        const i64 xj = big_x[j];
+        if (xj == T_INFLIGHT) continue;
+        const i64 dej = absdiff(big_e[j], me), dxj = absdiff(xj, mx);
+        const bool before = j < i;
+        rde += (dej < dei) || (dej == dei && before);
+        rdx += (dxj < dxi) || (dxj == dxi && before);
+      }
+      if (rde == km) { s_stat[2] = dei; seg_put(a, CCLD_SEG_ENTER_MAD, srow, dei); }
+      if (rdx == km) { s_stat[3] = dxi; seg_put(a, CCLD_SEG_EXIT_MAD, srow, dxi); }
+    }
+    __syncthreads();
+    const u32 comm = (u32)(k0 >> (rb + a.sf.ws));
+    const bool complete = nn == a.comm_size[comm] && ninfl == 0;
+    const bool consistent = s_incons == 0;
+    const bool barrier = h.op == CCLD_OP_ALLREDUCE && h.bytes < (u64)a.barrier_bytes;
+    const bool usable = complete && consistent && !barrier;
+    if (tid == 0)
+      seg_put(a, CCLD_SEG_STATE, srow,
+              (complete ? CCLD_SEG_COMPLETE : 0) | (consistent ? CCLD_SEG_CONSISTENT : 0) |
+                  (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+    for (u32 i = a0 + tid; i < b0; i += SEG_THREADS) {
+      i64 le = 0, lx = 0;
+      u32 f = 0;
+      if (usable) {
+        le = big_e[i] - me; lx = big_x[i] - mx;
+        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, s_stat[2])) f |= CCLD_FLAG_LATE_ENTER;
+        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, s_stat[3])) f |= CCLD_FLAG_LATE_EXIT;
+      }
+      a.rec_flag[i] = (uint8_t)f;
+      if (a.lag_e) a.lag_e[i] = le;
+      if (a.lag_x) a.lag_x[i] = lx;
+      if (f) { a.flag_lag[i] = le; a.flag_lag[a.cap_n + i] = lx; }
+    }
+    __syncthreads();
+  }
+}
+
+void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
+  if (a.n == 0) return;
+  hipLaunchKernelGGL(k_seg_wave, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
+  hipLaunchKernelGGL(k_seg_big, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+}
+
+}  // namespace ccld

@@ -130,368 +130,6 @@ void launch_scan_tiles(hipStream_t st, uint32_t* counts, uint32_t n_tiles, uint6
 }
 
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ void seg_put(const SegArgs& a, int col, u32 srow, i64 v) {
-  if (srow < a.seg_cap) a.seg[(u64)col * a.seg_cap + srow] = v;
-}
-__device__ __forceinline__ i64 absdiff(i64 a, i64 b) { return a >= b ? a - b : b - a; }
-__device__ __forceinline__ bool is_late(i64 lag, i64 floor_ns, u32 knum, u32 kden, i64 mad) {
-  return lag > floor_ns && (i128)lag * (i128)kden > (i128)knum * (i128)mad;
-}
-__device__ __forceinline__ void seg_put_empty_stats(const SegArgs& a, u32 srow) {
-  for (int c = CCLD_SEG_ENTER_MIN; c <= CCLD_SEG_DUR_MAX; ++c) seg_put(a, c, srow, 0);
-  seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, CCLD_NO_RANK);
-  seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, CCLD_NO_RANK);
-}
-
-// Per-collective statistics for every collective whose first record lies in this workgroup's
-// tile of the sorted window.  The tile plus a halo is staged in LDS; each record's rank among
-// its collective's completed records is found by counting, which yields the exact lower
-// median (order statistic floor((n-1)/2)), the extremes, and then the MAD the same way.
-__global__ __launch_bounds__(SEG_THREADS) void k_seg_analyze(SegArgs a) {
-  constexpr int L = SEG_TILE + SEG_HALO, PER = L / SEG_THREADS, OWN = SEG_TILE / SEG_THREADS;
-  constexpr int MAXSEG = 256;
-  constexpr int NW = SEG_THREADS / CCLD_WAVE;
-  __shared__ i64 s_e[L], s_x[L];
-  __shared__ unsigned short s_sl[L];               // collective number inside the tile, 0xFFFF = not ours
-  __shared__ unsigned short s_head[SEG_TILE + 2];  // first position of each collective, then the end
-  __shared__ i64 s_med_e[MAXSEG], s_med_x[MAXSEG], s_mad_e[MAXSEG], s_mad_x[MAXSEG];
-  __shared__ u32 s_incons[MAXSEG];
-  __shared__ u64 s_bnd_bytes[PER][NW];
-  __shared__ u32 s_bnd_op[PER][NW];
-  __shared__ u32 s_wave[NW];
-  __shared__ u32 s_halo_head;
-
-  const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE;
-  const u32 tile = blockIdx.x, base = tile * SEG_TILE;
-  const u32 Lv = (a.n - base) < (u32)L ? (a.n - base) : (u32)L;
-  const bool more = (u64)base + L < a.n;
-  const int rb = a.sf.rb;
-  const u64 rmask = ((u64)1 << rb) - 1;
-  const u64 smask = ((u64)1 << a.sf.ws) - 1;
-
-  if (tid == 0) s_halo_head = Lv;
-
-  u64 kreg[PER], nb[PER];
-  i64 e[PER], x[PER];
-  u32 op[PER];
-  bool head[PER];
-#pragma unroll
-  for (int r = 0; r < PER; ++r) {
-    const u32 pos = r * SEG_THREADS + tid;
-    head[r] = false; kreg[r] = 0; nb[r] = 0; op[r] = 0; e[r] = 0; x[r] = 0;
-    if (pos < Lv) {
-      const u32 j = base + pos;
-      const u64 k = a.key[j];
-      const Row rw = a.row[a.idx[j]];
-      kreg[r] = k; e[r] = rw.t_enter; x[r] = rw.t_exit; nb[r] = rw.bytes; op[r] = rw.op;
-      head[r] = (j == 0) || ((a.key[j - 1] >> rb) != (k >> rb));
-      s_e[pos] = e[r]; s_x[pos] = x[r];
-    }
-  }
-  __syncthreads();
-
-  // number the collectives that start in the tile proper, in position order
-  u32 carry = 0, incl[PER];
-#pragma unroll
-  for (int r = 0; r < OWN; ++r) {
-    const u32 pos = r * SEG_THREADS + tid;
-    const u32 h = head[r] ? 1u : 0u;
-    u32 tot;
-    const u32 ex = block_exclusive_sum<SEG_THREADS>(h, s_wave, &tot);
-    if (h) s_head[carry + ex] = (unsigned short)pos;
-    incl[r] = carry + ex + h;
-    carry += tot;
-  }
-  const u32 nheads = carry;
-#pragma unroll
-  for (int r = OWN; r < PER; ++r) {
-    const u32 pos = r * SEG_THREADS + tid;
-    if (head[r]) atomicMin(&s_halo_head, pos);
-  }
-  // previous record's operation type, for the consistency test
-  u64 pbytes[PER];
-  u32 pop[PER];
-#pragma unroll
-  for (int r = 0; r < PER; ++r) {
-    pbytes[r] = shfl_up_u64(nb[r], 1);
-    pop[r] = __shfl_up(op[r], 1, CCLD_WAVE);
-    if (lane == CCLD_WAVE - 1) { s_bnd_bytes[r][wave] = nb[r]; s_bnd_op[r][wave] = op[r]; }
-  }
-  __syncthreads();
-  const u32 end_last = s_halo_head;     // first collective head in the halo, or the end of what was loaded
-  const bool last_big = nheads > 0 && end_last == Lv && more;   // the last collective runs past the halo
-  const u32 n_own = last_big ? nheads - 1 : nheads;
-  if (tid == 0) s_head[nheads] = (unsigned short)end_last;
-  bool mism[PER];
-#pragma unroll
-  for (int r = 0; r < PER; ++r) {
-    const u32 pos = r * SEG_THREADS + tid;
-    if (lane == 0) {
-      if (wave > 0) { pbytes[r] = s_bnd_bytes[r][wave - 1]; pop[r] = s_bnd_op[r][wave - 1]; }
-      else if (r > 0) { pbytes[r] = s_bnd_bytes[r - 1][NW - 1]; pop[r] = s_bnd_op[r - 1][NW - 1]; }
-    }
-    mism[r] = pos < Lv && pos > 0 && !head[r] && (nb[r] != pbytes[r] || op[r] != pop[r]);
-    if (pos < Lv) {
-      u32 sl;
-      if (r < OWN) sl = incl[r] == 0 ? 0xFFFFu : incl[r] - 1;
-      else sl = (nheads > 0 && pos < end_last) ? nheads - 1 : 0xFFFFu;
-      s_sl[pos] = (unsigned short)sl;
-    }
-  }
-  __syncthreads();
-  const u32 seg0 = a.tile_heads[tile];
-  if (last_big && tid == 0) {
-    const u64 slot = atomic_add_u64(&a.counters[CNT_NBIG], 1);
-    a.big_list[2 * slot] = seg0 + nheads - 1;
-    a.big_list[2 * slot + 1] = base + s_head[nheads - 1];
-  }
-
-  for (u32 sbase = 0; sbase < n_own; sbase += MAXSEG) {
-    s_incons[tid] = 0;
-    __syncthreads();
-    u32 ndone[PER], ninfl[PER];
-    // ---- ranks of arrival, completion and duration; minimum, median, maximum -------------
-#pragma unroll
-    for (int r = 0; r < PER; ++r) {
-      const u32 pos = r * SEG_THREADS + tid;
-      ndone[r] = 0; ninfl[r] = 0;
-      const u32 sl = pos < Lv ? s_sl[pos] : 0xFFFFu;
-      if (sl == 0xFFFFu || sl < sbase || sl >= sbase + MAXSEG || sl >= n_own) continue;
-      const u32 slot = sl - sbase, srow = seg0 + sl;
-      if (mism[r]) atomicOr(&s_incons[slot], 1u);
-      const u32 a0 = s_head[sl], b0 = s_head[sl + 1];
-      const i64 ei = e[r], xi = x[r], di = xi - ei;
-      u32 re = 0, rx = 0, cmin = 0, cmax = 0, nd = 0, ni = 0;
-      i64 imin = T_INFLIGHT;
-      for (u32 j = a0; j < b0; ++j) {
-        const i64 ej = s_e[j], xj = s_x[j];
-        if (xj != T_INFLIGHT) {
-          const i64 dj = xj - ej;
-          const bool before = j < pos;
-          ++nd;
-          re += (ej < ei) || (ej == ei && before);
-          rx += (xj < xi) || (xj == xi && before);
-          cmin += (dj < di) || (dj == di && before);
-          cmax += (dj > di) || (dj == di && before);
-        } else {
-          ++ni;
-          imin = ej < imin ? ej : imin;
-        }
-      }
-      ndone[r] = nd; ninfl[r] = ni;
-      if (xi != T_INFLIGHT) {
-        const u32 km = (nd - 1) / 2;
-        if (re == km) { s_med_e[slot] = ei; seg_put(a, CCLD_SEG_ENTER_MED, srow, ei); }
-        if (re == 0) seg_put(a, CCLD_SEG_ENTER_MIN, srow, ei);
-        if (re == nd - 1) seg_put(a, CCLD_SEG_ENTER_MAX, srow, ei);
-        if (rx == km) { s_med_x[slot] = xi; seg_put(a, CCLD_SEG_EXIT_MED, srow, xi); }
-        if (rx == 0) seg_put(a, CCLD_SEG_EXIT_MIN, srow, xi);
-        if (rx == nd - 1) seg_put(a, CCLD_SEG_EXIT_MAX, srow, xi);
-        if (cmin == 0) { seg_put(a, CCLD_SEG_DUR_MIN, srow, di); seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)(kreg[r] & rmask)); }
-        if (cmax == 0) { seg_put(a, CCLD_SEG_DUR_MAX, srow, di); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)(kreg[r] & rmask)); }
-      }
-      if (pos == a0) {
-        seg_put(a, CCLD_SEG_COMM, srow, (i64)(kreg[r] >> (rb + a.sf.ws)));
-        seg_put(a, CCLD_SEG_SEQ, srow, (i64)((kreg[r] >> rb) & smask));
-        seg_put(a, CCLD_SEG_N, srow, (i64)(b0 - a0));
-        seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ni);
-        seg_put(a, CCLD_SEG_OP, srow, (i64)op[r]);
-        seg_put(a, CCLD_SEG_BYTES, srow, (i64)nb[r]);
-        seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
-        seg_put(a, CCLD_SEG_FIRST, srow, (i64)(base + pos));
-        if (nd == 0) seg_put_empty_stats(a, srow);
-      }
-    }
-    __syncthreads();
-    // ---- median absolute deviations ------------------------------------------------------
-#pragma unroll
-    for (int r = 0; r < PER; ++r) {
-      const u32 pos = r * SEG_THREADS + tid;
-      const u32 sl = pos < Lv ? s_sl[pos] : 0xFFFFu;
-      if (sl == 0xFFFFu || sl < sbase || sl >= sbase + MAXSEG || sl >= n_own) continue;
-      if (x[r] == T_INFLIGHT) continue;
-      const u32 slot = sl - sbase, srow = seg0 + sl;
-      const u32 a0 = s_head[sl], b0 = s_head[sl + 1];
-      const i64 me = s_med_e[slot], mx = s_med_x[slot];
-      const i64 dei = absdiff(e[r], me), dxi = absdiff(x[r], mx);
-      u32 rde = 0, rdx = 0;
-      for (u32 j = a0; j < b0; ++j) {
-        const i64 xj = s_x[j];
-        if (xj == T_INFLIGHT) continue;
-        const i64 dej = absdiff(s_e[j], me), dxj = absdiff(xj, mx);
-        const bool before = j < pos;
-        rde += (dej < dei) || (dej == dei && before);
-        rdx += (dxj < dxi) || (dxj == dxi && before);
-      }
-      const u32 km = (ndone[r] - 1) / 2;
-      if (rde == km) { s_mad_e[slot] = dei; seg_put(a, CCLD_SEG_ENTER_MAD, srow, dei); }
-      if (rdx == km) { s_mad_x[slot] = dxi; seg_put(a, CCLD_SEG_EXIT_MAD, srow, dxi); }
-    }
-    __syncthreads();
-    // ---- state of the collective, per-rank lag, late flags ----------------------------------
-#pragma unroll
-    for (int r = 0; r < PER; ++r) {
-      const u32 pos = r * SEG_THREADS + tid;
-      const u32 sl = pos < Lv ? s_sl[pos] : 0xFFFFu;
-      if (sl == 0xFFFFu || sl < sbase || sl >= sbase + MAXSEG || sl >= n_own) continue;
-      const u32 slot = sl - sbase, srow = seg0 + sl;
-      const u32 a0 = s_head[sl], b0 = s_head[sl + 1];
-      const u32 comm = (u32)(kreg[r] >> (rb + a.sf.ws));
-      const bool complete = (b0 - a0) == a.comm_size[comm] && ninfl[r] == 0;
-      const bool consistent = s_incons[slot] == 0;
-      const bool barrier = op[r] == CCLD_OP_ALLREDUCE && nb[r] < (u64)a.barrier_bytes;
-      const bool usable = complete && consistent && !barrier;
-      if (pos == a0)
-        seg_put(a, CCLD_SEG_STATE, srow,
-                (complete ? CCLD_SEG_COMPLETE : 0) | (consistent ? CCLD_SEG_CONSISTENT : 0) |
-                    (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
-      i64 le = 0, lx = 0;
-      u32 f = 0;
-      if (usable) {
-        le = e[r] - s_med_e[slot];
-        lx = x[r] - s_med_x[slot];
-        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, s_mad_e[slot])) f |= CCLD_FLAG_LATE_ENTER;
-        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, s_mad_x[slot])) f |= CCLD_FLAG_LATE_EXIT;
-      }
-      const u32 j = base + pos;
-      a.rec_flag[j] = (uint8_t)f;
-      if (a.lag_e) a.lag_e[j] = le;
-      if (a.lag_x) a.lag_x[j] = lx;
-      if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
-    }
-    __syncthreads();
-  }
-}
-
-// Collectives too long for a tile plus halo: one workgroup per collective, values staged in
-// global scratch, the same counting selection with all reads broadcast across the workgroup.
-__global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
-  __shared__ u32 s_end, s_ninfl, s_incons;
-  __shared__ unsigned long long s_imin;
-  __shared__ i64 s_stat[4];      // med_e, med_x, mad_e, mad_x
-  const u32 tid = threadIdx.x;
-  const int rb = a.sf.rb;
-  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
-  i64* big_e = a.big_ex;
-  i64* big_x = a.big_ex + a.cap_n;
-  const u32 nbig = (u32)a.counters[CNT_NBIG];
-  for (u32 ent = blockIdx.x; ent < nbig; ent += gridDim.x) {
-    const u32 srow = a.big_list[2 * ent], a0 = a.big_list[2 * ent + 1];
-    const u64 k0 = a.key[a0];
-    const u64 pref = k0 >> rb;
-    if (tid == 0) { s_end = a.n; s_ninfl = 0; s_incons = 0; s_imin = (unsigned long long)T_INFLIGHT; }
-    __syncthreads();
-    for (u64 j0 = (u64)a0 + 1;; j0 += SEG_THREADS) {
-      const u64 j = j0 + tid;
-      if (j < a.n && (a.key[j] >> rb) != pref) atomicMin(&s_end, (u32)j);
-      __syncthreads();
-      const bool stop = s_end != a.n || j0 + SEG_THREADS >= a.n;
-      __syncthreads();
-      if (stop) break;
-    }
-    const u32 b0 = s_end, nn = b0 - a0;
-    const Row h = a.row[a.idx[a0]];
-    {
-      u32 ni = 0; bool inc = false; i64 imin = T_INFLIGHT;
-      for (u32 j = a0 + tid; j < b0; j += SEG_THREADS) {
-        const Row rw = a.row[a.idx[j]];
-        big_e[j] = rw.t_enter; big_x[j] = rw.t_exit;
-        if (rw.t_exit == T_INFLIGHT) { ++ni; imin = rw.t_enter < imin ? rw.t_enter : imin; }
-        inc |= (rw.op != h.op || rw.bytes != h.bytes);
-      }
-      if (ni) { atomicAdd(&s_ninfl, ni); atomicMin(&s_imin, (unsigned long long)imin); }
-      if (inc) atomicOr(&s_incons, 1u);
-    }
-    __threadfence_block();
-    __syncthreads();
-    const u32 ninfl = s_ninfl, nd = nn - ninfl, km = nd ? (nd - 1) / 2 : 0;
-    if (tid == 0) {
-      seg_put(a, CCLD_SEG_COMM, srow, (i64)(k0 >> (rb + a.sf.ws)));
-      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> rb) & smask));
-      seg_put(a, CCLD_SEG_N, srow, (i64)nn);
-      seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
-      seg_put(a, CCLD_SEG_OP, srow, (i64)h.op);
-      seg_put(a, CCLD_SEG_BYTES, srow, (i64)h.bytes);
-      seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, (i64)s_imin);
-      seg_put(a, CCLD_SEG_FIRST, srow, (i64)a0);
-      if (nd == 0) seg_put_empty_stats(a, srow);
-    }
-    for (u32 i = a0 + tid; i < b0; i += SEG_THREADS) {
-      const i64 ei = big_e[i], xi = big_x[i];
-      if (xi == T_INFLIGHT) continue;
-      const i64 di = xi - ei;
-      u32 re = 0, rx = 0, cmin = 0, cmax = 0;
-      for (u32 j = a0; j < b0; ++j) {
-        const i64 ej = big_e[j], xj = big_x[j];
-        if (xj == T_INFLIGHT) continue;
-        const i64 dj = xj - ej;
-        const bool before = j < i;
-        re += (ej < ei) || (ej == ei && before);
-        rx += (xj < xi) || (xj == xi && before);
-        cmin += (dj < di) || (dj == di && before);
-        cmax += (dj > di) || (dj == di && before);
-      }
-      if (re == km) { s_stat[0] = ei; seg_put(a, CCLD_SEG_ENTER_MED, srow, ei); }
-      if (re == 0) seg_put(a, CCLD_SEG_ENTER_MIN, srow, ei);
-      if (re == nd - 1) seg_put(a, CCLD_SEG_ENTER_MAX, srow, ei);
-      if (rx == km) { s_stat[1] = xi; seg_put(a, CCLD_SEG_EXIT_MED, srow, xi); }
-      if (rx == 0) seg_put(a, CCLD_SEG_EXIT_MIN, srow, xi);
-      if (rx == nd - 1) seg_put(a, CCLD_SEG_EXIT_MAX, srow, xi);
-      const i64 rk = (i64)(a.key[i] & rmask);
-      if (cmin == 0) { seg_put(a, CCLD_SEG_DUR_MIN, srow, di); seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, rk); }
-      if (cmax == 0) { seg_put(a, CCLD_SEG_DUR_MAX, srow, di); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, rk); }
-    }
-    __syncthreads();
-    const i64 me = s_stat[0], mx = s_stat[1];
-    for (u32 i = a0 + tid; i < b0; i += SEG_THREADS) {
-      const i64 xi = big_x[i];
-      if (xi == T_INFLIGHT) continue;
-      const i64 dei = absdiff(big_e[i], me), dxi = absdiff(xi, mx);
-      u32 rde = 0, rdx = 0;
-      for (u32 j = a0; j < b0; ++j) {
-        const i64 xj = big_x[j];
-        if (xj == T_INFLIGHT) continue;
-        const i64 dej = absdiff(big_e[j], me), dxj = absdiff(xj, mx);
-        const bool before = j < i;
-        rde += (dej < dei) || (dej == dei && before);
-        rdx += (dxj < dxi) || (dxj == dxi && before);
-      }
-      if (rde == km) { s_stat[2] = dei; seg_put(a, CCLD_SEG_ENTER_MAD, srow, dei); }
-      if (rdx == km) { s_stat[3] = dxi; seg_put(a, CCLD_SEG_EXIT_MAD, srow, dxi); }
-    }
-    __syncthreads();
-    const u32 comm = (u32)(k0 >> (rb + a.sf.ws));
-    const bool complete = nn == a.comm_size[comm] && ninfl == 0;
-    const bool consistent = s_incons == 0;
-    const bool barrier = h.op == CCLD_OP_ALLREDUCE && h.bytes < (u64)a.barrier_bytes;
-    const bool usable = complete && consistent && !barrier;
-    if (tid == 0)
-      seg_put(a, CCLD_SEG_STATE, srow,
-              (complete ? CCLD_SEG_COMPLETE : 0) | (consistent ? CCLD_SEG_CONSISTENT : 0) |
-                  (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
-    for (u32 i = a0 + tid; i < b0; i += SEG_THREADS) {
-      i64 le = 0, lx = 0;
-      u32 f = 0;
-      if (usable) {
-        le = big_e[i] - me; lx = big_x[i] - mx;
-        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, s_stat[2])) f |= CCLD_FLAG_LATE_ENTER;
-        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, s_stat[3])) f |= CCLD_FLAG_LATE_EXIT;
-      }
-      a.rec_flag[i] = (uint8_t)f;
-      if (a.lag_e) a.lag_e[i] = le;
-      if (a.lag_x) a.lag_x[i] = lx;
-      if (f) { a.flag_lag[i] = le; a.flag_lag[a.cap_n + i] = lx; }
-    }
-    __syncthreads();
-  }
-}
-
-void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
-  if (a.n == 0) return;
-  hipLaunchKernelGGL(k_seg_analyze, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
-  hipLaunchKernelGGL(k_seg_big, dim3(128), dim3(SEG_THREADS), 0, st, a);
-}
-
 // ------------------------------------------------------------------------------------------
 // Ordered compaction of the flagged records into the flag list.
 __global__ __launch_bounds__(256) void k_flag_count(FlagArgs a) {
