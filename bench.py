@@ -103,11 +103,17 @@ def main() -> int:
     # Algorithmic HBM bytes per step of each kernel class (what the method has to move):
     #  ingest   reads the 41-byte SoA record, writes an 8-byte key and a 32-byte payload row
     #  hist     reads the 8-byte key once per pass
-    #  scatter  pass 1 reads the key and writes key + index (20 B); later passes move key + index (24 B)
+    #  scatter  pass 1 reads the key and writes key + index (20 B); later passes move key + index (24 B);
+    #           when key bits + index bits <= 64 the passes move one packed word (16 B) and the last
+    #           pass writes key + index (8 B in, 12 B out)
     #  segments reads key (twice: heads, then analysis) + index, gathers the 32-byte row, writes a
     #           21-column int64 row per collective and one flag byte per record
     n_seg = int(res.n_seg)
-    alg = {"ingest": n * 81.0, "sort_hist": n * 8.0 * passes, "sort_scatter": n * (20.0 + 24.0 * (passes - 1)),
+    bl = lambda v: int(v).bit_length()
+    key_bits = bl(tr.topo.n_comms - 1) + bl(spec.layout.n_ranks - 1) + bl(int(tr.cols["seq"].max()))
+    packed = passes >= 2 and key_bits + bl(n - 1) <= 64      # key and index travel as one 64-bit word
+    scatter_bytes = (16.0 * (passes - 1) + 20.0) if packed else (20.0 + 24.0 * (passes - 1))
+    alg = {"ingest": n * 81.0, "sort_hist": n * 8.0 * passes, "sort_scatter": n * scatter_bytes,
            "segments": n * (8.0 + 12.0 + 32.0 + 1.0) + n_seg * 21 * 8.0}
     kernels = {k: {"ms_per_step": round(v[0] / args.steps, 4), "launches_per_step": v[1] / args.steps}
                for k, v in prof.items() if v[1]}
@@ -147,7 +153,8 @@ def main() -> int:
                                f"{n} records, {'shuffled' if not args.no_shuffle else 'time-major'} order; "
                                "step = ingest + analyze_window + rank_blame",
                    "records": n, "collectives": int(res.n_seg), "flags": int(res.n_flag),
-                   "groups": int(res.n_group), "sort_passes": passes},
+                   "groups": int(res.n_group), "sort_passes": passes, "sort_key_bits": key_bits,
+                   "sort_packed_words": bool(packed)},
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "avg_launch_ms": d_avg_ms, "launches": d_cnt,

@@ -455,13 +455,12 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   const uint32_t n_usable = (uint32_t)c->h_pinned[CNT_NUSABLE];
   o->n_alert = c->h_pinned[CNT_NALERT];
   if (n_usable) {
-    if (cb + 10 + ws > 64) return o->status = CCLD_E_KEY_WIDTH;
     ga.gkey = c->keyC;            // blame's sort is done with C by stream order
     c->prof.begin();
     launch_group_keys(st, ga, n_usable);
     KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = n_usable; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0;
     // sort C -> buffers {other main, C}: the first pass reads C and writes buffer 0, so C is free again for pass 2
-    const int r3 = radix_sort_pairs(st, gs, n_usable, sb2, cb + 10 + ws);
+    const int r3 = radix_sort_pairs(st, gs, n_usable, sb2, cb + 10);
     if (r3 < 0) return o->status = CCLD_E_HIP;
     launch_group_heads(st, sb2.key[r3], n_usable, ws, c->tile_flags, c->group_first, c->counters);
     c->prof.end(CCLD_PROF_GROUPS);

@@ -65,7 +65,7 @@ constexpr int SEG_TILE = 1024;       // sorted records owned by one workgroup of
 constexpr int SEG_HALO = 256;        // records past the tile a workgroup may read to finish its last collective
 constexpr int SEG_THREADS = 256;
 constexpr int SEL_TILE = 2048;       // records per workgroup of the compaction kernels
-constexpr int RANKCOUNT_BLOCKS = 256;
+constexpr int RANKCOUNT_BLOCKS = 2048;
 
 // device counters written by kernels and read back by the host
 enum { CNT_NSEG, CNT_NFLAG, CNT_NBIG, CNT_NUSABLE, CNT_NGROUP, CNT_NALERT, CNT_NCAND, CNT_STATUS, CNT_COUNT = 16 };

@@ -4,14 +4,21 @@
 // every digit's row of tile counts, and a scatter that ranks the tile's keys with
 // wavefront ballots (stable), regroups them by digit in LDS and writes each digit's
 // run to its place with consecutive lanes on consecutive addresses.
+//
+// When the significant key bits and the index bits fit one 64-bit word together, the
+// passes move a single packed word (key << index_bits | index) instead of the pair and
+// only the last pass writes the pair out again.
 #include "radix_sort.h"
 #include "device_utils.h"
 #include "profiler.h"
 
 namespace ccld {
 
+enum SortIn { IN_SOURCE, IN_PAIR, IN_PACKED };
+enum SortOut { OUT_PAIR, OUT_PACKED };
+
 __device__ __forceinline__ u64 load_key(const KeySource& s, u32 j, u32* phys) {
-  u32 p = s.head + j;                       // head < cap and j < cap, no overflow below 2^32 (cap <= 2^31)
+  u32 p = s.head + j;                       // head < cap and j < cap <= 2^31: no wrap below 2^32
   if (p >= s.cap) p -= s.cap;
   *phys = p;
   u64 k = s.key[p];
@@ -43,36 +50,45 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, cons
 }
 
 // ---- exclusive scan of each digit's row of tile counts ------------------------------------
+// one workgroup per digit; every thread scans SCAN_PER consecutive tiles serially
+constexpr int SCAN_PER = 8;
 __global__ __launch_bounds__(SORT_THREADS) void k_radix_scan(u32* __restrict__ table, u32* __restrict__ totals,
                                                              u32 n_tiles) {
   __shared__ u32 s_wave[SORT_THREADS / CCLD_WAVE];
   u32* row = table + (u64)blockIdx.x * n_tiles;
   u32 carry = 0;
-  for (u32 base = 0; base < n_tiles; base += SORT_THREADS) {
-    u32 i = base + threadIdx.x;
-    u32 v = i < n_tiles ? row[i] : 0u, tot;
-    u32 ex = block_exclusive_sum<SORT_THREADS>(v, s_wave, &tot);
-    if (i < n_tiles) row[i] = carry + ex;
+  for (u32 base = 0; base < n_tiles; base += SORT_THREADS * SCAN_PER) {
+    const u32 i0 = base + threadIdx.x * SCAN_PER;
+    u32 v[SCAN_PER], sum = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_PER; ++k) { v[k] = (i0 + k) < n_tiles ? row[i0 + k] : 0u; sum += v[k]; }
+    u32 tot;
+    u32 ex = carry + block_exclusive_sum<SORT_THREADS>(sum, s_wave, &tot);
+#pragma unroll
+    for (int k = 0; k < SCAN_PER; ++k) { if ((i0 + k) < n_tiles) row[i0 + k] = ex; ex += v[k]; }
     carry += tot;
   }
   if (threadIdx.x == 0) totals[blockIdx.x] = carry;
 }
 
 // ---- rank, regroup in LDS, scatter --------------------------------------------------------------
-template <bool FIRST>
+// shift addresses the digit inside the word the kernel ranks: the key itself, or the packed word
+// (key << ibits | index) when either side is packed.
+template <int IN, int OUT>
 __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, const u64* __restrict__ key_in,
                                                                 const u32* __restrict__ idx_in,
                                                                 u64* __restrict__ key_out, u32* __restrict__ idx_out,
                                                                 const u32* __restrict__ table,
                                                                 const u32* __restrict__ totals, u32 n, u32 n_tiles,
-                                                                int shift, int nbits) {
+                                                                int shift, int nbits, int ibits) {
   constexpr int NW = SORT_THREADS / CCLD_WAVE;
+  constexpr bool PACKED = (IN == IN_PACKED) || (OUT == OUT_PACKED);   // one word per element inside the kernel
   __shared__ u32 s_cnt[NW][SORT_RADIX];   // per-wavefront digit counters, then each wavefront's base inside the digit
   __shared__ u32 s_dstart[SORT_RADIX];    // first tile-local position of each digit
   __shared__ u32 s_gbase[SORT_RADIX];     // global position of tile-local position 0 of each digit (minus dstart)
   __shared__ u32 s_wave[NW];
   __shared__ u64 s_key[SORT_TILE];
-  __shared__ u32 s_idx[SORT_TILE];
+  __shared__ u32 s_idx[PACKED ? 1 : SORT_TILE];
 
   const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE, tile = blockIdx.x;
   const u32 dmask = (1u << nbits) - 1u;
@@ -88,12 +104,19 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, c
 #pragma unroll
   for (int it = 0; it < SORT_ITEMS; ++it) {
     u32 e = wave * (CCLD_WAVE * SORT_ITEMS) + it * CCLD_WAVE + lane;
+    v[it] = 0;
     if (e < valid) {
-      if (FIRST) { k[it] = load_key(src, base + e, &v[it]); }
-      else { k[it] = key_in[base + e]; v[it] = idx_in[base + e]; }
+      if (IN == IN_SOURCE) {
+        k[it] = load_key(src, base + e, &v[it]);
+        if (PACKED) k[it] = (k[it] << ibits) | v[it];
+      } else if (IN == IN_PAIR) {
+        k[it] = key_in[base + e]; v[it] = idx_in[base + e];
+      } else {
+        k[it] = key_in[base + e];
+      }
       dig[it] = (u32)(k[it] >> shift) & dmask;
     } else {
-      k[it] = 0; v[it] = 0; dig[it] = dmask;   // padding sorts after every real key of the last digit
+      k[it] = 0; dig[it] = dmask;   // padding sorts after every real key of the last digit
     }
   }
   __syncthreads();
@@ -144,29 +167,49 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, c
     const u32 d = dig[it];
     const u32 pos = s_dstart[d] + s_cnt[wave][d] + pre[it];
     s_key[pos] = k[it];
-    s_idx[pos] = v[it];
+    if (!PACKED) s_idx[pos] = v[it];
   }
   __syncthreads();
 
+  const u64 imask = ibits >= 64 ? ~0ull : (((u64)1 << ibits) - 1);
 #pragma unroll
   for (int it = 0; it < SORT_ITEMS; ++it) {
     const u32 pos = it * SORT_THREADS + tid;
     if (pos < valid) {
       const u64 kk = s_key[pos];
       const u32 g = s_gbase[(u32)(kk >> shift) & dmask] + pos;
-      key_out[g] = kk;
-      idx_out[g] = s_idx[pos];
+      if (OUT == OUT_PACKED) {
+        key_out[g] = kk;
+      } else if (PACKED) {
+        key_out[g] = kk >> ibits;
+        idx_out[g] = (u32)(kk & imask);
+      } else {
+        key_out[g] = kk;
+        idx_out[g] = s_idx[pos];
+      }
     }
   }
 }
 
 static_assert(SORT_RADIX <= SORT_THREADS, "one thread per digit in the scatter prologue");
 
+template <int IN, int OUT>
+static void launch_scatter(hipStream_t stream, const KeySource& src, const u64* key_in, const u32* idx_in,
+                           u64* key_out, u32* idx_out, const SortBuffers& buf, u32 n, u32 n_tiles, int shift,
+                           int nbits, int ibits) {
+  hipLaunchKernelGGL((k_radix_scatter<IN, OUT>), dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src, key_in, idx_in,
+                     key_out, idx_out, (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, shift, nbits, ibits);
+}
+
+static int host_bits(uint64_t v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
+
 int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const SortBuffers& buf, int bits,
                      Profiler* prof, int cls_hist, int cls_scan, int cls_scatter) {
   if (n == 0) return 0;
   const u32 n_tiles = sort_tiles(n);
-  int passes = bits <= 0 ? 1 : (bits + SORT_RBITS - 1) / SORT_RBITS;
+  const int passes = bits <= 0 ? 1 : (bits + SORT_RBITS - 1) / SORT_RBITS;
+  const int ibits = host_bits(src.cap ? src.cap - 1 : 0);
+  const bool packed = passes >= 2 && bits + ibits <= 64;
   int done_bits = 0, cur = -1;
   for (int p = 0; p < passes; ++p) {
     // spread the bits evenly over the passes
@@ -174,25 +217,29 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const
     if (nb < 1) nb = 1;
     const u32 dmask = (1u << nb) - 1u;
     const int out = cur < 0 ? 0 : 1 - cur;
+    const bool first = p == 0, last = p == passes - 1;
+    // digit position inside the word each kernel looks at
+    const int hist_shift = done_bits + ((packed && !first) ? ibits : 0);
+    const int scat_shift = done_bits + (packed ? ibits : 0);
     if (prof) prof->begin();
-    if (p == 0) {
+    if (first)
       hipLaunchKernelGGL(k_radix_hist<true>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
-                         (const u64*)nullptr, buf.table, n, n_tiles, done_bits, dmask);
-    } else {
+                         (const u64*)nullptr, buf.table, n, n_tiles, hist_shift, dmask);
+    else
       hipLaunchKernelGGL(k_radix_hist<false>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
-                         (const u64*)buf.key[cur], buf.table, n, n_tiles, done_bits, dmask);
-    }
+                         (const u64*)buf.key[cur], buf.table, n, n_tiles, hist_shift, dmask);
     if (prof) { prof->end(cls_hist); prof->begin(); }
     hipLaunchKernelGGL(k_radix_scan, dim3(dmask + 1), dim3(SORT_THREADS), 0, stream, buf.table, buf.totals, n_tiles);
     if (prof) { prof->end(cls_scan); prof->begin(); }
-    if (p == 0) {
-      hipLaunchKernelGGL(k_radix_scatter<true>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
-                         (const u64*)nullptr, (const u32*)nullptr, buf.key[out], buf.idx[out],
-                         (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, done_bits, nb);
+    const u64* kin = first ? nullptr : buf.key[cur];
+    const u32* iin = first ? nullptr : buf.idx[cur];
+    if (!packed) {
+      if (first) launch_scatter<IN_SOURCE, OUT_PAIR>(stream, src, kin, iin, buf.key[out], buf.idx[out], buf, n, n_tiles, scat_shift, nb, ibits);
+      else launch_scatter<IN_PAIR, OUT_PAIR>(stream, src, kin, iin, buf.key[out], buf.idx[out], buf, n, n_tiles, scat_shift, nb, ibits);
     } else {
-      hipLaunchKernelGGL(k_radix_scatter<false>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
-                         (const u64*)buf.key[cur], (const u32*)buf.idx[cur], buf.key[out], buf.idx[out],
-                         (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, done_bits, nb);
+      if (first) launch_scatter<IN_SOURCE, OUT_PACKED>(stream, src, kin, iin, buf.key[out], buf.idx[out], buf, n, n_tiles, scat_shift, nb, ibits);
+      else if (!last) launch_scatter<IN_PACKED, OUT_PACKED>(stream, src, kin, iin, buf.key[out], buf.idx[out], buf, n, n_tiles, scat_shift, nb, ibits);
+      else launch_scatter<IN_PACKED, OUT_PAIR>(stream, src, kin, iin, buf.key[out], buf.idx[out], buf, n, n_tiles, scat_shift, nb, ibits);
     }
     if (prof) prof->end(cls_scatter);
     if (hipGetLastError() != hipSuccess) return -1;

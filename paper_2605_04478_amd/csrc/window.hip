@@ -227,14 +227,14 @@ void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag
                        uint64_t* out_key) {
   if (n_flag) hipLaunchKernelGGL(k_blame_keys, dim3((n_flag + 255) / 256), dim3(256), 0, st, key, flag_pos, n_flag, rb, out_key);
 }
+// one workgroup per rank: the rank's run in the sorted flag keys is summed by 256 threads
 __global__ __launch_bounds__(256) void k_blame_reduce(const u64* __restrict__ skey, const u32* __restrict__ sidx,
                                                       u32 n_flag, const u32* __restrict__ flag_pos,
                                                       const uint8_t* __restrict__ rec_flag,
                                                       const i64* __restrict__ flag_lag, u64 cap_n, u32 n_ranks,
                                                       i64* __restrict__ blame) {
-  const u32 r = blockIdx.x * 4 + threadIdx.x / CCLD_WAVE;
-  if (r >= n_ranks) return;
-  const u32 lane = lane_id();
+  __shared__ unsigned long long s_acc[4];
+  const u32 r = blockIdx.x, tid = threadIdx.x;
   // run of this rank in the sorted keys: [lower_bound(r), lower_bound(r + 1))
   u32 lo = 0, hi = n_flag;
   while (lo < hi) { const u32 m = (lo + hi) / 2; if (skey[m] < (u64)r) lo = m + 1; else hi = m; }
@@ -242,8 +242,14 @@ __global__ __launch_bounds__(256) void k_blame_reduce(const u64* __restrict__ sk
   hi = n_flag;
   while (lo < hi) { const u32 m = (lo + hi) / 2; if (skey[m] <= (u64)r) lo = m + 1; else hi = m; }
   const u32 last = lo;
+  if (first == last) {
+    if (tid < 4) blame[(u64)tid * n_ranks + r] = 0;     // columns 0..3 are the four flag sums
+    return;
+  }
+  if (tid < 4) s_acc[tid] = 0;
+  __syncthreads();
   u64 ne = 0, nx = 0, se = 0, sx = 0;
-  for (u32 q = first + lane; q < last; q += CCLD_WAVE) {
+  for (u32 q = first + tid; q < last; q += 256) {
     const u32 j = flag_pos[sidx[q]];
     const u32 f = rec_flag[j];
     if (f & CCLD_FLAG_LATE_ENTER) { ne += 1; se += (u64)flag_lag[j]; }
@@ -253,52 +259,48 @@ __global__ __launch_bounds__(256) void k_blame_reduce(const u64* __restrict__ sk
   for (int m = 32; m >= 1; m >>= 1) {
     ne += shfl_xor_u64(ne, m); nx += shfl_xor_u64(nx, m); se += shfl_xor_u64(se, m); sx += shfl_xor_u64(sx, m);
   }
-  if (lane == 0) {
-    blame[(u64)CCLD_BLM_N_LATE_ENTER * n_ranks + r] = (i64)ne;
-    blame[(u64)CCLD_BLM_N_LATE_EXIT * n_ranks + r] = (i64)nx;
-    blame[(u64)CCLD_BLM_SUM_LAG_ENTER * n_ranks + r] = (i64)se;
-    blame[(u64)CCLD_BLM_SUM_LAG_EXIT * n_ranks + r] = (i64)sx;
+  if (lane_id() == 0) {       // integer sums: the order of these LDS additions does not matter
+    atomicAdd(&s_acc[CCLD_BLM_N_LATE_ENTER], (unsigned long long)ne);
+    atomicAdd(&s_acc[CCLD_BLM_N_LATE_EXIT], (unsigned long long)nx);
+    atomicAdd(&s_acc[CCLD_BLM_SUM_LAG_ENTER], (unsigned long long)se);
+    atomicAdd(&s_acc[CCLD_BLM_SUM_LAG_EXIT], (unsigned long long)sx);
   }
+  __syncthreads();
+  if (tid < 4) blame[(u64)tid * n_ranks + r] = (i64)s_acc[tid];
 }
+static_assert(CCLD_BLM_N_LATE_ENTER == 0 && CCLD_BLM_N_LATE_EXIT == 1 && CCLD_BLM_SUM_LAG_ENTER == 2 &&
+              CCLD_BLM_SUM_LAG_EXIT == 3, "blame column order");
 void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* sidx, uint32_t n_flag,
                          const uint32_t* flag_pos, const uint8_t* rec_flag, const int64_t* flag_lag,
                          uint64_t cap_n, uint32_t n_ranks, int64_t* blame) {
-  hipLaunchKernelGGL(k_blame_reduce, dim3((n_ranks + 3) / 4), dim3(256), 0, st, skey, sidx, n_flag, flag_pos,
+  hipLaunchKernelGGL(k_blame_reduce, dim3(n_ranks), dim3(256), 0, st, skey, sidx, n_flag, flag_pos,
                      rec_flag, flag_lag, cap_n, n_ranks, blame);
 }
 
-// order[] = ranks by (flags descending, summed lag descending, rank ascending): each rank counts
-// the ranks that precede it, the table staged through LDS in tiles.
+// order[] = ranks by (flags descending, summed lag descending, rank ascending): one wavefront per
+// rank counts the ranks that precede it
 __global__ __launch_bounds__(256) void k_blame_order(const i64* __restrict__ blame, u32 n_ranks,
                                                      u32* __restrict__ order) {
-  __shared__ i64 s_n[256], s_s[256];
-  const u32 r = blockIdx.x * 256 + threadIdx.x;
-  const bool live = r < n_ranks;
-  i64 myn = 0, mys = 0;
-  if (live) {
-    myn = blame[(u64)CCLD_BLM_N_LATE_ENTER * n_ranks + r] + blame[(u64)CCLD_BLM_N_LATE_EXIT * n_ranks + r];
-    mys = (i64)((u64)blame[(u64)CCLD_BLM_SUM_LAG_ENTER * n_ranks + r] + (u64)blame[(u64)CCLD_BLM_SUM_LAG_EXIT * n_ranks + r]);
-  }
+  const u32 r = blockIdx.x * 4 + threadIdx.x / CCLD_WAVE;
+  if (r >= n_ranks) return;
+  const u32 lane = lane_id();
+  const i64* NE = blame + (u64)CCLD_BLM_N_LATE_ENTER * n_ranks;
+  const i64* NX = blame + (u64)CCLD_BLM_N_LATE_EXIT * n_ranks;
+  const i64* SE = blame + (u64)CCLD_BLM_SUM_LAG_ENTER * n_ranks;
+  const i64* SX = blame + (u64)CCLD_BLM_SUM_LAG_EXIT * n_ranks;
+  const i64 myn = NE[r] + NX[r];
+  const i64 mys = (i64)((u64)SE[r] + (u64)SX[r]);
   u32 before = 0;
-  for (u32 t0 = 0; t0 < n_ranks; t0 += 256) {
-    const u32 q = t0 + threadIdx.x;
-    __syncthreads();
-    if (q < n_ranks) {
-      s_n[threadIdx.x] = blame[(u64)CCLD_BLM_N_LATE_ENTER * n_ranks + q] + blame[(u64)CCLD_BLM_N_LATE_EXIT * n_ranks + q];
-      s_s[threadIdx.x] = (i64)((u64)blame[(u64)CCLD_BLM_SUM_LAG_ENTER * n_ranks + q] + (u64)blame[(u64)CCLD_BLM_SUM_LAG_EXIT * n_ranks + q]);
-    }
-    __syncthreads();
-    const u32 lim = (n_ranks - t0) < 256u ? (n_ranks - t0) : 256u;
-    for (u32 i = 0; i < lim; ++i) {
-      const i64 on = s_n[i], os = s_s[i];
-      const u32 o = t0 + i;
-      before += (on > myn) || (on == myn && (os > mys || (os == mys && o < r)));
-    }
+  for (u32 o = lane; o < n_ranks; o += CCLD_WAVE) {
+    const i64 on = NE[o] + NX[o];
+    const i64 os = (i64)((u64)SE[o] + (u64)SX[o]);
+    before += (on > myn) || (on == myn && (os > mys || (os == mys && o < r)));
   }
-  if (live) order[before] = r;
+  before = wave_sum(before);
+  if (lane == 0) order[before] = r;
 }
 void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, uint32_t* order) {
-  hipLaunchKernelGGL(k_blame_order, dim3((n_ranks + 255) / 256), dim3(256), 0, st, blame, n_ranks, order);
+  hipLaunchKernelGGL(k_blame_order, dim3((n_ranks + 3) / 4), dim3(256), 0, st, blame, n_ranks, order);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -311,8 +313,9 @@ void launch_usable_select(hipStream_t st, const GroupArgs& a) {
   run_select(st, p, a.n_seg, a.tile_counts, a.usable_list, &a.counters[CNT_NUSABLE]);
 }
 
-// detection-group key of a usable collective: (communicator, op, floor(log2 bytes)) then the
-// operation counter, so that a stable sort lists every group's rounds in ascending order
+// detection-group key of a usable collective: (communicator, op, floor(log2 bytes)); the usable
+// collectives are listed in (communicator, operation counter) order, so a stable sort by this key
+// lists every group's rounds in ascending operation counter
 __global__ __launch_bounds__(256) void k_group_keys(GroupArgs a, u32 n_usable) {
   const u32 q = blockIdx.x * 256 + threadIdx.x;
   if (q >= n_usable) return;
@@ -320,9 +323,8 @@ __global__ __launch_bounds__(256) void k_group_keys(GroupArgs a, u32 n_usable) {
   const u64 comm = (u64)a.seg[(u64)CCLD_SEG_COMM * a.seg_cap + s];
   const u64 op = (u64)a.seg[(u64)CCLD_SEG_OP * a.seg_cap + s];
   const u64 nb = (u64)a.seg[(u64)CCLD_SEG_BYTES * a.seg_cap + s];
-  const u64 seq = (u64)a.seg[(u64)CCLD_SEG_SEQ * a.seg_cap + s];
   const u64 cls = 63 - __clzll((long long)(nb | 1));
-  a.gkey[q] = (((comm * CCLD_OP_MAX + op) * GROUP_CLS + cls) << a.ws) | seq;
+  a.gkey[q] = (comm * CCLD_OP_MAX + op) * GROUP_CLS + cls;
 }
 void launch_group_keys(hipStream_t st, const GroupArgs& a, uint32_t n_usable) {
   if (n_usable) hipLaunchKernelGGL(k_group_keys, dim3((n_usable + 255) / 256), dim3(256), 0, st, a, n_usable);
@@ -330,7 +332,7 @@ void launch_group_keys(hipStream_t st, const GroupArgs& a, uint32_t n_usable) {
 
 struct PredGroupHead {
   const u64* skey; int ws;
-  __device__ bool operator()(u32 i) const { return i == 0 || (skey[i] >> ws) != (skey[i - 1] >> ws); }
+  __device__ bool operator()(u32 i) const { return i == 0 || skey[i] != skey[i - 1]; }
 };
 void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_usable, int ws, uint32_t* tile_counts,
                         uint32_t* group_first, uint64_t* counters) {
@@ -349,8 +351,9 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
   __shared__ unsigned long long s_sum, s_best;
   const u32 g = blockIdx.x, tid = threadIdx.x;
   const u32 f = group_first[g], e = (g + 1 < n_group) ? group_first[g + 1] : n_usable;
-  const u64 smask = ((u64)1 << a.ws) - 1;
-  const u64 gid = skey[f] >> a.ws;                       // (comm*OP_MAX + op)*CLS + cls
+  const u64 gid = skey[f];                               // (comm*OP_MAX + op)*CLS + cls
+  const i64* SEQ = a.seg + (u64)CCLD_SEG_SEQ * a.seg_cap;
+  auto seq_of = [&](u32 i) -> u64 { return (u64)SEQ[a.usable_list[sidx[i]]]; };
   GroupState* G = a.gstate + gid;
   const i64* EMIN = a.seg + (u64)CCLD_SEG_ENTER_MIN * a.seg_cap;
   const i64* DMAX = a.seg + (u64)CCLD_SEG_DUR_MAX * a.seg_cap;
@@ -360,7 +363,7 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
   __syncthreads();
   // rounds not yet visited by Eq. 1 form a suffix (ascending operation counters)
   for (u32 i = f + tid; i < e; i += 256)
-    if ((skey[i] & smask) + 1 > g0.baselined_wm) atomicMin(&s_i0, i);
+    if (seq_of(i) + 1 > g0.baselined_wm) atomicMin(&s_i0, i);
   // Eq. 2 needs the largest range
   for (u32 i = f + tid; i < e; i += 256) {
     const u32 s = a.usable_list[sidx[i]];
@@ -395,13 +398,13 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
     n.t0 = t0;
     n.sum = (i64)((u64)g0.sum + (u64)s_sum);
     n.cnt = g0.cnt + (istar - i0);
-    if (istar > i0) n.baseline_last_seq = skey[istar - 1] & smask;
+    if (istar > i0) n.baseline_last_seq = seq_of(istar - 1);
     if (istar < e) { n.frozen = 1; n.tbase_dyn = n.sum / (i64)n.cnt; }
   }
-  if (i0 < e) n.baselined_wm = (skey[e - 1] & smask) + 1;
+  if (i0 < e) n.baselined_wm = seq_of(e - 1) + 1;
   const u32 ks = s_kstar;
   const u32 sx = a.usable_list[sidx[ks]];
-  const u64 rseq = skey[ks] & smask;
+  const u64 rseq = seq_of(ks);
   const i64 tmax = DMAX[sx], tmin = DMIN[sx];
   const bool dynamic = n.frozen && rseq > n.baseline_last_seq;
   const i64 tbase = dynamic ? n.tbase_dyn : a.p.tbase_init_ns;
