@@ -39,6 +39,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->topo.tree_parent = w.take<int32_t>(n_members);
   c->topo.rank_comm_off = w.take<uint32_t>((uint64_t)n_ranks + 1);
   c->topo.rank_comms = w.take<uint32_t>(n_members);
+  c->topo.rank_comms4 = w.take<uint32_t>(4ull * n_ranks);
   // window
   c->win_key = w.take<uint64_t>(N);
   c->win_row = w.take<Row>(N);
@@ -232,6 +233,12 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
       for (uint32_t q = 0; q < topo->size[k]; ++q) rc[fill[topo->members[topo->member_off[k] + q]]++] = k;
   }
   if (topo->tree_parent) parent.assign(topo->tree_parent, topo->tree_parent + n_members);
+  std::vector<uint32_t> rc4(4ull * topo->n_ranks, 0xFFFFFFFFu);
+  bool fits4 = true;
+  for (uint32_t r = 0; r < topo->n_ranks; ++r) {
+    if (rc_off[r + 1] - rc_off[r] > 4) { fits4 = false; break; }
+    for (uint32_t q = rc_off[r]; q < rc_off[r + 1]; ++q) rc4[4ull * r + (q - rc_off[r])] = rc[q];
+  }
 
   ccld_status rs = CCLD_OK;
   auto up = [&](const void* dst, const void* src, size_t bytes) {
@@ -247,6 +254,8 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   up(c->topo.tree_parent, parent.data(), 4ull * n_members);
   up(c->topo.rank_comm_off, rc_off.data(), 4ull * rc_off.size());
   up(c->topo.rank_comms, rc.data(), 4ull * n_members);
+  up(c->topo.rank_comms4, rc4.data(), 4ull * rc4.size());
+  if (!fits4) c->topo.rank_comms4 = nullptr;
   if (hipMemsetAsync(c->gstate, 0, sizeof(GroupState) * (uint64_t)topo->n_comms * GROUP_SLOTS, c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->batch_meta, 0, sizeof(BatchMeta) * ((uint64_t)c->p.window_batches + 2), c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, c->stream) != hipSuccess) rs = CCLD_E_HIP;
@@ -456,6 +465,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   o->n_alert = c->h_pinned[CNT_NALERT];
   if (n_usable) {
     ga.gkey = c->keyC;            // blame's sort is done with C by stream order
+    ga.range_c = c->big_ex;       // free again once the collectives have been analysed
     c->prof.begin();
     launch_group_keys(st, ga, n_usable);
     KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = n_usable; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0;

@@ -41,6 +41,7 @@ struct DeviceTopology {
   const int32_t* tree_parent;
   const uint32_t* rank_comm_off;    // [n_ranks + 1] CSR: communicators each rank belongs to
   const uint32_t* rank_comms;
+  const uint32_t* rank_comms4;      // [n_ranks][4] the same lists padded with 0xFFFFFFFF, or null if a rank is in more than four
 };
 
 // Eq. 1 state and repetition counter of one detection group (communicator, op, size class).

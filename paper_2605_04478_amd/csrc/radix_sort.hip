@@ -27,26 +27,35 @@ __device__ __forceinline__ u64 load_key(const KeySource& s, u32 j, u32* phys) {
 }
 
 // ---- per-tile digit histogram --------------------------------------------------------------
+// A workgroup counts HIST_TILES consecutive tiles, so that each digit's counts leave as one
+// contiguous 32-byte piece of the digit-major table instead of eight scattered words.
+constexpr int HIST_TILES = 8;
 template <bool FIRST>
 __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, const u64* __restrict__ key_in,
                                                              u32* __restrict__ table, u32 n, u32 n_tiles,
                                                              int shift, u32 dmask) {
-  __shared__ u32 s_hist[SORT_RADIX];
-  const u32 tid = threadIdx.x, tile = blockIdx.x;
-  for (u32 i = tid; i < SORT_RADIX; i += SORT_THREADS) s_hist[i] = 0;
+  __shared__ u32 s_hist[HIST_TILES][SORT_RADIX];
+  const u32 tid = threadIdx.x, tile0 = blockIdx.x * HIST_TILES;
+  for (u32 i = tid; i < HIST_TILES * SORT_RADIX; i += SORT_THREADS) (&s_hist[0][0])[i] = 0;
   __syncthreads();
-  const u32 base = tile * SORT_TILE;
+#pragma unroll 4
+  for (int t = 0; t < HIST_TILES; ++t) {
+    const u32 base = (tile0 + t) * SORT_TILE;
+    if (tile0 + t >= n_tiles) continue;
 #pragma unroll
-  for (int it = 0; it < SORT_ITEMS; ++it) {
-    u32 j = base + it * SORT_THREADS + tid;
-    if (j < n) {
-      u64 k;
-      if (FIRST) { u32 ph; k = load_key(src, j, &ph); } else k = key_in[j];
-      atomicAdd(&s_hist[(u32)(k >> shift) & dmask], 1u);
+    for (int it = 0; it < SORT_ITEMS; ++it) {
+      u32 j = base + it * SORT_THREADS + tid;
+      if (j < n) {
+        u64 k;
+        if (FIRST) { u32 ph; k = load_key(src, j, &ph); } else k = key_in[j];
+        atomicAdd(&s_hist[t][(u32)(k >> shift) & dmask], 1u);
+      }
     }
   }
   __syncthreads();
-  for (u32 d = tid; d <= dmask; d += SORT_THREADS) table[(u64)d * n_tiles + tile] = s_hist[d];
+  const u32 nt = (n_tiles - tile0) < (u32)HIST_TILES ? (n_tiles - tile0) : (u32)HIST_TILES;
+  for (u32 d = tid; d <= dmask; d += SORT_THREADS)
+    for (u32 t = 0; t < nt; ++t) table[(u64)d * n_tiles + tile0 + t] = s_hist[t][d];
 }
 
 // ---- exclusive scan of each digit's row of tile counts ------------------------------------
@@ -223,10 +232,10 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const
     const int scat_shift = done_bits + (packed ? ibits : 0);
     if (prof) prof->begin();
     if (first)
-      hipLaunchKernelGGL(k_radix_hist<true>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
+      hipLaunchKernelGGL(k_radix_hist<true>, dim3((n_tiles + HIST_TILES - 1) / HIST_TILES), dim3(SORT_THREADS), 0, stream, src,
                          (const u64*)nullptr, buf.table, n, n_tiles, hist_shift, dmask);
     else
-      hipLaunchKernelGGL(k_radix_hist<false>, dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src,
+      hipLaunchKernelGGL(k_radix_hist<false>, dim3((n_tiles + HIST_TILES - 1) / HIST_TILES), dim3(SORT_THREADS), 0, stream, src,
                          (const u64*)buf.key[cur], buf.table, n, n_tiles, hist_shift, dmask);
     if (prof) { prof->end(cls_hist); prof->begin(); }
     hipLaunchKernelGGL(k_radix_scan, dim3(dmask + 1), dim3(SORT_THREADS), 0, stream, buf.table, buf.totals, n_tiles);

@@ -28,35 +28,71 @@ void launch_fill_u64(hipStream_t st, uint64_t* p, uint64_t n, uint64_t v) {
 // Ingest: validate each record, key it by Trace ID (communicator id, operation counter) plus
 // rank, store key and payload row at the window's tail.
 __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, KeyFormat kf) {
+  constexpr int U = 4;               // records per thread in flight
   __shared__ u64 s_status[4], s_max[4];
   u64 status = 0, maxseq = 0;
-  for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < a.n; i += (u64)gridDim.x * 256) {
-    const u32 r = a.rank[i], c = a.comm[i];
-    const u64 s = a.seq[i];
-    const u32 op = a.op[i];
-    const i64 te = a.t_enter[i], tx = a.t_exit[i];
-    u64 key = 0;
-    if (c >= T.n_comms) {
-      status |= DS_UNKNOWN_COMM;
-    } else {
-      bool member = false;
-      if (r < T.n_ranks)
-        for (u32 q = T.rank_comm_off[r]; q < T.rank_comm_off[r + 1]; ++q) member |= (T.rank_comms[q] == c);
-      if (!member) status |= DS_NOT_MEMBER;
-      if (op >= CCLD_OP_MAX || te < 0 || te == T_INFLIGHT || tx < te) status |= DS_RANGE;
-      if (kf.sb < 64 && (s >> kf.sb) != 0) {
-        status |= DS_KEY_WIDTH;
-      } else {
-        key = (kf.cb ? ((u64)c << (64 - kf.cb)) : 0ull) | (s << kf.rb) | (u64)r;
-        maxseq = s > maxseq ? s : maxseq;
+  const u32* __restrict__ in_rank = a.rank;
+  const u32* __restrict__ in_comm = a.comm;
+  const u64* __restrict__ in_seq = a.seq;
+  const uint8_t* __restrict__ in_op = a.op;
+  const u64* __restrict__ in_bytes = a.bytes;
+  const i64* __restrict__ in_te = a.t_enter;
+  const i64* __restrict__ in_tx = a.t_exit;
+  u64* __restrict__ out_key = a.win_key;
+  Row* __restrict__ out_row = a.win_row;
+  const uint4* __restrict__ comms4 = reinterpret_cast<const uint4*>(T.rank_comms4);
+  // every workgroup walks one contiguous slice of the batch, so its nine streams advance page by page
+  const u64 chunk = ((a.n + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+  const u64 i_end = (chunk * (blockIdx.x + 1)) < a.n ? chunk * (blockIdx.x + 1) : a.n;
+  for (u64 i0 = chunk * blockIdx.x + threadIdx.x; i0 < i_end; i0 += 256 * U) {
+    u32 r[U], c[U], op[U];
+    u64 sq[U], nb[U];
+    i64 te[U], tx[U];
+    uint4 mem[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u64 i = i0 + (u64)u * 256;
+      if (i < i_end) {
+        r[u] = in_rank[i]; c[u] = in_comm[i]; sq[u] = in_seq[i]; op[u] = in_op[i]; nb[u] = in_bytes[i];
+        te[u] = in_te[i]; tx[u] = in_tx[i];
       }
     }
-    u64 p = (u64)a.tail + i;
-    if (p >= a.cap) p -= a.cap;
-    a.win_key[p] = key;
-    Row rw;
-    rw.t_enter = te; rw.t_exit = tx; rw.bytes = a.bytes[i]; rw.op = op; rw.pad = 0;
-    a.win_row[p] = rw;
+    // the communicators of each rank: one 16-byte row when no rank is in more than four of them
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      mem[u] = make_uint4(~0u, ~0u, ~0u, ~0u);
+      if (i0 + (u64)u * 256 < i_end && comms4 && r[u] < T.n_ranks) mem[u] = comms4[r[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u64 i = i0 + (u64)u * 256;
+      if (i >= i_end) continue;
+      u64 key = 0;
+      if (c[u] >= T.n_comms) {
+        status |= DS_UNKNOWN_COMM;
+      } else {
+        bool member = false;
+        if (comms4) {
+          member = c[u] == mem[u].x || c[u] == mem[u].y || c[u] == mem[u].z || c[u] == mem[u].w;
+        } else if (r[u] < T.n_ranks) {
+          for (u32 q = T.rank_comm_off[r[u]]; q < T.rank_comm_off[r[u] + 1]; ++q) member |= (T.rank_comms[q] == c[u]);
+        }
+        if (!member) status |= DS_NOT_MEMBER;
+        if (op[u] >= CCLD_OP_MAX || te[u] < 0 || te[u] == T_INFLIGHT || tx[u] < te[u]) status |= DS_RANGE;
+        if (kf.sb < 64 && (sq[u] >> kf.sb) != 0) {
+          status |= DS_KEY_WIDTH;
+        } else {
+          key = (kf.cb ? ((u64)c[u] << (64 - kf.cb)) : 0ull) | (sq[u] << kf.rb) | (u64)r[u];
+          maxseq = sq[u] > maxseq ? sq[u] : maxseq;
+        }
+      }
+      u64 p = (u64)a.tail + i;
+      if (p >= a.cap) p -= a.cap;
+      out_key[p] = key;
+      Row rw;
+      rw.t_enter = te[u]; rw.t_exit = tx[u]; rw.bytes = nb[u]; rw.op = op[u]; rw.pad = 0;
+      out_row[p] = rw;
+    }
   }
   // one pair of atomics per workgroup
   u64 st = status;
@@ -202,18 +238,29 @@ __global__ __launch_bounds__(256) void k_rank_count(const u64* __restrict__ key,
     __syncthreads();
   }
 }
+// 64 ranks x 4 slices per workgroup; gridDim.y workgroups share the partial tables of a rank and
+// add their integer sums into the (zeroed) blame column
 __global__ __launch_bounds__(256) void k_rank_reduce(const u32* __restrict__ partial, u32 n_blocks, u32 n_ranks,
                                                      i64* __restrict__ blame) {
-  const u32 r = blockIdx.x * 256 + threadIdx.x;
-  if (r >= n_ranks) return;
+  __shared__ unsigned long long s_sum[64];
+  const u32 rr = threadIdx.x % 64, sl = threadIdx.x / 64;
+  const u32 r = blockIdx.x * 64 + rr;
+  if (threadIdx.x < 64) s_sum[threadIdx.x] = 0;
+  __syncthreads();
+  const u32 per = (n_blocks + gridDim.y - 1) / gridDim.y;
+  const u32 b0 = blockIdx.y * per, b1 = (b0 + per) < n_blocks ? (b0 + per) : n_blocks;
   u64 s = 0;
-  for (u32 b = 0; b < n_blocks; ++b) s += partial[(u64)b * n_ranks + r];
-  blame[(u64)CCLD_BLM_N_RECORDS * n_ranks + r] = (i64)s;
+  if (r < n_ranks)
+    for (u32 b = b0 + sl; b < b1; b += 4) s += partial[(u64)b * n_ranks + r];
+  if (s) atomicAdd(&s_sum[rr], (unsigned long long)s);
+  __syncthreads();
+  if (threadIdx.x < 64 && r < n_ranks && s_sum[rr])
+    atomicAdd((unsigned long long*)&blame[(u64)CCLD_BLM_N_RECORDS * n_ranks + r], s_sum[rr]);
 }
 void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, int rb, uint32_t n_ranks,
                        uint32_t* partial, int64_t* blame) {
   hipLaunchKernelGGL(k_rank_count, dim3(RANKCOUNT_BLOCKS), dim3(256), 0, st, key, n, rb, n_ranks, partial);
-  hipLaunchKernelGGL(k_rank_reduce, dim3((n_ranks + 255) / 256), dim3(256), 0, st, (const u32*)partial,
+  hipLaunchKernelGGL(k_rank_reduce, dim3((n_ranks + 63) / 64, 32), dim3(256), 0, st, (const u32*)partial,
                      (u32)RANKCOUNT_BLOCKS, n_ranks, blame);
 }
 
@@ -325,6 +372,8 @@ __global__ __launch_bounds__(256) void k_group_keys(GroupArgs a, u32 n_usable) {
   const u64 nb = (u64)a.seg[(u64)CCLD_SEG_BYTES * a.seg_cap + s];
   const u64 cls = 63 - __clzll((long long)(nb | 1));
   a.gkey[q] = (comm * CCLD_OP_MAX + op) * GROUP_CLS + cls;
+  // intra-round range T_max - T_min (Eq. 2), kept in usable-list order for the per-group pass
+  a.range_c[q] = a.seg[(u64)CCLD_SEG_DUR_MAX * a.seg_cap + s] - a.seg[(u64)CCLD_SEG_DUR_MIN * a.seg_cap + s];
 }
 void launch_group_keys(hipStream_t st, const GroupArgs& a, uint32_t n_usable) {
   if (n_usable) hipLaunchKernelGGL(k_group_keys, dim3((n_usable + 255) / 256), dim3(256), 0, st, a, n_usable);
@@ -362,13 +411,13 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
   if (tid == 0) { s_i0 = e; s_istar = e; s_kstar = e; s_sum = 0; s_best = 0; }
   __syncthreads();
   // rounds not yet visited by Eq. 1 form a suffix (ascending operation counters)
-  for (u32 i = f + tid; i < e; i += 256)
-    if (seq_of(i) + 1 > g0.baselined_wm) atomicMin(&s_i0, i);
+  // (ascending counters: compare the last round first; a fully visited group needs no search)
+  const bool any_new = seq_of(e - 1) + 1 > g0.baselined_wm;
+  if (any_new)
+    for (u32 i = f + tid; i < e; i += 256)
+      if (seq_of(i) + 1 > g0.baselined_wm) atomicMin(&s_i0, i);
   // Eq. 2 needs the largest range
-  for (u32 i = f + tid; i < e; i += 256) {
-    const u32 s = a.usable_list[sidx[i]];
-    atomicMax(&s_best, (unsigned long long)(DMAX[s] - DMIN[s]));
-  }
+  for (u32 i = f + tid; i < e; i += 256) atomicMax(&s_best, (unsigned long long)a.range_c[sidx[i]]);
   __syncthreads();
   const u32 i0 = s_i0;
   const i64 t0 = (g0.cnt == 0 && i0 < e) ? EMIN[a.usable_list[sidx[i0]]] : g0.t0;
@@ -380,10 +429,8 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
     }
   }
   const unsigned long long best = s_best;
-  for (u32 i = f + tid; i < e; i += 256) {
-    const u32 s = a.usable_list[sidx[i]];
-    if ((unsigned long long)(DMAX[s] - DMIN[s]) == best) atomicMin(&s_kstar, i);
-  }
+  for (u32 i = f + tid; i < e; i += 256)
+    if ((unsigned long long)a.range_c[sidx[i]] == best) atomicMin(&s_kstar, i);
   __syncthreads();
   const u32 istar = s_istar;
   if (!g0.frozen) {

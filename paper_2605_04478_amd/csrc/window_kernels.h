@@ -76,6 +76,7 @@ struct GroupArgs {
   uint32_t* tile_counts;
   uint64_t* counters;
   uint64_t* gkey;            // [n_usable]
+  int64_t* range_c;          // [n_usable] T_max - T_min of each usable collective
   GroupState* gstate;
   int64_t* group;
   uint64_t group_cap;
