@@ -44,6 +44,8 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->win_key = w.take<uint64_t>(N);
   c->win_row = w.take<Row>(N);
   c->batch_meta = w.take<BatchMeta>((uint64_t)c->p.window_batches + 2);
+  c->ing_table = w.take<uint32_t>((uint64_t)INGEST_MAX_BUCKETS * INGEST_BLOCKS);
+  c->ing_base = w.take<uint32_t>(INGEST_MAX_BUCKETS + 2);
   // sort
   const uint64_t tw = sort_table_words(N);
   for (int i = 0; i < 2; ++i) { c->sb.key[i] = w.take<uint64_t>(N); c->sb.idx[i] = w.take<uint32_t>(N); }
@@ -198,7 +200,9 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   c->stream = (hipStream_t)hip_stream;
   c->cap = max_window_records; c->batch_cap = max_batch_records; c->snap_cap = max_snapshot_rows;
   c->kf.rb = rb; c->kf.cb = cb; c->kf.sb = 64 - rb - cb;
-  c->head = 0; c->count = 0; c->next_slot = 0;
+  c->head = 0; c->count = 0; c->next_slot = 0; c->total_ingested = 0;
+  c->bshift = cb > 6 ? cb - 6 : 0;        // at most 64 buckets: long runs per workgroup, payload gathers stay inside one bucket
+  c->n_buckets = ((topo->n_comms - 1) >> c->bshift) + 1;
   c->sorted_buf = 0; c->last_n = 0; c->blame_valid = false; c->sort_passes = 0;
   c->sf.rb = rb; c->sf.ws = 0;
   uint64_t n_members = 0;
@@ -278,7 +282,7 @@ ccld_status ccld_destroy(ccld_ctx* c) {
 
 ccld_status ccld_reset_window(ccld_ctx* c) {
   if (!c) return CCLD_E_NULL;
-  c->head = 0; c->count = 0; c->batch_n.clear(); c->batch_slot.clear();
+  c->head = 0; c->count = 0; c->batch_n.clear(); c->batch_slot.clear(); c->batch_seqno.clear();
   return CCLD_OK;
 }
 
@@ -320,6 +324,8 @@ ccld_status ccld_ingest(ccld_ctx* c, const ccld_records* b, uint64_t n) {
   a.n = n; a.win_key = c->win_key; a.win_row = c->win_row;
   a.tail = (uint32_t)((head + count) % std::max<uint64_t>(c->cap, 1));
   a.cap = (uint32_t)c->cap;
+  a.table = c->ing_table; a.bucket_base = c->ing_base; a.scratch_total = &c->counters[CNT_COUNT - 1];
+  a.n_buckets = c->n_buckets; a.bshift = c->bshift; a.seqno0 = (uint32_t)c->total_ingested;
   c->prof.begin();
   launch_ingest(c->stream, a, c->topo, c->kf);
   c->prof.end(CCLD_PROF_INGEST);
@@ -327,8 +333,11 @@ ccld_status ccld_ingest(ccld_ctx* c, const ccld_records* b, uint64_t n) {
   if (!b->on_device && n) HIP_TRY(hipStreamSynchronize(c->stream));   // the host buffers may go away on return
   c->batch_n.erase(c->batch_n.begin(), c->batch_n.begin() + drop);
   c->batch_slot.erase(c->batch_slot.begin(), c->batch_slot.begin() + drop);
+  c->batch_seqno.erase(c->batch_seqno.begin(), c->batch_seqno.begin() + drop);
   c->batch_n.push_back(n);
   c->batch_slot.push_back(slot);
+  c->batch_seqno.push_back((uint32_t)c->total_ingested);
+  c->total_ingested += n;
   c->next_slot = (slot + 1) % (c->p.window_batches + 2);
   c->head = head; c->count = count + n;
   return CCLD_OK;
@@ -412,7 +421,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   c->prof.begin();
   launch_flag_compact(st, fa);
   c->prof.end(CCLD_PROF_FLAGS);
-  if (o->perm) launch_perm(st, sidx, n, (uint32_t)c->head, (uint32_t)c->cap, o->perm);
+  if (o->perm) launch_perm(st, sidx, c->win_row, n, c->batch_seqno.empty() ? 0u : c->batch_seqno[0], o->perm);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));

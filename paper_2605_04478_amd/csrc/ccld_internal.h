@@ -89,6 +89,11 @@ struct ccld_ctx {
   uint64_t* win_key;
   ccld::Row* win_row;
   ccld::BatchMeta* batch_meta;        // [window_batches + 1]
+  std::vector<uint32_t> batch_seqno;  // arrival number of each resident batch's first record
+  uint64_t total_ingested;
+  uint32_t* ing_table;                // [n_buckets][INGEST_BLOCKS]
+  uint32_t* ing_base;                 // [n_buckets + 1]
+  uint32_t n_buckets; int bshift;
   // sort
   ccld::SortBuffers sb;               // main sort
   uint64_t* keyC; uint32_t* idxC;     // third pair for the small sorts

@@ -27,9 +27,47 @@ void launch_fill_u64(hipStream_t st, uint64_t* p, uint64_t n, uint64_t v) {
 // ------------------------------------------------------------------------------------------
 // Ingest: validate each record, key it by Trace ID (communicator id, operation counter) plus
 // rank, store key and payload row at the window's tail.
+// Records per communicator bucket in each workgroup's slice of the batch (first half of the
+// two-step placement below).
+__global__ __launch_bounds__(256) void k_ingest_hist(IngestArgs a, u32 n_comms) {
+  extern __shared__ u32 s_cnt[];
+  for (u32 b = threadIdx.x; b < a.n_buckets; b += 256) s_cnt[b] = 0;
+  __syncthreads();
+  const u64 chunk = ((a.n + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+  const u64 i_end = (chunk * (blockIdx.x + 1)) < a.n ? chunk * (blockIdx.x + 1) : a.n;
+  for (u64 i = chunk * blockIdx.x + threadIdx.x; i < i_end; i += 256) {
+    const u32 c = a.comm[i];
+    atomicAdd(&s_cnt[c < n_comms ? (c >> a.bshift) : 0u], 1u);
+  }
+  __syncthreads();
+  for (u32 b = threadIdx.x; b < a.n_buckets; b += 256) a.table[(u64)b * gridDim.x + blockIdx.x] = s_cnt[b];
+}
+// exclusive scan of every bucket's row of per-workgroup counts (row length <= 2048)
+__global__ __launch_bounds__(256) void k_ingest_scan(u32* table, u32* totals, u32 n_blocks) {
+  __shared__ u32 s_wave[4];
+  u32* row = table + (u64)blockIdx.x * n_blocks;
+  u32 v[8], sum = 0;
+  const u32 i0 = threadIdx.x * 8;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { v[k] = (i0 + k) < n_blocks ? row[i0 + k] : 0u; sum += v[k]; }
+  u32 tot;
+  u32 ex = block_exclusive_sum<256>(sum, s_wave, &tot);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { if ((i0 + k) < n_blocks) row[i0 + k] = ex; ex += v[k]; }
+  if (threadIdx.x == 0) totals[blockIdx.x] = tot;
+}
+
+// Validates and keys every record and stores it in the window.  Inside the batch's slot range the
+// records are placed grouped by communicator bucket (the order inside a bucket is arbitrary), so
+// that the analysis, which walks the window in (communicator, ...) order, gathers its payload rows
+// from a small region at a time instead of from the whole window.
 __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, KeyFormat kf) {
   constexpr int U = 4;               // records per thread in flight
+  extern __shared__ u32 s_off[];     // next free slot of every bucket for this workgroup
   __shared__ u64 s_status[4], s_max[4];
+  for (u32 b = threadIdx.x; b < a.n_buckets; b += 256)
+    s_off[b] = a.bucket_base[b] + a.table[(u64)b * gridDim.x + blockIdx.x];
+  __syncthreads();
   u64 status = 0, maxseq = 0;
   const u32* __restrict__ in_rank = a.rank;
   const u32* __restrict__ in_comm = a.comm;
@@ -86,11 +124,13 @@ __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, 
           maxseq = sq[u] > maxseq ? sq[u] : maxseq;
         }
       }
-      u64 p = (u64)a.tail + i;
+      const u32 slot = atomicAdd(&s_off[c[u] < T.n_comms ? (c[u] >> a.bshift) : 0u], 1u);
+      u64 p = (u64)a.tail + slot;
       if (p >= a.cap) p -= a.cap;
       out_key[p] = key;
       Row rw;
-      rw.t_enter = te[u]; rw.t_exit = tx[u]; rw.bytes = nb[u]; rw.op = op[u]; rw.pad = 0;
+      rw.t_enter = te[u]; rw.t_exit = tx[u]; rw.bytes = nb[u]; rw.op = op[u];
+      rw.pad = a.seqno0 + (u32)i;          // arrival number of the record (modulo 2^32)
       out_row[p] = rw;
     }
   }
@@ -112,8 +152,12 @@ __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, 
 void launch_ingest(hipStream_t st, const IngestArgs& a, const DeviceTopology& T, const KeyFormat& kf) {
   if (a.n == 0) return;
   u64 g = (a.n + 255) / 256;
-  if (g > 2048) g = 2048;
-  hipLaunchKernelGGL(k_ingest, dim3((u32)g), dim3(256), 0, st, a, T, kf);
+  if (g > INGEST_BLOCKS) g = INGEST_BLOCKS;
+  const size_t lds = sizeof(u32) * a.n_buckets;
+  hipLaunchKernelGGL(k_ingest_hist, dim3((u32)g), dim3(256), lds, st, a, T.n_comms);
+  hipLaunchKernelGGL(k_ingest_scan, dim3(a.n_buckets), dim3(256), 0, st, a.table, a.bucket_base, (u32)g);
+  launch_scan_tiles(st, a.bucket_base, a.n_buckets, a.scratch_total);
+  hipLaunchKernelGGL(k_ingest, dim3((u32)g), dim3(256), lds, st, a, T, kf);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -580,14 +624,16 @@ void launch_alert_candidates(hipStream_t st, const AlertArgs& a, uint32_t n_aler
 }
 
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_perm(const u32* __restrict__ idx, u32 n, u32 head, u32 cap, u32* perm) {
+// position of every sorted record in the window's arrival order: its arrival number minus that of
+// the window's oldest record (both modulo 2^32)
+__global__ __launch_bounds__(256) void k_perm(const u32* __restrict__ idx, const Row* __restrict__ row, u32 n,
+                                              u32 seqno_head, u32* perm) {
   const u32 j = blockIdx.x * 256 + threadIdx.x;
   if (j >= n) return;
-  const u32 p = idx[j];
-  perm[j] = p >= head ? p - head : p + (cap - head);
+  perm[j] = row[idx[j]].pad - seqno_head;
 }
-void launch_perm(hipStream_t st, const uint32_t* idx, uint32_t n, uint32_t head, uint32_t cap, uint32_t* perm) {
-  if (n) hipLaunchKernelGGL(k_perm, dim3((n + 255) / 256), dim3(256), 0, st, idx, n, head, cap, perm);
+void launch_perm(hipStream_t st, const uint32_t* idx, const Row* row, uint32_t n, uint32_t seqno_head, uint32_t* perm) {
+  if (n) hipLaunchKernelGGL(k_perm, dim3((n + 255) / 256), dim3(256), 0, st, idx, row, n, seqno_head, perm);
 }
 
 }  // namespace ccld

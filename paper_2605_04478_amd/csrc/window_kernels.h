@@ -15,7 +15,15 @@ struct IngestArgs {
   Row* win_row;
   uint32_t tail, cap;
   BatchMeta* meta;
+  uint32_t* table;           // [n_buckets][workgroups] records per communicator bucket and workgroup
+  uint32_t* bucket_base;     // [n_buckets + 1]
+  uint64_t* scratch_total;
+  uint32_t n_buckets;
+  int bshift;                // bucket = comm >> bshift
+  uint32_t seqno0;           // arrival number of the batch's first record
 };
+constexpr uint32_t INGEST_BLOCKS = 1024;
+constexpr uint32_t INGEST_MAX_BUCKETS = 4096;
 void launch_ingest(hipStream_t st, const IngestArgs& a, const DeviceTopology& T, const KeyFormat& kf);
 void launch_fill_u64(hipStream_t st, uint64_t* p, uint64_t n, uint64_t v);
 
@@ -112,6 +120,6 @@ struct AlertArgs {
 void launch_alert_select(hipStream_t st, const AlertArgs& a);
 void launch_alert_candidates(hipStream_t st, const AlertArgs& a, uint32_t n_alert);
 
-void launch_perm(hipStream_t st, const uint32_t* idx, uint32_t n, uint32_t head, uint32_t cap, uint32_t* perm);
+void launch_perm(hipStream_t st, const uint32_t* idx, const Row* row, uint32_t n, uint32_t seqno_head, uint32_t* perm);
 
 }  // namespace ccld
