@@ -35,9 +35,14 @@ __global__ __launch_bounds__(256) void k_ingest_hist(IngestArgs a, u32 n_comms) 
   __syncthreads();
   const u64 chunk = ((a.n + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
   const u64 i_end = (chunk * (blockIdx.x + 1)) < a.n ? chunk * (blockIdx.x + 1) : a.n;
-  for (u64 i = chunk * blockIdx.x + threadIdx.x; i < i_end; i += 256) {
-    const u32 c = a.comm[i];
-    atomicAdd(&s_cnt[c < n_comms ? (c >> a.bshift) : 0u], 1u);
+  const u32* __restrict__ in_comm = a.comm;
+  for (u64 i0 = chunk * blockIdx.x + threadIdx.x; i0 < i_end; i0 += 256 * 8) {
+    u32 c[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) c[u] = (i0 + (u64)u * 256 < i_end) ? in_comm[i0 + (u64)u * 256] : 0xFFFFFFFFu;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (i0 + (u64)u * 256 < i_end) atomicAdd(&s_cnt[c[u] < n_comms ? (c[u] >> a.bshift) : 0u], 1u);
   }
   __syncthreads();
   for (u32 b = threadIdx.x; b < a.n_buckets; b += 256) a.table[(u64)b * gridDim.x + blockIdx.x] = s_cnt[b];
@@ -212,45 +217,50 @@ void launch_scan_tiles(hipStream_t st, uint32_t* counts, uint32_t n_tiles, uint6
 // ------------------------------------------------------------------------------------------
 // ------------------------------------------------------------------------------------------
 // Ordered compaction of the flagged records into the flag list.
+// eight consecutive flag bytes of one thread, as one 8-byte load where the tile is full
+__device__ __forceinline__ u64 load_flags8(const uint8_t* __restrict__ f, u32 j0, u32 n) {
+  if (j0 + 8 <= n && (reinterpret_cast<uintptr_t>(f + j0) & 7) == 0) return *reinterpret_cast<const u64*>(f + j0);
+  u64 v = 0;
+  for (u32 k = 0; k < 8; ++k) if (j0 + k < n) v |= (u64)f[j0 + k] << (8 * k);
+  return v;
+}
+static_assert(SEL_TILE == 256 * 8, "one 8-byte piece of the flag bytes per thread");
 __global__ __launch_bounds__(256) void k_flag_count(FlagArgs a) {
   __shared__ u32 s_wave[4];
-  const u32 base = blockIdx.x * SEL_TILE;
+  const u64 v = load_flags8(a.rec_flag, blockIdx.x * SEL_TILE + threadIdx.x * 8, a.n);
   u32 c = 0;
 #pragma unroll
-  for (int r = 0; r < SEL_TILE / 256; ++r) {
-    const u32 j = base + r * 256 + threadIdx.x;
-    if (j < a.n) c += a.rec_flag[j] != 0;
-  }
+  for (int k = 0; k < 8; ++k) c += ((v >> (8 * k)) & 0xFF) != 0;
   u32 tot;
   block_exclusive_sum<256>(c, s_wave, &tot);
   if (threadIdx.x == 0) a.tile_flags[blockIdx.x] = tot;
 }
 __global__ __launch_bounds__(256) void k_flag_emit(FlagArgs a) {
   __shared__ u32 s_wave[4];
-  const u32 base = blockIdx.x * SEL_TILE;
-  u32 carry = a.tile_flags[blockIdx.x];
+  const u32 j0 = blockIdx.x * SEL_TILE + threadIdx.x * 8;
   const int rb = a.sf.rb;
   const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
-#pragma unroll 1
-  for (int r = 0; r < SEL_TILE / 256; ++r) {
-    const u32 j = base + r * 256 + threadIdx.x;
-    const u32 f = j < a.n ? a.rec_flag[j] : 0u;
-    u32 tot;
-    const u32 ex = block_exclusive_sum<256>(f != 0, s_wave, &tot);
-    if (f) {
-      const u32 k = carry + ex;
-      a.flag_pos[k] = j;
-      if (a.flag && k < a.flag_cap) {
-        const u64 key = a.key[j];
-        a.flag[(u64)CCLD_FLG_COMM * a.flag_cap + k] = (i64)(key >> (rb + a.sf.ws));
-        a.flag[(u64)CCLD_FLG_SEQ * a.flag_cap + k] = (i64)((key >> rb) & smask);
-        a.flag[(u64)CCLD_FLG_RANK * a.flag_cap + k] = (i64)(key & rmask);
-        a.flag[(u64)CCLD_FLG_KIND * a.flag_cap + k] = (i64)f;
-        a.flag[(u64)CCLD_FLG_LAG_ENTER * a.flag_cap + k] = a.flag_lag[j];
-        a.flag[(u64)CCLD_FLG_LAG_EXIT * a.flag_cap + k] = a.flag_lag[a.cap_n + j];
-      }
+  const u64 v = load_flags8(a.rec_flag, j0, a.n);
+  u32 c = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) c += ((v >> (8 * k)) & 0xFF) != 0;
+  u32 tot;
+  u32 k_out = a.tile_flags[blockIdx.x] + block_exclusive_sum<256>(c, s_wave, &tot);
+  if (c == 0) return;
+  for (u32 b = 0; b < 8; ++b) {
+    const u32 f = (u32)(v >> (8 * b)) & 0xFF;
+    if (!f) continue;
+    const u32 j = j0 + b, k = k_out++;
+    a.flag_pos[k] = j;
+    if (a.flag && k < a.flag_cap) {
+      const u64 key = a.key[j];
+      a.flag[(u64)CCLD_FLG_COMM * a.flag_cap + k] = (i64)(key >> (rb + a.sf.ws));
+      a.flag[(u64)CCLD_FLG_SEQ * a.flag_cap + k] = (i64)((key >> rb) & smask);
+      a.flag[(u64)CCLD_FLG_RANK * a.flag_cap + k] = (i64)(key & rmask);
+      a.flag[(u64)CCLD_FLG_KIND * a.flag_cap + k] = (i64)f;
+      a.flag[(u64)CCLD_FLG_LAG_ENTER * a.flag_cap + k] = a.flag_lag[j];
+      a.flag[(u64)CCLD_FLG_LAG_EXIT * a.flag_cap + k] = a.flag_lag[a.cap_n + j];
     }
-    carry += tot;
   }
 }
 void launch_flag_compact(hipStream_t st, const FlagArgs& a) {
