@@ -42,6 +42,19 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, cons
   for (int t = 0; t < HIST_TILES; ++t) {
     const u32 base = (tile0 + t) * SORT_TILE;
     if (tile0 + t >= n_tiles) continue;
+    if (!FIRST && base + SORT_TILE <= n) {
+      // full tile of a plain array: 16-byte loads, two keys per lane
+      const ulonglong2* __restrict__ in2 = reinterpret_cast<const ulonglong2*>(key_in + base);
+      ulonglong2 kk[SORT_ITEMS / 2];
+#pragma unroll
+      for (int it = 0; it < SORT_ITEMS / 2; ++it) kk[it] = in2[it * SORT_THREADS + tid];
+#pragma unroll
+      for (int it = 0; it < SORT_ITEMS / 2; ++it) {
+        atomicAdd(&s_hist[t][(u32)(kk[it].x >> shift) & dmask], 1u);
+        atomicAdd(&s_hist[t][(u32)(kk[it].y >> shift) & dmask], 1u);
+      }
+      continue;
+    }
 #pragma unroll
     for (int it = 0; it < SORT_ITEMS; ++it) {
       u32 j = base + it * SORT_THREADS + tid;
