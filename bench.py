@@ -31,6 +31,32 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def kernel_sources_digest() -> str:
+    """sha256 over the library's sources: the counters in profiles/ only describe these kernels."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2605_04478_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+    recorded in profiles/window_config3_traffic.json, or None if the kernels have changed since."""
+    path = os.path.join(ROOT, "profiles", "window_config3_traffic.json")
+    try:
+        rec = json.load(open(path))
+        if rec.get("csrc_sha256") != kernel_sources_digest():
+            return None
+        k = rec["kernels"].get(kernel)
+        return None if k is None else k["fetch_bytes"] + k["write_bytes"]
+    except (OSError, ValueError, KeyError):
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -41,6 +67,10 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-cycles", type=int, default=2000, help="cycles of the trace given to the CPU oracle")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--workload", choices=("trace", "stream", "hang"), default="trace",
+                    help="trace: the 4,096-rank trace (default, the headline metric); stream: sliding window at "
+                         "16,384 ranks, per-step latency; hang: hang location on 17M snapshot rows")
+    ap.add_argument("--stream-steps", type=int, default=600)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (torch) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -58,6 +88,11 @@ def main() -> int:
         return 2
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.workload == "stream":
+        return bench_stream(args, torch, np, ccld, tg)
+    if args.workload == "hang":
+        return bench_hang(args, torch, np, ccld, tg)
 
     spec = tg.config3(n_cycles=args.cycles, seed=args.seed)
     t0 = time.time()
@@ -116,15 +151,16 @@ def main() -> int:
     #  scatter  pass 1 reads the key and writes key + index (20 B); later passes move key + index (24 B);
     #           when key bits + index bits <= 64 the passes move one packed word (16 B) and the last
     #           pass writes key + index (8 B in, 12 B out)
-    #  segments reads key (twice: heads, then analysis) + index, gathers the 32-byte row, writes a
-    #           21-column int64 row per collective and one flag byte per record
+    #  seg_heads reads the sorted key once (collective heads per tile)
+    #  segments reads key + index, gathers the 32-byte row, writes a 21-column int64 row per
+    #           collective and one flag byte per record
     n_seg = int(res.n_seg)
     bl = lambda v: int(v).bit_length()
     key_bits = bl(tr.topo.n_comms - 1) + bl(spec.layout.n_ranks - 1) + bl(int(tr.cols["seq"].max()))
     packed = passes >= 2 and key_bits + bl(n - 1) <= 64      # key and index travel as one 64-bit word
     scatter_bytes = (16.0 * (passes - 1) + 20.0) if packed else (20.0 + 24.0 * (passes - 1))
     alg = {"ingest": n * 81.0, "sort_hist": n * 8.0 * passes, "sort_scatter": n * scatter_bytes,
-           "segments": n * (8.0 + 12.0 + 32.0 + 1.0) + n_seg * 21 * 8.0}
+           "seg_heads": n * 8.0, "segments": n * (12.0 + 32.0 + 1.0) + n_seg * 21 * 8.0}
     kernels = {k: {"ms_per_step": round(v[0] / args.steps, 4), "launches_per_step": v[1] / args.steps}
                for k, v in prof.items() if v[1]}
     for k, b in alg.items():
@@ -137,7 +173,8 @@ def main() -> int:
     d_avg_ms = d_ms / max(d_cnt, 1)
     achieved = alg_bytes_per_launch / (d_avg_ms * 1e-3) / 1e9 if d_avg_ms > 0 else 0.0
     kname = {"ingest": "k_ingest", "sort_hist": "k_radix_hist", "sort_scatter": "k_radix_scatter",
-             "segments": "k_seg_analyze"}[dominant]
+             "seg_heads": "k_seg_count", "segments": "k_seg_wave"}[dominant]
+    traffic = measured_traffic(kname)
 
     cpu = None
     if not args.no_cpu:
@@ -166,12 +203,87 @@ def main() -> int:
                    "groups": int(res.n_group), "sort_passes": passes, "sort_key_bits": key_bits,
                    "sort_packed_words": bool(packed)},
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_ms": d_avg_ms, "launches": d_cnt,
                      "algorithmic_bytes_per_launch": alg_bytes_per_launch},
         "kernels": kernels,
         "cpu_baseline": cpu,
     }
+    print(json.dumps(out), flush=True)
+    an.close()
+    return 0
+
+
+def bench_stream(args, torch, np, ccld, tg) -> int:
+    """16,384 ranks, one-second batches of about 2M records, window of 10 batches kept on the device,
+    a slow rank re-drawn every 30 batches and one hang at batch 300; per-step latency of
+    ingest + analyze_window + rank_blame (the batch is already in HBM when the clock starts)."""
+    ss = tg.config5(n_steps=args.stream_steps, seed=args.seed, hang_step=min(300, args.stream_steps // 2))
+    topo = ss.layout.topology()
+    per = ss.slots_per_step * ss.layout.n_ranks
+    W = 10
+    an = ccld.Analyzer(topo, max_window_records=W * per, max_batch_records=per, window_batches=W,
+                       hang_threshold_ns=5_000_000_000, device="cuda:0")
+    buffers = an.alloc_window_result(W * per, seg_cap=W * per // 4 + 1024, flag_cap=W * per // 8 + 1024,
+                                     group_cap=min(an.n_comms * 1024, 1 << 22))
+    lat, alerts, first_alert, leaders = [], 0, None, []
+    for step in range(ss.n_steps):
+        b = tg.stream_batch(ss, step)
+        cols = an.to_device(b.cols)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        an.ingest(cols)
+        res = an.analyze_window(ss.now_ns(step), buffers=buffers)
+        blame, order = an.rank_blame()
+        torch.cuda.synchronize()
+        lat.append(time.perf_counter() - t0)
+        assert res.status == "OK", res.status
+        if res.n_alert:
+            alerts += 1
+            first_alert = step if first_alert is None else first_alert
+        if step % ss.epoch_steps == ss.epoch_steps - 1:
+            leaders.append(int(order[0]) == ss.slow_rank(step))
+    lat = np.asarray(lat[W:]) * 1e3                  # full windows only
+    out = {"metric": "streaming analysis at 16,384 ranks: per-step analyze latency and records/s", "unit": "records/s",
+           "value": float(per / (lat.mean() * 1e-3)), "n_gpus": 1, "steps": int(lat.shape[0]), "warmup": W,
+           "ms_per_step": float(lat.mean()), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"config 5: 16,384 ranks TP8xPP16xDP128, {per} new records per 1 s step, "
+                                  f"window of {W} steps ({W * per} records) resident on the device",
+                      "latency_ms": {"p50": float(np.percentile(lat, 50)), "p95": float(np.percentile(lat, 95)),
+                                     "max": float(lat.max())},
+                      "window_records_per_s": float(W * per / (lat.mean() * 1e-3)),
+                      "steps_with_hang_alert": alerts, "first_alert_step": first_alert, "hang_step": ss.hang_step,
+                      "slow_rank_led_blame_at_epoch_end": f"{sum(leaders)}/{len(leaders)}"}}
+    print(json.dumps(out), flush=True)
+    an.close()
+    return 0
+
+
+def bench_hang(args, torch, np, ccld, tg) -> int:
+    """Hang location at 4,096 ranks: 16,777,216 snapshot rows resident in HBM."""
+    ht = tg.generate_hang(tg.config4(seed=args.seed))
+    an = ccld.Analyzer(ht.topo, max_window_records=1024, max_snapshot_rows=ht.n, device="cuda:0")
+    cols = an.snapshots_to_device(ht.cols)
+    torch.cuda.synchronize()
+    res = None
+    for _ in range(args.warmup):
+        res = an.locate_hang(cols, 64, 16)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res = an.locate_hang(cols, 64, 16)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    roots = res.root
+    ok = list(roots["rank"]) == [ht.root_rank] and list(roots["comm"]) == [ht.root_comm]
+    out = {"metric": "hang location at 4,096 ranks: snapshot rows analysed/sec", "unit": "rows/s", "value": ht.n / dt,
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": "config 4: 4,096 ranks x {TP,PP,DP,world} x 16 channels x 64 snapshots "
+                                  f"({ht.n} rows, 32 B each), one frozen rank in one DP ring",
+                      "root_found": bool(ok), "hung_communicators": int(res.n_hung_comm),
+                      "algorithmic_GBps": ht.n * 48.0 / dt / 1e9}}
     print(json.dumps(out), flush=True)
     an.close()
     return 0

@@ -81,7 +81,7 @@ class _HangResult(C.Structure):
 _lib: Optional[C.CDLL] = None
 
 PROF_CLASSES = ("ingest", "sort_hist", "sort_scan", "sort_scatter", "segments", "flags", "blame", "groups", "alerts",
-                "hang")
+                "hang", "seg_heads")
 PROF_NCLASS = 16
 
 EXPORTS = ("ccld_profile_enable", "ccld_profile_read", "ccld_default_params", "ccld_query_workspace", "ccld_create", "ccld_destroy", "ccld_ingest",

@@ -408,6 +408,8 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   c->prof.begin();
   launch_seg_count(st, sa);
   launch_scan_tiles(st, c->tile_heads, seg_tiles, &c->counters[CNT_NSEG]);
+  c->prof.end(CCLD_PROF_SEG_HEADS);
+  c->prof.begin();
   launch_seg_analyze(st, sa);
   c->prof.end(CCLD_PROF_SEGMENTS);
   c->prof.begin();
