@@ -62,10 +62,12 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->rec_flag = w.take<uint8_t>(N);
   c->flag_pos = w.take<uint32_t>(N);
   c->flag_lag = w.take<int64_t>(2 * N);
-  c->big_list = w.take<uint32_t>(2 * (seg_tiles + 2));
+  c->big_list = w.take<uint32_t>(3 * (N / 65 + 2));
   c->big_ex = w.take<int64_t>(2 * N);
   c->rank_partial = w.take<uint32_t>((uint64_t)RANKCOUNT_BLOCKS * n_ranks);
   c->blame = w.take<int64_t>((uint64_t)CCLD_BLM_NCOL * n_ranks);
+  c->blame_list = w.take<uint32_t>(2ull * n_ranks);
+  c->blame_tiles = w.take<uint32_t>(n_ranks / SEL_TILE + 3);
   c->usable_list = w.take<uint32_t>(N);
   c->group_first = w.take<uint32_t>(N + 1);
   c->alert_list = w.take<uint32_t>(NT);
@@ -516,7 +518,7 @@ ccld_status ccld_rank_blame(ccld_ctx* c, int64_t* blame, uint32_t* order) {
   if (blame)
     HIP_TRY(hipMemcpyAsync(blame, c->blame, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)n_ranks,
                            hipMemcpyDeviceToDevice, c->stream));
-  if (order) launch_blame_order(c->stream, c->blame, n_ranks, order);
+  if (order) launch_blame_order(c->stream, c->blame, n_ranks, c->blame_list, c->blame_tiles, c->counters, order);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipStreamSynchronize(c->stream));
   return CCLD_OK;

@@ -63,13 +63,12 @@ struct BatchSlot { uint64_t n; };
 struct BatchMeta { uint64_t status; uint64_t max_seq; };
 
 constexpr int SEG_TILE = 1024;       // sorted records owned by one workgroup of the segment kernels
-constexpr int SEG_HALO = 256;        // records past the tile a workgroup may read to finish its last collective
 constexpr int SEG_THREADS = 256;
 constexpr int SEL_TILE = 2048;       // records per workgroup of the compaction kernels
 constexpr int RANKCOUNT_BLOCKS = 2048;
 
 // device counters written by kernels and read back by the host
-enum { CNT_NSEG, CNT_NFLAG, CNT_NBIG, CNT_NUSABLE, CNT_NGROUP, CNT_NALERT, CNT_NCAND, CNT_STATUS, CNT_COUNT = 16 };
+enum { CNT_NSEG, CNT_NFLAG, CNT_NBIG, CNT_NUSABLE, CNT_NGROUP, CNT_NALERT, CNT_NCAND, CNT_STATUS, CNT_NBLAMED, CNT_NCLEAN, CNT_COUNT = 16 };
 
 }  // namespace ccld
 
@@ -104,10 +103,12 @@ struct ccld_ctx {
   uint8_t* rec_flag;                  // [cap]
   uint32_t* flag_pos;                 // [cap] sorted position of the k-th flagged record
   int64_t* flag_lag;                  // [2][cap]
-  uint32_t* big_list;                 // [cap / SEG_HALO + 2][2]  (segment ordinal, first position)
+  uint32_t* big_list;                 // [cap / 65 + 2][3]  (segment ordinal, first position, length) of the collectives over 64 records
   int64_t* big_ex;                    // [2][cap]
   uint32_t* rank_partial;             // [RANKCOUNT_BLOCKS][n_ranks]
   int64_t* blame;                     // [CCLD_BLM_NCOL][n_ranks]
+  uint32_t* blame_list;               // [2][n_ranks] flagged ranks, then the others, each ascending
+  uint32_t* blame_tiles;              // [n_ranks / SEL_TILE + 3]
   uint32_t* usable_list;              // [cap]
   uint32_t* group_first;              // [cap + 1]
   uint32_t* alert_list;               // [cap]

@@ -1,8 +1,9 @@
 // Per-collective statistics for gfx950.  Collectives of up to 64 records are packed side by side
 // into the lanes of a wavefront and sorted there with a bitonic network whose exchanges are DPP
 // row operations wherever the lane pattern allows, which yields minimum, exact lower median
-// (order statistic floor((n-1)/2)), maximum, and then the median absolute deviation; longer
-// collectives take a workgroup each.
+// (order statistic floor((n-1)/2)), maximum, and then the median absolute deviation.  Collectives
+// of 65 to 2,048 records are sorted in LDS by one wavefront (up to 512) or one workgroup; longer
+// ones take the counting selection of k_seg_big.
 #include "window_kernels.h"
 #include "device_utils.h"
 
@@ -13,7 +14,9 @@
 namespace ccld {
 
 constexpr i64 T_INFLIGHT = INT64_MAX;
-constexpr int SEG_WAVE_MAX = 64;     // longest collective handled inside one wavefront
+constexpr int SEG_WAVE_MAX = 64;     // longest collective handled inside one wavefront's registers
+constexpr int SEG_TEAM_WAVE = 512;   // longest collective one wavefront sorts in LDS
+constexpr int SEG_TEAM_MAX = 2048;   // longest collective a workgroup sorts in LDS
 
 __device__ __forceinline__ u64 atomic_add_u64(u64* p, u64 v) {
   return atomicAdd((unsigned long long*)p, (unsigned long long)v);
@@ -125,8 +128,8 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
     const bool valid = small && l < n;
     if (n > (u32)SEG_WAVE_MAX && l == 0) {            // too long for a wavefront: leave it to k_seg_big
       const u64 slot = atomic_add_u64(&a.counters[CNT_NBIG], 1);
-      a.big_list[2 * slot] = seg0 + sl;
-      a.big_list[2 * slot + 1] = base + a0;
+      a.big_list[3 * slot] = seg0 + sl;
+      a.big_list[3 * slot + 1] = base + a0;
     }
     u64 key = 0, nb = 0;
     i64 e = 0, x = T_INFLIGHT;
@@ -264,8 +267,187 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
   else seg_wave_batches<64>(a, base, seg0, nheads, s_head, lane, wave);
 }
 
-// Collectives too long for a tile plus halo: one workgroup per collective, values staged in
-// global scratch, the same counting selection with all reads broadcast across the workgroup.
+// ---- collectives of 65 to SEG_TEAM_MAX records -------------------------------------------------
+// length of every listed collective, capped at SEG_TEAM_MAX + 1: one wavefront per entry walks the
+// sorted keys from the collective's first record until the (communicator, counter) prefix changes
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_lengths(SegArgs a) {
+  const u32 nbig = (u32)a.counters[CNT_NBIG];
+  const u32 lane = lane_id(), nw = SEG_THREADS / CCLD_WAVE;
+  const int rb = a.sf.rb;
+  for (u32 ent = blockIdx.x * nw + threadIdx.x / CCLD_WAVE; ent < nbig; ent += gridDim.x * nw) {
+    const u32 a0 = a.big_list[3 * ent + 1];
+    const u64 pref = a.key[a0] >> rb;
+    u32 len = SEG_TEAM_MAX + 1;
+    for (u32 o = 1; o <= (u32)SEG_TEAM_MAX + 1; o += CCLD_WAVE) {
+      const u64 j = (u64)a0 + o + lane;
+      const u64 m = ballot64(j >= a.n || (a.key[j] >> rb) != pref);
+      if (m) { len = o + (u32)__builtin_ctzll(m); break; }
+    }
+    if (lane == 0) a.big_list[3 * ent + 2] = len < (u32)SEG_TEAM_MAX + 1 ? len : (u32)SEG_TEAM_MAX + 1;
+  }
+}
+
+struct TeamAcc {
+  unsigned long long imin;
+  long long dmin, dmax;
+  u32 ninfl, incons, rmin, rmax;
+};
+
+// threads of a team wait for each other's LDS traffic: a wavefront's LDS operations complete in
+// issue order, so a single-wavefront team only has to keep the compiler from moving them
+template <int WAVES>
+__device__ __forceinline__ void team_sync() {
+  if constexpr (WAVES == 1) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  } else {
+    __syncthreads();
+  }
+}
+
+// one compare-exchange step of the network over v[0, P): partner of i is i ^ M, the element whose
+// bit HB (the top bit of M) is clear keeps the smaller value
+template <int WAVES>
+__device__ __forceinline__ void team_cmpx(i64* v, u32 P, u32 M, u32 HB, u32 t) {
+  for (u32 p = t; p < P / 2; p += CCLD_WAVE * WAVES) {
+    const u32 lo = p & (HB - 1), ia = ((p - lo) << 1) | lo, ib = ia ^ M;
+    const i64 va = v[ia], vb = v[ib];
+    if (vb < va) { v[ia] = vb; v[ib] = va; }
+  }
+  team_sync<WAVES>();
+}
+// ascending bitonic sort of v[0, P), P a power of two (same merges as sort_groups, in LDS)
+template <int WAVES>
+__device__ __forceinline__ void team_sort(i64* v, u32 P, u32 t) {
+  for (u32 k = 2; k <= P; k <<= 1) {
+    team_cmpx<WAVES>(v, P, k - 1, k >> 1, t);
+    for (u32 j = k >> 2; j; j >>= 1) team_cmpx<WAVES>(v, P, j, j, t);
+  }
+}
+
+// A team of WAVES wavefronts per collective; arrival and completion times are staged in LDS and a
+// third LDS array is sorted four times (arrival, completion, and their absolute deviations).
+template <int WAVES>
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
+  constexpr u32 TEAMS = SEG_THREADS / CCLD_WAVE / WAVES, TT = CCLD_WAVE * WAVES;
+  constexpr u32 CAPN = SEG_TEAM_WAVE * WAVES;
+  constexpr u32 LO = WAVES == 1 ? (u32)SEG_WAVE_MAX + 1 : (u32)SEG_TEAM_WAVE + 1;
+  __shared__ i64 s_e[TEAMS][CAPN], s_x[TEAMS][CAPN], s_v[TEAMS][CAPN];
+  __shared__ TeamAcc s_acc[TEAMS];
+  const u32 team = threadIdx.x / TT, t = threadIdx.x % TT;
+  i64 *E = s_e[team], *X = s_x[team], *V = s_v[team];
+  TeamAcc& acc = s_acc[team];
+  const int rb = a.sf.rb;
+  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  const u32 nbig = (u32)a.counters[CNT_NBIG];
+  for (u32 ent = blockIdx.x * TEAMS + team; ent < nbig; ent += gridDim.x * TEAMS) {
+    const u32 nn = a.big_list[3 * ent + 2];
+    if (nn < LO || nn > CAPN) continue;
+    const u32 srow = a.big_list[3 * ent], a0 = a.big_list[3 * ent + 1];
+    const u64 k0 = a.key[a0];
+    const Row h = a.row[a.idx[a0]];
+    if (t == 0) {
+      acc.imin = (unsigned long long)T_INFLIGHT; acc.dmin = INT64_MAX; acc.dmax = INT64_MIN;
+      acc.ninfl = 0; acc.incons = 0; acc.rmin = 0xFFFFFFFFu; acc.rmax = 0xFFFFFFFFu;
+    }
+    team_sync<WAVES>();
+    {
+      u32 ni = 0, rmin = 0xFFFFFFFFu, rmax = 0xFFFFFFFFu;
+      bool inc = false;
+      i64 imin = T_INFLIGHT, dmin = INT64_MAX, dmax = INT64_MIN;
+      for (u32 i = t; i < nn; i += TT) {
+        const u32 j = a0 + i;
+        const Row rw = a.row[a.idx[j]];
+        E[i] = rw.t_enter; X[i] = rw.t_exit;
+        inc |= (rw.op != h.op || rw.bytes != h.bytes);
+        if (rw.t_exit == T_INFLIGHT) {
+          ++ni; imin = rw.t_enter < imin ? rw.t_enter : imin;
+        } else {
+          const i64 d = rw.t_exit - rw.t_enter;
+          const u32 rk = (u32)(a.key[j] & rmask);
+          if (d < dmin || (d == dmin && rk < rmin)) { dmin = d; rmin = rk; }
+          if (d > dmax || (d == dmax && rk < rmax)) { dmax = d; rmax = rk; }
+        }
+      }
+      if (ni) { atomicAdd(&acc.ninfl, ni); atomicMin(&acc.imin, (unsigned long long)imin); }
+      if (inc) atomicOr(&acc.incons, 1u);
+      if (rmin != 0xFFFFFFFFu) { atomicMin(&acc.dmin, (long long)dmin); atomicMax(&acc.dmax, (long long)dmax); }
+      team_sync<WAVES>();
+      if (rmin != 0xFFFFFFFFu && dmin == (i64)acc.dmin) atomicMin(&acc.rmin, rmin);
+      if (rmax != 0xFFFFFFFFu && dmax == (i64)acc.dmax) atomicMin(&acc.rmax, rmax);
+    }
+    const u32 ninfl = acc.ninfl, nd = nn - ninfl;
+    const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
+    u32 P = 2;
+    while (P < nn) P <<= 1;
+    for (u32 i = t; i < P; i += TT) V[i] = (i < nn && X[i] != T_INFLIGHT) ? E[i] : T_INFLIGHT;
+    team_sync<WAVES>();
+    team_sort<WAVES>(V, P, t);
+    const i64 min_e = V[0], med_e = V[km], max_e = V[kl];
+    team_sync<WAVES>();
+    for (u32 i = t; i < P; i += TT) V[i] = i < nn ? X[i] : T_INFLIGHT;
+    team_sync<WAVES>();
+    team_sort<WAVES>(V, P, t);
+    const i64 min_x = V[0], med_x = V[km], max_x = V[kl];
+    team_sync<WAVES>();
+    for (u32 i = t; i < P; i += TT) V[i] = (i < nn && X[i] != T_INFLIGHT) ? absdiff(E[i], med_e) : T_INFLIGHT;
+    team_sync<WAVES>();
+    team_sort<WAVES>(V, P, t);
+    const i64 mad_e = V[km];
+    team_sync<WAVES>();
+    for (u32 i = t; i < P; i += TT) V[i] = (i < nn && X[i] != T_INFLIGHT) ? absdiff(X[i], med_x) : T_INFLIGHT;
+    team_sync<WAVES>();
+    team_sort<WAVES>(V, P, t);
+    const i64 mad_x = V[km];
+    const u32 comm = (u32)(k0 >> (rb + a.sf.ws));
+    const bool complete = nn == a.comm_size[comm] && ninfl == 0;
+    const bool consistent = acc.incons == 0;
+    const bool barrier = h.op == CCLD_OP_ALLREDUCE && h.bytes < (u64)a.barrier_bytes;
+    const bool usable = complete && consistent && !barrier;
+    if (t == 0) {
+      seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> rb) & smask));
+      seg_put(a, CCLD_SEG_N, srow, (i64)nn);
+      seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
+      seg_put(a, CCLD_SEG_STATE, srow,
+              (complete ? CCLD_SEG_COMPLETE : 0) | (consistent ? CCLD_SEG_CONSISTENT : 0) |
+                  (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+      seg_put(a, CCLD_SEG_OP, srow, (i64)h.op);
+      seg_put(a, CCLD_SEG_BYTES, srow, (i64)h.bytes);
+      seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, (i64)acc.imin);
+      seg_put(a, CCLD_SEG_FIRST, srow, (i64)a0);
+      if (nd == 0) {
+        seg_put_empty_stats(a, srow);
+      } else {
+        seg_put(a, CCLD_SEG_ENTER_MIN, srow, min_e); seg_put(a, CCLD_SEG_ENTER_MED, srow, med_e);
+        seg_put(a, CCLD_SEG_ENTER_MAX, srow, max_e); seg_put(a, CCLD_SEG_ENTER_MAD, srow, mad_e);
+        seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
+        seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
+        seg_put(a, CCLD_SEG_DUR_MIN, srow, (i64)acc.dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, (i64)acc.dmax);
+        seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)acc.rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)acc.rmax);
+      }
+    }
+    for (u32 i = t; i < nn; i += TT) {
+      const u32 j = a0 + i;
+      i64 le = 0, lx = 0;
+      u32 f = 0;
+      if (usable) {
+        le = E[i] - med_e; lx = X[i] - med_x;
+        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
+        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
+      }
+      a.rec_flag[j] = (uint8_t)f;
+      if (a.lag_e) a.lag_e[j] = le;
+      if (a.lag_x) a.lag_x[j] = lx;
+      if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
+    }
+    team_sync<WAVES>();     // the staged times and the accumulator are reused by the next collective
+  }
+}
+
+// Collectives longer than SEG_TEAM_MAX records: one workgroup per collective, values staged in
+// global scratch, order statistics by counting with all reads broadcast across the workgroup.
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
   __shared__ u32 s_end, s_ninfl, s_incons;
   __shared__ unsigned long long s_imin;
@@ -277,7 +459,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
   i64* big_x = a.big_ex + a.cap_n;
   const u32 nbig = (u32)a.counters[CNT_NBIG];
   for (u32 ent = blockIdx.x; ent < nbig; ent += gridDim.x) {
-    const u32 srow = a.big_list[2 * ent], a0 = a.big_list[2 * ent + 1];
+    if (a.big_list[3 * ent + 2] <= (u32)SEG_TEAM_MAX) continue;    // a team kernel has taken it
+    const u32 srow = a.big_list[3 * ent], a0 = a.big_list[3 * ent + 1];
     const u64 k0 = a.key[a0];
     const u64 pref = k0 >> rb;
     if (tid == 0) { s_end = a.n; s_ninfl = 0; s_incons = 0; s_imin = (unsigned long long)T_INFLIGHT; }
@@ -390,6 +573,9 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
 void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
   if (a.n == 0) return;
   hipLaunchKernelGGL(k_seg_wave, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
+  hipLaunchKernelGGL(k_seg_lengths, dim3(1024), dim3(SEG_THREADS), 0, st, a);
+  hipLaunchKernelGGL(k_seg_team<1>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+  hipLaunchKernelGGL(k_seg_team<4>, dim3(1024), dim3(SEG_THREADS), 0, st, a);
   hipLaunchKernelGGL(k_seg_big, dim3(2048), dim3(SEG_THREADS), 0, st, a);
 }
 

@@ -378,30 +378,49 @@ void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* s
                      rec_flag, flag_lag, cap_n, n_ranks, blame);
 }
 
-// order[] = ranks by (flags descending, summed lag descending, rank ascending): one wavefront per
-// rank counts the ranks that precede it
+// order[] = ranks by (flags descending, summed lag descending, rank ascending).  Ranks with any
+// flag come first and only they need ranking: a wavefront per flagged rank counts the flagged
+// ranks that precede it.  The ranks without a flag follow in ascending order.
+struct PredBlamed {
+  const i64 *ne, *nx;
+  bool want;
+  __device__ bool operator()(u32 r) const { return ((ne[r] + nx[r]) != 0) == want; }
+};
 __global__ __launch_bounds__(256) void k_blame_order(const i64* __restrict__ blame, u32 n_ranks,
+                                                     const u32* __restrict__ lists, const u64* __restrict__ counters,
                                                      u32* __restrict__ order) {
-  const u32 r = blockIdx.x * 4 + threadIdx.x / CCLD_WAVE;
-  if (r >= n_ranks) return;
+  const u32 nb = (u32)counters[CNT_NBLAMED];
   const u32 lane = lane_id();
   const i64* NE = blame + (u64)CCLD_BLM_N_LATE_ENTER * n_ranks;
   const i64* NX = blame + (u64)CCLD_BLM_N_LATE_EXIT * n_ranks;
   const i64* SE = blame + (u64)CCLD_BLM_SUM_LAG_ENTER * n_ranks;
   const i64* SX = blame + (u64)CCLD_BLM_SUM_LAG_EXIT * n_ranks;
-  const i64 myn = NE[r] + NX[r];
-  const i64 mys = (i64)((u64)SE[r] + (u64)SX[r]);
-  u32 before = 0;
-  for (u32 o = lane; o < n_ranks; o += CCLD_WAVE) {
-    const i64 on = NE[o] + NX[o];
-    const i64 os = (i64)((u64)SE[o] + (u64)SX[o]);
-    before += (on > myn) || (on == myn && (os > mys || (os == mys && o < r)));
+  for (u32 q = blockIdx.x * 4 + threadIdx.x / CCLD_WAVE; q < nb; q += gridDim.x * 4) {
+    const u32 r = lists[q];
+    const i64 myn = NE[r] + NX[r];
+    const i64 mys = (i64)((u64)SE[r] + (u64)SX[r]);
+    u32 before = 0;
+    for (u32 i = lane; i < nb; i += CCLD_WAVE) {
+      const u32 o = lists[i];
+      const i64 on = NE[o] + NX[o];
+      const i64 os = (i64)((u64)SE[o] + (u64)SX[o]);
+      before += (on > myn) || (on == myn && (os > mys || (os == mys && o < r)));
+    }
+    before = wave_sum(before);
+    if (lane == 0) order[before] = r;
   }
-  before = wave_sum(before);
-  if (lane == 0) order[before] = r;
+  const u32 stride = gridDim.x * 256;
+  for (u32 i = blockIdx.x * 256 + threadIdx.x; i < n_ranks - nb; i += stride) order[nb + i] = lists[n_ranks + i];
 }
-void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, uint32_t* order) {
-  hipLaunchKernelGGL(k_blame_order, dim3((n_ranks + 3) / 4), dim3(256), 0, st, blame, n_ranks, order);
+void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, uint32_t* lists,
+                        uint32_t* tile_counts, uint64_t* counters, uint32_t* order) {
+  PredBlamed p{blame + (u64)CCLD_BLM_N_LATE_ENTER * n_ranks, blame + (u64)CCLD_BLM_N_LATE_EXIT * n_ranks, true};
+  run_select(st, p, n_ranks, tile_counts, lists, &counters[CNT_NBLAMED]);
+  p.want = false;
+  run_select(st, p, n_ranks, tile_counts, lists + n_ranks, &counters[CNT_NCLEAN]);
+  const u32 blocks = std::min<u32>((n_ranks + 3) / 4, 4096);
+  hipLaunchKernelGGL(k_blame_order, dim3(std::max<u32>(blocks, 1)), dim3(256), 0, st, blame, n_ranks,
+                     (const u32*)lists, (const u64*)counters, order);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -73,7 +73,8 @@ void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag
 void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* sidx, uint32_t n_flag,
                          const uint32_t* flag_pos, const uint8_t* rec_flag, const int64_t* flag_lag,
                          uint64_t cap_n, uint32_t n_ranks, int64_t* blame);
-void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, uint32_t* order);
+void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, uint32_t* lists,
+                        uint32_t* tile_counts, uint64_t* counters, uint32_t* order);
 
 struct GroupArgs {
   const int64_t* seg;

@@ -105,13 +105,13 @@ def test_config3_layout_parity():
     assert g.n_flag > 0
 
 
-def test_random_partial_rounds_with_ties():
+@pytest.mark.parametrize("R,n_seq", [(70, 400), (700, 60)])
+def test_random_partial_rounds_with_ties(R, n_seq):
     rng = np.random.default_rng(3)
-    R = 70
     topo = ring_topology(R, comms=[list(range(R)), list(range(0, R, 2)), [1, 3, 5]])
     rows = []
     for c, members in enumerate([list(range(R)), list(range(0, R, 2)), [1, 3, 5]]):
-        for s in range(400):
+        for s in range(n_seq):
             n = int(rng.integers(1, len(members) + 1)) if rng.random() < 0.5 else len(members)
             ranks = rng.choice(members, n, replace=False)
             te = T0 + s * 1000 + rng.integers(0, 6, n)
@@ -125,9 +125,11 @@ def test_random_partial_rounds_with_ties():
              tbase_init_ns=2, kmad_num=1, kmad_den=1)
 
 
-@pytest.mark.parametrize("size,rounds", [(257, 9), (1500, 5), (3000, 3)])
+@pytest.mark.parametrize("size,rounds", [(65, 6), (128, 6), (257, 9), (512, 4), (513, 4), (1500, 5), (2048, 3),
+                                         (2049, 3), (3000, 3)])
 def test_large_communicators_cross_tiles(size, rounds):
-    """Collectives larger than a wavefront, than the halo and than a whole tile."""
+    """Collectives at both edges of every size class: one wavefront in LDS (65-512), one workgroup
+    in LDS (513-2048), counting selection (beyond), spanning tile boundaries."""
     rng = np.random.default_rng(size)
     topo = ring_topology(size, comms=[list(range(size)), [0, 1, 2, 3]])
     rows = []
