@@ -156,7 +156,8 @@ def main() -> int:
     #           collective and one flag byte per record
     n_seg = int(res.n_seg)
     bl = lambda v: int(v).bit_length()
-    key_bits = bl(tr.topo.n_comms - 1) + bl(spec.layout.n_ranks - 1) + bl(int(tr.cols["seq"].max()))
+    # key = (communicator, operation counter, member slot inside the communicator)
+    key_bits = bl(tr.topo.n_comms - 1) + bl(int(np.max(tr.topo.size)) - 1) + bl(int(tr.cols["seq"].max()))
     packed = passes >= 2 and key_bits + bl(n - 1) <= 64      # key and index travel as one 64-bit word
     scatter_bytes = (16.0 * (passes - 1) + 20.0) if packed else (20.0 + 24.0 * (passes - 1))
     alg = {"ingest": n * 81.0, "sort_hist": n * 8.0 * passes, "sort_scatter": n * scatter_bytes,

@@ -39,7 +39,8 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->topo.tree_parent = w.take<int32_t>(n_members);
   c->topo.rank_comm_off = w.take<uint32_t>((uint64_t)n_ranks + 1);
   c->topo.rank_comms = w.take<uint32_t>(n_members);
-  c->topo.rank_comms4 = w.take<uint32_t>(4ull * n_ranks);
+  c->topo.rank_slots = w.take<uint32_t>(n_members);
+  c->topo.rank_memb4 = w.take<uint32_t>(4ull * n_ranks);
   // window
   c->win_key = w.take<uint64_t>(N);
   c->win_row = w.take<Row>(N);
@@ -194,19 +195,22 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   ccld_status s = ccld_query_workspace(params, topo, max_window_records, max_batch_records, max_snapshot_rows, &need);
   if (s != CCLD_OK) return s;
   if (workspace_bytes < need || ((uintptr_t)workspace & 255) != 0) return CCLD_E_WORKSPACE;
-  const int rb = bits_for_host(topo->n_ranks - 1), cb = bits_for_host(topo->n_comms - 1);
-  if (rb + cb > 63) return CCLD_E_KEY_WIDTH;
+  uint32_t max_size = 1;
+  for (uint32_t k = 0; k < topo->n_comms; ++k) max_size = std::max(max_size, topo->size[k]);
+  const int mb = bits_for_host(max_size - 1), cb = bits_for_host(topo->n_comms - 1);
+  if (mb + cb > 63) return CCLD_E_KEY_WIDTH;
   ccld_ctx* c = new (std::nothrow) ccld_ctx();
   if (!c) return CCLD_E_BAD_ARG;
   c->p = *params;
   c->stream = (hipStream_t)hip_stream;
   c->cap = max_window_records; c->batch_cap = max_batch_records; c->snap_cap = max_snapshot_rows;
-  c->kf.rb = rb; c->kf.cb = cb; c->kf.sb = 64 - rb - cb;
+  c->kf.mb = mb; c->kf.cb = cb; c->kf.sb = 64 - mb - cb;
+  c->rank_bits = bits_for_host(topo->n_ranks - 1);
   c->head = 0; c->count = 0; c->next_slot = 0; c->total_ingested = 0;
   c->bshift = cb > 6 ? cb - 6 : 0;        // at most 64 buckets: long runs per workgroup, payload gathers stay inside one bucket
   c->n_buckets = ((topo->n_comms - 1) >> c->bshift) + 1;
   c->sorted_buf = 0; c->last_n = 0; c->blame_valid = false; c->sort_passes = 0;
-  c->sf.rb = rb; c->sf.ws = 0;
+  c->sf.mb = mb; c->sf.ws = 0;
   uint64_t n_members = 0;
   check_topology(topo, &n_members);
   Carver w{(uint8_t*)workspace, 0};
@@ -217,7 +221,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
 
   // derived host tables: sorted member lists, rank -> communicators CSR
   std::vector<uint32_t> sorted(topo->members, topo->members + n_members), sslot(n_members);
-  std::vector<uint32_t> rc_off((size_t)topo->n_ranks + 1, 0), rc(n_members);
+  std::vector<uint32_t> rc_off((size_t)topo->n_ranks + 1, 0), rc(n_members), rs_slot(n_members);
   std::vector<int32_t> parent(n_members, -1);
   for (uint32_t k = 0; k < topo->n_comms; ++k) {
     {
@@ -236,14 +240,17 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   {
     std::vector<uint32_t> fill(rc_off.begin(), rc_off.end() - 1);
     for (uint32_t k = 0; k < topo->n_comms; ++k)
-      for (uint32_t q = 0; q < topo->size[k]; ++q) rc[fill[topo->members[topo->member_off[k] + q]]++] = k;
+      for (uint32_t q = 0; q < topo->size[k]; ++q) {
+        const uint32_t at = fill[sorted[topo->member_off[k] + q]]++;
+        rc[at] = k; rs_slot[at] = q;
+      }
   }
   if (topo->tree_parent) parent.assign(topo->tree_parent, topo->tree_parent + n_members);
   std::vector<uint32_t> rc4(4ull * topo->n_ranks, 0xFFFFFFFFu);
-  bool fits4 = true;
-  for (uint32_t r = 0; r < topo->n_ranks; ++r) {
+  bool fits4 = mb + cb <= 31;       // a padding word then never matches a communicator id
+  for (uint32_t r = 0; fits4 && r < topo->n_ranks; ++r) {
     if (rc_off[r + 1] - rc_off[r] > 4) { fits4 = false; break; }
-    for (uint32_t q = rc_off[r]; q < rc_off[r + 1]; ++q) rc4[4ull * r + (q - rc_off[r])] = rc[q];
+    for (uint32_t q = rc_off[r]; q < rc_off[r + 1]; ++q) rc4[4ull * r + (q - rc_off[r])] = (rc[q] << mb) | rs_slot[q];
   }
 
   ccld_status rs = CCLD_OK;
@@ -260,8 +267,9 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   up(c->topo.tree_parent, parent.data(), 4ull * n_members);
   up(c->topo.rank_comm_off, rc_off.data(), 4ull * rc_off.size());
   up(c->topo.rank_comms, rc.data(), 4ull * n_members);
-  up(c->topo.rank_comms4, rc4.data(), 4ull * rc4.size());
-  if (!fits4) c->topo.rank_comms4 = nullptr;
+  up(c->topo.rank_slots, rs_slot.data(), 4ull * n_members);
+  up(c->topo.rank_memb4, rc4.data(), 4ull * rc4.size());
+  if (!fits4) c->topo.rank_memb4 = nullptr;
   if (hipMemsetAsync(c->gstate, 0, sizeof(GroupState) * (uint64_t)topo->n_comms * GROUP_SLOTS, c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->batch_meta, 0, sizeof(BatchMeta) * ((uint64_t)c->p.window_batches + 2), c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, c->stream) != hipSuccess) rs = CCLD_E_HIP;
@@ -380,17 +388,17 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   if (n == 0) { HIP_TRY(hipStreamSynchronize(st)); c->blame_valid = true; return o->status; }
 
   // 2. sort by (communicator, operation counter, rank) on the significant bits only
-  const int rb = c->kf.rb, cb = c->kf.cb, ws = bits_for_host(max_seq);
-  c->sf.rb = rb; c->sf.ws = ws;
+  const int mb = c->kf.mb, cb = c->kf.cb, ws = bits_for_host(max_seq);
+  c->sf.mb = mb; c->sf.ws = ws;
   KeySource src;
   src.key = c->win_key; src.head = (uint32_t)c->head; src.cap = (uint32_t)c->cap;
   src.squeeze = cb > 0 ? 1 : 0;
   src.hi_shift = cb > 0 ? 64 - cb : 0;
-  src.lo_bits = rb + ws;
-  src.lo_mask = (rb + ws) >= 64 ? ~0ull : (((uint64_t)1 << (rb + ws)) - 1);
-  const int sorted = radix_sort_pairs(st, src, n, c->sb, rb + ws + cb, &c->prof, CCLD_PROF_SORT_HIST,
+  src.lo_bits = mb + ws;
+  src.lo_mask = (mb + ws) >= 64 ? ~0ull : (((uint64_t)1 << (mb + ws)) - 1);
+  const int sorted = radix_sort_pairs(st, src, n, c->sb, mb + ws + cb, &c->prof, CCLD_PROF_SORT_HIST,
                                       CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER);
-  c->sort_passes = (rb + ws + cb) <= 0 ? 1 : (rb + ws + cb + SORT_RBITS - 1) / SORT_RBITS;
+  c->sort_passes = (mb + ws + cb) <= 0 ? 1 : (mb + ws + cb + SORT_RBITS - 1) / SORT_RBITS;
   if (sorted < 0) return o->status = CCLD_E_HIP;
   c->sorted_buf = sorted;
   const uint64_t* skey = c->sb.key[sorted];
@@ -400,6 +408,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   SegArgs sa;
   std::memset(&sa, 0, sizeof(sa));
   sa.key = skey; sa.idx = sidx; sa.row = c->win_row; sa.n = n; sa.sf = c->sf; sa.comm_size = c->topo.size;
+  sa.member_off = c->topo.member_off; sa.members_sorted = c->topo.members_sorted;
   sa.tile_heads = c->tile_heads; sa.seg = o->seg; sa.seg_cap = o->seg_cap;
   sa.rec_flag = o->rec_flag ? o->rec_flag : c->rec_flag;
   sa.lag_e = o->lag_enter; sa.lag_x = o->lag_exit; sa.flag_lag = c->flag_lag; sa.cap_n = c->cap;
@@ -415,11 +424,12 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   launch_seg_analyze(st, sa);
   c->prof.end(CCLD_PROF_SEGMENTS);
   c->prof.begin();
-  launch_rank_count(st, skey, n, rb, n_ranks, c->rank_partial, c->blame);
+  launch_rank_count(st, skey, n, c->sf, c->topo, c->rank_partial, c->blame);
   c->prof.end(CCLD_PROF_BLAME);
   FlagArgs fa;
   std::memset(&fa, 0, sizeof(fa));
   fa.key = skey; fa.rec_flag = sa.rec_flag; fa.flag_lag = c->flag_lag; fa.cap_n = c->cap; fa.n = n; fa.sf = c->sf;
+  fa.member_off = c->topo.member_off; fa.members_sorted = c->topo.members_sorted;
   fa.tile_flags = c->tile_flags; fa.flag_pos = c->flag_pos; fa.flag = o->flag; fa.flag_cap = o->flag_cap;
   fa.counters = c->counters;
   c->prof.begin();
@@ -443,9 +453,9 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   if (n_flag) {
     uint64_t* bk = c->keyC;       // keys are written to C, first pass sorts C -> buffer 0 of sb2
     c->prof.begin();
-    launch_blame_keys(st, skey, c->flag_pos, n_flag, rb, bk);
+    launch_blame_keys(st, skey, c->flag_pos, n_flag, c->sf, c->topo, bk);
     KeySource bs; bs.key = bk; bs.head = 0; bs.cap = n_flag; bs.squeeze = 0; bs.hi_shift = 0; bs.lo_bits = 0; bs.lo_mask = 0;
-    const int r2 = radix_sort_pairs(st, bs, n_flag, sb2, rb);
+    const int r2 = radix_sort_pairs(st, bs, n_flag, sb2, c->rank_bits);
     if (r2 < 0) return o->status = CCLD_E_HIP;
     launch_blame_reduce(st, sb2.key[r2], sb2.idx[r2], n_flag, c->flag_pos, sa.rec_flag, c->flag_lag, c->cap, n_ranks, c->blame);
     c->prof.end(CCLD_PROF_BLAME);

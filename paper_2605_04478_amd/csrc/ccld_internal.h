@@ -11,23 +11,25 @@
 namespace ccld {
 
 // One stored record: the payload the analysis gathers by sorted position (32 bytes, one
-// aligned access); rank, communicator and sequence number live in the key.
+// aligned access); communicator, sequence number and member slot live in the key.
 struct __attribute__((aligned(32))) Row {
   int64_t t_enter, t_exit;
   uint64_t bytes;
   uint32_t op, pad;
 };
 
-// Key layout at ingest: comm << (64 - cb) | seq << rb | rank, with rb / cb the bit widths of
-// the largest rank / communicator id.  The sort squeezes the unused middle bits out.
+// Key layout at ingest: comm << (64 - cb) | seq << mb | slot.  slot is the record's rank counted
+// among its communicator's members in ascending rank order, so keys order like (comm, seq, rank)
+// while the field needs only as many bits as the largest communicator has members; mb / cb are
+// the bit widths of the largest slot / communicator id.  The sort squeezes the unused middle bits out.
 struct KeyFormat {
-  int rb, cb;          // rank bits, communicator bits
-  int sb;              // bits available to the sequence number: 64 - rb - cb
+  int mb, cb;          // member-slot bits, communicator bits
+  int sb;              // bits available to the sequence number: 64 - mb - cb
 };
 
-// Squeezed key used from the sort onwards: comm << (rb + ws) | seq << rb | rank.
+// Squeezed key used from the sort onwards: comm << (mb + ws) | seq << mb | slot.
 struct SqueezedFormat {
-  int rb, ws;          // rank bits, sequence bits actually present in this window
+  int mb, ws;          // member-slot bits, sequence bits actually present in this window
 };
 
 struct DeviceTopology {
@@ -41,8 +43,16 @@ struct DeviceTopology {
   const int32_t* tree_parent;
   const uint32_t* rank_comm_off;    // [n_ranks + 1] CSR: communicators each rank belongs to
   const uint32_t* rank_comms;
-  const uint32_t* rank_comms4;      // [n_ranks][4] the same lists padded with 0xFFFFFFFF, or null if a rank is in more than four
+  const uint32_t* rank_slots;       // parallel to rank_comms: the rank's position in members_sorted of that communicator
+  const uint32_t* rank_memb4;       // [n_ranks][4] words comm << mb | position (padded with 0xFFFFFFFF); null if a rank is in more than four communicators or cb + mb > 31
 };
+
+// rank of the record whose key carries (comm, slot)
+__device__ __forceinline__ uint32_t rank_of_slot(const uint32_t* __restrict__ member_off,
+                                                 const uint32_t* __restrict__ members_sorted, uint32_t comm,
+                                                 uint32_t slot) {
+  return members_sorted[member_off[comm] + slot];
+}
 
 // Eq. 1 state and repetition counter of one detection group (communicator, op, size class).
 struct GroupState {
@@ -77,6 +87,7 @@ struct ccld_ctx {
   hipStream_t stream;
   uint64_t cap, batch_cap, snap_cap;
   ccld::KeyFormat kf;
+  int rank_bits;                      // bit width of the largest rank
   // topology
   std::vector<uint32_t> h_size;
   ccld::DeviceTopology topo;

@@ -116,8 +116,8 @@ template <int G>
 __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32 seg0, u32 nheads,
                                                  const unsigned short* s_head, u32 lane, u32 wave) {
   constexpr int SPW = CCLD_WAVE / G, NW = SEG_THREADS / CCLD_WAVE;
-  const int rb = a.sf.rb;
-  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  const int mb = a.sf.mb;
+  const u64 mmask = ((u64)1 << mb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
   const u32 q = lane / G, l = lane % G, gbase = q * G;
   const u64 gmask = (G == 64 ? ~0ull : (((u64)1 << (G & 63)) - 1)) << gbase;
   for (u32 b = wave; b * SPW < nheads; b += NW) {
@@ -133,11 +133,13 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
     }
     u64 key = 0, nb = 0;
     i64 e = 0, x = T_INFLIGHT;
-    u32 op = 0, j = 0;
+    u32 op = 0, j = 0, rank = 0;
     if (valid) {
       j = base + a0 + l;
       key = a.key[j];
       const Row rw = a.row[a.idx[j]];
+      // the slot -> rank lookup overlaps the row gather
+      rank = a.members_sorted[a.member_off[(u32)(key >> (mb + a.sf.ws))] + (u32)(key & mmask)];
       e = rw.t_enter; x = rw.t_exit; nb = rw.bytes; op = rw.op;
     }
     const bool done = valid && x != T_INFLIGHT;
@@ -155,7 +157,6 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
     const i64 sdx = sort_groups<G>(done ? (x >= med_x ? x - med_x : med_x - x) : T_INFLIGHT, lane);
     const i64 mad_e = shfl_i64(sde, gbase + km), mad_x = shfl_i64(sdx, gbase + km);
     // T_min / T_max of the Duration Time with the ranks attaining them (ties: smallest rank)
-    const u32 rank = (u32)(key & rmask);
     i64 dmin = done ? x - e : INT64_MAX, dmax = done ? x - e : INT64_MIN;
     u32 rmin = done ? rank : 0xFFFFFFFFu, rmax = rmin;
     reduce_dur<G, false>(dmin, rmin);
@@ -166,7 +167,7 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
     const bool incons = (ballot64(valid && (nb != hb || op != hop)) & gmask) != 0;
     i64 imin = T_INFLIGHT;
     if (m_infl) imin = reduce_min<G>((valid && !done) ? e : T_INFLIGHT);
-    const u32 comm = (u32)(key >> (rb + a.sf.ws));
+    const u32 comm = (u32)(key >> (mb + a.sf.ws));
     bool usable = false;
     if (valid) {
       const bool complete = n == a.comm_size[comm] && ninfl == 0;
@@ -175,7 +176,7 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
       if (l == 0) {
         const u32 srow = seg0 + sl;
         seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
-        seg_put(a, CCLD_SEG_SEQ, srow, (i64)((key >> rb) & smask));
+        seg_put(a, CCLD_SEG_SEQ, srow, (i64)((key >> mb) & smask));
         seg_put(a, CCLD_SEG_N, srow, (i64)n);
         seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
         seg_put(a, CCLD_SEG_STATE, srow,
@@ -223,13 +224,13 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
   const u32 tile = blockIdx.x, base = tile * SEG_TILE;
   const u32 rem = a.n - base;                                     // records from the tile's start to the end
   const u32 own = rem < (u32)SEG_TILE ? rem : (u32)SEG_TILE;
-  const int rb = a.sf.rb;
+  const int mb = a.sf.mb;
   if (tid == 0) { s_halo_head = rem <= (u32)(SEG_TILE + SEG_WAVE_MAX) ? rem : 0xFFFFu; s_gmax = 0; }
   bool head[OWN];
 #pragma unroll
   for (int r = 0; r < OWN; ++r) {
     const u32 pos = r * SEG_THREADS + tid, j = base + pos;
-    head[r] = pos < own && (j == 0 || (a.key[j - 1] >> rb) != (a.key[j] >> rb));
+    head[r] = pos < own && (j == 0 || (a.key[j - 1] >> mb) != (a.key[j] >> mb));
   }
   __syncthreads();
   u32 carry = 0;
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
     const u32 pos = SEG_TILE + tid;
     if (pos < rem) {
       const u32 j = base + pos;
-      if ((a.key[j - 1] >> rb) != (a.key[j] >> rb)) atomicMin(&s_halo_head, pos);
+      if ((a.key[j - 1] >> mb) != (a.key[j] >> mb)) atomicMin(&s_halo_head, pos);
     }
   }
   __syncthreads();
@@ -273,14 +274,14 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_lengths(SegArgs a) {
   const u32 nbig = (u32)a.counters[CNT_NBIG];
   const u32 lane = lane_id(), nw = SEG_THREADS / CCLD_WAVE;
-  const int rb = a.sf.rb;
+  const int mb = a.sf.mb;
   for (u32 ent = blockIdx.x * nw + threadIdx.x / CCLD_WAVE; ent < nbig; ent += gridDim.x * nw) {
     const u32 a0 = a.big_list[3 * ent + 1];
-    const u64 pref = a.key[a0] >> rb;
+    const u64 pref = a.key[a0] >> mb;
     u32 len = SEG_TEAM_MAX + 1;
     for (u32 o = 1; o <= (u32)SEG_TEAM_MAX + 1; o += CCLD_WAVE) {
       const u64 j = (u64)a0 + o + lane;
-      const u64 m = ballot64(j >= a.n || (a.key[j] >> rb) != pref);
+      const u64 m = ballot64(j >= a.n || (a.key[j] >> mb) != pref);
       if (m) { len = o + (u32)__builtin_ctzll(m); break; }
     }
     if (lane == 0) a.big_list[3 * ent + 2] = len < (u32)SEG_TEAM_MAX + 1 ? len : (u32)SEG_TEAM_MAX + 1;
@@ -338,8 +339,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
   const u32 team = threadIdx.x / TT, t = threadIdx.x % TT;
   i64 *E = s_e[team], *X = s_x[team], *V = s_v[team];
   TeamAcc& acc = s_acc[team];
-  const int rb = a.sf.rb;
-  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  const int mb = a.sf.mb;
+  const u64 mmask = ((u64)1 << mb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
   const u32 nbig = (u32)a.counters[CNT_NBIG];
   for (u32 ent = blockIdx.x * TEAMS + team; ent < nbig; ent += gridDim.x * TEAMS) {
     const u32 nn = a.big_list[3 * ent + 2];
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
           ++ni; imin = rw.t_enter < imin ? rw.t_enter : imin;
         } else {
           const i64 d = rw.t_exit - rw.t_enter;
-          const u32 rk = (u32)(a.key[j] & rmask);
+          const u32 rk = (u32)(a.key[j] & mmask);
           if (d < dmin || (d == dmin && rk < rmin)) { dmin = d; rmin = rk; }
           if (d > dmax || (d == dmax && rk < rmax)) { dmax = d; rmax = rk; }
         }
@@ -400,14 +401,14 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
     team_sync<WAVES>();
     team_sort<WAVES>(V, P, t);
     const i64 mad_x = V[km];
-    const u32 comm = (u32)(k0 >> (rb + a.sf.ws));
+    const u32 comm = (u32)(k0 >> (mb + a.sf.ws));
     const bool complete = nn == a.comm_size[comm] && ninfl == 0;
     const bool consistent = acc.incons == 0;
     const bool barrier = h.op == CCLD_OP_ALLREDUCE && h.bytes < (u64)a.barrier_bytes;
     const bool usable = complete && consistent && !barrier;
     if (t == 0) {
       seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
-      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> rb) & smask));
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> mb) & smask));
       seg_put(a, CCLD_SEG_N, srow, (i64)nn);
       seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
       seg_put(a, CCLD_SEG_STATE, srow,
@@ -425,7 +426,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
         seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
         seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
         seg_put(a, CCLD_SEG_DUR_MIN, srow, (i64)acc.dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, (i64)acc.dmax);
-        seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)acc.rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)acc.rmax);
+        const u32* ms = a.members_sorted + a.member_off[comm];
+        seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)ms[acc.rmin]); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)ms[acc.rmax]);
       }
     }
     for (u32 i = t; i < nn; i += TT) {
@@ -453,8 +455,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
   __shared__ unsigned long long s_imin;
   __shared__ i64 s_stat[4];      // med_e, med_x, mad_e, mad_x
   const u32 tid = threadIdx.x;
-  const int rb = a.sf.rb;
-  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  const int mb = a.sf.mb;
+  const u64 mmask = ((u64)1 << mb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
   i64* big_e = a.big_ex;
   i64* big_x = a.big_ex + a.cap_n;
   const u32 nbig = (u32)a.counters[CNT_NBIG];
@@ -462,12 +464,12 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
     if (a.big_list[3 * ent + 2] <= (u32)SEG_TEAM_MAX) continue;    // a team kernel has taken it
     const u32 srow = a.big_list[3 * ent], a0 = a.big_list[3 * ent + 1];
     const u64 k0 = a.key[a0];
-    const u64 pref = k0 >> rb;
+    const u64 pref = k0 >> mb;
     if (tid == 0) { s_end = a.n; s_ninfl = 0; s_incons = 0; s_imin = (unsigned long long)T_INFLIGHT; }
     __syncthreads();
     for (u64 j0 = (u64)a0 + 1;; j0 += SEG_THREADS) {
       const u64 j = j0 + tid;
-      if (j < a.n && (a.key[j] >> rb) != pref) atomicMin(&s_end, (u32)j);
+      if (j < a.n && (a.key[j] >> mb) != pref) atomicMin(&s_end, (u32)j);
       __syncthreads();
       const bool stop = s_end != a.n || j0 + SEG_THREADS >= a.n;
       __syncthreads();
@@ -490,8 +492,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
     __syncthreads();
     const u32 ninfl = s_ninfl, nd = nn - ninfl, km = nd ? (nd - 1) / 2 : 0;
     if (tid == 0) {
-      seg_put(a, CCLD_SEG_COMM, srow, (i64)(k0 >> (rb + a.sf.ws)));
-      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> rb) & smask));
+      seg_put(a, CCLD_SEG_COMM, srow, (i64)(k0 >> (mb + a.sf.ws)));
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> mb) & smask));
       seg_put(a, CCLD_SEG_N, srow, (i64)nn);
       seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
       seg_put(a, CCLD_SEG_OP, srow, (i64)h.op);
@@ -521,7 +523,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
       if (rx == km) { s_stat[1] = xi; seg_put(a, CCLD_SEG_EXIT_MED, srow, xi); }
       if (rx == 0) seg_put(a, CCLD_SEG_EXIT_MIN, srow, xi);
       if (rx == nd - 1) seg_put(a, CCLD_SEG_EXIT_MAX, srow, xi);
-      const i64 rk = (i64)(a.key[i] & rmask);
+      const i64 rk = (i64)a.members_sorted[a.member_off[(u32)(k0 >> (mb + a.sf.ws))] + (u32)(a.key[i] & mmask)];
       if (cmin == 0) { seg_put(a, CCLD_SEG_DUR_MIN, srow, di); seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, rk); }
       if (cmax == 0) { seg_put(a, CCLD_SEG_DUR_MAX, srow, di); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, rk); }
     }
@@ -544,7 +546,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
       if (rdx == km) { s_stat[3] = dxi; seg_put(a, CCLD_SEG_EXIT_MAD, srow, dxi); }
     }
     __syncthreads();
-    const u32 comm = (u32)(k0 >> (rb + a.sf.ws));
+    const u32 comm = (u32)(k0 >> (mb + a.sf.ws));
     const bool complete = nn == a.comm_size[comm] && ninfl == 0;
     const bool consistent = s_incons == 0;
     const bool barrier = h.op == CCLD_OP_ALLREDUCE && h.bytes < (u64)a.barrier_bytes;

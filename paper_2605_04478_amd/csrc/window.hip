@@ -83,7 +83,8 @@ __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, 
   const i64* __restrict__ in_tx = a.t_exit;
   u64* __restrict__ out_key = a.win_key;
   Row* __restrict__ out_row = a.win_row;
-  const uint4* __restrict__ comms4 = reinterpret_cast<const uint4*>(T.rank_comms4);
+  const uint4* __restrict__ memb4 = reinterpret_cast<const uint4*>(T.rank_memb4);
+  const u32 slot_mask = kf.mb < 32 ? (1u << kf.mb) - 1 : ~0u;
   // every workgroup walks one contiguous slice of the batch, so its nine streams advance page by page
   const u64 chunk = ((a.n + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
   const u64 i_end = (chunk * (blockIdx.x + 1)) < a.n ? chunk * (blockIdx.x + 1) : a.n;
@@ -100,11 +101,12 @@ __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, 
         te[u] = in_te[i]; tx[u] = in_tx[i];
       }
     }
-    // the communicators of each rank: one 16-byte row when no rank is in more than four of them
+    // the communicators of each rank with its member slot in each: one 16-byte row of words
+    // comm << mb | slot when no rank is in more than four communicators
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       mem[u] = make_uint4(~0u, ~0u, ~0u, ~0u);
-      if (i0 + (u64)u * 256 < i_end && comms4 && r[u] < T.n_ranks) mem[u] = comms4[r[u]];
+      if (i0 + (u64)u * 256 < i_end && memb4 && r[u] < T.n_ranks) mem[u] = memb4[r[u]];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -115,22 +117,27 @@ __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, 
         status |= DS_UNKNOWN_COMM;
       } else {
         bool member = false;
-        if (comms4) {
-          member = c[u] == mem[u].x || c[u] == mem[u].y || c[u] == mem[u].z || c[u] == mem[u].w;
+        u32 slot = 0;
+        if (memb4) {
+          const u32 w = c[u] == (mem[u].x >> kf.mb) ? mem[u].x : c[u] == (mem[u].y >> kf.mb) ? mem[u].y
+                      : c[u] == (mem[u].z >> kf.mb) ? mem[u].z : mem[u].w;
+          member = c[u] == (w >> kf.mb);
+          slot = w & slot_mask;
         } else if (r[u] < T.n_ranks) {
-          for (u32 q = T.rank_comm_off[r[u]]; q < T.rank_comm_off[r[u] + 1]; ++q) member |= (T.rank_comms[q] == c[u]);
+          for (u32 q = T.rank_comm_off[r[u]]; q < T.rank_comm_off[r[u] + 1]; ++q)
+            if (T.rank_comms[q] == c[u]) { member = true; slot = T.rank_slots[q]; }
         }
         if (!member) status |= DS_NOT_MEMBER;
         if (op[u] >= CCLD_OP_MAX || te[u] < 0 || te[u] == T_INFLIGHT || tx[u] < te[u]) status |= DS_RANGE;
         if (kf.sb < 64 && (sq[u] >> kf.sb) != 0) {
           status |= DS_KEY_WIDTH;
         } else {
-          key = (kf.cb ? ((u64)c[u] << (64 - kf.cb)) : 0ull) | (sq[u] << kf.rb) | (u64)r[u];
+          key = (kf.cb ? ((u64)c[u] << (64 - kf.cb)) : 0ull) | (sq[u] << kf.mb) | (u64)slot;
           maxseq = sq[u] > maxseq ? sq[u] : maxseq;
         }
       }
-      const u32 slot = atomicAdd(&s_off[c[u] < T.n_comms ? (c[u] >> a.bshift) : 0u], 1u);
-      u64 p = (u64)a.tail + slot;
+      const u32 at = atomicAdd(&s_off[c[u] < T.n_comms ? (c[u] >> a.bshift) : 0u], 1u);
+      u64 p = (u64)a.tail + at;
       if (p >= a.cap) p -= a.cap;
       out_key[p] = key;
       Row rw;
@@ -180,7 +187,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_count(SegArgs a) {
       if (j == 0) cnt += 1;
       else {
         const u64 kp = a.key[j - 1];
-        cnt += ((k >> a.sf.rb) != (kp >> a.sf.rb));
+        cnt += ((k >> a.sf.mb) != (kp >> a.sf.mb));
         dup |= (k == kp);
       }
     }
@@ -238,8 +245,8 @@ __global__ __launch_bounds__(256) void k_flag_count(FlagArgs a) {
 __global__ __launch_bounds__(256) void k_flag_emit(FlagArgs a) {
   __shared__ u32 s_wave[4];
   const u32 j0 = blockIdx.x * SEL_TILE + threadIdx.x * 8;
-  const int rb = a.sf.rb;
-  const u64 rmask = ((u64)1 << rb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  const int mb = a.sf.mb;
+  const u64 mmask = ((u64)1 << mb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
   const u64 v = load_flags8(a.rec_flag, j0, a.n);
   u32 c = 0;
 #pragma unroll
@@ -254,9 +261,11 @@ __global__ __launch_bounds__(256) void k_flag_emit(FlagArgs a) {
     a.flag_pos[k] = j;
     if (a.flag && k < a.flag_cap) {
       const u64 key = a.key[j];
-      a.flag[(u64)CCLD_FLG_COMM * a.flag_cap + k] = (i64)(key >> (rb + a.sf.ws));
-      a.flag[(u64)CCLD_FLG_SEQ * a.flag_cap + k] = (i64)((key >> rb) & smask);
-      a.flag[(u64)CCLD_FLG_RANK * a.flag_cap + k] = (i64)(key & rmask);
+      const u32 comm = (u32)(key >> (mb + a.sf.ws));
+      a.flag[(u64)CCLD_FLG_COMM * a.flag_cap + k] = (i64)comm;
+      a.flag[(u64)CCLD_FLG_SEQ * a.flag_cap + k] = (i64)((key >> mb) & smask);
+      a.flag[(u64)CCLD_FLG_RANK * a.flag_cap + k] =
+          (i64)rank_of_slot(a.member_off, a.members_sorted, comm, (u32)(key & mmask));
       a.flag[(u64)CCLD_FLG_KIND * a.flag_cap + k] = (i64)f;
       a.flag[(u64)CCLD_FLG_LAG_ENTER * a.flag_cap + k] = a.flag_lag[j];
       a.flag[(u64)CCLD_FLG_LAG_EXIT * a.flag_cap + k] = a.flag_lag[a.cap_n + j];
@@ -273,17 +282,21 @@ void launch_flag_compact(hipStream_t st, const FlagArgs& a) {
 // ------------------------------------------------------------------------------------------
 // Records per rank: privatised LDS histograms, per-workgroup partial tables, then a reduction.
 constexpr int RC_CHUNK = 8192;
-__global__ __launch_bounds__(256) void k_rank_count(const u64* __restrict__ key, u32 n, int rb, u32 n_ranks,
+__global__ __launch_bounds__(256) void k_rank_count(const u64* __restrict__ key, u32 n, SqueezedFormat sf,
+                                                    const u32* __restrict__ member_off,
+                                                    const u32* __restrict__ members_sorted, u32 n_ranks,
                                                     u32* __restrict__ partial) {
   __shared__ u32 s_h[RC_CHUNK];
-  const u64 rmask = ((u64)1 << rb) - 1;
+  const u64 mmask = ((u64)1 << sf.mb) - 1;
+  const int cshift = sf.mb + sf.ws;
   const u64 per = ((u64)n + gridDim.x - 1) / gridDim.x;
   const u64 lo = per * blockIdx.x, hi = (lo + per) < n ? (lo + per) : n;
   for (u32 r0 = 0; r0 < n_ranks; r0 += RC_CHUNK) {
     for (u32 i = threadIdx.x; i < RC_CHUNK; i += 256) s_h[i] = 0;
     __syncthreads();
     for (u64 j = lo + threadIdx.x; j < hi; j += 256) {
-      const u32 r = (u32)(key[j] & rmask);
+      const u64 k = key[j];
+      const u32 r = rank_of_slot(member_off, members_sorted, (u32)(k >> cshift), (u32)(k & mmask));
       if (r >= r0 && r < r0 + RC_CHUNK) atomicAdd(&s_h[r - r0], 1u);
     }
     __syncthreads();
@@ -311,22 +324,29 @@ __global__ __launch_bounds__(256) void k_rank_reduce(const u32* __restrict__ par
   if (threadIdx.x < 64 && r < n_ranks && s_sum[rr])
     atomicAdd((unsigned long long*)&blame[(u64)CCLD_BLM_N_RECORDS * n_ranks + r], s_sum[rr]);
 }
-void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, int rb, uint32_t n_ranks,
-                       uint32_t* partial, int64_t* blame) {
-  hipLaunchKernelGGL(k_rank_count, dim3(RANKCOUNT_BLOCKS), dim3(256), 0, st, key, n, rb, n_ranks, partial);
+void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, const SqueezedFormat& sf,
+                       const DeviceTopology& T, uint32_t* partial, int64_t* blame) {
+  const uint32_t n_ranks = T.n_ranks;
+  hipLaunchKernelGGL(k_rank_count, dim3(RANKCOUNT_BLOCKS), dim3(256), 0, st, key, n, sf, T.member_off,
+                     T.members_sorted, n_ranks, partial);
   hipLaunchKernelGGL(k_rank_reduce, dim3((n_ranks + 63) / 64, 32), dim3(256), 0, st, (const u32*)partial,
                      (u32)RANKCOUNT_BLOCKS, n_ranks, blame);
 }
 
 // Blame: key every flag by its rank, sort, then one wavefront per rank sums its run.
 __global__ __launch_bounds__(256) void k_blame_keys(const u64* __restrict__ key, const u32* __restrict__ flag_pos,
-                                                    u32 n_flag, int rb, u64* __restrict__ out_key) {
+                                                    u32 n_flag, SqueezedFormat sf, const u32* __restrict__ member_off,
+                                                    const u32* __restrict__ members_sorted, u64* __restrict__ out_key) {
   const u32 k = blockIdx.x * 256 + threadIdx.x;
-  if (k < n_flag) out_key[k] = key[flag_pos[k]] & (((u64)1 << rb) - 1);
+  if (k >= n_flag) return;
+  const u64 kk = key[flag_pos[k]];
+  out_key[k] = rank_of_slot(member_off, members_sorted, (u32)(kk >> (sf.mb + sf.ws)), (u32)(kk & (((u64)1 << sf.mb) - 1)));
 }
-void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag_pos, uint32_t n_flag, int rb,
-                       uint64_t* out_key) {
-  if (n_flag) hipLaunchKernelGGL(k_blame_keys, dim3((n_flag + 255) / 256), dim3(256), 0, st, key, flag_pos, n_flag, rb, out_key);
+void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag_pos, uint32_t n_flag,
+                       const SqueezedFormat& sf, const DeviceTopology& T, uint64_t* out_key) {
+  if (n_flag)
+    hipLaunchKernelGGL(k_blame_keys, dim3((n_flag + 255) / 256), dim3(256), 0, st, key, flag_pos, n_flag, sf,
+                       T.member_off, T.members_sorted, out_key);
 }
 // one workgroup per rank: the rank's run in the sorted flag keys is summed by 256 threads
 __global__ __launch_bounds__(256) void k_blame_reduce(const u64* __restrict__ skey, const u32* __restrict__ sidx,
@@ -594,7 +614,7 @@ __global__ __launch_bounds__(256) void k_alert_cand(AlertArgs a, u32 n_alert) {
   const u32 nn = (u32)a.seg[CCLD_SEG_N * C + s], ninfl = (u32)a.seg[CCLD_SEG_INFLIGHT * C + s];
   const u32 first = (u32)a.seg[CCLD_SEG_FIRST * C + s];
   const u32 size = a.topo.size[comm], moff = a.topo.member_off[comm];
-  const u64 rmask = ((u64)1 << a.sf.rb) - 1;
+  const u64 mmask = ((u64)1 << a.sf.mb) - 1;      // key slot = position among the members in ascending rank order
   const u32 off = EMIT ? a.alert_ncand[al] : 0u;
   int cls;
   u32 total = 0;
@@ -607,8 +627,8 @@ __global__ __launch_bounds__(256) void k_alert_cand(AlertArgs a, u32 n_alert) {
       if (q < size) {
         r = a.topo.members_sorted[moff + q];
         u32 lo = first, hi = first + nn;
-        while (lo < hi) { const u32 m = (lo + hi) / 2; if ((u32)(a.key[m] & rmask) < r) lo = m + 1; else hi = m; }
-        miss = !(lo < first + nn && (u32)(a.key[lo] & rmask) == r);
+        while (lo < hi) { const u32 m = (lo + hi) / 2; if ((u32)(a.key[m] & mmask) < q) lo = m + 1; else hi = m; }
+        miss = !(lo < first + nn && (u32)(a.key[lo] & mmask) == q);
       }
       u32 tot;
       const u32 ex = block_exclusive_sum<256>(miss ? 1u : 0u, s_wave, &tot);
@@ -622,7 +642,7 @@ __global__ __launch_bounds__(256) void k_alert_cand(AlertArgs a, u32 n_alert) {
       bool done = false;
       u32 r = 0;
       if (j < nn) {
-        r = (u32)(a.key[first + j] & rmask);
+        r = a.topo.members_sorted[moff + (u32)(a.key[first + j] & mmask)];
         done = a.row[a.idx[first + j]].t_exit != T_INFLIGHT;
       }
       u32 tot;

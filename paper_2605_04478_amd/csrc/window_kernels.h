@@ -34,6 +34,7 @@ struct SegArgs {
   uint32_t n;
   SqueezedFormat sf;
   const uint32_t* comm_size;
+  const uint32_t *member_off, *members_sorted;   // key slot -> rank
   uint32_t* tile_heads;      // [tiles + 1] head counts, then (after the scan) first segment ordinal of each tile
   int64_t* seg;
   uint64_t seg_cap;
@@ -58,6 +59,7 @@ struct FlagArgs {
   uint64_t cap_n;
   uint32_t n;
   SqueezedFormat sf;
+  const uint32_t *member_off, *members_sorted;
   uint32_t* tile_flags;      // [tiles + 1]
   uint32_t* flag_pos;
   int64_t* flag;             // caller's table (may be NULL)
@@ -66,10 +68,10 @@ struct FlagArgs {
 };
 void launch_flag_compact(hipStream_t st, const FlagArgs& a);
 
-void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, int rb, uint32_t n_ranks,
-                       uint32_t* partial, int64_t* blame);
-void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag_pos, uint32_t n_flag, int rb,
-                       uint64_t* out_key);
+void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, const SqueezedFormat& sf,
+                       const DeviceTopology& T, uint32_t* partial, int64_t* blame);
+void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag_pos, uint32_t n_flag,
+                       const SqueezedFormat& sf, const DeviceTopology& T, uint64_t* out_key);
 void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* sidx, uint32_t n_flag,
                          const uint32_t* flag_pos, const uint8_t* rec_flag, const int64_t* flag_lag,
                          uint64_t cap_n, uint32_t n_ranks, int64_t* blame);

@@ -163,6 +163,33 @@ def test_edge_sizes():
         run_both(topo, toy_cols(rows), what=f"rounds{n_rounds}", tbase_init_ns=10)
 
 
+def test_many_communicators_per_rank_and_unsorted_members():
+    """Ranks in more than four communicators (the membership lookup leaves its packed 16-byte row)
+    and member lists that are not in ascending rank order (keys carry the rank's position among
+    the sorted members, outputs carry ranks)."""
+    rng = np.random.default_rng(11)
+    comms = [[5, 2, 7, 0, 3], [7, 6, 5, 4, 3, 2, 1, 0], [1, 3, 5, 7], [0, 2, 4, 6], [6, 1, 4], [3, 7], [2, 5, 0, 6, 1]]
+    topo = ring_topology(8, comms=comms)
+    rows = []
+    for c, members in enumerate(comms):
+        for s in range(60):
+            te = T0 + s * 10**7 + rng.integers(0, 2000, len(members))
+            tx = te + 10**6 + rng.integers(0, 3000, len(members))
+            if s % 7 == 3:
+                k = int(rng.integers(0, len(members)))
+                te[k] += 5_000_000
+                tx[k] = max(tx[k], te[k] + 10)
+            for r, a, b in zip(members, te, tx):
+                if s == 59 and r == members[0]:
+                    continue
+                rows.append((r, c, s, 0, 1 << 16, int(a), INFLIGHT if s == 59 else int(b)))
+    cols = toy_cols(rows)
+    p = rng.permutation(len(rows))
+    cols = {k: v[p] for k, v in cols.items()}
+    g, o = run_both(topo, cols, now=T0 + 10**12, what="many-comms", tbase_init_ns=1000)
+    assert g.n_flag > 0 and g.n_alert > 0
+
+
 def test_validation_parity():
     topo = ring_topology(4, comms=[[0, 1], [2, 3]])
     ok = [(0, 0, 0, 0, 8, T0, T0 + 1), (1, 0, 0, 0, 8, T0, T0 + 1)]
