@@ -65,7 +65,6 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->flag_lag = w.take<int64_t>(2 * N);
   c->big_list = w.take<uint32_t>(3 * (N / 65 + 2));
   c->big_ex = w.take<int64_t>(2 * N);
-  c->rank_partial = w.take<uint32_t>((uint64_t)RANKCOUNT_BLOCKS * n_ranks);
   c->blame = w.take<int64_t>((uint64_t)CCLD_BLM_NCOL * n_ranks);
   c->blame_list = w.take<uint32_t>(2ull * n_ranks);
   c->blame_tiles = w.take<uint32_t>(n_ranks / SEL_TILE + 3);
@@ -424,7 +423,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   launch_seg_analyze(st, sa);
   c->prof.end(CCLD_PROF_SEGMENTS);
   c->prof.begin();
-  launch_rank_count(st, skey, n, c->sf, c->topo, c->rank_partial, c->blame);
+  launch_rank_count(st, skey, n, c->sf, c->topo, c->blame);
   c->prof.end(CCLD_PROF_BLAME);
   FlagArgs fa;
   std::memset(&fa, 0, sizeof(fa));

@@ -116,7 +116,6 @@ struct ccld_ctx {
   int64_t* flag_lag;                  // [2][cap]
   uint32_t* big_list;                 // [cap / 65 + 2][3]  (segment ordinal, first position, length) of the collectives over 64 records
   int64_t* big_ex;                    // [2][cap]
-  uint32_t* rank_partial;             // [RANKCOUNT_BLOCKS][n_ranks]
   int64_t* blame;                     // [CCLD_BLM_NCOL][n_ranks]
   uint32_t* blame_list;               // [2][n_ranks] flagged ranks, then the others, each ascending
   uint32_t* blame_tiles;              // [n_ranks / SEL_TILE + 3]

@@ -280,57 +280,62 @@ void launch_flag_compact(hipStream_t st, const FlagArgs& a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Records per rank: privatised LDS histograms, per-workgroup partial tables, then a reduction.
-constexpr int RC_CHUNK = 8192;
+// Records per rank.  The keys are sorted by communicator, so a workgroup's slice of them covers a
+// short run of communicators: it counts (communicator, member slot) pairs in an LDS table that spans
+// as many communicators as fit, then adds every non-zero cell to its rank's (zeroed) blame column
+// with one integer atomic.  A slice that covers more communicators takes several rounds.
+constexpr u32 RC_CELLS = 8192;
 __global__ __launch_bounds__(256) void k_rank_count(const u64* __restrict__ key, u32 n, SqueezedFormat sf,
                                                     const u32* __restrict__ member_off,
-                                                    const u32* __restrict__ members_sorted, u32 n_ranks,
-                                                    u32* __restrict__ partial) {
-  __shared__ u32 s_h[RC_CHUNK];
-  const u64 mmask = ((u64)1 << sf.mb) - 1;
-  const int cshift = sf.mb + sf.ws;
+                                                    const u32* __restrict__ members_sorted,
+                                                    const u32* __restrict__ comm_size, u32 n_ranks,
+                                                    i64* __restrict__ blame) {
+  __shared__ u32 s_h[RC_CELLS];
+  __shared__ u32 s_end;
+  const int mb = sf.mb, cshift = sf.mb + sf.ws;
+  const u64 mmask = ((u64)1 << mb) - 1;
+  const u32 slots = mb >= 13 ? RC_CELLS : (1u << mb);         // member slots covered by one round
+  const u32 width = RC_CELLS / slots;                         // communicators covered by one round
+  const u32 n_sub = mb >= 13 ? (1u << (mb - 13)) : 1u;        // rounds needed to cover every slot
   const u64 per = ((u64)n + gridDim.x - 1) / gridDim.x;
-  const u64 lo = per * blockIdx.x, hi = (lo + per) < n ? (lo + per) : n;
-  for (u32 r0 = 0; r0 < n_ranks; r0 += RC_CHUNK) {
-    for (u32 i = threadIdx.x; i < RC_CHUNK; i += 256) s_h[i] = 0;
-    __syncthreads();
-    for (u64 j = lo + threadIdx.x; j < hi; j += 256) {
-      const u64 k = key[j];
-      const u32 r = rank_of_slot(member_off, members_sorted, (u32)(k >> cshift), (u32)(k & mmask));
-      if (r >= r0 && r < r0 + RC_CHUNK) atomicAdd(&s_h[r - r0], 1u);
+  const u64 lo = per * blockIdx.x, hi64 = (lo + per) < n ? (lo + per) : n;
+  const u32 hi = (u32)hi64;
+  unsigned long long* out = (unsigned long long*)(blame + (u64)CCLD_BLM_N_RECORDS * n_ranks);
+  u32 pos = (u32)lo;
+  while (pos < hi) {
+    const u32 c0 = (u32)(key[pos] >> cshift);
+    u32 end = hi;
+    for (u32 sub = 0; sub < n_sub; ++sub) {
+      const u32 s0 = sub * slots;
+      for (u32 i = threadIdx.x; i < RC_CELLS; i += 256) s_h[i] = 0;
+      if (threadIdx.x == 0) s_end = hi;
+      __syncthreads();
+      for (u32 j = pos + threadIdx.x; j < hi; j += 256) {
+        const u64 k = key[j];
+        const u32 c = (u32)(k >> cshift);
+        if (c - c0 >= width) { atomicMin(&s_end, j); break; }
+        const u32 slot = (u32)(k & mmask);
+        if (slot - s0 < slots) atomicAdd(&s_h[(c - c0) * slots + (slot - s0)], 1u);
+      }
+      __syncthreads();
+      for (u32 i = threadIdx.x; i < RC_CELLS; i += 256) {
+        const u32 v = s_h[i];
+        if (!v) continue;
+        const u32 c = c0 + i / slots, slot = s0 + i % slots;
+        if (slot < comm_size[c]) atomicAdd(&out[members_sorted[member_off[c] + slot]], (unsigned long long)v);
+      }
+      end = s_end;
+      __syncthreads();
     }
-    __syncthreads();
-    for (u32 i = threadIdx.x; i < RC_CHUNK && r0 + i < n_ranks; i += 256)
-      partial[(u64)blockIdx.x * n_ranks + r0 + i] = s_h[i];
-    __syncthreads();
+    pos = end;
   }
 }
-// 64 ranks x 4 slices per workgroup; gridDim.y workgroups share the partial tables of a rank and
-// add their integer sums into the (zeroed) blame column
-__global__ __launch_bounds__(256) void k_rank_reduce(const u32* __restrict__ partial, u32 n_blocks, u32 n_ranks,
-                                                     i64* __restrict__ blame) {
-  __shared__ unsigned long long s_sum[64];
-  const u32 rr = threadIdx.x % 64, sl = threadIdx.x / 64;
-  const u32 r = blockIdx.x * 64 + rr;
-  if (threadIdx.x < 64) s_sum[threadIdx.x] = 0;
-  __syncthreads();
-  const u32 per = (n_blocks + gridDim.y - 1) / gridDim.y;
-  const u32 b0 = blockIdx.y * per, b1 = (b0 + per) < n_blocks ? (b0 + per) : n_blocks;
-  u64 s = 0;
-  if (r < n_ranks)
-    for (u32 b = b0 + sl; b < b1; b += 4) s += partial[(u64)b * n_ranks + r];
-  if (s) atomicAdd(&s_sum[rr], (unsigned long long)s);
-  __syncthreads();
-  if (threadIdx.x < 64 && r < n_ranks && s_sum[rr])
-    atomicAdd((unsigned long long*)&blame[(u64)CCLD_BLM_N_RECORDS * n_ranks + r], s_sum[rr]);
-}
 void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, const SqueezedFormat& sf,
-                       const DeviceTopology& T, uint32_t* partial, int64_t* blame) {
-  const uint32_t n_ranks = T.n_ranks;
-  hipLaunchKernelGGL(k_rank_count, dim3(RANKCOUNT_BLOCKS), dim3(256), 0, st, key, n, sf, T.member_off,
-                     T.members_sorted, n_ranks, partial);
-  hipLaunchKernelGGL(k_rank_reduce, dim3((n_ranks + 63) / 64, 32), dim3(256), 0, st, (const u32*)partial,
-                     (u32)RANKCOUNT_BLOCKS, n_ranks, blame);
+                       const DeviceTopology& T, int64_t* blame) {
+  if (n == 0) return;
+  const uint32_t blocks = std::min<uint32_t>((n + 4095) / 4096, RANKCOUNT_BLOCKS);
+  hipLaunchKernelGGL(k_rank_count, dim3(blocks), dim3(256), 0, st, key, n, sf, T.member_off, T.members_sorted,
+                     T.size, T.n_ranks, blame);
 }
 
 // Blame: key every flag by its rank, sort, then one wavefront per rank sums its run.

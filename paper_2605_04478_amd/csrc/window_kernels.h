@@ -69,7 +69,7 @@ struct FlagArgs {
 void launch_flag_compact(hipStream_t st, const FlagArgs& a);
 
 void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, const SqueezedFormat& sf,
-                       const DeviceTopology& T, uint32_t* partial, int64_t* blame);
+                       const DeviceTopology& T, int64_t* blame);     // adds into the zeroed records column
 void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag_pos, uint32_t n_flag,
                        const SqueezedFormat& sf, const DeviceTopology& T, uint64_t* out_key);
 void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* sidx, uint32_t n_flag,
