@@ -89,6 +89,7 @@ typedef struct {
 typedef struct {
   uint32_t n_comms;
   orc_group_state *g;         /* [n_comms][OP_MAX][CLS_MAX] */
+  int64_t *rate_root;         /* [n_comms] rank of minimal SendRate / RecvRate from the latest rate pass, or none */
 } orc_state;
 
 /* ------------------------------------------------------------------ */
@@ -97,10 +98,12 @@ orc_state *orc_state_create(uint32_t n_comms) {
   if (!s) return NULL;
   s->n_comms = n_comms;
   s->g = (orc_group_state *)calloc((size_t)n_comms * OP_MAX * CLS_MAX, sizeof(orc_group_state));
-  if (!s->g) { free(s); return NULL; }
+  s->rate_root = (int64_t *)malloc(sizeof(int64_t) * (n_comms ? n_comms : 1));
+  if (!s->g || !s->rate_root) { free(s->g); free(s->rate_root); free(s); return NULL; }
+  for (uint32_t c = 0; c < n_comms; ++c) s->rate_root[c] = ORC_NO_RANK;
   return s;
 }
-void orc_state_destroy(orc_state *s) { if (s) { free(s->g); free(s); } }
+void orc_state_destroy(orc_state *s) { if (s) { free(s->g); free(s->rate_root); free(s); } }
 
 void orc_window_result_free(orc_window_result *r) {
   if (!r) return;
@@ -425,7 +428,11 @@ int orc_analyze_window(const int64_t *P, const orc_topology *T, uint64_t n,
     O[GRP_N_USABLE] = (int64_t)(k1 - k0); O[GRP_RSTAR_SEQ] = (int64_t)items[kstar].seq;
     O[GRP_TMAX] = tmax; O[GRP_TMIN] = tmin; O[GRP_TBASE] = tbase; O[GRP_STATIC] = !dynamic;
     O[GRP_FROZEN] = G->frozen; O[GRP_M] = G->cnt; O[GRP_SLOW] = slow; O[GRP_CLASS] = cls;
-    O[GRP_ROOT_S1] = root1; O[GRP_ROOT_S2] = ORC_NO_RANK; O[GRP_REPEATS] = G->repeats;
+    /* communication-slow (and the communication half of a mixed slowdown): the rank of minimal
+       SendRate / RecvRate in this communicator, known once a rate pass has run (Section 4.2.1, Eq. 4) */
+    O[GRP_ROOT_S1] = root1;
+    O[GRP_ROOT_S2] = (cls == 2 || cls == 3) ? st->rate_root[items[k0].comm] : ORC_NO_RANK;
+    O[GRP_REPEATS] = G->repeats;
     O[GRP_LOCATE] = slow && G->repeats >= (uint64_t)P[P_REPEAT_THRESHOLD];
     k0 = k1;
   }
@@ -480,28 +487,29 @@ static int cmp_root(const void *pa, const void *pb) {
   return 0;
 }
 
-int orc_locate_hang(const int64_t *P, const orc_topology *T, uint64_t n_rows, uint32_t n_snap, uint32_t n_ch,
-                    const uint32_t *snap, const uint32_t *rank, const uint32_t *comm, const uint32_t *channel,
-                    const uint64_t *seq_posted, const uint32_t *chunks_sent, const uint32_t *chunks_recv,
-                    orc_hang_result *R) {
-  memset(R, 0, sizeof(*R));
-  if (n_snap == 0 || n_ch == 0) { R->status = ORC_E_BAD_ARG; return R->status; }
+/* Validates the snapshot rows and places every row in its cell [pair][channel][snapshot], where
+ * pair = the member's position in the communicator table.  Returns ORC_OK and the cell array (the
+ * caller frees it), or the status of the first failing check in the order unknown communicator,
+ * non-member, range, duplicate, gap. */
+static int place_cells(const orc_topology *T, uint64_t n_rows, uint32_t n_snap, uint32_t n_ch,
+                       const uint32_t *snap, const uint32_t *rank, const uint32_t *comm, const uint32_t *channel,
+                       const uint64_t *seq_posted, const uint32_t *chunks_sent, const uint32_t *chunks_recv,
+                       uint64_t *n_pair_out, cell_t **cell_out) {
+  *cell_out = NULL;
+  if (n_snap == 0 || n_ch == 0) return ORC_E_BAD_ARG;
   uint64_t n_pair = 0;
   for (uint32_t c = 0; c < T->n_comms; ++c) n_pair += T->size[c];
+  *n_pair_out = n_pair;
   const uint64_t n_cell = n_pair * n_ch * n_snap;
-
-  /* ---- validation ---- */
   int bad_comm = 0, bad_member = 0, bad_range = 0;
   for (uint64_t i = 0; i < n_rows; ++i) {
     if (comm[i] >= T->n_comms) { bad_comm = 1; continue; }
     if (rank[i] >= T->n_ranks || !is_member(T, comm[i], rank[i])) bad_member = 1;
     if (snap[i] >= n_snap || channel[i] >= n_ch) bad_range = 1;
   }
-  if (bad_comm) { R->status = ORC_E_UNKNOWN_COMM; return R->status; }
-  if (bad_member) { R->status = ORC_E_RANK_NOT_MEMBER; return R->status; }
-  if (bad_range) { R->status = ORC_E_RANGE; return R->status; }
-
-  /* ---- place every row in its cell [pair][channel][snapshot] ---- */
+  if (bad_comm) return ORC_E_UNKNOWN_COMM;
+  if (bad_member) return ORC_E_RANK_NOT_MEMBER;
+  if (bad_range) return ORC_E_RANGE;
   cell_t *cell = (cell_t *)calloc(n_cell ? n_cell : 1, sizeof(cell_t));
   uint8_t *seen = (uint8_t *)calloc(n_cell ? n_cell : 1, 1);
   int dup = 0, gap = 0;
@@ -515,8 +523,22 @@ int orc_locate_hang(const int64_t *P, const orc_topology *T, uint64_t n_rows, ui
   }
   for (uint64_t k = 0; k < n_cell; ++k) if (!seen[k]) gap = 1;
   free(seen);
-  if (dup) { free(cell); R->status = ORC_E_DUPLICATE_KEY; return R->status; }
-  if (gap) { free(cell); R->status = ORC_E_SNAPSHOT_GAP; return R->status; }
+  if (dup) { free(cell); return ORC_E_DUPLICATE_KEY; }
+  if (gap) { free(cell); return ORC_E_SNAPSHOT_GAP; }
+  *cell_out = cell;
+  return ORC_OK;
+}
+
+int orc_locate_hang(const int64_t *P, const orc_topology *T, uint64_t n_rows, uint32_t n_snap, uint32_t n_ch,
+                    const uint32_t *snap, const uint32_t *rank, const uint32_t *comm, const uint32_t *channel,
+                    const uint64_t *seq_posted, const uint32_t *chunks_sent, const uint32_t *chunks_recv,
+                    orc_hang_result *R) {
+  memset(R, 0, sizeof(*R));
+  uint64_t n_pair = 0;
+  cell_t *cell = NULL;
+  R->status = place_cells(T, n_rows, n_snap, n_ch, snap, rank, comm, channel, seq_posted, chunks_sent, chunks_recv,
+                          &n_pair, &cell);
+  if (R->status != ORC_OK) return R->status;
 
   const uint32_t L = n_snap - 1;
   const int64_t W = P[P_STALL_SNAPSHOTS];
@@ -685,4 +707,111 @@ int orc_locate_hang(const int64_t *P, const orc_topology *T, uint64_t n_rows, ui
   free(is_cand);
   R->status = ORC_OK;
   return ORC_OK;
+}
+
+
+/* ------------------------------------------------------------------ */
+/* SendRate / RecvRate (Section 4.1.2, "Slow Diagnostic Metrics"): the rate of a rank's progress is
+ * the reciprocal of the number of times its SendCount (RecvCount) changes between samples while an
+ * operation runs; a slow rank needs more samples, hence more changes, for the same operation.
+ *
+ * Per (pair, channel) the series is cut into runs of equal operation counter.  The last run is
+ * still open (its operation may not have finished) and is left out.  Inside a run the count is
+ * compared with the previous sample of the run, or with zero for the run's first sample (the
+ * count starts at zero when the operation is posted).  A run with at least one change is one
+ * observed operation.  Per pair, ops and changes are summed over channels; its rate is
+ * ops / changes (compared by cross-multiplication), undefined without a change.
+ * Per communicator: the member of minimal SendRate, of minimal RecvRate, and of the minimal of
+ * both kinds (ties: smallest rank); the last one is stored in the state for Eq. 4's
+ * communication-slow root. */
+enum { RATE_RANK, RATE_COMM, RATE_OPS_SEND, RATE_CHG_SEND, RATE_OPS_RECV, RATE_CHG_RECV, RATE_NCOL };
+enum { RC_COMM, RC_ROOT_SEND, RC_ROOT_RECV, RC_ROOT, RC_NCOL };
+
+typedef struct {
+  int32_t status;
+  uint64_t n_pair, n_comm;
+  int64_t *pair;   /* [n_pair][RATE_NCOL] one row per member slot of every communicator, in table order */
+  int64_t *comm;   /* [n_comm][RC_NCOL] */
+} orc_rate_result;
+
+void orc_rate_result_free(orc_rate_result *r) {
+  if (!r) return;
+  free(r->pair); free(r->comm);
+  memset(r, 0, sizeof(*r));
+}
+
+/* is rate a = ops_a/chg_a smaller than rate b, or equal with the smaller rank */
+static int rate_less(int64_t ops_a, int64_t chg_a, int64_t rank_a, int64_t ops_b, int64_t chg_b, int64_t rank_b) {
+  __int128 l = (__int128)ops_a * (__int128)chg_b, r = (__int128)ops_b * (__int128)chg_a;
+  if (l != r) return l < r;
+  return rank_a < rank_b;
+}
+
+int orc_progress_rates(const orc_topology *T, uint64_t n_rows, uint32_t n_snap, uint32_t n_ch,
+                       const uint32_t *snap, const uint32_t *rank, const uint32_t *comm, const uint32_t *channel,
+                       const uint64_t *seq_posted, const uint32_t *chunks_sent, const uint32_t *chunks_recv,
+                       orc_state *st, orc_rate_result *R) {
+  memset(R, 0, sizeof(*R));
+  uint64_t n_pair = 0;
+  cell_t *cell = NULL;
+  R->status = place_cells(T, n_rows, n_snap, n_ch, snap, rank, comm, channel, seq_posted, chunks_sent, chunks_recv,
+                          &n_pair, &cell);
+  if (R->status != ORC_OK) return R->status;
+  R->n_pair = n_pair; R->n_comm = T->n_comms;
+  R->pair = (int64_t *)calloc((n_pair ? n_pair : 1) * RATE_NCOL, sizeof(int64_t));
+  R->comm = (int64_t *)calloc((size_t)(T->n_comms ? T->n_comms : 1) * RC_NCOL, sizeof(int64_t));
+  for (uint32_t c = 0; c < T->n_comms; ++c) {
+    for (uint32_t q = 0; q < T->size[c]; ++q) {
+      const uint64_t p = (uint64_t)T->member_off[c] + q;
+      int64_t *Q = R->pair + p * RATE_NCOL;
+      Q[RATE_RANK] = T->members[p]; Q[RATE_COMM] = c;
+      for (uint32_t ch = 0; ch < n_ch; ++ch) {
+        const cell_t *s = cell + (p * n_ch + ch) * n_snap;
+        uint32_t open = n_snap - 1;          /* first sample of the open run */
+        while (open > 0 && s[open - 1].seq == s[n_snap - 1].seq) --open;
+        uint32_t t = 0;
+        while (t < open) {
+          const uint64_t run = s[t].seq;
+          uint32_t ps = 0, pr = 0;
+          int64_t cs = 0, cr = 0;
+          for (; t < open && s[t].seq == run; ++t) {
+            if (s[t].sent != ps) ++cs;
+            if (s[t].recv != pr) ++cr;
+            ps = s[t].sent; pr = s[t].recv;
+          }
+          if (cs) { Q[RATE_OPS_SEND] += 1; Q[RATE_CHG_SEND] += cs; }
+          if (cr) { Q[RATE_OPS_RECV] += 1; Q[RATE_CHG_RECV] += cr; }
+        }
+      }
+    }
+  }
+  free(cell);
+  for (uint32_t c = 0; c < T->n_comms; ++c) {
+    int64_t *H = R->comm + (size_t)c * RC_NCOL;
+    H[RC_COMM] = c; H[RC_ROOT_SEND] = ORC_NO_RANK; H[RC_ROOT_RECV] = ORC_NO_RANK; H[RC_ROOT] = ORC_NO_RANK;
+    int64_t bs[2] = {0, 0}, br[2] = {0, 0}, bb[2] = {0, 0};   /* (ops, changes) of the current minima */
+    for (uint32_t q = 0; q < T->size[c]; ++q) {
+      const int64_t *Q = R->pair + ((uint64_t)T->member_off[c] + q) * RATE_NCOL;
+      const int64_t rk = Q[RATE_RANK];
+      if (Q[RATE_CHG_SEND] > 0) {
+        if (H[RC_ROOT_SEND] == ORC_NO_RANK || rate_less(Q[RATE_OPS_SEND], Q[RATE_CHG_SEND], rk, bs[0], bs[1], H[RC_ROOT_SEND])) {
+          bs[0] = Q[RATE_OPS_SEND]; bs[1] = Q[RATE_CHG_SEND]; H[RC_ROOT_SEND] = rk;
+        }
+        if (H[RC_ROOT] == ORC_NO_RANK || rate_less(Q[RATE_OPS_SEND], Q[RATE_CHG_SEND], rk, bb[0], bb[1], H[RC_ROOT])) {
+          bb[0] = Q[RATE_OPS_SEND]; bb[1] = Q[RATE_CHG_SEND]; H[RC_ROOT] = rk;
+        }
+      }
+      if (Q[RATE_CHG_RECV] > 0) {
+        if (H[RC_ROOT_RECV] == ORC_NO_RANK || rate_less(Q[RATE_OPS_RECV], Q[RATE_CHG_RECV], rk, br[0], br[1], H[RC_ROOT_RECV])) {
+          br[0] = Q[RATE_OPS_RECV]; br[1] = Q[RATE_CHG_RECV]; H[RC_ROOT_RECV] = rk;
+        }
+        if (H[RC_ROOT] == ORC_NO_RANK || rate_less(Q[RATE_OPS_RECV], Q[RATE_CHG_RECV], rk, bb[0], bb[1], H[RC_ROOT])) {
+          bb[0] = Q[RATE_OPS_RECV]; bb[1] = Q[RATE_CHG_RECV]; H[RC_ROOT] = rk;
+        }
+      }
+    }
+    if (st && c < st->n_comms) st->rate_root[c] = H[RC_ROOT];
+  }
+  R->status = ORC_OK;
+  return R->status;
 }

@@ -83,6 +83,22 @@ class HangResult:
     comm: Dict[str, np.ndarray]
 
 
+class _RateRes(C.Structure):
+    _fields_ = [("status", C.c_int32), ("n_pair", C.c_uint64), ("n_comm", C.c_uint64),
+                ("pair", C.c_void_p), ("comm", C.c_void_p)]
+
+
+RATE_PAIR_COLS = ("rank", "comm", "ops_send", "changes_send", "ops_recv", "changes_recv")
+RATE_COMM_COLS = ("comm", "root_send", "root_recv", "root")
+
+
+@dataclass
+class RateResult:
+    status: str
+    pair: Dict[str, np.ndarray]
+    comm: Dict[str, np.ndarray]
+
+
 _lib: Optional[C.CDLL] = None
 
 
@@ -102,6 +118,10 @@ def lib() -> C.CDLL:
         L.orc_locate_hang.restype = C.c_int
         L.orc_locate_hang.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32] + \
             [C.c_void_p] * 7 + [C.c_void_p]
+        L.orc_rate_result_free.argtypes = [C.c_void_p]
+        L.orc_progress_rates.restype = C.c_int
+        L.orc_progress_rates.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32] + [C.c_void_p] * 7 + \
+            [C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -225,3 +245,27 @@ class Oracle:
                               _cols(_table(res.comm, res.n_comm, len(HANG_COMM_COLS)), HANG_COMM_COLS))
         finally:
             self.L.orc_hang_result_free(C.addressof(res))
+
+    def progress_rates(self, cols: Dict[str, np.ndarray], n_snapshots: int, n_channels: int) -> RateResult:
+        """SendRate / RecvRate of every (communicator, member) from a snapshot series; the
+        communicators' minimal-rate ranks stay in the state for the next analyze_window."""
+        dt = {"snap": np.uint32, "rank": np.uint32, "comm": np.uint32, "channel": np.uint32,
+              "seq_posted": np.uint64, "chunks_sent": np.uint32, "chunks_recv": np.uint32}
+        a = {k: np.ascontiguousarray(cols[k], dtype=dt[k]) for k in dt}
+        n = int(a["snap"].shape[0])
+        res = _RateRes()
+        self.L.orc_progress_rates(C.addressof(self._topo), n, int(n_snapshots), int(n_channels),
+                                  _ptr(a["snap"]), _ptr(a["rank"]), _ptr(a["comm"]), _ptr(a["channel"]),
+                                  _ptr(a["seq_posted"]), _ptr(a["chunks_sent"]), _ptr(a["chunks_recv"]),
+                                  self._state, C.addressof(res))
+        try:
+            status = STATUS[res.status]
+            if res.status != 0:
+                z = np.zeros((0,), np.int64)
+                e = lambda names: {k: z.copy() for k in names}
+                return RateResult(status, e(RATE_PAIR_COLS), e(RATE_COMM_COLS))
+            return RateResult(status,
+                              _cols(_table(res.pair, res.n_pair, len(RATE_PAIR_COLS)), RATE_PAIR_COLS),
+                              _cols(_table(res.comm, res.n_comm, len(RATE_COMM_COLS)), RATE_COMM_COLS))
+        finally:
+            self.L.orc_rate_result_free(C.addressof(res))

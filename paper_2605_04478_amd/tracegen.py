@@ -449,6 +449,7 @@ def config3(n_cycles: int = 2000, seed: int = 0, faults: bool = True,
 # --------------------------------------------------------------------------
 SNAP_COLUMNS = ("snap", "rank", "comm", "channel", "seq_posted", "chunks_sent", "chunks_recv")
 _S_HROOT, _S_HC0, _S_HTOT = 31, 32, 33
+_S_RSLOW, _S_RPHASE, _S_RK = 41, 42, 43        # _S_RK and _S_RK + 1: send / receive
 
 
 def ring_steady_state(n: int, frozen: int, c0: np.ndarray, total: int, depth: int):
@@ -659,3 +660,89 @@ def config4(seed: int = 0, layout: Optional[Layout3D] = None, healthy: bool = Fa
     one DP ring stops at operation 12,345 from snapshot 20 on."""
     lay = layout or Layout3D(tp=8, pp=8, dp=64, world=True)
     return HangSpec(layout=lay, hang_snapshot=None if healthy else kw.pop("hang_snapshot", 20), seed=seed, **kw)
+
+
+# --------------------------------------------------------------------------
+# progress-rate series: SendCount / RecvCount sampled while operations run
+# --------------------------------------------------------------------------
+@dataclass
+class RateSpec:
+    layout: Layout3D
+    n_snapshots: int = 64              # samples of every (rank, communicator, channel)
+    n_channels: int = 4
+    chunks: int = 8                    # chunks one operation moves per channel
+    op_samples: int = 10               # samples from one operation's start to the next one's
+    normal_changes: Tuple[int, int] = (1, 3)   # samples a healthy rank's count keeps changing, per operation
+    slow_changes: Tuple[int, int] = (6, 8)     # the same for the slow rank
+    slow_rank: Optional[int] = None    # None = seeded choice; -1 = nobody is slow
+    seed: int = 0
+
+
+@dataclass
+class RateTrace:
+    spec: RateSpec
+    topo: Topology
+    cols: Dict[str, np.ndarray]
+    slow_rank: int                     # ground truth (-1 = none)
+
+    @property
+    def n(self) -> int:
+        return int(self.cols["snap"].shape[0])
+
+
+def generate_rates(spec: RateSpec, shuffle: bool = True) -> RateTrace:
+    """SendCount / RecvCount of every (rank, communicator, channel) sampled at a fixed period while
+    operations run back to back.
+
+    Communicator c starts an operation every `op_samples` samples (seeded phase).  The sample taken
+    at an operation's start shows zero counts; from then on a rank's count rises at every sample
+    until the operation's `chunks` chunks are done: after k samples for a healthy rank (k drawn
+    from `normal_changes` per rank, operation, channel and direction) and after k drawn from
+    `slow_changes` for the slow rank.  Every k is at most `chunks`, so each of those k samples
+    shows a new value: an operation is observed with exactly k value changes."""
+    L = spec.layout
+    topo = L.topology()
+    R = L.n_ranks
+    nch, nsn = spec.n_channels, spec.n_snapshots
+    if max(spec.slow_changes) > spec.chunks or max(spec.slow_changes) >= spec.op_samples:
+        raise ValueError("an operation must finish before the next one starts, one chunk or more per sample")
+    seed = spec.seed
+    slow = spec.slow_rank
+    if slow is None:
+        slow = int(rand_u64(seed, _S_RSLOW, 0) % np.uint64(R))
+    kinds = ["tp", "pp", "dp"] + (["world"] if L.world else [])
+    ranks = np.arange(R, dtype=np.int64)
+    ch = np.arange(nch, dtype=np.int64)
+    out = {k: [] for k in SNAP_COLUMNS}
+    is_slow = ranks == slow
+    for kind in kinds:
+        comm_r = L.comm_of(kind, ranks).astype(np.int64)                          # [R]
+        phase = (rand_u64(seed, _S_RPHASE, comm_r) % np.uint64(spec.op_samples)).astype(np.int64)
+        seq0 = 1000 + (rand_u64(seed, _S_RPHASE, comm_r, 1) % np.uint64(9000)).astype(np.int64)
+        for s in range(nsn):
+            j = np.floor_divide(s - phase, spec.op_samples)                       # operation index, -1 before the first
+            u = (s - phase) - j * spec.op_samples                                 # samples since its start
+            seq = seq0 + j                                                        # [R]
+            cnt = []
+            for direction in (0, 1):
+                lo_n, hi_n = spec.normal_changes
+                lo_s, hi_s = spec.slow_changes
+                draw = rand_u64(seed, _S_RK + direction, (ranks * 4 + kinds.index(kind))[:, None] * 1000003 + seq[:, None],
+                                ch[None, :])                                      # [R, ch]
+                k = np.where(is_slow[:, None], lo_s + (draw % np.uint64(hi_s - lo_s + 1)).astype(np.int64),
+                             lo_n + (draw % np.uint64(hi_n - lo_n + 1)).astype(np.int64))
+                done = np.minimum(u[:, None], k)
+                cnt.append(np.where(j[:, None] < 0, spec.chunks, (spec.chunks * done) // k))
+            n_rows = R * nch
+            out["snap"].append(np.full(n_rows, s, dtype=np.uint32))
+            out["rank"].append(np.repeat(ranks, nch).astype(np.uint32))
+            out["comm"].append(np.repeat(comm_r, nch).astype(np.uint32))
+            out["channel"].append(np.tile(ch, R).astype(np.uint32))
+            out["seq_posted"].append(np.repeat(seq, nch).astype(np.uint64))
+            out["chunks_sent"].append(cnt[0].reshape(-1).astype(np.uint32))
+            out["chunks_recv"].append(cnt[1].reshape(-1).astype(np.uint32))
+    cols = {k: np.concatenate(v) for k, v in out.items()}
+    if shuffle:
+        perm = np.random.Generator(np.random.PCG64(seed + 29)).permutation(cols["snap"].shape[0])
+        cols = {k: v[perm] for k, v in cols.items()}
+    return RateTrace(spec, topo, cols, slow)
