@@ -67,7 +67,7 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-cycles", type=int, default=2000, help="cycles of the trace given to the CPU oracle")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--workload", choices=("trace", "stream", "hang"), default="trace",
+    ap.add_argument("--workload", choices=("trace", "stream", "hang", "rates"), default="trace",
                     help="trace: the 4,096-rank trace (default, the headline metric); stream: sliding window at "
                          "16,384 ranks, per-step latency; hang: hang location on 17M snapshot rows")
     ap.add_argument("--stream-steps", type=int, default=600)
@@ -93,6 +93,8 @@ def main() -> int:
         return bench_stream(args, torch, np, ccld, tg)
     if args.workload == "hang":
         return bench_hang(args, torch, np, ccld, tg)
+    if args.workload == "rates":
+        return bench_rates(args, torch, np, ccld, tg)
 
     spec = tg.config3(n_cycles=args.cycles, seed=args.seed)
     t0 = time.time()
@@ -285,6 +287,37 @@ def bench_hang(args, torch, np, ccld, tg) -> int:
                                   f"({ht.n} rows, 32 B each), one frozen rank in one DP ring",
                       "root_found": bool(ok), "hung_communicators": int(res.n_hung_comm),
                       "algorithmic_GBps": ht.n * 48.0 / dt / 1e9}}
+    print(json.dumps(out), flush=True)
+    an.close()
+    return 0
+
+
+def bench_rates(args, torch, np, ccld, tg) -> int:
+    """SendRate / RecvRate at 4,096 ranks: 16,777,216 snapshot rows resident in HBM."""
+    spec = tg.RateSpec(layout=tg.Layout3D(tp=8, pp=8, dp=64, world=True), n_snapshots=64, n_channels=16, seed=args.seed)
+    tr = tg.generate_rates(spec)
+    an = ccld.Analyzer(tr.topo, max_window_records=1024, max_snapshot_rows=tr.n, device="cuda:0")
+    cols = an.snapshots_to_device(tr.cols)
+    torch.cuda.synchronize()
+    res = None
+    for _ in range(args.warmup):
+        res = an.progress_rates(cols, 64, 16)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res = an.progress_rates(cols, 64, 16)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    pair, comm = res.pair, res.comm
+    mine = np.unique(pair["comm"][pair["rank"] == tr.slow_rank])
+    ok = all(int(comm["root"][c]) == tr.slow_rank for c in mine)
+    out = {"metric": "progress rates at 4,096 ranks: snapshot rows analysed/sec", "unit": "rows/s", "value": tr.n / dt,
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": "4,096 ranks x {TP,PP,DP,world} x 16 channels x 64 samples "
+                                  f"({tr.n} rows, 32 B each), one slow rank",
+                      "slow_rank_is_minimal_rate_member_of_its_communicators": bool(ok),
+                      "algorithmic_GBps": tr.n * 48.0 / dt / 1e9}}
     print(json.dumps(out), flush=True)
     an.close()
     return 0

@@ -179,6 +179,24 @@ typedef struct {
   int32_t reserved;
 } ccld_hang_result;
 
+/* progress-rate tables */
+/* one row per member slot of every communicator, in the order of the topology's members[]:
+ * operations observed and count changes observed, for SendCount and for RecvCount */
+enum { CCLD_RATE_RANK, CCLD_RATE_COMM, CCLD_RATE_OPS_SEND, CCLD_RATE_CHANGES_SEND, CCLD_RATE_OPS_RECV,
+       CCLD_RATE_CHANGES_RECV, CCLD_RATE_NCOL };
+/* one row per communicator: the member of minimal SendRate, of minimal RecvRate, and of the minimal
+ * of both kinds (CCLD_NO_RANK when no member has a rate) */
+enum { CCLD_RCOMM_COMM, CCLD_RCOMM_ROOT_SEND, CCLD_RCOMM_ROOT_RECV, CCLD_RCOMM_ROOT, CCLD_RCOMM_NCOL };
+
+typedef struct {
+  uint64_t pair_cap, comm_cap;  /* in: rows                                                          */
+  int64_t *pair;       /* device [CCLD_RATE_NCOL][pair_cap] or NULL                                   */
+  int64_t *comm;       /* device [CCLD_RCOMM_NCOL][comm_cap] or NULL                                  */
+  uint64_t n_pair, n_comm;      /* out (host): rows the full tables have                              */
+  ccld_status status;  /* out (host)                                                                  */
+  int32_t reserved;
+} ccld_rate_result;
+
 /* ---- entry points ---------------------------------------------------------------------------- */
 
 /* Fills *params with the defaults listed above. */
@@ -239,11 +257,27 @@ ccld_status ccld_analyze_window(ccld_ctx *ctx, int64_t now_ns, ccld_window_resul
 ccld_status ccld_locate_hang(ccld_ctx *ctx, const ccld_snapshots *snapshots, uint64_t n_rows,
                              ccld_hang_result *out);
 
+/* SendRate / RecvRate of every (communicator, member) from a series of SendCount / RecvCount
+ * snapshots (Section 4.1.2, slow diagnostic metrics): the rate is the reciprocal of the number of
+ * times the count changes from one sample to the next while an operation runs, so a rank whose
+ * transfers are slow shows more changes for the same operation.  Rows, validation and capacity as
+ * for ccld_locate_hang.  Per (member, channel) the series is cut into runs of equal operation
+ * counter; the last run is still open and is left out; inside a run a sample is compared with the
+ * previous one, the run's first sample with zero; a run with at least one change counts as one
+ * observed operation.  Per member the operations and changes are summed over channels: its rate is
+ * ops / changes (undefined without a change; rates are compared by cross-multiplication, ties go
+ * to the smaller rank).  The communicators' minimal-rate members (CCLD_RCOMM_ROOT) stay in the
+ * context: from then on ccld_analyze_window reports them as CCLD_GRP_ROOT_S2 of communication-slow
+ * and mixed groups (Section 4.2.1, Eq. 4: the rank of minimal SendRate / RecvRate is the root of a
+ * communication slowdown).  Before the first call that column holds CCLD_NO_RANK. */
+ccld_status ccld_progress_rates(ccld_ctx *ctx, const ccld_snapshots *snapshots, uint64_t n_rows,
+                                ccld_rate_result *out);
+
 /* Per-rank blame of the most recent ccld_analyze_window: blame = device [CCLD_BLM_NCOL][n_ranks]
  * (late-entry and late-exit counts, their summed lags, records seen); order = device [n_ranks]
  * ranks sorted by (number of flags descending, summed lag descending, rank ascending).  Either
- * pointer may be NULL.  The first entries of order[] name the faulty rank(s) (Section 1: "precisely
- * identifying the faulty GPU rank"). */
+ * pointer may be NULL.  The first entries of order[] name the faulty rank(s): locating the faulty
+ * GPU rank is the analyzer's stated purpose (Section 1). */
 ccld_status ccld_rank_blame(ccld_ctx *ctx, int64_t *blame, uint32_t *order);
 
 /* Optional timing of the library's kernels with HIP events recorded on the context's stream, by

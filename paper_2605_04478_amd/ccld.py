@@ -78,6 +78,11 @@ class _HangResult(C.Structure):
                 ("status", C.c_int32), ("reserved", C.c_int32)]
 
 
+class _RateResult(C.Structure):
+    _fields_ = [("pair_cap", C.c_uint64), ("comm_cap", C.c_uint64), ("pair", C.c_void_p), ("comm", C.c_void_p),
+                ("n_pair", C.c_uint64), ("n_comm", C.c_uint64), ("status", C.c_int32), ("reserved", C.c_int32)]
+
+
 _lib: Optional[C.CDLL] = None
 
 PROF_CLASSES = ("ingest", "sort_hist", "sort_scan", "sort_scatter", "segments", "flags", "blame", "groups", "alerts",
@@ -85,7 +90,8 @@ PROF_CLASSES = ("ingest", "sort_hist", "sort_scan", "sort_scatter", "segments", 
 PROF_NCLASS = 16
 
 EXPORTS = ("ccld_profile_enable", "ccld_profile_read", "ccld_default_params", "ccld_query_workspace", "ccld_create", "ccld_destroy", "ccld_ingest",
-           "ccld_reset_window", "ccld_analyze_window", "ccld_rank_blame", "ccld_locate_hang", "ccld_status_str")
+           "ccld_reset_window", "ccld_analyze_window", "ccld_rank_blame", "ccld_locate_hang", "ccld_progress_rates",
+           "ccld_status_str")
 
 
 def lib() -> C.CDLL:
@@ -105,8 +111,8 @@ def lib() -> C.CDLL:
         L.ccld_reset_window.argtypes = [vp]
         L.ccld_analyze_window.argtypes = [vp, C.c_int64, vp]
         L.ccld_rank_blame.argtypes = [vp, vp, vp]
-        if hasattr(L, "ccld_locate_hang"):
-            L.ccld_locate_hang.argtypes = [vp, vp, u64, vp]
+        L.ccld_locate_hang.argtypes = [vp, vp, u64, vp]
+        L.ccld_progress_rates.argtypes = [vp, vp, u64, vp]
         L.ccld_profile_enable.argtypes = [vp, C.c_int32]
         L.ccld_profile_read.argtypes = [vp, vp, vp, vp]
         L.ccld_status_str.argtypes = [C.c_int32]
@@ -187,6 +193,24 @@ class HangResult:
     def pair(self): return _table(self.dev["pair"], HANG_PAIR_COLS, self.caps["pair"], self.n_pair)
     @property
     def comm(self): return _table(self.dev["comm"], HANG_COMM_COLS, self.caps["comm"], self.caps["comm"])
+
+
+RATE_PAIR_COLS = ("rank", "comm", "ops_send", "changes_send", "ops_recv", "changes_recv")
+RATE_COMM_COLS = ("comm", "root_send", "root_recv", "root")
+
+
+@dataclass
+class RateResult:
+    status: str
+    n_pair: int
+    n_comm: int
+    caps: Dict[str, int]
+    dev: Dict[str, "object"] = field(repr=False, default_factory=dict)
+
+    @property
+    def pair(self): return _table(self.dev["pair"], RATE_PAIR_COLS, self.caps["pair"], min(self.n_pair, self.caps["pair"]))
+    @property
+    def comm(self): return _table(self.dev["comm"], RATE_COMM_COLS, self.caps["comm"], min(self.n_comm, self.caps["comm"]))
 
 
 class Analyzer:
@@ -370,3 +394,30 @@ class Analyzer:
         if st in (-7, -11, -6, -8):
             raise CcldError(st, "ccld_locate_hang")
         return HangResult(STATUS.get(st, str(st)), r.n_root, r.n_pair, r.n_hung_comm, caps, dev)
+
+    def progress_rates(self, cols, n_snapshots: int, n_channels: int, pair_cap: Optional[int] = None,
+                       comm_cap: Optional[int] = None) -> RateResult:
+        """SendRate / RecvRate tables from a snapshot series (host numpy columns or device tensors)."""
+        t = self.torch
+        first = cols["snap"]
+        on_device = not isinstance(first, np.ndarray)
+        n = int(first.shape[0])
+        if on_device:
+            ptr = lambda k: C.c_void_p(cols[k].data_ptr())
+        else:
+            dt = {"snap": np.uint32, "rank": np.uint32, "comm": np.uint32, "channel": np.uint32,
+                  "seq_posted": np.uint64, "chunks_sent": np.uint32, "chunks_recv": np.uint32}
+            keep = {k: np.ascontiguousarray(cols[k], dtype=dt[k]) for k in dt}
+            ptr = lambda k: keep[k].ctypes.data_as(C.c_void_p)
+        sn = _Snapshots(ptr("snap"), ptr("rank"), ptr("comm"), ptr("channel"), ptr("seq_posted"),
+                        ptr("chunks_sent"), ptr("chunks_recv"), 1 if on_device else 0, int(n_snapshots),
+                        int(n_channels))
+        caps = {"pair": int(pair_cap or int(self._size.sum())), "comm": int(comm_cap or self.n_comms)}
+        i64 = dict(dtype=t.int64, device=self.device)
+        dev = {"pair": t.empty(len(RATE_PAIR_COLS) * caps["pair"], **i64),
+               "comm": t.empty(len(RATE_COMM_COLS) * caps["comm"], **i64)}
+        r = _RateResult(caps["pair"], caps["comm"], dev["pair"].data_ptr(), dev["comm"].data_ptr())
+        st = self.L.ccld_progress_rates(self._ctx, C.addressof(sn), n, C.addressof(r))
+        if st in (-7, -11, -6, -8):
+            raise CcldError(st, "ccld_progress_rates")
+        return RateResult(STATUS.get(st, str(st)), r.n_pair, r.n_comm, caps, dev)

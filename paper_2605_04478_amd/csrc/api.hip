@@ -78,6 +78,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   // hang location
   const uint64_t SN = std::max<uint64_t>(c->snap_cap, 1);
   c->n_members = n_members;
+  c->rate_root = w.take<int64_t>(n_comms);
   c->h_cell = w.take<uint64_t>(2 * SN);
   c->h_cnt = w.take<uint32_t>(SN);
   c->h_pair = w.take<int64_t>((uint64_t)CCLD_HPAIR_NCOL * n_members);
@@ -272,6 +273,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   if (hipMemsetAsync(c->gstate, 0, sizeof(GroupState) * (uint64_t)topo->n_comms * GROUP_SLOTS, c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->batch_meta, 0, sizeof(BatchMeta) * ((uint64_t)c->p.window_batches + 2), c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, c->stream) != hipSuccess) rs = CCLD_E_HIP;
+  launch_fill_u64(c->stream, (uint64_t*)c->rate_root, topo->n_comms, (uint64_t)CCLD_NO_RANK);
   if (hipMemsetAsync(c->blame, 0, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)topo->n_ranks, c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipHostMalloc((void**)&c->h_pinned, 4096 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) rs = CCLD_E_HIP;
   if (hipStreamSynchronize(c->stream) != hipSuccess) rs = CCLD_E_HIP;   // host vectors above die at return
@@ -465,7 +467,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   std::memset(&ga, 0, sizeof(ga));
   ga.seg = o->seg; ga.seg_cap = o->seg_cap; ga.n_seg = seg_rows; ga.ws = ws; ga.cb = cb;
   ga.usable_list = c->usable_list; ga.tile_counts = c->tile_flags; ga.counters = c->counters;
-  ga.gstate = c->gstate; ga.group = o->group; ga.group_cap = o->group_cap; ga.p = c->p;
+  ga.gstate = c->gstate; ga.rate_root = c->rate_root; ga.group = o->group; ga.group_cap = o->group_cap; ga.p = c->p;
   c->prof.begin();
   launch_usable_select(st, ga);
   c->prof.end(CCLD_PROF_GROUPS);

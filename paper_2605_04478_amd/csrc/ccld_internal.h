@@ -138,6 +138,7 @@ struct ccld_ctx {
   uint8_t* h_cand;                    // [n_members]
   uint64_t* h_layer_max;              // [n_members]
   uint32_t* h_root_list;              // [n_members]
+  int64_t* rate_root;                 // [n_comms] member of minimal SendRate / RecvRate from the latest rate pass, or CCLD_NO_RANK
   uint8_t* h_stage;                   // [snap_cap * 32] device staging for host-resident snapshots
   // last analysis
   int sorted_buf;                     // which ping-pong buffer holds the sorted window

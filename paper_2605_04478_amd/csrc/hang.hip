@@ -299,6 +299,123 @@ __global__ __launch_bounds__(256) void k_copy_table(const i64* src, u64 src_cap,
   dst[col * dst_cap + r] = src[col * src_cap + r];
 }
 
+// ---- SendRate / RecvRate: count changes per operation (Section 4.1.2) ------------------------------
+#define RPAIR(a, col, p) (a.pair[(u64)(col) * a.n_members + (p)])
+#define RCOMM(a, col, c) (a.hcomm[(u64)(col) * a.T.n_comms + (c)])
+
+// One wavefront per member slot, lanes on consecutive snapshots of one channel.  A run of equal
+// operation counters is committed when the next run starts, so the open last run never counts.
+__global__ __launch_bounds__(256) void k_rate_pairs(HangArgs a) {
+  const u32 lane = lane_id();
+  const u64 p = (u64)blockIdx.x * 4 + threadIdx.x / CCLD_WAVE;
+  if (p >= a.n_members) return;
+  u64 ops_s = 0, chg_s = 0, ops_r = 0, chg_r = 0, status = 0;
+  const u64 below = ((u64)1 << lane) - 1;                // lanes before this one
+  for (u32 ch = 0; ch < a.n_ch; ++ch) {
+    const u64 base = (p * a.n_ch + ch) * a.n_snap;
+    u64 c_seq = 0, c_cnt = 0;                            // last sample of the previous chunk
+    u32 pend_s = 0, pend_r = 0;                          // changes seen so far in the run that is still open
+    for (u32 s0 = 0; s0 < a.n_snap; s0 += CCLD_WAVE) {
+      const u32 s = s0 + lane;
+      const bool in = s < a.n_snap;
+      u64 seq = 0, cnt = 0;
+      if (in) {
+        seq = a.cell[2 * (base + s)]; cnt = a.cell[2 * (base + s) + 1];
+        const u32 seen = a.cnt[base + s];
+        if (seen == 0) status |= DS_SNAPSHOT_GAP;
+        if (seen > 1) status |= DS_DUPLICATE;
+      }
+      u64 pseq = shfl_u64(seq, (int)lane - 1), pcnt = shfl_u64(cnt, (int)lane - 1);
+      if (lane == 0) { pseq = c_seq; pcnt = c_cnt; }
+      const bool start = in && (s == 0 || seq != pseq);
+      if (start) pcnt = 0;                               // a run's first sample is compared with zero
+      const u64 B = ballot64(start);
+      const u64 Cs = ballot64(in && (u32)cnt != (u32)pcnt);
+      const u64 Cr = ballot64(in && (u32)(cnt >> 32) != (u32)(pcnt >> 32));
+      if (B == 0) {
+        pend_s += (u32)__popcll(Cs); pend_r += (u32)__popcll(Cr);
+      } else {
+        const u32 last = 63 - (u32)__clzll((long long)B);             // start of the run still open
+        const u64 closed = ((u64)1 << last) - 1;                      // samples of runs that close here
+        // this lane's run begins at the highest start at or below it (or came in from the last chunk)
+        const u64 Bat = B & (below | ((u64)1 << lane));
+        const bool carried = Bat == 0;
+        const u32 rs = carried ? 0u : 63 - (u32)__clzll((long long)Bat);
+        const u64 run_before = below & ~(((u64)1 << rs) - 1);         // lanes of my run before me
+        const bool mine = ((closed >> lane) & 1) != 0;
+        const bool first_s = mine && ((Cs >> lane) & 1) && (Cs & run_before) == 0 && !(carried && pend_s);
+        const bool first_r = mine && ((Cr >> lane) & 1) && (Cr & run_before) == 0 && !(carried && pend_r);
+        const u32 first_start = (u32)__builtin_ctzll(B);
+        // the carried run closes at the chunk's first start: it is one operation if it had a change
+        // earlier, else if one of its lanes here is a first change (counted below)
+        ops_s += (u64)__popcll(ballot64(first_s)) + ((pend_s && first_start <= last) ? 1 : 0);
+        ops_r += (u64)__popcll(ballot64(first_r)) + ((pend_r && first_start <= last) ? 1 : 0);
+        chg_s += pend_s + (u64)__popcll(Cs & closed);
+        chg_r += pend_r + (u64)__popcll(Cr & closed);
+        pend_s = (u32)__popcll(Cs & ~closed); pend_r = (u32)__popcll(Cr & ~closed);
+      }
+      c_seq = shfl_u64(seq, 63); c_cnt = shfl_u64(cnt, 63);
+    }
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) status |= shfl_xor_u64(status, m);
+  if (lane == 0) {
+    if (status) atomicOr((unsigned long long*)&a.counters[CNT_STATUS], (unsigned long long)status);
+    u32 lo = 0, hi = a.T.n_comms;
+    while (hi - lo > 1) { const u32 m = (lo + hi) / 2; if (a.T.member_off[m] <= p) lo = m; else hi = m; }
+    RPAIR(a, CCLD_RATE_RANK, p) = a.T.members[p];
+    RPAIR(a, CCLD_RATE_COMM, p) = lo;
+    RPAIR(a, CCLD_RATE_OPS_SEND, p) = (i64)ops_s;
+    RPAIR(a, CCLD_RATE_CHANGES_SEND, p) = (i64)chg_s;
+    RPAIR(a, CCLD_RATE_OPS_RECV, p) = (i64)ops_r;
+    RPAIR(a, CCLD_RATE_CHANGES_RECV, p) = (i64)chg_r;
+  }
+}
+
+// a rate (ops / changes, rank); changes == 0 means "no rate" and loses against everything
+struct RateCand { u64 ops, chg; u32 rank; };
+__device__ __forceinline__ bool rate_less(const RateCand& x, const RateCand& y) {
+  if (x.chg == 0) return false;
+  if (y.chg == 0) return true;
+  const u128 l = (u128)x.ops * (u128)y.chg, r = (u128)y.ops * (u128)x.chg;
+  if (l != r) return l < r;
+  return x.rank < y.rank;
+}
+
+// One workgroup per communicator: the member of minimal SendRate, RecvRate, and of both kinds.
+__global__ __launch_bounds__(256) void k_rate_comm(HangArgs a, i64* __restrict__ rate_root) {
+  __shared__ RateCand s_best[3][256];
+  const u32 c = blockIdx.x, tid = threadIdx.x;
+  const u32 off = a.T.member_off[c], n = a.T.size[c];
+  RateCand best[3] = {{0, 0, 0xFFFFFFFFu}, {0, 0, 0xFFFFFFFFu}, {0, 0, 0xFFFFFFFFu}};
+  for (u32 q = tid; q < n; q += 256) {
+    const u64 p = (u64)off + q;
+    const u32 rk = (u32)RPAIR(a, CCLD_RATE_RANK, p);
+    const RateCand snd{(u64)RPAIR(a, CCLD_RATE_OPS_SEND, p), (u64)RPAIR(a, CCLD_RATE_CHANGES_SEND, p), rk};
+    const RateCand rcv{(u64)RPAIR(a, CCLD_RATE_OPS_RECV, p), (u64)RPAIR(a, CCLD_RATE_CHANGES_RECV, p), rk};
+    if (rate_less(snd, best[0])) best[0] = snd;
+    if (rate_less(rcv, best[1])) best[1] = rcv;
+    if (rate_less(snd, best[2])) best[2] = snd;
+    if (rate_less(rcv, best[2])) best[2] = rcv;
+  }
+  for (int k = 0; k < 3; ++k) s_best[k][tid] = best[k];
+  __syncthreads();
+  for (u32 w = 128; w >= 1; w >>= 1) {
+    if (tid < w)
+      for (int k = 0; k < 3; ++k)
+        if (rate_less(s_best[k][tid + w], s_best[k][tid])) s_best[k][tid] = s_best[k][tid + w];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    RCOMM(a, CCLD_RCOMM_COMM, c) = c;
+    RCOMM(a, CCLD_RCOMM_ROOT_SEND, c) = s_best[0][0].chg ? (i64)s_best[0][0].rank : (i64)CCLD_NO_RANK;
+    RCOMM(a, CCLD_RCOMM_ROOT_RECV, c) = s_best[1][0].chg ? (i64)s_best[1][0].rank : (i64)CCLD_NO_RANK;
+    const i64 root = s_best[2][0].chg ? (i64)s_best[2][0].rank : (i64)CCLD_NO_RANK;
+    RCOMM(a, CCLD_RCOMM_ROOT, c) = root;
+    rate_root[c] = root;
+  }
+}
+
 }  // namespace ccld
 
 #define HIP_TRY(x) do { if ((x) != hipSuccess) { (void)hipGetLastError(); return CCLD_E_HIP; } } while (0)
@@ -310,6 +427,40 @@ static ccld_status hang_status(uint64_t bits) {
   if (bits & DS_DUPLICATE) return CCLD_E_DUPLICATE_KEY;
   if (bits & DS_SNAPSHOT_GAP) return CCLD_E_SNAPSHOT_GAP;
   return CCLD_OK;
+}
+
+// Stages host-resident rows, clears the grid's presence counts and places every row in its cell.
+static hipError_t place_snapshots(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, uint64_t n_cell,
+                                  HangArgs& a) {
+  hipStream_t st = c->stream;
+  std::memset(&a, 0, sizeof(a));
+  hipError_t e = hipSuccess;
+  if (sn->on_device) {
+    a.snap = sn->snap; a.rank = sn->rank; a.comm = sn->comm; a.channel = sn->channel;
+    a.seq_posted = sn->seq_posted; a.sent = sn->chunks_sent; a.recv = sn->chunks_recv;
+  } else if (n_rows) {
+    uint64_t* d_seq = (uint64_t*)c->h_stage;
+    uint32_t* d32 = (uint32_t*)(d_seq + n_rows);
+    const uint32_t* src[6] = {sn->snap, sn->rank, sn->comm, sn->channel, sn->chunks_sent, sn->chunks_recv};
+    if ((e = hipMemcpyAsync(d_seq, sn->seq_posted, 8 * n_rows, hipMemcpyHostToDevice, st)) != hipSuccess) return e;
+    for (int i = 0; i < 6; ++i)
+      if ((e = hipMemcpyAsync(d32 + i * n_rows, src[i], 4 * n_rows, hipMemcpyHostToDevice, st)) != hipSuccess) return e;
+    a.seq_posted = d_seq; a.snap = d32; a.rank = d32 + n_rows; a.comm = d32 + 2 * n_rows; a.channel = d32 + 3 * n_rows;
+    a.sent = d32 + 4 * n_rows; a.recv = d32 + 5 * n_rows;
+  }
+  a.n_rows = n_rows; a.n_snap = sn->n_snapshots; a.n_ch = sn->n_channels; a.T = c->topo; a.n_members = c->n_members;
+  a.cell = c->h_cell; a.cnt = c->h_cnt; a.pair = c->h_pair; a.hcomm = c->h_comm; a.wait_slot = c->h_wait_slot;
+  a.cand = c->h_cand; a.layer_max = c->h_layer_max; a.counters = c->counters;
+  a.stall_snapshots = c->p.stall_snapshots; a.fifo_depth = c->p.fifo_depth;
+
+  c->prof.begin();
+  if ((e = hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st)) != hipSuccess) return e;
+  if ((e = hipMemsetAsync(c->h_cnt, 0, sizeof(uint32_t) * n_cell, st)) != hipSuccess) return e;
+  if (n_rows) {
+    uint64_t g = (n_rows + 255) / 256; if (g > 4096) g = 4096;
+    hipLaunchKernelGGL(k_hang_place, dim3((uint32_t)g), dim3(256), 0, st, a);
+  }
+  return hipSuccess;
 }
 
 extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, ccld_hang_result* o) {
@@ -325,31 +476,7 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
   hipStream_t st = c->stream;
 
   HangArgs a;
-  std::memset(&a, 0, sizeof(a));
-  if (sn->on_device) {
-    a.snap = sn->snap; a.rank = sn->rank; a.comm = sn->comm; a.channel = sn->channel;
-    a.seq_posted = sn->seq_posted; a.sent = sn->chunks_sent; a.recv = sn->chunks_recv;
-  } else if (n_rows) {
-    uint64_t* d_seq = (uint64_t*)c->h_stage;
-    uint32_t* d32 = (uint32_t*)(d_seq + n_rows);
-    const uint32_t* src[6] = {sn->snap, sn->rank, sn->comm, sn->channel, sn->chunks_sent, sn->chunks_recv};
-    HIP_TRY(hipMemcpyAsync(d_seq, sn->seq_posted, 8 * n_rows, hipMemcpyHostToDevice, st));
-    for (int i = 0; i < 6; ++i) HIP_TRY(hipMemcpyAsync(d32 + i * n_rows, src[i], 4 * n_rows, hipMemcpyHostToDevice, st));
-    a.seq_posted = d_seq; a.snap = d32; a.rank = d32 + n_rows; a.comm = d32 + 2 * n_rows; a.channel = d32 + 3 * n_rows;
-    a.sent = d32 + 4 * n_rows; a.recv = d32 + 5 * n_rows;
-  }
-  a.n_rows = n_rows; a.n_snap = sn->n_snapshots; a.n_ch = sn->n_channels; a.T = c->topo; a.n_members = c->n_members;
-  a.cell = c->h_cell; a.cnt = c->h_cnt; a.pair = c->h_pair; a.hcomm = c->h_comm; a.wait_slot = c->h_wait_slot;
-  a.cand = c->h_cand; a.layer_max = c->h_layer_max; a.counters = c->counters;
-  a.stall_snapshots = c->p.stall_snapshots; a.fifo_depth = c->p.fifo_depth;
-
-  c->prof.begin();
-  HIP_TRY(hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st));
-  HIP_TRY(hipMemsetAsync(c->h_cnt, 0, sizeof(uint32_t) * n_cell, st));
-  if (n_rows) {
-    uint64_t g = (n_rows + 255) / 256; if (g > 4096) g = 4096;
-    hipLaunchKernelGGL(k_hang_place, dim3((uint32_t)g), dim3(256), 0, st, a);
-  }
+  HIP_TRY(place_snapshots(c, sn, n_rows, n_cell, a));
   const uint32_t nm = (uint32_t)c->n_members;
   hipLaunchKernelGGL(k_hang_pairs, dim3((nm + 3) / 4), dim3(256), 0, st, a);
   HIP_TRY(hipGetLastError());
@@ -400,5 +527,47 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
   c->prof.collect();
   if (o->n_root > o->root_cap || (o->pair && o->pair_cap < c->n_members) || (o->comm && o->comm_cap < c->topo.n_comms))
     o->status = CCLD_W_TRUNCATED;
+  return o->status;
+}
+
+extern "C" ccld_status ccld_progress_rates(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, ccld_rate_result* o) {
+  if (!c || !sn || !o) return CCLD_E_NULL;
+  o->n_pair = o->n_comm = 0;
+  o->status = CCLD_OK;
+  if (n_rows && (!sn->snap || !sn->rank || !sn->comm || !sn->channel || !sn->seq_posted || !sn->chunks_sent || !sn->chunks_recv))
+    return o->status = CCLD_E_NULL;
+  if (sn->n_snapshots == 0 || sn->n_channels == 0) return o->status = CCLD_E_BAD_ARG;
+  const uint64_t n_cell = c->n_members * sn->n_channels * sn->n_snapshots;
+  if (n_cell > c->snap_cap || n_rows > c->snap_cap) return o->status = CCLD_E_CAPACITY;
+  hipStream_t st = c->stream;
+  HangArgs a;
+  HIP_TRY(place_snapshots(c, sn, n_rows, n_cell, a));
+  const uint32_t nm = (uint32_t)c->n_members;
+  if (nm) hipLaunchKernelGGL(k_rate_pairs, dim3((nm + 3) / 4), dim3(256), 0, st, a);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (c->h_pinned[CNT_STATUS]) { c->prof.end(CCLD_PROF_HANG); c->prof.collect(); return o->status = hang_status(c->h_pinned[CNT_STATUS]); }
+  if (c->topo.n_comms) hipLaunchKernelGGL(k_rate_comm, dim3(c->topo.n_comms), dim3(256), 0, st, a, c->rate_root);
+  o->n_pair = c->n_members;
+  o->n_comm = c->topo.n_comms;
+  if (o->pair && o->pair_cap) {
+    const uint64_t rows = std::min<uint64_t>(o->pair_cap, c->n_members);
+    if (rows)
+      hipLaunchKernelGGL(k_copy_table, dim3((uint32_t)((rows * CCLD_RATE_NCOL + 255) / 256)), dim3(256), 0, st,
+                         (const i64*)c->h_pair, c->n_members, o->pair, o->pair_cap, rows, (int)CCLD_RATE_NCOL);
+  }
+  if (o->comm && o->comm_cap) {
+    const uint64_t rows = std::min<uint64_t>(o->comm_cap, c->topo.n_comms);
+    if (rows)
+      hipLaunchKernelGGL(k_copy_table, dim3((uint32_t)((rows * CCLD_RCOMM_NCOL + 255) / 256)), dim3(256), 0, st,
+                         (const i64*)c->h_comm, (uint64_t)c->topo.n_comms, o->comm, o->comm_cap, rows, (int)CCLD_RCOMM_NCOL);
+  }
+  c->prof.end(CCLD_PROF_HANG);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(st));
+  c->prof.collect();
+  if (o->pair_cap < o->n_pair && o->pair) o->status = CCLD_W_TRUNCATED;
+  if (o->comm_cap < o->n_comm && o->comm) o->status = CCLD_W_TRUNCATED;
   return o->status;
 }

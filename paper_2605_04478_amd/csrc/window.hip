@@ -582,7 +582,9 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
     O[CCLD_GRP_SLOW * C + g] = slow ? 1 : 0;
     O[CCLD_GRP_CLASS * C + g] = cls;
     O[CCLD_GRP_ROOT_S1 * C + g] = root1;
-    O[CCLD_GRP_ROOT_S2 * C + g] = CCLD_NO_RANK;
+    // communication-slow root (Eq. 4): the communicator's member of minimal SendRate / RecvRate
+    O[CCLD_GRP_ROOT_S2 * C + g] = (cls == CCLD_SLOW_S2_COMMUNICATION || cls == CCLD_SLOW_S3_MIXED)
+                                      ? a.rate_root[gid / (CCLD_OP_MAX * GROUP_CLS)] : (i64)CCLD_NO_RANK;
     O[CCLD_GRP_REPEATS * C + g] = n.repeats;
     O[CCLD_GRP_LOCATE * C + g] = (slow && n.repeats >= a.p.repeat_threshold) ? 1 : 0;
   }

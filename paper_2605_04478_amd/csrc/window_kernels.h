@@ -89,6 +89,7 @@ struct GroupArgs {
   uint64_t* gkey;            // [n_usable]
   int64_t* range_c;          // [n_usable] T_max - T_min of each usable collective
   GroupState* gstate;
+  const int64_t* rate_root;  // [n_comms] minimal-rate member per communicator (CCLD_NO_RANK before any rate pass)
   int64_t* group;
   uint64_t group_cap;
   ccld_params p;

@@ -29,6 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_host_only_calls():
     L = ccld.lib()
+    for name in ccld.EXPORTS:                       # every entry point is called with declared argument types
+        assert getattr(L, name).argtypes is not None, name
     p = ccld.default_params()
     assert p.tbase_rounds == 100 and p.theta_num == 3 and p.alpha_num == 4 and p.beta_num == 6
     assert p.hang_threshold_ns == 300 * 10**9 and p.barrier_bytes == 4

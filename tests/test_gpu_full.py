@@ -70,3 +70,21 @@ def test_config4_full_size_hang_locate():
         for k in ot:
             assert np.array_equal(gt[k], ot[k]), (name, k)
     an.close()
+
+
+def test_progress_rates_at_4096_ranks():
+    from paper_2605_04478_amd import ccld
+    spec = tg.RateSpec(layout=tg.Layout3D(tp=8, pp=8, dp=64, world=True), n_snapshots=64, n_channels=16, seed=2)
+    tr = tg.generate_rates(spec)
+    assert tr.n == 16_777_216
+    an = ccld.Analyzer(tr.topo, max_window_records=1024, max_snapshot_rows=tr.n)
+    g = an.progress_rates(an.snapshots_to_device(tr.cols), 64, 16)
+    assert g.status == "OK"
+    o = orc.Oracle(tr.topo).progress_rates(tr.cols, 64, 16)
+    for name in ("pair", "comm"):
+        gt, ot = getattr(g, name), getattr(o, name)
+        for k in ot:
+            assert np.array_equal(gt[k], ot[k]), (name, k)
+    mine = np.unique(o.pair["comm"][o.pair["rank"] == tr.slow_rank])
+    assert len(mine) == 4 and all(g.comm["root"][c] == tr.slow_rank for c in mine)
+    an.close()
