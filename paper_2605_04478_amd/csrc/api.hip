@@ -207,7 +207,16 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   c->kf.mb = mb; c->kf.cb = cb; c->kf.sb = 64 - mb - cb;
   c->rank_bits = bits_for_host(topo->n_ranks - 1);
   c->head = 0; c->count = 0; c->next_slot = 0; c->total_ingested = 0;
-  c->bshift = cb > 6 ? cb - 6 : 0;        // at most 64 buckets: long runs per workgroup, payload gathers stay inside one bucket
+  // Communicator buckets of the window placement: enough of them that one bucket's payload rows
+  // (32 bytes per record) stay within about 100 MB, which the memory-side cache holds while the
+  // analysis gathers from that bucket; no more than that, because every further bucket shortens the
+  // runs a workgroup writes at ingest (measured at 82M records: 17 buckets 8.46 ms per step, 34
+  // buckets 8.60 ms, 9 buckets 8.51 ms, one bucket 9.45 ms).
+  {
+    int bb = 0;
+    while (bb < 6 && ((max_window_records * 32) >> bb) > 100000000ull) ++bb;
+    c->bshift = cb > bb ? cb - bb : 0;
+  }
   c->n_buckets = ((topo->n_comms - 1) >> c->bshift) + 1;
   c->sorted_buf = 0; c->last_n = 0; c->blame_valid = false; c->sort_passes = 0;
   c->sf.mb = mb; c->sf.ws = 0;
