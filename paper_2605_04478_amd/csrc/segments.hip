@@ -2,8 +2,9 @@
 // into the lanes of a wavefront and sorted there with a bitonic network whose exchanges are DPP
 // row operations wherever the lane pattern allows, which yields minimum, exact lower median
 // (order statistic floor((n-1)/2)), maximum, and then the median absolute deviation.  Collectives
-// of 65 to 2,048 records are sorted in LDS by one wavefront (up to 512) or one workgroup; longer
-// ones take the counting selection of k_seg_big.
+// of 65 to 512 records take a wavefront each with 2, 4 or 8 values per lane in registers, those of
+// up to 2,048 records a workgroup each with a bitonic sort in LDS, and longer ones the counting
+// selection of k_seg_big.
 #include "window_kernels.h"
 #include "device_utils.h"
 
@@ -15,7 +16,7 @@ namespace ccld {
 
 constexpr i64 T_INFLIGHT = INT64_MAX;
 constexpr int SEG_WAVE_MAX = 64;     // longest collective handled inside one wavefront's registers
-constexpr int SEG_TEAM_WAVE = 512;   // longest collective one wavefront sorts in LDS
+constexpr int SEG_MULTI_MAX = 512;   // longest collective one wavefront sorts in registers (eight values per lane)
 constexpr int SEG_TEAM_MAX = 2048;   // longest collective a workgroup sorts in LDS
 
 __device__ __forceinline__ u64 atomic_add_u64(u64* p, u64 v) {
@@ -268,6 +269,172 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
   else seg_wave_batches<64>(a, base, seg0, nheads, s_head, lane, wave);
 }
 
+// ---- collectives of 65 to 512 records: E values per lane, sorted in registers ---------------------
+// Element i of the collective sits in register i / 64 of lane i % 64.  Every register is sorted by
+// the 64-lane network, then runs of 2, 4, 8 registers are merged: the mirror step pairs register r
+// with r ^ (run - 1) and lane l with 63 - l, strides of whole registers need no lane exchange, and
+// strides below 64 are the lane exchanges of the 64-lane merge.
+template <int E>
+__device__ __forceinline__ void sort_multi(i64 (&v)[E], u32 lane) {
+#pragma unroll
+  for (int r = 0; r < E; ++r) v[r] = sort_groups<64>(v[r], lane);
+#pragma unroll
+  for (int kb = 2; kb <= E; kb <<= 1) {
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      if ((r & (kb >> 1)) == 0) {
+        const int q = r ^ (kb - 1);
+        const i64 b = xor_lane_i64<63>(v[q]);
+        const bool sw = b < v[r];
+        const i64 lo = sw ? b : v[r], hi = sw ? v[r] : b;
+        v[r] = lo;
+        v[q] = xor_lane_i64<63>(hi);
+      }
+    }
+#pragma unroll
+    for (int jb = kb >> 2; jb >= 1; jb >>= 1) {
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        if ((r & jb) == 0) {
+          const int q = r | jb;
+          const bool sw = v[q] < v[r];
+          const i64 lo = sw ? v[q] : v[r], hi = sw ? v[r] : v[q];
+          v[r] = lo; v[q] = hi;
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      v[r] = cmpx<32>(v[r], lane); v[r] = cmpx<16>(v[r], lane); v[r] = cmpx<8>(v[r], lane);
+      v[r] = cmpx<4>(v[r], lane); v[r] = cmpx<2>(v[r], lane); v[r] = cmpx<1>(v[r], lane);
+    }
+  }
+}
+// k-th smallest after sort_multi (k uniform across the wavefront)
+template <int E>
+__device__ __forceinline__ i64 kth_multi(const i64 (&v)[E], u32 k) {
+  i64 sel = v[0];
+#pragma unroll
+  for (int r = 1; r < E; ++r) if ((k >> 6) == (u32)r) sel = v[r];
+  return shfl_i64(sel, (int)(k & 63));
+}
+
+// One wavefront per listed collective of 32 E + 1 .. 64 E records.
+template <int E>
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_multi(SegArgs a) {
+  constexpr u32 LO = 32 * E + 1, HI = 64 * E, NW = SEG_THREADS / CCLD_WAVE;
+  const u32 lane = lane_id();
+  const int mb = a.sf.mb;
+  const u64 mmask = ((u64)1 << mb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  const u32 nbig = (u32)a.counters[CNT_NBIG];
+  for (u32 ent = blockIdx.x * NW + threadIdx.x / CCLD_WAVE; ent < nbig; ent += gridDim.x * NW) {
+    const u32 nn = a.big_list[3 * ent + 2];
+    if (nn < LO || nn > HI) continue;
+    const u32 srow = a.big_list[3 * ent], a0 = a.big_list[3 * ent + 1];
+    const u64 k0 = a.key[a0];
+    const u32 comm = (u32)(k0 >> (mb + a.sf.ws));
+    const u32* ms = a.members_sorted + a.member_off[comm];
+    i64 e[E], x[E];
+    u32 ninfl = 0, nd = 0;
+    bool inc = false;
+    i64 imin = T_INFLIGHT, dmin = INT64_MAX, dmax = INT64_MIN;
+    u32 rmin = 0xFFFFFFFFu, rmax = 0xFFFFFFFFu;
+    u64 hb = 0;
+    u32 hop = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const u32 i = r * CCLD_WAVE + lane;
+      const bool valid = i < nn;
+      e[r] = 0; x[r] = T_INFLIGHT;
+      u64 nb = 0;
+      u32 op = 0, rank = 0;
+      if (valid) {
+        const u32 j = a0 + i;
+        const u64 key = a.key[j];
+        const Row rw = a.row[a.idx[j]];
+        rank = ms[(u32)(key & mmask)];
+        e[r] = rw.t_enter; x[r] = rw.t_exit; nb = rw.bytes; op = rw.op;
+      }
+      if (r == 0) { hb = shfl_u64(nb, 0); hop = __shfl(op, 0, CCLD_WAVE); }
+      inc |= valid && (nb != hb || op != hop);
+      const bool done = valid && x[r] != T_INFLIGHT;
+      nd += (u32)__popcll(ballot64(done));
+      ninfl += (u32)__popcll(ballot64(valid && !done));
+      if (valid && !done) imin = e[r] < imin ? e[r] : imin;
+      if (done) {
+        const i64 d = x[r] - e[r];
+        if (d < dmin || (d == dmin && rank < rmin)) { dmin = d; rmin = rank; }
+        if (d > dmax || (d == dmax && rank < rmax)) { dmax = d; rmax = rank; }
+      }
+    }
+    const bool incons = ballot64(inc) != 0;
+    if (ninfl) imin = reduce_min<64>(imin);
+    reduce_dur<64, false>(dmin, rmin);
+    reduce_dur<64, true>(dmax, rmax);
+    const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
+    // four sorts: arrival, completion, then their absolute deviations from the medians
+    i64 stat_min[2] = {0, 0}, stat_med[2] = {0, 0}, stat_max[2] = {0, 0}, stat_mad[2] = {0, 0};
+#pragma unroll 1
+    for (int pass = 0; pass < 4; ++pass) {
+      const int w = pass & 1;                      // 0 arrival, 1 completion
+      i64 v[E];
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        const bool done = x[r] != T_INFLIGHT;      // lanes past the end hold the in-flight mark too
+        const i64 t = w ? x[r] : e[r];
+        v[r] = !done ? T_INFLIGHT : (pass < 2 ? t : absdiff(t, stat_med[w]));
+      }
+      sort_multi<E>(v, lane);
+      const i64 mid = kth_multi<E>(v, km);
+      if (pass < 2) { stat_min[w] = kth_multi<E>(v, 0); stat_med[w] = mid; stat_max[w] = kth_multi<E>(v, kl); }
+      else stat_mad[w] = mid;
+    }
+    const bool complete = nn == a.comm_size[comm] && ninfl == 0;
+    const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
+    const bool usable = complete && !incons && !barrier;
+    if (lane == 0) {
+      seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> mb) & smask));
+      seg_put(a, CCLD_SEG_N, srow, (i64)nn);
+      seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
+      seg_put(a, CCLD_SEG_STATE, srow,
+              (complete ? CCLD_SEG_COMPLETE : 0) | (!incons ? CCLD_SEG_CONSISTENT : 0) |
+                  (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+      seg_put(a, CCLD_SEG_OP, srow, (i64)hop);
+      seg_put(a, CCLD_SEG_BYTES, srow, (i64)hb);
+      seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
+      seg_put(a, CCLD_SEG_FIRST, srow, (i64)a0);
+      if (nd == 0) {
+        seg_put_empty_stats(a, srow);
+      } else {
+        seg_put(a, CCLD_SEG_ENTER_MIN, srow, stat_min[0]); seg_put(a, CCLD_SEG_ENTER_MED, srow, stat_med[0]);
+        seg_put(a, CCLD_SEG_ENTER_MAX, srow, stat_max[0]); seg_put(a, CCLD_SEG_ENTER_MAD, srow, stat_mad[0]);
+        seg_put(a, CCLD_SEG_EXIT_MIN, srow, stat_min[1]); seg_put(a, CCLD_SEG_EXIT_MED, srow, stat_med[1]);
+        seg_put(a, CCLD_SEG_EXIT_MAX, srow, stat_max[1]); seg_put(a, CCLD_SEG_EXIT_MAD, srow, stat_mad[1]);
+        seg_put(a, CCLD_SEG_DUR_MIN, srow, dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, dmax);
+        seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)rmax);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const u32 i = r * CCLD_WAVE + lane;
+      if (i >= nn) continue;
+      const u32 j = a0 + i;
+      i64 le = 0, lx = 0;
+      u32 f = 0;
+      if (usable) {
+        le = e[r] - stat_med[0]; lx = x[r] - stat_med[1];
+        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, stat_mad[0])) f |= CCLD_FLAG_LATE_ENTER;
+        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, stat_mad[1])) f |= CCLD_FLAG_LATE_EXIT;
+      }
+      a.rec_flag[j] = (uint8_t)f;
+      if (a.lag_e) a.lag_e[j] = le;
+      if (a.lag_x) a.lag_x[j] = lx;
+      if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
+    }
+  }
+}
+
 // ---- collectives of 65 to SEG_TEAM_MAX records -------------------------------------------------
 // length of every listed collective, capped at SEG_TEAM_MAX + 1: one wavefront per entry walks the
 // sorted keys from the collective's first record until the (communicator, counter) prefix changes
@@ -294,46 +461,31 @@ struct TeamAcc {
   u32 ninfl, incons, rmin, rmax;
 };
 
-// threads of a team wait for each other's LDS traffic: a wavefront's LDS operations complete in
-// issue order, so a single-wavefront team only has to keep the compiler from moving them
-template <int WAVES>
-__device__ __forceinline__ void team_sync() {
-  if constexpr (WAVES == 1) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  } else {
-    __syncthreads();
-  }
-}
-
 // one compare-exchange step of the network over v[0, P): partner of i is i ^ M, the element whose
 // bit HB (the top bit of M) is clear keeps the smaller value
-template <int WAVES>
 __device__ __forceinline__ void team_cmpx(i64* v, u32 P, u32 M, u32 HB, u32 t) {
-  for (u32 p = t; p < P / 2; p += CCLD_WAVE * WAVES) {
+  for (u32 p = t; p < P / 2; p += SEG_THREADS) {
     const u32 lo = p & (HB - 1), ia = ((p - lo) << 1) | lo, ib = ia ^ M;
     const i64 va = v[ia], vb = v[ib];
     if (vb < va) { v[ia] = vb; v[ib] = va; }
   }
-  team_sync<WAVES>();
+  __syncthreads();
 }
 // ascending bitonic sort of v[0, P), P a power of two (same merges as sort_groups, in LDS)
-template <int WAVES>
 __device__ __forceinline__ void team_sort(i64* v, u32 P, u32 t) {
   for (u32 k = 2; k <= P; k <<= 1) {
-    team_cmpx<WAVES>(v, P, k - 1, k >> 1, t);
-    for (u32 j = k >> 2; j; j >>= 1) team_cmpx<WAVES>(v, P, j, j, t);
+    team_cmpx(v, P, k - 1, k >> 1, t);
+    for (u32 j = k >> 2; j; j >>= 1) team_cmpx(v, P, j, j, t);
   }
 }
 
-// A team of WAVES wavefronts per collective; arrival and completion times are staged in LDS and a
-// third LDS array is sorted four times (arrival, completion, and their absolute deviations).
-template <int WAVES>
+// One workgroup per collective of 513 to SEG_TEAM_MAX records; arrival and completion times are
+// staged in LDS and a third LDS array is sorted four times (arrival, completion, and their absolute
+// deviations).
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
-  constexpr u32 TEAMS = SEG_THREADS / CCLD_WAVE / WAVES, TT = CCLD_WAVE * WAVES;
-  constexpr u32 CAPN = SEG_TEAM_WAVE * WAVES;
-  constexpr u32 LO = WAVES == 1 ? (u32)SEG_WAVE_MAX + 1 : (u32)SEG_TEAM_WAVE + 1;
+  constexpr u32 TEAMS = 1, TT = SEG_THREADS;
+  constexpr u32 CAPN = SEG_TEAM_MAX;
+  constexpr u32 LO = (u32)SEG_MULTI_MAX + 1;
   __shared__ i64 s_e[TEAMS][CAPN], s_x[TEAMS][CAPN], s_v[TEAMS][CAPN];
   __shared__ TeamAcc s_acc[TEAMS];
   const u32 team = threadIdx.x / TT, t = threadIdx.x % TT;
@@ -352,7 +504,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
       acc.imin = (unsigned long long)T_INFLIGHT; acc.dmin = INT64_MAX; acc.dmax = INT64_MIN;
       acc.ninfl = 0; acc.incons = 0; acc.rmin = 0xFFFFFFFFu; acc.rmax = 0xFFFFFFFFu;
     }
-    team_sync<WAVES>();
+    __syncthreads();
     {
       u32 ni = 0, rmin = 0xFFFFFFFFu, rmax = 0xFFFFFFFFu;
       bool inc = false;
@@ -374,7 +526,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
       if (ni) { atomicAdd(&acc.ninfl, ni); atomicMin(&acc.imin, (unsigned long long)imin); }
       if (inc) atomicOr(&acc.incons, 1u);
       if (rmin != 0xFFFFFFFFu) { atomicMin(&acc.dmin, (long long)dmin); atomicMax(&acc.dmax, (long long)dmax); }
-      team_sync<WAVES>();
+      __syncthreads();
       if (rmin != 0xFFFFFFFFu && dmin == (i64)acc.dmin) atomicMin(&acc.rmin, rmin);
       if (rmax != 0xFFFFFFFFu && dmax == (i64)acc.dmax) atomicMin(&acc.rmax, rmax);
     }
@@ -383,23 +535,23 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
     u32 P = 2;
     while (P < nn) P <<= 1;
     for (u32 i = t; i < P; i += TT) V[i] = (i < nn && X[i] != T_INFLIGHT) ? E[i] : T_INFLIGHT;
-    team_sync<WAVES>();
-    team_sort<WAVES>(V, P, t);
+    __syncthreads();
+    team_sort(V, P, t);
     const i64 min_e = V[0], med_e = V[km], max_e = V[kl];
-    team_sync<WAVES>();
+    __syncthreads();
     for (u32 i = t; i < P; i += TT) V[i] = i < nn ? X[i] : T_INFLIGHT;
-    team_sync<WAVES>();
-    team_sort<WAVES>(V, P, t);
+    __syncthreads();
+    team_sort(V, P, t);
     const i64 min_x = V[0], med_x = V[km], max_x = V[kl];
-    team_sync<WAVES>();
+    __syncthreads();
     for (u32 i = t; i < P; i += TT) V[i] = (i < nn && X[i] != T_INFLIGHT) ? absdiff(E[i], med_e) : T_INFLIGHT;
-    team_sync<WAVES>();
-    team_sort<WAVES>(V, P, t);
+    __syncthreads();
+    team_sort(V, P, t);
     const i64 mad_e = V[km];
-    team_sync<WAVES>();
+    __syncthreads();
     for (u32 i = t; i < P; i += TT) V[i] = (i < nn && X[i] != T_INFLIGHT) ? absdiff(X[i], med_x) : T_INFLIGHT;
-    team_sync<WAVES>();
-    team_sort<WAVES>(V, P, t);
+    __syncthreads();
+    team_sort(V, P, t);
     const i64 mad_x = V[km];
     const u32 comm = (u32)(k0 >> (mb + a.sf.ws));
     const bool complete = nn == a.comm_size[comm] && ninfl == 0;
@@ -444,7 +596,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
       if (a.lag_x) a.lag_x[j] = lx;
       if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
     }
-    team_sync<WAVES>();     // the staged times and the accumulator are reused by the next collective
+    __syncthreads();     // the staged times and the accumulator are reused by the next collective
   }
 }
 
@@ -576,8 +728,10 @@ void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
   if (a.n == 0) return;
   hipLaunchKernelGGL(k_seg_wave, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
   hipLaunchKernelGGL(k_seg_lengths, dim3(1024), dim3(SEG_THREADS), 0, st, a);
-  hipLaunchKernelGGL(k_seg_team<1>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
-  hipLaunchKernelGGL(k_seg_team<4>, dim3(1024), dim3(SEG_THREADS), 0, st, a);
+  hipLaunchKernelGGL(k_seg_multi<2>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+  hipLaunchKernelGGL(k_seg_multi<4>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+  hipLaunchKernelGGL(k_seg_multi<8>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+  hipLaunchKernelGGL(k_seg_team, dim3(1024), dim3(SEG_THREADS), 0, st, a);
   hipLaunchKernelGGL(k_seg_big, dim3(2048), dim3(SEG_THREADS), 0, st, a);
 }
 
