@@ -7,7 +7,7 @@ namespace ccld {
 
 constexpr int SORT_RBITS = 8;                    // widest digit of one pass
 constexpr int SORT_RADIX = 1 << SORT_RBITS;
-constexpr int SORT_THREADS = 256;
+constexpr int SORT_THREADS = 512;
 constexpr int SORT_ITEMS = 8;                    // keys per thread
 constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
 
