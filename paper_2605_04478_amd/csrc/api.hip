@@ -80,7 +80,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->n_members = n_members;
   c->rate_root = w.take<int64_t>(n_comms);
   c->h_cell = w.take<uint64_t>(2 * SN);
-  c->h_cnt = w.take<uint32_t>(SN);
+  c->h_cnt = w.take<uint32_t>(SN / 32 + 1);
   c->h_pair = w.take<int64_t>((uint64_t)CCLD_HPAIR_NCOL * n_members);
   c->h_comm = w.take<int64_t>((uint64_t)CCLD_HCOMM_NCOL * n_comms);
   c->h_wait_slot = w.take<int32_t>(n_members);

@@ -131,7 +131,7 @@ struct ccld_ctx {
   // hang location
   uint64_t n_members;                 // member slots over all communicators
   uint64_t* h_cell;                   // [snap_cap][2]  (operation counter, sent | recv << 32)
-  uint32_t* h_cnt;                    // [snap_cap] rows seen per cell
+  uint32_t* h_cnt;                    // [snap_cap / 32 + 1] presence bitmap of the grid cells
   int64_t* h_pair;                    // [CCLD_HPAIR_NCOL][n_members]
   int64_t* h_comm;                    // [CCLD_HCOMM_NCOL][n_comms]
   int32_t* h_wait_slot;               // [n_members] slot waited on, -1 = none

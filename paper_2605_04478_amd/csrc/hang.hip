@@ -22,11 +22,12 @@ struct HangArgs {
   const u32 *sent, *recv;
   u64 n_rows;
   u32 n_snap, n_ch;
+  int mb;             // bits of the position field in the packed membership words
   DeviceTopology T;
   u64 n_members;
   // grid
   u64* cell;          // [n_members * n_ch * n_snap][2]
-  u32* cnt;
+  u32* cnt;           // presence bitmap, one bit per cell
   // tables
   i64* pair;          // [CCLD_HPAIR_NCOL][n_members]
   i64* hcomm;         // [CCLD_HCOMM_NCOL][n_comms]
@@ -52,16 +53,29 @@ __device__ __forceinline__ int slot_of(const DeviceTopology& T, u32 c, u32 r) {
 // ---- place every row in its cell ------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_hang_place(HangArgs a) {
   u64 status = 0;
+  const uint4* __restrict__ memb4 = reinterpret_cast<const uint4*>(a.T.rank_memb4);
+  const u32 mmask = a.mb < 32 ? (1u << a.mb) - 1 : ~0u;
   for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < a.n_rows; i += (u64)gridDim.x * 256) {
     const u32 c = a.comm[i], r = a.rank[i], ch = a.channel[i], s = a.snap[i];
     if (c >= a.T.n_comms) { status |= DS_UNKNOWN_COMM; continue; }
-    const int slot = r < a.T.n_ranks ? slot_of(a.T, c, r) : -1;
+    int slot = -1;
+    if (r < a.T.n_ranks) {
+      if (memb4) {      // the rank's packed (communicator, position among sorted members) words
+        const uint4 m = memb4[r];
+        const u32 w = c == (m.x >> a.mb) ? m.x : c == (m.y >> a.mb) ? m.y : c == (m.z >> a.mb) ? m.z : m.w;
+        if (c == (w >> a.mb)) slot = (int)a.T.sorted_slot[a.T.member_off[c] + (w & mmask)];
+      } else {
+        slot = slot_of(a.T, c, r);
+      }
+    }
     if (slot < 0) { status |= DS_NOT_MEMBER; continue; }
     if (ch >= a.n_ch || s >= a.n_snap) { status |= DS_RANGE; continue; }
     const u64 k = (((u64)a.T.member_off[c] + (u32)slot) * a.n_ch + ch) * a.n_snap + s;
     a.cell[2 * k] = a.seq_posted[i];
     a.cell[2 * k + 1] = (u64)a.sent[i] | ((u64)a.recv[i] << 32);
-    atomicAdd(&a.cnt[k], 1u);
+    // presence bitmap (one bit per cell: small enough to stay in cache); a bit already set is a duplicate
+    const u32 bit = 1u << (k & 31);
+    if (atomicOr(&a.cnt[k >> 5], bit) & bit) status |= DS_DUPLICATE;
   }
   u64 st = status;
 #pragma unroll
@@ -94,9 +108,7 @@ __global__ __launch_bounds__(256) void k_hang_pairs(HangArgs a) {
       bool diff = false;
       if (s < a.n_snap) {
         diff = a.cell[2 * (base + s)] != sL0 || a.cell[2 * (base + s) + 1] != sL1;
-        const u32 seen = a.cnt[base + s];
-        if (seen == 0) status |= DS_SNAPSHOT_GAP;
-        if (seen > 1) status |= DS_DUPLICATE;
+        if (((a.cnt[(base + s) >> 5] >> ((base + s) & 31)) & 1u) == 0) status |= DS_SNAPSHOT_GAP;
       }
       const u64 m = ballot64(diff);
       if (m) last_diff = s0 + (64 - (u32)__clzll((long long)m));
@@ -321,9 +333,7 @@ __global__ __launch_bounds__(256) void k_rate_pairs(HangArgs a) {
       u64 seq = 0, cnt = 0;
       if (in) {
         seq = a.cell[2 * (base + s)]; cnt = a.cell[2 * (base + s) + 1];
-        const u32 seen = a.cnt[base + s];
-        if (seen == 0) status |= DS_SNAPSHOT_GAP;
-        if (seen > 1) status |= DS_DUPLICATE;
+        if (((a.cnt[(base + s) >> 5] >> ((base + s) & 31)) & 1u) == 0) status |= DS_SNAPSHOT_GAP;
       }
       u64 pseq = shfl_u64(seq, (int)lane - 1), pcnt = shfl_u64(cnt, (int)lane - 1);
       if (lane == 0) { pseq = c_seq; pcnt = c_cnt; }
@@ -448,14 +458,14 @@ static hipError_t place_snapshots(ccld_ctx* c, const ccld_snapshots* sn, uint64_
     a.seq_posted = d_seq; a.snap = d32; a.rank = d32 + n_rows; a.comm = d32 + 2 * n_rows; a.channel = d32 + 3 * n_rows;
     a.sent = d32 + 4 * n_rows; a.recv = d32 + 5 * n_rows;
   }
-  a.n_rows = n_rows; a.n_snap = sn->n_snapshots; a.n_ch = sn->n_channels; a.T = c->topo; a.n_members = c->n_members;
+  a.n_rows = n_rows; a.n_snap = sn->n_snapshots; a.n_ch = sn->n_channels; a.T = c->topo; a.mb = c->kf.mb; a.n_members = c->n_members;
   a.cell = c->h_cell; a.cnt = c->h_cnt; a.pair = c->h_pair; a.hcomm = c->h_comm; a.wait_slot = c->h_wait_slot;
   a.cand = c->h_cand; a.layer_max = c->h_layer_max; a.counters = c->counters;
   a.stall_snapshots = c->p.stall_snapshots; a.fifo_depth = c->p.fifo_depth;
 
   c->prof.begin();
   if ((e = hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st)) != hipSuccess) return e;
-  if ((e = hipMemsetAsync(c->h_cnt, 0, sizeof(uint32_t) * n_cell, st)) != hipSuccess) return e;
+  if ((e = hipMemsetAsync(c->h_cnt, 0, sizeof(uint32_t) * ((n_cell + 31) / 32), st)) != hipSuccess) return e;
   if (n_rows) {
     uint64_t g = (n_rows + 255) / 256; if (g > 4096) g = 4096;
     hipLaunchKernelGGL(k_hang_place, dim3((uint32_t)g), dim3(256), 0, st, a);

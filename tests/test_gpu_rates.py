@@ -62,6 +62,24 @@ def test_random_series_with_long_runs_and_idle_channels():
     run_both(topo, series_cols(series), n_snap, n_ch, on_device=False, what="random-series-host")
 
 
+def test_ranks_in_more_than_four_communicators():
+    # the membership lookup leaves its packed row: placement falls back to searching the member list
+    rng = np.random.default_rng(9)
+    comms = [[3, 0, 2, 1], [0, 1], [2, 0], [0, 3], [1, 0, 3], [2, 3]]
+    topo = ring_topology(4, comms=comms)
+    series = {}
+    for c, members in enumerate(comms):
+        for r in members:
+            q, sent, recv, s = 3, 0, 0, []
+            for t in range(40):
+                if rng.random() < 0.15:
+                    q, sent, recv = q + 1, 0, 0
+                sent += int(rng.integers(0, 3)); recv += int(rng.integers(0, 2))
+                s.append((q, sent, recv))
+            series[(r, c, 0)] = s
+    run_both(topo, series_cols(series), 40, 1, what="five-comms")
+
+
 def test_paper_example_and_validation():
     topo = ring_topology(2)
     series = {(0, 0, 0): [(7, s, 0) for s in [0, 5, 8, 8, 8, 8, 8, 8]] + [(8, 0, 0)],
