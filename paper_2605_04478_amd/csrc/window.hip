@@ -66,12 +66,21 @@ __global__ __launch_bounds__(256) void k_ingest_scan(u32* table, u32* totals, u3
 // records are placed grouped by communicator bucket (the order inside a bucket is arbitrary), so
 // that the analysis, which walks the window in (communicator, ...) order, gathers its payload rows
 // from a small region at a time instead of from the whole window.
-__global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, KeyFormat kf) {
+// THREADS = 512 with LDS_TABLE keeps a copy of the ranks' packed membership rows in LDS (16 bytes per
+// rank): with records in random order that lookup is a gather with no locality, cheaper from LDS
+// than from the L2.
+template <int THREADS, bool LDS_TABLE>
+__global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology T, KeyFormat kf) {
   constexpr int U = 4;               // records per thread in flight
-  extern __shared__ u32 s_off[];     // next free slot of every bucket for this workgroup
-  __shared__ u64 s_status[4], s_max[4];
-  for (u32 b = threadIdx.x; b < a.n_buckets; b += 256)
+  extern __shared__ uint4 s_dyn[];   // [n_ranks] membership rows (LDS_TABLE), then the buckets' next free slots
+  __shared__ u64 s_status[THREADS / CCLD_WAVE], s_max[THREADS / CCLD_WAVE];
+  u32* s_off = reinterpret_cast<u32*>(s_dyn + (LDS_TABLE ? T.n_ranks : 0u));
+  for (u32 b = threadIdx.x; b < a.n_buckets; b += THREADS)
     s_off[b] = a.bucket_base[b] + a.table[(u64)b * gridDim.x + blockIdx.x];
+  if (LDS_TABLE) {
+    const uint4* __restrict__ g = reinterpret_cast<const uint4*>(T.rank_memb4);
+    for (u32 r = threadIdx.x; r < T.n_ranks; r += THREADS) s_dyn[r] = g[r];
+  }
   __syncthreads();
   u64 status = 0, maxseq = 0;
   const u32* __restrict__ in_rank = a.rank;
@@ -88,14 +97,14 @@ __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, 
   // every workgroup walks one contiguous slice of the batch, so its nine streams advance page by page
   const u64 chunk = ((a.n + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
   const u64 i_end = (chunk * (blockIdx.x + 1)) < a.n ? chunk * (blockIdx.x + 1) : a.n;
-  for (u64 i0 = chunk * blockIdx.x + threadIdx.x; i0 < i_end; i0 += 256 * U) {
+  for (u64 i0 = chunk * blockIdx.x + threadIdx.x; i0 < i_end; i0 += THREADS * U) {
     u32 r[U], c[U], op[U];
     u64 sq[U], nb[U];
     i64 te[U], tx[U];
     uint4 mem[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const u64 i = i0 + (u64)u * 256;
+      const u64 i = i0 + (u64)u * THREADS;
       if (i < i_end) {
         r[u] = in_rank[i]; c[u] = in_comm[i]; sq[u] = in_seq[i]; op[u] = in_op[i]; nb[u] = in_bytes[i];
         te[u] = in_te[i]; tx[u] = in_tx[i];
@@ -106,11 +115,11 @@ __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       mem[u] = make_uint4(~0u, ~0u, ~0u, ~0u);
-      if (i0 + (u64)u * 256 < i_end && memb4 && r[u] < T.n_ranks) mem[u] = memb4[r[u]];
+      if (i0 + (u64)u * THREADS < i_end && memb4 && r[u] < T.n_ranks) mem[u] = LDS_TABLE ? s_dyn[r[u]] : memb4[r[u]];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const u64 i = i0 + (u64)u * 256;
+      const u64 i = i0 + (u64)u * THREADS;
       if (i >= i_end) continue;
       u64 key = 0;
       if (c[u] >= T.n_comms) {
@@ -156,7 +165,7 @@ __global__ __launch_bounds__(256) void k_ingest(IngestArgs a, DeviceTopology T, 
   __syncthreads();
   if (threadIdx.x == 0) {
     u64 S = 0, M = 0;
-    for (int w = 0; w < 4; ++w) { S |= s_status[w]; M = s_max[w] > M ? s_max[w] : M; }
+    for (int w = 0; w < THREADS / CCLD_WAVE; ++w) { S |= s_status[w]; M = s_max[w] > M ? s_max[w] : M; }
     if (S) atomic_or_u64(&a.meta->status, S);
     if (M) atomicMax((unsigned long long*)&a.meta->max_seq, (unsigned long long)M);
   }
@@ -166,10 +175,24 @@ void launch_ingest(hipStream_t st, const IngestArgs& a, const DeviceTopology& T,
   u64 g = (a.n + 255) / 256;
   if (g > INGEST_BLOCKS) g = INGEST_BLOCKS;
   const size_t lds = sizeof(u32) * a.n_buckets;
+  // large batches over few enough ranks: half as many workgroups of twice the size, each with the
+  // membership rows in LDS (two workgroups per compute unit)
+  const bool lds_table = T.rank_memb4 && (u64)T.n_ranks * 16 + lds <= 72 * 1024 && a.n >= (1u << 22);
+  if (lds_table) g = (g + 1) / 2;
   hipLaunchKernelGGL(k_ingest_hist, dim3((u32)g), dim3(256), lds, st, a, T.n_comms);
   hipLaunchKernelGGL(k_ingest_scan, dim3(a.n_buckets), dim3(256), 0, st, a.table, a.bucket_base, (u32)g);
   launch_scan_tiles(st, a.bucket_base, a.n_buckets, a.scratch_total);
-  hipLaunchKernelGGL(k_ingest, dim3((u32)g), dim3(256), lds, st, a, T, kf);
+  if (lds_table) {
+    static bool raised = false;       // more than 64 KB of dynamic LDS has to be asked for once
+    if (!raised) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_ingest<512, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+      raised = true;
+    }
+    hipLaunchKernelGGL((k_ingest<512, true>), dim3((u32)g), dim3(512), lds + (size_t)T.n_ranks * 16, st, a, T, kf);
+  }
+  else
+    hipLaunchKernelGGL((k_ingest<256, false>), dim3((u32)g), dim3(256), lds, st, a, T, kf);
 }
 
 // ------------------------------------------------------------------------------------------
