@@ -112,7 +112,13 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, c
   __shared__ u64 s_key[SORT_TILE];
   __shared__ u32 s_idx[PACKED ? 1 : SORT_TILE];
 
-  const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE, tile = blockIdx.x;
+  const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE;
+  // Workgroups are dealt to the eight XCDs in turn.  Neighbouring tiles write neighbouring runs of
+  // every digit, so each XCD takes one contiguous eighth of the tiles: the two halves of an output
+  // line then meet in one L2 instead of leaving two L2s as partial lines.
+  const u32 per_xcd = (n_tiles + 7) / 8;
+  const u32 tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (tile >= n_tiles) return;
   const u32 dmask = (1u << nbits) - 1u;
   const u32 base = tile * SORT_TILE;
   const u32 valid = (n - base) < (u32)SORT_TILE ? (n - base) : (u32)SORT_TILE;
@@ -219,7 +225,7 @@ template <int IN, int OUT>
 static void launch_scatter(hipStream_t stream, const KeySource& src, const u64* key_in, const u32* idx_in,
                            u64* key_out, u32* idx_out, const SortBuffers& buf, u32 n, u32 n_tiles, int shift,
                            int nbits, int ibits) {
-  hipLaunchKernelGGL((k_radix_scatter<IN, OUT>), dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src, key_in, idx_in,
+  hipLaunchKernelGGL((k_radix_scatter<IN, OUT>), dim3((n_tiles + 7) / 8 * 8), dim3(SORT_THREADS), 0, stream, src, key_in, idx_in,
                      key_out, idx_out, (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, shift, nbits, ibits);
 }
 
