@@ -228,14 +228,18 @@ void launch_seg_count(hipStream_t st, const SegArgs& a) {
 // In-place exclusive scan of per-tile counts by one workgroup; counts[n_tiles] and *total_out
 // receive the total.
 __global__ __launch_bounds__(1024) void k_scan_tiles(u32* counts, u32 n_tiles, u64* total_out) {
+  constexpr int PER = 8;             // consecutive counts per thread and round
   __shared__ u32 s_wave[1024 / CCLD_WAVE];
   u32 carry = 0;
-  for (u32 b = 0; b < n_tiles; b += 1024) {
-    const u32 i = b + threadIdx.x;
-    const u32 v = i < n_tiles ? counts[i] : 0u;
+  for (u32 b = 0; b < n_tiles; b += 1024 * PER) {
+    const u32 i0 = b + threadIdx.x * PER;
+    u32 v[PER], sum = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) { v[k] = (i0 + k) < n_tiles ? counts[i0 + k] : 0u; sum += v[k]; }
     u32 tot;
-    const u32 ex = block_exclusive_sum<1024>(v, s_wave, &tot);
-    if (i < n_tiles) counts[i] = carry + ex;
+    u32 ex = carry + block_exclusive_sum<1024>(sum, s_wave, &tot);
+#pragma unroll
+    for (int k = 0; k < PER; ++k) { if ((i0 + k) < n_tiles) counts[i0 + k] = ex; ex += v[k]; }
     carry += tot;
   }
   if (threadIdx.x == 0) { counts[n_tiles] = carry; *total_out = carry; }
@@ -333,12 +337,22 @@ __global__ __launch_bounds__(256) void k_rank_count(const u64* __restrict__ key,
       for (u32 i = threadIdx.x; i < RC_CELLS; i += 256) s_h[i] = 0;
       if (threadIdx.x == 0) s_end = hi;
       __syncthreads();
-      for (u32 j = pos + threadIdx.x; j < hi; j += 256) {
-        const u64 k = key[j];
-        const u32 c = (u32)(k >> cshift);
-        if (c - c0 >= width) { atomicMin(&s_end, j); break; }
-        const u32 slot = (u32)(k & mmask);
-        if (slot - s0 < slots) atomicAdd(&s_h[(c - c0) * slots + (slot - s0)], 1u);
+      // eight keys per thread in flight; the keys are sorted, so the first one past the table's
+      // communicators ends this thread's walk
+      bool more = true;
+      for (u32 j0 = pos + threadIdx.x; more && j0 < hi; j0 += 256 * 8) {
+        u64 k[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const u32 j = j0 + u * 256; k[u] = j < hi ? key[j] : ~0ull; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const u32 j = j0 + u * 256;
+          if (!more || j >= hi) continue;
+          const u32 c = (u32)(k[u] >> cshift);
+          if (c - c0 >= width) { atomicMin(&s_end, j); more = false; continue; }
+          const u32 slot = (u32)(k[u] & mmask);
+          if (slot - s0 < slots) atomicAdd(&s_h[(c - c0) * slots + (slot - s0)], 1u);
+        }
       }
       __syncthreads();
       for (u32 i = threadIdx.x; i < RC_CELLS; i += 256) {
