@@ -20,7 +20,7 @@
  * Pinned by tests/test_oracle_*.py (closed forms of Eq. 1-4, brute force,
  * invariants, injected-fault recovery).  The choices the paper leaves open
  * (segment usability, detection groups by operation type and size class,
- * watermarks under re-analysis, tie rules) are this build's definitions and
+ * watermarks under re-analysis, tie rules) are definitions made here and
  * are "parity unpinned" by the paper itself.
  */
 #include <stdint.h>
@@ -456,7 +456,7 @@ int orc_analyze_window(const int64_t *P, const orc_topology *T, uint64_t n,
  *                                                                 fewest SendCount/RecvCount
  * The operational definitions below (stall test over stall_snapshots snapshots, idle test, ring
  * wait-for edges with a FIFO depth, the filter for ranks that are blocked inside another hung
- * communicator) are this build's reading and are "parity unpinned" by the paper; the tests pin
+ * communicator) are readings made here and are "parity unpinned" by the paper; the tests pin
  * them by brute force on small rings and by the recovery of injected roots.
  * ================================================================================================== */
 enum { PAIR_RANK, PAIR_COMM, PAIR_STALLED, PAIR_ENTERED, PAIR_SEQ, PAIR_SENT, PAIR_RECV, PAIR_WAITS_ON,
@@ -723,7 +723,10 @@ int orc_locate_hang(const int64_t *P, const orc_topology *T, uint64_t n_rows, ui
  * ops / changes (compared by cross-multiplication), undefined without a change.
  * Per communicator: the member of minimal SendRate, of minimal RecvRate, and of the minimal of
  * both kinds (ties: smallest rank); the last one is stored in the state for Eq. 4's
- * communication-slow root. */
+ * communication-slow root.
+ * The paper fixes the reciprocal-of-changes definition and one worked example (pinned in
+ * tests/golden/sendrate_example.txt); the run boundaries, the open last run, the sum over channels
+ * and the tie rule are readings made here: "parity unpinned" by the paper. */
 enum { RATE_RANK, RATE_COMM, RATE_OPS_SEND, RATE_CHG_SEND, RATE_OPS_RECV, RATE_CHG_RECV, RATE_NCOL };
 enum { RC_COMM, RC_ROOT_SEND, RC_ROOT_RECV, RC_ROOT, RC_NCOL };
 
