@@ -220,6 +220,8 @@ class TraceSpec:
     exit_jitter_ns: int = 5_000
     slow_ranks: List[SlowRank] = field(default_factory=list)
     slow_groups: List[SlowGroup] = field(default_factory=list)
+    same_size_per_kind: bool = False  # one size and jitter draw per (communicator kind, counter): every TP / PP / DP
+                                     # group runs the same operation at the same step, as one SPMD program does
     seed: int = 0
     name: str = "trace"
 
@@ -275,14 +277,15 @@ def _gen_slots(spec: TraceSpec, k0: int, k1: int, out: Dict[str, np.ndarray]) ->
         op_k = np.asarray([cyc[int(i)][1] for i in (ks % len(cyc))], dtype=np.uint8)
         # one draw per collective (comm, seq): message size and transfer jitter
         ucomm, inv = np.unique(comm_r, return_inverse=True)
-        ub = rand_unit(spec.seed, _S_BYTES, ucomm[None, :], seq_k[:, None])
+        draw_id = np.full_like(ucomm, 1_000_003 + sorted(per_cycle).index(kind)) if spec.same_size_per_kind else ucomm
+        ub = rand_unit(spec.seed, _S_BYTES, draw_id[None, :], seq_k[:, None])
         if spec.bytes_dist[0] == "pow2":
             lo, hi = spec.bytes_dist[1], spec.bytes_dist[2]
             nbytes_c = np.left_shift(np.int64(1), (lo + np.floor(ub * (hi - lo + 1))).astype(np.int64))
         else:
             lo, hi = spec.bytes_dist[1], spec.bytes_dist[2]
             nbytes_c = np.floor(np.exp2(lo + (hi - lo) * ub)).astype(np.int64)
-        jit_c = np.exp(spec.sigma * rand_normal(spec.seed, _S_JIT, ucomm[None, :], seq_k[:, None]))
+        jit_c = np.exp(spec.sigma * rand_normal(spec.seed, _S_JIT, draw_id[None, :], seq_k[:, None]))
         nbytes = nbytes_c[:, inv]                                    # [m, R]
         jit = jit_c[:, inv]
         # per-record draws
@@ -381,6 +384,53 @@ def generate(spec: TraceSpec, chunk_slots: int = 0, workers: int = 0) -> Trace:
             list(ex.map(work, chunks))
     cols = {k: out[k] for k in COLUMNS}
     return Trace(spec, spec.layout.topology(), cols, out["inj_delay"], out["stretched"])
+
+
+def propagate(tr: Trace, gap_ns: int) -> Trace:
+    """Replays a slot-major trace (as `generate` returns it, not shuffled) as a dependent schedule.
+
+    In the generated trace every collective starts at its slot's fixed time, so a late rank never
+    disturbs anybody's later operations.  Here a rank enters its next collective `gap_ns` (its
+    compute time) after leaving the previous one, plus the record's own entry jitter and injected
+    delay; a collective starts when its last member has entered and every member leaves after the
+    record's own transfer time.  A delay therefore travels: the peers of a late rank leave late,
+    carry the delay into their next collectives on other communicators, and so on until the whole
+    job has absorbed it.  Sizes, jitter draws, injected delays and clock skews are those of the
+    input trace; only the two time columns change."""
+    spec = tr.spec
+    L = spec.layout
+    R = L.n_ranks
+    cyc = spec.cycle
+    ranks = np.arange(R, dtype=np.int64)
+    skew = np.rint((rand_unit(spec.seed, _S_SKEW, ranks) * 2.0 - 1.0) * spec.skew_ns).astype(np.int64)
+    if not np.array_equal(tr.cols["rank"][:R], ranks.astype(np.uint32)):
+        raise ValueError("propagate() needs the slot-major order of generate()")
+    te = tr.cols["t_enter"].reshape(-1, R) - T_EPOCH_NS - skew[None, :]
+    tx = tr.cols["t_exit"].reshape(-1, R) - T_EPOCH_NS - skew[None, :]
+    n_slots = te.shape[0]
+
+    def group_max(v, kind):
+        v4 = v.reshape(L.pp, L.dp, L.tp)
+        axis = {"tp": 2, "pp": 0, "dp": 1}.get(kind)
+        m = v4.max(axis=axis, keepdims=True) if axis is not None else v4.max(keepdims=True)
+        return np.broadcast_to(m, v4.shape).reshape(R)
+
+    new_e = np.empty_like(te)
+    new_x = np.empty_like(tx)
+    ready = np.zeros(R, dtype=np.int64)
+    for k in range(n_slots):
+        kind = cyc[k % len(cyc)][0]
+        own = te[k] - k * spec.slot_ns                      # entry jitter + injected delay of the record
+        tail = tx[k] - group_max(te[k], kind)               # transfer time + exit jitter of the record
+        ent = ready + gap_ns + own
+        ext = group_max(ent, kind) + tail
+        new_e[k] = ent
+        new_x[k] = ext
+        ready = ext
+    cols = dict(tr.cols)
+    cols["t_enter"] = (new_e + skew[None, :] + T_EPOCH_NS).reshape(-1)
+    cols["t_exit"] = (new_x + skew[None, :] + T_EPOCH_NS).reshape(-1)
+    return Trace(spec, tr.topo, cols, tr.inj_delay, tr.stretched)
 
 
 # --------------------------------------------------------------------------

@@ -105,6 +105,18 @@ def test_config3_layout_parity():
     assert g.n_flag > 0
 
 
+def test_propagating_schedule_parity():
+    """A dependent schedule (delays travel to the peers' later operations): tens of thousands of
+    secondary flags on every rank; the faulty ranks still lead the blame order."""
+    spec = tg.config2(n_cycles=60)
+    spec.same_size_per_kind = True
+    tr = tg.propagate(tg.generate(spec), gap_ns=2_000_000).shuffled(2)
+    g, o = run_both(tr.topo, tr.cols, now=int(tr.cols["t_exit"].max()) + 1, what="propagating")
+    faulty = sorted([s.rank for s in spec.slow_ranks] + [r for grp in spec.slow_groups for r in grp.ranks])
+    assert g.n_flag > 1000
+    assert sorted(int(r) for r in o.order[:len(faulty)]) == faulty
+
+
 @pytest.mark.parametrize("R,n_seq", [(70, 400), (700, 60)])
 def test_random_partial_rounds_with_ties(R, n_seq):
     rng = np.random.default_rng(3)

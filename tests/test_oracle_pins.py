@@ -404,3 +404,34 @@ def test_config3_shape_faults_are_located_on_a_small_layout():
     top = set(np.nonzero(r.blame["n_late_enter"] >= 2)[0].tolist())
     assert top == set(slow)
     assert set(np.nonzero(r.blame["n_late_exit"] >= 2)[0].tolist()) == set(nic)
+
+
+# ---- dependent schedules: a delay travels to the peers' later operations ---------------------------
+def test_propagating_schedule_keeps_faulty_ranks_on_top_and_clean_runs_clean():
+    # every group of a kind runs the same operation at the same step (one SPMD program): without
+    # that, groups finish at different times and their members meet late without any fault
+    spec = tg.config2(n_cycles=120)
+    spec.same_size_per_kind = True
+    tr = tg.generate(spec)
+    pr = tg.propagate(tr, gap_ns=2_000_000)
+    R = spec.layout.n_ranks
+    # the replay keeps every record's own entry offset and transfer time: only the schedule moves
+    assert np.all(pr.cols["t_exit"] >= pr.cols["t_enter"])
+    e0 = tr.cols["t_enter"].reshape(-1, R)
+    e1 = pr.cols["t_enter"].reshape(-1, R)
+    assert np.array_equal(e1[0] - e0[0], np.full(R, 2_000_000))          # first slot: shifted by the gap only
+    assert np.all(np.diff(e1, axis=0) > 0)                               # a rank's operations stay ordered
+    faulty = sorted([s.rank for s in spec.slow_ranks] + [r for g in spec.slow_groups for r in g.ranks])
+    o = orc.Oracle(pr.topo)
+    w = o.analyze_window(pr.shuffled(1).cols, int(pr.cols["t_exit"].max()) + 1)
+    assert w.status == "OK"
+    n_flags = w.blame["n_late_enter"] + w.blame["n_late_exit"]
+    # secondary flags reach far more ranks than were faulty, yet the faulty ranks lead the blame order
+    assert int((n_flags > 0).sum()) > 10 * len(faulty)
+    assert sorted(int(r) for r in w.order[:len(faulty)]) == faulty
+    # without faults nothing is flagged although every collective now waits for its slowest member
+    cspec = tg.config2(n_cycles=60, faults=False)
+    cspec.same_size_per_kind = True
+    clean = tg.propagate(tg.generate(cspec), gap_ns=2_000_000)
+    wc = orc.Oracle(clean.topo).analyze_window(clean.cols, int(clean.cols["t_exit"].max()) + 1)
+    assert wc.status == "OK" and len(wc.flag["rank"]) == 0
