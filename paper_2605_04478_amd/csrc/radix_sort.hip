@@ -29,8 +29,8 @@ __device__ __forceinline__ u64 load_key(const KeySource& s, u32 j, u32* phys) {
 // ---- per-tile digit histogram --------------------------------------------------------------
 // A workgroup counts HIST_TILES consecutive tiles, so that each digit's counts leave as one
 // contiguous 32-byte piece of the digit-major table instead of eight scattered words.
-constexpr int HIST_TILES = 8;
-template <bool FIRST>
+// Small inputs take fewer tiles per workgroup so that there are still several workgroups per compute unit.
+template <bool FIRST, int HIST_TILES>
 __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, const u64* __restrict__ key_in,
                                                              u32* __restrict__ table, u32 n, u32 n_tiles,
                                                              int shift, u32 dmask) {
@@ -250,12 +250,14 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const
     const int hist_shift = done_bits + ((packed && !first) ? ibits : 0);
     const int scat_shift = done_bits + (packed ? ibits : 0);
     if (prof) prof->begin();
-    if (first)
-      hipLaunchKernelGGL(k_radix_hist<true>, dim3((n_tiles + HIST_TILES - 1) / HIST_TILES), dim3(SORT_THREADS), 0, stream, src,
-                         (const u64*)nullptr, buf.table, n, n_tiles, hist_shift, dmask);
-    else
-      hipLaunchKernelGGL(k_radix_hist<false>, dim3((n_tiles + HIST_TILES - 1) / HIST_TILES), dim3(SORT_THREADS), 0, stream, src,
-                         (const u64*)buf.key[cur], buf.table, n, n_tiles, hist_shift, dmask);
+    const u64* hin = first ? nullptr : buf.key[cur];
+    if (n_tiles >= 8192) {
+      if (first) hipLaunchKernelGGL((k_radix_hist<true, 8>), dim3((n_tiles + 7) / 8), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
+      else hipLaunchKernelGGL((k_radix_hist<false, 8>), dim3((n_tiles + 7) / 8), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
+    } else {
+      if (first) hipLaunchKernelGGL((k_radix_hist<true, 2>), dim3((n_tiles + 1) / 2), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
+      else hipLaunchKernelGGL((k_radix_hist<false, 2>), dim3((n_tiles + 1) / 2), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
+    }
     if (prof) { prof->end(cls_hist); prof->begin(); }
     hipLaunchKernelGGL(k_radix_scan, dim3(dmask + 1), dim3(SORT_THREADS), 0, stream, buf.table, buf.totals, n_tiles);
     if (prof) { prof->end(cls_scan); prof->begin(); }
