@@ -551,8 +551,24 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
   if (any_new)
     for (u32 i = f + tid; i < e; i += 256)
       if (seq_of(i) + 1 > g0.baselined_wm) atomicMin(&s_i0, i);
-  // Eq. 2 needs the largest range
-  for (u32 i = f + tid; i < e; i += 256) atomicMax(&s_best, (unsigned long long)a.range_c[sidx[i]]);
+  // Eq. 2 needs the largest range; the first rounds of every thread stay in registers for the
+  // second look below
+  constexpr int KEEP = 4;
+  unsigned long long kept[KEEP];
+  {
+    unsigned long long mine = 0;
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+      const u32 i = f + tid + 256u * j;
+      kept[j] = i < e ? (unsigned long long)a.range_c[sidx[i]] : 0ull;
+      mine = kept[j] > mine ? kept[j] : mine;
+    }
+    for (u32 i = f + tid + 256u * KEEP; i < e; i += 256) {
+      const unsigned long long v = (unsigned long long)a.range_c[sidx[i]];
+      mine = v > mine ? v : mine;
+    }
+    if (mine) atomicMax(&s_best, mine);
+  }
   __syncthreads();
   const u32 i0 = s_i0;
   const i64 t0 = (g0.cnt == 0 && i0 < e) ? EMIN[a.usable_list[sidx[i0]]] : g0.t0;
@@ -564,8 +580,18 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
     }
   }
   const unsigned long long best = s_best;
-  for (u32 i = f + tid; i < e; i += 256)
-    if ((unsigned long long)a.range_c[sidx[i]] == best) atomicMin(&s_kstar, i);
+  {
+    u32 first = e;
+#pragma unroll
+    for (int j = KEEP - 1; j >= 0; --j) {
+      const u32 i = f + tid + 256u * j;
+      if (i < e && kept[j] == best) first = i;
+    }
+    if (first == e)
+      for (u32 i = f + tid + 256u * KEEP; i < e; i += 256)
+        if ((unsigned long long)a.range_c[sidx[i]] == best) { first = i; break; }
+    if (first < e) atomicMin(&s_kstar, first);
+  }
   __syncthreads();
   const u32 istar = s_istar;
   if (!g0.frozen) {
