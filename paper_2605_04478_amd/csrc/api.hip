@@ -219,7 +219,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   }
   c->n_buckets = ((topo->n_comms - 1) >> c->bshift) + 1;
   c->sorted_buf = 0; c->last_n = 0; c->blame_valid = false; c->sort_passes = 0;
-  c->sf.mb = mb; c->sf.ws = 0;
+  c->sf.mb = mb; c->sf.ws = 0; c->sf.seq_base = 0;
   uint64_t n_members = 0;
   check_topology(topo, &n_members);
   Carver w{(uint8_t*)workspace, 0};
@@ -284,7 +284,10 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   if (hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, c->stream) != hipSuccess) rs = CCLD_E_HIP;
   launch_fill_u64(c->stream, (uint64_t*)c->rate_root, topo->n_comms, (uint64_t)CCLD_NO_RANK);
   if (hipMemsetAsync(c->blame, 0, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)topo->n_ranks, c->stream) != hipSuccess) rs = CCLD_E_HIP;
-  if (hipHostMalloc((void**)&c->h_pinned, 4096 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) rs = CCLD_E_HIP;
+  {     // pinned readback buffer: the counters, or the headers of every batch slot
+    const size_t bytes = std::max<size_t>(4096 * sizeof(uint64_t), sizeof(BatchMeta) * ((size_t)c->p.window_batches + 2));
+    if (hipHostMalloc((void**)&c->h_pinned, bytes, hipHostMallocDefault) != hipSuccess) rs = CCLD_E_HIP;
+  }
   if (hipStreamSynchronize(c->stream) != hipSuccess) rs = CCLD_E_HIP;   // host vectors above die at return
   if (rs != CCLD_OK) { (void)hipGetLastError(); if (c->h_pinned) (void)hipHostFree(c->h_pinned); delete c; return rs; }
   *out = c;
@@ -382,13 +385,16 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
 
   // 1. data errors found at ingest, and the widest sequence number in the window
   const size_t nb = c->batch_slot.size();
-  uint64_t bits = 0, max_seq = 0;
+  uint64_t bits = 0, max_seq = 0, min_seq = ~0ull;
   if (nb) {
     const uint32_t n_meta = c->p.window_batches + 2;
     HIP_TRY(hipMemcpyAsync(c->h_pinned, c->batch_meta, sizeof(BatchMeta) * n_meta, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     const BatchMeta* hm = (const BatchMeta*)c->h_pinned;
-    for (size_t i = 0; i < nb; ++i) { bits |= hm[c->batch_slot[i]].status; max_seq = std::max(max_seq, hm[c->batch_slot[i]].max_seq); }
+    for (size_t i = 0; i < nb; ++i) {
+      const BatchMeta& m = hm[c->batch_slot[i]];
+      bits |= m.status; max_seq = std::max(max_seq, m.max_seq); min_seq = std::min(min_seq, ~m.max_inv_seq);
+    }
   }
   if (bits) return o->status = data_status(bits);
   o->n_records = n;
@@ -398,14 +404,17 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   if (n == 0) { HIP_TRY(hipStreamSynchronize(st)); c->blame_valid = true; return o->status; }
 
   // 2. sort by (communicator, operation counter, rank) on the significant bits only
-  const int mb = c->kf.mb, cb = c->kf.cb, ws = bits_for_host(max_seq);
-  c->sf.mb = mb; c->sf.ws = ws;
+  // the operation counters of the window relative to its smallest one
+  if (min_seq > max_seq) min_seq = max_seq;
+  const int mb = c->kf.mb, cb = c->kf.cb, ws = bits_for_host(max_seq - min_seq);
+  c->sf.mb = mb; c->sf.ws = ws; c->sf.seq_base = min_seq;
   KeySource src;
   src.key = c->win_key; src.head = (uint32_t)c->head; src.cap = (uint32_t)c->cap;
-  src.squeeze = cb > 0 ? 1 : 0;
-  src.hi_shift = cb > 0 ? 64 - cb : 0;
+  src.squeeze = 1;
+  src.hi_shift = 64 - cb;                                  // 64 when there is a single communicator
   src.lo_bits = mb + ws;
-  src.lo_mask = (mb + ws) >= 64 ? ~0ull : (((uint64_t)1 << (mb + ws)) - 1);
+  src.lo_mask = cb > 0 ? (((uint64_t)1 << (64 - cb)) - 1) : ~0ull;      // everything below the communicator field
+  src.lo_sub = min_seq << mb;
   const int sorted = radix_sort_pairs(st, src, n, c->sb, mb + ws + cb, &c->prof, CCLD_PROF_SORT_HIST,
                                       CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER);
   c->sort_passes = (mb + ws + cb) <= 0 ? 1 : (mb + ws + cb + SORT_RBITS - 1) / SORT_RBITS;
@@ -464,7 +473,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
     uint64_t* bk = c->keyC;       // keys are written to C, first pass sorts C -> buffer 0 of sb2
     c->prof.begin();
     launch_blame_keys(st, skey, c->flag_pos, n_flag, c->sf, c->topo, bk);
-    KeySource bs; bs.key = bk; bs.head = 0; bs.cap = n_flag; bs.squeeze = 0; bs.hi_shift = 0; bs.lo_bits = 0; bs.lo_mask = 0;
+    KeySource bs; bs.key = bk; bs.head = 0; bs.cap = n_flag; bs.squeeze = 0; bs.hi_shift = 0; bs.lo_bits = 0; bs.lo_mask = 0; bs.lo_sub = 0;
     const int r2 = radix_sort_pairs(st, bs, n_flag, sb2, c->rank_bits);
     if (r2 < 0) return o->status = CCLD_E_HIP;
     launch_blame_reduce(st, sb2.key[r2], sb2.idx[r2], n_flag, c->flag_pos, sa.rec_flag, c->flag_lag, c->cap, n_ranks, c->blame);
@@ -501,7 +510,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
     ga.range_c = c->big_ex;       // free again once the collectives have been analysed
     c->prof.begin();
     launch_group_keys(st, ga, n_usable);
-    KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = n_usable; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0;
+    KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = n_usable; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0; gs.lo_sub = 0;
     // sort C -> buffers {other main, C}: the first pass reads C and writes buffer 0, so C is free again for pass 2
     const int r3 = radix_sort_pairs(st, gs, n_usable, sb2, cb + 10);
     if (r3 < 0) return o->status = CCLD_E_HIP;

@@ -27,9 +27,12 @@ struct KeyFormat {
   int sb;              // bits available to the sequence number: 64 - mb - cb
 };
 
-// Squeezed key used from the sort onwards: comm << (mb + ws) | seq << mb | slot.
+// Squeezed key used from the sort onwards: comm << (mb + ws) | (seq - seq_base) << mb | slot, with
+// seq_base the window's smallest operation counter: a long-running job's large counters do not
+// widen the key.
 struct SqueezedFormat {
-  int mb, ws;          // member-slot bits, sequence bits actually present in this window
+  int mb, ws;          // member-slot bits, bits of (largest - smallest operation counter) in this window
+  uint64_t seq_base;   // the window's smallest operation counter
 };
 
 struct DeviceTopology {
@@ -69,8 +72,9 @@ enum { DS_UNKNOWN_COMM = 1, DS_NOT_MEMBER = 2, DS_RANGE = 4, DS_KEY_WIDTH = 8, D
 
 struct BatchSlot { uint64_t n; };
 
-// device-side header of per-batch results: [status bits, max sequence number]
-struct BatchMeta { uint64_t status; uint64_t max_seq; };
+// device-side header of per-batch results: status bits, largest operation counter, and the largest
+// complement of one (i.e. ~smallest counter), so that a zeroed header means "no record yet"
+struct BatchMeta { uint64_t status; uint64_t max_seq; uint64_t max_inv_seq; uint64_t pad; };
 
 constexpr int SEG_TILE = 1024;       // sorted records owned by one workgroup of the segment kernels
 constexpr int SEG_THREADS = 256;

@@ -17,9 +17,9 @@ constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
 struct KeySource {
   const uint64_t* key;
   uint32_t head, cap;        // circular: element j lives at (head + j) mod cap
-  int squeeze;               // 1: key' = ((key >> hi_shift) << lo_bits) | (key & lo_mask)
+  int squeeze;               // 1: key' = ((key >> hi_shift) << lo_bits) | ((key & lo_mask) - lo_sub); hi_shift 64 = no high field
   int hi_shift, lo_bits;
-  uint64_t lo_mask;
+  uint64_t lo_mask, lo_sub;
 };
 
 struct SortBuffers {

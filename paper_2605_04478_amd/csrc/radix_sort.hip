@@ -22,7 +22,7 @@ __device__ __forceinline__ u64 load_key(const KeySource& s, u32 j, u32* phys) {
   if (p >= s.cap) p -= s.cap;
   *phys = p;
   u64 k = s.key[p];
-  if (s.squeeze) k = ((k >> s.hi_shift) << s.lo_bits) | (k & s.lo_mask);
+  if (s.squeeze) k = (s.hi_shift < 64 ? (k >> s.hi_shift) << s.lo_bits : 0ull) | ((k & s.lo_mask) - s.lo_sub);
   return k;
 }
 

@@ -177,7 +177,7 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
       if (l == 0) {
         const u32 srow = seg0 + sl;
         seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
-        seg_put(a, CCLD_SEG_SEQ, srow, (i64)((key >> mb) & smask));
+        seg_put(a, CCLD_SEG_SEQ, srow, (i64)(((key >> mb) & smask) + a.sf.seq_base));
         seg_put(a, CCLD_SEG_N, srow, (i64)n);
         seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
         seg_put(a, CCLD_SEG_STATE, srow,
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_multi(SegArgs a) {
     const bool usable = complete && !incons && !barrier;
     if (lane == 0) {
       seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
-      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> mb) & smask));
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)(((k0 >> mb) & smask) + a.sf.seq_base));
       seg_put(a, CCLD_SEG_N, srow, (i64)nn);
       seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
       seg_put(a, CCLD_SEG_STATE, srow,
@@ -560,7 +560,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
     const bool usable = complete && consistent && !barrier;
     if (t == 0) {
       seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
-      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> mb) & smask));
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)(((k0 >> mb) & smask) + a.sf.seq_base));
       seg_put(a, CCLD_SEG_N, srow, (i64)nn);
       seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
       seg_put(a, CCLD_SEG_STATE, srow,
@@ -645,7 +645,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
     const u32 ninfl = s_ninfl, nd = nn - ninfl, km = nd ? (nd - 1) / 2 : 0;
     if (tid == 0) {
       seg_put(a, CCLD_SEG_COMM, srow, (i64)(k0 >> (mb + a.sf.ws)));
-      seg_put(a, CCLD_SEG_SEQ, srow, (i64)((k0 >> mb) & smask));
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)(((k0 >> mb) & smask) + a.sf.seq_base));
       seg_put(a, CCLD_SEG_N, srow, (i64)nn);
       seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
       seg_put(a, CCLD_SEG_OP, srow, (i64)h.op);

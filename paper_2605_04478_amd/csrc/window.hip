@@ -73,7 +73,7 @@ template <int THREADS, bool LDS_TABLE>
 __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology T, KeyFormat kf) {
   constexpr int U = 4;               // records per thread in flight
   extern __shared__ uint4 s_dyn[];   // [n_ranks] membership rows (LDS_TABLE), then the buckets' next free slots
-  __shared__ u64 s_status[THREADS / CCLD_WAVE], s_max[THREADS / CCLD_WAVE];
+  __shared__ u64 s_status[THREADS / CCLD_WAVE], s_max[THREADS / CCLD_WAVE], s_inv[THREADS / CCLD_WAVE];
   u32* s_off = reinterpret_cast<u32*>(s_dyn + (LDS_TABLE ? T.n_ranks : 0u));
   for (u32 b = threadIdx.x; b < a.n_buckets; b += THREADS)
     s_off[b] = a.bucket_base[b] + a.table[(u64)b * gridDim.x + blockIdx.x];
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology
     for (u32 r = threadIdx.x; r < T.n_ranks; r += THREADS) s_dyn[r] = g[r];
   }
   __syncthreads();
-  u64 status = 0, maxseq = 0;
+  u64 status = 0, maxseq = 0, maxinv = 0;      // maxinv = ~(smallest operation counter)
   const u32* __restrict__ in_rank = a.rank;
   const u32* __restrict__ in_comm = a.comm;
   const u64* __restrict__ in_seq = a.seq;
@@ -143,6 +143,7 @@ __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology
         } else {
           key = (kf.cb ? ((u64)c[u] << (64 - kf.cb)) : 0ull) | (sq[u] << kf.mb) | (u64)slot;
           maxseq = sq[u] > maxseq ? sq[u] : maxseq;
+          maxinv = ~sq[u] > maxinv ? ~sq[u] : maxinv;
         }
       }
       const u32 at = atomicAdd(&s_off[c[u] < T.n_comms ? (c[u] >> a.bshift) : 0u], 1u);
@@ -159,15 +160,18 @@ __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology
   u64 st = status;
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) st |= shfl_xor_u64(st, m);
-  u64 mx = wave_max_u64(maxseq);
+  u64 mx = wave_max_u64(maxseq), mi = wave_max_u64(maxinv);
   const u32 lane = lane_id(), wave = threadIdx.x / CCLD_WAVE;
-  if (lane == 0) { s_status[wave] = st; s_max[wave] = mx; }
+  if (lane == 0) { s_status[wave] = st; s_max[wave] = mx; s_inv[wave] = mi; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    u64 S = 0, M = 0;
-    for (int w = 0; w < THREADS / CCLD_WAVE; ++w) { S |= s_status[w]; M = s_max[w] > M ? s_max[w] : M; }
+    u64 S = 0, M = 0, I = 0;
+    for (int w = 0; w < THREADS / CCLD_WAVE; ++w) {
+      S |= s_status[w]; M = s_max[w] > M ? s_max[w] : M; I = s_inv[w] > I ? s_inv[w] : I;
+    }
     if (S) atomic_or_u64(&a.meta->status, S);
     if (M) atomicMax((unsigned long long*)&a.meta->max_seq, (unsigned long long)M);
+    if (I) atomicMax((unsigned long long*)&a.meta->max_inv_seq, (unsigned long long)I);
   }
 }
 void launch_ingest(hipStream_t st, const IngestArgs& a, const DeviceTopology& T, const KeyFormat& kf) {
@@ -290,7 +294,7 @@ __global__ __launch_bounds__(256) void k_flag_emit(FlagArgs a) {
       const u64 key = a.key[j];
       const u32 comm = (u32)(key >> (mb + a.sf.ws));
       a.flag[(u64)CCLD_FLG_COMM * a.flag_cap + k] = (i64)comm;
-      a.flag[(u64)CCLD_FLG_SEQ * a.flag_cap + k] = (i64)((key >> mb) & smask);
+      a.flag[(u64)CCLD_FLG_SEQ * a.flag_cap + k] = (i64)(((key >> mb) & smask) + a.sf.seq_base);
       a.flag[(u64)CCLD_FLG_RANK * a.flag_cap + k] =
           (i64)rank_of_slot(a.member_off, a.members_sorted, comm, (u32)(key & mmask));
       a.flag[(u64)CCLD_FLG_KIND * a.flag_cap + k] = (i64)f;

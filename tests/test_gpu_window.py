@@ -202,6 +202,31 @@ def test_many_communicators_per_rank_and_unsorted_members():
     assert g.n_flag > 0 and g.n_alert > 0
 
 
+@pytest.mark.parametrize("seq0", [0, 7, 10**6 + 3, 2**40 + 12345])
+def test_large_operation_counters(seq0):
+    """Counters of a long-running job: the sort keys carry them relative to the window's smallest
+    one; one communicator (no communicator field in the key) and several."""
+    rng = np.random.default_rng(5)
+    for comms in ([[0, 1, 2, 3]], [[0, 1, 2, 3], [2, 0], [1, 3, 2]]):
+        topo = ring_topology(4, comms=comms)
+        rows = []
+        for c, members in enumerate(comms):
+            for j in range(90):
+                s = seq0 + 3 * c + j + (5 if j > 60 else 0)           # a gap in the counters
+                te = T0 + j * 10**7 + rng.integers(0, 2000, len(members))
+                tx = te + 10**6 + rng.integers(0, 3000, len(members))
+                if j % 9 == 4:
+                    te[0] += 4_000_000
+                    tx[0] = max(tx[0], te[0] + 10)
+                for r, a, b in zip(members, te, tx):
+                    rows.append((r, c, s, 0, 1 << 16, int(a), int(b)))
+        cols = toy_cols(rows)
+        p = rng.permutation(len(rows))
+        cols = {k: v[p] for k, v in cols.items()}
+        g, o = run_both(topo, cols, what=f"seq0={seq0}", tbase_init_ns=1000)
+        assert g.n_flag > 0 and int(g.seg["seq"].min()) == seq0
+
+
 def test_validation_parity():
     topo = ring_topology(4, comms=[[0, 1], [2, 3]])
     ok = [(0, 0, 0, 0, 8, T0, T0 + 1), (1, 0, 0, 0, 8, T0, T0 + 1)]
