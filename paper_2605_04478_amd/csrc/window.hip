@@ -532,7 +532,8 @@ void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_usable,
 // (m = min(tbase_rounds, rounds within the warm-up span)); Eq. 2: the window's round of largest
 // T_max - T_min; Eq. 3: slow iff (T_max - T_base)/T_base > theta; Eq. 4: P = (T_max - T_min)/
 // (T_max - T_base) against alpha / beta; repetition counter.  All ratios cross-multiplied.
-__global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __restrict__ skey,
+template <int T>          // threads per group: a full workgroup, or one wavefront where groups are short
+__global__ __launch_bounds__(T) void k_group_eval(GroupArgs a, const u64* __restrict__ skey,
                                                     const u32* __restrict__ sidx, u32 n_usable,
                                                     const u32* __restrict__ group_first, u32 n_group) {
   __shared__ u32 s_i0, s_istar, s_kstar;
@@ -553,7 +554,7 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
   // (ascending counters: compare the last round first; a fully visited group needs no search)
   const bool any_new = seq_of(e - 1) + 1 > g0.baselined_wm;
   if (any_new)
-    for (u32 i = f + tid; i < e; i += 256)
+    for (u32 i = f + tid; i < e; i += T)
       if (seq_of(i) + 1 > g0.baselined_wm) atomicMin(&s_i0, i);
   // Eq. 2 needs the largest range; the first rounds of every thread stay in registers for the
   // second look below
@@ -563,11 +564,11 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
     unsigned long long mine = 0;
 #pragma unroll
     for (int j = 0; j < KEEP; ++j) {
-      const u32 i = f + tid + 256u * j;
+      const u32 i = f + tid + (u32)T * j;
       kept[j] = i < e ? (unsigned long long)a.range_c[sidx[i]] : 0ull;
       mine = kept[j] > mine ? kept[j] : mine;
     }
-    for (u32 i = f + tid + 256u * KEEP; i < e; i += 256) {
+    for (u32 i = f + tid + (u32)T * KEEP; i < e; i += T) {
       const unsigned long long v = (unsigned long long)a.range_c[sidx[i]];
       mine = v > mine ? v : mine;
     }
@@ -577,7 +578,7 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
   const u32 i0 = s_i0;
   const i64 t0 = (g0.cnt == 0 && i0 < e) ? EMIN[a.usable_list[sidx[i0]]] : g0.t0;
   if (!g0.frozen) {
-    for (u32 i = i0 + tid; i < e; i += 256) {
+    for (u32 i = i0 + tid; i < e; i += T) {
       const u32 s = a.usable_list[sidx[i]];
       const u64 q = i - i0;
       if ((u64)g0.cnt + q >= (u64)a.p.tbase_rounds || EMIN[s] - t0 > a.p.tbase_warmup_ns) atomicMin(&s_istar, i);
@@ -588,11 +589,11 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
     u32 first = e;
 #pragma unroll
     for (int j = KEEP - 1; j >= 0; --j) {
-      const u32 i = f + tid + 256u * j;
+      const u32 i = f + tid + (u32)T * j;
       if (i < e && kept[j] == best) first = i;
     }
     if (first == e)
-      for (u32 i = f + tid + 256u * KEEP; i < e; i += 256)
+      for (u32 i = f + tid + (u32)T * KEEP; i < e; i += T)
         if ((unsigned long long)a.range_c[sidx[i]] == best) { first = i; break; }
     if (first < e) atomicMin(&s_kstar, first);
   }
@@ -600,7 +601,7 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
   const u32 istar = s_istar;
   if (!g0.frozen) {
     unsigned long long part = 0;
-    for (u32 i = i0 + tid; i < istar; i += 256) part += (unsigned long long)DMAX[a.usable_list[sidx[i]]];
+    for (u32 i = i0 + tid; i < istar; i += T) part += (unsigned long long)DMAX[a.usable_list[sidx[i]]];
     if (part) atomicAdd(&s_sum, part);
   }
   __syncthreads();
@@ -658,7 +659,11 @@ __global__ __launch_bounds__(256) void k_group_eval(GroupArgs a, const u64* __re
 }
 void launch_group_eval(hipStream_t st, const GroupArgs& a, const uint64_t* skey, const uint32_t* sidx,
                        uint32_t n_usable, const uint32_t* group_first, uint32_t n_group) {
-  if (n_group) hipLaunchKernelGGL(k_group_eval, dim3(n_group), dim3(256), 0, st, a, skey, sidx, n_usable, group_first, n_group);
+  if (!n_group) return;
+  if (n_usable / n_group < 128)
+    hipLaunchKernelGGL(k_group_eval<64>, dim3(n_group), dim3(64), 0, st, a, skey, sidx, n_usable, group_first, n_group);
+  else
+    hipLaunchKernelGGL(k_group_eval<256>, dim3(n_group), dim3(256), 0, st, a, skey, sidx, n_usable, group_first, n_group);
 }
 
 // ------------------------------------------------------------------------------------------
