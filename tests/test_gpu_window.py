@@ -227,6 +227,35 @@ def test_large_operation_counters(seq0):
         assert g.n_flag > 0 and int(g.seg["seq"].min()) == seq0
 
 
+def test_stragglers_seconds_behind_their_collective():
+    """Arrival and completion times spread over more than 32 bits of nanoseconds inside one
+    collective (values around +/- 2^31 ns and several seconds)."""
+    rng = np.random.default_rng(8)
+    topo = ring_topology(8, comms=[list(range(8)), [0, 2, 4, 6]])
+    rows = []
+    for c, members in enumerate([list(range(8)), [0, 2, 4, 6]]):
+        for s in range(300):
+            te = T0 + s * 10**10 + rng.integers(0, 2000, len(members))
+            tx = te + 10**6 + rng.integers(0, 3000, len(members))
+            kind = s % 6
+            k = int(rng.integers(0, len(members)))
+            if kind == 1:
+                te[k] += 5 * 10**9; tx[k] = te[k] + 10**6                  # enters 5 s late
+            elif kind == 2:
+                tx[k] += 3 * 10**9                                         # leaves 3 s late
+            elif kind == 3:
+                te[k] -= 2**31 + 5; tx[k] = max(tx[k], te[k] + 1)           # just outside the offset range, early
+            elif kind == 4:
+                te[k] += 2**31 - 3; tx[k] = te[k] + 10**6                   # just inside / at the edge
+            for r, a, b in zip(members, te, tx):
+                rows.append((r, c, s, 0, 1 << 16, int(a), int(b)))
+    cols = toy_cols(rows)
+    p = rng.permutation(len(rows))
+    cols = {k: v[p] for k, v in cols.items()}
+    g, o = run_both(topo, cols, what="wide", tbase_init_ns=1000)
+    assert g.n_flag > 100
+
+
 def test_validation_parity():
     topo = ring_topology(4, comms=[[0, 1], [2, 3]])
     ok = [(0, 0, 0, 0, 8, T0, T0 + 1), (1, 0, 0, 0, 8, T0, T0 + 1)]
