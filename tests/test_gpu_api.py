@@ -1,0 +1,56 @@
+"""GPU: error reporting and bookkeeping of the C-ABI entry points (no kernel is asked to misbehave:
+every case is rejected by a host-side check)."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2605_04478_amd import tracegen as tg
+from tests.helpers import T0, ring_topology, rounds_with_durations, toy_cols
+
+pytestmark = pytest.mark.gpu
+
+
+def test_capacity_blame_order_and_profile_calls():
+    from paper_2605_04478_amd import ccld
+    topo = ring_topology(4)
+    cols = toy_cols(rounds_with_durations([[100, 200, 300, 400]] * 8))        # 32 records
+    an = ccld.Analyzer(topo, max_window_records=40, max_batch_records=40, window_batches=4)
+    with pytest.raises(ccld.CcldError) as e:                                   # no analysis yet: no blame
+        an.rank_blame()
+    assert e.value.status == -6
+    an.ingest(an.to_device(cols))
+    with pytest.raises(ccld.CcldError) as e:                                   # 32 + 32 > 40
+        an.ingest(an.to_device(cols))
+    assert e.value.status == -8
+    big = toy_cols(rounds_with_durations([[100, 200, 300, 400]] * 11))        # 44 > batch capacity
+    with pytest.raises(ccld.CcldError) as e:
+        an.ingest(an.to_device(big))
+    assert e.value.status == -8
+    an.profile_enable(True)
+    g = an.analyze_window(T0 + 10**12)
+    assert g.status == "OK" and g.n_records == 32 and g.n_seg == 8            # the rejected batches left no trace
+    prof, passes = an.profile_read()
+    assert passes >= 1 and prof["segments"][1] >= 1 and prof["segments"][0] > 0
+    blame, order = an.rank_blame()
+    assert list(blame["n_records"]) == [8, 8, 8, 8] and sorted(order) == [0, 1, 2, 3]
+    an.reset_window()
+    g = an.analyze_window(T0 + 10**12)
+    assert g.status == "OK" and g.n_records == 0 and g.n_seg == 0
+    an.close()
+
+
+def test_create_rejects_bad_arguments():
+    from paper_2605_04478_amd import ccld
+    L = ccld.lib()
+    topo = ring_topology(4)
+    with pytest.raises(ccld.CcldError):
+        ccld.Analyzer(topo, max_window_records=16, tbase_rounds=0)
+    # a member list that names a rank twice
+    bad = tg.make_topology(4, [[0, 1, 1, 2]])
+    with pytest.raises(ccld.CcldError) as e:
+        ccld.Analyzer(bad, max_window_records=16)
+    assert e.value.status == -10
+    assert L.ccld_ingest(None, None, 0) == -7
+    assert L.ccld_analyze_window(None, 0, None) == -7
+    assert L.ccld_progress_rates(None, None, 0, None) == -7
