@@ -1,6 +1,7 @@
-// Window analysis kernels for gfx950: ingest, per-collective statistics with exact integer
-// lower median / MAD by rank-counting in LDS, late-rank flags and their compaction, per-rank
-// blame, the slow-detection rules (Eq. 1-4) per detection group, and hang alerts.
+// Window analysis kernels for gfx950: ingest (validation, keys, bucketed placement), collective
+// heads per tile, compaction of the late-rank flags, per-rank blame, the slow-detection rules
+// (Eq. 1-4) per detection group, and hang alerts.  The per-collective statistics are in
+// segments.hip, the sort in radix_sort.hip.
 #include "window_kernels.h"
 #include "device_utils.h"
 #include "select.h"
