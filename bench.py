@@ -106,10 +106,12 @@ def main() -> int:
 
     an = ccld.Analyzer(tr.topo, max_window_records=n, device="cuda:0")
     cols = an.to_device(tr.cols)
+    cols_time_major = None
     if not args.no_shuffle:
         g = torch.Generator(device=dev)
         g.manual_seed(args.seed + 1)
         perm = torch.randperm(n, device=dev, generator=g)
+        cols_time_major = cols          # kept for a secondary figure: the order a probe fleet would deliver
         cols = {k: v[perm].contiguous() for k, v in cols.items()}
         del perm
     torch.cuda.synchronize()
@@ -146,6 +148,20 @@ def main() -> int:
     prof, passes = an.profile_read()
     an.profile_enable(False)
     assert res is not None and res.status == "OK", res
+    time_major_ms = None
+    if cols_time_major is not None:
+        for timed in (False, True):
+            torch.cuda.synchronize()
+            t_t = time.perf_counter()
+            for _ in range(2):
+                an.reset_window()
+                an.ingest(cols_time_major)
+                r3 = an.analyze_window(now, buffers=buffers)
+                an.rank_blame()
+            torch.cuda.synchronize()
+            if timed:
+                time_major_ms = (time.perf_counter() - t_t) / 2 * 1e3
+        assert r3.status == "OK" and int(r3.n_flag) == int(res.n_flag)
     pcie = None
     if args.host_batch:
         # the same batch handed over as host arrays (pinned): the library stages it over PCIe first
@@ -226,7 +242,7 @@ def main() -> int:
                                f"{n} records, {'shuffled' if not args.no_shuffle else 'time-major'} order; "
                                "step = ingest + analyze_window + rank_blame",
                    "records": n, "collectives": int(res.n_seg), "flags": int(res.n_flag),
-                   "groups": int(res.n_group), "pcie_inclusive_records_per_s": pcie, "sort_passes": passes, "sort_key_bits": key_bits,
+                   "groups": int(res.n_group), "pcie_inclusive_records_per_s": pcie, "time_major_order_ms_per_step": time_major_ms, "sort_passes": passes, "sort_key_bits": key_bits,
                    "sort_packed_words": bool(packed)},
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
