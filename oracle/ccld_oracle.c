@@ -818,3 +818,110 @@ int orc_progress_rates(const orc_topology *T, uint64_t n_rows, uint32_t n_snap, 
   R->status = ORC_OK;
   return R->status;
 }
+
+
+/* ------------------------------------------------------------------ */
+/* Probing Frame decoder (Section 5.1, "Probing Frame"; sizes from Section 6.2: a 32-byte header and
+ * a 1152-byte body of 8 blocks, each holding one 16-byte Trace ID and, per channel, two consecutive
+ * slots for SendCount and RecvCount; 8 channels; the block of an operation is its kernel counter
+ * modulo the number of blocks).
+ *
+ * Byte layout taken here (little-endian; the paper lists the fields, not their widths):
+ *   header  u64 kernel counter | u32 mode (bit 0: measurement on) | u32 kernelIndex | u32 channels | 12 reserved
+ *   block   u32 communicator id | u32 extension (bit 0: block written) | u64 operation counter
+ *           then 8 x { u64 SendCount, u64 RecvCount }
+ * One call decodes one frame per rank for snapshot `snap`: per frame and communicator the written
+ * block with the largest operation counter (then the largest block index) describes the rank's
+ * latest kernel there; it replaces the remembered state of (rank, communicator) unless that is
+ * newer; communicators absent from the frame keep their remembered state (the frame only holds the
+ * latest 8 kernels).  Then one snapshot row is written for every member slot and channel, in table
+ * order.  Checks, in this order of precedence: unknown communicator, rank not a member (or no such
+ * rank), range (more than 8 channels in a header, a count above 2^32 - 1), two frames of one rank.
+ * On an error nothing is remembered and no row is written.  "parity unpinned" beyond the sizes. */
+enum { FRAME_BYTES = 1184, FRAME_HEADER = 32, FRAME_BLOCKS = 8, FRAME_BLOCK_BYTES = 144, FRAME_CHANNELS = 8 };
+
+typedef struct {
+  uint64_t n_pair;
+  uint32_t n_ch;
+  cell_t *last;     /* [n_pair][n_ch] */
+} orc_frame_state;
+
+orc_frame_state *orc_frames_create(const orc_topology *T, uint32_t n_ch) {
+  if (n_ch == 0 || n_ch > FRAME_CHANNELS) return NULL;
+  orc_frame_state *s = (orc_frame_state *)calloc(1, sizeof(*s));
+  if (!s) return NULL;
+  for (uint32_t c = 0; c < T->n_comms; ++c) s->n_pair += T->size[c];
+  s->n_ch = n_ch;
+  s->last = (cell_t *)calloc((s->n_pair ? s->n_pair : 1) * n_ch, sizeof(cell_t));
+  if (!s->last) { free(s); return NULL; }
+  return s;
+}
+void orc_frames_destroy(orc_frame_state *s) { if (s) { free(s->last); free(s); } }
+
+static uint32_t rd_u32(const uint8_t *p) { return (uint32_t)p[0] | (uint32_t)p[1] << 8 | (uint32_t)p[2] << 16 | (uint32_t)p[3] << 24; }
+static uint64_t rd_u64(const uint8_t *p) { return (uint64_t)rd_u32(p) | (uint64_t)rd_u32(p + 4) << 32; }
+
+int orc_decode_frames(const orc_topology *T, orc_frame_state *st, const uint8_t *frames, const uint32_t *frame_rank,
+                      uint64_t n_frames, uint32_t snap, uint32_t *o_snap, uint32_t *o_rank, uint32_t *o_comm,
+                      uint32_t *o_channel, uint64_t *o_seq, uint32_t *o_sent, uint32_t *o_recv) {
+  int bad_comm = 0, bad_member = 0, bad_range = 0, dup = 0;
+  uint8_t *seen = (uint8_t *)calloc(T->n_ranks ? T->n_ranks : 1, 1);
+  for (uint64_t f = 0; f < n_frames; ++f) {
+    const uint8_t *F = frames + f * FRAME_BYTES;
+    const uint32_t r = frame_rank[f], nch = rd_u32(F + 16);
+    if (nch > FRAME_CHANNELS) bad_range = 1;
+    if (r < T->n_ranks) { if (seen[r]) dup = 1; seen[r] = 1; }
+    for (int b = 0; b < FRAME_BLOCKS; ++b) {
+      const uint8_t *B = F + FRAME_HEADER + b * FRAME_BLOCK_BYTES;
+      if (!(rd_u32(B + 4) & 1u)) continue;
+      const uint32_t c = rd_u32(B);
+      if (c >= T->n_comms) { bad_comm = 1; continue; }
+      if (r >= T->n_ranks || !is_member(T, c, r)) bad_member = 1;
+      for (uint32_t ch = 0; ch < nch && ch < FRAME_CHANNELS; ++ch)
+        if (rd_u64(B + 16 + ch * 16) > 0xFFFFFFFFull || rd_u64(B + 16 + ch * 16 + 8) > 0xFFFFFFFFull) bad_range = 1;
+    }
+  }
+  free(seen);
+  if (bad_comm) return ORC_E_UNKNOWN_COMM;
+  if (bad_member) return ORC_E_RANK_NOT_MEMBER;
+  if (bad_range) return ORC_E_RANGE;
+  if (dup) return ORC_E_DUPLICATE_KEY;
+  for (uint64_t f = 0; f < n_frames; ++f) {
+    const uint8_t *F = frames + f * FRAME_BYTES;
+    const uint32_t r = frame_rank[f], nch = rd_u32(F + 16);
+    for (int b = 0; b < FRAME_BLOCKS; ++b) {
+      const uint8_t *B = F + FRAME_HEADER + b * FRAME_BLOCK_BYTES;
+      if (!(rd_u32(B + 4) & 1u)) continue;
+      const uint32_t c = rd_u32(B);
+      const uint64_t cnt = rd_u64(B + 8);
+      /* is another written block of this frame the rank's later kernel on the same communicator? */
+      int loses = 0;
+      for (int b2 = 0; b2 < FRAME_BLOCKS; ++b2) {
+        const uint8_t *B2 = F + FRAME_HEADER + b2 * FRAME_BLOCK_BYTES;
+        if (b2 == b || !(rd_u32(B2 + 4) & 1u) || rd_u32(B2) != c) continue;
+        const uint64_t cnt2 = rd_u64(B2 + 8);
+        if (cnt2 > cnt || (cnt2 == cnt && b2 > b)) loses = 1;
+      }
+      if (loses) continue;
+      uint32_t slot = 0;
+      while (T->members[T->member_off[c] + slot] != r) ++slot;
+      const uint64_t p = (uint64_t)T->member_off[c] + slot;
+      for (uint32_t ch = 0; ch < st->n_ch; ++ch) {
+        cell_t *L = st->last + p * st->n_ch + ch;
+        if (cnt < L->seq) continue;                 /* what is remembered is newer */
+        L->seq = cnt;
+        L->sent = ch < nch ? (uint32_t)rd_u64(B + 16 + ch * 16) : 0;
+        L->recv = ch < nch ? (uint32_t)rd_u64(B + 16 + ch * 16 + 8) : 0;
+      }
+    }
+  }
+  uint64_t k = 0;
+  for (uint32_t c = 0; c < T->n_comms; ++c)
+    for (uint32_t q = 0; q < T->size[c]; ++q)
+      for (uint32_t ch = 0; ch < st->n_ch; ++ch, ++k) {
+        const cell_t *L = st->last + ((uint64_t)T->member_off[c] + q) * st->n_ch + ch;
+        o_snap[k] = snap; o_rank[k] = T->members[T->member_off[c] + q]; o_comm[k] = c; o_channel[k] = ch;
+        o_seq[k] = L->seq; o_sent[k] = L->sent; o_recv[k] = L->recv;
+      }
+  return ORC_OK;
+}

@@ -118,6 +118,12 @@ def lib() -> C.CDLL:
         L.orc_locate_hang.restype = C.c_int
         L.orc_locate_hang.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32] + \
             [C.c_void_p] * 7 + [C.c_void_p]
+        L.orc_frames_create.restype = C.c_void_p
+        L.orc_frames_create.argtypes = [C.c_void_p, C.c_uint32]
+        L.orc_frames_destroy.argtypes = [C.c_void_p]
+        L.orc_decode_frames.restype = C.c_int
+        L.orc_decode_frames.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32] + \
+            [C.c_void_p] * 7
         L.orc_rate_result_free.argtypes = [C.c_void_p]
         L.orc_progress_rates.restype = C.c_int
         L.orc_progress_rates.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32] + [C.c_void_p] * 7 + \
@@ -269,3 +275,29 @@ class Oracle:
                               _cols(_table(res.comm, res.n_comm, len(RATE_COMM_COLS)), RATE_COMM_COLS))
         finally:
             self.L.orc_rate_result_free(C.addressof(res))
+
+    # ---- Probing Frames --------------------------------------------------------------------
+    def frames_begin(self, n_channels: int) -> None:
+        """Forget every remembered (rank, communicator) state; frames carry `n_channels` channels."""
+        self.frames_end()
+        self._frames = self.L.orc_frames_create(C.addressof(self._topo), int(n_channels))
+        if not self._frames:
+            raise ValueError("1 .. 8 channels")
+        self._frames_nch = int(n_channels)
+
+    def frames_end(self) -> None:
+        if getattr(self, "_frames", None):
+            self.L.orc_frames_destroy(self._frames)
+        self._frames = None
+
+    def decode_frames(self, frames: np.ndarray, frame_rank: np.ndarray, snap: int):
+        """One frame per rank -> (status, the snapshot's rows for every member slot and channel)."""
+        buf = np.ascontiguousarray(frames).view(np.uint8).reshape(-1)
+        fr = np.ascontiguousarray(frame_rank, dtype=np.uint32)
+        n = int(self._size.sum()) * self._frames_nch
+        dt = {"snap": np.uint32, "rank": np.uint32, "comm": np.uint32, "channel": np.uint32,
+              "seq_posted": np.uint64, "chunks_sent": np.uint32, "chunks_recv": np.uint32}
+        out = {k: np.zeros(n, dtype=v) for k, v in dt.items()}
+        st = self.L.orc_decode_frames(C.addressof(self._topo), self._frames, _ptr(buf), _ptr(fr), int(fr.shape[0]),
+                                      int(snap), *[_ptr(out[k]) for k in dt])
+        return STATUS[st], out

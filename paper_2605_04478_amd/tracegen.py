@@ -796,3 +796,58 @@ def generate_rates(spec: RateSpec, shuffle: bool = True) -> RateTrace:
         perm = np.random.Generator(np.random.PCG64(seed + 29)).permutation(cols["snap"].shape[0])
         cols = {k: v[perm] for k, v in cols.items()}
     return RateTrace(spec, topo, cols, slow)
+
+
+# --------------------------------------------------------------------------
+# Probing Frames: the probe's per-rank record of its latest kernels
+# --------------------------------------------------------------------------
+FRAME_BYTES = 1184                     # 32-byte header + 8 blocks of 144 bytes
+FRAME_BLOCKS = 8
+FRAME_CHANNELS = 8
+FRAME_DTYPE = np.dtype([
+    ("counter", "<u8"), ("mode", "<u4"), ("kernel_index", "<u4"), ("n_channels", "<u4"), ("reserved", "<u4", (3,)),
+    ("block", [("comm", "<u4"), ("ext", "<u4"), ("counter", "<u8"),
+               ("count", "<u8", (FRAME_CHANNELS, 2))], (FRAME_BLOCKS,)),
+])
+assert FRAME_DTYPE.itemsize == FRAME_BYTES
+
+
+def encode_frames(topo: Topology, rows: Dict[str, np.ndarray], n_channels: int, keep: Optional[np.ndarray] = None,
+                  kernel_counter: int = 0):
+    """Packs one snapshot's rows (every (rank, communicator, channel) once) into one frame per rank.
+
+    A rank's communicators take consecutive blocks starting at block `kernel_counter mod 8`, so the
+    block positions move from call to call as they do in the probe's cyclic body.  `keep[rank,
+    k]` = False leaves the rank's k-th communicator out of its frame (the probe only holds its
+    latest kernels: a communicator that was not used lately is not in the frame).  Blocks that are
+    not written keep a zero extension field.  Returns (frames as a structured array, ranks)."""
+    if n_channels > FRAME_CHANNELS:
+        raise ValueError("a frame block has 8 channels")
+    R = topo.n_ranks
+    frames = np.zeros(R, dtype=FRAME_DTYPE)
+    frames["mode"] = 1
+    frames["n_channels"] = n_channels
+    order = np.lexsort((rows["channel"], rows["comm"], rows["rank"]))
+    rk, cm, ch = rows["rank"][order], rows["comm"][order], rows["channel"][order]
+    sq, sent, recv = rows["seq_posted"][order], rows["chunks_sent"][order], rows["chunks_recv"][order]
+    first = ch == 0
+    # ordinal of each (rank, comm) among the rank's communicators
+    pair_rank, pair_comm = rk[first], cm[first]
+    start = np.r_[True, pair_rank[1:] != pair_rank[:-1]]
+    idx = np.arange(len(pair_rank))
+    ordinal = idx - np.maximum.accumulate(np.where(start, idx, 0))
+    if ordinal.max(initial=0) >= FRAME_BLOCKS:
+        raise ValueError("a frame holds 8 kernels: ranks in more than 8 communicators are not supported here")
+    on = np.ones(len(pair_rank), dtype=bool) if keep is None else keep[pair_rank, ordinal]
+    blk = (kernel_counter + ordinal) % FRAME_BLOCKS
+    pr, pb = pair_rank[on], blk[on]
+    frames["block"]["comm"][pr, pb] = pair_comm[on]
+    frames["block"]["ext"][pr, pb] = 1
+    frames["block"]["counter"][pr, pb] = sq[first][on]
+    row_on = np.repeat(on, n_channels)
+    rr, rb = np.repeat(pair_rank, n_channels)[row_on], np.repeat(blk, n_channels)[row_on]
+    frames["block"]["count"][rr, rb, ch[row_on], 0] = sent[row_on]
+    frames["block"]["count"][rr, rb, ch[row_on], 1] = recv[row_on]
+    frames["counter"] = kernel_counter + FRAME_BLOCKS - 1
+    frames["kernel_index"] = frames["counter"] % FRAME_BLOCKS
+    return frames, np.arange(R, dtype=np.uint32)
