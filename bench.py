@@ -69,7 +69,7 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--host-batch", action="store_true",
                     help="also time two steps whose batch starts in pinned host memory (PCIe-inclusive rate)")
-    ap.add_argument("--workload", choices=("trace", "stream", "hang", "rates"), default="trace",
+    ap.add_argument("--workload", choices=("trace", "stream", "hang", "rates", "frames"), default="trace",
                     help="trace: the 4,096-rank trace (default, the headline metric); stream: sliding window at "
                          "16,384 ranks, per-step latency; hang: hang location on 17M snapshot rows")
     ap.add_argument("--stream-steps", type=int, default=600)
@@ -97,6 +97,8 @@ def main() -> int:
         return bench_hang(args, torch, np, ccld, tg)
     if args.workload == "rates":
         return bench_rates(args, torch, np, ccld, tg)
+    if args.workload == "frames":
+        return bench_frames(args, torch, np, ccld, tg)
 
     spec = tg.config3(n_cycles=args.cycles, seed=args.seed)
     t0 = time.time()
@@ -357,6 +359,40 @@ def bench_rates(args, torch, np, ccld, tg) -> int:
                                   f"({tr.n} rows, 32 B each), one slow rank",
                       "slow_rank_is_minimal_rate_member_of_its_communicators": bool(ok),
                       "algorithmic_GBps": tr.n * 48.0 / dt / 1e9}}
+    print(json.dumps(out), flush=True)
+    an.close()
+    return 0
+
+
+def bench_frames(args, torch, np, ccld, tg) -> int:
+    """Probing Frame decoding at 4,096 ranks: one 1184-byte frame per rank and snapshot, resident in HBM."""
+    lay = tg.Layout3D(tp=8, pp=8, dp=64, world=True)
+    ht = tg.generate_hang(tg.config4(seed=args.seed, layout=lay, n_channels=8, n_snapshots=8), shuffle=False)
+    an = ccld.Analyzer(ht.topo, max_window_records=1024, max_snapshot_rows=ht.n, device="cuda:0")
+    c = ht.cols
+    frames_d, ranks_d = [], []
+    for s in range(8):
+        m = c["snap"] == s
+        fr, rk = tg.encode_frames(ht.topo, {k: v[m] for k, v in c.items()}, 8, kernel_counter=3 * s)
+        frames_d.append(torch.from_numpy(fr.view(np.uint8).reshape(-1).copy()).to("cuda:0"))
+        ranks_d.append(torch.from_numpy(rk.view(np.int32).copy()).to("cuda:0"))
+    torch.cuda.synchronize()
+    for s in range(8):
+        st, _ = an.decode_frames(frames_d[s], ranks_d[s], s, 8)
+        assert st == "OK"
+    torch.cuda.synchronize()
+    reps = max(args.steps, 1) * 8
+    t0 = time.perf_counter()
+    for i in range(reps):
+        an.decode_frames(frames_d[i % 8], ranks_d[i % 8], 8 + i, 8)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    n_frames = lay.n_ranks
+    out = {"metric": "Probing Frame decoding at 4,096 ranks: frames decoded/sec", "unit": "frames/s", "value": n_frames / dt,
+           "n_gpus": 1, "steps": reps, "warmup": 8, "ms_per_step": dt * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"{n_frames} frames of 1184 bytes per snapshot -> {int(ht.topo.size.sum()) * 8} snapshot rows",
+                      "algorithmic_GBps": (n_frames * 1184.0 + int(ht.topo.size.sum()) * 8 * 32.0) / dt / 1e9}}
     print(json.dumps(out), flush=True)
     an.close()
     return 0

@@ -197,6 +197,33 @@ typedef struct {
   int32_t reserved;
 } ccld_rate_result;
 
+/* Probing Frames (Section 5.1): one 1184-byte frame per rank = 32-byte header + 8 blocks of 144
+ * bytes; a block = one 16-byte Trace ID + 8 channels x {SendCount, RecvCount}.  Byte layout
+ * (little-endian; the paper lists the fields, the widths are this library's):
+ *   header: u64 kernel counter | u32 mode (bit 0: measurement on) | u32 kernelIndex | u32 channels | 12 reserved
+ *   block : u32 communicator id | u32 extension (bit 0: block written) | u64 operation counter
+ *           | 8 x { u64 SendCount, u64 RecvCount } */
+enum { CCLD_FRAME_BYTES = 1184, CCLD_FRAME_HEADER_BYTES = 32, CCLD_FRAME_BLOCKS = 8, CCLD_FRAME_BLOCK_BYTES = 144,
+       CCLD_FRAME_CHANNELS = 8 };
+
+typedef struct {
+  const uint8_t *frames;       /* [n_frames][CCLD_FRAME_BYTES], 16-byte aligned; host or device per on_device */
+  const uint32_t *frame_rank;  /* [n_frames] rank each frame belongs to (same memory space as frames)        */
+  uint64_t n_frames;
+  int32_t on_device;
+  uint32_t n_channels;         /* channels of the snapshot rows to write, 1 .. CCLD_FRAME_CHANNELS           */
+  uint32_t snapshot;           /* snapshot number the rows get                                               */
+  uint32_t reserved;
+} ccld_frames;
+
+/* snapshot rows written by ccld_decode_frames: device arrays of `capacity` entries each */
+typedef struct {
+  uint32_t *snap, *rank, *comm, *channel;
+  uint64_t *seq_posted;
+  uint32_t *chunks_sent, *chunks_recv;
+  uint64_t capacity;
+} ccld_snapshot_rows;
+
 /* ---- entry points ---------------------------------------------------------------------------- */
 
 /* Fills *params with the defaults listed above. */
@@ -272,6 +299,22 @@ ccld_status ccld_locate_hang(ccld_ctx *ctx, const ccld_snapshots *snapshots, uin
  * communication slowdown).  Before the first call that column holds CCLD_NO_RANK. */
 ccld_status ccld_progress_rates(ccld_ctx *ctx, const ccld_snapshots *snapshots, uint64_t n_rows,
                                 ccld_rate_result *out);
+
+/* Decodes one Probing Frame per rank into the rows of one snapshot (the input of ccld_locate_hang
+ * and ccld_progress_rates).  Per frame and communicator the written block with the largest
+ * operation counter (then the largest block index) is the rank's latest kernel there; it replaces
+ * what the context remembers for (rank, communicator) unless that is newer.  Communicators that are
+ * absent from a frame (a frame only holds the rank's latest 8 kernels) keep their remembered state.
+ * Then one row per member slot (in the order of the topology's members[]) and channel
+ * 0 .. n_channels-1 is written: *n_rows = member slots x n_channels rows, which must fit
+ * rows->capacity (else CCLD_E_CAPACITY).  Channels beyond a frame's own channel count read zero.
+ * Checked, in this order of precedence: unknown communicator, rank not a member (or no such rank),
+ * range (a header with more than 8 channels, a count above 2^32 - 1), two frames of one rank
+ * (CCLD_E_DUPLICATE_KEY).  On an error nothing is remembered and no row is written.
+ * ccld_reset_frames forgets every remembered state. */
+ccld_status ccld_decode_frames(ccld_ctx *ctx, const ccld_frames *frames, const ccld_snapshot_rows *rows,
+                               uint64_t *n_rows);
+ccld_status ccld_reset_frames(ccld_ctx *ctx);
 
 /* Per-rank blame of the most recent ccld_analyze_window: blame = device [CCLD_BLM_NCOL][n_ranks]
  * (late-entry and late-exit counts, their summed lags, records seen); order = device [n_ranks]

@@ -78,6 +78,17 @@ class _HangResult(C.Structure):
                 ("status", C.c_int32), ("reserved", C.c_int32)]
 
 
+class _Frames(C.Structure):
+    _fields_ = [("frames", C.c_void_p), ("frame_rank", C.c_void_p), ("n_frames", C.c_uint64), ("on_device", C.c_int32),
+                ("n_channels", C.c_uint32), ("snapshot", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class _SnapshotRows(C.Structure):
+    _fields_ = [("snap", C.c_void_p), ("rank", C.c_void_p), ("comm", C.c_void_p), ("channel", C.c_void_p),
+                ("seq_posted", C.c_void_p), ("chunks_sent", C.c_void_p), ("chunks_recv", C.c_void_p),
+                ("capacity", C.c_uint64)]
+
+
 class _RateResult(C.Structure):
     _fields_ = [("pair_cap", C.c_uint64), ("comm_cap", C.c_uint64), ("pair", C.c_void_p), ("comm", C.c_void_p),
                 ("n_pair", C.c_uint64), ("n_comm", C.c_uint64), ("status", C.c_int32), ("reserved", C.c_int32)]
@@ -91,7 +102,7 @@ PROF_NCLASS = 16
 
 EXPORTS = ("ccld_profile_enable", "ccld_profile_read", "ccld_default_params", "ccld_query_workspace", "ccld_create", "ccld_destroy", "ccld_ingest",
            "ccld_reset_window", "ccld_analyze_window", "ccld_rank_blame", "ccld_locate_hang", "ccld_progress_rates",
-           "ccld_status_str")
+           "ccld_decode_frames", "ccld_reset_frames", "ccld_status_str")
 
 
 def lib() -> C.CDLL:
@@ -113,6 +124,8 @@ def lib() -> C.CDLL:
         L.ccld_rank_blame.argtypes = [vp, vp, vp]
         L.ccld_locate_hang.argtypes = [vp, vp, u64, vp]
         L.ccld_progress_rates.argtypes = [vp, vp, u64, vp]
+        L.ccld_decode_frames.argtypes = [vp, vp, vp, vp]
+        L.ccld_reset_frames.argtypes = [vp]
         L.ccld_profile_enable.argtypes = [vp, C.c_int32]
         L.ccld_profile_read.argtypes = [vp, vp, vp, vp]
         L.ccld_status_str.argtypes = [C.c_int32]
@@ -394,6 +407,38 @@ class Analyzer:
         if st in (-7, -11, -6, -8):
             raise CcldError(st, "ccld_locate_hang")
         return HangResult(STATUS.get(st, str(st)), r.n_root, r.n_pair, r.n_hung_comm, caps, dev)
+
+    def reset_frames(self) -> None:
+        self._check(self.L.ccld_reset_frames(self._ctx), "ccld_reset_frames")
+
+    def decode_frames(self, frames, frame_rank, snapshot: int, n_channels: int):
+        """One Probing Frame per rank (numpy array of 1184-byte frames on the host, or a device uint8
+        tensor) -> (status, the snapshot's rows as device tensors in the snapshot column format)."""
+        t = self.torch
+        on_device = not isinstance(frames, np.ndarray)
+        if on_device:
+            n = int(frame_rank.shape[0])
+            fptr, rptr = C.c_void_p(frames.data_ptr()), C.c_void_p(frame_rank.data_ptr())
+            keep = (frames, frame_rank)
+        else:
+            buf = np.ascontiguousarray(frames).view(np.uint8).reshape(-1)
+            fr = np.ascontiguousarray(frame_rank, dtype=np.uint32)
+            n = int(fr.shape[0])
+            fptr, rptr = buf.ctypes.data_as(C.c_void_p), fr.ctypes.data_as(C.c_void_p)
+            keep = (buf, fr)
+        cap = int(self._size.sum()) * int(n_channels)
+        i32 = dict(dtype=t.int32, device=self.device)
+        out = {k: t.empty(cap, **i32) for k in ("snap", "rank", "comm", "channel", "chunks_sent", "chunks_recv")}
+        out["seq_posted"] = t.empty(cap, dtype=t.int64, device=self.device)
+        f = _Frames(fptr, rptr, n, 1 if on_device else 0, int(n_channels), int(snapshot), 0)
+        r = _SnapshotRows(*[out[k].data_ptr() for k in ("snap", "rank", "comm", "channel", "seq_posted",
+                                                        "chunks_sent", "chunks_recv")], cap)
+        n_rows = C.c_uint64(0)
+        st = self.L.ccld_decode_frames(self._ctx, C.addressof(f), C.addressof(r), C.addressof(n_rows))
+        if st in (-7, -11, -6, -8):
+            raise CcldError(st, "ccld_decode_frames")
+        del keep
+        return STATUS.get(st, str(st)), out
 
     def progress_rates(self, cols, n_snapshots: int, n_channels: int, pair_cap: Optional[int] = None,
                        comm_cap: Optional[int] = None) -> RateResult:

@@ -87,6 +87,8 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->h_cand = w.take<uint8_t>(n_members);
   c->h_layer_max = w.take<uint64_t>(n_members);
   c->h_root_list = w.take<uint32_t>(n_members + 1);
+  c->f_last = w.take<uint64_t>(2ull * CCLD_FRAME_CHANNELS * n_members);
+  c->f_seen = w.take<uint32_t>(n_ranks / 32 + 1);
   c->h_stage = w.take<uint8_t>(SN * 32);
 }
 
@@ -283,6 +285,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   if (hipMemsetAsync(c->batch_meta, 0, sizeof(BatchMeta) * ((uint64_t)c->p.window_batches + 2), c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, c->stream) != hipSuccess) rs = CCLD_E_HIP;
   launch_fill_u64(c->stream, (uint64_t*)c->rate_root, topo->n_comms, (uint64_t)CCLD_NO_RANK);
+  if (hipMemsetAsync(c->f_last, 0, sizeof(uint64_t) * 2 * CCLD_FRAME_CHANNELS * n_members, c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->blame, 0, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)topo->n_ranks, c->stream) != hipSuccess) rs = CCLD_E_HIP;
   {     // pinned readback buffer: the counters, or the headers of every batch slot
     const size_t bytes = std::max<size_t>(4096 * sizeof(uint64_t), sizeof(BatchMeta) * ((size_t)c->p.window_batches + 2));

@@ -143,6 +143,8 @@ struct ccld_ctx {
   uint64_t* h_layer_max;              // [n_members]
   uint32_t* h_root_list;              // [n_members]
   int64_t* rate_root;                 // [n_comms] member of minimal SendRate / RecvRate from the latest rate pass, or CCLD_NO_RANK
+  uint64_t* f_last;                   // [n_members][CCLD_FRAME_CHANNELS][2] remembered (operation counter, sent | recv << 32) per member and channel
+  uint32_t* f_seen;                   // [n_ranks / 32 + 1] ranks that delivered a frame in the current call
   uint8_t* h_stage;                   // [snap_cap * 32] device staging for host-resident snapshots
   // last analysis
   int sorted_buf;                     // which ping-pong buffer holds the sorted window

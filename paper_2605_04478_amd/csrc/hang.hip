@@ -426,6 +426,99 @@ __global__ __launch_bounds__(256) void k_rate_comm(HangArgs a, i64* __restrict__
   }
 }
 
+// ---- Probing Frames (Section 5.1) -------------------------------------------------------------------
+struct FrameArgs {
+  const uint8_t* frames;
+  const u32* frame_rank;
+  u64 n_frames;
+  u32 n_ch, snap;
+  int mb;
+  DeviceTopology T;
+  u64 n_members;
+  u64* last;          // [n_members][CCLD_FRAME_CHANNELS][2]
+  u32* seen;          // ranks that delivered a frame
+  u64* counters;
+};
+
+// member slot of rank r in communicator c (r < n_ranks), or -1
+__device__ __forceinline__ int member_slot(const DeviceTopology& T, int mb, u32 c, u32 r) {
+  if (T.rank_memb4) {
+    const uint4 m = reinterpret_cast<const uint4*>(T.rank_memb4)[r];
+    const u32 w = c == (m.x >> mb) ? m.x : c == (m.y >> mb) ? m.y : c == (m.z >> mb) ? m.z : m.w;
+    if (c != (w >> mb)) return -1;
+    return (int)T.sorted_slot[T.member_off[c] + (w & (mb < 32 ? (1u << mb) - 1 : ~0u))];
+  }
+  return slot_of(T, c, r);
+}
+
+// One wavefront per frame, lane = 8 * block + channel.  CHECK: the validity checks only.  Otherwise:
+// the block that holds the rank's latest kernel on its communicator replaces the remembered state.
+template <bool CHECK>
+__global__ __launch_bounds__(256) void k_frames(FrameArgs a) {
+  const u32 lane = lane_id();
+  const u64 f = (u64)blockIdx.x * 4 + threadIdx.x / CCLD_WAVE;
+  if (f >= a.n_frames) return;
+  const uint8_t* F = a.frames + f * CCLD_FRAME_BYTES;
+  const u32 b = lane / CCLD_FRAME_CHANNELS, ch = lane % CCLD_FRAME_CHANNELS;
+  const u32 r = a.frame_rank[f];
+  const u32 nch = reinterpret_cast<const u32*>(F)[4];
+  const uint4 tid4 = *reinterpret_cast<const uint4*>(F + CCLD_FRAME_HEADER_BYTES + b * CCLD_FRAME_BLOCK_BYTES);
+  const uint4 cnt4 = *reinterpret_cast<const uint4*>(F + CCLD_FRAME_HEADER_BYTES + b * CCLD_FRAME_BLOCK_BYTES + 16 + ch * 16);
+  const u32 comm = tid4.x;
+  const bool written = (tid4.y & 1u) != 0;
+  const u64 opc = (u64)tid4.z | ((u64)tid4.w << 32);
+  const u64 sent = (u64)cnt4.x | ((u64)cnt4.y << 32), recv = (u64)cnt4.z | ((u64)cnt4.w << 32);
+  if (CHECK) {
+    u64 status = 0;
+    if (nch > CCLD_FRAME_CHANNELS) status |= DS_RANGE;
+    if (lane == 0 && r < a.T.n_ranks) {
+      const u32 bit = 1u << (r & 31);
+      if (atomicOr(&a.seen[r >> 5], bit) & bit) status |= DS_DUPLICATE;
+    }
+    if (written) {
+      if (comm >= a.T.n_comms) {
+        status |= DS_UNKNOWN_COMM;
+      } else {
+        if (r >= a.T.n_ranks || member_slot(a.T, a.mb, comm, r) < 0) status |= DS_NOT_MEMBER;
+        if (ch < nch && (sent > 0xFFFFFFFFull || recv > 0xFFFFFFFFull)) status |= DS_RANGE;
+      }
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) status |= shfl_xor_u64(status, m);
+    if (lane == 0 && status) atomicOr((unsigned long long*)&a.counters[CNT_STATUS], (unsigned long long)status);
+    return;
+  }
+  // a later kernel of this rank on the same communicator in another block of the frame?
+  bool loses = false;
+#pragma unroll
+  for (u32 b2 = 0; b2 < CCLD_FRAME_BLOCKS; ++b2) {
+    const u32 c2 = __shfl(comm, (int)(b2 * CCLD_FRAME_CHANNELS), CCLD_WAVE);
+    const u32 w2 = __shfl(written ? 1u : 0u, (int)(b2 * CCLD_FRAME_CHANNELS), CCLD_WAVE);
+    const u64 o2 = shfl_u64(opc, (int)(b2 * CCLD_FRAME_CHANNELS));
+    if (b2 != b && w2 && c2 == comm && (o2 > opc || (o2 == opc && b2 > b))) loses = true;
+  }
+  if (!written || loses) return;
+  const int slot = member_slot(a.T, a.mb, comm, r);
+  const u64 p = (u64)a.T.member_off[comm] + (u32)slot;
+  u64* L = a.last + (p * CCLD_FRAME_CHANNELS + ch) * 2;
+  if (opc < L[0]) return;                                  // what is remembered is newer
+  L[0] = opc;
+  L[1] = ch < nch ? ((sent & 0xFFFFFFFFull) | (recv << 32)) : 0ull;
+}
+
+// one snapshot row per member slot and channel, from the remembered state
+__global__ __launch_bounds__(256) void k_frame_rows(FrameArgs a, ccld_snapshot_rows o) {
+  const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.n_members * a.n_ch) return;
+  const u64 p = i / a.n_ch;
+  const u32 ch = (u32)(i % a.n_ch);
+  u32 lo = 0, hi = a.T.n_comms;
+  while (hi - lo > 1) { const u32 m = (lo + hi) / 2; if (a.T.member_off[m] <= p) lo = m; else hi = m; }
+  const u64* L = a.last + (p * CCLD_FRAME_CHANNELS + ch) * 2;
+  o.snap[i] = a.snap; o.rank[i] = a.T.members[p]; o.comm[i] = lo; o.channel[i] = ch;
+  o.seq_posted[i] = L[0]; o.chunks_sent[i] = (u32)L[1]; o.chunks_recv[i] = (u32)(L[1] >> 32);
+}
+
 }  // namespace ccld
 
 #define HIP_TRY(x) do { if ((x) != hipSuccess) { (void)hipGetLastError(); return CCLD_E_HIP; } } while (0)
@@ -580,4 +673,59 @@ extern "C" ccld_status ccld_progress_rates(ccld_ctx* c, const ccld_snapshots* sn
   if (o->pair_cap < o->n_pair && o->pair) o->status = CCLD_W_TRUNCATED;
   if (o->comm_cap < o->n_comm && o->comm) o->status = CCLD_W_TRUNCATED;
   return o->status;
+}
+
+extern "C" ccld_status ccld_reset_frames(ccld_ctx* c) {
+  if (!c) return CCLD_E_NULL;
+  HIP_TRY(hipMemsetAsync(c->f_last, 0, sizeof(uint64_t) * 2 * CCLD_FRAME_CHANNELS * c->n_members, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  return CCLD_OK;
+}
+
+extern "C" ccld_status ccld_decode_frames(ccld_ctx* c, const ccld_frames* fr, const ccld_snapshot_rows* rows,
+                                          uint64_t* n_rows) {
+  if (!c || !fr || !rows || !n_rows) return CCLD_E_NULL;
+  *n_rows = 0;
+  if (fr->n_channels == 0 || fr->n_channels > CCLD_FRAME_CHANNELS) return CCLD_E_BAD_ARG;
+  if (fr->n_frames && (!fr->frames || !fr->frame_rank)) return CCLD_E_NULL;
+  if (!rows->snap || !rows->rank || !rows->comm || !rows->channel || !rows->seq_posted || !rows->chunks_sent ||
+      !rows->chunks_recv)
+    return CCLD_E_NULL;
+  const uint64_t n_out = c->n_members * fr->n_channels;
+  if (n_out > rows->capacity) return CCLD_E_CAPACITY;
+  hipStream_t st = c->stream;
+  FrameArgs a;
+  std::memset(&a, 0, sizeof(a));
+  if (fr->on_device) {
+    if ((reinterpret_cast<uintptr_t>(fr->frames) & 15) != 0) return CCLD_E_BAD_ARG;
+    a.frames = fr->frames; a.frame_rank = fr->frame_rank;
+  } else if (fr->n_frames) {
+    // staging buffer of the snapshot rows: 32 bytes per row of capacity
+    const uint64_t need = fr->n_frames * (CCLD_FRAME_BYTES + 4);
+    if (need > c->snap_cap * 32) return CCLD_E_CAPACITY;
+    uint8_t* d = c->h_stage;
+    HIP_TRY(hipMemcpyAsync(d, fr->frames, fr->n_frames * CCLD_FRAME_BYTES, hipMemcpyHostToDevice, st));
+    uint32_t* dr = reinterpret_cast<uint32_t*>(d + fr->n_frames * CCLD_FRAME_BYTES);
+    HIP_TRY(hipMemcpyAsync(dr, fr->frame_rank, fr->n_frames * 4, hipMemcpyHostToDevice, st));
+    a.frames = d; a.frame_rank = dr;
+  }
+  a.n_frames = fr->n_frames; a.n_ch = fr->n_channels; a.snap = fr->snapshot; a.mb = c->kf.mb; a.T = c->topo;
+  a.n_members = c->n_members; a.last = c->f_last; a.seen = c->f_seen; a.counters = c->counters;
+  c->prof.begin();
+  HIP_TRY(hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st));
+  HIP_TRY(hipMemsetAsync(c->f_seen, 0, sizeof(uint32_t) * (c->topo.n_ranks / 32 + 1), st));
+  const uint32_t fblocks = (uint32_t)((fr->n_frames + 3) / 4);
+  if (fr->n_frames) hipLaunchKernelGGL(k_frames<true>, dim3(fblocks), dim3(256), 0, st, a);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (c->h_pinned[CNT_STATUS]) { c->prof.end(CCLD_PROF_HANG); c->prof.collect(); return hang_status(c->h_pinned[CNT_STATUS]); }
+  if (fr->n_frames) hipLaunchKernelGGL(k_frames<false>, dim3(fblocks), dim3(256), 0, st, a);
+  if (n_out) hipLaunchKernelGGL(k_frame_rows, dim3((uint32_t)((n_out + 255) / 256)), dim3(256), 0, st, a, *rows);
+  c->prof.end(CCLD_PROF_HANG);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(st));
+  c->prof.collect();
+  *n_rows = n_out;
+  return CCLD_OK;
 }
