@@ -32,14 +32,15 @@ def log(*a):
 
 
 def kernel_sources_digest() -> str:
-    """sha256 over the library's sources: the counters in profiles/ only describe these kernels."""
+    """sha256 over the sources of the kernels the trace workload launches (ingest, sort, collectives,
+    flags, blame, groups, alerts): the counters in profiles/ only describe these kernels."""
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2605_04478_amd", "csrc")
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".h")):
-            h.update(name.encode())
-            h.update(open(os.path.join(csrc, name), "rb").read())
+    for name in ("device_utils.h", "radix_sort.h", "radix_sort.hip", "select.h", "segments.hip", "window.hip",
+                 "window_kernels.h"):
+        h.update(name.encode())
+        h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()
 
 
