@@ -243,11 +243,12 @@ ccld_status ccld_create(const ccld_params *params, const ccld_topology *topo,
                         void *workspace, uint64_t workspace_bytes, void *hip_stream, ccld_ctx **out);
 ccld_status ccld_destroy(ccld_ctx *ctx);
 
-/* Appends one batch of n records to the window (the analyzer "periodically processes metrics from
- * all ranks", Section 3); when the window already holds window_batches batches the oldest batch is
- * dropped first.  The records are validated, keyed by Trace ID (communicator id, operation counter;
- * Section 5.1) plus rank, and stored on the device.  Asynchronous for device input; data errors
- * found on the device are reported by the next ccld_analyze_window. */
+/* Appends one batch of n records to the window (the analyzer works through the ranks' metrics
+ * period by period, Section 3); when the window already holds window_batches batches the oldest
+ * batch is dropped first.  The records are validated, keyed by Trace ID (communicator id, operation
+ * counter; Section 5.1) plus the rank's position among the communicator's members, and stored on
+ * the device.  Asynchronous for device input; data errors found on the device are reported by the
+ * next ccld_analyze_window. */
 ccld_status ccld_ingest(ccld_ctx *ctx, const ccld_records *batch, uint64_t n);
 
 /* Drops every batch from the window; the per-group detection state (Eq. 1 baseline, repetition
