@@ -439,15 +439,12 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   sa.barrier_bytes = c->p.barrier_bytes;
   const uint32_t seg_tiles = (n + SEG_TILE - 1) / SEG_TILE;
   c->prof.begin();
-  launch_seg_count(st, sa);
+  launch_keys_pass(st, skey, n, c->sf, c->topo, c->blame, c->tile_heads, c->counters);
   launch_scan_tiles(st, c->tile_heads, seg_tiles, &c->counters[CNT_NSEG]);
   c->prof.end(CCLD_PROF_SEG_HEADS);
   c->prof.begin();
   launch_seg_analyze(st, sa);
   c->prof.end(CCLD_PROF_SEGMENTS);
-  c->prof.begin();
-  launch_rank_count(st, skey, n, c->sf, c->topo, c->blame);
-  c->prof.end(CCLD_PROF_BLAME);
   FlagArgs fa;
   std::memset(&fa, 0, sizeof(fa));
   fa.key = skey; fa.rec_flag = sa.rec_flag; fa.flag_lag = c->flag_lag; fa.cap_n = c->cap; fa.n = n; fa.sf = c->sf;

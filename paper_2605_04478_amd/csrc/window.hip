@@ -201,51 +201,47 @@ void launch_ingest(hipStream_t st, const IngestArgs& a, const DeviceTopology& T,
 }
 
 // ------------------------------------------------------------------------------------------
-// Collective (segment) heads per tile of the sorted keys; equal neighbours are duplicates.
-__global__ __launch_bounds__(SEG_THREADS) void k_seg_count(SegArgs a) {
-  __shared__ u32 s_wave[SEG_THREADS / CCLD_WAVE];
-  const u32 base = blockIdx.x * SEG_TILE;
-  u32 cnt = 0;
-  bool dup = false;
-#pragma unroll
-  for (int r = 0; r < SEG_TILE / SEG_THREADS; ++r) {
-    const u32 j = base + r * SEG_THREADS + threadIdx.x;
-    if (j < a.n) {
-      const u64 k = a.key[j];
-      if (j == 0) cnt += 1;
-      else {
-        const u64 kp = a.key[j - 1];
-        cnt += ((k >> a.sf.mb) != (kp >> a.sf.mb));
-        dup |= (k == kp);
-      }
-    }
-  }
-  u32 tot;
-  block_exclusive_sum<SEG_THREADS>(cnt, s_wave, &tot);
-  if (threadIdx.x == 0) a.tile_heads[blockIdx.x] = tot;
-  if (dup) atomic_or_u64(&a.counters[CNT_STATUS], DS_DUPLICATE);
-}
-void launch_seg_count(hipStream_t st, const SegArgs& a) {
-  if (a.n == 0) return;
-  hipLaunchKernelGGL(k_seg_count, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
-}
-
 // In-place exclusive scan of per-tile counts by one workgroup; counts[n_tiles] and *total_out
 // receive the total.
-__global__ __launch_bounds__(1024) void k_scan_tiles(u32* counts, u32 n_tiles, u64* total_out) {
-  constexpr int PER = 8;             // consecutive counts per thread and round
-  __shared__ u32 s_wave[1024 / CCLD_WAVE];
-  u32 carry = 0;
-  for (u32 b = 0; b < n_tiles; b += 1024 * PER) {
-    const u32 i0 = b + threadIdx.x * PER;
-    u32 v[PER], sum = 0;
+constexpr int SCAN_PER = 8;          // consecutive counts per thread and round
+__device__ __forceinline__ void scan_load(const u32* counts, u32 i0, u32 n_tiles, bool vec, u32 (&v)[SCAN_PER]) {
+  if (vec && i0 + SCAN_PER <= n_tiles) {
+    const uint4 a = *reinterpret_cast<const uint4*>(counts + i0), b = *reinterpret_cast<const uint4*>(counts + i0 + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  } else {
 #pragma unroll
-    for (int k = 0; k < PER; ++k) { v[k] = (i0 + k) < n_tiles ? counts[i0 + k] : 0u; sum += v[k]; }
+    for (int k = 0; k < SCAN_PER; ++k) v[k] = (i0 + k) < n_tiles ? counts[i0 + k] : 0u;
+  }
+}
+__global__ __launch_bounds__(1024) void k_scan_tiles(u32* counts, u32 n_tiles, u64* total_out) {
+  static_assert(SCAN_PER == 8, "two 16-byte pieces per thread");
+  __shared__ u32 s_wave[1024 / CCLD_WAVE];
+  const bool vec = (reinterpret_cast<uintptr_t>(counts) & 15) == 0;
+  u32 carry = 0;
+  u32 v[SCAN_PER], nv[SCAN_PER];
+  scan_load(counts, threadIdx.x * SCAN_PER, n_tiles, vec, v);
+  for (u32 b = 0; b < n_tiles; b += 1024 * SCAN_PER) {
+    const u32 i0 = b + threadIdx.x * SCAN_PER;
+    // the next round's counts are on their way while this round is scanned and stored
+    scan_load(counts, i0 + 1024 * SCAN_PER, n_tiles, vec, nv);
+    u32 sum = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_PER; ++k) sum += v[k];
     u32 tot;
     u32 ex = carry + block_exclusive_sum<1024>(sum, s_wave, &tot);
+    if (vec && i0 + SCAN_PER <= n_tiles) {
+      u32 o[SCAN_PER];
 #pragma unroll
-    for (int k = 0; k < PER; ++k) { if ((i0 + k) < n_tiles) counts[i0 + k] = ex; ex += v[k]; }
+      for (int k = 0; k < SCAN_PER; ++k) { o[k] = ex; ex += v[k]; }
+      *reinterpret_cast<uint4*>(counts + i0) = make_uint4(o[0], o[1], o[2], o[3]);
+      *reinterpret_cast<uint4*>(counts + i0 + 4) = make_uint4(o[4], o[5], o[6], o[7]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < SCAN_PER; ++k) { if ((i0 + k) < n_tiles) counts[i0 + k] = ex; ex += v[k]; }
+    }
     carry += tot;
+#pragma unroll
+    for (int k = 0; k < SCAN_PER; ++k) v[k] = nv[k];
   }
   if (threadIdx.x == 0) { counts[n_tiles] = carry; *total_out = carry; }
 }
@@ -312,28 +308,39 @@ void launch_flag_compact(hipStream_t st, const FlagArgs& a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Records per rank.  The keys are sorted by communicator, so a workgroup's slice of them covers a
-// short run of communicators: it counts (communicator, member slot) pairs in an LDS table that spans
-// as many communicators as fit, then adds every non-zero cell to its rank's (zeroed) blame column
-// with one integer atomic.  A slice that covers more communicators takes several rounds.
+// One pass over the sorted keys for two results.
+// (1) Collective heads per tile of SEG_TILE keys (a head = the first key of a (communicator,
+//     operation counter) pair); equal neighbours are duplicates.
+// (2) Records per rank.  The keys are sorted by communicator, so a workgroup's slice of them covers a
+//     short run of communicators: it counts (communicator, member slot) pairs in an LDS table that
+//     spans as many communicators as fit, then adds every non-zero cell to its rank's (zeroed) blame
+//     column with one integer atomic.  A slice that covers more communicators takes several rounds.
 constexpr u32 RC_CELLS = 8192;
-__global__ __launch_bounds__(256) void k_rank_count(const u64* __restrict__ key, u32 n, SqueezedFormat sf,
-                                                    const u32* __restrict__ member_off,
-                                                    const u32* __restrict__ members_sorted,
-                                                    const u32* __restrict__ comm_size, u32 n_ranks,
-                                                    i64* __restrict__ blame) {
+constexpr u32 RC_MAX_TILES = 1024 + 8;      // tiles of one workgroup's slice (the launch keeps slices within 1024 tiles)
+__global__ __launch_bounds__(256) void k_keys_pass(const u64* __restrict__ key, u32 n, SqueezedFormat sf,
+                                                   const u32* __restrict__ member_off,
+                                                   const u32* __restrict__ members_sorted,
+                                                   const u32* __restrict__ comm_size, u32 n_ranks,
+                                                   i64* __restrict__ blame, u32* __restrict__ tile_heads,
+                                                   u64* __restrict__ counters) {
   __shared__ u32 s_h[RC_CELLS];
+  __shared__ u32 s_tile[RC_MAX_TILES];
   __shared__ u32 s_end;
   const int mb = sf.mb, cshift = sf.mb + sf.ws;
   const u64 mmask = ((u64)1 << mb) - 1;
   const u32 slots = mb >= 13 ? RC_CELLS : (1u << mb);         // member slots covered by one round
   const u32 width = RC_CELLS / slots;                         // communicators covered by one round
   const u32 n_sub = mb >= 13 ? (1u << (mb - 13)) : 1u;        // rounds needed to cover every slot
-  const u64 per = ((u64)n + gridDim.x - 1) / gridDim.x;
-  const u64 lo = per * blockIdx.x, hi64 = (lo + per) < n ? (lo + per) : n;
-  const u32 hi = (u32)hi64;
+  // slices of whole tiles
+  const u64 per = (((u64)n + gridDim.x - 1) / gridDim.x + SEG_TILE - 1) / SEG_TILE * SEG_TILE;
+  const u64 lo64 = per * blockIdx.x;
+  if (lo64 >= n) return;
+  const u32 lo = (u32)lo64, hi = (u32)((lo64 + per) < n ? (lo64 + per) : n);
+  const u32 my_tiles = (hi - lo + SEG_TILE - 1) / SEG_TILE;
+  for (u32 i = threadIdx.x; i < my_tiles; i += 256) s_tile[i] = 0;
   unsigned long long* out = (unsigned long long*)(blame + (u64)CCLD_BLM_N_RECORDS * n_ranks);
-  u32 pos = (u32)lo;
+  bool dup = false;
+  u32 pos = lo;
   while (pos < hi) {
     const u32 c0 = (u32)(key[pos] >> cshift);
     u32 end = hi;
@@ -343,18 +350,33 @@ __global__ __launch_bounds__(256) void k_rank_count(const u64* __restrict__ key,
       if (threadIdx.x == 0) s_end = hi;
       __syncthreads();
       // eight keys per thread in flight; the keys are sorted, so the first one past the table's
-      // communicators ends this thread's walk
+      // communicators ends this thread's walk (that key is taken up by the next round)
       bool more = true;
       for (u32 j0 = pos + threadIdx.x; more && j0 < hi; j0 += 256 * 8) {
-        u64 k[8];
+        u64 k[8], kp[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) { const u32 j = j0 + u * 256; k[u] = j < hi ? key[j] : ~0ull; }
+        for (int u = 0; u < 8; ++u) {
+          const u32 j = j0 + u * 256;
+          k[u] = j < hi ? key[j] : ~0ull;
+        }
+        // the key before each one sits in the lane below (a lane walks on no longer than the lanes
+        // below it, so that lane is active); a wave's first lane reads it from memory
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const u32 j = j0 + u * 256;
+          kp[u] = __shfl_up((unsigned long long)k[u], 1);
+          if ((threadIdx.x & 63) == 0) kp[u] = (j < hi && j > 0) ? key[j - 1] : ~0ull;
+        }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           const u32 j = j0 + u * 256;
           if (!more || j >= hi) continue;
           const u32 c = (u32)(k[u] >> cshift);
           if (c - c0 >= width) { atomicMin(&s_end, j); more = false; continue; }
+          if (sub == 0) {
+            if (j == 0 || (k[u] >> mb) != (kp[u] >> mb)) atomicAdd(&s_tile[(j - lo) / SEG_TILE], 1u);
+            else dup |= (k[u] == kp[u]);
+          }
           const u32 slot = (u32)(k[u] & mmask);
           if (slot - s0 < slots) atomicAdd(&s_h[(c - c0) * slots + (slot - s0)], 1u);
         }
@@ -371,13 +393,17 @@ __global__ __launch_bounds__(256) void k_rank_count(const u64* __restrict__ key,
     }
     pos = end;
   }
+  for (u32 i = threadIdx.x; i < my_tiles; i += 256) tile_heads[lo / SEG_TILE + i] = s_tile[i];
+  if (dup) atomic_or_u64(&counters[CNT_STATUS], DS_DUPLICATE);
 }
-void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, const SqueezedFormat& sf,
-                       const DeviceTopology& T, int64_t* blame) {
+void launch_keys_pass(hipStream_t st, const uint64_t* key, uint32_t n, const SqueezedFormat& sf,
+                      const DeviceTopology& T, int64_t* blame, uint32_t* tile_heads, uint64_t* counters) {
   if (n == 0) return;
-  const uint32_t blocks = std::min<uint32_t>((n + 4095) / 4096, RANKCOUNT_BLOCKS);
-  hipLaunchKernelGGL(k_rank_count, dim3(blocks), dim3(256), 0, st, key, n, sf, T.member_off, T.members_sorted,
-                     T.size, T.n_ranks, blame);
+  uint32_t blocks = std::min<uint32_t>((n + 4095) / 4096, RANKCOUNT_BLOCKS);
+  const uint32_t max_slice = (RC_MAX_TILES - 8) * (uint32_t)SEG_TILE;        // the per-tile counters of one slice fit in LDS
+  blocks = std::max<uint32_t>(blocks, (uint32_t)(((uint64_t)n + max_slice - 1) / max_slice));
+  hipLaunchKernelGGL(k_keys_pass, dim3(blocks), dim3(256), 0, st, key, n, sf, T.member_off, T.members_sorted,
+                     T.size, T.n_ranks, blame, tile_heads, counters);
 }
 
 // Blame: key every flag by its rank, sort, then one wavefront per rank sums its run.

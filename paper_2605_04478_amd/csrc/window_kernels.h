@@ -48,7 +48,6 @@ struct SegArgs {
   int64_t lag_floor;
   uint32_t kmad_num, kmad_den, barrier_bytes;
 };
-void launch_seg_count(hipStream_t st, const SegArgs& a);          // fills tile_heads, flags duplicates
 void launch_scan_tiles(hipStream_t st, uint32_t* counts, uint32_t n_tiles, uint64_t* total_out);
 void launch_seg_analyze(hipStream_t st, const SegArgs& a);        // small collectives, then the oversized ones
 
@@ -68,8 +67,10 @@ struct FlagArgs {
 };
 void launch_flag_compact(hipStream_t st, const FlagArgs& a);
 
-void launch_rank_count(hipStream_t st, const uint64_t* key, uint32_t n, const SqueezedFormat& sf,
-                       const DeviceTopology& T, int64_t* blame);     // adds into the zeroed records column
+// one pass over the sorted keys: collective heads per tile (tile_heads), duplicates (status counter),
+// records per rank (added into the zeroed records column of blame)
+void launch_keys_pass(hipStream_t st, const uint64_t* key, uint32_t n, const SqueezedFormat& sf,
+                      const DeviceTopology& T, int64_t* blame, uint32_t* tile_heads, uint64_t* counters);
 void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag_pos, uint32_t n_flag,
                        const SqueezedFormat& sf, const DeviceTopology& T, uint64_t* out_key);
 void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* sidx, uint32_t n_flag,
