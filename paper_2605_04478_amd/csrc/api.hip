@@ -48,11 +48,14 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->ing_table = w.take<uint32_t>((uint64_t)INGEST_MAX_BUCKETS * INGEST_BLOCKS);
   c->ing_base = w.take<uint32_t>(INGEST_MAX_BUCKETS + 2);
   // sort
-  const uint64_t tw = sort_table_words(N);
-  for (int i = 0; i < 2; ++i) { c->sb.key[i] = w.take<uint64_t>(N); c->sb.idx[i] = w.take<uint32_t>(N); }
+  // (the hang pass sorts its root list, at most one entry per communicator member, in these buffers too)
+  const uint64_t NS = std::max<uint64_t>(N, n_members);
+  c->sort_cap = NS;
+  const uint64_t tw = sort_table_words(NS);
+  for (int i = 0; i < 2; ++i) { c->sb.key[i] = w.take<uint64_t>(NS); c->sb.idx[i] = w.take<uint32_t>(NS); }
   c->sb.table = w.take<uint32_t>(tw);
   c->sb.totals = w.take<uint32_t>(SORT_RADIX);
-  c->keyC = w.take<uint64_t>(N); c->idxC = w.take<uint32_t>(N);
+  c->keyC = w.take<uint64_t>(NS); c->idxC = w.take<uint32_t>(NS);
   c->table2 = w.take<uint32_t>(tw);
   c->totals2 = w.take<uint32_t>(SORT_RADIX);
   // analysis scratch

@@ -606,7 +606,7 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
     SortBuffers sb2;
     sb2.key[0] = c->sb.key[0]; sb2.idx[0] = c->sb.idx[0]; sb2.key[1] = c->sb.key[1]; sb2.idx[1] = c->sb.idx[1];
     sb2.table = c->table2; sb2.totals = c->totals2;
-    if (n_root > c->cap) return o->status = CCLD_E_CAPACITY;
+    if (n_root > c->sort_cap) return o->status = CCLD_E_CAPACITY;
     hipLaunchKernelGGL(k_hang_root_keys, dim3((n_root + 255) / 256), dim3(256), 0, st, a, (const u32*)c->h_root_list, n_root, c->kf.cb, c->keyC);
     KeySource ks; ks.key = c->keyC; ks.head = 0; ks.cap = n_root; ks.squeeze = 0; ks.hi_shift = 0; ks.lo_bits = 0; ks.lo_mask = 0; ks.lo_sub = 0;
     const int r = radix_sort_pairs(st, ks, n_root, sb2, c->kf.cb + c->rank_bits);
