@@ -3,7 +3,10 @@ member order, ring and tree), partial and tied rounds, stragglers, operations in
 and very large operation counters, one to three windows with state carried over, host and device
 batches, random analyzer parameters; and snapshot series of random progress (healthy, not-entered,
 inconsistent and all-stalled communicators, missing and repeated rows) through the hang and the
-progress-rate passes.  Every table is compared with the oracle's, bit-exactly."""
+progress-rate passes; and random Probing Frames (any blocks written, communicators repeated in a
+frame, bad ranks, communicators and counts) through the frame decoder.  Every table is compared with the oracle's, bit-exactly."""
+import collections
+
 import numpy as np
 import pytest
 
@@ -123,6 +126,52 @@ def test_random_cases_match_the_oracle(block):
     total = 0
     for seed in range(block * 30, block * 30 + 30):
         total += run(seed)
+    assert total > 0
+
+
+# ---- windows of several batches: each ingest drops the oldest batch -------------------------------
+def run_stream(seed):
+    topo, rows, params, rng = rand_case(seed)
+    if not rows:
+        return 0
+    cols = toy_cols(rows)
+    n = len(rows)
+    order = np.argsort(cols["t_enter"], kind="stable")
+    wb = int(rng.integers(1, 6))
+    n_b = int(rng.integers(1, 9))
+    cuts = [0] + sorted(int(x) for x in rng.integers(0, n + 1, n_b - 1)) + [n]
+    batches = []
+    for i in range(n_b):
+        sel = order[cuts[i]:cuts[i + 1]]
+        sel = sel[rng.permutation(len(sel))]
+        batches.append({k: v[sel] for k, v in cols.items()})
+    max_b = max(max(len(b["rank"]) for b in batches), 1)
+    params = dict(params, window_batches=wb)
+    from paper_2605_04478_amd import ccld
+    an = ccld.Analyzer(topo, max_window_records=max(wb * max_b, 1), max_batch_records=max_b, **params)
+    o = orc.Oracle(topo, params)
+    for i, b in enumerate(batches):
+        on_dev = rng.random() < 0.7
+        an.ingest(an.to_device(b) if on_dev else b)
+        if rng.random() < 0.3 and i + 1 < n_b:
+            continue                                    # several ingests between analyses
+        win = batches[max(0, i - wb + 1): i + 1]
+        wc = {k: np.concatenate([w[k] for w in win]) for k in b}
+        nw = len(wc["rank"])
+        g = an.analyze_window(FAR, n_records=max(nw, 1), per_record=True, alert_cap=nw + 1, cand_cap=max(65536, 8 * nw))
+        ref = o.analyze_window(wc, FAR)
+        blame = order_ = None
+        if ref.status == "OK":
+            blame, order_ = an.rank_blame()
+        compare(g, ref, blame, order_, what=f"seed{seed} step{i} wb={wb} n={nw} status={ref.status}")
+    an.close()
+    return n
+
+
+def test_random_windows_of_several_batches_match_the_oracle():
+    total = 0
+    for seed in range(1000, 1040):
+        total += run_stream(seed)
     assert total > 0
 
 
@@ -249,3 +298,71 @@ def test_random_snapshot_series_match_the_oracle(block):
     for seed in list(range(block * 40, block * 40 + 40)) + ([230] if block == 0 else []):
         seen.add(run_hang(seed)[1])
     assert "OK" in seen
+
+
+# ---- Probing Frames: ccld_decode_frames -------------------------------------------------------------
+def run_frames(seed):
+    rng = np.random.default_rng(seed)
+    topo, comms = rand_topo(rng)
+    R = topo.n_ranks
+    n_ch = int(rng.integers(1, 9))
+    n_snap = int(rng.integers(1, 12))
+    of_rank = collections.defaultdict(list)
+    for c, mem in enumerate(comms):
+        for r in mem:
+            of_rank[r].append(c)
+    cells = int(topo.size.sum())
+    from paper_2605_04478_amd import ccld
+    from tests.test_gpu_frames import both
+    an = ccld.Analyzer(topo, max_window_records=16, max_snapshot_rows=max(cells * n_ch * 2, 40 * (min(R, 300) + 2)))
+    o = orc.Oracle(topo)
+    o.frames_begin(n_ch)
+    st_seen = collections.Counter()
+    for s in range(n_snap):
+        k = int(rng.integers(0, min(R, 300) + 1))
+        ranks = rng.choice(R, k, replace=False).astype(np.uint32)
+        if rng.random() < 0.03 and k > 0:
+            ranks = np.concatenate([ranks, ranks[:1]])          # the same rank twice
+        frames = np.zeros(len(ranks), dtype=tg.FRAME_DTYPE)
+        frames["mode"] = 1
+        frames["n_channels"] = n_ch if rng.random() > 0.02 else int(rng.integers(0, 12))
+        frames["counter"] = rng.integers(0, 2**40, len(ranks))
+        frames["kernel_index"] = frames["counter"] % 8
+        bad = (int(rng.integers(0, max(len(ranks), 1))), int(rng.integers(0, 8))) if rng.random() < 0.12 else None
+        for i, r in enumerate(ranks):
+            mine = of_rank.get(int(r), [])
+            for b in range(8):
+                if rng.random() < 0.5 and bad != (i, b):
+                    continue
+                u = rng.random() if bad == (i, b) else 0.0
+                if not mine and bad != (i, b):
+                    continue
+                if mine and u < 0.4:
+                    cm = int(rng.choice(mine))
+                elif u < 0.7:
+                    cm = int(rng.integers(0, topo.n_comms))      # maybe not a member
+                else:
+                    cm = topo.n_comms + int(rng.integers(0, 3))  # unknown communicator
+                frames["block"]["comm"][i, b] = cm
+                frames["block"]["ext"][i, b] = 1 if rng.random() > 0.05 else 0
+                frames["block"]["counter"][i, b] = int(rng.integers(0, 50)) if rng.random() < 0.8 else int(rng.integers(0, 2**50))
+                cnt = rng.integers(0, 2**32, (8, 2), dtype=np.uint64) if rng.random() < 0.5 else rng.integers(0, 9, (8, 2)).astype(np.uint64)
+                if bad == (i, b) and u < 0.2:
+                    cnt[int(rng.integers(0, 8)), 0] = 2**32 + 5
+                frames["block"]["count"][i, b] = cnt
+        if rng.random() < 0.01 and len(ranks):
+            ranks = ranks.copy(); ranks[0] = R + 3               # rank out of range
+        fr = frames.view(np.uint8).reshape(len(ranks), tg.FRAME_BYTES)
+        st, _ = both(an, o, fr, ranks, s, n_ch, on_device=bool(rng.random() < 0.5), what=f"seed{seed} snap{s}")
+        st_seen[st] += 1
+        if rng.random() < 0.05:
+            an.reset_frames(); o.frames_begin(n_ch)
+    an.close()
+    return st_seen
+
+
+def test_random_frames_match_the_oracle():
+    seen = collections.Counter()
+    for seed in range(80):
+        seen += run_frames(seed)
+    assert seen["OK"] > 100 and len(seen) > 2
