@@ -66,6 +66,8 @@ def main() -> int:
     ap.add_argument("--cycles", type=int, default=2000, help="10-op cycles per rank (2000 = the 82M-record trace)")
     ap.add_argument("--no-shuffle", action="store_true", help="keep the generator's time-major record order")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-time-major", action="store_true",
+                    help="skip the secondary figure on the generator's record order (keeps a profile to the timed steps)")
     ap.add_argument("--cpu-cycles", type=int, default=2000, help="cycles of the trace given to the CPU oracle")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--host-batch", action="store_true",
@@ -152,7 +154,7 @@ def main() -> int:
     an.profile_enable(False)
     assert res is not None and res.status == "OK", res
     time_major_ms = None
-    if cols_time_major is not None:
+    if cols_time_major is not None and not args.no_time_major:
         for timed in (False, True):
             torch.cuda.synchronize()
             t_t = time.perf_counter()
