@@ -21,7 +21,7 @@ __device__ __forceinline__ u64 load_key(const KeySource& s, u32 j, u32* phys) {
   u32 p = s.head + j;                       // head < cap and j < cap <= 2^31: no wrap below 2^32
   if (p >= s.cap) p -= s.cap;
   *phys = p;
-  u64 k = s.key[p];
+  u64 k = __builtin_nontemporal_load(s.key + p);
   if (s.squeeze) k = (s.hi_shift < 64 ? (k >> s.hi_shift) << s.lo_bits : 0ull) | ((k & s.lo_mask) - s.lo_sub);
   return k;
 }
@@ -47,7 +47,11 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, cons
       const ulonglong2* __restrict__ in2 = reinterpret_cast<const ulonglong2*>(key_in + base);
       ulonglong2 kk[SORT_ITEMS / 2];
 #pragma unroll
-      for (int it = 0; it < SORT_ITEMS / 2; ++it) kk[it] = in2[it * SORT_THREADS + tid];
+      for (int it = 0; it < SORT_ITEMS / 2; ++it) {
+        typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+        const u64x2 t2 = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(in2 + it * SORT_THREADS + tid));
+        kk[it].x = t2.x; kk[it].y = t2.y;
+      }
 #pragma unroll
       for (int it = 0; it < SORT_ITEMS / 2; ++it) {
         atomicAdd(&s_hist[t][(u32)(kk[it].x >> shift) & dmask], 1u);
@@ -138,9 +142,9 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, c
         k[it] = load_key(src, base + e, &v[it]);
         if (PACKED) k[it] = (k[it] << ibits) | v[it];
       } else if (IN == IN_PAIR) {
-        k[it] = key_in[base + e]; v[it] = idx_in[base + e];
+        k[it] = __builtin_nontemporal_load(key_in + base + e); v[it] = __builtin_nontemporal_load(idx_in + base + e);
       } else {
-        k[it] = key_in[base + e];
+        k[it] = __builtin_nontemporal_load(key_in + base + e);
       }
       dig[it] = (u32)(k[it] >> shift) & dmask;
     } else {

@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void k_ingest_hist(IngestArgs a, u32 n_comms) 
   for (u64 i0 = chunk * blockIdx.x + threadIdx.x; i0 < i_end; i0 += 256 * 8) {
     u32 c[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) c[u] = (i0 + (u64)u * 256 < i_end) ? in_comm[i0 + (u64)u * 256] : 0xFFFFFFFFu;
+    for (int u = 0; u < 8; ++u) c[u] = (i0 + (u64)u * 256 < i_end) ? __builtin_nontemporal_load(in_comm + i0 + (u64)u * 256) : 0xFFFFFFFFu;
 #pragma unroll
     for (int u = 0; u < 8; ++u)
       if (i0 + (u64)u * 256 < i_end) atomicAdd(&s_cnt[c[u] < n_comms ? (c[u] >> a.bshift) : 0u], 1u);
@@ -107,8 +107,10 @@ __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology
     for (int u = 0; u < U; ++u) {
       const u64 i = i0 + (u64)u * THREADS;
       if (i < i_end) {
-        r[u] = in_rank[i]; c[u] = in_comm[i]; sq[u] = in_seq[i]; op[u] = in_op[i]; nb[u] = in_bytes[i];
-        te[u] = in_te[i]; tx[u] = in_tx[i];
+        r[u] = __builtin_nontemporal_load(in_rank + i); c[u] = __builtin_nontemporal_load(in_comm + i);
+        sq[u] = __builtin_nontemporal_load(in_seq + i); op[u] = __builtin_nontemporal_load(in_op + i);
+        nb[u] = __builtin_nontemporal_load(in_bytes + i);
+        te[u] = __builtin_nontemporal_load(in_te + i); tx[u] = __builtin_nontemporal_load(in_tx + i);
       }
     }
     // the communicators of each rank with its member slot in each: one 16-byte row of words
@@ -357,7 +359,7 @@ __global__ __launch_bounds__(256) void k_keys_pass(const u64* __restrict__ key, 
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           const u32 j = j0 + u * 256;
-          k[u] = j < hi ? key[j] : ~0ull;
+          k[u] = j < hi ? __builtin_nontemporal_load(key + j) : ~0ull;
         }
         // the key before each one sits in the lane below (a lane walks on no longer than the lanes
         // below it, so that lane is active); a wave's first lane reads it from memory
