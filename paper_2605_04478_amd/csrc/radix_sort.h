@@ -10,6 +10,9 @@ constexpr int SORT_RADIX = 1 << SORT_RBITS;
 constexpr int SORT_THREADS = 512;
 constexpr int SORT_ITEMS = 8;                    // keys per thread
 constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
+// arrays of at least this many tiles (268 MB of keys) exceed the memory-side cache: eight tiles per
+// histogram workgroup, loads with the non-temporal hint
+constexpr uint32_t SORT_STREAM_TILES = 8192;
 
 // Where the first pass reads its keys.  The window keeps records in a circular buffer and
 // keys with a gap between the (sequence, rank) field and the communicator field; the first

@@ -17,11 +17,20 @@ namespace ccld {
 enum SortIn { IN_SOURCE, IN_PAIR, IN_PACKED };
 enum SortOut { OUT_PAIR, OUT_PACKED };
 
+// Arrays larger than the memory-side cache are read once per kernel and gone before the next one
+// reads them again: their loads carry the non-temporal hint so that they do not displace the lines
+// the scatter's partial writes are merged in.  Smaller arrays are read plainly (the scatter finds
+// in the cache what the histogram just read).
+template <bool STREAM, class T> __device__ __forceinline__ T load_once(const T* p) {
+  return STREAM ? __builtin_nontemporal_load(p) : *p;
+}
+
+template <bool STREAM>
 __device__ __forceinline__ u64 load_key(const KeySource& s, u32 j, u32* phys) {
   u32 p = s.head + j;                       // head < cap and j < cap <= 2^31: no wrap below 2^32
   if (p >= s.cap) p -= s.cap;
   *phys = p;
-  u64 k = __builtin_nontemporal_load(s.key + p);
+  u64 k = load_once<STREAM>(s.key + p);
   if (s.squeeze) k = (s.hi_shift < 64 ? (k >> s.hi_shift) << s.lo_bits : 0ull) | ((k & s.lo_mask) - s.lo_sub);
   return k;
 }
@@ -34,6 +43,7 @@ template <bool FIRST, int HIST_TILES>
 __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, const u64* __restrict__ key_in,
                                                              u32* __restrict__ table, u32 n, u32 n_tiles,
                                                              int shift, u32 dmask) {
+  constexpr bool STREAM = HIST_TILES == 8;      // the many-tile variant serves the arrays beyond the cache size
   __shared__ u32 s_hist[HIST_TILES][SORT_RADIX];
   const u32 tid = threadIdx.x, tile0 = blockIdx.x * HIST_TILES;
   for (u32 i = tid; i < HIST_TILES * SORT_RADIX; i += SORT_THREADS) (&s_hist[0][0])[i] = 0;
@@ -49,7 +59,7 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, cons
 #pragma unroll
       for (int it = 0; it < SORT_ITEMS / 2; ++it) {
         typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
-        const u64x2 t2 = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(in2 + it * SORT_THREADS + tid));
+        const u64x2 t2 = load_once<STREAM>(reinterpret_cast<const u64x2*>(in2 + it * SORT_THREADS + tid));
         kk[it].x = t2.x; kk[it].y = t2.y;
       }
 #pragma unroll
@@ -64,7 +74,7 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, cons
       u32 j = base + it * SORT_THREADS + tid;
       if (j < n) {
         u64 k;
-        if (FIRST) { u32 ph; k = load_key(src, j, &ph); } else k = key_in[j];
+        if (FIRST) { u32 ph; k = load_key<STREAM>(src, j, &ph); } else k = key_in[j];
         atomicAdd(&s_hist[t][(u32)(k >> shift) & dmask], 1u);
       }
     }
@@ -100,7 +110,7 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scan(u32* __restrict__ t
 // ---- rank, regroup in LDS, scatter --------------------------------------------------------------
 // shift addresses the digit inside the word the kernel ranks: the key itself, or the packed word
 // (key << ibits | index) when either side is packed.
-template <int IN, int OUT>
+template <int IN, int OUT, bool STREAM>
 __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, const u64* __restrict__ key_in,
                                                                 const u32* __restrict__ idx_in,
                                                                 u64* __restrict__ key_out, u32* __restrict__ idx_out,
@@ -139,12 +149,12 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, c
     v[it] = 0;
     if (e < valid) {
       if (IN == IN_SOURCE) {
-        k[it] = load_key(src, base + e, &v[it]);
+        k[it] = load_key<STREAM>(src, base + e, &v[it]);
         if (PACKED) k[it] = (k[it] << ibits) | v[it];
       } else if (IN == IN_PAIR) {
-        k[it] = __builtin_nontemporal_load(key_in + base + e); v[it] = __builtin_nontemporal_load(idx_in + base + e);
+        k[it] = load_once<STREAM>(key_in + base + e); v[it] = load_once<STREAM>(idx_in + base + e);
       } else {
-        k[it] = __builtin_nontemporal_load(key_in + base + e);
+        k[it] = load_once<STREAM>(key_in + base + e);
       }
       dig[it] = (u32)(k[it] >> shift) & dmask;
     } else {
@@ -229,15 +239,20 @@ template <int IN, int OUT>
 static void launch_scatter(hipStream_t stream, const KeySource& src, const u64* key_in, const u32* idx_in,
                            u64* key_out, u32* idx_out, const SortBuffers& buf, u32 n, u32 n_tiles, int shift,
                            int nbits, int ibits) {
-  hipLaunchKernelGGL((k_radix_scatter<IN, OUT>), dim3((n_tiles + 7) / 8 * 8), dim3(SORT_THREADS), 0, stream, src, key_in, idx_in,
-                     key_out, idx_out, (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, shift, nbits, ibits);
+  if (n_tiles >= SORT_STREAM_TILES)
+    hipLaunchKernelGGL((k_radix_scatter<IN, OUT, true>), dim3((n_tiles + 7) / 8 * 8), dim3(SORT_THREADS), 0, stream, src, key_in, idx_in,
+                       key_out, idx_out, (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, shift, nbits, ibits);
+  else
+    hipLaunchKernelGGL((k_radix_scatter<IN, OUT, false>), dim3((n_tiles + 7) / 8 * 8), dim3(SORT_THREADS), 0, stream, src, key_in, idx_in,
+                       key_out, idx_out, (const u32*)buf.table, (const u32*)buf.totals, n, n_tiles, shift, nbits, ibits);
 }
 
 static int host_bits(uint64_t v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
 
-int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const SortBuffers& buf, int bits,
+int radix_sort_pairs(hipStream_t stream, const KeySource& src_in, uint32_t n, const SortBuffers& buf, int bits,
                      Profiler* prof, int cls_hist, int cls_scan, int cls_scatter) {
   if (n == 0) return 0;
+  const KeySource& src = src_in;
   const u32 n_tiles = sort_tiles(n);
   const int passes = bits <= 0 ? 1 : (bits + SORT_RBITS - 1) / SORT_RBITS;
   const int ibits = host_bits(src.cap ? src.cap - 1 : 0);
@@ -255,7 +270,7 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src, uint32_t n, const
     const int scat_shift = done_bits + (packed ? ibits : 0);
     if (prof) prof->begin();
     const u64* hin = first ? nullptr : buf.key[cur];
-    if (n_tiles >= 8192) {
+    if (n_tiles >= SORT_STREAM_TILES) {
       if (first) hipLaunchKernelGGL((k_radix_hist<true, 8>), dim3((n_tiles + 7) / 8), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
       else hipLaunchKernelGGL((k_radix_hist<false, 8>), dim3((n_tiles + 7) / 8), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
     } else {
