@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void k_ingest_hist(IngestArgs a, u32 n_comms) 
   extern __shared__ u32 s_cnt[];
   for (u32 b = threadIdx.x; b < a.n_buckets; b += 256) s_cnt[b] = 0;
   __syncthreads();
-  const u64 chunk = ((a.n + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+  const u64 chunk = a.chunk / a.hist_split;
   const u64 i_end = (chunk * (blockIdx.x + 1)) < a.n ? chunk * (blockIdx.x + 1) : a.n;
   const u32* __restrict__ in_comm = a.comm;
   for (u64 i0 = chunk * blockIdx.x + threadIdx.x; i0 < i_end; i0 += 256 * 8) {
@@ -63,6 +63,60 @@ __global__ __launch_bounds__(256) void k_ingest_scan(u32* table, u32* totals, u3
   if (threadIdx.x == 0) totals[blockIdx.x] = tot;
 }
 
+// Validation and key of one record (Trace ID = communicator id + operation counter, then the rank's
+// member slot).  mem = the rank's packed membership row when the topology has one (memb4 != null).
+__device__ __forceinline__ u64 ingest_key(u32 r, u32 c, u64 sq, u32 op, i64 te, i64 tx, const uint4& mem,
+                                          const uint4* memb4, const DeviceTopology& T, const KeyFormat& kf,
+                                          u32 slot_mask, u64& status, u64& maxseq, u64& maxinv) {
+  u64 key = 0;
+  if (c >= T.n_comms) {
+    status |= DS_UNKNOWN_COMM;
+    return key;
+  }
+  bool member = false;
+  u32 slot = 0;
+  if (memb4) {
+    const u32 w = c == (mem.x >> kf.mb) ? mem.x : c == (mem.y >> kf.mb) ? mem.y : c == (mem.z >> kf.mb) ? mem.z : mem.w;
+    member = c == (w >> kf.mb);
+    slot = w & slot_mask;
+  } else if (r < T.n_ranks) {
+    for (u32 q = T.rank_comm_off[r]; q < T.rank_comm_off[r + 1]; ++q)
+      if (T.rank_comms[q] == c) { member = true; slot = T.rank_slots[q]; }
+  }
+  if (!member) status |= DS_NOT_MEMBER;
+  if (op >= CCLD_OP_MAX || te < 0 || te == T_INFLIGHT || tx < te) status |= DS_RANGE;
+  if (kf.sb < 64 && (sq >> kf.sb) != 0) {
+    status |= DS_KEY_WIDTH;
+  } else {
+    key = (kf.cb ? ((u64)c << (64 - kf.cb)) : 0ull) | (sq << kf.mb) | (u64)slot;
+    maxseq = sq > maxseq ? sq : maxseq;
+    maxinv = ~sq > maxinv ? ~sq : maxinv;
+  }
+  return key;
+}
+
+// status bits and the extreme operation counters of a workgroup leave through one set of atomics
+template <int THREADS>
+__device__ __forceinline__ void ingest_publish(u64 status, u64 maxseq, u64 maxinv, u64* s_status, u64* s_max,
+                                               u64* s_inv, BatchMeta* meta) {
+  u64 st = status;
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) st |= shfl_xor_u64(st, m);
+  u64 mx = wave_max_u64(maxseq), mi = wave_max_u64(maxinv);
+  const u32 lane = lane_id(), wave = threadIdx.x / CCLD_WAVE;
+  if (lane == 0) { s_status[wave] = st; s_max[wave] = mx; s_inv[wave] = mi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    u64 S = 0, M = 0, I = 0;
+    for (int w = 0; w < THREADS / CCLD_WAVE; ++w) {
+      S |= s_status[w]; M = s_max[w] > M ? s_max[w] : M; I = s_inv[w] > I ? s_inv[w] : I;
+    }
+    if (S) atomic_or_u64(&meta->status, S);
+    if (M) atomicMax((unsigned long long*)&meta->max_seq, (unsigned long long)M);
+    if (I) atomicMax((unsigned long long*)&meta->max_inv_seq, (unsigned long long)I);
+  }
+}
+
 // Validates and keys every record and stores it in the window.  Inside the batch's slot range the
 // records are placed grouped by communicator bucket (the order inside a bucket is arbitrary), so
 // that the analysis, which walks the window in (communicator, ...) order, gathers its payload rows
@@ -77,7 +131,7 @@ __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology
   __shared__ u64 s_status[THREADS / CCLD_WAVE], s_max[THREADS / CCLD_WAVE], s_inv[THREADS / CCLD_WAVE];
   u32* s_off = reinterpret_cast<u32*>(s_dyn + (LDS_TABLE ? T.n_ranks : 0u));
   for (u32 b = threadIdx.x; b < a.n_buckets; b += THREADS)
-    s_off[b] = a.bucket_base[b] + a.table[(u64)b * gridDim.x + blockIdx.x];
+    s_off[b] = a.bucket_base[b] + a.table[((u64)b * gridDim.x + blockIdx.x) * a.hist_split];
   if (LDS_TABLE) {
     const uint4* __restrict__ g = reinterpret_cast<const uint4*>(T.rank_memb4);
     for (u32 r = threadIdx.x; r < T.n_ranks; r += THREADS) s_dyn[r] = g[r];
@@ -96,7 +150,7 @@ __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology
   const uint4* __restrict__ memb4 = reinterpret_cast<const uint4*>(T.rank_memb4);
   const u32 slot_mask = kf.mb < 32 ? (1u << kf.mb) - 1 : ~0u;
   // every workgroup walks one contiguous slice of the batch, so its nine streams advance page by page
-  const u64 chunk = ((a.n + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+  const u64 chunk = a.chunk;
   const u64 i_end = (chunk * (blockIdx.x + 1)) < a.n ? chunk * (blockIdx.x + 1) : a.n;
   for (u64 i0 = chunk * blockIdx.x + threadIdx.x; i0 < i_end; i0 += THREADS * U) {
     u32 r[U], c[U], op[U];
@@ -124,31 +178,8 @@ __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology
     for (int u = 0; u < U; ++u) {
       const u64 i = i0 + (u64)u * THREADS;
       if (i >= i_end) continue;
-      u64 key = 0;
-      if (c[u] >= T.n_comms) {
-        status |= DS_UNKNOWN_COMM;
-      } else {
-        bool member = false;
-        u32 slot = 0;
-        if (memb4) {
-          const u32 w = c[u] == (mem[u].x >> kf.mb) ? mem[u].x : c[u] == (mem[u].y >> kf.mb) ? mem[u].y
-                      : c[u] == (mem[u].z >> kf.mb) ? mem[u].z : mem[u].w;
-          member = c[u] == (w >> kf.mb);
-          slot = w & slot_mask;
-        } else if (r[u] < T.n_ranks) {
-          for (u32 q = T.rank_comm_off[r[u]]; q < T.rank_comm_off[r[u] + 1]; ++q)
-            if (T.rank_comms[q] == c[u]) { member = true; slot = T.rank_slots[q]; }
-        }
-        if (!member) status |= DS_NOT_MEMBER;
-        if (op[u] >= CCLD_OP_MAX || te[u] < 0 || te[u] == T_INFLIGHT || tx[u] < te[u]) status |= DS_RANGE;
-        if (kf.sb < 64 && (sq[u] >> kf.sb) != 0) {
-          status |= DS_KEY_WIDTH;
-        } else {
-          key = (kf.cb ? ((u64)c[u] << (64 - kf.cb)) : 0ull) | (sq[u] << kf.mb) | (u64)slot;
-          maxseq = sq[u] > maxseq ? sq[u] : maxseq;
-          maxinv = ~sq[u] > maxinv ? ~sq[u] : maxinv;
-        }
-      }
+      const u64 key = ingest_key(r[u], c[u], sq[u], op[u], te[u], tx[u], mem[u], memb4, T, kf, slot_mask, status, maxseq,
+                                 maxinv);
       const u32 at = atomicAdd(&s_off[c[u] < T.n_comms ? (c[u] >> a.bshift) : 0u], 1u);
       u64 p = (u64)a.tail + at;
       if (p >= a.cap) p -= a.cap;
@@ -159,45 +190,156 @@ __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology
       out_row[p] = rw;
     }
   }
-  // one pair of atomics per workgroup
-  u64 st = status;
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) st |= shfl_xor_u64(st, m);
-  u64 mx = wave_max_u64(maxseq), mi = wave_max_u64(maxinv);
-  const u32 lane = lane_id(), wave = threadIdx.x / CCLD_WAVE;
-  if (lane == 0) { s_status[wave] = st; s_max[wave] = mx; s_inv[wave] = mi; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    u64 S = 0, M = 0, I = 0;
-    for (int w = 0; w < THREADS / CCLD_WAVE; ++w) {
-      S |= s_status[w]; M = s_max[w] > M ? s_max[w] : M; I = s_inv[w] > I ? s_inv[w] : I;
-    }
-    if (S) atomic_or_u64(&a.meta->status, S);
-    if (M) atomicMax((unsigned long long*)&a.meta->max_seq, (unsigned long long)M);
-    if (I) atomicMax((unsigned long long*)&a.meta->max_inv_seq, (unsigned long long)I);
-  }
+  ingest_publish<THREADS>(status, maxseq, maxinv, s_status, s_max, s_inv, a.meta);
 }
-void launch_ingest(hipStream_t st, const IngestArgs& a, const DeviceTopology& T, const KeyFormat& kf) {
-  if (a.n == 0) return;
+// Large batches: the same placement with the write-out regrouped in LDS.  A workgroup takes CHUNK
+// records per round, gives each its slot in its bucket (LDS atomic, as above), then stages keys and
+// rows in LDS ordered by (bucket, slot) and writes them out with consecutive lanes on consecutive
+// 16-byte pieces: every bucket's share of the round leaves as one contiguous run instead of one
+// scattered 40-byte store per lane.  At most 64 buckets.
+template <int THREADS, bool LDS_TABLE>
+__global__ __launch_bounds__(THREADS) void k_ingest_staged(IngestArgs a, DeviceTopology T, KeyFormat kf) {
+  constexpr int U = 2;
+  constexpr u32 CHUNK = THREADS * U;
+  // [n_ranks] membership rows (LDS_TABLE) | [2 CHUNK] row halves | [CHUNK] keys | [CHUNK] window slots
+  extern __shared__ uint4 s_dyn[];
+  __shared__ u64 s_status[THREADS / CCLD_WAVE], s_max[THREADS / CCLD_WAVE], s_inv[THREADS / CCLD_WAVE];
+  __shared__ u32 s_off[64], s_start[64], s_pre[64], s_total;
+  uint4* s_row = s_dyn + (LDS_TABLE ? T.n_ranks : 0u);
+  u64* s_key = reinterpret_cast<u64*>(s_row + 2 * CHUNK);
+  u32* s_p = reinterpret_cast<u32*>(s_key + CHUNK);
+  const u32 tid = threadIdx.x;
+  if (tid < a.n_buckets) {
+    const u32 o = a.bucket_base[tid] + a.table[((u64)tid * gridDim.x + blockIdx.x) * a.hist_split];
+    s_off[tid] = o; s_start[tid] = o;
+  }
+  if (LDS_TABLE) {
+    const uint4* __restrict__ g = reinterpret_cast<const uint4*>(T.rank_memb4);
+    for (u32 r = tid; r < T.n_ranks; r += THREADS) s_dyn[r] = g[r];
+  }
+  __syncthreads();
+  u64 status = 0, maxseq = 0, maxinv = 0;
+  const u32* __restrict__ in_rank = a.rank;
+  const u32* __restrict__ in_comm = a.comm;
+  const u64* __restrict__ in_seq = a.seq;
+  const uint8_t* __restrict__ in_op = a.op;
+  const u64* __restrict__ in_bytes = a.bytes;
+  const i64* __restrict__ in_te = a.t_enter;
+  const i64* __restrict__ in_tx = a.t_exit;
+  u64* __restrict__ out_key = a.win_key;
+  uint4* __restrict__ out_row = reinterpret_cast<uint4*>(a.win_row);
+  const uint4* __restrict__ memb4 = reinterpret_cast<const uint4*>(T.rank_memb4);
+  const u32 slot_mask = kf.mb < 32 ? (1u << kf.mb) - 1 : ~0u;
+  const u64 i_begin = a.chunk * blockIdx.x;
+  const u64 i_end = (a.chunk * (blockIdx.x + 1)) < a.n ? a.chunk * (blockIdx.x + 1) : a.n;
+  // the next round's columns are loaded while this round is staged and written out
+  u32 r[U], c[U], op[U], nr[U], nc[U], nop[U];
+  u64 sq[U], nb[U], nsq[U], nnb[U];
+  i64 te[U], tx[U], nte[U], ntx[U];
+  auto load_round = [&](u64 base, u32 (&R)[U], u32 (&C)[U], u64 (&S)[U], u32 (&O)[U], u64 (&B)[U], i64 (&E)[U], i64 (&X)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u64 i = base + (u64)u * THREADS + tid;
+      if (i < i_end) {
+        R[u] = __builtin_nontemporal_load(in_rank + i); C[u] = __builtin_nontemporal_load(in_comm + i);
+        S[u] = __builtin_nontemporal_load(in_seq + i); O[u] = __builtin_nontemporal_load(in_op + i);
+        B[u] = __builtin_nontemporal_load(in_bytes + i);
+        E[u] = __builtin_nontemporal_load(in_te + i); X[u] = __builtin_nontemporal_load(in_tx + i);
+      }
+    }
+  };
+  load_round(i_begin, r, c, sq, op, nb, te, tx);
+  for (u64 base = i_begin; base < i_end; base += CHUNK) {        // uniform over the workgroup
+    u32 at[U], bk[U];
+    u64 key[U];
+    bool on[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) on[u] = base + (u64)u * THREADS + tid < i_end;
+    load_round(base + CHUNK, nr, nc, nsq, nop, nnb, nte, ntx);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!on[u]) continue;
+      uint4 mem = make_uint4(~0u, ~0u, ~0u, ~0u);
+      if (memb4 && r[u] < T.n_ranks) mem = LDS_TABLE ? s_dyn[r[u]] : memb4[r[u]];
+      key[u] = ingest_key(r[u], c[u], sq[u], op[u], te[u], tx[u], mem, memb4, T, kf, slot_mask, status, maxseq, maxinv);
+      bk[u] = c[u] < T.n_comms ? (c[u] >> a.bshift) : 0u;
+      at[u] = atomicAdd(&s_off[bk[u]], 1u);
+    }
+    __syncthreads();
+    // this round's records per bucket -> where each bucket's run starts in the staging order
+    if (tid < CCLD_WAVE) {
+      const u32 cnt = tid < a.n_buckets ? s_off[tid] - s_start[tid] : 0u;
+      const u32 inc = wave_inclusive_sum(cnt);
+      s_pre[tid] = inc - cnt;
+      if (tid == CCLD_WAVE - 1) s_total = inc;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!on[u]) continue;
+      const u32 q = s_pre[bk[u]] + (at[u] - s_start[bk[u]]);
+      u64 p = (u64)a.tail + at[u];
+      if (p >= a.cap) p -= a.cap;
+      s_p[q] = (u32)p;
+      s_key[q] = key[u];
+      const u64 last = (u64)op[u] | ((u64)(a.seqno0 + (u32)(base + (u64)u * THREADS + tid)) << 32);   // op, arrival number
+      s_row[2 * q] = make_uint4((u32)te[u], (u32)((u64)te[u] >> 32), (u32)tx[u], (u32)((u64)tx[u] >> 32));
+      s_row[2 * q + 1] = make_uint4((u32)nb[u], (u32)(nb[u] >> 32), (u32)last, (u32)(last >> 32));
+    }
+    __syncthreads();
+    const u32 total = s_total;
+    for (u32 i = tid; i < 2 * total; i += THREADS) out_row[2ull * s_p[i >> 1] + (i & 1)] = s_row[i];
+    for (u32 q = tid; q < total; q += THREADS) out_key[s_p[q]] = s_key[q];
+    if (tid < a.n_buckets) s_start[tid] = s_off[tid];
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      r[u] = nr[u]; c[u] = nc[u]; sq[u] = nsq[u]; op[u] = nop[u]; nb[u] = nnb[u]; te[u] = nte[u]; tx[u] = ntx[u];
+    }
+  }
+  ingest_publish<THREADS>(status, maxseq, maxinv, s_status, s_max, s_inv, a.meta);
+}
+
+void launch_ingest(hipStream_t st, const IngestArgs& a_in, const DeviceTopology& T, const KeyFormat& kf) {
+  if (a_in.n == 0) return;
+  IngestArgs a = a_in;
   u64 g = (a.n + 255) / 256;
   if (g > INGEST_BLOCKS) g = INGEST_BLOCKS;
+  a.hist_split = 1;
   const size_t lds = sizeof(u32) * a.n_buckets;
-  // large batches over few enough ranks: half as many workgroups of twice the size, each with the
+  // large batches: one 1,024-thread workgroup per compute unit with the write-out regrouped in LDS, the
+  // membership rows in LDS too when they fit beside the staging area; four counting workgroups per
+  // placement workgroup
+  const bool staged = a.n >= (1u << 22) && a.n_buckets <= 64;
+  const size_t stage_bytes = (size_t)2048 * (32 + 8 + 4);
+  const bool staged_table = staged && T.rank_memb4 && (u64)T.n_ranks * 16 + stage_bytes <= 156 * 1024;
+  // otherwise, large batches over few enough ranks: half as many workgroups of twice the size, each with the
   // membership rows in LDS (two workgroups per compute unit)
-  const bool lds_table = T.rank_memb4 && (u64)T.n_ranks * 16 + lds <= 72 * 1024 && a.n >= (1u << 22);
-  if (lds_table) g = (g + 1) / 2;
-  hipLaunchKernelGGL(k_ingest_hist, dim3((u32)g), dim3(256), lds, st, a, T.n_comms);
-  hipLaunchKernelGGL(k_ingest_scan, dim3(a.n_buckets), dim3(256), 0, st, a.table, a.bucket_base, (u32)g);
+  const bool lds_table = !staged && T.rank_memb4 && (u64)T.n_ranks * 16 + lds <= 72 * 1024 && a.n >= (1u << 22);
+  if (staged) { g = 256; a.hist_split = 4; }
+  else if (lds_table) g = (g + 1) / 2;
+  const u64 unit = 256ull * a.hist_split;
+  a.chunk = ((a.n + g - 1) / g + unit - 1) / unit * unit;
+  const u32 g_hist = (u32)(g * a.hist_split);
+  hipLaunchKernelGGL(k_ingest_hist, dim3(g_hist), dim3(256), lds, st, a, T.n_comms);
+  hipLaunchKernelGGL(k_ingest_scan, dim3(a.n_buckets), dim3(256), 0, st, a.table, a.bucket_base, g_hist);
   launch_scan_tiles(st, a.bucket_base, a.n_buckets, a.scratch_total);
-  if (lds_table) {
-    static bool raised = false;       // more than 64 KB of dynamic LDS has to be asked for once
-    if (!raised) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_ingest<512, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-      raised = true;
-    }
-    hipLaunchKernelGGL((k_ingest<512, true>), dim3((u32)g), dim3(512), lds + (size_t)T.n_ranks * 16, st, a, T, kf);
+  static bool raised = false;       // more than 64 KB of dynamic LDS has to be asked for once
+  if (!raised) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_ingest<512, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_ingest_staged<1024, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_ingest_staged<1024, false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    raised = true;
   }
+  if (staged_table)
+    hipLaunchKernelGGL((k_ingest_staged<1024, true>), dim3((u32)g), dim3(1024), stage_bytes + (size_t)T.n_ranks * 16, st, a, T, kf);
+  else if (staged)
+    hipLaunchKernelGGL((k_ingest_staged<1024, false>), dim3((u32)g), dim3(1024), stage_bytes, st, a, T, kf);
+  else if (lds_table)
+    hipLaunchKernelGGL((k_ingest<512, true>), dim3((u32)g), dim3(512), lds + (size_t)T.n_ranks * 16, st, a, T, kf);
   else
     hipLaunchKernelGGL((k_ingest<256, false>), dim3((u32)g), dim3(256), lds, st, a, T, kf);
 }

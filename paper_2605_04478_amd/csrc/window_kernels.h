@@ -21,6 +21,8 @@ struct IngestArgs {
   uint32_t n_buckets;
   int bshift;                // bucket = comm >> bshift
   uint32_t seqno0;           // arrival number of the batch's first record
+  uint64_t chunk;            // records per placement workgroup (a multiple of 256 * hist_split)
+  uint32_t hist_split;       // counting workgroups per placement workgroup
 };
 constexpr uint32_t INGEST_BLOCKS = 1024;
 constexpr uint32_t INGEST_MAX_BUCKETS = 4096;
