@@ -88,3 +88,48 @@ def test_progress_rates_at_4096_ranks():
     mine = np.unique(o.pair["comm"][o.pair["rank"] == tr.slow_rank])
     assert len(mine) == 4 and all(g.comm["root"][c] == tr.slow_rank for c in mine)
     an.close()
+
+
+def test_large_batches_wrap_errors_and_many_ranks():
+    """Batches above four million records take the placement that regroups its write-out in LDS:
+    with more ranks than the LDS membership table holds, across the wrap of the circular window,
+    and with a bad record."""
+    from paper_2605_04478_amd import ccld
+    lay = tg.Layout3D(tp=8, pp=4, dp=144)                            # 4,608 ranks
+    tr = tg.generate(tg.config3(n_cycles=95, layout=lay)).shuffled(7)
+    assert tr.n > (1 << 22)
+    per = tr.n // 3 // lay.n_ranks * lay.n_ranks
+    now = int(tr.cols["t_exit"].max()) + 1
+    # one batch, all ranks
+    an = ccld.Analyzer(tr.topo, max_window_records=tr.n)
+    an.ingest(an.to_device(tr.cols))
+    g = an.analyze_window(now, n_records=tr.n, per_record=True)
+    o = orc.Oracle(tr.topo)
+    ref = o.analyze_window(tr.cols, now)
+    blame, order = an.rank_blame()
+    compare(g, ref, blame, order, what="large-one-batch")
+    # a bad record in the middle of the batch
+    bad = {k: v.copy() for k, v in tr.cols.items()}
+    bad["comm"][tr.n // 2] = tr.topo.n_comms
+    an.reset_window()
+    an.ingest(an.to_device(bad))
+    g = an.analyze_window(now, n_records=tr.n)
+    assert g.status == "E_UNKNOWN_COMM" == orc.Oracle(tr.topo).analyze_window(bad, now).status
+    an.close()
+    # two-batch window over a circular buffer that is not a multiple of the batch: the third batch wraps
+    big = tg.generate(tg.config3(n_cycles=830, layout=tg.Layout3D(tp=8, pp=4, dp=48))).shuffled(8)
+    nb = big.n // 3
+    assert nb > (1 << 22)
+    batches = [{k: v[i * nb:(i + 1) * nb] for k, v in big.cols.items()} for i in range(3)]
+    an = ccld.Analyzer(big.topo, max_window_records=2 * nb + 4099, max_batch_records=nb, window_batches=2)
+    o = orc.Oracle(big.topo, dict(window_batches=2))
+    now = int(big.cols["t_exit"].max()) + 1
+    for i, b in enumerate(batches):
+        an.ingest(an.to_device(b))
+        win = batches[max(0, i - 1): i + 1]
+        cols = {k: np.concatenate([w[k] for w in win]) for k in b}
+        g = an.analyze_window(now, n_records=2 * nb, per_record=True)
+        ref = o.analyze_window(cols, now)
+        blame, order = an.rank_blame()
+        compare(g, ref, blame, order, what=f"large-wrap{i}")
+    an.close()
