@@ -25,14 +25,16 @@ template <bool STREAM, class T> __device__ __forceinline__ T load_once(const T* 
   return STREAM ? __builtin_nontemporal_load(p) : *p;
 }
 
+__device__ __forceinline__ u64 squeeze_key(const KeySource& s, u64 k) {
+  if (s.squeeze) k = (s.hi_shift < 64 ? (k >> s.hi_shift) << s.lo_bits : 0ull) | ((k & s.lo_mask) - s.lo_sub);
+  return k;
+}
 template <bool STREAM>
 __device__ __forceinline__ u64 load_key(const KeySource& s, u32 j, u32* phys) {
   u32 p = s.head + j;                       // head < cap and j < cap <= 2^31: no wrap below 2^32
   if (p >= s.cap) p -= s.cap;
   *phys = p;
-  u64 k = load_once<STREAM>(s.key + p);
-  if (s.squeeze) k = (s.hi_shift < 64 ? (k >> s.hi_shift) << s.lo_bits : 0ull) | ((k & s.lo_mask) - s.lo_sub);
-  return k;
+  return squeeze_key(s, load_once<STREAM>(s.key + p));
 }
 
 // ---- per-tile digit histogram --------------------------------------------------------------
@@ -52,15 +54,24 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, cons
   for (int t = 0; t < HIST_TILES; ++t) {
     const u32 base = (tile0 + t) * SORT_TILE;
     if (tile0 + t >= n_tiles) continue;
-    if (!FIRST && base + SORT_TILE <= n) {
-      // full tile of a plain array: 16-byte loads, two keys per lane
-      const ulonglong2* __restrict__ in2 = reinterpret_cast<const ulonglong2*>(key_in + base);
+    // full tile of consecutive, 16-byte aligned keys (a plain array, or a stretch of the circular
+    // window that does not wrap): 16-byte loads, two keys per lane
+    u32 p0 = base;
+    bool plain = base + SORT_TILE <= n;
+    if (FIRST) {
+      p0 = src.head + base;
+      if (p0 >= src.cap) p0 -= src.cap;
+      plain = plain && p0 + SORT_TILE <= src.cap && (p0 & 1) == 0;
+    }
+    if (plain) {
+      const ulonglong2* __restrict__ in2 = reinterpret_cast<const ulonglong2*>((FIRST ? src.key : key_in) + p0);
       ulonglong2 kk[SORT_ITEMS / 2];
 #pragma unroll
       for (int it = 0; it < SORT_ITEMS / 2; ++it) {
         typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
         const u64x2 t2 = load_once<STREAM>(reinterpret_cast<const u64x2*>(in2 + it * SORT_THREADS + tid));
         kk[it].x = t2.x; kk[it].y = t2.y;
+        if (FIRST) { kk[it].x = squeeze_key(src, kk[it].x); kk[it].y = squeeze_key(src, kk[it].y); }
       }
 #pragma unroll
       for (int it = 0; it < SORT_ITEMS / 2; ++it) {
