@@ -479,7 +479,8 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
     KeySource bs; bs.key = bk; bs.head = 0; bs.cap = n_flag; bs.squeeze = 0; bs.hi_shift = 0; bs.lo_bits = 0; bs.lo_mask = 0; bs.lo_sub = 0;
     const int r2 = radix_sort_pairs(st, bs, n_flag, sb2, c->rank_bits);
     if (r2 < 0) return o->status = CCLD_E_HIP;
-    launch_blame_reduce(st, sb2.key[r2], sb2.idx[r2], n_flag, c->flag_pos, sa.rec_flag, c->flag_lag, c->cap, n_ranks, c->blame);
+    launch_blame_reduce(st, sb2.key[r2], sb2.idx[r2], n_flag, c->flag_pos, sa.rec_flag, c->flag_lag, c->cap, n_ranks,
+                        c->blame_list, c->blame);
     c->prof.end(CCLD_PROF_BLAME);
   }
 

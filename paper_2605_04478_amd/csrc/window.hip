@@ -19,6 +19,14 @@ __device__ __forceinline__ u64 atomic_add_u64(u64* p, u64 v) {
 __global__ __launch_bounds__(256) void k_fill_u64(u64* p, u64 n, u64 v) {
   for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < n; i += (u64)gridDim.x * 256) p[i] = v;
 }
+__global__ __launch_bounds__(256) void k_fill_u32(u32* p, u64 n, u32 v) {
+  for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < n; i += (u64)gridDim.x * 256) p[i] = v;
+}
+static void launch_fill_u32(hipStream_t st, uint32_t* p, uint64_t n, uint32_t v) {
+  if (n == 0) return;
+  u32 g = (u32)((n + 255) / 256); if (g > 4096) g = 4096;
+  hipLaunchKernelGGL(k_fill_u32, dim3(g), dim3(256), 0, st, p, n, v);
+}
 void launch_fill_u64(hipStream_t st, uint64_t* p, uint64_t n, uint64_t v) {
   if (n == 0) return;
   u32 g = (u32)((n + 255) / 256); if (g > 4096) g = 4096;
@@ -565,21 +573,26 @@ void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag
     hipLaunchKernelGGL(k_blame_keys, dim3((n_flag + 255) / 256), dim3(256), 0, st, key, flag_pos, n_flag, sf,
                        T.member_off, T.members_sorted, out_key);
 }
-// one workgroup per rank: the rank's run in the sorted flag keys is summed by 256 threads
-__global__ __launch_bounds__(256) void k_blame_reduce(const u64* __restrict__ skey, const u32* __restrict__ sidx,
-                                                      u32 n_flag, const u32* __restrict__ flag_pos,
+// ends of every rank's run in the sorted flag keys: run[r] = first, run[n_ranks + r] = one past the
+// last (both zero for a rank without a flag; the array is cleared before)
+__global__ __launch_bounds__(256) void k_blame_runs(const u64* __restrict__ skey, u32 n_flag, u32 n_ranks,
+                                                    u32* __restrict__ run) {
+  const u32 q = blockIdx.x * 256 + threadIdx.x;
+  if (q >= n_flag) return;
+  const u64 r = skey[q];
+  if (q == 0 || skey[q - 1] != r) run[r] = q;
+  if (q + 1 == n_flag || skey[q + 1] != r) run[n_ranks + r] = q + 1;
+}
+// one workgroup per rank: the rank's run in the sorted flag keys is summed by 256 threads, four flags
+// per thread in flight (a faulty rank's run is tens of thousands of flags long)
+__global__ __launch_bounds__(256) void k_blame_reduce(const u32* __restrict__ run, const u32* __restrict__ sidx,
+                                                      const u32* __restrict__ flag_pos,
                                                       const uint8_t* __restrict__ rec_flag,
                                                       const i64* __restrict__ flag_lag, u64 cap_n, u32 n_ranks,
                                                       i64* __restrict__ blame) {
   __shared__ unsigned long long s_acc[4];
   const u32 r = blockIdx.x, tid = threadIdx.x;
-  // run of this rank in the sorted keys: [lower_bound(r), lower_bound(r + 1))
-  u32 lo = 0, hi = n_flag;
-  while (lo < hi) { const u32 m = (lo + hi) / 2; if (skey[m] < (u64)r) lo = m + 1; else hi = m; }
-  const u32 first = lo;
-  hi = n_flag;
-  while (lo < hi) { const u32 m = (lo + hi) / 2; if (skey[m] <= (u64)r) lo = m + 1; else hi = m; }
-  const u32 last = lo;
+  const u32 first = run[r], last = run[n_ranks + r];
   if (first == last) {
     if (tid < 4) blame[(u64)tid * n_ranks + r] = 0;     // columns 0..3 are the four flag sums
     return;
@@ -587,11 +600,21 @@ __global__ __launch_bounds__(256) void k_blame_reduce(const u64* __restrict__ sk
   if (tid < 4) s_acc[tid] = 0;
   __syncthreads();
   u64 ne = 0, nx = 0, se = 0, sx = 0;
-  for (u32 q = first + tid; q < last; q += 256) {
-    const u32 j = flag_pos[sidx[q]];
-    const u32 f = rec_flag[j];
-    if (f & CCLD_FLAG_LATE_ENTER) { ne += 1; se += (u64)flag_lag[j]; }
-    if (f & CCLD_FLAG_LATE_EXIT) { nx += 1; sx += (u64)flag_lag[cap_n + j]; }
+  for (u32 q0 = first + tid; q0 < last; q0 += 256 * 4) {
+    u32 j[4], f[4];
+    i64 le[4], lx[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) j[u] = q0 + u * 256 < last ? flag_pos[sidx[q0 + u * 256]] : 0xFFFFFFFFu;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      f[u] = 0; le[u] = 0; lx[u] = 0;
+      if (j[u] != 0xFFFFFFFFu) { f[u] = rec_flag[j[u]]; le[u] = flag_lag[j[u]]; lx[u] = flag_lag[cap_n + j[u]]; }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (f[u] & CCLD_FLAG_LATE_ENTER) { ne += 1; se += (u64)le[u]; }
+      if (f[u] & CCLD_FLAG_LATE_EXIT) { nx += 1; sx += (u64)lx[u]; }
+    }
   }
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) {
@@ -610,9 +633,11 @@ static_assert(CCLD_BLM_N_LATE_ENTER == 0 && CCLD_BLM_N_LATE_EXIT == 1 && CCLD_BL
               CCLD_BLM_SUM_LAG_EXIT == 3, "blame column order");
 void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* sidx, uint32_t n_flag,
                          const uint32_t* flag_pos, const uint8_t* rec_flag, const int64_t* flag_lag,
-                         uint64_t cap_n, uint32_t n_ranks, int64_t* blame) {
-  hipLaunchKernelGGL(k_blame_reduce, dim3(n_ranks), dim3(256), 0, st, skey, sidx, n_flag, flag_pos,
-                     rec_flag, flag_lag, cap_n, n_ranks, blame);
+                         uint64_t cap_n, uint32_t n_ranks, uint32_t* run, int64_t* blame) {
+  launch_fill_u32(st, run, 2ull * n_ranks, 0u);
+  hipLaunchKernelGGL(k_blame_runs, dim3((n_flag + 255) / 256), dim3(256), 0, st, skey, n_flag, n_ranks, run);
+  hipLaunchKernelGGL(k_blame_reduce, dim3(n_ranks), dim3(256), 0, st, (const u32*)run, sidx, flag_pos, rec_flag,
+                     flag_lag, cap_n, n_ranks, blame);
 }
 
 // order[] = ranks by (flags descending, summed lag descending, rank ascending).  Ranks with any

@@ -77,7 +77,7 @@ void launch_blame_keys(hipStream_t st, const uint64_t* key, const uint32_t* flag
                        const SqueezedFormat& sf, const DeviceTopology& T, uint64_t* out_key);
 void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* sidx, uint32_t n_flag,
                          const uint32_t* flag_pos, const uint8_t* rec_flag, const int64_t* flag_lag,
-                         uint64_t cap_n, uint32_t n_ranks, int64_t* blame);
+                         uint64_t cap_n, uint32_t n_ranks, uint32_t* run /* [2 n_ranks] scratch */, int64_t* blame);
 void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, uint32_t* lists,
                         uint32_t* tile_counts, uint64_t* counters, uint32_t* order);
 
