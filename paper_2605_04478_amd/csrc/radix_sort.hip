@@ -122,7 +122,7 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scan(u32* __restrict__ t
 // shift addresses the digit inside the word the kernel ranks: the key itself, or the packed word
 // (key << ibits | index) when either side is packed.
 template <int IN, int OUT, bool STREAM>
-__global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, const u64* __restrict__ key_in,
+__global__ __launch_bounds__(SORT_THREADS) __attribute__((amdgpu_waves_per_eu(8))) void k_radix_scatter(KeySource src, const u64* __restrict__ key_in,
                                                                 const u32* __restrict__ idx_in,
                                                                 u64* __restrict__ key_out, u32* __restrict__ idx_out,
                                                                 const u32* __restrict__ table,
@@ -130,7 +130,9 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, c
                                                                 int shift, int nbits, int ibits) {
   constexpr int NW = SORT_THREADS / CCLD_WAVE;
   constexpr bool PACKED = (IN == IN_PACKED) || (OUT == OUT_PACKED);   // one word per element inside the kernel
-  __shared__ u32 s_cnt[NW][SORT_RADIX];   // per-wavefront digit counters, then each wavefront's base inside the digit
+  // per-wavefront digit counters, then each wavefront's base inside the digit (at most 4,096: 16 bits, which
+  // keeps the packed variants within 40 KB of LDS, four workgroups per compute unit)
+  __shared__ unsigned short s_cnt[NW][SORT_RADIX];
   __shared__ u32 s_dstart[SORT_RADIX];    // first tile-local position of each digit
   __shared__ u32 s_gbase[SORT_RADIX];     // global position of tile-local position 0 of each digit (minus dstart)
   __shared__ u32 s_wave[NW];
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, c
     const u32 below = mbcnt64(same), cnt = (u32)__popcll(same);
     const u32 old = s_cnt[wave][d];
     __builtin_amdgcn_wave_barrier();
-    if (below == cnt - 1) s_cnt[wave][d] = old + cnt;
+    if (below == cnt - 1) s_cnt[wave][d] = (unsigned short)(old + cnt);
     __builtin_amdgcn_wave_barrier();
     pre[it] = old + below;
   }
@@ -201,7 +203,7 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scatter(KeySource src, c
     u32 gtot = 0;
     if (tid < SORT_RADIX) {
 #pragma unroll
-      for (int w = 0; w < NW; ++w) { u32 c = s_cnt[w][tid]; s_cnt[w][tid] = tot; tot += c; }
+      for (int w = 0; w < NW; ++w) { u32 c = s_cnt[w][tid]; s_cnt[w][tid] = (unsigned short)tot; tot += c; }
       gtot = tid <= dmask ? totals[tid] : 0u;
     }
     u32 t0, t1;
