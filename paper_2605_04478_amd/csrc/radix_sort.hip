@@ -122,7 +122,8 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_scan(u32* __restrict__ t
 // shift addresses the digit inside the word the kernel ranks: the key itself, or the packed word
 // (key << ibits | index) when either side is packed.
 template <int IN, int OUT, bool STREAM>
-__global__ __launch_bounds__(SORT_THREADS) __attribute__((amdgpu_waves_per_eu(8))) void k_radix_scatter(KeySource src, const u64* __restrict__ key_in,
+__global__ __launch_bounds__(SORT_THREADS)
+__attribute__((amdgpu_waves_per_eu(((IN == IN_PACKED) || (OUT == OUT_PACKED)) ? 8 : 4))) void k_radix_scatter(KeySource src, const u64* __restrict__ key_in,
                                                                 const u32* __restrict__ idx_in,
                                                                 u64* __restrict__ key_out, u32* __restrict__ idx_out,
                                                                 const u32* __restrict__ table,
