@@ -210,6 +210,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   c->stream = (hipStream_t)hip_stream;
   c->cap = max_window_records; c->batch_cap = max_batch_records; c->snap_cap = max_snapshot_rows;
   c->kf.mb = mb; c->kf.cb = cb; c->kf.sb = 64 - mb - cb;
+  c->max_comm_size = max_size;
   c->rank_bits = bits_for_host(topo->n_ranks - 1);
   c->head = 0; c->count = 0; c->next_slot = 0; c->total_ingested = 0;
   // Communicator buckets of the window placement: enough of them that one bucket's payload rows
@@ -439,7 +440,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   sa.lag_e = o->lag_enter; sa.lag_x = o->lag_exit; sa.flag_lag = c->flag_lag; sa.cap_n = c->cap;
   sa.big_list = c->big_list; sa.big_ex = c->big_ex; sa.counters = c->counters;
   sa.lag_floor = c->p.lag_floor_ns; sa.kmad_num = c->p.kmad_num; sa.kmad_den = c->p.kmad_den;
-  sa.barrier_bytes = c->p.barrier_bytes;
+  sa.barrier_bytes = c->p.barrier_bytes; sa.max_size = c->max_comm_size;
   const uint32_t seg_tiles = (n + SEG_TILE - 1) / SEG_TILE;
   c->prof.begin();
   launch_keys_pass(st, skey, n, c->sf, c->topo, c->blame, c->tile_heads, c->counters);

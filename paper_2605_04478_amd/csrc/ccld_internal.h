@@ -129,6 +129,7 @@ struct ccld_ctx {
   uint32_t* alert_ncand;              // [cap + 1]
   ccld::GroupState* gstate;           // [n_comms][GROUP_SLOTS]
   uint64_t* counters;                 // [CNT_COUNT] device
+  uint32_t max_comm_size;             // members of the largest communicator
   uint64_t sort_cap;                  // items the sort buffers hold: max(window records, communicator members)
   uint64_t* h_pinned;                 // pinned host staging
   // staging for host-resident batches

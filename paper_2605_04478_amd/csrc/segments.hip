@@ -727,12 +727,16 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
 void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
   if (a.n == 0) return;
   hipLaunchKernelGGL(k_seg_wave, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
+  // a collective has at most as many records as its communicator has members (a longer one holds a
+  // duplicate, which ends the analysis with an error): size classes that cannot occur are not launched
+  const uint32_t m = a.max_size;
+  if (m <= (uint32_t)SEG_WAVE_MAX) return;
   hipLaunchKernelGGL(k_seg_lengths, dim3(1024), dim3(SEG_THREADS), 0, st, a);
   hipLaunchKernelGGL(k_seg_multi<2>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
-  hipLaunchKernelGGL(k_seg_multi<4>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
-  hipLaunchKernelGGL(k_seg_multi<8>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
-  hipLaunchKernelGGL(k_seg_team, dim3(1024), dim3(SEG_THREADS), 0, st, a);
-  hipLaunchKernelGGL(k_seg_big, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+  if (m > 128) hipLaunchKernelGGL(k_seg_multi<4>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+  if (m > 256) hipLaunchKernelGGL(k_seg_multi<8>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+  if (m > (uint32_t)SEG_MULTI_MAX) hipLaunchKernelGGL(k_seg_team, dim3(1024), dim3(SEG_THREADS), 0, st, a);
+  if (m > (uint32_t)SEG_TEAM_MAX) hipLaunchKernelGGL(k_seg_big, dim3(2048), dim3(SEG_THREADS), 0, st, a);
 }
 
 }  // namespace ccld

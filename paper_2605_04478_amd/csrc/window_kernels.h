@@ -49,6 +49,7 @@ struct SegArgs {
   uint64_t* counters;
   int64_t lag_floor;
   uint32_t kmad_num, kmad_den, barrier_bytes;
+  uint32_t max_size;         // members of the largest communicator (host-side: which size classes can occur)
 };
 void launch_scan_tiles(hipStream_t st, uint32_t* counts, uint32_t n_tiles, uint64_t* total_out);
 void launch_seg_analyze(hipStream_t st, const SegArgs& a);        // small collectives, then the oversized ones
