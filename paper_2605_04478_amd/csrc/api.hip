@@ -68,7 +68,6 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->flag_lag = w.take<int64_t>(2 * N);
   c->big_list = w.take<uint32_t>(3 * (N / 65 + 2));
   c->big_ex = w.take<int64_t>(2 * N);
-  c->blame = w.take<int64_t>((uint64_t)CCLD_BLM_NCOL * n_ranks);
   c->blame_list = w.take<uint32_t>(2ull * n_ranks);
   c->blame_tiles = w.take<uint32_t>(n_ranks / SEL_TILE + 3);
   c->usable_list = w.take<uint32_t>(N);
@@ -76,7 +75,9 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->alert_list = w.take<uint32_t>(NT);
   c->alert_ncand = w.take<uint32_t>(N + 2);
   c->gstate = w.take<GroupState>((uint64_t)n_comms * GROUP_SLOTS);
+  // the counters and the blame table are cleared together at the start of every analysis
   c->counters = w.take<uint64_t>(CNT_COUNT);
+  c->blame = w.take<int64_t>((uint64_t)CCLD_BLM_NCOL * n_ranks);
   c->stage = w.take<uint8_t>(B * 48);
   // hang location
   const uint64_t SN = std::max<uint64_t>(c->snap_cap, 1);
@@ -332,7 +333,7 @@ ccld_status ccld_ingest(ccld_ctx* c, const ccld_records* b, uint64_t n) {
   std::memset(&a, 0, sizeof(a));
   const uint32_t slot = c->next_slot;
   a.meta = c->batch_meta + slot;
-  HIP_TRY(hipMemsetAsync(a.meta, 0, sizeof(BatchMeta), c->stream));
+  if (n == 0) HIP_TRY(hipMemsetAsync(a.meta, 0, sizeof(BatchMeta), c->stream));     // otherwise the counting kernel clears it
   if (b->on_device) {
     a.rank = b->rank; a.comm = b->comm; a.seq = b->seq; a.op = b->op; a.bytes = b->bytes;
     a.t_enter = b->t_enter; a.t_exit = b->t_exit;
@@ -405,8 +406,17 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   }
   if (bits) return o->status = data_status(bits);
   o->n_records = n;
-  HIP_TRY(hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st));
-  HIP_TRY(hipMemsetAsync(c->blame, 0, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)n_ranks, st));
+  {
+    const size_t blame_bytes = sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)n_ranks;
+    uint8_t* c0 = reinterpret_cast<uint8_t*>(c->counters);
+    uint8_t* b0 = reinterpret_cast<uint8_t*>(c->blame);
+    if (b0 >= c0 && (size_t)(b0 - c0) < 4096) {        // adjacent in the workspace: one fill
+      HIP_TRY(hipMemsetAsync(c0, 0, (size_t)(b0 - c0) + blame_bytes, st));
+    } else {
+      HIP_TRY(hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st));
+      HIP_TRY(hipMemsetAsync(c->blame, 0, blame_bytes, st));
+    }
+  }
   c->last_n = n;
   if (n == 0) { HIP_TRY(hipStreamSynchronize(st)); c->blame_valid = true; return o->status; }
 

@@ -41,6 +41,8 @@ void launch_fill_u64(hipStream_t st, uint64_t* p, uint64_t n, uint64_t v) {
 __global__ __launch_bounds__(256) void k_ingest_hist(IngestArgs a, u32 n_comms) {
   extern __shared__ u32 s_cnt[];
   for (u32 b = threadIdx.x; b < a.n_buckets; b += 256) s_cnt[b] = 0;
+  // the batch's header starts from zero (the placement kernel, next on the stream, accumulates into it)
+  if (blockIdx.x == 0 && threadIdx.x == 0) { a.meta->status = 0; a.meta->max_seq = 0; a.meta->max_inv_seq = 0; a.meta->pad = 0; }
   __syncthreads();
   const u64 chunk = a.chunk / a.hist_split;
   const u64 i_end = (chunk * (blockIdx.x + 1)) < a.n ? chunk * (blockIdx.x + 1) : a.n;
