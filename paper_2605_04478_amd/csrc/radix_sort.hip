@@ -156,7 +156,9 @@ __attribute__((amdgpu_waves_per_eu(((IN == IN_PACKED) || (OUT == OUT_PACKED)) ? 
   // wavefront w owns tile elements [w*64*ITEMS, (w+1)*64*ITEMS); item `it` of lane l is element
   // w*64*ITEMS + it*64 + l, so (wavefront, item, lane) order is input order
   u64 k[SORT_ITEMS];
-  u32 v[SORT_ITEMS], dig[SORT_ITEMS], pre[SORT_ITEMS];
+  u32 v[SORT_ITEMS], pre[SORT_ITEMS];
+  // the digit is recomputed from the key where it is needed (eight registers fewer)
+  auto digit_of = [&](u64 key) -> u32 { return (u32)(key >> shift) & dmask; };
 #pragma unroll
   for (int it = 0; it < SORT_ITEMS; ++it) {
     u32 e = wave * (CCLD_WAVE * SORT_ITEMS) + it * CCLD_WAVE + lane;
@@ -170,16 +172,15 @@ __attribute__((amdgpu_waves_per_eu(((IN == IN_PACKED) || (OUT == OUT_PACKED)) ? 
       } else {
         k[it] = load_once<STREAM>(key_in + base + e);
       }
-      dig[it] = (u32)(k[it] >> shift) & dmask;
     } else {
-      k[it] = 0; dig[it] = dmask;   // padding sorts after every real key of the last digit
+      k[it] = ~0ull;                // padding: the last digit, after every real key of it
     }
   }
   __syncthreads();
 
 #pragma unroll
   for (int it = 0; it < SORT_ITEMS; ++it) {
-    const u32 d = dig[it];
+    const u32 d = digit_of(k[it]);
     u64 same = ~0ull;                      // lanes of this wavefront holding the same digit
 #pragma unroll
     for (int b = 0; b < SORT_RBITS; ++b) {
@@ -220,7 +221,7 @@ __attribute__((amdgpu_waves_per_eu(((IN == IN_PACKED) || (OUT == OUT_PACKED)) ? 
 
 #pragma unroll
   for (int it = 0; it < SORT_ITEMS; ++it) {
-    const u32 d = dig[it];
+    const u32 d = digit_of(k[it]);
     const u32 pos = s_dstart[d] + s_cnt[wave][d] + pre[it];
     s_key[pos] = k[it];
     if (!PACKED) s_idx[pos] = v[it];
