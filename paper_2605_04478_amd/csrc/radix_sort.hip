@@ -99,21 +99,46 @@ __global__ __launch_bounds__(SORT_THREADS) void k_radix_hist(KeySource src, cons
 // ---- exclusive scan of each digit's row of tile counts ------------------------------------
 // one workgroup per digit; every thread scans SCAN_PER consecutive tiles serially
 constexpr int SCAN_PER = 8;
+__device__ __forceinline__ void scan_row_load(const u32* row, u32 i0, u32 n, bool vec, u32 (&v)[SCAN_PER]) {
+  if (vec && i0 + SCAN_PER <= n) {
+    const uint4 a = *reinterpret_cast<const uint4*>(row + i0), b = *reinterpret_cast<const uint4*>(row + i0 + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  } else {
+#pragma unroll
+    for (int k = 0; k < SCAN_PER; ++k) v[k] = (i0 + k) < n ? row[i0 + k] : 0u;
+  }
+}
 __global__ __launch_bounds__(SORT_THREADS) void k_radix_scan(u32* __restrict__ table, u32* __restrict__ totals,
                                                              u32 n_tiles) {
+  static_assert(SCAN_PER == 8, "two 16-byte pieces per thread");
   __shared__ u32 s_wave[SORT_THREADS / CCLD_WAVE];
   u32* row = table + (u64)blockIdx.x * n_tiles;
+  const bool vec = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
   u32 carry = 0;
+  u32 v[SCAN_PER], nv[SCAN_PER];
+  scan_row_load(row, threadIdx.x * SCAN_PER, n_tiles, vec, v);
   for (u32 base = 0; base < n_tiles; base += SORT_THREADS * SCAN_PER) {
     const u32 i0 = base + threadIdx.x * SCAN_PER;
-    u32 v[SCAN_PER], sum = 0;
+    // the next round's counts are on their way while this round is scanned and stored
+    scan_row_load(row, i0 + SORT_THREADS * SCAN_PER, n_tiles, vec, nv);
+    u32 sum = 0;
 #pragma unroll
-    for (int k = 0; k < SCAN_PER; ++k) { v[k] = (i0 + k) < n_tiles ? row[i0 + k] : 0u; sum += v[k]; }
+    for (int k = 0; k < SCAN_PER; ++k) sum += v[k];
     u32 tot;
     u32 ex = carry + block_exclusive_sum<SORT_THREADS>(sum, s_wave, &tot);
+    if (vec && i0 + SCAN_PER <= n_tiles) {
+      u32 o[SCAN_PER];
 #pragma unroll
-    for (int k = 0; k < SCAN_PER; ++k) { if ((i0 + k) < n_tiles) row[i0 + k] = ex; ex += v[k]; }
+      for (int k = 0; k < SCAN_PER; ++k) { o[k] = ex; ex += v[k]; }
+      *reinterpret_cast<uint4*>(row + i0) = make_uint4(o[0], o[1], o[2], o[3]);
+      *reinterpret_cast<uint4*>(row + i0 + 4) = make_uint4(o[4], o[5], o[6], o[7]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < SCAN_PER; ++k) { if ((i0 + k) < n_tiles) row[i0 + k] = ex; ex += v[k]; }
+    }
     carry += tot;
+#pragma unroll
+    for (int k = 0; k < SCAN_PER; ++k) v[k] = nv[k];
   }
   if (threadIdx.x == 0) totals[blockIdx.x] = carry;
 }
