@@ -182,6 +182,13 @@ __attribute__((amdgpu_waves_per_eu(((IN == IN_PACKED) || (OUT == OUT_PACKED)) ? 
   // w*64*ITEMS + it*64 + l, so (wavefront, item, lane) order is input order
   u64 k[SORT_ITEMS];
   u32 v[SORT_ITEMS], pre[SORT_ITEMS];
+  u32 src_p0 = 0;
+  bool src_plain = false;
+  if (IN == IN_SOURCE) {
+    src_p0 = src.head + base;
+    if (src_p0 >= src.cap) src_p0 -= src.cap;
+    src_plain = src_p0 + SORT_TILE <= src.cap;
+  }
   // the digit is recomputed from the key where it is needed (eight registers fewer)
   auto digit_of = [&](u64 key) -> u32 { return (u32)(key >> shift) & dmask; };
 #pragma unroll
@@ -190,7 +197,12 @@ __attribute__((amdgpu_waves_per_eu(((IN == IN_PACKED) || (OUT == OUT_PACKED)) ? 
     v[it] = 0;
     if (e < valid) {
       if (IN == IN_SOURCE) {
-        k[it] = load_key<STREAM>(src, base + e, &v[it]);
+        if (src_plain) {      // the tile does not cross the end of the circular window
+          v[it] = src_p0 + e;
+          k[it] = squeeze_key(src, load_once<STREAM>(src.key + src_p0 + e));
+        } else {
+          k[it] = load_key<STREAM>(src, base + e, &v[it]);
+        }
         if (PACKED) k[it] = (k[it] << ibits) | v[it];
       } else if (IN == IN_PAIR) {
         k[it] = load_once<STREAM>(key_in + base + e); v[it] = load_once<STREAM>(idx_in + base + e);
