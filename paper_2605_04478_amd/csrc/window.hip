@@ -751,9 +751,13 @@ __global__ __launch_bounds__(T) void k_group_eval(GroupArgs a, const u64* __rest
   // rounds not yet visited by Eq. 1 form a suffix (ascending operation counters)
   // (ascending counters: compare the last round first; a fully visited group needs no search)
   const bool any_new = seq_of(e - 1) + 1 > g0.baselined_wm;
-  if (any_new)
+  if (any_new) {
+    // a suffix: the first hit of a thread's ascending walk is its smallest, one atomic per thread
+    u32 mine = e;
     for (u32 i = f + tid; i < e; i += T)
-      if (seq_of(i) + 1 > g0.baselined_wm) atomicMin(&s_i0, i);
+      if (seq_of(i) + 1 > g0.baselined_wm) { mine = i; break; }
+    if (mine < e) atomicMin(&s_i0, mine);
+  }
   // Eq. 2 needs the largest range; the first rounds of every thread stay in registers for the
   // second look below
   constexpr int KEEP = 4;
