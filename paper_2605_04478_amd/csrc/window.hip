@@ -862,7 +862,7 @@ __global__ __launch_bounds__(T) void k_group_eval(GroupArgs a, const u64* __rest
 void launch_group_eval(hipStream_t st, const GroupArgs& a, const uint64_t* skey, const uint32_t* sidx,
                        uint32_t n_usable, const uint32_t* group_first, uint32_t n_group) {
   if (!n_group) return;
-  if (n_usable / n_group < 128)
+  if (n_usable / n_group < 1024)     // short groups: the dependent lookups of many groups overlap
     hipLaunchKernelGGL(k_group_eval<64>, dim3(n_group), dim3(64), 0, st, a, skey, sidx, n_usable, group_first, n_group);
   else
     hipLaunchKernelGGL(k_group_eval<256>, dim3(n_group), dim3(256), 0, st, a, skey, sidx, n_usable, group_first, n_group);
