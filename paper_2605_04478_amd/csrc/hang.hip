@@ -52,30 +52,56 @@ __device__ __forceinline__ int slot_of(const DeviceTopology& T, u32 c, u32 r) {
 
 // ---- place every row in its cell ------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_hang_place(HangArgs a) {
+  constexpr int U = 4;               // rows per thread in flight
   u64 status = 0;
   const uint4* __restrict__ memb4 = reinterpret_cast<const uint4*>(a.T.rank_memb4);
   const u32 mmask = a.mb < 32 ? (1u << a.mb) - 1 : ~0u;
-  for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < a.n_rows; i += (u64)gridDim.x * 256) {
-    const u32 c = a.comm[i], r = a.rank[i], ch = a.channel[i], s = a.snap[i];
-    if (c >= a.T.n_comms) { status |= DS_UNKNOWN_COMM; continue; }
-    int slot = -1;
-    if (r < a.T.n_ranks) {
-      if (memb4) {      // the rank's packed (communicator, position among sorted members) words
-        const uint4 m = memb4[r];
-        const u32 w = c == (m.x >> a.mb) ? m.x : c == (m.y >> a.mb) ? m.y : c == (m.z >> a.mb) ? m.z : m.w;
-        if (c == (w >> a.mb)) slot = (int)a.T.sorted_slot[a.T.member_off[c] + (w & mmask)];
-      } else {
-        slot = slot_of(a.T, c, r);
+  ulonglong2* __restrict__ cell2 = reinterpret_cast<ulonglong2*>(a.cell);
+  const u64 stride = (u64)gridDim.x * 256;
+  for (u64 i0 = (u64)blockIdx.x * 256 + threadIdx.x; i0 < a.n_rows; i0 += stride * U) {
+    u32 c[U], r[U], ch[U], sn[U], se[U], rv[U];
+    u64 sq[U];
+    bool on[U];
+    // the seven columns are read once: streaming loads
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u64 i = i0 + stride * u;
+      on[u] = i < a.n_rows;
+      if (on[u]) {
+        c[u] = __builtin_nontemporal_load(a.comm + i); r[u] = __builtin_nontemporal_load(a.rank + i);
+        ch[u] = __builtin_nontemporal_load(a.channel + i); sn[u] = __builtin_nontemporal_load(a.snap + i);
+        sq[u] = __builtin_nontemporal_load(a.seq_posted + i);
+        se[u] = __builtin_nontemporal_load(a.sent + i); rv[u] = __builtin_nontemporal_load(a.recv + i);
       }
     }
-    if (slot < 0) { status |= DS_NOT_MEMBER; continue; }
-    if (ch >= a.n_ch || s >= a.n_snap) { status |= DS_RANGE; continue; }
-    const u64 k = (((u64)a.T.member_off[c] + (u32)slot) * a.n_ch + ch) * a.n_snap + s;
-    a.cell[2 * k] = a.seq_posted[i];
-    a.cell[2 * k + 1] = (u64)a.sent[i] | ((u64)a.recv[i] << 32);
-    // presence bitmap (one bit per cell: small enough to stay in cache); a bit already set is a duplicate
-    const u32 bit = 1u << (k & 31);
-    if (atomicOr(&a.cnt[k >> 5], bit) & bit) status |= DS_DUPLICATE;
+    uint4 m[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      m[u] = make_uint4(~0u, ~0u, ~0u, ~0u);
+      if (on[u] && memb4 && r[u] < a.T.n_ranks) m[u] = memb4[r[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!on[u]) continue;
+      if (c[u] >= a.T.n_comms) { status |= DS_UNKNOWN_COMM; continue; }
+      int slot = -1;
+      if (r[u] < a.T.n_ranks) {
+        if (memb4) {      // the rank's packed (communicator, position among sorted members) words
+          const u32 w = c[u] == (m[u].x >> a.mb) ? m[u].x : c[u] == (m[u].y >> a.mb) ? m[u].y
+                      : c[u] == (m[u].z >> a.mb) ? m[u].z : m[u].w;
+          if (c[u] == (w >> a.mb)) slot = (int)a.T.sorted_slot[a.T.member_off[c[u]] + (w & mmask)];
+        } else {
+          slot = slot_of(a.T, c[u], r[u]);
+        }
+      }
+      if (slot < 0) { status |= DS_NOT_MEMBER; continue; }
+      if (ch[u] >= a.n_ch || sn[u] >= a.n_snap) { status |= DS_RANGE; continue; }
+      const u64 k = (((u64)a.T.member_off[c[u]] + (u32)slot) * a.n_ch + ch[u]) * a.n_snap + sn[u];
+      cell2[k] = make_ulonglong2(sq[u], (u64)se[u] | ((u64)rv[u] << 32));
+      // presence bitmap (one bit per cell: small enough to stay in cache); a bit already set is a duplicate
+      const u32 bit = 1u << (k & 31);
+      if (atomicOr(&a.cnt[k >> 5], bit) & bit) status |= DS_DUPLICATE;
+    }
   }
   u64 st = status;
 #pragma unroll
