@@ -176,7 +176,14 @@ __global__ __launch_bounds__(256) void k_hang_comm(HangArgs a) {
   const bool tree = a.T.algo[c] == CCLD_ALGO_TREE;
   if (tid == 0) { s_seqmax = 0; s_minsum = ~0ull; s_minrecv = ~0ull; s_worst = 0; s_flags = 0; s_best = 0xFFFFFFFFu; s_ncand = 0; }
   __syncthreads();
-  for (u32 q = tid; q < n; q += 256) atomicMax(&s_seqmax, (unsigned long long)PAIR(a, CCLD_HPAIR_SEQ, off + q));
+  {     // every thread reduces its own members first: one LDS atomic per thread, not per member
+    unsigned long long mine = 0;
+    for (u32 q = tid; q < n; q += 256) {
+      const unsigned long long v = (unsigned long long)PAIR(a, CCLD_HPAIR_SEQ, off + q);
+      mine = v > mine ? v : mine;
+    }
+    if (tid < n) atomicMax(&s_seqmax, mine);
+  }
   __syncthreads();
   const u64 seq_max = s_seqmax;
   // depth of a slot in the tree (layers are contiguous in BFS order)
@@ -185,33 +192,51 @@ __global__ __launch_bounds__(256) void k_hang_comm(HangArgs a) {
     if (tree) { int cur = (int)q; while (a.T.tree_parent[off + cur] >= 0) { cur = a.T.tree_parent[off + cur]; ++d; } }
     return d;
   };
-  for (u32 q = tid; q < n; q += 256) {
-    const u64 p = off + q;
-    const bool entered = (u64)PAIR(a, CCLD_HPAIR_SEQ, p) == seq_max;
-    PAIR(a, CCLD_HPAIR_ENTERED, p) = entered ? 1 : 0;
-    u32 f = 0;
-    if (!entered) f |= 1 | 8;
-    if (PAIR(a, CCLD_HPAIR_STALLED, p)) f |= 2; else f |= 4;
-    // identical totals across comparable ranks: every adjacent pair of the same layer
-    if (q > 0 && (!tree || depth_of(q) == depth_of(q - 1)) &&
-        (PAIR(a, CCLD_HPAIR_SENT, p) != PAIR(a, CCLD_HPAIR_SENT, p - 1) ||
-         PAIR(a, CCLD_HPAIR_RECV, p) != PAIR(a, CCLD_HPAIR_RECV, p - 1)))
-      f |= 8;
-    if (f) atomicOr(&s_flags, f);
-    atomicMin(&s_minsum, (unsigned long long)(PAIR(a, CCLD_HPAIR_SENT, p) + PAIR(a, CCLD_HPAIR_RECV, p)));
-    if (tree) atomicMax((unsigned long long*)&a.layer_max[off + depth_of(q)],
-                        (unsigned long long)(PAIR(a, CCLD_HPAIR_SENT, p) + PAIR(a, CCLD_HPAIR_RECV, p)));
+  {
+    u32 fl = 0;
+    unsigned long long minsum = ~0ull;
+    for (u32 q = tid; q < n; q += 256) {
+      const u64 p = off + q;
+      const bool entered = (u64)PAIR(a, CCLD_HPAIR_SEQ, p) == seq_max;
+      PAIR(a, CCLD_HPAIR_ENTERED, p) = entered ? 1 : 0;
+      if (!entered) fl |= 1 | 8;
+      if (PAIR(a, CCLD_HPAIR_STALLED, p)) fl |= 2; else fl |= 4;
+      // identical totals across comparable ranks: every adjacent pair of the same layer
+      if (q > 0 && (!tree || depth_of(q) == depth_of(q - 1)) &&
+          (PAIR(a, CCLD_HPAIR_SENT, p) != PAIR(a, CCLD_HPAIR_SENT, p - 1) ||
+           PAIR(a, CCLD_HPAIR_RECV, p) != PAIR(a, CCLD_HPAIR_RECV, p - 1)))
+        fl |= 8;
+      const unsigned long long sum = (unsigned long long)(PAIR(a, CCLD_HPAIR_SENT, p) + PAIR(a, CCLD_HPAIR_RECV, p));
+      minsum = sum < minsum ? sum : minsum;
+      if (tree) atomicMax((unsigned long long*)&a.layer_max[off + depth_of(q)], sum);
+    }
+    if (fl) atomicOr(&s_flags, fl);
+    if (tid < n) atomicMin(&s_minsum, minsum);
   }
   __syncthreads();
   // fewest SendCount + RecvCount, then fewest received, then smallest rank
-  for (u32 q = tid; q < n; q += 256)
-    if ((u64)(PAIR(a, CCLD_HPAIR_SENT, off + q) + PAIR(a, CCLD_HPAIR_RECV, off + q)) == s_minsum)
-      atomicMin(&s_minrecv, (unsigned long long)PAIR(a, CCLD_HPAIR_RECV, off + q));
+  {
+    const unsigned long long ms = s_minsum;
+    unsigned long long mr = ~0ull;
+    for (u32 q = tid; q < n; q += 256)
+      if ((u64)(PAIR(a, CCLD_HPAIR_SENT, off + q) + PAIR(a, CCLD_HPAIR_RECV, off + q)) == ms) {
+        const unsigned long long v = (unsigned long long)PAIR(a, CCLD_HPAIR_RECV, off + q);
+        mr = v < mr ? v : mr;
+      }
+    if (mr != ~0ull) atomicMin(&s_minrecv, mr);
+  }
   __syncthreads();
-  for (u32 q = tid; q < n; q += 256)
-    if ((u64)(PAIR(a, CCLD_HPAIR_SENT, off + q) + PAIR(a, CCLD_HPAIR_RECV, off + q)) == s_minsum &&
-        (u64)PAIR(a, CCLD_HPAIR_RECV, off + q) == s_minrecv)
-      atomicMin(&s_best, (u32)PAIR(a, CCLD_HPAIR_RANK, off + q));
+  {
+    const unsigned long long ms = s_minsum, mr = s_minrecv;
+    u32 best = 0xFFFFFFFFu;
+    for (u32 q = tid; q < n; q += 256)
+      if ((u64)(PAIR(a, CCLD_HPAIR_SENT, off + q) + PAIR(a, CCLD_HPAIR_RECV, off + q)) == ms &&
+          (u64)PAIR(a, CCLD_HPAIR_RECV, off + q) == mr) {
+        const u32 rk = (u32)PAIR(a, CCLD_HPAIR_RANK, off + q);
+        best = rk < best ? rk : best;
+      }
+    if (best != 0xFFFFFFFFu) atomicMin(&s_best, best);
+  }
   __syncthreads();
   const u32 flags = s_flags;
   const bool all_entered = !(flags & 1), any_stalled = flags & 2, all_stalled = !(flags & 4), idle_ok = !(flags & 8);
