@@ -124,6 +124,9 @@ def main() -> int:
     n_seg_expected = n // 4 + 1024
     buffers = an.alloc_window_result(n, seg_cap=n_seg_expected, flag_cap=max(n // 8, 1 << 16),
                                      group_cap=min(an.n_comms * 1024, 1 << 22))
+    # every result table stays in HBM (the counts come back with each call's status)
+    blame_buffers = (torch.empty(5 * an.n_ranks, dtype=torch.int64, device=dev),
+                     torch.empty(an.n_ranks, dtype=torch.int32, device=dev))
     log(f"workspace {an.workspace_bytes / 2**30:.2f} GiB; inputs resident in HBM")
 
     # Every step analyses operation counters the analyzer has not seen before (the counters of step i are
@@ -141,7 +144,7 @@ def main() -> int:
         an.reset_window()
         an.ingest(w)
         res = an.analyze_window(now, buffers=buffers)
-        an.rank_blame()
+        an.rank_blame(to_host=False, buffers=blame_buffers)
         return res
 
     if args.calibrate_copy:
@@ -173,7 +176,7 @@ def main() -> int:
                 an.reset_window()
                 an.ingest(cols_time_major)
                 r3 = an.analyze_window(now, buffers=buffers)
-                an.rank_blame()
+                an.rank_blame(to_host=False, buffers=blame_buffers)
             torch.cuda.synchronize()
             if timed:
                 time_major_ms = (time.perf_counter() - t_t) / 2 * 1e3
@@ -194,7 +197,7 @@ def main() -> int:
             an.reset_window()
             an.ingest(host)
             r2 = an.analyze_window(now, buffers=buffers)
-            an.rank_blame()
+            an.rank_blame(to_host=False, buffers=blame_buffers)
         torch.cuda.synchronize()
         pcie = n / ((time.perf_counter() - t_h) / 2)
         assert r2.status == "OK" and int(r2.n_flag) == int(res.n_flag)
@@ -285,6 +288,8 @@ def bench_stream(args, torch, np, ccld, tg) -> int:
                        hang_threshold_ns=5_000_000_000, device="cuda:0")
     buffers = an.alloc_window_result(W * per, seg_cap=W * per // 4 + 1024, flag_cap=W * per // 8 + 1024,
                                      group_cap=min(an.n_comms * 1024, 1 << 22))
+    blame_buffers = (torch.empty(5 * an.n_ranks, dtype=torch.int64, device="cuda:0"),
+                     torch.empty(an.n_ranks, dtype=torch.int32, device="cuda:0"))
     lat, alerts, first_alert, leaders = [], 0, None, []
     for step in range(ss.n_steps):
         b = tg.stream_batch(ss, step)
@@ -293,7 +298,7 @@ def bench_stream(args, torch, np, ccld, tg) -> int:
         t0 = time.perf_counter()
         an.ingest(cols)
         res = an.analyze_window(ss.now_ns(step), buffers=buffers)
-        blame, order = an.rank_blame()
+        blame, order = an.rank_blame(to_host=False, buffers=blame_buffers)
         torch.cuda.synchronize()
         lat.append(time.perf_counter() - t0)
         assert res.status == "OK", res.status

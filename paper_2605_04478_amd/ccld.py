@@ -350,11 +350,18 @@ class Analyzer:
         return WindowResult(STATUS.get(st, str(st)), r.n_records, r.n_seg, r.n_flag, r.n_group, r.n_alert,
                             r.n_cand, caps, dev)
 
-    def rank_blame(self):
+    def rank_blame(self, to_host: bool = True, buffers=None):
+        """-> (blame columns, order).  to_host=False leaves both on the device (column-major int64 table
+        [len(BLAME_COLS)][n_ranks], int32 order), written into `buffers` = (blame, order) when given."""
         t = self.torch
-        blame = t.empty(len(BLAME_COLS) * self.n_ranks, dtype=t.int64, device=self.device)
-        order = t.empty(self.n_ranks, dtype=t.int32, device=self.device)
+        if buffers is not None:
+            blame, order = buffers
+        else:
+            blame = t.empty(len(BLAME_COLS) * self.n_ranks, dtype=t.int64, device=self.device)
+            order = t.empty(self.n_ranks, dtype=t.int32, device=self.device)
         self._check(self.L.ccld_rank_blame(self._ctx, blame.data_ptr(), order.data_ptr()), "ccld_rank_blame")
+        if not to_host:
+            return blame.view(len(BLAME_COLS), self.n_ranks), order
         b = blame.view(len(BLAME_COLS), self.n_ranks).cpu().numpy()
         return ({nm: np.ascontiguousarray(b[i]) for i, nm in enumerate(BLAME_COLS)},
                 order.cpu().numpy().astype(np.int64))

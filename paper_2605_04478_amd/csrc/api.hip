@@ -70,7 +70,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->big_ex = w.take<int64_t>(2 * N);
   c->blame_list = w.take<uint32_t>(2ull * n_ranks);
   c->blame_tiles = w.take<uint32_t>(n_ranks / SEL_TILE + 3);
-  c->usable_list = w.take<uint32_t>(N);
+  c->group_long = w.take<uint32_t>(N / GROUP_LONG_MIN + 2);
   c->group_first = w.take<uint32_t>(N + 1);
   c->alert_list = w.take<uint32_t>(NT);
   c->alert_ncand = w.take<uint32_t>(N + 2);
@@ -234,6 +234,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   c->topo.n_ranks = topo->n_ranks; c->topo.n_comms = topo->n_comms;
   c->h_size.assign(topo->size, topo->size + topo->n_comms);
   c->h_pinned = nullptr;
+  c->ev_heads = nullptr;
 
   // derived host tables: sorted member lists, rank -> communicators CSR
   std::vector<uint32_t> sorted(topo->members, topo->members + n_members), sslot(n_members);
@@ -296,8 +297,15 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
     const size_t bytes = std::max<size_t>(4096 * sizeof(uint64_t), sizeof(BatchMeta) * ((size_t)c->p.window_batches + 2));
     if (hipHostMalloc((void**)&c->h_pinned, bytes, hipHostMallocDefault) != hipSuccess) rs = CCLD_E_HIP;
   }
+  if (hipEventCreateWithFlags(&c->ev_heads, hipEventDisableTiming) != hipSuccess) { c->ev_heads = nullptr; rs = CCLD_E_HIP; }
   if (hipStreamSynchronize(c->stream) != hipSuccess) rs = CCLD_E_HIP;   // host vectors above die at return
-  if (rs != CCLD_OK) { (void)hipGetLastError(); if (c->h_pinned) (void)hipHostFree(c->h_pinned); delete c; return rs; }
+  if (rs != CCLD_OK) {
+    (void)hipGetLastError();
+    if (c->h_pinned) (void)hipHostFree(c->h_pinned);
+    if (c->ev_heads) (void)hipEventDestroy(c->ev_heads);
+    delete c;
+    return rs;
+  }
   *out = c;
   return CCLD_OK;
 }
@@ -306,6 +314,7 @@ ccld_status ccld_destroy(ccld_ctx* c) {
   if (!c) return CCLD_E_NULL;
   (void)hipStreamSynchronize(c->stream);
   if (c->h_pinned) (void)hipHostFree(c->h_pinned);
+  if (c->ev_heads) (void)hipEventDestroy(c->ev_heads);
   c->prof.destroy();
   delete c;
   return CCLD_OK;
@@ -456,9 +465,21 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   launch_keys_pass(st, skey, n, c->sf, c->topo, c->blame, c->tile_heads, c->counters);
   launch_scan_tiles(st, c->tile_heads, seg_tiles, &c->counters[CNT_NSEG]);
   c->prof.end(CCLD_PROF_SEG_HEADS);
+  // the number of collectives is known here; it comes back while the statistics kernels run
+  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipEventRecord(c->ev_heads, st));
   c->prof.begin();
   launch_seg_analyze(st, sa);
   c->prof.end(CCLD_PROF_SEGMENTS);
+  HIP_TRY(hipEventSynchronize(c->ev_heads));
+  if (c->h_pinned[CNT_STATUS]) {
+    const uint64_t bad = c->h_pinned[CNT_STATUS];
+    HIP_TRY(hipStreamSynchronize(st));
+    zero_counts(o);
+    return o->status = data_status(bad);
+  }
+  o->n_seg = c->h_pinned[CNT_NSEG];
+  const uint32_t seg_rows = (uint32_t)std::min<uint64_t>(o->n_seg, o->seg_cap);
   FlagArgs fa;
   std::memset(&fa, 0, sizeof(fa));
   fa.key = skey; fa.rec_flag = sa.rec_flag; fa.flag_lag = c->flag_lag; fa.cap_n = c->cap; fa.n = n; fa.sf = c->sf;
@@ -469,20 +490,55 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   launch_flag_compact(st, fa);
   c->prof.end(CCLD_PROF_FLAGS);
   if (o->perm) launch_perm(st, sidx, c->win_row, n, c->batch_seqno.empty() ? 0u : c->batch_seqno[0], o->perm);
+
+  // 4. hang alerts: which collectives
+  AlertArgs aa;
+  std::memset(&aa, 0, sizeof(aa));
+  aa.seg = o->seg; aa.seg_cap = o->seg_cap; aa.n_seg = seg_rows; aa.now_ns = now_ns;
+  aa.hang_threshold_ns = c->p.hang_threshold_ns; aa.key = skey; aa.idx = sidx; aa.row = c->win_row; aa.n = n;
+  aa.sf = c->sf; aa.topo = c->topo; aa.tile_counts = c->tile_heads; aa.alert_list = c->alert_list;
+  aa.alert_ncand = c->alert_ncand; aa.alert = o->alert; aa.alert_cap = o->alert_cap; aa.cand = o->cand;
+  aa.cand_cap = o->cand_cap; aa.counters = c->counters;
+  c->prof.begin();
+  launch_alert_select(st, aa);
+  c->prof.end(CCLD_PROF_ALERTS);
+
+  // 5. slow detection and location per detection group (Eq. 1-4): every collective of the table is keyed
+  //    (those that take no part sort behind the groups), and the evaluation reads the numbers of groups and of
+  //    usable collectives on the device, so nothing here waits for the host
+  SortBuffers sb2;
+  sb2.key[0] = c->sb.key[1 - sorted]; sb2.idx[0] = c->sb.idx[1 - sorted];
+  sb2.key[1] = c->keyC; sb2.idx[1] = c->idxC; sb2.table = c->table2; sb2.totals = c->totals2;
+  GroupArgs ga;
+  std::memset(&ga, 0, sizeof(ga));
+  ga.seg = o->seg; ga.seg_cap = o->seg_cap; ga.n_seg = seg_rows; ga.ws = ws; ga.cb = cb;
+  ga.tile_counts = c->tile_flags; ga.counters = c->counters;
+  ga.gstate = c->gstate; ga.rate_root = c->rate_root; ga.group = o->group; ga.group_cap = o->group_cap; ga.p = c->p;
+  ga.gkey = c->keyC;
+  ga.range_c = c->big_ex;       // free again once the collectives have been analysed
+  if (seg_rows) {
+    const uint64_t no_group = (uint64_t)c->topo.n_comms * CCLD_OP_MAX * GROUP_CLS;     // one past every group key
+    c->prof.begin();
+    launch_group_keys(st, ga, no_group);
+    KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = seg_rows; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0; gs.lo_sub = 0;
+    // sort C -> buffers {other main, C}: the first pass reads C and writes buffer 0, so C is free again for pass 2
+    const int r3 = radix_sort_pairs(st, gs, seg_rows, sb2, bits_for_host(no_group));
+    if (r3 < 0) return o->status = CCLD_E_HIP;
+    launch_group_heads(st, sb2.key[r3], seg_rows, no_group, c->tile_flags, c->group_first, c->counters);
+    launch_group_eval(st, ga, sb2.key[r3], sb2.idx[r3], c->group_first, c->group_long);
+    c->prof.end(CCLD_PROF_GROUPS);
+  }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   if (c->h_pinned[CNT_STATUS]) { zero_counts(o); return o->status = data_status(c->h_pinned[CNT_STATUS]); }
-  o->n_seg = c->h_pinned[CNT_NSEG];
   o->n_flag = c->h_pinned[CNT_NFLAG];
+  o->n_alert = c->h_pinned[CNT_NALERT];
+  o->n_group = c->h_pinned[CNT_NGROUP];
   const uint32_t n_flag = (uint32_t)o->n_flag;
-  const uint32_t seg_rows = (uint32_t)std::min<uint64_t>(o->n_seg, o->seg_cap);
-  if (o->n_seg > o->seg_cap || o->n_flag > o->flag_cap) o->status = CCLD_W_TRUNCATED;
+  if (o->n_seg > o->seg_cap || o->n_flag > o->flag_cap || o->n_group > o->group_cap) o->status = CCLD_W_TRUNCATED;
 
-  // 4. blame: flags keyed by rank, sorted, one wavefront per rank sums its run
-  SortBuffers sb2;
-  sb2.key[0] = c->sb.key[1 - sorted]; sb2.idx[0] = c->sb.idx[1 - sorted];
-  sb2.key[1] = c->keyC; sb2.idx[1] = c->idxC; sb2.table = c->table2; sb2.totals = c->totals2;
+  // 6. blame: flags keyed by rank, sorted, one workgroup per rank sums its run
   if (n_flag) {
     uint64_t* bk = c->keyC;       // keys are written to C, first pass sorts C -> buffer 0 of sb2
     c->prof.begin();
@@ -494,51 +550,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
                         c->blame_list, c->blame);
     c->prof.end(CCLD_PROF_BLAME);
   }
-
-  // 5. slow detection and location per detection group (Eq. 1-4)
-  GroupArgs ga;
-  std::memset(&ga, 0, sizeof(ga));
-  ga.seg = o->seg; ga.seg_cap = o->seg_cap; ga.n_seg = seg_rows; ga.ws = ws; ga.cb = cb;
-  ga.usable_list = c->usable_list; ga.tile_counts = c->tile_flags; ga.counters = c->counters;
-  ga.gstate = c->gstate; ga.rate_root = c->rate_root; ga.group = o->group; ga.group_cap = o->group_cap; ga.p = c->p;
-  c->prof.begin();
-  launch_usable_select(st, ga);
-  c->prof.end(CCLD_PROF_GROUPS);
-  // 6. hang alerts
-  AlertArgs aa;
-  std::memset(&aa, 0, sizeof(aa));
-  aa.seg = o->seg; aa.seg_cap = o->seg_cap; aa.n_seg = seg_rows; aa.now_ns = now_ns;
-  aa.hang_threshold_ns = c->p.hang_threshold_ns; aa.key = skey; aa.idx = sidx; aa.row = c->win_row; aa.n = n;
-  aa.sf = c->sf; aa.topo = c->topo; aa.tile_counts = c->tile_heads; aa.alert_list = c->alert_list;
-  aa.alert_ncand = c->alert_ncand; aa.alert = o->alert; aa.alert_cap = o->alert_cap; aa.cand = o->cand;
-  aa.cand_cap = o->cand_cap; aa.counters = c->counters;
-  c->prof.begin();
-  launch_alert_select(st, aa);
-  c->prof.end(CCLD_PROF_ALERTS);
-  HIP_TRY(hipGetLastError());
-  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
-  const uint32_t n_usable = (uint32_t)c->h_pinned[CNT_NUSABLE];
-  o->n_alert = c->h_pinned[CNT_NALERT];
-  if (n_usable) {
-    ga.gkey = c->keyC;            // blame's sort is done with C by stream order
-    ga.range_c = c->big_ex;       // free again once the collectives have been analysed
-    c->prof.begin();
-    launch_group_keys(st, ga, n_usable);
-    KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = n_usable; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0; gs.lo_sub = 0;
-    // sort C -> buffers {other main, C}: the first pass reads C and writes buffer 0, so C is free again for pass 2
-    const int r3 = radix_sort_pairs(st, gs, n_usable, sb2, cb + 10);
-    if (r3 < 0) return o->status = CCLD_E_HIP;
-    launch_group_heads(st, sb2.key[r3], n_usable, ws, c->tile_flags, c->group_first, c->counters);
-    c->prof.end(CCLD_PROF_GROUPS);
-    HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipStreamSynchronize(st));
-    o->n_group = c->h_pinned[CNT_NGROUP];
-    c->prof.begin();
-    launch_group_eval(st, ga, sb2.key[r3], sb2.idx[r3], n_usable, c->group_first, (uint32_t)o->n_group);
-    c->prof.end(CCLD_PROF_GROUPS);
-    if (o->n_group > o->group_cap) o->status = CCLD_W_TRUNCATED;
-  }
+  // 7. hang alerts: candidates of every alert
   if (o->n_alert) {
     c->prof.begin();
     launch_alert_candidates(st, aa, (uint32_t)o->n_alert);

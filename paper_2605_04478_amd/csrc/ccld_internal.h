@@ -82,7 +82,8 @@ constexpr int SEL_TILE = 2048;       // records per workgroup of the compaction 
 constexpr int RANKCOUNT_BLOCKS = 2048;
 
 // device counters written by kernels and read back by the host
-enum { CNT_NSEG, CNT_NFLAG, CNT_NBIG, CNT_NUSABLE, CNT_NGROUP, CNT_NALERT, CNT_NCAND, CNT_STATUS, CNT_NBLAMED, CNT_NCLEAN, CNT_COUNT = 16 };
+enum { CNT_NSEG, CNT_NFLAG, CNT_NBIG, CNT_NUSABLE, CNT_NGROUP, CNT_NALERT, CNT_NCAND, CNT_STATUS, CNT_NBLAMED, CNT_NCLEAN, CNT_NLONG, CNT_COUNT = 16 };
+constexpr uint32_t GROUP_LONG_MIN = 4096;   // a detection group of more rounds than this gets a whole workgroup
 
 }  // namespace ccld
 
@@ -123,7 +124,7 @@ struct ccld_ctx {
   int64_t* blame;                     // [CCLD_BLM_NCOL][n_ranks]
   uint32_t* blame_list;               // [2][n_ranks] flagged ranks, then the others, each ascending
   uint32_t* blame_tiles;              // [n_ranks / SEL_TILE + 3]
-  uint32_t* usable_list;              // [cap]
+  uint32_t* group_long;               // [cap / GROUP_LONG_MIN + 2] detection groups left to the workgroup-per-group pass
   uint32_t* group_first;              // [cap + 1]
   uint32_t* alert_list;               // [cap]
   uint32_t* alert_ncand;              // [cap + 1]
@@ -132,6 +133,7 @@ struct ccld_ctx {
   uint32_t max_comm_size;             // members of the largest communicator
   uint64_t sort_cap;                  // items the sort buffers hold: max(window records, communicator members)
   uint64_t* h_pinned;                 // pinned host staging
+  hipEvent_t ev_heads;                // marks the early readback of the collective count
   // staging for host-resident batches
   uint8_t* stage;                     // [batch_cap * 41] device
   // hang location

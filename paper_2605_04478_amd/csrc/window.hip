@@ -688,184 +688,203 @@ void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, 
 }
 
 // ------------------------------------------------------------------------------------------
-struct PredUsable {
-  const i64* state;
-  __device__ bool operator()(u32 s) const { return (state[s] & CCLD_SEG_USABLE) != 0; }
-};
-void launch_usable_select(hipStream_t st, const GroupArgs& a) {
-  PredUsable p{a.seg + (u64)CCLD_SEG_STATE * a.seg_cap};
-  run_select(st, p, a.n_seg, a.tile_counts, a.usable_list, &a.counters[CNT_NUSABLE]);
+// Detection-group key of every collective in the table: (communicator, op, floor(log2 bytes)) for a
+// usable one, one value past every real key otherwise.  The table is in (communicator, operation
+// counter) order, so a stable sort by this key lists every group's rounds in ascending operation
+// counter, with the collectives that take no part at the end.
+__global__ __launch_bounds__(256) void k_group_keys(GroupArgs a, u64 no_group) {
+  const u32 s = blockIdx.x * 256 + threadIdx.x;
+  if (s < a.n_seg) {
+    const bool usable = (a.seg[(u64)CCLD_SEG_STATE * a.seg_cap + s] & CCLD_SEG_USABLE) != 0;
+    u64 key = no_group;
+    i64 range = 0;
+    if (usable) {
+      const u64 comm = (u64)a.seg[(u64)CCLD_SEG_COMM * a.seg_cap + s];
+      const u64 op = (u64)a.seg[(u64)CCLD_SEG_OP * a.seg_cap + s];
+      const u64 nb = (u64)a.seg[(u64)CCLD_SEG_BYTES * a.seg_cap + s];
+      const u64 cls = 63 - __clzll((long long)(nb | 1));
+      key = (comm * CCLD_OP_MAX + op) * GROUP_CLS + cls;
+      // intra-round range T_max - T_min (Eq. 2), kept per collective for the per-group pass
+      range = a.seg[(u64)CCLD_SEG_DUR_MAX * a.seg_cap + s] - a.seg[(u64)CCLD_SEG_DUR_MIN * a.seg_cap + s];
+    }
+    a.gkey[s] = key;
+    a.range_c[s] = range;
+  }
 }
-
-// detection-group key of a usable collective: (communicator, op, floor(log2 bytes)); the usable
-// collectives are listed in (communicator, operation counter) order, so a stable sort by this key
-// lists every group's rounds in ascending operation counter
-__global__ __launch_bounds__(256) void k_group_keys(GroupArgs a, u32 n_usable) {
-  const u32 q = blockIdx.x * 256 + threadIdx.x;
-  if (q >= n_usable) return;
-  const u32 s = a.usable_list[q];
-  const u64 comm = (u64)a.seg[(u64)CCLD_SEG_COMM * a.seg_cap + s];
-  const u64 op = (u64)a.seg[(u64)CCLD_SEG_OP * a.seg_cap + s];
-  const u64 nb = (u64)a.seg[(u64)CCLD_SEG_BYTES * a.seg_cap + s];
-  const u64 cls = 63 - __clzll((long long)(nb | 1));
-  a.gkey[q] = (comm * CCLD_OP_MAX + op) * GROUP_CLS + cls;
-  // intra-round range T_max - T_min (Eq. 2), kept in usable-list order for the per-group pass
-  a.range_c[q] = a.seg[(u64)CCLD_SEG_DUR_MAX * a.seg_cap + s] - a.seg[(u64)CCLD_SEG_DUR_MIN * a.seg_cap + s];
+// number of usable collectives = position of the first key past the groups in the sorted keys
+__global__ void k_group_bound(const u64* __restrict__ skey, u32 n_rows, u64 no_group, u64* __restrict__ counters) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  u32 lo = 0, hi = n_rows;
+  while (lo < hi) { const u32 m = (lo + hi) / 2; if (skey[m] < no_group) lo = m + 1; else hi = m; }
+  counters[CNT_NUSABLE] = lo;
 }
-void launch_group_keys(hipStream_t st, const GroupArgs& a, uint32_t n_usable) {
-  if (n_usable) hipLaunchKernelGGL(k_group_keys, dim3((n_usable + 255) / 256), dim3(256), 0, st, a, n_usable);
+void launch_group_keys(hipStream_t st, const GroupArgs& a, uint64_t no_group) {
+  if (a.n_seg) hipLaunchKernelGGL(k_group_keys, dim3((a.n_seg + 255) / 256), dim3(256), 0, st, a, no_group);
 }
 
 struct PredGroupHead {
-  const u64* skey; int ws;
-  __device__ bool operator()(u32 i) const { return i == 0 || skey[i] != skey[i - 1]; }
+  const u64* skey; u64 no_group;
+  __device__ bool operator()(u32 i) const { return skey[i] != no_group && (i == 0 || skey[i] != skey[i - 1]); }
 };
-void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_usable, int ws, uint32_t* tile_counts,
+void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_rows, uint64_t no_group, uint32_t* tile_counts,
                         uint32_t* group_first, uint64_t* counters) {
-  PredGroupHead p{skey, ws};
-  run_select(st, p, n_usable, tile_counts, group_first, &counters[CNT_NGROUP]);
+  PredGroupHead p{skey, no_group};
+  hipLaunchKernelGGL(k_group_bound, dim3(1), dim3(64), 0, st, skey, n_rows, no_group, counters);
+  run_select(st, p, n_rows, tile_counts, group_first, &counters[CNT_NGROUP]);
 }
 
-// One workgroup per detection group.  Eq. 1: baseline = mean of T_max over the first m rounds
-// (m = min(tbase_rounds, rounds within the warm-up span)); Eq. 2: the window's round of largest
-// T_max - T_min; Eq. 3: slow iff (T_max - T_base)/T_base > theta; Eq. 4: P = (T_max - T_min)/
-// (T_max - T_base) against alpha / beta; repetition counter.  All ratios cross-multiplied.
-template <int T>          // threads per group: a full workgroup, or one wavefront where groups are short
+// Eq. 1: baseline = mean of T_max over the first m rounds (m = min(tbase_rounds, rounds within the
+// warm-up span)); Eq. 2: the window's round of largest T_max - T_min; Eq. 3: slow iff (T_max - T_base)/
+// T_base > theta; Eq. 4: P = (T_max - T_min)/(T_max - T_base) against alpha / beta; repetition counter.
+// All ratios cross-multiplied.  The numbers of groups and of usable collectives are read from the
+// device counters, so the host does not have to learn them before this launch.
+// T threads per group: one wavefront walks all groups and leaves those longer than GROUP_LONG rounds on a
+// list (BIG = false); a second launch takes that list with a full workgroup per group (BIG = true).
+constexpr u32 GROUP_LONG = GROUP_LONG_MIN;
+template <int T, bool BIG>
 __global__ __launch_bounds__(T) void k_group_eval(GroupArgs a, const u64* __restrict__ skey,
-                                                    const u32* __restrict__ sidx, u32 n_usable,
-                                                    const u32* __restrict__ group_first, u32 n_group) {
+                                                    const u32* __restrict__ sidx,
+                                                    const u32* __restrict__ group_first, u32* __restrict__ long_list) {
   __shared__ u32 s_i0, s_istar, s_kstar;
   __shared__ unsigned long long s_sum, s_best;
-  const u32 g = blockIdx.x, tid = threadIdx.x;
-  const u32 f = group_first[g], e = (g + 1 < n_group) ? group_first[g + 1] : n_usable;
-  const u64 gid = skey[f];                               // (comm*OP_MAX + op)*CLS + cls
+  const u32 tid = threadIdx.x;
+  const u32 n_group = (u32)a.counters[CNT_NGROUP], n_usable = (u32)a.counters[CNT_NUSABLE];
+  const u32 n_work = BIG ? (u32)a.counters[CNT_NLONG] : n_group;
   const i64* SEQ = a.seg + (u64)CCLD_SEG_SEQ * a.seg_cap;
-  auto seq_of = [&](u32 i) -> u64 { return (u64)SEQ[a.usable_list[sidx[i]]]; };
-  GroupState* G = a.gstate + gid;
   const i64* EMIN = a.seg + (u64)CCLD_SEG_ENTER_MIN * a.seg_cap;
   const i64* DMAX = a.seg + (u64)CCLD_SEG_DUR_MAX * a.seg_cap;
   const i64* DMIN = a.seg + (u64)CCLD_SEG_DUR_MIN * a.seg_cap;
-  const GroupState g0 = *G;
-  if (tid == 0) { s_i0 = e; s_istar = e; s_kstar = e; s_sum = 0; s_best = 0; }
-  __syncthreads();
-  // rounds not yet visited by Eq. 1 form a suffix (ascending operation counters)
-  // (ascending counters: compare the last round first; a fully visited group needs no search)
-  const bool any_new = seq_of(e - 1) + 1 > g0.baselined_wm;
-  if (any_new) {
-    // a suffix: the first hit of a thread's ascending walk is its smallest, one atomic per thread
-    u32 mine = e;
-    for (u32 i = f + tid; i < e; i += T)
-      if (seq_of(i) + 1 > g0.baselined_wm) { mine = i; break; }
-    if (mine < e) atomicMin(&s_i0, mine);
-  }
-  // Eq. 2 needs the largest range; the first rounds of every thread stay in registers for the
-  // second look below
-  constexpr int KEEP = 4;
-  unsigned long long kept[KEEP];
-  {
-    unsigned long long mine = 0;
+  auto seq_of = [&](u32 i) -> u64 { return (u64)SEQ[sidx[i]]; };
+  for (u32 w = blockIdx.x; w < n_work; w += gridDim.x) {
+    const u32 g = BIG ? long_list[w] : w;
+    const u32 f = group_first[g], e = (g + 1 < n_group) ? group_first[g + 1] : n_usable;
+    if (!BIG && e - f > GROUP_LONG) {
+      if (tid == 0) long_list[(u32)atomic_add_u64(&a.counters[CNT_NLONG], 1)] = g;
+      continue;
+    }
+    const u64 gid = skey[f];                               // (comm*OP_MAX + op)*CLS + cls
+    GroupState* G = a.gstate + gid;
+    const GroupState g0 = *G;
+    if (tid == 0) { s_i0 = e; s_istar = e; s_kstar = e; s_sum = 0; s_best = 0; }
+    __syncthreads();
+    // rounds not yet visited by Eq. 1 form a suffix (ascending operation counters): compare the last
+    // round first; a fully visited group needs no search
+    const bool any_new = seq_of(e - 1) + 1 > g0.baselined_wm;
+    if (any_new) {
+      // the first hit of a thread's ascending walk is its smallest, one atomic per thread
+      u32 mine = e;
+      for (u32 i = f + tid; i < e; i += T)
+        if (seq_of(i) + 1 > g0.baselined_wm) { mine = i; break; }
+      if (mine < e) atomicMin(&s_i0, mine);
+    }
+    // Eq. 2 needs the largest range; the first rounds of every thread stay in registers for the
+    // second look below
+    constexpr int KEEP = 4;
+    unsigned long long kept[KEEP];
+    {
+      unsigned long long mine = 0;
 #pragma unroll
-    for (int j = 0; j < KEEP; ++j) {
-      const u32 i = f + tid + (u32)T * j;
-      kept[j] = i < e ? (unsigned long long)a.range_c[sidx[i]] : 0ull;
-      mine = kept[j] > mine ? kept[j] : mine;
+      for (int j = 0; j < KEEP; ++j) {
+        const u32 i = f + tid + (u32)T * j;
+        kept[j] = i < e ? (unsigned long long)a.range_c[sidx[i]] : 0ull;
+        mine = kept[j] > mine ? kept[j] : mine;
+      }
+      for (u32 i = f + tid + (u32)T * KEEP; i < e; i += T) {
+        const unsigned long long v = (unsigned long long)a.range_c[sidx[i]];
+        mine = v > mine ? v : mine;
+      }
+      if (mine) atomicMax(&s_best, mine);
     }
-    for (u32 i = f + tid + (u32)T * KEEP; i < e; i += T) {
-      const unsigned long long v = (unsigned long long)a.range_c[sidx[i]];
-      mine = v > mine ? v : mine;
+    __syncthreads();
+    const u32 i0 = s_i0;
+    const i64 t0 = (g0.cnt == 0 && i0 < e) ? EMIN[sidx[i0]] : g0.t0;
+    if (!g0.frozen) {
+      for (u32 i = i0 + tid; i < e; i += T) {
+        const u32 s = sidx[i];
+        const u64 q = i - i0;
+        if ((u64)g0.cnt + q >= (u64)a.p.tbase_rounds || EMIN[s] - t0 > a.p.tbase_warmup_ns) atomicMin(&s_istar, i);
+      }
     }
-    if (mine) atomicMax(&s_best, mine);
-  }
-  __syncthreads();
-  const u32 i0 = s_i0;
-  const i64 t0 = (g0.cnt == 0 && i0 < e) ? EMIN[a.usable_list[sidx[i0]]] : g0.t0;
-  if (!g0.frozen) {
-    for (u32 i = i0 + tid; i < e; i += T) {
-      const u32 s = a.usable_list[sidx[i]];
-      const u64 q = i - i0;
-      if ((u64)g0.cnt + q >= (u64)a.p.tbase_rounds || EMIN[s] - t0 > a.p.tbase_warmup_ns) atomicMin(&s_istar, i);
-    }
-  }
-  const unsigned long long best = s_best;
-  {
-    u32 first = e;
+    const unsigned long long best = s_best;
+    {
+      u32 first = e;
 #pragma unroll
-    for (int j = KEEP - 1; j >= 0; --j) {
-      const u32 i = f + tid + (u32)T * j;
-      if (i < e && kept[j] == best) first = i;
+      for (int j = KEEP - 1; j >= 0; --j) {
+        const u32 i = f + tid + (u32)T * j;
+        if (i < e && kept[j] == best) first = i;
+      }
+      if (first == e)
+        for (u32 i = f + tid + (u32)T * KEEP; i < e; i += T)
+          if ((unsigned long long)a.range_c[sidx[i]] == best) { first = i; break; }
+      if (first < e) atomicMin(&s_kstar, first);
     }
-    if (first == e)
-      for (u32 i = f + tid + (u32)T * KEEP; i < e; i += T)
-        if ((unsigned long long)a.range_c[sidx[i]] == best) { first = i; break; }
-    if (first < e) atomicMin(&s_kstar, first);
-  }
-  __syncthreads();
-  const u32 istar = s_istar;
-  if (!g0.frozen) {
-    unsigned long long part = 0;
-    for (u32 i = i0 + tid; i < istar; i += T) part += (unsigned long long)DMAX[a.usable_list[sidx[i]]];
-    if (part) atomicAdd(&s_sum, part);
-  }
-  __syncthreads();
-  if (tid != 0) return;
-  GroupState n = g0;
-  if (!g0.frozen && i0 < e) {
-    n.t0 = t0;
-    n.sum = (i64)((u64)g0.sum + (u64)s_sum);
-    n.cnt = g0.cnt + (istar - i0);
-    if (istar > i0) n.baseline_last_seq = seq_of(istar - 1);
-    if (istar < e) { n.frozen = 1; n.tbase_dyn = n.sum / (i64)n.cnt; }
-  }
-  if (i0 < e) n.baselined_wm = seq_of(e - 1) + 1;
-  const u32 ks = s_kstar;
-  const u32 sx = a.usable_list[sidx[ks]];
-  const u64 rseq = seq_of(ks);
-  const i64 tmax = DMAX[sx], tmin = DMIN[sx];
-  const bool dynamic = n.frozen && rseq > n.baseline_last_seq;
-  const i64 tbase = dynamic ? n.tbase_dyn : a.p.tbase_init_ns;
-  const bool slow = (i128)(tmax - tbase) * (i128)a.p.theta_den > (i128)a.p.theta_num * (i128)tbase;
-  int cls = CCLD_SLOW_NONE;
-  i64 root1 = CCLD_NO_RANK;
-  if (slow) {
-    const i128 num = (i128)(tmax - tmin) * (i128)a.p.ab_den, den = (i128)(tmax - tbase);
-    if (num > (i128)a.p.beta_num * den) cls = CCLD_SLOW_S1_COMPUTATION;
-    else if (num < (i128)a.p.alpha_num * den) cls = CCLD_SLOW_S2_COMMUNICATION;
-    else cls = CCLD_SLOW_S3_MIXED;
-    if (cls != CCLD_SLOW_S2_COMMUNICATION) root1 = a.seg[(u64)CCLD_SEG_ARGMIN_RANK * a.seg_cap + sx];
-    if (rseq + 1 > n.detected_wm) { n.repeats += 1; n.detected_wm = rseq + 1; }
-  }
-  *G = n;
-  if (g < a.group_cap) {
-    i64* O = a.group;
-    const u64 C = a.group_cap;
-    O[CCLD_GRP_COMM * C + g] = (i64)(gid / (CCLD_OP_MAX * GROUP_CLS));
-    O[CCLD_GRP_OP * C + g] = (i64)((gid / GROUP_CLS) % CCLD_OP_MAX);
-    O[CCLD_GRP_CLS * C + g] = (i64)(gid % GROUP_CLS);
-    O[CCLD_GRP_N_USABLE * C + g] = (i64)(e - f);
-    O[CCLD_GRP_RSTAR_SEQ * C + g] = (i64)rseq;
-    O[CCLD_GRP_TMAX * C + g] = tmax;
-    O[CCLD_GRP_TMIN * C + g] = tmin;
-    O[CCLD_GRP_TBASE * C + g] = tbase;
-    O[CCLD_GRP_STATIC * C + g] = dynamic ? 0 : 1;
-    O[CCLD_GRP_FROZEN * C + g] = n.frozen;
-    O[CCLD_GRP_M * C + g] = n.cnt;
-    O[CCLD_GRP_SLOW * C + g] = slow ? 1 : 0;
-    O[CCLD_GRP_CLASS * C + g] = cls;
-    O[CCLD_GRP_ROOT_S1 * C + g] = root1;
-    // communication-slow root (Eq. 4): the communicator's member of minimal SendRate / RecvRate
-    O[CCLD_GRP_ROOT_S2 * C + g] = (cls == CCLD_SLOW_S2_COMMUNICATION || cls == CCLD_SLOW_S3_MIXED)
-                                      ? a.rate_root[gid / (CCLD_OP_MAX * GROUP_CLS)] : (i64)CCLD_NO_RANK;
-    O[CCLD_GRP_REPEATS * C + g] = n.repeats;
-    O[CCLD_GRP_LOCATE * C + g] = (slow && n.repeats >= a.p.repeat_threshold) ? 1 : 0;
+    __syncthreads();
+    const u32 istar = s_istar;
+    if (!g0.frozen) {
+      unsigned long long part = 0;
+      for (u32 i = i0 + tid; i < istar; i += T) part += (unsigned long long)DMAX[sidx[i]];
+      if (part) atomicAdd(&s_sum, part);
+    }
+    __syncthreads();
+    if (tid == 0) {
+    GroupState n = g0;
+    if (!g0.frozen && i0 < e) {
+      n.t0 = t0;
+      n.sum = (i64)((u64)g0.sum + (u64)s_sum);
+      n.cnt = g0.cnt + (istar - i0);
+      if (istar > i0) n.baseline_last_seq = seq_of(istar - 1);
+      if (istar < e) { n.frozen = 1; n.tbase_dyn = n.sum / (i64)n.cnt; }
+    }
+    if (i0 < e) n.baselined_wm = seq_of(e - 1) + 1;
+    const u32 ks = s_kstar;
+    const u32 sx = sidx[ks];
+    const u64 rseq = seq_of(ks);
+    const i64 tmax = DMAX[sx], tmin = DMIN[sx];
+    const bool dynamic = n.frozen && rseq > n.baseline_last_seq;
+    const i64 tbase = dynamic ? n.tbase_dyn : a.p.tbase_init_ns;
+    const bool slow = (i128)(tmax - tbase) * (i128)a.p.theta_den > (i128)a.p.theta_num * (i128)tbase;
+    int cls = CCLD_SLOW_NONE;
+    i64 root1 = CCLD_NO_RANK;
+    if (slow) {
+      const i128 num = (i128)(tmax - tmin) * (i128)a.p.ab_den, den = (i128)(tmax - tbase);
+      if (num > (i128)a.p.beta_num * den) cls = CCLD_SLOW_S1_COMPUTATION;
+      else if (num < (i128)a.p.alpha_num * den) cls = CCLD_SLOW_S2_COMMUNICATION;
+      else cls = CCLD_SLOW_S3_MIXED;
+      if (cls != CCLD_SLOW_S2_COMMUNICATION) root1 = a.seg[(u64)CCLD_SEG_ARGMIN_RANK * a.seg_cap + sx];
+      if (rseq + 1 > n.detected_wm) { n.repeats += 1; n.detected_wm = rseq + 1; }
+    }
+    *G = n;
+    if (g < a.group_cap) {
+      i64* O = a.group;
+      const u64 C = a.group_cap;
+      O[CCLD_GRP_COMM * C + g] = (i64)(gid / (CCLD_OP_MAX * GROUP_CLS));
+      O[CCLD_GRP_OP * C + g] = (i64)((gid / GROUP_CLS) % CCLD_OP_MAX);
+      O[CCLD_GRP_CLS * C + g] = (i64)(gid % GROUP_CLS);
+      O[CCLD_GRP_N_USABLE * C + g] = (i64)(e - f);
+      O[CCLD_GRP_RSTAR_SEQ * C + g] = (i64)rseq;
+      O[CCLD_GRP_TMAX * C + g] = tmax;
+      O[CCLD_GRP_TMIN * C + g] = tmin;
+      O[CCLD_GRP_TBASE * C + g] = tbase;
+      O[CCLD_GRP_STATIC * C + g] = dynamic ? 0 : 1;
+      O[CCLD_GRP_FROZEN * C + g] = n.frozen;
+      O[CCLD_GRP_M * C + g] = n.cnt;
+      O[CCLD_GRP_SLOW * C + g] = slow ? 1 : 0;
+      O[CCLD_GRP_CLASS * C + g] = cls;
+      O[CCLD_GRP_ROOT_S1 * C + g] = root1;
+      // communication-slow root (Eq. 4): the communicator's member of minimal SendRate / RecvRate
+      O[CCLD_GRP_ROOT_S2 * C + g] = (cls == CCLD_SLOW_S2_COMMUNICATION || cls == CCLD_SLOW_S3_MIXED)
+                                        ? a.rate_root[gid / (CCLD_OP_MAX * GROUP_CLS)] : (i64)CCLD_NO_RANK;
+      O[CCLD_GRP_REPEATS * C + g] = n.repeats;
+      O[CCLD_GRP_LOCATE * C + g] = (slow && n.repeats >= a.p.repeat_threshold) ? 1 : 0;
+    }
+    }
+    __syncthreads();       // the shared cells are reused by the next group
   }
 }
 void launch_group_eval(hipStream_t st, const GroupArgs& a, const uint64_t* skey, const uint32_t* sidx,
-                       uint32_t n_usable, const uint32_t* group_first, uint32_t n_group) {
-  if (!n_group) return;
-  if (n_usable / n_group < 1024)     // short groups: the dependent lookups of many groups overlap
-    hipLaunchKernelGGL(k_group_eval<64>, dim3(n_group), dim3(64), 0, st, a, skey, sidx, n_usable, group_first, n_group);
-  else
-    hipLaunchKernelGGL(k_group_eval<256>, dim3(n_group), dim3(256), 0, st, a, skey, sidx, n_usable, group_first, n_group);
+                       const uint32_t* group_first, uint32_t* long_list) {
+  hipLaunchKernelGGL((k_group_eval<64, false>), dim3(256 * 16), dim3(64), 0, st, a, skey, sidx, group_first, long_list);
+  hipLaunchKernelGGL((k_group_eval<256, true>), dim3(256 * 4), dim3(256), 0, st, a, skey, sidx, group_first, long_list);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -87,23 +87,21 @@ struct GroupArgs {
   uint64_t seg_cap;
   uint32_t n_seg;            // rows present in the table
   int ws, cb;
-  uint32_t* usable_list;
   uint32_t* tile_counts;
   uint64_t* counters;
-  uint64_t* gkey;            // [n_usable]
-  int64_t* range_c;          // [n_usable] T_max - T_min of each usable collective
+  uint64_t* gkey;            // [n_seg] detection-group key of every collective
+  int64_t* range_c;          // [n_seg] T_max - T_min of each usable collective
   GroupState* gstate;
   const int64_t* rate_root;  // [n_comms] minimal-rate member per communicator (CCLD_NO_RANK before any rate pass)
   int64_t* group;
   uint64_t group_cap;
   ccld_params p;
 };
-void launch_usable_select(hipStream_t st, const GroupArgs& a);
-void launch_group_keys(hipStream_t st, const GroupArgs& a, uint32_t n_usable);
-void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_usable, int ws, uint32_t* tile_counts,
+void launch_group_keys(hipStream_t st, const GroupArgs& a, uint64_t no_group);
+void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_rows, uint64_t no_group, uint32_t* tile_counts,
                         uint32_t* group_first, uint64_t* counters);
 void launch_group_eval(hipStream_t st, const GroupArgs& a, const uint64_t* skey, const uint32_t* sidx,
-                       uint32_t n_usable, const uint32_t* group_first, uint32_t n_group);
+                       const uint32_t* group_first, uint32_t* long_list);
 
 struct AlertArgs {
   const int64_t* seg;

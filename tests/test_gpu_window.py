@@ -324,3 +324,52 @@ def test_truncated_tables_keep_exact_counts():
     assert np.array_equal(g.group["tmax"], ref.group["tmax"][:2])
     blame, order = an.rank_blame()
     assert np.array_equal(blame["n_late_enter"], ref.blame["n_late_enter"])
+
+
+def test_long_detection_groups_take_the_workgroup_pass():
+    """Groups of more than 4,096 rounds are evaluated by a workgroup each, the others by a wavefront
+    each; both kinds side by side, over two windows (baseline and repetition state carried)."""
+    from paper_2605_04478_amd import ccld
+    rng = np.random.default_rng(11)
+    R = 6
+    topo = ring_topology(R, comms=[list(range(R)), [0, 2, 4]])
+    rows = []
+    plan = [(0, 9000, 1 << 20), (0, 5000, 1 << 12), (0, 10, 1 << 26), (1, 4500, 1 << 20), (1, 100, 1 << 8)]
+    span = 20_000_000_000
+    # every group's rounds are spread over the whole time span, so both windows hold a part of each;
+    # operation counters of a communicator follow the time order
+    events = []
+    for g, (comm, rounds, nbytes) in enumerate(plan):
+        for j in range(rounds):
+            events.append((T0 + (j * span) // rounds + g, comm, nbytes))
+    events.sort()
+    seq_next = {0: 0, 1: 0}
+    for t, comm, nbytes in events:
+        members = [0, 1, 2, 3, 4, 5] if comm == 0 else [0, 2, 4]
+        s = seq_next[comm]
+        seq_next[comm] += 1
+        base = 50_000 + int(rng.integers(0, 2_000))
+        slow = members[int(rng.integers(0, len(members)))] if rng.random() < 0.002 else -1   # one rank several times slower
+        for r in members:
+            te = t + int(rng.integers(0, 1_000))
+            d = base * (8 if r == slow else 1) + int(rng.integers(0, 500))
+            rows.append((r, comm, s, 0, nbytes, te, te + d))
+    cols = toy_cols(rows)
+    order = np.argsort(cols["t_enter"], kind="stable")
+    half = len(rows) // 2
+    an = ccld.Analyzer(topo, max_window_records=len(rows), tbase_rounds=50, tbase_warmup_ns=10**12)
+    o = orc.Oracle(topo, dict(tbase_rounds=50, tbase_warmup_ns=10**12))
+    seen_long = False
+    for w, sel in enumerate([order[:half], order[half:]]):
+        sel = sel[rng.permutation(len(sel))]
+        sl = {k: v[sel] for k, v in cols.items()}
+        an.reset_window()
+        an.ingest(an.to_device(sl))
+        g = an.analyze_window(FAR, n_records=len(sel), per_record=True)
+        ref = o.analyze_window(sl, FAR)
+        blame, order_ = an.rank_blame()
+        compare(g, ref, blame, order_, what=f"long-groups window{w}")
+        seen_long = seen_long or int(ref.group["n_usable"].max()) > 4096
+        assert int(ref.group["slow"].sum()) >= 1
+    assert seen_long
+    an.close()
