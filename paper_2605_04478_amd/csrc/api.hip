@@ -464,13 +464,12 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   c->prof.begin();
   launch_keys_pass(st, skey, n, c->sf, c->topo, c->blame, c->tile_heads, c->counters);
   launch_scan_tiles(st, c->tile_heads, seg_tiles, &c->counters[CNT_NSEG]);
-  c->prof.end(CCLD_PROF_SEG_HEADS);
   // the number of collectives is known here; it comes back while the statistics kernels run
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipEventRecord(c->ev_heads, st));
-  c->prof.begin();
+  c->prof.split(CCLD_PROF_SEG_HEADS);          // one event ends a timed span and begins the next
   launch_seg_analyze(st, sa);
-  c->prof.end(CCLD_PROF_SEGMENTS);
+  c->prof.split(CCLD_PROF_SEGMENTS);
   HIP_TRY(hipEventSynchronize(c->ev_heads));
   if (c->h_pinned[CNT_STATUS]) {
     const uint64_t bad = c->h_pinned[CNT_STATUS];
@@ -486,9 +485,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   fa.member_off = c->topo.member_off; fa.members_sorted = c->topo.members_sorted;
   fa.tile_flags = c->tile_flags; fa.flag_pos = c->flag_pos; fa.flag = o->flag; fa.flag_cap = o->flag_cap;
   fa.counters = c->counters;
-  c->prof.begin();
   launch_flag_compact(st, fa);
-  c->prof.end(CCLD_PROF_FLAGS);
   if (o->perm) launch_perm(st, sidx, c->win_row, n, c->batch_seqno.empty() ? 0u : c->batch_seqno[0], o->perm);
 
   // 4. hang alerts: which collectives
@@ -499,9 +496,9 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   aa.sf = c->sf; aa.topo = c->topo; aa.tile_counts = c->tile_heads; aa.alert_list = c->alert_list;
   aa.alert_ncand = c->alert_ncand; aa.alert = o->alert; aa.alert_cap = o->alert_cap; aa.cand = o->cand;
   aa.cand_cap = o->cand_cap; aa.counters = c->counters;
-  c->prof.begin();
+  c->prof.split(CCLD_PROF_FLAGS);
   launch_alert_select(st, aa);
-  c->prof.end(CCLD_PROF_ALERTS);
+  c->prof.split(CCLD_PROF_ALERTS);
 
   // 5. slow detection and location per detection group (Eq. 1-4): every collective of the table is keyed
   //    (those that take no part sort behind the groups), and the evaluation reads the numbers of groups and of
@@ -518,7 +515,6 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   ga.range_c = c->big_ex;       // free again once the collectives have been analysed
   if (seg_rows) {
     const uint64_t no_group = (uint64_t)c->topo.n_comms * CCLD_OP_MAX * GROUP_CLS;     // one past every group key
-    c->prof.begin();
     launch_group_keys(st, ga, no_group);
     KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = seg_rows; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0; gs.lo_sub = 0;
     // sort C -> buffers {other main, C}: the first pass reads C and writes buffer 0, so C is free again for pass 2
@@ -526,8 +522,8 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
     if (r3 < 0) return o->status = CCLD_E_HIP;
     launch_group_heads(st, sb2.key[r3], seg_rows, no_group, c->tile_flags, c->group_first, c->counters);
     launch_group_eval(st, ga, sb2.key[r3], sb2.idx[r3], c->group_first, c->group_long);
-    c->prof.end(CCLD_PROF_GROUPS);
   }
+  c->prof.end(CCLD_PROF_GROUPS);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));

@@ -12,9 +12,9 @@ struct Profiler {
   bool on = false;
   hipStream_t st = nullptr;
   std::vector<hipEvent_t> pool;
-  struct Span { int cls; size_t e0; };
+  struct Span { int cls; size_t e0, e1; };
   std::vector<Span> spans;
-  size_t used = 0;
+  size_t used = 0, cur = 0;
   double ms[PROF_NCLASS] = {0};
   uint64_t cnt[PROF_NCLASS] = {0};
 
@@ -29,18 +29,26 @@ struct Profiler {
     on = want;
     return true;
   }
-  void begin() { if (on && used + 2 <= pool.size()) (void)hipEventRecord(pool[used], st); }
+  bool room() const { return on && used + 2 <= pool.size(); }
+  void begin() { if (room()) { (void)hipEventRecord(pool[used], st); cur = used++; } }
   void end(int cls) {
-    if (!on || used + 2 > pool.size()) return;
-    (void)hipEventRecord(pool[used + 1], st);
-    spans.push_back({cls, used});
-    used += 2;
+    if (!room()) return;
+    (void)hipEventRecord(pool[used], st);
+    spans.push_back({cls, cur, used});
+    ++used;
+  }
+  // ends the current span and begins the next one with a single event
+  void split(int cls) {
+    if (!room()) return;
+    (void)hipEventRecord(pool[used], st);
+    spans.push_back({cls, cur, used});
+    cur = used++;
   }
   // after the stream has been synchronised
   void collect() {
     for (const Span& s : spans) {
       float t = 0;
-      if (hipEventElapsedTime(&t, pool[s.e0], pool[s.e0 + 1]) == hipSuccess) { ms[s.cls] += t; cnt[s.cls] += 1; }
+      if (hipEventElapsedTime(&t, pool[s.e0], pool[s.e1]) == hipSuccess) { ms[s.cls] += t; cnt[s.cls] += 1; }
     }
     spans.clear(); used = 0;
   }

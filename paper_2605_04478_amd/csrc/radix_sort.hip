@@ -329,9 +329,9 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src_in, uint32_t n, co
       if (first) hipLaunchKernelGGL((k_radix_hist<true, 2>), dim3((n_tiles + 1) / 2), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
       else hipLaunchKernelGGL((k_radix_hist<false, 2>), dim3((n_tiles + 1) / 2), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
     }
-    if (prof) { prof->end(cls_hist); prof->begin(); }
+    if (prof) prof->split(cls_hist);
     hipLaunchKernelGGL(k_radix_scan, dim3(dmask + 1), dim3(SORT_THREADS), 0, stream, buf.table, buf.totals, n_tiles);
-    if (prof) { prof->end(cls_scan); prof->begin(); }
+    if (prof) prof->split(cls_scan);
     const u64* kin = first ? nullptr : buf.key[cur];
     const u32* iin = first ? nullptr : buf.idx[cur];
     if (!packed) {
