@@ -326,8 +326,8 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src_in, uint32_t n, co
       if (first) hipLaunchKernelGGL((k_radix_hist<true, 8>), dim3((n_tiles + 7) / 8), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
       else hipLaunchKernelGGL((k_radix_hist<false, 8>), dim3((n_tiles + 7) / 8), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
     } else {
-      if (first) hipLaunchKernelGGL((k_radix_hist<true, 2>), dim3((n_tiles + 1) / 2), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
-      else hipLaunchKernelGGL((k_radix_hist<false, 2>), dim3((n_tiles + 1) / 2), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
+      if (first) hipLaunchKernelGGL((k_radix_hist<true, 1>), dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
+      else hipLaunchKernelGGL((k_radix_hist<false, 1>), dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
     }
     if (prof) prof->split(cls_hist);
     hipLaunchKernelGGL(k_radix_scan, dim3(dmask + 1), dim3(SORT_THREADS), 0, stream, buf.table, buf.totals, n_tiles);
