@@ -325,9 +325,10 @@ ccld_status ccld_reset_frames(ccld_ctx *ctx);
 ccld_status ccld_rank_blame(ccld_ctx *ctx, int64_t *blame, uint32_t *order);
 
 /* Optional timing of the library's kernels with HIP events recorded on the context's stream, by
- * kernel class.  ccld_profile_enable(ctx, 1) clears the accumulators and starts timing every
- * following call; ccld_profile_read copies the accumulated milliseconds and launch counts
- * (host arrays of CCLD_PROF_NCLASS entries). */
+ * kernel class.  ccld_profile_enable(ctx, 1) clears the accumulators and starts timing every class
+ * in the following calls; ccld_profile_enable(ctx, 2 + class) times that one class only (every
+ * event record costs several microseconds on the stream); 0 stops.  ccld_profile_read copies the
+ * accumulated milliseconds and launch counts (host arrays of CCLD_PROF_NCLASS entries). */
 enum { CCLD_PROF_INGEST, CCLD_PROF_SORT_HIST, CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER, CCLD_PROF_SEGMENTS,
        CCLD_PROF_FLAGS, CCLD_PROF_BLAME, CCLD_PROF_GROUPS, CCLD_PROF_ALERTS, CCLD_PROF_HANG,
        CCLD_PROF_SEG_HEADS,

@@ -367,8 +367,11 @@ class Analyzer:
                 order.cpu().numpy().astype(np.int64))
 
     # ---- kernel timing ------------------------------------------------------------------
-    def profile_enable(self, on: bool = True) -> None:
-        self._check(self.L.ccld_profile_enable(self._ctx, 1 if on else 0), "ccld_profile_enable")
+    def profile_enable(self, on: bool = True, only: Optional[str] = None) -> None:
+        """Times every kernel class, or (only=<class name>) that one class: each event record costs a few
+        microseconds on the stream."""
+        mode = 0 if not on else (1 if only is None else 2 + PROF_CLASSES.index(only))
+        self._check(self.L.ccld_profile_enable(self._ctx, mode), "ccld_profile_enable")
 
     def profile_read(self):
         """-> ({class: (milliseconds, launches)}, passes of the last main sort)"""

@@ -366,7 +366,7 @@ ccld_status ccld_ingest(ccld_ctx* c, const ccld_records* b, uint64_t n) {
   a.cap = (uint32_t)c->cap;
   a.table = c->ing_table; a.bucket_base = c->ing_base; a.scratch_total = &c->counters[CNT_COUNT - 1];
   a.n_buckets = c->n_buckets; a.bshift = c->bshift; a.seqno0 = (uint32_t)c->total_ingested;
-  c->prof.begin();
+  c->prof.begin(CCLD_PROF_INGEST);
   launch_ingest(c->stream, a, c->topo, c->kf);
   c->prof.end(CCLD_PROF_INGEST);
   HIP_TRY(hipGetLastError());
@@ -461,15 +461,15 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   sa.lag_floor = c->p.lag_floor_ns; sa.kmad_num = c->p.kmad_num; sa.kmad_den = c->p.kmad_den;
   sa.barrier_bytes = c->p.barrier_bytes; sa.max_size = c->max_comm_size;
   const uint32_t seg_tiles = (n + SEG_TILE - 1) / SEG_TILE;
-  c->prof.begin();
+  c->prof.begin(CCLD_PROF_SEG_HEADS);
   launch_keys_pass(st, skey, n, c->sf, c->topo, c->blame, c->tile_heads, c->counters);
   launch_scan_tiles(st, c->tile_heads, seg_tiles, &c->counters[CNT_NSEG]);
   // the number of collectives is known here; it comes back while the statistics kernels run
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipEventRecord(c->ev_heads, st));
-  c->prof.split(CCLD_PROF_SEG_HEADS);          // one event ends a timed span and begins the next
+  c->prof.split(CCLD_PROF_SEG_HEADS, CCLD_PROF_SEGMENTS);          // one event ends a timed span and begins the next
   launch_seg_analyze(st, sa);
-  c->prof.split(CCLD_PROF_SEGMENTS);
+  c->prof.split(CCLD_PROF_SEGMENTS, CCLD_PROF_FLAGS);
   HIP_TRY(hipEventSynchronize(c->ev_heads));
   if (c->h_pinned[CNT_STATUS]) {
     const uint64_t bad = c->h_pinned[CNT_STATUS];
@@ -496,9 +496,9 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   aa.sf = c->sf; aa.topo = c->topo; aa.tile_counts = c->tile_heads; aa.alert_list = c->alert_list;
   aa.alert_ncand = c->alert_ncand; aa.alert = o->alert; aa.alert_cap = o->alert_cap; aa.cand = o->cand;
   aa.cand_cap = o->cand_cap; aa.counters = c->counters;
-  c->prof.split(CCLD_PROF_FLAGS);
+  c->prof.split(CCLD_PROF_FLAGS, CCLD_PROF_ALERTS);
   launch_alert_select(st, aa);
-  c->prof.split(CCLD_PROF_ALERTS);
+  c->prof.split(CCLD_PROF_ALERTS, CCLD_PROF_GROUPS);
 
   // 5. slow detection and location per detection group (Eq. 1-4): every collective of the table is keyed
   //    (those that take no part sort behind the groups), and the evaluation reads the numbers of groups and of
@@ -537,7 +537,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   // 6. blame: flags keyed by rank, sorted, one workgroup per rank sums its run
   if (n_flag) {
     uint64_t* bk = c->keyC;       // keys are written to C, first pass sorts C -> buffer 0 of sb2
-    c->prof.begin();
+    c->prof.begin(CCLD_PROF_BLAME);
     launch_blame_keys(st, skey, c->flag_pos, n_flag, c->sf, c->topo, bk);
     KeySource bs; bs.key = bk; bs.head = 0; bs.cap = n_flag; bs.squeeze = 0; bs.hi_shift = 0; bs.lo_bits = 0; bs.lo_mask = 0; bs.lo_sub = 0;
     const int r2 = radix_sort_pairs(st, bs, n_flag, sb2, c->rank_bits);
@@ -548,7 +548,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   }
   // 7. hang alerts: candidates of every alert
   if (o->n_alert) {
-    c->prof.begin();
+    c->prof.begin(CCLD_PROF_ALERTS);
     launch_alert_candidates(st, aa, (uint32_t)o->n_alert);
     c->prof.end(CCLD_PROF_ALERTS);
     HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
@@ -579,7 +579,8 @@ ccld_status ccld_rank_blame(ccld_ctx* c, int64_t* blame, uint32_t* order) {
 ccld_status ccld_profile_enable(ccld_ctx* c, int32_t on) {
   if (!c) return CCLD_E_NULL;
   HIP_TRY(hipStreamSynchronize(c->stream));
-  return c->prof.enable(c->stream, on != 0) ? CCLD_OK : CCLD_E_HIP;
+  if (on < 0 || on >= 2 + CCLD_PROF_NCLASS) return CCLD_E_BAD_ARG;
+  return c->prof.enable(c->stream, on != 0, on >= 2 ? on - 2 : -1) ? CCLD_OK : CCLD_E_HIP;
 }
 
 ccld_status ccld_profile_read(ccld_ctx* c, double* ms, uint64_t* launches, uint64_t* sort_passes) {

@@ -607,7 +607,7 @@ static hipError_t place_snapshots(ccld_ctx* c, const ccld_snapshots* sn, uint64_
   a.cand = c->h_cand; a.layer_max = c->h_layer_max; a.counters = c->counters;
   a.stall_snapshots = c->p.stall_snapshots; a.fifo_depth = c->p.fifo_depth;
 
-  c->prof.begin();
+  c->prof.begin(CCLD_PROF_HANG);
   if ((e = hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st)) != hipSuccess) return e;
   if ((e = hipMemsetAsync(c->h_cnt, 0, sizeof(uint32_t) * ((n_cell + 31) / 32), st)) != hipSuccess) return e;
   if (n_rows) {
@@ -762,7 +762,7 @@ extern "C" ccld_status ccld_decode_frames(ccld_ctx* c, const ccld_frames* fr, co
   }
   a.n_frames = fr->n_frames; a.n_ch = fr->n_channels; a.snap = fr->snapshot; a.mb = c->kf.mb; a.T = c->topo;
   a.n_members = c->n_members; a.last = c->f_last; a.seen = c->f_seen; a.counters = c->counters;
-  c->prof.begin();
+  c->prof.begin(CCLD_PROF_HANG);
   HIP_TRY(hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st));
   HIP_TRY(hipMemsetAsync(c->f_seen, 0, sizeof(uint32_t) * (c->topo.n_ranks / 32 + 1), st));
   const uint32_t fblocks = (uint32_t)((fr->n_frames + 3) / 4);

@@ -15,11 +15,14 @@ struct Profiler {
   struct Span { int cls; size_t e0, e1; };
   std::vector<Span> spans;
   size_t used = 0, cur = 0;
+  bool open = false;
+  int only = -1;             // -1: every class
   double ms[PROF_NCLASS] = {0};
   uint64_t cnt[PROF_NCLASS] = {0};
 
-  bool enable(hipStream_t stream, bool want) {
+  bool enable(hipStream_t stream, bool want, int only_class = -1) {
     st = stream;
+    only = only_class; open = false;
     for (int i = 0; i < PROF_NCLASS; ++i) { ms[i] = 0; cnt[i] = 0; }
     spans.clear(); used = 0;
     if (want && pool.empty()) {
@@ -30,19 +33,33 @@ struct Profiler {
     return true;
   }
   bool room() const { return on && used + 2 <= pool.size(); }
-  void begin() { if (room()) { (void)hipEventRecord(pool[used], st); cur = used++; } }
+  bool wanted(int cls) const { return only < 0 || cls == only; }
+  // A span is timed if its class is wanted (every class, or the one class asked for: a record costs
+  // several microseconds on the stream, so a caller that needs one class does not pay for the others).
+  void begin(int cls) {
+    open = false;
+    if (!room() || !wanted(cls)) return;
+    (void)hipEventRecord(pool[used], st);
+    cur = used++;
+    open = true;
+  }
   void end(int cls) {
-    if (!room()) return;
+    if (!open || !room()) { open = false; return; }
     (void)hipEventRecord(pool[used], st);
     spans.push_back({cls, cur, used});
     ++used;
+    open = false;
   }
-  // ends the current span and begins the next one with a single event
-  void split(int cls) {
-    if (!room()) return;
+  // ends the span of cls_end and begins the span of cls_next with a single event
+  void split(int cls_end, int cls_next) {
+    const bool need_end = open, need_begin = wanted(cls_next);
+    if (!need_end && !need_begin) return;
+    if (!room()) { open = false; return; }
     (void)hipEventRecord(pool[used], st);
-    spans.push_back({cls, cur, used});
-    cur = used++;
+    if (need_end) spans.push_back({cls_end, cur, used});
+    open = need_begin;
+    if (need_begin) cur = used;
+    ++used;
   }
   // after the stream has been synchronised
   void collect() {

@@ -320,7 +320,7 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src_in, uint32_t n, co
     // digit position inside the word each kernel looks at
     const int hist_shift = done_bits + ((packed && !first) ? ibits : 0);
     const int scat_shift = done_bits + (packed ? ibits : 0);
-    if (prof && first) prof->begin();
+    if (prof && first) prof->begin(cls_hist);
     const u64* hin = first ? nullptr : buf.key[cur];
     if (n_tiles >= SORT_STREAM_TILES) {
       if (first) hipLaunchKernelGGL((k_radix_hist<true, 8>), dim3((n_tiles + 7) / 8), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
@@ -329,9 +329,9 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src_in, uint32_t n, co
       if (first) hipLaunchKernelGGL((k_radix_hist<true, 1>), dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
       else hipLaunchKernelGGL((k_radix_hist<false, 1>), dim3(n_tiles), dim3(SORT_THREADS), 0, stream, src, hin, buf.table, n, n_tiles, hist_shift, dmask);
     }
-    if (prof) prof->split(cls_hist);
+    if (prof) prof->split(cls_hist, cls_scan);
     hipLaunchKernelGGL(k_radix_scan, dim3(dmask + 1), dim3(SORT_THREADS), 0, stream, buf.table, buf.totals, n_tiles);
-    if (prof) prof->split(cls_scan);
+    if (prof) prof->split(cls_scan, cls_scatter);
     const u64* kin = first ? nullptr : buf.key[cur];
     const u32* iin = first ? nullptr : buf.idx[cur];
     if (!packed) {
@@ -342,7 +342,7 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src_in, uint32_t n, co
       else if (!last) launch_scatter<IN_PACKED, OUT_PACKED>(stream, src, kin, iin, buf.key[out], buf.idx[out], buf, n, n_tiles, scat_shift, nb, ibits);
       else launch_scatter<IN_PACKED, OUT_PAIR>(stream, src, kin, iin, buf.key[out], buf.idx[out], buf, n, n_tiles, scat_shift, nb, ibits);
     }
-    if (prof) { if (last) prof->end(cls_scatter); else prof->split(cls_scatter); }
+    if (prof) { if (last) prof->end(cls_scatter); else prof->split(cls_scatter, cls_hist); }
     if (hipGetLastError() != hipSuccess) return -1;
     done_bits += nb;
     cur = out;
