@@ -311,8 +311,9 @@ int radix_sort_pairs(hipStream_t stream, const KeySource& src_in, uint32_t n, co
   const bool packed = passes >= 2 && bits + ibits <= 64;
   int done_bits = 0, cur = -1;
   for (int p = 0; p < passes; ++p) {
-    // spread the bits evenly over the passes
-    int left = bits - done_bits, nb = bits <= 0 ? 1 : (left + (passes - p) - 1) / (passes - p);
+    // spread the bits evenly over the passes, the narrower digits first (the first pass also squeezes the
+    // keys and is the slowest: fewer digit values mean longer runs in its scatter)
+    int left = bits - done_bits, nb = bits <= 0 ? 1 : left / (passes - p);
     if (nb < 1) nb = 1;
     const u32 dmask = (1u << nb) - 1u;
     const int out = cur < 0 ? 0 : 1 - cur;
