@@ -43,14 +43,16 @@ template <int M>
 __device__ __forceinline__ u32 xor_lane_u32(u32 v) {
 #if CCLD_USE_DPP
   const int s = (int)v;
-  if constexpr (M == 1) return (u32)__builtin_amdgcn_update_dpp(s, s, 0xB1, 0xF, 0xF, false);        // quad_perm [1,0,3,2]
-  else if constexpr (M == 2) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
-  else if constexpr (M == 3) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x1B, 0xF, 0xF, false);   // quad_perm [3,2,1,0]
-  else if constexpr (M == 7) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x141, 0xF, 0xF, false);  // row_half_mirror
-  else if constexpr (M == 15) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x140, 0xF, 0xF, false); // row_mirror
-  else if constexpr (M == 8) return (u32)__builtin_amdgcn_update_dpp(s, s, 0x128, 0xF, 0xF, false);  // row_ror:8
+  // every lane of these patterns reads a valid lane, so no previous value has to be kept: the plain
+  // DPP move needs no copy of the destination first
+  if constexpr (M == 1) return (u32)__builtin_amdgcn_mov_dpp(s, 0xB1, 0xF, 0xF, true);        // quad_perm [1,0,3,2]
+  else if constexpr (M == 2) return (u32)__builtin_amdgcn_mov_dpp(s, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+  else if constexpr (M == 3) return (u32)__builtin_amdgcn_mov_dpp(s, 0x1B, 0xF, 0xF, true);   // quad_perm [3,2,1,0]
+  else if constexpr (M == 7) return (u32)__builtin_amdgcn_mov_dpp(s, 0x141, 0xF, 0xF, true);  // row_half_mirror
+  else if constexpr (M == 15) return (u32)__builtin_amdgcn_mov_dpp(s, 0x140, 0xF, 0xF, true); // row_mirror
+  else if constexpr (M == 8) return (u32)__builtin_amdgcn_mov_dpp(s, 0x128, 0xF, 0xF, true);  // row_ror:8
   else if constexpr (M == 4) {
-    int t = __builtin_amdgcn_update_dpp(s, s, 0x104, 0xF, 0x5, false);    // banks 0,2 read lane + 4 (row_shl:4)
+    int t = __builtin_amdgcn_mov_dpp(s, 0x104, 0xF, 0x5, true);           // banks 0,2 read lane + 4 (row_shl:4)
     t = __builtin_amdgcn_update_dpp(t, s, 0x114, 0xF, 0xA, false);        // banks 1,3 read lane - 4 (row_shr:4)
     return (u32)t;
   } else
