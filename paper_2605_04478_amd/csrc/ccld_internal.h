@@ -68,7 +68,8 @@ constexpr int GROUP_SLOTS = CCLD_OP_MAX * GROUP_CLS;
 
 // status bits accumulated on the device
 enum { DS_UNKNOWN_COMM = 1, DS_NOT_MEMBER = 2, DS_RANGE = 4, DS_KEY_WIDTH = 8, DS_DUPLICATE = 16,
-       DS_SNAPSHOT_GAP = 32 };
+       DS_SNAPSHOT_GAP = 32,
+       DS_SUSPECT = 64 };   // snapshot grid placed without the presence bitmap: a cell still holds the fill pattern
 
 struct BatchSlot { uint64_t n; };
 

@@ -28,6 +28,8 @@ struct HangArgs {
   // grid
   u64* cell;          // [n_members * n_ch * n_snap][2]
   u32* cnt;           // presence bitmap, one bit per cell
+  int exact;          // 1: the bitmap is kept (duplicates and gaps told apart); 0: cells start from an all-ones fill and a
+                      //    cell that still holds it is suspect
   // tables
   i64* pair;          // [CCLD_HPAIR_NCOL][n_members]
   i64* hcomm;         // [CCLD_HCOMM_NCOL][n_comms]
@@ -50,7 +52,16 @@ __device__ __forceinline__ int slot_of(const DeviceTopology& T, u32 c, u32 r) {
   return -1;
 }
 
+// Status of one cell as the per-member passes read it.  With the bitmap: its bit.  Without: a cell that still
+// holds the all-ones fill was (almost certainly) never written; the caller then repeats the placement with the
+// bitmap, which tells a gap from a duplicate and from a row that really holds that pattern.
+__device__ __forceinline__ u64 cell_status(const HangArgs& a, u64 cell, u64 w0, u64 w1) {
+  if (a.exact) return ((a.cnt[cell >> 5] >> (cell & 31)) & 1u) ? 0 : (u64)DS_SNAPSHOT_GAP;
+  return (w0 == ~0ull && w1 == ~0ull) ? (u64)DS_SUSPECT : 0;
+}
+
 // ---- place every row in its cell ------------------------------------------------------------
+template <bool EXACT>
 __global__ __launch_bounds__(256) void k_hang_place(HangArgs a) {
   constexpr int U = 4;               // rows per thread in flight
   u64 status = 0;
@@ -98,9 +109,11 @@ __global__ __launch_bounds__(256) void k_hang_place(HangArgs a) {
       if (ch[u] >= a.n_ch || sn[u] >= a.n_snap) { status |= DS_RANGE; continue; }
       const u64 k = (((u64)a.T.member_off[c[u]] + (u32)slot) * a.n_ch + ch[u]) * a.n_snap + sn[u];
       cell2[k] = make_ulonglong2(sq[u], (u64)se[u] | ((u64)rv[u] << 32));
-      // presence bitmap (one bit per cell: small enough to stay in cache); a bit already set is a duplicate
-      const u32 bit = 1u << (k & 31);
-      if (atomicOr(&a.cnt[k >> 5], bit) & bit) status |= DS_DUPLICATE;
+      if (EXACT) {
+        // presence bitmap (one bit per cell: small enough to stay in cache); a bit already set is a duplicate
+        const u32 bit = 1u << (k & 31);
+        if (atomicOr(&a.cnt[k >> 5], bit) & bit) status |= DS_DUPLICATE;
+      }
     }
   }
   u64 st = status;
@@ -133,8 +146,9 @@ __global__ __launch_bounds__(256) void k_hang_pairs(HangArgs a) {
       const u32 s = s0 + lane;
       bool diff = false;
       if (s < a.n_snap) {
-        diff = a.cell[2 * (base + s)] != sL0 || a.cell[2 * (base + s) + 1] != sL1;
-        if (((a.cnt[(base + s) >> 5] >> ((base + s) & 31)) & 1u) == 0) status |= DS_SNAPSHOT_GAP;
+        const u64 w0 = a.cell[2 * (base + s)], w1 = a.cell[2 * (base + s) + 1];
+        diff = w0 != sL0 || w1 != sL1;
+        status |= cell_status(a, base + s, w0, w1);
       }
       const u64 m = ballot64(diff);
       if (m) last_diff = s0 + (64 - (u32)__clzll((long long)m));
@@ -384,7 +398,7 @@ __global__ __launch_bounds__(256) void k_rate_pairs(HangArgs a) {
       u64 seq = 0, cnt = 0;
       if (in) {
         seq = a.cell[2 * (base + s)]; cnt = a.cell[2 * (base + s) + 1];
-        if (((a.cnt[(base + s) >> 5] >> ((base + s) & 31)) & 1u) == 0) status |= DS_SNAPSHOT_GAP;
+        status |= cell_status(a, base + s, seq, cnt);
       }
       u64 pseq = shfl_u64(seq, (int)lane - 1), pcnt = shfl_u64(cnt, (int)lane - 1);
       if (lane == 0) { pseq = c_seq; pcnt = c_cnt; }
@@ -585,7 +599,7 @@ static ccld_status hang_status(uint64_t bits) {
 
 // Stages host-resident rows, clears the grid's presence counts and places every row in its cell.
 static hipError_t place_snapshots(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, uint64_t n_cell,
-                                  HangArgs& a) {
+                                  HangArgs& a, bool exact) {
   hipStream_t st = c->stream;
   std::memset(&a, 0, sizeof(a));
   hipError_t e = hipSuccess;
@@ -609,10 +623,14 @@ static hipError_t place_snapshots(ccld_ctx* c, const ccld_snapshots* sn, uint64_
 
   c->prof.begin(CCLD_PROF_HANG);
   if ((e = hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st)) != hipSuccess) return e;
-  if ((e = hipMemsetAsync(c->h_cnt, 0, sizeof(uint32_t) * ((n_cell + 31) / 32), st)) != hipSuccess) return e;
+  a.exact = exact ? 1 : 0;
+  if (exact) e = hipMemsetAsync(c->h_cnt, 0, sizeof(uint32_t) * ((n_cell + 31) / 32), st);
+  else e = hipMemsetAsync(c->h_cell, 0xFF, 16 * n_cell, st);
+  if (e != hipSuccess) return e;
   if (n_rows) {
     uint64_t g = (n_rows + 255) / 256; if (g > 4096) g = 4096;
-    hipLaunchKernelGGL(k_hang_place, dim3((uint32_t)g), dim3(256), 0, st, a);
+    if (exact) hipLaunchKernelGGL(k_hang_place<true>, dim3((uint32_t)g), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(k_hang_place<false>, dim3((uint32_t)g), dim3(256), 0, st, a);
   }
   return hipSuccess;
 }
@@ -630,12 +648,20 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
   hipStream_t st = c->stream;
 
   HangArgs a;
-  HIP_TRY(place_snapshots(c, sn, n_rows, n_cell, a));
   const uint32_t nm = (uint32_t)c->n_members;
-  hipLaunchKernelGGL(k_hang_pairs, dim3((nm + 3) / 4), dim3(256), 0, st, a);
-  HIP_TRY(hipGetLastError());
-  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
+  // One row per cell is the normal case: the rows are placed without the presence bitmap (its atomics are a
+  // third of the placement's time) and the per-member pass looks for cells that nobody wrote.  If it finds one
+  // and no row was refused for a worse reason, or if the row count already rules the normal case out, the
+  // placement is repeated with the bitmap, which tells duplicates from gaps.
+  for (bool exact = n_rows != n_cell;; exact = true) {
+    HIP_TRY(place_snapshots(c, sn, n_rows, n_cell, a, exact));
+    hipLaunchKernelGGL(k_hang_pairs, dim3((nm + 3) / 4), dim3(256), 0, st, a);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (exact || c->h_pinned[CNT_STATUS] != (uint64_t)DS_SUSPECT) break;
+    c->prof.end(CCLD_PROF_HANG);
+  }
   if (c->h_pinned[CNT_STATUS]) { c->prof.end(CCLD_PROF_HANG); c->prof.collect(); return o->status = hang_status(c->h_pinned[CNT_STATUS]); }
 
   hipLaunchKernelGGL(k_hang_comm, dim3(c->topo.n_comms), dim3(256), 0, st, a);
@@ -695,12 +721,16 @@ extern "C" ccld_status ccld_progress_rates(ccld_ctx* c, const ccld_snapshots* sn
   if (n_cell > c->snap_cap || n_rows > c->snap_cap) return o->status = CCLD_E_CAPACITY;
   hipStream_t st = c->stream;
   HangArgs a;
-  HIP_TRY(place_snapshots(c, sn, n_rows, n_cell, a));
   const uint32_t nm = (uint32_t)c->n_members;
-  if (nm) hipLaunchKernelGGL(k_rate_pairs, dim3((nm + 3) / 4), dim3(256), 0, st, a);
-  HIP_TRY(hipGetLastError());
-  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
+  for (bool exact = n_rows != n_cell;; exact = true) {       // see ccld_locate_hang
+    HIP_TRY(place_snapshots(c, sn, n_rows, n_cell, a, exact));
+    if (nm) hipLaunchKernelGGL(k_rate_pairs, dim3((nm + 3) / 4), dim3(256), 0, st, a);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (exact || c->h_pinned[CNT_STATUS] != (uint64_t)DS_SUSPECT) break;
+    c->prof.end(CCLD_PROF_HANG);
+  }
   if (c->h_pinned[CNT_STATUS]) { c->prof.end(CCLD_PROF_HANG); c->prof.collect(); return o->status = hang_status(c->h_pinned[CNT_STATUS]); }
   if (c->topo.n_comms) hipLaunchKernelGGL(k_rate_comm, dim3(c->topo.n_comms), dim3(256), 0, st, a, c->rate_root);
   o->n_pair = c->n_members;

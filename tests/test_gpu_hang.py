@@ -98,3 +98,13 @@ def test_too_few_snapshots_parity():
     cols = snap_rows(topo, 4, 1, lambda s, c, q, ch: (1, q, 0))
     run_both(topo, cols, 4, 1, what="few3", stall_snapshots=3)
     run_both(topo, cols, 4, 1, what="few4", stall_snapshots=4)
+
+
+def test_a_row_that_holds_the_fill_pattern_is_still_a_row():
+    """The quick placement starts the grid from an all-ones fill and takes a cell that still holds it for an
+    empty one; a real row with exactly that content makes it repeat the placement with the presence bitmap."""
+    topo = ring_topology(3)
+    full = (2**64 - 1, 2**32 - 1, 2**32 - 1)
+    state = lambda s, c, q, ch: full if (s == 2 and q == 1 and ch == 0) else (7 + (s > 4), 3 + s, 2 + s)
+    g, o = run_both(topo, snap_rows(topo, 9, 2, state), 9, 2, what="all-ones-row", stall_snapshots=3)
+    assert g.status == "OK"
