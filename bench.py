@@ -58,6 +58,19 @@ def measured_traffic(kernel: str):
         return None
 
 
+def measured_step_traffic():
+    """HBM bytes of one whole step (every kernel of the counter runs times its launches per step), or None if the
+    kernels have changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "window_config3_traffic.json")
+    try:
+        rec = json.load(open(path))
+        if rec.get("csrc_sha256") != kernel_sources_digest():
+            return None
+        return sum((k["fetch_bytes"] + k["write_bytes"]) * k["launches"] for k in rec["kernels"].values())
+    except (OSError, ValueError, KeyError):
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -246,6 +259,14 @@ def main() -> int:
     kname = {"ingest": "k_ingest", "sort_hist": "k_radix_hist", "sort_scatter": "k_radix_scatter",
              "seg_heads": "k_keys_pass", "segments": "k_seg_wave"}[dominant]
     traffic = measured_traffic(kname)
+    # the whole step against the HBM peak: algorithmic bytes of the priced classes, and the counted traffic
+    step_alg = sum(alg[k] for k in alg if k in kernels)
+    step_traffic = measured_step_traffic()
+    whole_step = {"algorithmic_bytes": step_alg, "algorithmic_GBps": round(step_alg / (ms_per_step * 1e-3) / 1e9, 1),
+                  "traffic_bytes": step_traffic,
+                  "traffic_GBps": None if step_traffic is None else round(step_traffic / (ms_per_step * 1e-3) / 1e9, 1),
+                  "traffic_frac_of_peak": None if step_traffic is None
+                  else round(step_traffic / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 3)}
 
     cpu = None
     if not args.no_cpu:
@@ -277,7 +298,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_ms": d_avg_ms, "launches": d_cnt,
-                     "algorithmic_bytes_per_launch": alg_bytes_per_launch},
+                     "algorithmic_bytes_per_launch": alg_bytes_per_launch, "whole_step": whole_step},
         "kernels": kernels,
         "cpu_baseline": cpu,
     }
