@@ -34,6 +34,15 @@ def test_capacity_blame_order_and_profile_calls():
     assert passes >= 1 and prof["segments"][1] >= 1 and prof["segments"][0] > 0
     blame, order = an.rank_blame()
     assert list(blame["n_records"]) == [8, 8, 8, 8] and sorted(order) == [0, 1, 2, 3]
+    # one class only: the others record no event
+    an.profile_enable(True, only="segments")
+    g2 = an.analyze_window(T0 + 10**12)
+    prof, _ = an.profile_read()
+    assert g2.status == "OK" and prof["segments"][1] >= 1
+    assert all(v[1] == 0 for k, v in prof.items() if k != "segments")
+    an.profile_enable(False)
+    dev_blame, dev_order = an.rank_blame(to_host=False)
+    assert dev_blame.shape == (5, 4) and int(dev_blame[4].sum()) == 32 and sorted(dev_order.tolist()) == [0, 1, 2, 3]
     an.reset_window()
     g = an.analyze_window(T0 + 10**12)
     assert g.status == "OK" and g.n_records == 0 and g.n_seg == 0
