@@ -5,6 +5,7 @@
 
 #include "ccld_internal.h"
 #include "window_kernels.h"
+#include "merge.h"
 
 using namespace ccld;
 
@@ -226,6 +227,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   }
   c->n_buckets = ((topo->n_comms - 1) >> c->bshift) + 1;
   c->sorted_buf = 0; c->last_n = 0; c->blame_valid = false; c->sort_passes = 0;
+  c->inc_ok = false; c->inc_head = c->inc_count = c->inc_total = 0;
   c->sf.mb = mb; c->sf.ws = 0; c->sf.seq_base = 0;
   uint64_t n_members = 0;
   check_topology(topo, &n_members);
@@ -323,6 +325,7 @@ ccld_status ccld_destroy(ccld_ctx* c) {
 ccld_status ccld_reset_window(ccld_ctx* c) {
   if (!c) return CCLD_E_NULL;
   c->head = 0; c->count = 0; c->batch_n.clear(); c->batch_slot.clear(); c->batch_seqno.clear();
+  c->inc_ok = false;
   return CCLD_OK;
 }
 
@@ -441,8 +444,46 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   src.lo_bits = mb + ws;
   src.lo_mask = cb > 0 ? (((uint64_t)1 << (64 - cb)) - 1) : ~0ull;      // everything below the communicator field
   src.lo_sub = min_seq << mb;
-  const int sorted = radix_sort_pairs(st, src, n, c->sb, mb + ws + cb, &c->prof, CCLD_PROF_SORT_HIST,
-                                      CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER);
+  // A window of several batches that still holds at least half of the previously analysed window keeps that
+  // window's order: the entries of the batches that left are dropped, the keys are re-based to this window's
+  // format, the new records are sorted on their own and the two sequences are merged.
+  const bool was_ok = c->inc_ok;
+  c->inc_ok = false;
+  const uint64_t cap = std::max<uint64_t>(c->cap, 1);
+  const uint64_t n_new = c->total_ingested - c->inc_total;
+  int sorted = -1;
+  if (was_ok && n_new > 0 && n_new < n && c->inc_sf.mb == mb) {
+    const uint64_t kept = n - n_new;                                     // records of the previous window still here
+    if (kept >= n_new && kept <= c->inc_count) {
+      const uint64_t exp_n = c->inc_count - kept;
+      const uint64_t old_tail = (c->inc_head + c->inc_count) % cap;
+      if ((c->inc_head + exp_n) % cap == c->head && (old_tail + n_new) % cap == (c->head + n) % cap) {
+        const int s = c->sorted_buf;
+        SortBuffers sbn;
+        sbn.key[0] = c->sb.key[1 - s]; sbn.idx[0] = c->sb.idx[1 - s]; sbn.key[1] = c->keyC; sbn.idx[1] = c->idxC;
+        sbn.table = c->table2; sbn.totals = c->totals2;
+        KeySource fresh = src;
+        fresh.head = (uint32_t)old_tail;
+        const int rb = radix_sort_pairs(st, fresh, (uint32_t)n_new, sbn, mb + ws + cb, &c->prof, CCLD_PROF_SORT_HIST,
+                                        CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER);
+        if (rb < 0) return o->status = CCLD_E_HIP;
+        c->prof.begin(CCLD_PROF_SORT_SCATTER);
+        RetainArgs ra;
+        ra.key = c->sb.key[s]; ra.idx = c->sb.idx[s]; ra.n = (uint32_t)c->inc_count; ra.from = c->inc_sf; ra.to = c->sf;
+        ra.exp_lo = (uint32_t)c->inc_head; ra.exp_n = (uint32_t)exp_n; ra.cap = (uint32_t)cap;
+        ra.tile_counts = c->tile_flags; ra.total_out = &c->counters[CNT_NRETAINED];
+        ra.key_out = sbn.key[1 - rb]; ra.idx_out = sbn.idx[1 - rb];
+        launch_retain(st, ra);
+        launch_merge(st, sbn.key[1 - rb], sbn.idx[1 - rb], (uint32_t)kept, sbn.key[rb], sbn.idx[rb], (uint32_t)n_new,
+                     c->tile_flags, c->sb.key[s], c->sb.idx[s]);
+        c->prof.end(CCLD_PROF_SORT_SCATTER);
+        sorted = s;
+      }
+    }
+  }
+  if (sorted < 0)
+    sorted = radix_sort_pairs(st, src, n, c->sb, mb + ws + cb, &c->prof, CCLD_PROF_SORT_HIST,
+                              CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER);
   c->sort_passes = (mb + ws + cb) <= 0 ? 1 : (mb + ws + cb + SORT_RBITS - 1) / SORT_RBITS;
   if (sorted < 0) return o->status = CCLD_E_HIP;
   c->sorted_buf = sorted;
@@ -560,6 +601,9 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   HIP_TRY(hipStreamSynchronize(st));
   c->prof.collect();
   c->blame_valid = true;
+  // the order of this window serves the next analysis (windows of several batches only)
+  c->inc_ok = c->p.window_batches > 1;
+  c->inc_sf = c->sf; c->inc_head = c->head; c->inc_count = n; c->inc_total = c->total_ingested;
   return o->status;
 }
 

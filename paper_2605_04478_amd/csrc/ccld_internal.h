@@ -83,7 +83,8 @@ constexpr int SEL_TILE = 2048;       // records per workgroup of the compaction 
 constexpr int RANKCOUNT_BLOCKS = 2048;
 
 // device counters written by kernels and read back by the host
-enum { CNT_NSEG, CNT_NFLAG, CNT_NBIG, CNT_NUSABLE, CNT_NGROUP, CNT_NALERT, CNT_NCAND, CNT_STATUS, CNT_NBLAMED, CNT_NCLEAN, CNT_NLONG, CNT_COUNT = 16 };
+enum { CNT_NSEG, CNT_NFLAG, CNT_NBIG, CNT_NUSABLE, CNT_NGROUP, CNT_NALERT, CNT_NCAND, CNT_STATUS, CNT_NBLAMED, CNT_NCLEAN, CNT_NLONG,
+       CNT_NRETAINED, CNT_COUNT = 16 };
 constexpr uint32_t GROUP_LONG_MIN = 4096;   // a detection group of more rounds than this gets a whole workgroup
 
 }  // namespace ccld
@@ -153,6 +154,10 @@ struct ccld_ctx {
   uint8_t* h_stage;                   // [snap_cap * 32] device staging for host-resident snapshots
   // last analysis
   int sorted_buf;                     // which ping-pong buffer holds the sorted window
+  // the order of the last analysed window, kept for the next analysis of a window of several batches
+  bool inc_ok;                        // sb.key/idx[sorted_buf] hold it, in format inc_sf
+  ccld::SqueezedFormat inc_sf;
+  uint64_t inc_head, inc_count, inc_total;   // that window's first slot, records, and total_ingested at the time
   uint64_t last_n;
   ccld::SqueezedFormat sf;
   bool blame_valid;

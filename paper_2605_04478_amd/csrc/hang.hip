@@ -647,6 +647,7 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
   if (n_cell > c->snap_cap || n_rows > c->snap_cap) return o->status = CCLD_E_CAPACITY;
   hipStream_t st = c->stream;
 
+  c->inc_ok = false;            // the root list is sorted in the window's sort buffers
   HangArgs a;
   const uint32_t nm = (uint32_t)c->n_members;
   // One row per cell is the normal case: the rows are placed without the presence bitmap (its atomics are a
