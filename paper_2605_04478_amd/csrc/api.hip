@@ -237,6 +237,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   c->h_size.assign(topo->size, topo->size + topo->n_comms);
   c->h_pinned = nullptr;
   c->ev_heads = nullptr;
+  c->ev_flags = nullptr;
 
   // derived host tables: sorted member lists, rank -> communicators CSR
   std::vector<uint32_t> sorted(topo->members, topo->members + n_members), sslot(n_members);
@@ -300,11 +301,14 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
     if (hipHostMalloc((void**)&c->h_pinned, bytes, hipHostMallocDefault) != hipSuccess) rs = CCLD_E_HIP;
   }
   if (hipEventCreateWithFlags(&c->ev_heads, hipEventDisableTiming) != hipSuccess) { c->ev_heads = nullptr; rs = CCLD_E_HIP; }
+  if (hipEventCreateWithFlags(&c->ev_flags, hipEventDisableTiming) != hipSuccess) { c->ev_flags = nullptr; rs = CCLD_E_HIP; }
   if (hipStreamSynchronize(c->stream) != hipSuccess) rs = CCLD_E_HIP;   // host vectors above die at return
   if (rs != CCLD_OK) {
     (void)hipGetLastError();
     if (c->h_pinned) (void)hipHostFree(c->h_pinned);
     if (c->ev_heads) (void)hipEventDestroy(c->ev_heads);
+  if (c->ev_flags) (void)hipEventDestroy(c->ev_flags);
+    if (c->ev_flags) (void)hipEventDestroy(c->ev_flags);
     delete c;
     return rs;
   }
@@ -527,6 +531,10 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   fa.tile_flags = c->tile_flags; fa.flag_pos = c->flag_pos; fa.flag = o->flag; fa.flag_cap = o->flag_cap;
   fa.counters = c->counters;
   launch_flag_compact(st, fa);
+  // the number of flags comes back while the alert and group kernels run
+  uint64_t* h_flags = c->h_pinned + CNT_COUNT;
+  HIP_TRY(hipMemcpyAsync(h_flags, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipEventRecord(c->ev_flags, st));
   if (o->perm) launch_perm(st, sidx, c->win_row, n, c->batch_seqno.empty() ? 0u : c->batch_seqno[0], o->perm);
 
   // 4. hang alerts: which collectives
@@ -566,16 +574,10 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   }
   c->prof.end(CCLD_PROF_GROUPS);
   HIP_TRY(hipGetLastError());
-  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
-  if (c->h_pinned[CNT_STATUS]) { zero_counts(o); return o->status = data_status(c->h_pinned[CNT_STATUS]); }
-  o->n_flag = c->h_pinned[CNT_NFLAG];
-  o->n_alert = c->h_pinned[CNT_NALERT];
-  o->n_group = c->h_pinned[CNT_NGROUP];
-  const uint32_t n_flag = (uint32_t)o->n_flag;
-  if (o->n_seg > o->seg_cap || o->n_flag > o->flag_cap || o->n_group > o->group_cap) o->status = CCLD_W_TRUNCATED;
-
-  // 6. blame: flags keyed by rank, sorted, one workgroup per rank sums its run
+  // 6. blame: flags keyed by rank, sorted, one workgroup per rank sums its run; launched behind the group
+  //    kernels, before the host waits for them
+  HIP_TRY(hipEventSynchronize(c->ev_flags));
+  const uint32_t n_flag = (uint32_t)h_flags[CNT_NFLAG];
   if (n_flag) {
     uint64_t* bk = c->keyC;       // keys are written to C, first pass sorts C -> buffer 0 of sb2
     c->prof.begin(CCLD_PROF_BLAME);
@@ -587,6 +589,14 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
                         c->blame_list, c->blame);
     c->prof.end(CCLD_PROF_BLAME);
   }
+  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (c->h_pinned[CNT_STATUS]) { zero_counts(o); return o->status = data_status(c->h_pinned[CNT_STATUS]); }
+  o->n_flag = c->h_pinned[CNT_NFLAG];
+  o->n_alert = c->h_pinned[CNT_NALERT];
+  o->n_group = c->h_pinned[CNT_NGROUP];
+  if (o->n_seg > o->seg_cap || o->n_flag > o->flag_cap || o->n_group > o->group_cap) o->status = CCLD_W_TRUNCATED;
+
   // 7. hang alerts: candidates of every alert
   if (o->n_alert) {
     c->prof.begin(CCLD_PROF_ALERTS);

@@ -136,6 +136,7 @@ struct ccld_ctx {
   uint64_t sort_cap;                  // items the sort buffers hold: max(window records, communicator members)
   uint64_t* h_pinned;                 // pinned host staging
   hipEvent_t ev_heads;                // marks the early readback of the collective count
+  hipEvent_t ev_flags;                // marks the early readback of the flag count
   // staging for host-resident batches
   uint8_t* stage;                     // [batch_cap * 41] device
   // hang location
