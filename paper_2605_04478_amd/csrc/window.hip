@@ -585,8 +585,9 @@ __global__ __launch_bounds__(256) void k_blame_runs(const u64* __restrict__ skey
   if (q == 0 || skey[q - 1] != r) run[r] = q;
   if (q + 1 == n_flag || skey[q + 1] != r) run[n_ranks + r] = q + 1;
 }
-// one workgroup per rank: the rank's run in the sorted flag keys is summed by 256 threads, four flags
-// per thread in flight (a faulty rank's run is tens of thousands of flags long)
+// gridDim.y workgroups per rank: the rank's run in the sorted flag keys is dealt to them in pieces of 1,024
+// flags, four flags per thread in flight (a faulty rank's run is tens of thousands of flags long).  The
+// table was cleared before; the integer sums do not depend on the order of the additions.
 __global__ __launch_bounds__(256) void k_blame_reduce(const u32* __restrict__ run, const u32* __restrict__ sidx,
                                                       const u32* __restrict__ flag_pos,
                                                       const uint8_t* __restrict__ rec_flag,
@@ -595,18 +596,16 @@ __global__ __launch_bounds__(256) void k_blame_reduce(const u32* __restrict__ ru
   __shared__ unsigned long long s_acc[4];
   const u32 r = blockIdx.x, tid = threadIdx.x;
   const u32 first = run[r], last = run[n_ranks + r];
-  if (first == last) {
-    if (tid < 4) blame[(u64)tid * n_ranks + r] = 0;     // columns 0..3 are the four flag sums
-    return;
-  }
+  if ((u64)first + (u64)blockIdx.y * 1024 >= last) return;
   if (tid < 4) s_acc[tid] = 0;
   __syncthreads();
   u64 ne = 0, nx = 0, se = 0, sx = 0;
-  for (u32 q0 = first + tid; q0 < last; q0 += 256 * 4) {
+  for (u64 q1 = (u64)first + blockIdx.y * 1024 + tid; q1 < last; q1 += 1024ull * gridDim.y) {
+    const u32 q0 = (u32)q1;
     u32 j[4], f[4];
     i64 le[4], lx[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) j[u] = q0 + u * 256 < last ? flag_pos[sidx[q0 + u * 256]] : 0xFFFFFFFFu;
+    for (int u = 0; u < 4; ++u) j[u] = (u64)q0 + u * 256 < last ? flag_pos[sidx[q0 + u * 256]] : 0xFFFFFFFFu;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       f[u] = 0; le[u] = 0; lx[u] = 0;
@@ -622,14 +621,15 @@ __global__ __launch_bounds__(256) void k_blame_reduce(const u32* __restrict__ ru
   for (int m = 32; m >= 1; m >>= 1) {
     ne += shfl_xor_u64(ne, m); nx += shfl_xor_u64(nx, m); se += shfl_xor_u64(se, m); sx += shfl_xor_u64(sx, m);
   }
-  if (lane_id() == 0) {       // integer sums: the order of these LDS additions does not matter
+  if (lane_id() == 0) {
     atomicAdd(&s_acc[CCLD_BLM_N_LATE_ENTER], (unsigned long long)ne);
     atomicAdd(&s_acc[CCLD_BLM_N_LATE_EXIT], (unsigned long long)nx);
     atomicAdd(&s_acc[CCLD_BLM_SUM_LAG_ENTER], (unsigned long long)se);
     atomicAdd(&s_acc[CCLD_BLM_SUM_LAG_EXIT], (unsigned long long)sx);
   }
   __syncthreads();
-  if (tid < 4) blame[(u64)tid * n_ranks + r] = (i64)s_acc[tid];
+  if (tid < 4 && s_acc[tid])
+    atomicAdd(reinterpret_cast<unsigned long long*>(&blame[(u64)tid * n_ranks + r]), s_acc[tid]);
 }
 static_assert(CCLD_BLM_N_LATE_ENTER == 0 && CCLD_BLM_N_LATE_EXIT == 1 && CCLD_BLM_SUM_LAG_ENTER == 2 &&
               CCLD_BLM_SUM_LAG_EXIT == 3, "blame column order");
@@ -638,7 +638,9 @@ void launch_blame_reduce(hipStream_t st, const uint64_t* skey, const uint32_t* s
                          uint64_t cap_n, uint32_t n_ranks, uint32_t* run, int64_t* blame) {
   launch_fill_u32(st, run, 2ull * n_ranks, 0u);
   hipLaunchKernelGGL(k_blame_runs, dim3((n_flag + 255) / 256), dim3(256), 0, st, skey, n_flag, n_ranks, run);
-  hipLaunchKernelGGL(k_blame_reduce, dim3(n_ranks), dim3(256), 0, st, (const u32*)run, sidx, flag_pos, rec_flag,
+  // no run is longer than n_flag: a few thousand flags need no second workgroup per rank
+  const u32 split = std::min<u32>(std::max<u32>(n_flag / 4096, 1), 8);
+  hipLaunchKernelGGL(k_blame_reduce, dim3(n_ranks, split), dim3(256), 0, st, (const u32*)run, sidx, flag_pos, rec_flag,
                      flag_lag, cap_n, n_ranks, blame);
 }
 
