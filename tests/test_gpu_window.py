@@ -373,3 +373,27 @@ def test_long_detection_groups_take_the_workgroup_pass():
         assert int(ref.group["slow"].sum()) >= 1
     assert seen_long
     an.close()
+
+
+def test_blame_of_a_rank_with_tens_of_thousands_of_flags():
+    """A rank that is late in every one of 12,000 collectives owns a run of flags long enough to be
+    summed by several workgroups; two other ranks are late now and then."""
+    rng = np.random.default_rng(5)
+    R, rounds = 8, 12_000
+    topo = ring_topology(R)
+    rows = []
+    for s in range(rounds):
+        t = T0 + s * 1_000_000
+        for r in range(R):
+            te = t + int(rng.integers(0, 2_000))
+            if r == 3:
+                te += 400_000 + int(rng.integers(0, 50_000))
+            elif r in (1, 6) and rng.random() < 0.01:
+                te += 300_000
+            rows.append((r, 0, s, 0, 1 << 20, te, te + 60_000 + int(rng.integers(0, 3_000))))
+    cols = toy_cols(rows)
+    p = rng.permutation(len(rows))
+    cols = {k: v[p] for k, v in cols.items()}
+    g, o = run_both(topo, cols, what="long blame run")
+    assert int(o.blame["n_late_enter"][3]) + int(o.blame["n_late_exit"][3]) > 8192
+    assert int(o.order[0]) == 3
