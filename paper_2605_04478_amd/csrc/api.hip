@@ -449,39 +449,46 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   src.lo_mask = cb > 0 ? (((uint64_t)1 << (64 - cb)) - 1) : ~0ull;      // everything below the communicator field
   src.lo_sub = min_seq << mb;
   // A window of several batches that still holds at least half of the previously analysed window keeps that
-  // window's order: the entries of the batches that left are dropped, the keys are re-based to this window's
-  // format, the new records are sorted on their own and the two sequences are merged.
+  // window's order: the new records are sorted on their own and merged with the previous order, whose keys are
+  // re-based to this window's format and whose entries of the batches that left are dropped on the way.
   const bool was_ok = c->inc_ok;
   c->inc_ok = false;
   const uint64_t cap = std::max<uint64_t>(c->cap, 1);
   const uint64_t n_new = c->total_ingested - c->inc_total;
   int sorted = -1;
-  if (was_ok && n_new > 0 && n_new < n && c->inc_sf.mb == mb) {
+  if (was_ok && n_new > 0 && n_new < n && c->inc_sf.mb == mb && mb + ws + cb <= 64 && mb + ws < 64) {
     const uint64_t kept = n - n_new;                                     // records of the previous window still here
     if (kept >= n_new && kept <= c->inc_count) {
       const uint64_t exp_n = c->inc_count - kept;
       const uint64_t old_tail = (c->inc_head + c->inc_count) % cap;
       if ((c->inc_head + exp_n) % cap == c->head && (old_tail + n_new) % cap == (c->head + n) % cap) {
+        // the new records end in the third buffer pair (a sort of p passes ends in its buffer (p - 1) % 2), so
+        // that the merge can read the previous order where it lies and write beside it
         const int s = c->sorted_buf;
+        const int passes = (mb + ws + cb) <= 0 ? 1 : (mb + ws + cb + SORT_RBITS - 1) / SORT_RBITS;
+        const int third = (passes - 1) % 2;
         SortBuffers sbn;
-        sbn.key[0] = c->sb.key[1 - s]; sbn.idx[0] = c->sb.idx[1 - s]; sbn.key[1] = c->keyC; sbn.idx[1] = c->idxC;
+        sbn.key[third] = c->keyC; sbn.idx[third] = c->idxC;
+        sbn.key[1 - third] = c->sb.key[1 - s]; sbn.idx[1 - third] = c->sb.idx[1 - s];
         sbn.table = c->table2; sbn.totals = c->totals2;
         KeySource fresh = src;
         fresh.head = (uint32_t)old_tail;
         const int rb = radix_sort_pairs(st, fresh, (uint32_t)n_new, sbn, mb + ws + cb, &c->prof, CCLD_PROF_SORT_HIST,
                                         CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER);
         if (rb < 0) return o->status = CCLD_E_HIP;
+        if (rb != third) {
+          HIP_TRY(hipMemcpyAsync(c->keyC, sbn.key[rb], sizeof(uint64_t) * n_new, hipMemcpyDeviceToDevice, st));
+          HIP_TRY(hipMemcpyAsync(c->idxC, sbn.idx[rb], sizeof(uint32_t) * n_new, hipMemcpyDeviceToDevice, st));
+        }
         c->prof.begin(CCLD_PROF_SORT_SCATTER);
         RetainArgs ra;
         ra.key = c->sb.key[s]; ra.idx = c->sb.idx[s]; ra.n = (uint32_t)c->inc_count; ra.from = c->inc_sf; ra.to = c->sf;
         ra.exp_lo = (uint32_t)c->inc_head; ra.exp_n = (uint32_t)exp_n; ra.cap = (uint32_t)cap;
         ra.tile_counts = c->tile_flags; ra.total_out = &c->counters[CNT_NRETAINED];
-        ra.key_out = sbn.key[1 - rb]; ra.idx_out = sbn.idx[1 - rb];
-        launch_retain(st, ra);
-        launch_merge(st, sbn.key[1 - rb], sbn.idx[1 - rb], (uint32_t)kept, sbn.key[rb], sbn.idx[rb], (uint32_t)n_new,
-                     c->tile_flags, c->sb.key[s], c->sb.idx[s]);
+        ra.key_out = c->sb.key[1 - s]; ra.idx_out = c->sb.idx[1 - s];
+        launch_merge_kept(st, ra, c->keyC, c->idxC, (uint32_t)n_new, c->tile_heads);
         c->prof.end(CCLD_PROF_SORT_SCATTER);
-        sorted = s;
+        sorted = 1 - s;
       }
     }
   }

@@ -1,6 +1,6 @@
 // Keeping the window's order from one analysis to the next (windows of several batches): the sorted
 // (key, window slot) arrays of the previous analysis lose the records of the batches that left the
-// window, are re-based to the new window's key format, and are merged with the sorted new records.
+// window and are re-based to the new window's key format while they are merged with the sorted new records.
 #pragma once
 #include "ccld_internal.h"
 
@@ -18,11 +18,11 @@ struct RetainArgs {
   uint64_t* key_out;
   uint32_t* idx_out;
 };
-// entries whose slot is still in the window, in order, with keys in the new format
-void launch_retain(hipStream_t st, const RetainArgs& a);
-// two sorted sequences -> one (at equal keys the first sequence's entry comes first)
-// split: scratch of (na + nb) / 2048 + 2 words
-void launch_merge(hipStream_t st, const uint64_t* ka, const uint32_t* ia, uint32_t na, const uint64_t* kb,
-                  const uint32_t* ib, uint32_t nb, uint32_t* split, uint64_t* ko, uint32_t* io);
+// The previous order (a.key, a.idx: a.n entries, those that left included) merged with the sorted new records
+// (kb, ib: nb entries) into a.key_out / a.idx_out, which must not overlap the inputs: the entries that left are
+// dropped, keys are written in the new format, and at equal keys the previous order's entry comes first.
+// a.tile_counts: a.n / 2048 + 2 words; split: (a.n + nb) / 2048 + 2 words.
+void launch_merge_kept(hipStream_t st, const RetainArgs& a, const uint64_t* kb, const uint32_t* ib, uint32_t nb,
+                       uint32_t* split);
 
 }  // namespace ccld
