@@ -321,6 +321,27 @@ __device__ __forceinline__ i64 kth_multi(const i64 (&v)[E], u32 k) {
   return shfl_i64(sel, (int)(k & 63));
 }
 
+// Lower median of |value - median| over the nd smallest values of a sorted collective (nd >= 1, km = (nd - 1) / 2,
+// all uniform across the wavefront).  The deviations of the values up to the median, walked downwards, and of
+// the values above it, walked upwards, are two ascending lists; the km-th smallest of their union is found by
+// the split that takes km + 1 entries from the two lists in order, without sorting the deviations.
+template <int E>
+__device__ __forceinline__ i64 mad_of_sorted(const i64 (&v)[E], u32 nd, u32 km) {
+  const i64 med = kth_multi<E>(v, km);
+  const u32 nl = km + 1, nr = nd - nl, d = km + 1;
+  auto below = [&](u32 j) { return med - kth_multi<E>(v, km - j); };          // j < nl, ascending, below(0) = 0
+  auto above = [&](u32 j) { return kth_multi<E>(v, km + 1 + j) - med; };      // j < nr, ascending
+  u32 lo = d > nr ? d - nr : 0u, hi = d < nl ? d : nl;
+  while (lo < hi) {
+    const u32 mid = (lo + hi) >> 1;
+    if (below(mid) <= above(d - 1 - mid)) lo = mid + 1; else hi = mid;
+  }
+  // lo entries come from the lower list, d - lo from the upper one; the largest of them is the answer
+  i64 r = lo > 0 ? below(lo - 1) : INT64_MIN;
+  if (d - lo > 0) { const i64 u = above(d - lo - 1); r = u > r ? u : r; }
+  return r;
+}
+
 // One wavefront per listed collective of 32 E + 1 .. 64 E records.
 template <int E>
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_multi(SegArgs a) {
@@ -374,22 +395,20 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_multi(SegArgs a) {
     reduce_dur<64, false>(dmin, rmin);
     reduce_dur<64, true>(dmax, rmax);
     const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
-    // four sorts: arrival, completion, then their absolute deviations from the medians
+    // two sorts, arrival and completion; the median of the absolute deviations is selected from each sorted
+    // sequence (records still in flight carry the largest value and sort behind the nd finished ones)
     i64 stat_min[2] = {0, 0}, stat_med[2] = {0, 0}, stat_max[2] = {0, 0}, stat_mad[2] = {0, 0};
 #pragma unroll 1
-    for (int pass = 0; pass < 4; ++pass) {
-      const int w = pass & 1;                      // 0 arrival, 1 completion
+    for (int w = 0; w < 2; ++w) {                  // 0 arrival, 1 completion
       i64 v[E];
 #pragma unroll
       for (int r = 0; r < E; ++r) {
         const bool done = x[r] != T_INFLIGHT;      // lanes past the end hold the in-flight mark too
-        const i64 t = w ? x[r] : e[r];
-        v[r] = !done ? T_INFLIGHT : (pass < 2 ? t : absdiff(t, stat_med[w]));
+        v[r] = !done ? T_INFLIGHT : (w ? x[r] : e[r]);
       }
       sort_multi<E>(v, lane);
-      const i64 mid = kth_multi<E>(v, km);
-      if (pass < 2) { stat_min[w] = kth_multi<E>(v, 0); stat_med[w] = mid; stat_max[w] = kth_multi<E>(v, kl); }
-      else stat_mad[w] = mid;
+      stat_min[w] = kth_multi<E>(v, 0); stat_med[w] = kth_multi<E>(v, km); stat_max[w] = kth_multi<E>(v, kl);
+      if (nd) stat_mad[w] = mad_of_sorted<E>(v, nd, km);
     }
     const bool complete = nn == a.comm_size[comm] && ninfl == 0;
     const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
