@@ -234,7 +234,7 @@ def main() -> int:
     #           pass writes key + index (8 B in, 12 B out)
     #  seg_heads reads the sorted key once (collective heads per tile)
     #  segments reads key + index, gathers the 32-byte row, writes a 21-column int64 row per
-    #           collective and one flag byte per record
+    #           collective, its detection-group key and range (16 B) and one flag byte per record
     n_seg = int(res.n_seg)
     bl = lambda v: int(v).bit_length()
     # key = (communicator, operation counter, member slot inside the communicator)
@@ -242,7 +242,7 @@ def main() -> int:
     packed = passes >= 2 and key_bits + bl(n - 1) <= 64      # key and index travel as one 64-bit word
     scatter_bytes = (16.0 * (passes - 1) + 20.0) if packed else (20.0 + 24.0 * (passes - 1))
     alg = {"ingest": n * 81.0, "sort_hist": n * 8.0 * passes, "sort_scatter": n * scatter_bytes,
-           "seg_heads": n * 8.0, "segments": n * (12.0 + 32.0 + 1.0) + n_seg * 21 * 8.0}
+           "seg_heads": n * 8.0, "segments": n * (12.0 + 32.0 + 1.0) + n_seg * (21 * 8.0 + 16.0)}
     kernels = {k: {"ms_per_step": round(v[0] / args.steps, 4), "launches_per_step": v[1] / args.steps}
                for k, v in prof.items() if v[1]}
     for k, b in alg.items():

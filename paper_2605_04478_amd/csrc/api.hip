@@ -69,6 +69,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->flag_lag = w.take<int64_t>(2 * N);
   c->big_list = w.take<uint32_t>(3 * (N / 65 + 2));
   c->big_ex = w.take<int64_t>(2 * N);
+  c->range_c = w.take<int64_t>(N);
   c->blame_list = w.take<uint32_t>(2ull * n_ranks);
   c->blame_tiles = w.take<uint32_t>(n_ranks / SEL_TILE + 3);
   c->group_long = w.take<uint32_t>(N / GROUP_LONG_MIN + 2);
@@ -512,6 +513,8 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   sa.big_list = c->big_list; sa.big_ex = c->big_ex; sa.counters = c->counters;
   sa.lag_floor = c->p.lag_floor_ns; sa.kmad_num = c->p.kmad_num; sa.kmad_den = c->p.kmad_den;
   sa.barrier_bytes = c->p.barrier_bytes; sa.max_size = c->max_comm_size;
+  sa.gkey = c->keyC; sa.range_c = c->range_c;
+  sa.no_group = (uint64_t)c->topo.n_comms * CCLD_OP_MAX * GROUP_CLS;     // one past every group key
   const uint32_t seg_tiles = (n + SEG_TILE - 1) / SEG_TILE;
   c->prof.begin(CCLD_PROF_SEG_HEADS);
   launch_keys_pass(st, skey, n, c->sf, c->topo, c->blame, c->tile_heads, c->counters);
@@ -567,11 +570,9 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   ga.seg = o->seg; ga.seg_cap = o->seg_cap; ga.n_seg = seg_rows; ga.ws = ws; ga.cb = cb;
   ga.tile_counts = c->tile_flags; ga.counters = c->counters;
   ga.gstate = c->gstate; ga.rate_root = c->rate_root; ga.group = o->group; ga.group_cap = o->group_cap; ga.p = c->p;
-  ga.gkey = c->keyC;
-  ga.range_c = c->big_ex;       // free again once the collectives have been analysed
+  ga.range_c = c->range_c;
   if (seg_rows) {
-    const uint64_t no_group = (uint64_t)c->topo.n_comms * CCLD_OP_MAX * GROUP_CLS;     // one past every group key
-    launch_group_keys(st, ga, no_group);
+    const uint64_t no_group = sa.no_group;
     KeySource gs; gs.key = c->keyC; gs.head = 0; gs.cap = seg_rows; gs.squeeze = 0; gs.hi_shift = 0; gs.lo_bits = 0; gs.lo_mask = 0; gs.lo_sub = 0;
     // sort C -> buffers {other main, C}: the first pass reads C and writes buffer 0, so C is free again for pass 2
     const int r3 = radix_sort_pairs(st, gs, seg_rows, sb2, bits_for_host(no_group));

@@ -123,6 +123,7 @@ struct ccld_ctx {
   int64_t* flag_lag;                  // [2][cap]
   uint32_t* big_list;                 // [cap / 65 + 2][3]  (segment ordinal, first position, length) of the collectives over 64 records
   int64_t* big_ex;                    // [2][cap]
+  int64_t* range_c;                   // [cap] T_max - T_min of every usable collective
   int64_t* blame;                     // [CCLD_BLM_NCOL][n_ranks]
   uint32_t* blame_list;               // [2][n_ranks] flagged ranks, then the others, each ascending
   uint32_t* blame_tiles;              // [n_ranks / SEL_TILE + 3]

@@ -26,6 +26,19 @@ __device__ __forceinline__ u64 atomic_add_u64(u64* p, u64 v) {
 __device__ __forceinline__ void seg_put(const SegArgs& a, int col, u32 srow, i64 v) {
   if (srow < a.seg_cap) a.seg[(u64)col * a.seg_cap + srow] = v;
 }
+// detection-group key and intra-round range T_max - T_min (Eq. 2) of one collective
+__device__ __forceinline__ void seg_put_group(const SegArgs& a, u32 srow, bool usable, u32 comm, u32 op, u64 nb,
+                                              i64 dmax, i64 dmin) {
+  u64 key = a.no_group;
+  i64 range = 0;
+  if (usable) {
+    const u64 cls = 63 - __clzll((long long)(nb | 1));
+    key = ((u64)comm * CCLD_OP_MAX + op) * GROUP_CLS + cls;
+    range = dmax - dmin;
+  }
+  a.gkey[srow] = key;
+  a.range_c[srow] = range;
+}
 __device__ __forceinline__ i64 absdiff(i64 a, i64 b) { return a >= b ? a - b : b - a; }
 __device__ __forceinline__ bool is_late(i64 lag, i64 floor_ns, u32 knum, u32 kden, i64 mad) {
   return lag > floor_ns && (i128)lag * (i128)kden > (i128)knum * (i128)mad;
@@ -189,6 +202,7 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
         seg_put(a, CCLD_SEG_BYTES, srow, (i64)nb);
         seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
         seg_put(a, CCLD_SEG_FIRST, srow, (i64)j);
+        seg_put_group(a, srow, usable, comm, op, nb, dmax, dmin);
         if (nd == 0) {
           seg_put_empty_stats(a, srow);
         } else {
@@ -425,6 +439,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_multi(SegArgs a) {
       seg_put(a, CCLD_SEG_BYTES, srow, (i64)hb);
       seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
       seg_put(a, CCLD_SEG_FIRST, srow, (i64)a0);
+      seg_put_group(a, srow, usable, comm, hop, hb, dmax, dmin);
       if (nd == 0) {
         seg_put_empty_stats(a, srow);
       } else {
@@ -745,6 +760,22 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
   }
 }
 
+// group key and range of the collectives that a workgroup analysed (more than SEG_MULTI_MAX records), from
+// their rows of the table; a row past the table's capacity is not stored and takes no part in the group stage
+__global__ __launch_bounds__(256) void k_seg_group_listed(SegArgs a) {
+  const u32 nbig = (u32)a.counters[CNT_NBIG];
+  for (u32 ent = blockIdx.x * 256 + threadIdx.x; ent < nbig; ent += gridDim.x * 256) {
+    if (a.big_list[3 * ent + 2] <= (u32)SEG_MULTI_MAX) continue;
+    const u32 srow = a.big_list[3 * ent];
+    if (srow >= a.seg_cap) { a.gkey[srow] = a.no_group; a.range_c[srow] = 0; continue; }
+    const u64 C = a.seg_cap;
+    const bool usable = (a.seg[(u64)CCLD_SEG_STATE * C + srow] & CCLD_SEG_USABLE) != 0;
+    seg_put_group(a, srow, usable, (u32)a.seg[(u64)CCLD_SEG_COMM * C + srow], (u32)a.seg[(u64)CCLD_SEG_OP * C + srow],
+                  (u64)a.seg[(u64)CCLD_SEG_BYTES * C + srow], a.seg[(u64)CCLD_SEG_DUR_MAX * C + srow],
+                  a.seg[(u64)CCLD_SEG_DUR_MIN * C + srow]);
+  }
+}
+
 void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
   if (a.n == 0) return;
   hipLaunchKernelGGL(k_seg_wave, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
@@ -758,6 +789,7 @@ void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
   if (m > 256) hipLaunchKernelGGL(k_seg_multi<8>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
   if (m > (uint32_t)SEG_MULTI_MAX) hipLaunchKernelGGL(k_seg_team, dim3(1024), dim3(SEG_THREADS), 0, st, a);
   if (m > (uint32_t)SEG_TEAM_MAX) hipLaunchKernelGGL(k_seg_big, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+  if (m > (uint32_t)SEG_MULTI_MAX) hipLaunchKernelGGL(k_seg_group_listed, dim3(256), dim3(256), 0, st, a);
 }
 
 }  // namespace ccld

@@ -690,29 +690,10 @@ void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, 
 }
 
 // ------------------------------------------------------------------------------------------
-// Detection-group key of every collective in the table: (communicator, op, floor(log2 bytes)) for a
-// usable one, one value past every real key otherwise.  The table is in (communicator, operation
-// counter) order, so a stable sort by this key lists every group's rounds in ascending operation
-// counter, with the collectives that take no part at the end.
-__global__ __launch_bounds__(256) void k_group_keys(GroupArgs a, u64 no_group) {
-  const u32 s = blockIdx.x * 256 + threadIdx.x;
-  if (s < a.n_seg) {
-    const bool usable = (a.seg[(u64)CCLD_SEG_STATE * a.seg_cap + s] & CCLD_SEG_USABLE) != 0;
-    u64 key = no_group;
-    i64 range = 0;
-    if (usable) {
-      const u64 comm = (u64)a.seg[(u64)CCLD_SEG_COMM * a.seg_cap + s];
-      const u64 op = (u64)a.seg[(u64)CCLD_SEG_OP * a.seg_cap + s];
-      const u64 nb = (u64)a.seg[(u64)CCLD_SEG_BYTES * a.seg_cap + s];
-      const u64 cls = 63 - __clzll((long long)(nb | 1));
-      key = (comm * CCLD_OP_MAX + op) * GROUP_CLS + cls;
-      // intra-round range T_max - T_min (Eq. 2), kept per collective for the per-group pass
-      range = a.seg[(u64)CCLD_SEG_DUR_MAX * a.seg_cap + s] - a.seg[(u64)CCLD_SEG_DUR_MIN * a.seg_cap + s];
-    }
-    a.gkey[s] = key;
-    a.range_c[s] = range;
-  }
-}
+// The detection-group key of every collective was written with its statistics: (communicator, op,
+// floor(log2 bytes)) for a usable one, one value past every real key otherwise.  The table is in
+// (communicator, operation counter) order, so a stable sort by this key lists every group's rounds in
+// ascending operation counter, with the collectives that take no part at the end.
 // number of usable collectives = position of the first key past the groups in the sorted keys
 __global__ void k_group_bound(const u64* __restrict__ skey, u32 n_rows, u64 no_group, u64* __restrict__ counters) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
@@ -720,10 +701,6 @@ __global__ void k_group_bound(const u64* __restrict__ skey, u32 n_rows, u64 no_g
   while (lo < hi) { const u32 m = (lo + hi) / 2; if (skey[m] < no_group) lo = m + 1; else hi = m; }
   counters[CNT_NUSABLE] = lo;
 }
-void launch_group_keys(hipStream_t st, const GroupArgs& a, uint64_t no_group) {
-  if (a.n_seg) hipLaunchKernelGGL(k_group_keys, dim3((a.n_seg + 255) / 256), dim3(256), 0, st, a, no_group);
-}
-
 struct PredGroupHead {
   const u64* skey; u64 no_group;
   __device__ bool operator()(u32 i) const { return skey[i] != no_group && (i == 0 || skey[i] != skey[i - 1]); }

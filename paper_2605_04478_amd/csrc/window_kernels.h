@@ -50,6 +50,11 @@ struct SegArgs {
   int64_t lag_floor;
   uint32_t kmad_num, kmad_den, barrier_bytes;
   uint32_t max_size;         // members of the largest communicator (host-side: which size classes can occur)
+  // detection-group key (communicator, op, size class) and T_max - T_min of every collective, for the
+  // group stage; a collective that takes no part gets no_group, one value past every real key
+  uint64_t* gkey;
+  int64_t* range_c;
+  uint64_t no_group;
 };
 void launch_scan_tiles(hipStream_t st, uint32_t* counts, uint32_t n_tiles, uint64_t* total_out);
 void launch_seg_analyze(hipStream_t st, const SegArgs& a);        // small collectives, then the oversized ones
@@ -89,15 +94,13 @@ struct GroupArgs {
   int ws, cb;
   uint32_t* tile_counts;
   uint64_t* counters;
-  uint64_t* gkey;            // [n_seg] detection-group key of every collective
-  int64_t* range_c;          // [n_seg] T_max - T_min of each usable collective
+  const int64_t* range_c;    // [n_seg] T_max - T_min of each usable collective (written with the collectives' statistics)
   GroupState* gstate;
   const int64_t* rate_root;  // [n_comms] minimal-rate member per communicator (CCLD_NO_RANK before any rate pass)
   int64_t* group;
   uint64_t group_cap;
   ccld_params p;
 };
-void launch_group_keys(hipStream_t st, const GroupArgs& a, uint64_t no_group);
 void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_rows, uint64_t no_group, uint32_t* tile_counts,
                         uint32_t* group_first, uint64_t* counters);
 void launch_group_eval(hipStream_t st, const GroupArgs& a, const uint64_t* skey, const uint32_t* sidx,
