@@ -457,7 +457,8 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   const uint64_t cap = std::max<uint64_t>(c->cap, 1);
   const uint64_t n_new = c->total_ingested - c->inc_total;
   int sorted = -1;
-  if (was_ok && n_new > 0 && n_new < n && c->inc_sf.mb == mb && mb + ws + cb <= 64 && mb + ws < 64) {
+  if (was_ok && n_new > 0 && n_new < n && c->inc_sf.mb == mb && mb + ws + cb <= 64 && mb + ws < 64 &&
+      c->inc_sf.mb + c->inc_sf.ws < 64) {
     const uint64_t kept = n - n_new;                                     // records of the previous window still here
     if (kept >= n_new && kept <= c->inc_count) {
       const uint64_t exp_n = c->inc_count - kept;
