@@ -72,6 +72,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->range_c = w.take<int64_t>(N);
   c->blame_list = w.take<uint32_t>(2ull * n_ranks);
   c->blame_tiles = w.take<uint32_t>(n_ranks / SEL_TILE + 3);
+  c->blame_order = w.take<uint32_t>(n_ranks);
   c->group_long = w.take<uint32_t>(N / GROUP_LONG_MIN + 2);
   c->group_first = w.take<uint32_t>(N + 1);
   c->alert_list = w.take<uint32_t>(NT);
@@ -435,7 +436,12 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
     }
   }
   c->last_n = n;
-  if (n == 0) { HIP_TRY(hipStreamSynchronize(st)); c->blame_valid = true; return o->status; }
+  if (n == 0) {
+    launch_blame_order(st, c->blame, n_ranks, c->blame_list, c->blame_tiles, c->counters, c->blame_order);
+    HIP_TRY(hipStreamSynchronize(st));
+    c->blame_valid = true;
+    return o->status;
+  }
 
   // 2. sort by (communicator, operation counter, rank) on the significant bits only
   // the operation counters of the window relative to its smallest one
@@ -598,6 +604,8 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
                         c->blame_list, c->blame);
     c->prof.end(CCLD_PROF_BLAME);
   }
+  // the blame order is ready when ccld_rank_blame asks for it: its kernels are queued here, before the wait
+  launch_blame_order(st, c->blame, n_ranks, c->blame_list, c->blame_tiles, c->counters, c->blame_order);
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   if (c->h_pinned[CNT_STATUS]) { zero_counts(o); return o->status = data_status(c->h_pinned[CNT_STATUS]); }
@@ -633,7 +641,8 @@ ccld_status ccld_rank_blame(ccld_ctx* c, int64_t* blame, uint32_t* order) {
   if (blame)
     HIP_TRY(hipMemcpyAsync(blame, c->blame, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)n_ranks,
                            hipMemcpyDeviceToDevice, c->stream));
-  if (order) launch_blame_order(c->stream, c->blame, n_ranks, c->blame_list, c->blame_tiles, c->counters, order);
+  if (order)
+    HIP_TRY(hipMemcpyAsync(order, c->blame_order, sizeof(uint32_t) * (uint64_t)n_ranks, hipMemcpyDeviceToDevice, c->stream));
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipStreamSynchronize(c->stream));
   return CCLD_OK;

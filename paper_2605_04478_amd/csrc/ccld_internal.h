@@ -127,6 +127,7 @@ struct ccld_ctx {
   int64_t* blame;                     // [CCLD_BLM_NCOL][n_ranks]
   uint32_t* blame_list;               // [2][n_ranks] flagged ranks, then the others, each ascending
   uint32_t* blame_tiles;              // [n_ranks / SEL_TILE + 3]
+  uint32_t* blame_order;              // [n_ranks] ranks by (flags, summed lag, rank), written at the end of every analysis
   uint32_t* group_long;               // [cap / GROUP_LONG_MIN + 2] detection groups left to the workgroup-per-group pass
   uint32_t* group_first;              // [cap + 1]
   uint32_t* alert_list;               // [cap]
