@@ -63,3 +63,40 @@ def test_create_rejects_bad_arguments():
     assert L.ccld_ingest(None, None, 0) == -7
     assert L.ccld_analyze_window(None, 0, None) == -7
     assert L.ccld_progress_rates(None, None, 0, None) == -7
+
+
+def test_blame_of_the_last_analysis_survives_a_hang_location():
+    """ccld_rank_blame returns the table and the order of the most recent analysis, also when a hang
+    location (which borrows the sort buffers and the scratch of the selections) ran in between; an
+    analysis of an empty window then leaves an all-zero table and the ranks in ascending order."""
+    from oracle import ccld_oracle as orc
+    from paper_2605_04478_amd import ccld
+    lay = tg.Layout3D(tp=2, pp=2, dp=4, world=True)
+    ht = tg.generate_hang(tg.config4(layout=lay, n_channels=3))
+    topo = ht.topo
+    R = lay.n_ranks
+    rng = np.random.default_rng(3)
+    rows = []
+    for s in range(300):                          # world communicator (the last one): rank 5 enters late every time
+        c = topo.n_comms - 1
+        for r in range(R):
+            te = T0 + s * 1_000_000 + int(rng.integers(0, 1_000)) + (400_000 if r == 5 else 0)
+            rows.append((r, c, s, 0, 1 << 20, te, te + 50_000))
+    cols = toy_cols(rows)
+    an = ccld.Analyzer(topo, max_window_records=len(rows), max_snapshot_rows=ht.n)
+    an.ingest(an.to_device(cols))
+    g = an.analyze_window(T0 + 10**12)
+    ref = orc.Oracle(topo).analyze_window(cols, T0 + 10**12)
+    assert g.status == ref.status == "OK" and int(ref.blame["n_late_enter"][5]) == 300
+    h = an.locate_hang(an.snapshots_to_device(ht.cols), ht.spec.n_snapshots, ht.spec.n_channels)
+    assert h.status == "OK"
+    blame, order = an.rank_blame()
+    for k in ref.blame:
+        assert np.array_equal(blame[k], ref.blame[k]), k
+    assert np.array_equal(order, ref.order) and int(order[0]) == 5
+    an.reset_window()
+    g = an.analyze_window(T0 + 10**12)
+    blame, order = an.rank_blame()
+    assert g.n_records == 0 and all(int(v.sum()) == 0 for v in blame.values())
+    assert list(order) == list(range(R))
+    an.close()
