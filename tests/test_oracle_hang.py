@@ -180,3 +180,114 @@ def test_cluster_hang_names_exactly_the_injected_rank(seed):
     healthy = tg.generate_hang(tg.config4(layout=lay, seed=seed, n_channels=4, healthy=True))
     rh = orc.Oracle(healthy.topo).locate_hang(healthy.cols, 64, 4)
     assert roots(rh) == [] and rh.comm["hung"].sum() == 0
+
+
+# --------------------------------------------------------------------------
+# the rules of the hardware branch and of the per-member pass, one at a time (expected values
+# written out by hand from the definitions)
+# --------------------------------------------------------------------------
+def test_fewest_counts_tie_goes_to_fewer_received_then_smaller_rank():
+    """Fewest SendCount + RecvCount; among equals the rank that received less; then the smaller rank."""
+    topo = ring_topology(4)
+    # sums: 8, 8, 12, 12; rank 1 received 3, rank 0 received 5 -> rank 1 although rank 0 is smaller
+    sr = {0: (3, 5), 1: (5, 3), 2: (6, 6), 3: (6, 6)}
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (9, *sr[q])), 8, 1, stall_snapshots=3, fifo_depth=8)
+    assert r.comm["hung"][0] == 1 and r.comm["root_by_count"][0] == 1
+    # equal sums and equal received counts: the smaller rank
+    sr = {0: (6, 6), 1: (4, 4), 2: (4, 4), 3: (6, 6)}
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (9, *sr[q])), 8, 1, stall_snapshots=3, fifo_depth=8)
+    assert r.comm["root_by_count"][0] == 1
+    # a smaller sum beats a smaller received count
+    sr = {0: (7, 0), 1: (6, 6), 2: (3, 3), 3: (6, 6)}
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (9, *sr[q])), 8, 1, stall_snapshots=3, fifo_depth=8)
+    assert r.comm["root_by_count"][0] == 2
+
+
+def test_back_pressure_starts_at_exactly_fifo_depth_unconsumed_chunks():
+    """A rank waits on its successor once the successor holds fifo_depth chunks it has not consumed
+    (sent - received_by_successor >= depth), not one chunk later."""
+    topo = ring_topology(3)
+    # rank 0 sent 12, rank 1 received 4: exactly 8 unconsumed.  rank 0 is not starved (received 2 < 9 sent by rank 2).
+    # rank 1: received 4 < 12, sent 4, rank 2 received 4: 0 unconsumed -> waits on nobody: the root.
+    # rank 2: received 4 >= 4 sent by rank 1 -> starved, waits on rank 1.
+    sr = {0: (12, 2), 1: (4, 4), 2: (9, 4)}
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (9, *sr[q])), 8, 1, stall_snapshots=3, fifo_depth=8)
+    assert r.comm["class"][0] == 3
+    assert list(r.pair["waits_on"]) == [1, NO_RANK, 1]
+    assert roots(r) == [(1, 0, 3)] and list(r.pair["hops"]) == [1, 0, 1]
+    # one chunk fewer in flight: rank 0 waits on nobody either
+    sr[0] = (11, 2)
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (9, *sr[q])), 8, 1, stall_snapshots=3, fifo_depth=8)
+    assert list(r.pair["waits_on"]) == [NO_RANK, NO_RANK, 1]
+    assert roots(r) == [(0, 0, 3), (1, 0, 3)]
+    # starvation has precedence over back-pressure: rank 0 with both conditions waits on its predecessor
+    sr = {0: (12, 9), 1: (4, 4), 2: (9, 4)}
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (9, *sr[q])), 8, 1, stall_snapshots=3, fifo_depth=8)
+    assert list(r.pair["waits_on"]) == [2, NO_RANK, 1]
+
+
+def test_onset_is_the_latest_channel_and_a_stall_needs_every_channel():
+    topo = ring_topology(2)
+
+    def st(s, c, q, ch):
+        if q == 0:                                  # channel 0 freezes at snapshot 2, channel 1 at snapshot 5
+            return (7, min(s, 2) if ch == 0 else min(s, 5), 0)
+        if ch == 0:                                 # rank 1: channel 0 frozen from the start ...
+            return (7, 1, 1)
+        return (7, s, 0)                            # ... channel 1 still moving
+    r = locate(topo, snap_rows(topo, 12, 2, st), 12, 2, stall_snapshots=4)
+    assert list(r.pair["onset"]) == [5, 11]
+    assert list(r.pair["stalled"]) == [1, 0]
+    assert list(r.pair["sent"]) == [2 + 5, 1 + 11] and list(r.pair["recv"]) == [0, 1]
+    # all entered, rank 1 not stalled -> inconsistent hang with the moving rank as root
+    assert roots(r) == [(1, 0, 2)]
+    # the other channel moving instead: same verdict
+    r = locate(topo, snap_rows(topo, 12, 2, lambda s, c, q, ch: st(s, c, q, 1 - ch)), 12, 2, stall_snapshots=4)
+    assert list(r.pair["onset"]) == [5, 11] and list(r.pair["stalled"]) == [1, 0]
+    # frozen exactly stall_snapshots before the last snapshot counts as stalled, one later does not
+    r = locate(topo, snap_rows(topo, 12, 1, lambda s, c, q, ch: (7, min(s, 7) if q == 0 else min(s, 8), 0)), 12, 1,
+               stall_snapshots=4)
+    assert list(r.pair["onset"]) == [7, 8] and list(r.pair["stalled"]) == [1, 0]
+
+
+def test_tree_root_is_only_the_rank_furthest_behind_its_layer():
+    # root + four children in one layer, BFS order; sums of the layer: 20, 17, 14, 20 -> deficits 0, 3, 6, 0
+    topo = tg.make_topology(5, [list(range(5))], algo=[tg.ALGO_TREE], tree_parent=[[-1, 0, 0, 0, 0]])
+    sr = {0: (30, 30), 1: (10, 10), 2: (9, 8), 3: (7, 7), 4: (10, 10)}
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (3, *sr[q])), 8, 1, stall_snapshots=3)
+    assert r.comm["class"][0] == 3 and roots(r) == [(3, 0, 3)] and r.comm["n_cand"][0] == 1
+    # two ranks equally far behind are both roots
+    sr[2] = (7, 7)
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (3, *sr[q])), 8, 1, stall_snapshots=3)
+    assert roots(r) == [(2, 0, 3), (3, 0, 3)]
+    # the deficit is measured inside the layer: the root rank's own large counts do not matter
+    sr = {0: (1, 1), 1: (10, 10), 2: (10, 10), 3: (10, 9), 4: (10, 10)}
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (3, *sr[q])), 8, 1, stall_snapshots=3)
+    assert roots(r) == [(3, 0, 3)]
+
+
+def test_victim_filter_needs_the_rank_inside_the_other_hung_communicator():
+    """A rank that has not entered communicator 0 is dropped as a victim only if it HAS entered
+    another hung communicator; membership of a hung communicator that it has not entered either
+    leaves it a root of both."""
+    # communicator 0 = {0, 1, 2}, communicator 1 = {2, 3, 4}
+    topo = ring_topology(5, comms=[[0, 1, 2], [2, 3, 4]])
+
+    def st(entered_in_1):
+        def f(s, c, q, ch):
+            r = topo.members_of(c)[q]
+            if c == 0:
+                return (50, 9, 9) if r == 2 else (51, 1, 0)         # rank 2 never posts operation 51 on communicator 0
+            if r == 2:
+                return (71, 2, 1) if entered_in_1 else (70, 9, 9)
+            return (71, 1, 0)
+        return f
+    # rank 2 is blocked inside communicator 1 (entered operation 71 there, everyone stalled, counts differ):
+    # communicator 1 is a hardware-type hang, rank 2's absence from communicator 0 is a consequence
+    r = locate(topo, snap_rows(topo, 8, 1, st(True)), 8, 1, stall_snapshots=3)
+    assert list(r.comm["hung"]) == [1, 1] and list(r.comm["class"]) == [1, 3]
+    assert all(c == 1 for _, c, _ in roots(r)) and r.comm["n_cand"][0] == 0
+    # rank 2 has entered neither: it is the not-entered root of both
+    r = locate(topo, snap_rows(topo, 8, 1, st(False)), 8, 1, stall_snapshots=3)
+    assert list(r.comm["class"]) == [1, 1]
+    assert roots(r) == [(2, 0, 1), (2, 1, 1)]

@@ -435,3 +435,124 @@ def test_propagating_schedule_keeps_faulty_ranks_on_top_and_clean_runs_clean():
     clean = tg.propagate(tg.generate(cspec), gap_ns=2_000_000)
     wc = orc.Oracle(clean.topo).analyze_window(clean.cols, int(clean.cols["t_exit"].max()) + 1)
     assert wc.status == "OK" and len(wc.flag["rank"]) == 0
+
+
+# --------------------------------------------------------------------------
+# the late test, one leg at a time (expected values written out by hand from the definition:
+# late iff lag > floor and lag * kmad_den > kmad_num * MAD, both strict)
+# --------------------------------------------------------------------------
+def _one_round(enters, exits, nbytes=1 << 20):
+    return [(r, 0, 0, tg.OP_ALLREDUCE, nbytes, T0 + int(e), T0 + int(x)) for r, (e, x) in enumerate(zip(enters, exits))]
+
+
+@pytest.mark.parametrize("side", ["enter", "exit"])
+def test_late_needs_both_the_floor_and_the_mad_multiple(side):
+    topo = ring_topology(5)
+    kind = orc.FLAG_LATE_ENTER if side == "enter" else orc.FLAG_LATE_EXIT
+    base = 10_000_000          # the other side: everyone at the same time, never late
+
+    def run(offsets, **params):
+        if side == "enter":
+            rows = _one_round(offsets, [base] * 5)
+        else:
+            rows = _one_round([0] * 5, [base + o for o in offsets])
+        r, _ = analyze(topo, toy_cols(rows), **params)
+        assert r.status == "OK" and r.seg["state"][0] & orc.SEG_USABLE
+        return r
+
+    # spread values: median 400,000, deviations {0, 200k, 200k, 400k, 400k} -> MAD 200,000.
+    # rank 4: lag 400,000 exceeds the floor (300,000) but 2 * 400,000 <= 9 * 200,000: not late
+    r = run([0, 200_000, 400_000, 600_000, 800_000])
+    assert r.seg[side + "_med"][0] - T0 - (base if side == "exit" else 0) == 400_000
+    assert r.seg[side + "_mad"][0] == 200_000
+    assert list(r.rec["lag_" + side]) == [-400_000, -200_000, 0, 200_000, 400_000]
+    assert len(r.flag["rank"]) == 0 and r.rec["flag"].sum() == 0
+    # equality of the MAD leg: median 400,000, MAD 200,000, lag 900,000: 2 * 900,000 == 9 * 200,000 -> not late
+    r = run([0, 200_000, 400_000, 600_000, 1_300_000])
+    assert r.seg[side + "_mad"][0] == 200_000 and r.rec["lag_" + side][4] == 900_000
+    assert len(r.flag["rank"]) == 0
+    # one nanosecond more: late
+    r = run([0, 200_000, 400_000, 600_000, 1_300_001])
+    assert list(r.flag["rank"]) == [4] and list(r.flag["kind"]) == [kind]
+    assert r.flag["lag_" + side][0] == 900_001
+    # the multiple itself: with kmad = 2/1 the same round flags at 400,001 and not at 400,000
+    r = run([0, 200_000, 400_000, 600_000, 800_000], kmad_num=2, kmad_den=1)
+    assert len(r.flag["rank"]) == 0
+    r = run([0, 200_000, 400_000, 600_000, 800_001], kmad_num=2, kmad_den=1)
+    assert list(r.flag["rank"]) == [4]
+    # the ratio is num/den, not den/num: 1/3 flags lag 400,000 (3 * 400,000 > 200,000), 3/1 does not
+    assert list(run([0, 200_000, 400_000, 600_000, 800_000], kmad_num=1, kmad_den=3).flag["rank"]) == [4]
+    assert len(run([0, 200_000, 400_000, 600_000, 800_000], kmad_num=3, kmad_den=1).flag["rank"]) == 0
+    # the floor leg alone: MAD 0 (four equal values), lag == floor -> not late, floor + 1 -> late
+    r = run([0, 0, 0, 0, 300_000])
+    assert r.seg[side + "_mad"][0] == 0 and len(r.flag["rank"]) == 0
+    r = run([0, 0, 0, 0, 300_001])
+    assert list(r.flag["rank"]) == [4] and list(r.flag["kind"]) == [kind]
+    assert r.blame["n_late_" + side][4] == 1 and r.blame["sum_lag_" + side][4] == 300_001
+    other = "exit" if side == "enter" else "enter"
+    assert r.blame["n_late_" + other].sum() == 0
+
+
+def test_blame_order_is_flags_then_summed_lag_then_rank():
+    """order[] = (number of flags descending, summed lag descending, rank ascending)."""
+    topo = ring_topology(6)
+    dur = 10_000_000
+    late = {0: {2: 400_000},               # round -> {rank: entry delay}
+            1: {2: 400_000},
+            2: {1: 500_000},
+            3: {3: 700_000},
+            4: {4: 500_000}}
+    rows = []
+    for j in range(5):
+        t = T0 + j * 1_000_000_000
+        for r in range(6):
+            rows.append((r, 0, j, tg.OP_ALLREDUCE, 1 << 20, t + late[j].get(r, 0), t + dur))
+    r, _ = analyze(topo, toy_cols(rows))
+    assert list(r.blame["n_late_enter"]) == [0, 1, 2, 1, 1, 0] and r.blame["n_late_exit"].sum() == 0
+    assert list(r.blame["sum_lag_enter"]) == [0, 500_000, 800_000, 700_000, 500_000, 0]
+    # rank 2 has two flags; ranks 3, 1, 4 one each with lags 700k > 500k = 500k (1 before 4); then 0, 5
+    assert list(r.order) == [2, 3, 1, 4, 0, 5]
+    # the lag that orders is the sum of both kinds: rank 4 also leaves late by 300,001 ns in its round
+    rows2 = [(rk, c, s, op, nb, te, tx + (300_001 if (s == 4 and rk == 4) else 0)) for rk, c, s, op, nb, te, tx in rows]
+    r2, _ = analyze(topo, toy_cols(rows2))
+    assert list(r2.blame["n_late_exit"]) == [0, 0, 0, 0, 1, 0]
+    assert list(r2.order) == [4, 2, 3, 1, 0, 5]        # ranks 4 and 2 have two flags each; 800,001 > 800,000
+
+
+def test_round_with_an_operation_in_flight_is_not_usable():
+    """Every member has a record but one operation has not completed: the round is neither complete
+    nor usable, it raises no flag and forms no detection group."""
+    topo = ring_topology(4)
+    t = T0
+    rows = [(0, 0, 0, tg.OP_ALLREDUCE, 1 << 20, t, t + 1000), (1, 0, 0, tg.OP_ALLREDUCE, 1 << 20, t, t + 1000),
+            (2, 0, 0, tg.OP_ALLREDUCE, 1 << 20, t + 900_000, INFLIGHT), (3, 0, 0, tg.OP_ALLREDUCE, 1 << 20, t, t + 1000)]
+    r, _ = analyze(topo, toy_cols(rows), now=t + 10**9)
+    assert r.seg["n"][0] == 4 and r.seg["inflight"][0] == 1
+    assert r.seg["state"][0] == orc.SEG_CONSISTENT
+    assert len(r.group["comm"]) == 0 and len(r.flag["rank"]) == 0 and r.rec["flag"].sum() == 0
+    assert list(r.rec["lag_enter"]) == [0, 0, 0, 0]
+    # statistics cover the three completed records only
+    assert r.seg["enter_max"][0] == t and r.seg["exit_med"][0] == t + 1000 and r.seg["dur_max"][0] == 1000
+    # the same round completed: usable, one group, rank 2 late on entry
+    rows[2] = (2, 0, 0, tg.OP_ALLREDUCE, 1 << 20, t + 900_000, t + 900_500)
+    r, _ = analyze(topo, toy_cols(rows), now=t + 10**9)
+    assert r.seg["state"][0] == orc.SEG_COMPLETE | orc.SEG_CONSISTENT | orc.SEG_USABLE
+    assert len(r.group["comm"]) == 1 and list(r.flag["rank"]) == [2]
+
+
+def test_eq1_round_exactly_at_the_end_of_the_warmup_span_still_counts():
+    """Rounds start 0, 60 and 120 s after the first one with a 120 s span: all three are averaged
+    (m = 3); one nanosecond later the third round already ends the warm-up (m = 2)."""
+    topo = ring_topology(2)
+    span = 120_000_000_000
+    for extra, m, base in ((0, 3, (100 + 200 + 600) // 3), (1, 2, (100 + 200) // 2)):
+        rows = []
+        for j, (t, d) in enumerate(((0, 100), (span // 2, 200), (span + extra, 600), (span + 10**9, 700),
+                                    (span + 2 * 10**9, 100_000))):
+            # the last round alone has a spread, so Eq. 2 selects it and the averaged baseline shows
+            rows += [(r, 0, j, tg.OP_ALLREDUCE, 1 << 20, T0 + t, T0 + t + (1 if (j == 4 and r == 1) else d))
+                     for r in range(2)]
+        r, _ = analyze(topo, toy_cols(rows), tbase_warmup_ns=span, tbase_rounds=100)
+        assert r.group["rstar_seq"][0] == 4
+        assert r.group["frozen"][0] == 1 and r.group["m"][0] == m
+        assert r.group["static"][0] == 0 and r.group["tbase"][0] == base

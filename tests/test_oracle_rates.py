@@ -171,3 +171,23 @@ def test_communication_slow_root_uses_the_rate_pass():
     o.progress_rates(series_cols(series), 3, 1)
     w = o.analyze_window(toy_cols(rows), T0 + 10**10)
     assert w.group["class"][0] == 2 and w.group["root_s2"][0] == 3
+
+
+def test_equal_rates_name_the_smaller_rank():
+    """Ranks 1 and 2 both show 3 changes per operation (rate 1/3), rank 0 shows 1, rank 3 shows 2:
+    the minimal rate is shared, the smaller rank is reported.  2/6 equals 1/3 as well."""
+    topo = ring_topology(4)
+    fast = [(1, 0, 0), (1, 8, 8), (1, 8, 8), (1, 8, 8), (2, 0, 0)]
+    three = [(1, 0, 0), (1, 2, 2), (1, 5, 5), (1, 8, 8), (2, 0, 0)]
+    two = [(1, 0, 0), (1, 4, 4), (1, 8, 8), (1, 8, 8), (2, 0, 0)]
+    series = {(0, 0, 0): fast, (1, 0, 0): three, (2, 0, 0): three, (3, 0, 0): two}
+    r = rates(topo, series, 5)
+    assert list(r.pair["ops_send"]) == [1, 1, 1, 1] and list(r.pair["changes_send"]) == [1, 3, 3, 2]
+    assert r.comm["root_send"][0] == 1 and r.comm["root_recv"][0] == 1 and r.comm["root"][0] == 1
+    # rank 0 with two operations of three changes each: 2/6 == 1/3, now rank 0 is the smallest of the tied ranks
+    twice = [(1, 0, 0), (1, 2, 2), (1, 5, 5), (1, 8, 8), (2, 1, 1), (2, 4, 4), (2, 8, 8), (3, 0, 0)]
+    pad = lambda s: s[:-1] + [s[-2]] * 3 + [s[-1]]
+    series = {(0, 0, 0): twice, (1, 0, 0): pad(three), (2, 0, 0): pad(three), (3, 0, 0): pad(two)}
+    r = rates(topo, series, 8)
+    assert list(r.pair["ops_send"]) == [2, 1, 1, 1] and list(r.pair["changes_send"]) == [6, 3, 3, 2]
+    assert r.comm["root_send"][0] == 0 and r.comm["root"][0] == 0
