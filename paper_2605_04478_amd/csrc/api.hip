@@ -309,7 +309,6 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
     (void)hipGetLastError();
     if (c->h_pinned) (void)hipHostFree(c->h_pinned);
     if (c->ev_heads) (void)hipEventDestroy(c->ev_heads);
-  if (c->ev_flags) (void)hipEventDestroy(c->ev_flags);
     if (c->ev_flags) (void)hipEventDestroy(c->ev_flags);
     delete c;
     return rs;
@@ -323,6 +322,7 @@ ccld_status ccld_destroy(ccld_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   if (c->h_pinned) (void)hipHostFree(c->h_pinned);
   if (c->ev_heads) (void)hipEventDestroy(c->ev_heads);
+  if (c->ev_flags) (void)hipEventDestroy(c->ev_flags);
   c->prof.destroy();
   delete c;
   return CCLD_OK;
