@@ -285,6 +285,22 @@ ccld_status ccld_analyze_window(ccld_ctx *ctx, int64_t now_ns, ccld_window_resul
 ccld_status ccld_locate_hang(ccld_ctx *ctx, const ccld_snapshots *snapshots, uint64_t n_rows,
                              ccld_hang_result *out);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture set-up, tight serving
+ * loops, harnesses that forbid hipMalloc) and whose context was created with max_snapshot_rows = 0:
+ * ccld_locate_hang with every buffer of the pass (the snapshot grid, the per-member and
+ * per-communicator tables, the root list's sort buffers, staging for host-resident rows) taken from a
+ * static device array of CCLD_STATIC_SCRATCH_BYTES bytes that the library holds on every GPU it runs
+ * on until the process ends, instead of from the context's workspace.  Inputs, outputs, results and
+ * error behaviour are those of ccld_locate_hang, except that the capacity limit is the array: a grid
+ * (member slots x channels x snapshots, 16 bytes per cell, plus about 200 bytes per member slot and
+ * 32 bytes per host-resident row) that does not fit returns CCLD_E_CAPACITY.  The call allocates and
+ * frees nothing.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (from several contexts, streams or threads) race; everything the pass needs cleared is cleared by
+ * the call itself.  The context's window state is left alone (its sort buffers are not borrowed). */
+#define CCLD_STATIC_SCRATCH_BYTES (32u << 20)
+ccld_status ccld_locate_hang_static(ccld_ctx *ctx, const ccld_snapshots *snapshots, uint64_t n_rows,
+                                    ccld_hang_result *out);
+
 /* SendRate / RecvRate of every (communicator, member) from a series of SendCount / RecvCount
  * snapshots (Section 4.1.2, slow diagnostic metrics): the rate is the reciprocal of the number of
  * times the count changes from one sample to the next while an operation runs, so a rank whose

@@ -101,7 +101,8 @@ PROF_CLASSES = ("ingest", "sort_hist", "sort_scan", "sort_scatter", "segments", 
 PROF_NCLASS = 16
 
 EXPORTS = ("ccld_profile_enable", "ccld_profile_read", "ccld_default_params", "ccld_query_workspace", "ccld_create", "ccld_destroy", "ccld_ingest",
-           "ccld_reset_window", "ccld_analyze_window", "ccld_rank_blame", "ccld_locate_hang", "ccld_progress_rates",
+           "ccld_reset_window", "ccld_analyze_window", "ccld_rank_blame", "ccld_locate_hang", "ccld_locate_hang_static",
+           "ccld_progress_rates",
            "ccld_decode_frames", "ccld_reset_frames", "ccld_status_str")
 
 
@@ -123,6 +124,7 @@ def lib() -> C.CDLL:
         L.ccld_analyze_window.argtypes = [vp, C.c_int64, vp]
         L.ccld_rank_blame.argtypes = [vp, vp, vp]
         L.ccld_locate_hang.argtypes = [vp, vp, u64, vp]
+        L.ccld_locate_hang_static.argtypes = [vp, vp, u64, vp]
         L.ccld_progress_rates.argtypes = [vp, vp, u64, vp]
         L.ccld_decode_frames.argtypes = [vp, vp, vp, vp]
         L.ccld_reset_frames.argtypes = [vp]
@@ -390,7 +392,10 @@ class Analyzer:
         return {k: t.from_numpy(np.ascontiguousarray(cols[k]).view(sign[k])).to(self.device) for k in sign}
 
     def locate_hang(self, cols, n_snapshots: int, n_channels: int, root_cap: int = 4096,
-                    pair_cap: Optional[int] = None, comm_cap: Optional[int] = None) -> HangResult:
+                    pair_cap: Optional[int] = None, comm_cap: Optional[int] = None, static: bool = False,
+                    buffers=None) -> HangResult:
+        """static=True calls ccld_locate_hang_static (the pass works in the library's static device array
+        instead of the context's workspace); buffers = (caps, dev) reuses result tables."""
         t = self.torch
         first = cols["snap"]
         on_device = not isinstance(first, np.ndarray)
@@ -405,17 +410,21 @@ class Analyzer:
         sn = _Snapshots(ptr("snap"), ptr("rank"), ptr("comm"), ptr("channel"), ptr("seq_posted"),
                         ptr("chunks_sent"), ptr("chunks_recv"), 1 if on_device else 0, int(n_snapshots),
                         int(n_channels))
-        caps = {"root": int(root_cap), "pair": int(pair_cap or int(self._size.sum())),
-                "comm": int(comm_cap or self.n_comms)}
-        i64 = dict(dtype=t.int64, device=self.device)
-        dev = {"root": t.empty(len(HANG_ROOT_COLS) * caps["root"], **i64),
-               "pair": t.empty(len(HANG_PAIR_COLS) * caps["pair"], **i64),
-               "comm": t.empty(len(HANG_COMM_COLS) * caps["comm"], **i64)}
+        if buffers is not None:
+            caps, dev = buffers
+        else:
+            caps = {"root": int(root_cap), "pair": int(pair_cap or int(self._size.sum())),
+                    "comm": int(comm_cap or self.n_comms)}
+            i64 = dict(dtype=t.int64, device=self.device)
+            dev = {"root": t.empty(len(HANG_ROOT_COLS) * caps["root"], **i64),
+                   "pair": t.empty(len(HANG_PAIR_COLS) * caps["pair"], **i64),
+                   "comm": t.empty(len(HANG_COMM_COLS) * caps["comm"], **i64)}
         r = _HangResult(caps["root"], caps["pair"], caps["comm"], dev["root"].data_ptr(), dev["pair"].data_ptr(),
                         dev["comm"].data_ptr())
-        st = self.L.ccld_locate_hang(self._ctx, C.addressof(sn), n, C.addressof(r))
+        fn = self.L.ccld_locate_hang_static if static else self.L.ccld_locate_hang
+        st = fn(self._ctx, C.addressof(sn), n, C.addressof(r))
         if st in (-7, -11, -6, -8):
-            raise CcldError(st, "ccld_locate_hang")
+            raise CcldError(st, "ccld_locate_hang_static" if static else "ccld_locate_hang")
         return HangResult(STATUS.get(st, str(st)), r.n_root, r.n_pair, r.n_hung_comm, caps, dev)
 
     def reset_frames(self) -> None:

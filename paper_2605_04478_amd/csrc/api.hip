@@ -304,6 +304,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   }
   if (hipEventCreateWithFlags(&c->ev_heads, hipEventDisableTiming) != hipSuccess) { c->ev_heads = nullptr; rs = CCLD_E_HIP; }
   if (hipEventCreateWithFlags(&c->ev_flags, hipEventDisableTiming) != hipSuccess) { c->ev_flags = nullptr; rs = CCLD_E_HIP; }
+  if (ccld_static_scratch_init() != CCLD_OK) rs = CCLD_E_HIP;          // address of the static array on this device
   if (hipStreamSynchronize(c->stream) != hipSuccess) rs = CCLD_E_HIP;   // host vectors above die at return
   if (rs != CCLD_OK) {
     (void)hipGetLastError();

@@ -167,3 +167,6 @@ struct ccld_ctx {
   ccld::Profiler prof;
   int sort_passes;                    // passes of the last main sort
 };
+
+// looks up the device address of the library's static scratch array on the current device (hang.hip)
+ccld_status ccld_static_scratch_init();

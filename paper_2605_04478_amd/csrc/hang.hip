@@ -5,6 +5,7 @@
 // walked to the roots.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 
 #include "ccld_internal.h"
 #include "device_utils.h"
@@ -597,9 +598,48 @@ static ccld_status hang_status(uint64_t bits) {
   return CCLD_OK;
 }
 
+// Device memory the hang and rate passes work in, beyond their inputs and outputs: either carved from the
+// context's workspace or from the library's static device array.
+struct HangScratch {
+  uint64_t* counters;        // [CNT_COUNT]
+  uint64_t* cell;            // [n_cell][2]
+  uint32_t* cnt;             // presence bitmap, one bit per cell
+  int64_t* pair;             // [CCLD_HPAIR_NCOL][n_members]
+  int64_t* hcomm;            // [CCLD_HCOMM_NCOL][n_comms]
+  int32_t* wait_slot;        // [n_members]
+  uint8_t* cand;             // [n_members]
+  uint64_t* layer_max;       // [n_members]
+  uint32_t* root_list;       // [n_members + 1]
+  uint32_t* tiles_a;         // [n_members / SEL_TILE + 2] per-tile counts of the root selection
+  uint32_t* tiles_b;         // [n_comms / SEL_TILE + 2] per-tile counts of the hung-communicator selection
+  uint32_t* comm_list;       // [n_comms] hung communicators
+  SortBuffers sb;            // root list sort: n_members items
+  uint64_t* keyC;            // [n_members]
+  uint64_t sort_cap;
+  uint8_t* stage;            // [n_rows * 32] staging for host-resident rows, or null
+  bool fill_kernels;         // clear with fill kernels instead of hipMemsetAsync
+};
+
+static HangScratch scratch_of_context(ccld_ctx* c) {
+  HangScratch S;
+  S.counters = c->counters; S.cell = c->h_cell; S.cnt = c->h_cnt; S.pair = c->h_pair; S.hcomm = c->h_comm;
+  S.wait_slot = c->h_wait_slot; S.cand = c->h_cand; S.layer_max = c->h_layer_max; S.root_list = c->h_root_list;
+  S.tiles_a = c->tile_flags; S.tiles_b = c->tile_heads; S.comm_list = c->alert_list;
+  S.sb.key[0] = c->sb.key[0]; S.sb.idx[0] = c->sb.idx[0]; S.sb.key[1] = c->sb.key[1]; S.sb.idx[1] = c->sb.idx[1];
+  S.sb.table = c->table2; S.sb.totals = c->totals2;
+  S.keyC = c->keyC; S.sort_cap = c->sort_cap; S.stage = c->h_stage; S.fill_kernels = false;
+  return S;
+}
+
+static hipError_t clear_bytes(hipStream_t st, void* p, int value, uint64_t bytes, bool fill_kernels) {
+  if (!fill_kernels) return hipMemsetAsync(p, value, bytes, st);
+  launch_fill_u64(st, (uint64_t*)p, (bytes + 7) / 8, value ? ~0ull : 0ull);     // regions are padded to 256 bytes
+  return hipGetLastError();
+}
+
 // Stages host-resident rows, clears the grid's presence counts and places every row in its cell.
-static hipError_t place_snapshots(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, uint64_t n_cell,
-                                  HangArgs& a, bool exact) {
+static hipError_t place_snapshots(ccld_ctx* c, const HangScratch& S, const ccld_snapshots* sn, uint64_t n_rows,
+                                  uint64_t n_cell, HangArgs& a, bool exact) {
   hipStream_t st = c->stream;
   std::memset(&a, 0, sizeof(a));
   hipError_t e = hipSuccess;
@@ -607,7 +647,7 @@ static hipError_t place_snapshots(ccld_ctx* c, const ccld_snapshots* sn, uint64_
     a.snap = sn->snap; a.rank = sn->rank; a.comm = sn->comm; a.channel = sn->channel;
     a.seq_posted = sn->seq_posted; a.sent = sn->chunks_sent; a.recv = sn->chunks_recv;
   } else if (n_rows) {
-    uint64_t* d_seq = (uint64_t*)c->h_stage;
+    uint64_t* d_seq = (uint64_t*)S.stage;
     uint32_t* d32 = (uint32_t*)(d_seq + n_rows);
     const uint32_t* src[6] = {sn->snap, sn->rank, sn->comm, sn->channel, sn->chunks_sent, sn->chunks_recv};
     if ((e = hipMemcpyAsync(d_seq, sn->seq_posted, 8 * n_rows, hipMemcpyHostToDevice, st)) != hipSuccess) return e;
@@ -617,15 +657,15 @@ static hipError_t place_snapshots(ccld_ctx* c, const ccld_snapshots* sn, uint64_
     a.sent = d32 + 4 * n_rows; a.recv = d32 + 5 * n_rows;
   }
   a.n_rows = n_rows; a.n_snap = sn->n_snapshots; a.n_ch = sn->n_channels; a.T = c->topo; a.mb = c->kf.mb; a.n_members = c->n_members;
-  a.cell = c->h_cell; a.cnt = c->h_cnt; a.pair = c->h_pair; a.hcomm = c->h_comm; a.wait_slot = c->h_wait_slot;
-  a.cand = c->h_cand; a.layer_max = c->h_layer_max; a.counters = c->counters;
+  a.cell = S.cell; a.cnt = S.cnt; a.pair = S.pair; a.hcomm = S.hcomm; a.wait_slot = S.wait_slot;
+  a.cand = S.cand; a.layer_max = S.layer_max; a.counters = S.counters;
   a.stall_snapshots = c->p.stall_snapshots; a.fifo_depth = c->p.fifo_depth;
 
   c->prof.begin(CCLD_PROF_HANG);
-  if ((e = hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st)) != hipSuccess) return e;
+  if ((e = clear_bytes(st, S.counters, 0, sizeof(uint64_t) * CNT_COUNT, S.fill_kernels)) != hipSuccess) return e;
   a.exact = exact ? 1 : 0;
-  if (exact) e = hipMemsetAsync(c->h_cnt, 0, sizeof(uint32_t) * ((n_cell + 31) / 32), st);
-  else e = hipMemsetAsync(c->h_cell, 0xFF, 16 * n_cell, st);
+  if (exact) e = clear_bytes(st, S.cnt, 0, sizeof(uint32_t) * ((n_cell + 31) / 32), S.fill_kernels);
+  else e = clear_bytes(st, S.cell, 0xFF, 16 * n_cell, S.fill_kernels);
   if (e != hipSuccess) return e;
   if (n_rows) {
     uint64_t g = (n_rows + 255) / 256; if (g > 4096) g = 4096;
@@ -635,7 +675,9 @@ static hipError_t place_snapshots(ccld_ctx* c, const ccld_snapshots* sn, uint64_
   return hipSuccess;
 }
 
-extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, ccld_hang_result* o) {
+// argument checks shared by the hang entry points; *n_cell receives the grid size
+static ccld_status check_hang_args(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, ccld_hang_result* o,
+                                   uint64_t* n_cell) {
   if (!c || !sn || !o) return CCLD_E_NULL;
   o->n_root = o->n_pair = o->n_hung_comm = 0;
   o->status = CCLD_OK;
@@ -643,11 +685,14 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
   if (n_rows && (!sn->snap || !sn->rank || !sn->comm || !sn->channel || !sn->seq_posted || !sn->chunks_sent || !sn->chunks_recv))
     return o->status = CCLD_E_NULL;
   if (sn->n_snapshots == 0 || sn->n_channels == 0) return o->status = CCLD_E_BAD_ARG;
-  const uint64_t n_cell = c->n_members * sn->n_channels * sn->n_snapshots;
-  if (n_cell > c->snap_cap || n_rows > c->snap_cap) return o->status = CCLD_E_CAPACITY;
-  hipStream_t st = c->stream;
+  *n_cell = c->n_members * sn->n_channels * sn->n_snapshots;
+  return CCLD_OK;
+}
 
-  c->inc_ok = false;            // the root list is sorted in the window's sort buffers
+// the hang pass proper, on scratch memory S (n_cell cells and n_rows rows fit it)
+static ccld_status locate_hang_on(ccld_ctx* c, const HangScratch& S, const ccld_snapshots* sn, uint64_t n_rows,
+                                  uint64_t n_cell, ccld_hang_result* o) {
+  hipStream_t st = c->stream;
   HangArgs a;
   const uint32_t nm = (uint32_t)c->n_members;
   // One row per cell is the normal case: the rows are placed without the presence bitmap (its atomics are a
@@ -655,10 +700,10 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
   // and no row was refused for a worse reason, or if the row count already rules the normal case out, the
   // placement is repeated with the bitmap, which tells duplicates from gaps.
   for (bool exact = n_rows != n_cell;; exact = true) {
-    HIP_TRY(place_snapshots(c, sn, n_rows, n_cell, a, exact));
+    HIP_TRY(place_snapshots(c, S, sn, n_rows, n_cell, a, exact));
     hipLaunchKernelGGL(k_hang_pairs, dim3((nm + 3) / 4), dim3(256), 0, st, a);
     HIP_TRY(hipGetLastError());
-    HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(c->h_pinned, S.counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (exact || c->h_pinned[CNT_STATUS] != (uint64_t)DS_SUSPECT) break;
     c->prof.end(CCLD_PROF_HANG);
@@ -669,38 +714,36 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
   hipLaunchKernelGGL(k_hang_filter, dim3((nm + 255) / 256), dim3(256), 0, st, a);
   hipLaunchKernelGGL(k_hang_hops, dim3((nm + 255) / 256), dim3(256), 0, st, a);
   // roots in (rank, communicator) order
-  PredRoot pr{c->h_cand};
-  run_select(st, pr, nm, c->tile_flags, c->h_root_list, &c->counters[CNT_NCAND]);
-  PredHung ph{c->h_comm + (uint64_t)CCLD_HCOMM_HUNG * c->topo.n_comms};
-  run_select(st, ph, c->topo.n_comms, c->tile_heads, c->alert_list, &c->counters[CNT_NALERT]);
+  PredRoot pr{S.cand};
+  run_select(st, pr, nm, S.tiles_a, S.root_list, &S.counters[CNT_NCAND]);
+  PredHung ph{S.hcomm + (uint64_t)CCLD_HCOMM_HUNG * c->topo.n_comms};
+  run_select(st, ph, c->topo.n_comms, S.tiles_b, S.comm_list, &S.counters[CNT_NALERT]);
   HIP_TRY(hipGetLastError());
-  HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(c->h_pinned, S.counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   const uint32_t n_root = (uint32_t)c->h_pinned[CNT_NCAND];
   o->n_root = n_root;
   o->n_hung_comm = c->h_pinned[CNT_NALERT];
   o->n_pair = c->n_members;
   if (n_root && o->root_cap) {
-    SortBuffers sb2;
-    sb2.key[0] = c->sb.key[0]; sb2.idx[0] = c->sb.idx[0]; sb2.key[1] = c->sb.key[1]; sb2.idx[1] = c->sb.idx[1];
-    sb2.table = c->table2; sb2.totals = c->totals2;
-    if (n_root > c->sort_cap) return o->status = CCLD_E_CAPACITY;
-    hipLaunchKernelGGL(k_hang_root_keys, dim3((n_root + 255) / 256), dim3(256), 0, st, a, (const u32*)c->h_root_list, n_root, c->kf.cb, c->keyC);
-    KeySource ks; ks.key = c->keyC; ks.head = 0; ks.cap = n_root; ks.squeeze = 0; ks.hi_shift = 0; ks.lo_bits = 0; ks.lo_mask = 0; ks.lo_sub = 0;
+    const SortBuffers& sb2 = S.sb;
+    if (n_root > S.sort_cap) return o->status = CCLD_E_CAPACITY;
+    hipLaunchKernelGGL(k_hang_root_keys, dim3((n_root + 255) / 256), dim3(256), 0, st, a, (const u32*)S.root_list, n_root, c->kf.cb, S.keyC);
+    KeySource ks; ks.key = S.keyC; ks.head = 0; ks.cap = n_root; ks.squeeze = 0; ks.hi_shift = 0; ks.lo_bits = 0; ks.lo_mask = 0; ks.lo_sub = 0;
     const int r = radix_sort_pairs(st, ks, n_root, sb2, c->kf.cb + c->rank_bits);
     if (r < 0) return o->status = CCLD_E_HIP;
-    hipLaunchKernelGGL(k_hang_root_emit, dim3((n_root + 255) / 256), dim3(256), 0, st, a, (const u32*)c->h_root_list,
+    hipLaunchKernelGGL(k_hang_root_emit, dim3((n_root + 255) / 256), dim3(256), 0, st, a, (const u32*)S.root_list,
                        (const u32*)sb2.idx[r], n_root, o->root, o->root_cap);
   }
   if (o->pair && o->pair_cap) {
     const uint64_t rows = std::min<uint64_t>(o->pair_cap, c->n_members);
     hipLaunchKernelGGL(k_copy_table, dim3((uint32_t)((rows * CCLD_HPAIR_NCOL + 255) / 256)), dim3(256), 0, st,
-                       (const i64*)c->h_pair, c->n_members, o->pair, o->pair_cap, rows, (int)CCLD_HPAIR_NCOL);
+                       (const i64*)S.pair, c->n_members, o->pair, o->pair_cap, rows, (int)CCLD_HPAIR_NCOL);
   }
   if (o->comm && o->comm_cap) {
     const uint64_t rows = std::min<uint64_t>(o->comm_cap, c->topo.n_comms);
     hipLaunchKernelGGL(k_copy_table, dim3((uint32_t)((rows * CCLD_HCOMM_NCOL + 255) / 256)), dim3(256), 0, st,
-                       (const i64*)c->h_comm, (uint64_t)c->topo.n_comms, o->comm, o->comm_cap, rows, (int)CCLD_HCOMM_NCOL);
+                       (const i64*)S.hcomm, (uint64_t)c->topo.n_comms, o->comm, o->comm_cap, rows, (int)CCLD_HCOMM_NCOL);
   }
   c->prof.end(CCLD_PROF_HANG);
   HIP_TRY(hipGetLastError());
@@ -709,6 +752,96 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
   if (o->n_root > o->root_cap || (o->pair && o->pair_cap < c->n_members) || (o->comm && o->comm_cap < c->topo.n_comms))
     o->status = CCLD_W_TRUNCATED;
   return o->status;
+}
+
+extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, ccld_hang_result* o) {
+  uint64_t n_cell = 0;
+  const ccld_status s = check_hang_args(c, sn, n_rows, o, &n_cell);
+  if (s != CCLD_OK) return s;
+  if (n_cell > c->snap_cap || n_rows > c->snap_cap) return o->status = CCLD_E_CAPACITY;
+  c->inc_ok = false;            // the root list is sorted in the window's sort buffers
+  return locate_hang_on(c, scratch_of_context(c), sn, n_rows, n_cell, o);
+}
+
+// ---- hang location on the library's static device array ------------------------------------------------
+// For callers that cannot allocate device memory and whose context was created without room for snapshots:
+// the grid, the per-member and per-communicator tables and the sort buffers of the hang pass live in one
+// file-scope device array.  Every GPU the library runs on holds its own copy of the array at its own
+// address until the process ends; the address is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[CCLD_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+unsigned char* g_scratch_ptr[MAX_DEVICES] = {nullptr};     // device address of `scratch` on each GPU
+std::mutex g_scratch_mutex;
+
+// device address of the static array on the current device (looked up on the first call per device)
+ccld_status static_scratch_address(unsigned char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) { (void)hipGetLastError(); return CCLD_E_HIP; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return CCLD_E_HIP; }
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return CCLD_OK;
+}
+
+// Bump allocator over the static array; regions start on 256-byte boundaries and are padded to them.
+struct StaticCarver {
+  unsigned char* base; uint64_t off;
+  template <class T> T* take(uint64_t count) {
+    T* p = reinterpret_cast<T*>(base + off);
+    off += (count * sizeof(T) + 255) & ~(uint64_t)255;
+    return p;
+  }
+};
+}  // namespace
+
+// called by ccld_create with the context's device current: the first look-up happens at set-up
+ccld_status ccld_static_scratch_init() {
+  unsigned char* p = nullptr;
+  return static_scratch_address(&p);
+}
+
+extern "C" ccld_status ccld_locate_hang_static(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows,
+                                               ccld_hang_result* o) {
+  uint64_t n_cell = 0;
+  const ccld_status s = check_hang_args(c, sn, n_rows, o, &n_cell);
+  if (s != CCLD_OK) return s;
+  unsigned char* base = nullptr;
+  const ccld_status sa = static_scratch_address(&base);
+  if (sa != CCLD_OK) return o->status = sa;
+  const uint64_t nm = c->n_members, nc = c->topo.n_comms;
+  // every size below is bounded before it is multiplied: a grid beyond the array is refused here
+  if (n_cell > CCLD_STATIC_SCRATCH_BYTES / 16 || n_rows > CCLD_STATIC_SCRATCH_BYTES / 32 ||
+      nm > CCLD_STATIC_SCRATCH_BYTES / 64 || nc > CCLD_STATIC_SCRATCH_BYTES / 64)
+    return o->status = CCLD_E_CAPACITY;
+  HangScratch S;
+  StaticCarver w{base, 0};
+  S.counters = w.take<uint64_t>(CNT_COUNT);
+  S.cell = w.take<uint64_t>(2 * n_cell);
+  S.cnt = w.take<uint32_t>(n_cell / 32 + 1);
+  S.pair = w.take<int64_t>((uint64_t)CCLD_HPAIR_NCOL * nm);
+  S.hcomm = w.take<int64_t>((uint64_t)CCLD_HCOMM_NCOL * nc);
+  S.wait_slot = w.take<int32_t>(nm);
+  S.cand = w.take<uint8_t>(nm);
+  S.layer_max = w.take<uint64_t>(nm);
+  S.root_list = w.take<uint32_t>(nm + 1);
+  S.tiles_a = w.take<uint32_t>(nm / SEL_TILE + 3);
+  S.tiles_b = w.take<uint32_t>(nc / SEL_TILE + 3);
+  S.comm_list = w.take<uint32_t>(nc + 1);
+  for (int i = 0; i < 2; ++i) { S.sb.key[i] = w.take<uint64_t>(nm + 1); S.sb.idx[i] = w.take<uint32_t>(nm + 1); }
+  S.sb.table = w.take<uint32_t>(sort_table_words(nm + 1));
+  S.sb.totals = w.take<uint32_t>(SORT_RADIX);
+  S.keyC = w.take<uint64_t>(nm + 1);
+  S.sort_cap = nm;
+  S.stage = sn->on_device ? nullptr : w.take<uint8_t>(n_rows * 32);
+  S.fill_kernels = true;
+  if (w.off > CCLD_STATIC_SCRATCH_BYTES) return o->status = CCLD_E_CAPACITY;
+  return locate_hang_on(c, S, sn, n_rows, n_cell, o);
 }
 
 extern "C" ccld_status ccld_progress_rates(ccld_ctx* c, const ccld_snapshots* sn, uint64_t n_rows, ccld_rate_result* o) {
@@ -724,7 +857,7 @@ extern "C" ccld_status ccld_progress_rates(ccld_ctx* c, const ccld_snapshots* sn
   HangArgs a;
   const uint32_t nm = (uint32_t)c->n_members;
   for (bool exact = n_rows != n_cell;; exact = true) {       // see ccld_locate_hang
-    HIP_TRY(place_snapshots(c, sn, n_rows, n_cell, a, exact));
+    HIP_TRY(place_snapshots(c, scratch_of_context(c), sn, n_rows, n_cell, a, exact));
     if (nm) hipLaunchKernelGGL(k_rate_pairs, dim3((nm + 3) / 4), dim3(256), 0, st, a);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
