@@ -78,8 +78,14 @@ typedef struct {
   uint32_t stall_snapshots;    /* [30] a counter unchanged over this many snapshots is stalled              */
   uint32_t fifo_depth;         /* [8] ring back-pressure depth used by the wait-for edges                   */
   uint32_t window_batches;     /* [1] the window holds the last this-many ingested batches                  */
-  uint32_t reserved;
+  uint32_t placement;          /* [CCLD_PLACEMENT_AUTO] how ccld_analyze_window brings a collective's records together */
 } ccld_params;
+
+/* ccld_params.placement.  AUTO: a window of one batch whose (communicator, operation counter, member) grid
+ * is dense (Section 5.1: every rank bumps the same counter, so the Trace ID fixes the record's cell) is
+ * analysed without sorting; any other window, and any window in which the attempt finds a round without a
+ * single record or counters that are far apart, is sorted.  SORT: always sort.  Both give the same tables. */
+enum { CCLD_PLACEMENT_AUTO = 0, CCLD_PLACEMENT_SORT = 1 };
 
 /* Communicator table (host pointers, copied by ccld_create). */
 typedef struct {
@@ -156,7 +162,7 @@ typedef struct {
   uint32_t *perm;      /* device [n_records] or NULL: window index of the j-th record in (comm, seq, rank) order */
   uint64_t n_records, n_seg, n_flag, n_group, n_alert, n_cand;  /* out (host)                   */
   ccld_status status;  /* out (host): CCLD_OK, a data error (no tables written), or CCLD_W_TRUNCATED */
-  int32_t reserved;
+  int32_t path;        /* out (host): 0 the window was sorted, 1 it was analysed by dense placement     */
 } ccld_window_result;
 
 /* hang location tables */
@@ -347,7 +353,7 @@ ccld_status ccld_rank_blame(ccld_ctx *ctx, int64_t *blame, uint32_t *order);
  * accumulated milliseconds and launch counts (host arrays of CCLD_PROF_NCLASS entries). */
 enum { CCLD_PROF_INGEST, CCLD_PROF_SORT_HIST, CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER, CCLD_PROF_SEGMENTS,
        CCLD_PROF_FLAGS, CCLD_PROF_BLAME, CCLD_PROF_GROUPS, CCLD_PROF_ALERTS, CCLD_PROF_HANG,
-       CCLD_PROF_SEG_HEADS,
+       CCLD_PROF_SEG_HEADS, CCLD_PROF_DENSE_PARTITION,
        CCLD_PROF_NCLASS = 16 };
 ccld_status ccld_profile_enable(ccld_ctx *ctx, int32_t on);
 ccld_status ccld_profile_read(ccld_ctx *ctx, double *ms, uint64_t *launches, uint64_t *sort_passes);

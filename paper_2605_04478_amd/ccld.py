@@ -42,7 +42,7 @@ class Params(C.Structure):
                 ("theta_den", C.c_uint32), ("alpha_num", C.c_uint32), ("beta_num", C.c_uint32),
                 ("ab_den", C.c_uint32), ("barrier_bytes", C.c_uint32), ("kmad_num", C.c_uint32),
                 ("kmad_den", C.c_uint32), ("lag_floor_ns", C.c_int64), ("stall_snapshots", C.c_uint32),
-                ("fifo_depth", C.c_uint32), ("window_batches", C.c_uint32), ("reserved", C.c_uint32)]
+                ("fifo_depth", C.c_uint32), ("window_batches", C.c_uint32), ("placement", C.c_uint32)]
 
 
 class _Topology(C.Structure):
@@ -68,7 +68,7 @@ class _WindowResult(C.Structure):
                 ("cand", C.c_void_p), ("lag_enter", C.c_void_p), ("lag_exit", C.c_void_p),
                 ("rec_flag", C.c_void_p), ("perm", C.c_void_p),
                 ("n_records", C.c_uint64), ("n_seg", C.c_uint64), ("n_flag", C.c_uint64), ("n_group", C.c_uint64),
-                ("n_alert", C.c_uint64), ("n_cand", C.c_uint64), ("status", C.c_int32), ("reserved", C.c_int32)]
+                ("n_alert", C.c_uint64), ("n_cand", C.c_uint64), ("status", C.c_int32), ("path", C.c_int32)]
 
 
 class _HangResult(C.Structure):
@@ -97,7 +97,8 @@ class _RateResult(C.Structure):
 _lib: Optional[C.CDLL] = None
 
 PROF_CLASSES = ("ingest", "sort_hist", "sort_scan", "sort_scatter", "segments", "flags", "blame", "groups", "alerts",
-                "hang", "seg_heads")
+                "hang", "seg_heads", "dense_partition")
+PLACEMENT_AUTO, PLACEMENT_SORT = 0, 1
 PROF_NCLASS = 16
 
 EXPORTS = ("ccld_profile_enable", "ccld_profile_read", "ccld_default_params", "ccld_query_workspace", "ccld_create", "ccld_destroy", "ccld_ingest",
@@ -173,6 +174,7 @@ class WindowResult:
     n_cand: int
     caps: Dict[str, int]
     dev: Dict[str, "object"] = field(repr=False, default_factory=dict)   # device tensors
+    path: int = 0                    # 0: the window was sorted, 1: dense placement
 
     @property
     def seg(self): return _table(self.dev["seg"], SEG_COLS, self.caps["seg"], self.n_seg)
@@ -350,7 +352,7 @@ class Analyzer:
         if st in (-7, -11, -6):
             raise CcldError(st, "ccld_analyze_window")
         return WindowResult(STATUS.get(st, str(st)), r.n_records, r.n_seg, r.n_flag, r.n_group, r.n_alert,
-                            r.n_cand, caps, dev)
+                            r.n_cand, caps, dev, int(r.path))
 
     def rank_blame(self, to_host: bool = True, buffers=None):
         """-> (blame columns, order).  to_host=False leaves both on the device (column-major int64 table

@@ -6,6 +6,7 @@
 #include "ccld_internal.h"
 #include "window_kernels.h"
 #include "merge.h"
+#include "dense.h"
 
 using namespace ccld;
 
@@ -82,6 +83,18 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->counters = w.take<uint64_t>(CNT_COUNT);
   c->blame = w.take<int64_t>((uint64_t)CCLD_BLM_NCOL * n_ranks);
   c->stage = w.take<uint8_t>(B * 48);
+  // dense placement: counter ranges, layout, fine-bucket fill counts and the partitioned rows (room for an
+  // eighth more cells than records, and one partly filled fine bucket per communicator)
+  c->fine_cap = 0;
+  c->comm_range = nullptr; c->d_lay = nullptr; c->d_hdr = nullptr; c->d_fill = nullptr; c->d_rows = nullptr;
+  if (c->dense_capable) {
+    c->fine_cap = (uint32_t)((N + N / 8) / DENSE_B + n_comms + 16);
+    c->comm_range = w.take<uint64_t>(2ull * n_comms);
+    c->d_lay = w.take<CommLayout>((uint64_t)n_comms + 1);
+    c->d_hdr = w.take<uint32_t>(DH_COUNT);
+    c->d_fill = w.take<uint32_t>((uint64_t)c->fine_cap + 4);
+    c->d_rows = w.take<Row>((uint64_t)c->fine_cap * DENSE_STRIDE);
+  }
   // hang location
   const uint64_t SN = std::max<uint64_t>(c->snap_cap, 1);
   c->n_members = n_members;
@@ -102,7 +115,8 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
 ccld_status check_params(const ccld_params* p) {
   if (!p) return CCLD_E_NULL;
   if (p->tbase_rounds < 1 || p->theta_den < 1 || p->ab_den < 1 || p->kmad_den < 1 || p->tbase_warmup_ns < 0 ||
-      p->window_batches < 1 || p->window_batches > 4096 || p->hang_threshold_ns < 0)
+      p->window_batches < 1 || p->window_batches > 4096 || p->hang_threshold_ns < 0 ||
+      p->placement > CCLD_PLACEMENT_SORT)
     return CCLD_E_BAD_ARG;
   return CCLD_OK;
 }
@@ -141,6 +155,14 @@ ccld_status check_topology(const ccld_topology* t, uint64_t* n_members) {
   }
   *n_members = total;
   return CCLD_OK;
+}
+
+// Windows of one batch can be analysed by dense placement when every communicator fits a fine bucket and
+// the counting kernel's LDS holds a counter range per communicator.
+bool dense_capable(const ccld_params* p, const ccld_topology* t) {
+  if (p->placement == CCLD_PLACEMENT_SORT || p->window_batches != 1 || t->n_comms > DENSE_MAX_COMMS) return false;
+  for (uint32_t k = 0; k < t->n_comms; ++k) if (t->size[k] > DENSE_B) return false;
+  return true;
 }
 
 ccld_status data_status(uint64_t bits) {
@@ -189,6 +211,7 @@ ccld_status ccld_query_workspace(const ccld_params* params, const ccld_topology*
     return CCLD_E_CAPACITY;
   ccld_ctx tmp;
   tmp.p = *params; tmp.cap = max_window_records; tmp.batch_cap = max_batch_records; tmp.snap_cap = max_snapshot_rows;
+  tmp.dense_capable = dense_capable(params, topo);
   Carver w{nullptr, 0};
   carve_all(&tmp, w, topo->n_ranks, topo->n_comms, n_members);
   *bytes = w.off + 256;
@@ -214,6 +237,8 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   c->stream = (hipStream_t)hip_stream;
   c->cap = max_window_records; c->batch_cap = max_batch_records; c->snap_cap = max_snapshot_rows;
   c->kf.mb = mb; c->kf.cb = cb; c->kf.sb = 64 - mb - cb;
+  c->dense_capable = dense_capable(params, topo);
+  c->last_path = 0;
   c->max_comm_size = max_size;
   c->rank_bits = bits_for_host(topo->n_ranks - 1);
   c->head = 0; c->count = 0; c->next_slot = 0; c->total_ingested = 0;
@@ -225,6 +250,9 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   {
     int bb = 0;
     while (bb < 6 && ((max_window_records * 32) >> bb) > 100000000ull) ++bb;
+    // dense placement partitions every bucket once more: about half a million records per bucket keep the
+    // fine buckets of two neighbouring buckets within what a partition workgroup addresses
+    if (c->dense_capable) while (bb < 8 && (max_window_records >> bb) > 512 * 1024) ++bb;
     c->bshift = cb > bb ? cb - bb : 0;
   }
   c->n_buckets = ((topo->n_comms - 1) >> c->bshift) + 1;
@@ -376,6 +404,10 @@ ccld_status ccld_ingest(ccld_ctx* c, const ccld_records* b, uint64_t n) {
   a.cap = (uint32_t)c->cap;
   a.table = c->ing_table; a.bucket_base = c->ing_base; a.scratch_total = &c->counters[CNT_COUNT - 1];
   a.n_buckets = c->n_buckets; a.bshift = c->bshift; a.seqno0 = (uint32_t)c->total_ingested;
+  if (c->dense_capable && n) {
+    a.range = c->comm_range;
+    HIP_TRY(hipMemsetAsync(a.range, 0, 16ull * c->topo.n_comms, c->stream));
+  }
   c->prof.begin(CCLD_PROF_INGEST);
   launch_ingest(c->stream, a, c->topo, c->kf);
   c->prof.end(CCLD_PROF_INGEST);
@@ -397,10 +429,14 @@ static void zero_counts(ccld_window_result* o) {
   o->n_records = o->n_seg = o->n_flag = o->n_group = o->n_alert = o->n_cand = 0;
 }
 
-ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result* o) {
-  if (!c || !o) return CCLD_E_NULL;
+// One analysis of the resident window.  dense: bring the collectives together by dense placement instead of
+// sorting; *fallback is set (and nothing of the context's detection state has changed) when the window turns
+// out not to fill a dense grid, and the caller then sorts.
+static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_result* o, bool dense, bool* fallback) {
   zero_counts(o);
   o->status = CCLD_OK;
+  o->path = dense ? 1 : 0;
+  *fallback = false;
   c->blame_valid = false;
   if (!o->seg || o->seg_cap == 0) return o->status = CCLD_E_NULL;
   if ((o->flag_cap && !o->flag) || (o->group_cap && !o->group) || (o->alert_cap && !o->alert) ||
@@ -459,7 +495,7 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   // A window of several batches that still holds at least half of the previously analysed window keeps that
   // window's order: the new records are sorted on their own and merged with the previous order, whose keys are
   // re-based to this window's format and whose entries of the batches that left are dropped on the way.
-  const bool was_ok = c->inc_ok;
+  const bool was_ok = c->inc_ok && !dense;
   c->inc_ok = false;
   const uint64_t cap = std::max<uint64_t>(c->cap, 1);
   const uint64_t n_new = c->total_ingested - c->inc_total;
@@ -501,29 +537,69 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
       }
     }
   }
+  DenseArgs da;
+  std::memset(&da, 0, sizeof(da));
+  uint32_t dense_n_seg = 0;
+  if (dense) {
+    // the grid's layout from the batch's counter ranges; its size comes back while the partition runs
+    da.win_key = c->win_key; da.win_row = c->win_row; da.head = (uint32_t)c->head; da.cap = (uint32_t)cap; da.n = n;
+    da.kf = c->kf; da.comm_size = c->topo.size; da.n_comms = c->topo.n_comms;
+    da.bucket_base = c->ing_base; da.n_buckets = c->n_buckets; da.bshift = c->bshift;
+    da.range = c->comm_range; da.lay = (CommLayout*)c->d_lay; da.hdr = c->d_hdr; da.fill = c->d_fill;
+    da.rows = c->d_rows; da.fine_cap = c->fine_cap; da.counters = c->counters;
+    c->prof.begin(CCLD_PROF_DENSE_PARTITION);
+    launch_dense_layout(st, da);
+    uint32_t* h_hdr = reinterpret_cast<uint32_t*>(c->h_pinned + 2 * CNT_COUNT);
+    HIP_TRY(hipMemcpyAsync(h_hdr, c->d_hdr, sizeof(uint32_t) * DH_COUNT, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipEventRecord(c->ev_heads, st));
+    launch_fill_u64(st, reinterpret_cast<uint64_t*>(c->d_fill), ((uint64_t)c->fine_cap + 4) / 2, 0ull);
+    launch_dense_partition(st, da);
+    launch_scan_tiles(st, c->d_fill, c->fine_cap + 1, &c->counters[CNT_NRETAINED]);
+    HIP_TRY(hipEventSynchronize(c->ev_heads));
+    if (!h_hdr[DH_FEASIBLE]) {          // far-apart counters or too many fine buckets: the kernels above did nothing
+      HIP_TRY(hipStreamSynchronize(st));
+      c->prof.end(CCLD_PROF_DENSE_PARTITION);
+      c->prof.collect();
+      *fallback = true;
+      return CCLD_OK;
+    }
+    dense_n_seg = h_hdr[DH_N_SEG];
+    sorted = 0;
+    c->sort_passes = 0;
+  } else {
   if (sorted < 0)
     sorted = radix_sort_pairs(st, src, n, c->sb, mb + ws + cb, &c->prof, CCLD_PROF_SORT_HIST,
                               CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER);
   c->sort_passes = (mb + ws + cb) <= 0 ? 1 : (mb + ws + cb + SORT_RBITS - 1) / SORT_RBITS;
   if (sorted < 0) return o->status = CCLD_E_HIP;
+  }
   c->sorted_buf = sorted;
   const uint64_t* skey = c->sb.key[sorted];
   const uint32_t* sidx = c->sb.idx[sorted];
+  const Row* rows = dense ? c->d_rows : c->win_row;     // payload rows that sidx addresses
 
   // 3. collectives: heads per tile, their scan, statistics, flags
   SegArgs sa;
   std::memset(&sa, 0, sizeof(sa));
-  sa.key = skey; sa.idx = sidx; sa.row = c->win_row; sa.n = n; sa.sf = c->sf; sa.comm_size = c->topo.size;
+  sa.key = skey; sa.idx = sidx; sa.row = rows; sa.n = n; sa.sf = c->sf; sa.comm_size = c->topo.size;
   sa.member_off = c->topo.member_off; sa.members_sorted = c->topo.members_sorted;
   sa.tile_heads = c->tile_heads; sa.seg = o->seg; sa.seg_cap = o->seg_cap;
   sa.rec_flag = o->rec_flag ? o->rec_flag : c->rec_flag;
   sa.lag_e = o->lag_enter; sa.lag_x = o->lag_exit; sa.flag_lag = c->flag_lag; sa.cap_n = c->cap;
-  sa.big_list = c->big_list; sa.big_ex = c->big_ex; sa.counters = c->counters;
+  sa.big_list = c->big_list; sa.big_cap = c->cap / 65 + 2; sa.big_ex = c->big_ex; sa.counters = c->counters;
   sa.lag_floor = c->p.lag_floor_ns; sa.kmad_num = c->p.kmad_num; sa.kmad_den = c->p.kmad_den;
   sa.barrier_bytes = c->p.barrier_bytes; sa.max_size = c->max_comm_size;
   sa.gkey = c->keyC; sa.range_c = c->range_c;
   sa.no_group = (uint64_t)c->topo.n_comms * CCLD_OP_MAX * GROUP_CLS;     // one past every group key
   const uint32_t seg_tiles = (n + SEG_TILE - 1) / SEG_TILE;
+  if (dense) {
+    // every collective's row of the table is fixed by the layout; a duplicate key or a round without any
+    // record shows in the status word at the end (the group stage leaves the detection state alone then)
+    c->prof.split(CCLD_PROF_DENSE_PARTITION, CCLD_PROF_SEGMENTS);
+    launch_dense_stats(st, sa, da, c->sb.key[sorted], c->sb.idx[sorted], c->blame, n_ranks);
+    c->prof.split(CCLD_PROF_SEGMENTS, CCLD_PROF_FLAGS);
+    o->n_seg = dense_n_seg;
+  } else {
   c->prof.begin(CCLD_PROF_SEG_HEADS);
   launch_keys_pass(st, skey, n, c->sf, c->topo, c->blame, c->tile_heads, c->counters);
   launch_scan_tiles(st, c->tile_heads, seg_tiles, &c->counters[CNT_NSEG]);
@@ -537,10 +613,12 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   if (c->h_pinned[CNT_STATUS]) {
     const uint64_t bad = c->h_pinned[CNT_STATUS];
     HIP_TRY(hipStreamSynchronize(st));
+    c->prof.collect();
     zero_counts(o);
     return o->status = data_status(bad);
   }
   o->n_seg = c->h_pinned[CNT_NSEG];
+  }
   const uint32_t seg_rows = (uint32_t)std::min<uint64_t>(o->n_seg, o->seg_cap);
   FlagArgs fa;
   std::memset(&fa, 0, sizeof(fa));
@@ -553,13 +631,13 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   uint64_t* h_flags = c->h_pinned + CNT_COUNT;
   HIP_TRY(hipMemcpyAsync(h_flags, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipEventRecord(c->ev_flags, st));
-  if (o->perm) launch_perm(st, sidx, c->win_row, n, c->batch_seqno.empty() ? 0u : c->batch_seqno[0], o->perm);
+  if (o->perm) launch_perm(st, sidx, rows, n, c->batch_seqno.empty() ? 0u : c->batch_seqno[0], o->perm);
 
   // 4. hang alerts: which collectives
   AlertArgs aa;
   std::memset(&aa, 0, sizeof(aa));
   aa.seg = o->seg; aa.seg_cap = o->seg_cap; aa.n_seg = seg_rows; aa.now_ns = now_ns;
-  aa.hang_threshold_ns = c->p.hang_threshold_ns; aa.key = skey; aa.idx = sidx; aa.row = c->win_row; aa.n = n;
+  aa.hang_threshold_ns = c->p.hang_threshold_ns; aa.key = skey; aa.idx = sidx; aa.row = rows; aa.n = n;
   aa.sf = c->sf; aa.topo = c->topo; aa.tile_counts = c->tile_heads; aa.alert_list = c->alert_list;
   aa.alert_ncand = c->alert_ncand; aa.alert = o->alert; aa.alert_cap = o->alert_cap; aa.cand = o->cand;
   aa.cand_cap = o->cand_cap; aa.counters = c->counters;
@@ -609,7 +687,13 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   launch_blame_order(st, c->blame, n_ranks, c->blame_list, c->blame_tiles, c->counters, c->blame_order);
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
-  if (c->h_pinned[CNT_STATUS]) { zero_counts(o); return o->status = data_status(c->h_pinned[CNT_STATUS]); }
+  if (c->h_pinned[CNT_STATUS]) {
+    const uint64_t bad = c->h_pinned[CNT_STATUS];
+    c->prof.collect();
+    zero_counts(o);
+    if (dense && (bad & DS_DENSE_FALLBACK)) { *fallback = true; return CCLD_OK; }
+    return o->status = data_status(bad);
+  }
   o->n_flag = c->h_pinned[CNT_NFLAG];
   o->n_alert = c->h_pinned[CNT_NALERT];
   o->n_group = c->h_pinned[CNT_NGROUP];
@@ -630,9 +714,21 @@ ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result*
   c->prof.collect();
   c->blame_valid = true;
   // the order of this window serves the next analysis (windows of several batches only)
-  c->inc_ok = c->p.window_batches > 1;
+  c->inc_ok = c->p.window_batches > 1 && !dense;
+  c->last_path = dense ? 1 : 0;
   c->inc_sf = c->sf; c->inc_head = c->head; c->inc_count = n; c->inc_total = c->total_ingested;
   return o->status;
+}
+
+ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result* o) {
+  if (!c || !o) return CCLD_E_NULL;
+  bool fallback = false;
+  // a window of one batch is first tried by dense placement; one that does not fill a dense grid is sorted
+  if (c->dense_capable && c->batch_n.size() == 1 && c->count > 0) {
+    const ccld_status s = analyze_window_once(c, now_ns, o, true, &fallback);
+    if (!fallback) return s;
+  }
+  return analyze_window_once(c, now_ns, o, false, &fallback);
 }
 
 ccld_status ccld_rank_blame(ccld_ctx* c, int64_t* blame, uint32_t* order) {

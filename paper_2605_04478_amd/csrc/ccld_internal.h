@@ -69,7 +69,8 @@ constexpr int GROUP_SLOTS = CCLD_OP_MAX * GROUP_CLS;
 // status bits accumulated on the device
 enum { DS_UNKNOWN_COMM = 1, DS_NOT_MEMBER = 2, DS_RANGE = 4, DS_KEY_WIDTH = 8, DS_DUPLICATE = 16,
        DS_SNAPSHOT_GAP = 32,
-       DS_SUSPECT = 64 };   // snapshot grid placed without the presence bitmap: a cell still holds the fill pattern
+       DS_SUSPECT = 64,     // snapshot grid placed without the presence bitmap: a cell still holds the fill pattern
+       DS_DENSE_FALLBACK = 128 };   // the window does not fill a dense grid (far-apart counters, a round without any record): sort instead
 
 struct BatchSlot { uint64_t n; };
 
@@ -155,6 +156,15 @@ struct ccld_ctx {
   uint64_t* f_last;                   // [n_members][CCLD_FRAME_CHANNELS][2] remembered (operation counter, sent | recv << 32) per member and channel
   uint32_t* f_seen;                   // [n_ranks / 32 + 1] ranks that delivered a frame in the current call
   uint8_t* h_stage;                   // [snap_cap * 32] device staging for host-resident snapshots
+  // dense placement (single-batch windows)
+  bool dense_capable;                 // window_batches == 1, every communicator fits a fine bucket, few enough communicators
+  uint64_t* comm_range;               // [n_comms][2] per communicator of the latest batch: largest counter, largest complement
+  void* d_lay;                        // [n_comms + 1] CommLayout
+  uint32_t* d_hdr;                    // [DH_COUNT]
+  uint32_t* d_fill;                   // [fine_cap + 2]
+  ccld::Row* d_rows;                  // [fine_cap * DENSE_STRIDE]
+  uint32_t fine_cap;
+  int last_path;                      // 1: the last analysis used the dense placement
   // last analysis
   int sorted_buf;                     // which ping-pong buffer holds the sorted window
   // the order of the last analysed window, kept for the next analysis of a window of several batches

@@ -6,6 +6,7 @@
 // up to 2,048 records a workgroup each with a bitonic sort in LDS, and longer ones the counting
 // selection of k_seg_big.
 #include "window_kernels.h"
+#include "dense.h"
 #include "device_utils.h"
 
 #ifndef CCLD_USE_DPP
@@ -40,6 +41,13 @@ __device__ __forceinline__ void seg_put_group(const SegArgs& a, u32 srow, bool u
   a.range_c[srow] = range;
 }
 __device__ __forceinline__ i64 absdiff(i64 a, i64 b) { return a >= b ? a - b : b - a; }
+// payload row of the j-th record in (communicator, counter, rank) order; the op word's upper bits belong
+// to the dense placement
+__device__ __forceinline__ Row load_row(const SegArgs& a, u32 j) {
+  Row r = a.row[a.idx[j]];
+  r.op &= 15u;
+  return r;
+}
 __device__ __forceinline__ bool is_late(i64 lag, i64 floor_ns, u32 knum, u32 kden, i64 mad) {
   return lag > floor_ns && (i128)lag * (i128)kden > (i128)knum * (i128)mad;
 }
@@ -153,7 +161,7 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
     if (valid) {
       j = base + a0 + l;
       key = a.key[j];
-      const Row rw = a.row[a.idx[j]];
+      const Row rw = load_row(a, j);
       // the slot -> rank lookup overlaps the row gather
       rank = a.members_sorted[a.member_off[(u32)(key >> (mb + a.sf.ws))] + (u32)(key & mmask)];
       e = rw.t_enter; x = rw.t_exit; nb = rw.bytes; op = rw.op;
@@ -356,10 +364,11 @@ __device__ __forceinline__ i64 mad_of_sorted(const i64 (&v)[E], u32 nd, u32 km) 
   return r;
 }
 
-// One wavefront per listed collective of 32 E + 1 .. 64 E records.
+// One wavefront per listed collective of 32 E + 1 .. 64 E records (E = 1: of 1 .. 64 records; only the dense
+// placement lists collectives that short, those of communicators with more than 64 members).
 template <int E>
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_multi(SegArgs a) {
-  constexpr u32 LO = 32 * E + 1, HI = 64 * E, NW = SEG_THREADS / CCLD_WAVE;
+  constexpr u32 LO = E == 1 ? 1 : 32 * E + 1, HI = 64 * E, NW = SEG_THREADS / CCLD_WAVE;
   const u32 lane = lane_id();
   const int mb = a.sf.mb;
   const u64 mmask = ((u64)1 << mb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
@@ -388,7 +397,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_multi(SegArgs a) {
       if (valid) {
         const u32 j = a0 + i;
         const u64 key = a.key[j];
-        const Row rw = a.row[a.idx[j]];
+        const Row rw = load_row(a, j);
         rank = ms[(u32)(key & mmask)];
         e[r] = rw.t_enter; x[r] = rw.t_exit; nb = rw.bytes; op = rw.op;
       }
@@ -535,7 +544,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
     if (nn < LO || nn > CAPN) continue;
     const u32 srow = a.big_list[3 * ent], a0 = a.big_list[3 * ent + 1];
     const u64 k0 = a.key[a0];
-    const Row h = a.row[a.idx[a0]];
+    const Row h = load_row(a, a0);
     if (t == 0) {
       acc.imin = (unsigned long long)T_INFLIGHT; acc.dmin = INT64_MAX; acc.dmax = INT64_MIN;
       acc.ninfl = 0; acc.incons = 0; acc.rmin = 0xFFFFFFFFu; acc.rmax = 0xFFFFFFFFu;
@@ -547,7 +556,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
       i64 imin = T_INFLIGHT, dmin = INT64_MAX, dmax = INT64_MIN;
       for (u32 i = t; i < nn; i += TT) {
         const u32 j = a0 + i;
-        const Row rw = a.row[a.idx[j]];
+        const Row rw = load_row(a, j);
         E[i] = rw.t_enter; X[i] = rw.t_exit;
         inc |= (rw.op != h.op || rw.bytes != h.bytes);
         if (rw.t_exit == T_INFLIGHT) {
@@ -664,11 +673,11 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
       if (stop) break;
     }
     const u32 b0 = s_end, nn = b0 - a0;
-    const Row h = a.row[a.idx[a0]];
+    const Row h = load_row(a, a0);
     {
       u32 ni = 0; bool inc = false; i64 imin = T_INFLIGHT;
       for (u32 j = a0 + tid; j < b0; j += SEG_THREADS) {
-        const Row rw = a.row[a.idx[j]];
+        const Row rw = load_row(a, j);
         big_e[j] = rw.t_enter; big_x[j] = rw.t_exit;
         if (rw.t_exit == T_INFLIGHT) { ++ni; imin = rw.t_enter < imin ? rw.t_enter : imin; }
         inc |= (rw.op != h.op || rw.bytes != h.bytes);
@@ -776,20 +785,295 @@ __global__ __launch_bounds__(256) void k_seg_group_listed(SegArgs a) {
   }
 }
 
-void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
-  if (a.n == 0) return;
-  hipLaunchKernelGGL(k_seg_wave, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
+// ---- dense placement: statistics straight from the partitioned rows -----------------------------------
+// One workgroup per fine bucket: the bucket's rows (in arrival order) are placed in LDS by grid cell
+// (round inside the bucket x member slot), which puts every collective's records side by side in rank
+// order with empty cells where a member has no record; the wavefronts then take the collectives
+// 64 / G at a time exactly as k_seg_wave does.  The kernel also writes the records' squeezed keys and row
+// indices in (communicator, counter, rank) order, which the flag, blame, group and alert stages read, and
+// adds the records per rank to the blame table.
+constexpr int DENSE_THREADS = 512;
+
+template <int G>
+__device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, const uint4* s_cell, const u32* s_pres,
+                                                  const u32* s_pre, u32 K, u32 size, u32 comm, u64 rel0, u32 srow0,
+                                                  u32 rec0, u32 row0, u64* __restrict__ skey, u32* __restrict__ sidx,
+                                                  u32 lane, u32 wave) {
+  constexpr int SPW = CCLD_WAVE / G, NW = DENSE_THREADS / CCLD_WAVE;
+  const int mb = a.sf.mb;
+  const u32 q = lane / G, l = lane % G, gbase = q * G;
+  const u64 gmask = (G == 64 ? ~0ull : (((u64)1 << (G & 63)) - 1)) << gbase;
+  const u64 below = ((u64)1 << lane) - 1;
+  const u32* __restrict__ ms = a.members_sorted + a.member_off[comm];
+  const u32 rank = l < size ? ms[l] : 0u;
+  u32 mine = 0;                                    // records seen in this lane's member slot
+  for (u32 b = wave; b * SPW < K; b += NW) {
+    const u32 k = b * SPW + q;
+    const bool in = k < K && l < size;
+    const u32 cell = k * size + l;
+    const bool valid = in && ((s_pres[cell >> 5] >> (cell & 31)) & 1u);
+    const u64 pm = ballot64(valid) & gmask;          // members of this lane's collective that have a record
+    const u32 n = (u32)__popcll(pm);
+    i64 e = 0, x = T_INFLIGHT;
+    u64 nb = 0;
+    u32 op = 0, ai = 0;
+    if (valid) {
+      const uint4 h0 = s_cell[2 * cell], h1 = s_cell[2 * cell + 1];
+      e = (i64)(((u64)h0.y << 32) | h0.x); x = (i64)(((u64)h0.w << 32) | h0.z);
+      nb = ((u64)h1.y << 32) | h1.x; op = h1.z & 15u; ai = h1.z >> 4;
+      ++mine;
+    }
+    const u32 first = rec0 + (k < K ? s_pre[k] : 0u);          // sorted position of the collective's first record
+    const u32 j = first + (u32)__popcll(pm & below);
+    const u32 fl = pm ? (u32)__builtin_ctzll(pm) : gbase;      // lane of the first member present
+    const bool done = valid && x != T_INFLIGHT;
+    const u64 m_infl = ballot64(valid && !done);
+    const u32 nd = (u32)__popcll(ballot64(done) & gmask);
+    const u32 ninfl = (u32)__popcll(m_infl & gmask);
+    const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
+    const i64 se = sort_groups<G>(done ? e : T_INFLIGHT, lane);
+    const i64 sx = sort_groups<G>(done ? x : T_INFLIGHT, lane);
+    const i64 med_e = shfl_i64(se, gbase + km), med_x = shfl_i64(sx, gbase + km);
+    const i64 min_e = shfl_i64(se, gbase), max_e = shfl_i64(se, gbase + kl);
+    const i64 min_x = shfl_i64(sx, gbase), max_x = shfl_i64(sx, gbase + kl);
+    const i64 sde = sort_groups<G>(done ? (e >= med_e ? e - med_e : med_e - e) : T_INFLIGHT, lane);
+    const i64 sdx = sort_groups<G>(done ? (x >= med_x ? x - med_x : med_x - x) : T_INFLIGHT, lane);
+    const i64 mad_e = shfl_i64(sde, gbase + km), mad_x = shfl_i64(sdx, gbase + km);
+    i64 dmin = done ? x - e : INT64_MAX, dmax = done ? x - e : INT64_MIN;
+    u32 rmin = done ? rank : 0xFFFFFFFFu, rmax = rmin;
+    reduce_dur<G, false>(dmin, rmin);
+    reduce_dur<G, true>(dmax, rmax);
+    const u64 hb = shfl_u64(nb, (int)fl);
+    const u32 hop = __shfl(op, (int)fl, CCLD_WAVE);
+    const bool incons = (ballot64(valid && (nb != hb || op != hop)) & gmask) != 0;
+    i64 imin = T_INFLIGHT;
+    if (m_infl) imin = reduce_min<G>((valid && !done) ? e : T_INFLIGHT);
+    if (!valid) continue;
+    const bool complete = n == size && ninfl == 0;
+    const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
+    const bool usable = complete && !incons && !barrier;
+    const u64 rel = rel0 + k;
+    if (lane == fl) {
+      const u32 srow = srow0 + k;
+      seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)(rel + a.sf.seq_base));
+      seg_put(a, CCLD_SEG_N, srow, (i64)n);
+      seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
+      seg_put(a, CCLD_SEG_STATE, srow,
+              (complete ? CCLD_SEG_COMPLETE : 0) | (!incons ? CCLD_SEG_CONSISTENT : 0) |
+                  (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+      seg_put(a, CCLD_SEG_OP, srow, (i64)hop);
+      seg_put(a, CCLD_SEG_BYTES, srow, (i64)hb);
+      seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
+      seg_put(a, CCLD_SEG_FIRST, srow, (i64)first);
+      seg_put_group(a, srow, usable, comm, hop, hb, dmax, dmin);
+      if (nd == 0) {
+        seg_put_empty_stats(a, srow);
+      } else {
+        seg_put(a, CCLD_SEG_ENTER_MIN, srow, min_e); seg_put(a, CCLD_SEG_ENTER_MED, srow, med_e);
+        seg_put(a, CCLD_SEG_ENTER_MAX, srow, max_e); seg_put(a, CCLD_SEG_ENTER_MAD, srow, mad_e);
+        seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
+        seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
+        seg_put(a, CCLD_SEG_DUR_MIN, srow, dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, dmax);
+        seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)rmax);
+      }
+    }
+    i64 le = 0, lx = 0;
+    u32 f = 0;
+    if (usable) {
+      le = e - med_e; lx = x - med_x;
+      if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
+      if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
+    }
+    skey[j] = ((u64)comm << (mb + a.sf.ws)) | (rel << mb) | (u64)l;
+    sidx[j] = row0 + ai;
+    a.rec_flag[j] = (uint8_t)f;
+    if (a.lag_e) a.lag_e[j] = le;
+    if (a.lag_x) a.lag_x[j] = lx;
+    if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
+  }
+  return mine;
+}
+
+__global__ __launch_bounds__(DENSE_THREADS) void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
+                                                               u32* __restrict__ sidx, i64* __restrict__ blame,
+                                                               u32 n_ranks) {
+  __shared__ uint4 s_cell[2 * DENSE_B];
+  __shared__ u32 s_pres[DENSE_B / 32];
+  __shared__ unsigned short s_n[DENSE_B];
+  __shared__ u32 s_aux[DENSE_B + 4];          // [K] first record of each collective, then [size] records per member slot
+  __shared__ u32 s_wave[DENSE_THREADS / CCLD_WAVE];
+  if (d.hdr[DH_FEASIBLE] == 0) return;
+  const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE;
+  const u32 n_fine = d.hdr[DH_N_FINE];
+  const uint4* __restrict__ rows4 = reinterpret_cast<const uint4*>(d.rows);
+  unsigned long long* nrec = (unsigned long long*)(blame + (u64)CCLD_BLM_N_RECORDS * n_ranks);
+  for (u32 f = blockIdx.x; f < n_fine; f += gridDim.x) {
+    // the communicator whose fine buckets include f
+    u32 c;
+    {
+      u32 lo = 0, hi = d.n_comms;
+      while (lo < hi) { const u32 m = (lo + hi) >> 1; if (d.lay[m].fb_base <= f) lo = m + 1; else hi = m; }
+      c = lo - 1;
+    }
+    const CommLayout L = d.lay[c];
+    const u32 size = d.comm_size[c];
+    const u32 r0 = (f - L.fb_base) * L.rpb;
+    const u32 K = (L.rounds - r0) < L.rpb ? (L.rounds - r0) : L.rpb;         // collectives in this bucket
+    const u32 rec0 = d.fill[f], cnt_raw = d.fill[f + 1] - rec0;
+    const u32 cnt = cnt_raw < DENSE_STRIDE ? cnt_raw : DENSE_STRIDE;
+    const u32 row0 = f * DENSE_STRIDE;
+    u32* s_pre = s_aux;
+    u32* s_slot = s_aux + K;
+    for (u32 i = tid; i < DENSE_B / 32; i += DENSE_THREADS) s_pres[i] = 0;
+    for (u32 i = tid; i < size; i += DENSE_THREADS) s_slot[i] = 0;
+    __syncthreads();
+    // 1. every row into its cell; a cell taken twice is a duplicate key
+    bool dup = cnt_raw > DENSE_STRIDE;
+    {
+      typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+      u32x4 h0[4], h1[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const u32 i = tid + u * DENSE_THREADS;
+        if (i < cnt) {
+          h0[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rows4 + 2ull * (row0 + i)));
+          h1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rows4 + 2ull * (row0 + i) + 1));
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const u32 i = tid + u * DENSE_THREADS;
+        if (i >= cnt) continue;
+        const u32 cell = (h1[u].z >> 4) & 0x7FFu;
+        if (cell >= K * size) { dup = true; continue; }
+        const u32 bit = 1u << (cell & 31);
+        if (atomicOr(&s_pres[cell >> 5], bit) & bit) { dup = true; continue; }
+        s_cell[2 * cell] = make_uint4(h0[u].x, h0[u].y, h0[u].z, h0[u].w);
+        s_cell[2 * cell + 1] = make_uint4(h1[u].x, h1[u].y, (h1[u].z & 15u) | (i << 4), h1[u].w);
+      }
+    }
+    __syncthreads();
+    // 2. records per collective, their exclusive scan; a round without any record is a hole in the grid
+    for (u32 k = tid; k < K; k += DENSE_THREADS) {
+      const u32 b0 = k * size, b1 = b0 + size;      // bits [b0, b1)
+      u32 nk = 0;
+      for (u32 w = b0 >> 5; w <= (b1 - 1) >> 5; ++w) {
+        u32 m = s_pres[w];
+        if (w == (b0 >> 5)) m &= ~0u << (b0 & 31);
+        if (w == ((b1 - 1) >> 5) && (b1 & 31)) m &= (1u << (b1 & 31)) - 1;
+        nk += __popc(m);
+      }
+      s_n[k] = (unsigned short)nk;
+    }
+    __syncthreads();
+    bool gap = false;
+    {
+      u32 v[4], sum = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const u32 k = 4 * tid + i;
+        v[i] = k < K ? s_n[k] : 0u;
+        gap |= k < K && v[i] == 0;
+        sum += v[i];
+      }
+      u32 tot;
+      u32 ex = block_exclusive_sum<DENSE_THREADS>(sum, s_wave, &tot);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const u32 k = 4 * tid + i;
+        if (k < K) s_pre[k] = ex;
+        ex += v[i];
+      }
+    }
+    __syncthreads();
+    u64 bad = (dup ? (u64)DS_DUPLICATE : 0) | (gap ? (u64)DS_DENSE_FALLBACK : 0);
+    // 3. the collectives
+    const u64 rel0 = L.seq_min + r0 - a.sf.seq_base;
+    const u32 srow0 = L.seg_base + r0;
+    if (size <= (u32)SEG_WAVE_MAX) {
+      u32 mine;
+      if (size <= 2) mine = dense_wave_batches<2>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else if (size <= 4) mine = dense_wave_batches<4>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else if (size <= 8) mine = dense_wave_batches<8>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else if (size <= 16) mine = dense_wave_batches<16>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else if (size <= 32) mine = dense_wave_batches<32>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else mine = dense_wave_batches<64>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      // the lane's member slot is the same in every pass
+      u32 G = 2; while (G < size) G <<= 1;
+      if (mine) atomicAdd(&s_slot[lane % G], mine);
+    } else {
+      // communicators of more than 64 members: the records are written out in rank order and every
+      // collective goes on the list of the kernels that take long collectives
+      const int mb = a.sf.mb;
+      for (u32 k = wave; k < K; k += DENSE_THREADS / CCLD_WAVE) {
+        const u32 nk = s_n[k];
+        if (nk == 0) continue;
+        const u32 first = rec0 + s_pre[k];
+        u32 run = 0;
+        for (u32 s0 = 0; s0 < size; s0 += CCLD_WAVE) {
+          const u32 slot = s0 + lane, cell = k * size + slot;
+          const bool valid = slot < size && ((s_pres[cell >> 5] >> (cell & 31)) & 1u);
+          const u64 pm = ballot64(valid);
+          if (valid) {
+            const u32 j = first + run + mbcnt64(pm);
+            skey[j] = ((u64)c << (mb + a.sf.ws)) | ((rel0 + k) << mb) | (u64)slot;
+            sidx[j] = row0 + (s_cell[2 * cell + 1].z >> 4);
+            atomicAdd(&s_slot[slot], 1u);
+          }
+          run += (u32)__popcll(pm);
+        }
+        if (lane == 0) {
+          const u64 at = atomic_add_u64(&a.counters[CNT_NBIG], 1);
+          if (at < a.big_cap) {
+            a.big_list[3 * at] = srow0 + k; a.big_list[3 * at + 1] = first; a.big_list[3 * at + 2] = nk;
+          } else {
+            bad |= (u64)DS_DENSE_FALLBACK;      // more listed collectives than the list holds
+          }
+        }
+      }
+    }
+    if (bad) atomicOr((unsigned long long*)&a.counters[CNT_STATUS], (unsigned long long)bad);
+    __syncthreads();
+    // 4. records per rank
+    {
+      const u32* __restrict__ ms = a.members_sorted + a.member_off[c];
+      for (u32 sl = tid; sl < size; sl += DENSE_THREADS) {
+        const u32 v = s_slot[sl];
+        if (v) atomicAdd(&nrec[ms[sl]], (unsigned long long)v);
+      }
+    }
+    __syncthreads();       // the LDS cells are reused by the next bucket
+  }
+}
+
+// the collectives on the list (more than 64 records; from the dense placement also shorter ones)
+static void launch_seg_listed(hipStream_t st, const SegArgs& a, bool with_short) {
   // a collective has at most as many records as its communicator has members (a longer one holds a
   // duplicate, which ends the analysis with an error): size classes that cannot occur are not launched
   const uint32_t m = a.max_size;
   if (m <= (uint32_t)SEG_WAVE_MAX) return;
   hipLaunchKernelGGL(k_seg_lengths, dim3(1024), dim3(SEG_THREADS), 0, st, a);
+  if (with_short) hipLaunchKernelGGL(k_seg_multi<1>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
   hipLaunchKernelGGL(k_seg_multi<2>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
   if (m > 128) hipLaunchKernelGGL(k_seg_multi<4>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
   if (m > 256) hipLaunchKernelGGL(k_seg_multi<8>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
   if (m > (uint32_t)SEG_MULTI_MAX) hipLaunchKernelGGL(k_seg_team, dim3(1024), dim3(SEG_THREADS), 0, st, a);
   if (m > (uint32_t)SEG_TEAM_MAX) hipLaunchKernelGGL(k_seg_big, dim3(2048), dim3(SEG_THREADS), 0, st, a);
   if (m > (uint32_t)SEG_MULTI_MAX) hipLaunchKernelGGL(k_seg_group_listed, dim3(256), dim3(256), 0, st, a);
+}
+
+void launch_dense_stats(hipStream_t st, const SegArgs& a, const DenseArgs& d, uint64_t* skey, uint32_t* sidx,
+                        int64_t* blame, uint32_t n_ranks) {
+  if (a.n == 0) return;
+  hipLaunchKernelGGL(k_dense_stats, dim3(4096), dim3(DENSE_THREADS), 0, st, a, d, skey, sidx, blame, n_ranks);
+  launch_seg_listed(st, a, true);
+}
+
+void launch_seg_analyze(hipStream_t st, const SegArgs& a) {
+  if (a.n == 0) return;
+  hipLaunchKernelGGL(k_seg_wave, dim3((a.n + SEG_TILE - 1) / SEG_TILE), dim3(SEG_THREADS), 0, st, a);
+  launch_seg_listed(st, a, false);
 }
 
 }  // namespace ccld

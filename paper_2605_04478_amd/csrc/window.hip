@@ -38,25 +38,47 @@ void launch_fill_u64(hipStream_t st, uint64_t* p, uint64_t n, uint64_t v) {
 // rank, store key and payload row at the window's tail.
 // Records per communicator bucket in each workgroup's slice of the batch (first half of the
 // two-step placement below).
+// With RANGE the kernel also reads the operation counters and leaves, per communicator, the batch's
+// largest counter and the largest complement of one (i.e. ~smallest) in a.range (zeroed before): the
+// dense placement lays the window out from these.
+template <bool RANGE>
 __global__ __launch_bounds__(256) void k_ingest_hist(IngestArgs a, u32 n_comms) {
   extern __shared__ u32 s_cnt[];
+  // [n_buckets] counts, then (RANGE) [n_comms][2] extreme counters, 8-byte aligned
+  unsigned long long* s_rng = reinterpret_cast<unsigned long long*>(s_cnt + ((a.n_buckets + 1) & ~1u));
   for (u32 b = threadIdx.x; b < a.n_buckets; b += 256) s_cnt[b] = 0;
+  if (RANGE) for (u32 i = threadIdx.x; i < 2 * n_comms; i += 256) s_rng[i] = 0;
   // the batch's header starts from zero (the placement kernel, next on the stream, accumulates into it)
   if (blockIdx.x == 0 && threadIdx.x == 0) { a.meta->status = 0; a.meta->max_seq = 0; a.meta->max_inv_seq = 0; a.meta->pad = 0; }
   __syncthreads();
   const u64 chunk = a.chunk / a.hist_split;
   const u64 i_end = (chunk * (blockIdx.x + 1)) < a.n ? chunk * (blockIdx.x + 1) : a.n;
   const u32* __restrict__ in_comm = a.comm;
+  const u64* __restrict__ in_seq = a.seq;
   for (u64 i0 = chunk * blockIdx.x + threadIdx.x; i0 < i_end; i0 += 256 * 8) {
     u32 c[8];
+    u64 q[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) c[u] = (i0 + (u64)u * 256 < i_end) ? __builtin_nontemporal_load(in_comm + i0 + (u64)u * 256) : 0xFFFFFFFFu;
+    for (int u = 0; u < 8; ++u) {
+      const bool on = i0 + (u64)u * 256 < i_end;
+      c[u] = on ? __builtin_nontemporal_load(in_comm + i0 + (u64)u * 256) : 0xFFFFFFFFu;
+      if (RANGE) q[u] = on ? __builtin_nontemporal_load(in_seq + i0 + (u64)u * 256) : 0ull;
+    }
 #pragma unroll
     for (int u = 0; u < 8; ++u)
-      if (i0 + (u64)u * 256 < i_end) atomicAdd(&s_cnt[c[u] < n_comms ? (c[u] >> a.bshift) : 0u], 1u);
+      if (i0 + (u64)u * 256 < i_end) {
+        atomicAdd(&s_cnt[c[u] < n_comms ? (c[u] >> a.bshift) : 0u], 1u);
+        if (RANGE && c[u] < n_comms) {
+          atomicMax(&s_rng[2 * c[u]], (unsigned long long)q[u]);
+          atomicMax(&s_rng[2 * c[u] + 1], (unsigned long long)~q[u]);
+        }
+      }
   }
   __syncthreads();
   for (u32 b = threadIdx.x; b < a.n_buckets; b += 256) a.table[(u64)b * gridDim.x + blockIdx.x] = s_cnt[b];
+  if (RANGE)
+    for (u32 i = threadIdx.x; i < 2 * n_comms; i += 256)
+      if (s_rng[i]) atomicMax((unsigned long long*)&a.range[i], s_rng[i]);
 }
 // exclusive scan of every bucket's row of per-workgroup counts (row length <= 2048)
 __global__ __launch_bounds__(256) void k_ingest_scan(u32* table, u32* totals, u32 n_blocks) {
@@ -206,7 +228,7 @@ __global__ __launch_bounds__(THREADS) void k_ingest(IngestArgs a, DeviceTopology
 // records per round, gives each its slot in its bucket (LDS atomic, as above), then stages keys and
 // rows in LDS ordered by (bucket, slot) and writes them out with consecutive lanes on consecutive
 // 16-byte pieces: every bucket's share of the round leaves as one contiguous run instead of one
-// scattered 40-byte store per lane.  At most 64 buckets.
+// scattered 40-byte store per lane.  At most INGEST_STAGED_BUCKETS buckets.
 template <int THREADS, bool LDS_TABLE>
 __global__ __launch_bounds__(THREADS) void k_ingest_staged(IngestArgs a, DeviceTopology T, KeyFormat kf) {
   constexpr int U = 2;
@@ -214,7 +236,8 @@ __global__ __launch_bounds__(THREADS) void k_ingest_staged(IngestArgs a, DeviceT
   // [n_ranks] membership rows (LDS_TABLE) | [2 CHUNK] row halves | [CHUNK] keys | [CHUNK] window slots
   extern __shared__ uint4 s_dyn[];
   __shared__ u64 s_status[THREADS / CCLD_WAVE], s_max[THREADS / CCLD_WAVE], s_inv[THREADS / CCLD_WAVE];
-  __shared__ u32 s_off[64], s_start[64], s_pre[64], s_total;
+  __shared__ u32 s_off[INGEST_STAGED_BUCKETS], s_start[INGEST_STAGED_BUCKETS], s_pre[INGEST_STAGED_BUCKETS], s_total;
+  __shared__ u32 s_scan[THREADS / CCLD_WAVE];
   uint4* s_row = s_dyn + (LDS_TABLE ? T.n_ranks : 0u);
   u64* s_key = reinterpret_cast<u64*>(s_row + 2 * CHUNK);
   u32* s_p = reinterpret_cast<u32*>(s_key + CHUNK);
@@ -277,13 +300,22 @@ __global__ __launch_bounds__(THREADS) void k_ingest_staged(IngestArgs a, DeviceT
     }
     __syncthreads();
     // this round's records per bucket -> where each bucket's run starts in the staging order
-    if (tid < CCLD_WAVE) {
+    if (a.n_buckets <= CCLD_WAVE) {
+      if (tid < CCLD_WAVE) {
+        const u32 cnt = tid < a.n_buckets ? s_off[tid] - s_start[tid] : 0u;
+        const u32 inc = wave_inclusive_sum(cnt);
+        s_pre[tid] = inc - cnt;
+        if (tid == CCLD_WAVE - 1) s_total = inc;
+      }
+      __syncthreads();
+    } else {
       const u32 cnt = tid < a.n_buckets ? s_off[tid] - s_start[tid] : 0u;
-      const u32 inc = wave_inclusive_sum(cnt);
-      s_pre[tid] = inc - cnt;
-      if (tid == CCLD_WAVE - 1) s_total = inc;
+      u32 tot;
+      const u32 ex = block_exclusive_sum<THREADS>(cnt, s_scan, &tot);
+      if (tid < a.n_buckets) s_pre[tid] = ex;
+      if (tid == 0) s_total = tot;
+      __syncthreads();
     }
-    __syncthreads();
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (!on[u]) continue;
@@ -298,8 +330,32 @@ __global__ __launch_bounds__(THREADS) void k_ingest_staged(IngestArgs a, DeviceT
     }
     __syncthreads();
     const u32 total = s_total;
-    for (u32 i = tid; i < 2 * total; i += THREADS) out_row[2ull * s_p[i >> 1] + (i & 1)] = s_row[i];
-    for (u32 q = tid; q < total; q += THREADS) out_key[s_p[q]] = s_key[q];
+    // Pieces of a line that this round writes completely leave with the streaming hint: they do not stay in
+    // the L2, where they would displace the partially written lines at the buckets' frontiers before the
+    // next round completes them.
+    {
+      typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+      for (u32 i = tid; i < 2 * total; i += THREADS) {
+        const u64 D = 2ull * s_p[i >> 1] + (i & 1);
+        const u32 o = (u32)(D & 7);
+        bool full = false;
+        if (i >= o && i + 7 - o < 2 * total) {
+          const u32 lo = i - o, hi = i + 7 - o;
+          full = (2ull * s_p[lo >> 1] + (lo & 1) == D - o) && (2ull * s_p[hi >> 1] + (hi & 1) == D + 7 - o);
+        }
+        const uint4 v = s_row[i];
+        if (full) { u32x4 vv = {v.x, v.y, v.z, v.w}; __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(out_row + D)); }
+        else out_row[D] = v;
+      }
+      for (u32 q = tid; q < total; q += THREADS) {
+        const u32 D = s_p[q];
+        const u32 o = D & 15;
+        bool full = false;
+        if (q >= o && q + 15 - o < total) full = (s_p[q - o] == D - o) && (s_p[q + 15 - o] == D + 15 - o);
+        if (full) __builtin_nontemporal_store(s_key[q], out_key + D);
+        else out_key[D] = s_key[q];
+      }
+    }
     if (tid < a.n_buckets) s_start[tid] = s_off[tid];
     __syncthreads();
 #pragma unroll
@@ -316,11 +372,13 @@ void launch_ingest(hipStream_t st, const IngestArgs& a_in, const DeviceTopology&
   u64 g = (a.n + 255) / 256;
   if (g > INGEST_BLOCKS) g = INGEST_BLOCKS;
   a.hist_split = 1;
+  const bool range = a.range != nullptr;
   const size_t lds = sizeof(u32) * a.n_buckets;
+  const size_t lds_hist = sizeof(u32) * ((a.n_buckets + 1) & ~1u) + (range ? (size_t)16 * T.n_comms : 0);
   // large batches: one 1,024-thread workgroup per compute unit with the write-out regrouped in LDS, the
   // membership rows in LDS too when they fit beside the staging area; four counting workgroups per
   // placement workgroup
-  const bool staged = a.n >= (1u << 22) && a.n_buckets <= 64;
+  const bool staged = a.n >= (1u << 22) && a.n_buckets <= INGEST_STAGED_BUCKETS;
   const size_t stage_bytes = (size_t)2048 * (32 + 8 + 4);
   const bool staged_table = staged && T.rank_memb4 && (u64)T.n_ranks * 16 + stage_bytes <= 156 * 1024;
   // otherwise, large batches over few enough ranks: half as many workgroups of twice the size, each with the
@@ -331,7 +389,8 @@ void launch_ingest(hipStream_t st, const IngestArgs& a_in, const DeviceTopology&
   const u64 unit = 256ull * a.hist_split;
   a.chunk = ((a.n + g - 1) / g + unit - 1) / unit * unit;
   const u32 g_hist = (u32)(g * a.hist_split);
-  hipLaunchKernelGGL(k_ingest_hist, dim3(g_hist), dim3(256), lds, st, a, T.n_comms);
+  if (range) hipLaunchKernelGGL(k_ingest_hist<true>, dim3(g_hist), dim3(256), lds_hist, st, a, T.n_comms);
+  else hipLaunchKernelGGL(k_ingest_hist<false>, dim3(g_hist), dim3(256), lds_hist, st, a, T.n_comms);
   hipLaunchKernelGGL(k_ingest_scan, dim3(a.n_buckets), dim3(256), 0, st, a.table, a.bucket_base, g_hist);
   launch_scan_tiles(st, a.bucket_base, a.n_buckets, a.scratch_total);
   static bool raised = false;       // more than 64 KB of dynamic LDS has to be asked for once
@@ -727,6 +786,9 @@ __global__ __launch_bounds__(T) void k_group_eval(GroupArgs a, const u64* __rest
   __shared__ u32 s_i0, s_istar, s_kstar;
   __shared__ unsigned long long s_sum, s_best;
   const u32 tid = threadIdx.x;
+  // a data error or an abandoned dense placement found by an earlier kernel of this analysis: the tables are
+  // not valid and the detection state must stay as it is
+  if (a.counters[CNT_STATUS] != 0) return;
   const u32 n_group = (u32)a.counters[CNT_NGROUP], n_usable = (u32)a.counters[CNT_NUSABLE];
   const u32 n_work = BIG ? (u32)a.counters[CNT_NLONG] : n_group;
   const i64* SEQ = a.seg + (u64)CCLD_SEG_SEQ * a.seg_cap;

@@ -21,11 +21,15 @@ struct IngestArgs {
   uint32_t n_buckets;
   int bshift;                // bucket = comm >> bshift
   uint32_t seqno0;           // arrival number of the batch's first record
+  uint64_t* range;           // [n_comms][2] per communicator: largest operation counter, largest complement of one
+                             // (zeroed by the caller); null: not wanted.  At most INGEST_RANGE_COMMS communicators.
   uint64_t chunk;            // records per placement workgroup (a multiple of 256 * hist_split)
   uint32_t hist_split;       // counting workgroups per placement workgroup
 };
 constexpr uint32_t INGEST_BLOCKS = 1024;
 constexpr uint32_t INGEST_MAX_BUCKETS = 4096;
+constexpr uint32_t INGEST_STAGED_BUCKETS = 256;   // most buckets the LDS-regrouped placement kernel handles
+constexpr uint32_t INGEST_RANGE_COMMS = 3584;     // most communicators whose counter ranges fit the counting kernel's LDS
 void launch_ingest(hipStream_t st, const IngestArgs& a, const DeviceTopology& T, const KeyFormat& kf);
 void launch_fill_u64(hipStream_t st, uint64_t* p, uint64_t n, uint64_t v);
 
@@ -45,6 +49,7 @@ struct SegArgs {
   int64_t* flag_lag;         // [2][cap_n] lags of flagged records by sorted position
   uint64_t cap_n;
   uint32_t* big_list;
+  uint64_t big_cap;          // entries the list holds
   int64_t* big_ex;           // [2][cap_n]
   uint64_t* counters;
   int64_t lag_floor;

@@ -44,18 +44,27 @@ def compare(g, o, blame=None, order=None, per_record=True, what=""):
         assert np.array_equal(order, o.order), (what, "order")
 
 
-def run_both(topo, cols, now=FAR, on_device=True, what="", **params):
+def run_both(topo, cols, now=FAR, on_device=True, what="", expect_path=None, **params):
+    """Both placements of the library (dense placement where the window allows it, and the sort) against
+    the oracle; returns the result of the automatic choice."""
     n = int(cols["rank"].shape[0])
-    an = _analyzer(topo, n, **params)
-    an.ingest(an.to_device(cols) if on_device else cols)
-    g = an.analyze_window(now, n_records=n, per_record=True)
     o = orc.Oracle(topo, params).analyze_window(cols, now)
-    blame = order = None
-    if o.status == "OK":
-        blame, order = an.rank_blame()
-    compare(g, o, blame, order, what=what)
-    an.close()
-    return g, o
+    first = None
+    for placement in (0, 1):                   # CCLD_PLACEMENT_AUTO, CCLD_PLACEMENT_SORT
+        an = _analyzer(topo, n, placement=placement, **params)
+        an.ingest(an.to_device(cols) if on_device else cols)
+        g = an.analyze_window(now, n_records=n, per_record=True)
+        blame = order = None
+        if o.status == "OK":
+            blame, order = an.rank_blame()
+        compare(g, o, blame, order, what=f"{what} placement={placement}")
+        if placement == 1:
+            assert g.path == 0
+        elif expect_path is not None and o.status == "OK":
+            assert g.path == expect_path, (what, g.path)
+        an.close()
+        first = first or g
+    return first, o
 
 
 def test_config1_parity():
@@ -397,3 +406,81 @@ def test_blame_of_a_rank_with_tens_of_thousands_of_flags():
     g, o = run_both(topo, cols, what="long blame run")
     assert int(o.blame["n_late_enter"][3]) + int(o.blame["n_late_exit"][3]) > 8192
     assert int(o.order[0]) == 3
+
+
+# --------------------------------------------------------------------------
+# dense placement: taken when the window fills a dense grid, abandoned for the sort otherwise
+# --------------------------------------------------------------------------
+def test_dense_placement_is_taken_on_dense_windows():
+    tr = tg.generate(tg.config1(n_slots=300)).shuffled(3)
+    g, o = run_both(tr.topo, tr.cols, what="dense config1", expect_path=1)
+    tr = tg.generate(tg.config3(n_cycles=30, layout=tg.Layout3D(tp=8, pp=4, dp=64))).shuffled(6)
+    g, o = run_both(tr.topo, tr.cols, what="dense config3 layout", expect_path=1)
+    assert g.n_flag > 0
+    # members without a record, operations in flight, inconsistent and barrier rounds stay on the dense path
+    tr = tg.generate(tg.config2(n_cycles=60)).shuffled(4)
+    cols = _disturb(tr)
+    g, o = run_both(tr.topo, cols, now=int(cols["t_enter"].max()) + 10_000_000, what="dense disturbed",
+                    expect_path=1, hang_threshold_ns=1_000_000)
+    assert g.n_alert >= 3
+
+
+def test_dense_placement_falls_back_to_the_sort():
+    tr = tg.generate(tg.config2(n_cycles=40)).shuffled(7)
+    c = tr.cols
+    # a round without any record in the middle of a communicator's counters
+    keep = ~((c["comm"] == 9) & (c["seq"] == 17))
+    g, o = run_both(tr.topo, {k: v[keep] for k, v in c.items()}, what="hole", expect_path=0)
+    assert g.n_seg == len(o.seg["comm"])
+    # counters that are far apart: one communicator's records renumbered from a large counter on
+    far = {k: v.copy() for k, v in c.items()}
+    m = (far["comm"] == 3) & (far["seq"] >= 20)
+    far["seq"][m] += 10**12
+    run_both(tr.topo, far, what="far apart", expect_path=0)
+    # the same at the window's edge is still dense: every communicator has its own first counter
+    off = {k: v.copy() for k, v in c.items()}
+    off["seq"][off["comm"] == 3] += 10**6
+    off["seq"][off["comm"] == 4] += 5
+    run_both(tr.topo, off, what="offset counters", expect_path=1)
+
+
+def test_dense_placement_duplicates_and_small_sizes():
+    # communicators of 1, 2, 3, 5, 6, 12 and 33 members over 62 ranks
+    comms = [[0], [1, 2], [3, 4, 5], list(range(6, 11)), list(range(11, 17)), list(range(17, 29)), list(range(29, 62))]
+    topo = tg.make_topology(62, comms)
+    rng = np.random.default_rng(11)
+    rows = []
+    for c, mem in enumerate(comms):
+        for s in range(700 if len(mem) < 6 else 90):
+            t = T0 + s * 1_000_000 + int(rng.integers(0, 1000))
+            present = [r for r in mem if rng.random() > 0.03] or mem[:1]
+            for r in present:
+                te = t + int(rng.integers(0, 400_000) if rng.random() < 0.1 else rng.integers(0, 50))
+                rows.append((r, c, 1000 + s, c % 3, 4096, te, te + 5000 + int(rng.integers(0, 9))))
+    cols = toy_cols(rows)
+    p = rng.permutation(len(rows))
+    cols = {k: v[p] for k, v in cols.items()}
+    g, o = run_both(topo, cols, what="sizes", expect_path=1, tbase_init_ns=1000, lag_floor_ns=1000)
+    assert g.n_flag > 0 and g.n_group > 3
+    # one record twice: a data error on both paths
+    dup = {k: np.concatenate([v, v[5:6]]) for k, v in cols.items()}
+    g, o = run_both(topo, dup, what="dup")
+    assert g.status == "E_DUPLICATE_KEY"
+    # the detection state survives the abandoned attempts and the error: a context that has seen them agrees
+    # with one that has not
+    from paper_2605_04478_amd import ccld
+    keep = ~((cols["comm"] == 5) & (cols["seq"] == 1010))
+    hole = {k: v[keep] for k, v in cols.items()}
+    an = ccld.Analyzer(topo, max_window_records=len(rows) + 1, tbase_init_ns=1000, lag_floor_ns=1000)
+    orc_ = orc.Oracle(topo, dict(tbase_init_ns=1000, lag_floor_ns=1000))
+    for step, w in enumerate((cols, dup, hole, cols)):
+        an.reset_window()
+        an.ingest(an.to_device(w))
+        gg = an.analyze_window(FAR, n_records=len(rows) + 1, per_record=True)
+        oo = orc_.analyze_window(w, FAR)
+        blame = order = None
+        if oo.status == "OK":
+            blame, order = an.rank_blame()
+        compare(gg, oo, blame, order, what=f"state step {step}")
+        assert gg.path == (0 if step == 2 else 1) or oo.status != "OK"
+    an.close()
