@@ -78,14 +78,17 @@ typedef struct {
   uint32_t stall_snapshots;    /* [30] a counter unchanged over this many snapshots is stalled              */
   uint32_t fifo_depth;         /* [8] ring back-pressure depth used by the wait-for edges                   */
   uint32_t window_batches;     /* [1] the window holds the last this-many ingested batches                  */
-  uint32_t placement;          /* [CCLD_PLACEMENT_AUTO] how ccld_analyze_window brings a collective's records together */
+  uint32_t placement;          /* [CCLD_PLACEMENT_SORT] how ccld_analyze_window brings a collective's records together */
 } ccld_params;
 
-/* ccld_params.placement.  AUTO: a window of one batch whose (communicator, operation counter, member) grid
- * is dense (Section 5.1: every rank bumps the same counter, so the Trace ID fixes the record's cell) is
- * analysed without sorting; any other window, and any window in which the attempt finds a round without a
- * single record or counters that are far apart, is sorted.  SORT: always sort.  Both give the same tables. */
-enum { CCLD_PLACEMENT_AUTO = 0, CCLD_PLACEMENT_SORT = 1 };
+/* ccld_params.placement.  SORT: the window is sorted by (communicator, operation counter, rank).  DENSE: a
+ * window of one batch is first analysed without sorting: every rank of a communicator bumps the same
+ * operation counter (Section 5.1), so the Trace ID and the member slot fix a record's cell in a dense
+ * (communicator, counter, member) grid, and one partition pass brings the records of a cell range together.
+ * A window of several batches, a window with a round in which no member has a record or with counters
+ * that are far apart, and a topology with a communicator of more than 2,048 members are sorted as under
+ * SORT.  Both give the same tables; ccld_window_result.path tells which one ran. */
+enum { CCLD_PLACEMENT_SORT = 0, CCLD_PLACEMENT_DENSE = 1 };
 
 /* Communicator table (host pointers, copied by ccld_create). */
 typedef struct {

@@ -98,7 +98,7 @@ _lib: Optional[C.CDLL] = None
 
 PROF_CLASSES = ("ingest", "sort_hist", "sort_scan", "sort_scatter", "segments", "flags", "blame", "groups", "alerts",
                 "hang", "seg_heads", "dense_partition")
-PLACEMENT_AUTO, PLACEMENT_SORT = 0, 1
+PLACEMENT_SORT, PLACEMENT_DENSE = 0, 1
 PROF_NCLASS = 16
 
 EXPORTS = ("ccld_profile_enable", "ccld_profile_read", "ccld_default_params", "ccld_query_workspace", "ccld_create", "ccld_destroy", "ccld_ingest",

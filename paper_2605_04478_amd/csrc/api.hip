@@ -86,7 +86,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   // dense placement: counter ranges, layout, fine-bucket fill counts and the partitioned rows (room for an
   // eighth more cells than records, and one partly filled fine bucket per communicator)
   c->fine_cap = 0;
-  c->comm_range = nullptr; c->d_lay = nullptr; c->d_hdr = nullptr; c->d_fill = nullptr; c->d_rows = nullptr;
+  c->comm_range = nullptr; c->d_lay = nullptr; c->d_hdr = nullptr; c->d_fill = nullptr; c->d_rows = nullptr; c->d_desc = nullptr;
   if (c->dense_capable) {
     c->fine_cap = (uint32_t)((N + N / 8) / DENSE_B + n_comms + 16);
     c->comm_range = w.take<uint64_t>(2ull * n_comms);
@@ -94,6 +94,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
     c->d_hdr = w.take<uint32_t>(DH_COUNT);
     c->d_fill = w.take<uint32_t>((uint64_t)c->fine_cap + 4);
     c->d_rows = w.take<Row>((uint64_t)c->fine_cap * DENSE_STRIDE);
+    c->d_desc = w.take<FineDesc>((uint64_t)c->fine_cap);
   }
   // hang location
   const uint64_t SN = std::max<uint64_t>(c->snap_cap, 1);
@@ -116,7 +117,7 @@ ccld_status check_params(const ccld_params* p) {
   if (!p) return CCLD_E_NULL;
   if (p->tbase_rounds < 1 || p->theta_den < 1 || p->ab_den < 1 || p->kmad_den < 1 || p->tbase_warmup_ns < 0 ||
       p->window_batches < 1 || p->window_batches > 4096 || p->hang_threshold_ns < 0 ||
-      p->placement > CCLD_PLACEMENT_SORT)
+      p->placement > CCLD_PLACEMENT_DENSE)
     return CCLD_E_BAD_ARG;
   return CCLD_OK;
 }
@@ -160,7 +161,7 @@ ccld_status check_topology(const ccld_topology* t, uint64_t* n_members) {
 // Windows of one batch can be analysed by dense placement when every communicator fits a fine bucket and
 // the counting kernel's LDS holds a counter range per communicator.
 bool dense_capable(const ccld_params* p, const ccld_topology* t) {
-  if (p->placement == CCLD_PLACEMENT_SORT || p->window_batches != 1 || t->n_comms > DENSE_MAX_COMMS) return false;
+  if (p->placement != CCLD_PLACEMENT_DENSE || p->window_batches != 1 || t->n_comms > DENSE_MAX_COMMS) return false;
   for (uint32_t k = 0; k < t->n_comms; ++k) if (t->size[k] > DENSE_B) return false;
   return true;
 }
@@ -547,6 +548,7 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
     da.bucket_base = c->ing_base; da.n_buckets = c->n_buckets; da.bshift = c->bshift;
     da.range = c->comm_range; da.lay = (CommLayout*)c->d_lay; da.hdr = c->d_hdr; da.fill = c->d_fill;
     da.rows = c->d_rows; da.fine_cap = c->fine_cap; da.counters = c->counters;
+    da.desc = (FineDesc*)c->d_desc; da.seq_base = c->sf.seq_base;
     c->prof.begin(CCLD_PROF_DENSE_PARTITION);
     launch_dense_layout(st, da);
     uint32_t* h_hdr = reinterpret_cast<uint32_t*>(c->h_pinned + 2 * CNT_COUNT);
@@ -555,6 +557,7 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
     launch_fill_u64(st, reinterpret_cast<uint64_t*>(c->d_fill), ((uint64_t)c->fine_cap + 4) / 2, 0ull);
     launch_dense_partition(st, da);
     launch_scan_tiles(st, c->d_fill, c->fine_cap + 1, &c->counters[CNT_NRETAINED]);
+    launch_dense_desc(st, da);
     HIP_TRY(hipEventSynchronize(c->ev_heads));
     if (!h_hdr[DH_FEASIBLE]) {          // far-apart counters or too many fine buckets: the kernels above did nothing
       HIP_TRY(hipStreamSynchronize(st));

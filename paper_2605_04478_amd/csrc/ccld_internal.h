@@ -163,6 +163,7 @@ struct ccld_ctx {
   uint32_t* d_hdr;                    // [DH_COUNT]
   uint32_t* d_fill;                   // [fine_cap + 2]
   ccld::Row* d_rows;                  // [fine_cap * DENSE_STRIDE]
+  void* d_desc;                       // [fine_cap] FineDesc
   uint32_t fine_cap;
   int last_path;                      // 1: the last analysis used the dense placement
   // last analysis

@@ -26,6 +26,16 @@ struct CommLayout {
   uint32_t seg_base;       // row of the collective table of the first round
 };
 
+// What the statistics kernel needs to know about one fine bucket (written once the records per bucket are
+// known): its communicator, the collectives it holds and where their records and table rows go.
+struct FineDesc {
+  uint32_t comm, size;     // communicator and its members
+  uint32_t K;              // collectives (rounds) in the bucket
+  uint32_t rec0, cnt;      // first record of the bucket in (communicator, counter, rank) order; records placed
+  uint32_t srow0;          // row of the collective table of the bucket's first round
+  uint64_t rel0;           // operation counter of the first round minus the window's smallest counter
+};
+
 // device-side header of the layout
 enum { DH_FEASIBLE, DH_N_FINE, DH_N_SEG, DH_COUNT = 8 };
 
@@ -47,6 +57,8 @@ struct DenseArgs {
   uint32_t* hdr;                 // [DH_COUNT]
   // fine buckets
   uint32_t* fill;                // [fine_cap + 1] records per fine bucket, later their exclusive scan
+  FineDesc* desc;                // [fine_cap]
+  uint64_t seq_base;             // the window's smallest operation counter
   Row* rows;                     // [fine_cap * DENSE_STRIDE]
   uint32_t fine_cap;
   uint64_t* counters;
@@ -54,6 +66,7 @@ struct DenseArgs {
 
 void launch_dense_layout(hipStream_t st, const DenseArgs& d);
 void launch_dense_partition(hipStream_t st, const DenseArgs& d);
+void launch_dense_desc(hipStream_t st, const DenseArgs& d);      // after the scan of fill
 // statistics of every collective from the partitioned rows (segments.hip); also writes the sorted keys
 // and row indices that the flag, blame, group and alert stages read
 void launch_dense_stats(hipStream_t st, const SegArgs& a, const DenseArgs& d, uint64_t* skey, uint32_t* sidx,

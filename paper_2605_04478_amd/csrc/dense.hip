@@ -116,7 +116,7 @@ __device__ __forceinline__ u32 bucket_of(const u32* __restrict__ base, u32 n_buc
 // that the round writes completely leave with the streaming hint, which keeps them from displacing
 // the partially written lines at the buckets' frontiers from the L2.
 constexpr u32 PART_THREADS = 1024;
-constexpr u32 PART_U = 2;
+constexpr u32 PART_U = 3;          // 3,072 records per round (96 KB of staged rows): the longest runs the LDS allows
 constexpr u32 PART_CHUNK = PART_THREADS * PART_U;
 __global__ __launch_bounds__(PART_THREADS) void k_dense_partition(DenseArgs d) {
   extern __shared__ uint4 s_dyn[];      // [2 PART_CHUNK] staged row halves | [PART_CHUNK] destinations | 3 x [DENSE_SPAN] tables
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(PART_THREADS) void k_dense_partition(DenseArgs d) {
     }
     __syncthreads();
     {     // exclusive scan of the round's counts: consecutive buckets per thread
-      constexpr u32 PER = DENSE_SPAN / PART_THREADS;
+      constexpr u32 PER = (DENSE_SPAN + PART_THREADS - 1) / PART_THREADS;
       u32 v[PER], sum = 0;
 #pragma unroll
       for (u32 i = 0; i < PER; ++i) { const u32 b = PER * tid + i; v[i] = b < span ? s_rc[b] : 0u; sum += v[i]; }
@@ -264,6 +264,29 @@ __global__ __launch_bounds__(PART_THREADS) void k_dense_partition(DenseArgs d) {
 #pragma unroll
     for (u32 u = 0; u < PART_U; ++u) { key[u] = nkey[u]; r0[u] = n0[u]; r1[u] = n1[u]; }
   }
+}
+
+// ---- fine bucket descriptors ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_dense_desc(DenseArgs d) {
+  if (d.hdr[DH_FEASIBLE] == 0) return;
+  const u32 f = blockIdx.x * 256 + threadIdx.x;
+  if (f >= d.hdr[DH_N_FINE]) return;
+  // the communicator whose fine buckets include f: the last one whose first bucket is <= f
+  u32 lo = 0, hi = d.n_comms;
+  while (lo < hi) { const u32 m = (lo + hi) >> 1; if (d.lay[m].fb_base <= f) lo = m + 1; else hi = m; }
+  const u32 c = lo - 1;
+  const CommLayout L = d.lay[c];
+  const u32 r0 = (f - L.fb_base) * L.rpb;
+  FineDesc D;
+  D.comm = c; D.size = d.comm_size[c];
+  D.K = (L.rounds - r0) < L.rpb ? (L.rounds - r0) : L.rpb;
+  D.rec0 = d.fill[f]; D.cnt = d.fill[f + 1] - D.rec0;
+  D.srow0 = L.seg_base + r0;
+  D.rel0 = L.seq_min + r0 - d.seq_base;
+  d.desc[f] = D;
+}
+void launch_dense_desc(hipStream_t st, const DenseArgs& d) {
+  hipLaunchKernelGGL(k_dense_desc, dim3((d.fine_cap + 255) / 256), dim3(256), 0, st, d);
 }
 
 void launch_dense_partition(hipStream_t st, const DenseArgs& d) {

@@ -6,6 +6,7 @@
 typedef uint32_t u32;
 typedef uint64_t u64;
 typedef int64_t i64;
+typedef int32_t i32;
 typedef unsigned __int128 u128;
 typedef __int128 i128;
 

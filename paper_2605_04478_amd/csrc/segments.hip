@@ -792,7 +792,196 @@ __global__ __launch_bounds__(256) void k_seg_group_listed(SegArgs a) {
 // 64 / G at a time exactly as k_seg_wave does.  The kernel also writes the records' squeezed keys and row
 // indices in (communicator, counter, rank) order, which the flag, blame, group and alert stages read, and
 // adds the records per rank to the blame table.
-constexpr int DENSE_THREADS = 512;
+constexpr int DENSE_THREADS = 256;
+
+// What one lane knows about its record before the group-wide statistics.
+struct DenseLane {
+  i64 e, x;          // arrival, completion (T_INFLIGHT while the operation runs)
+  u64 nb;            // bytes
+  u32 op, rank;
+  bool valid;        // the lane's member has a record in this collective
+  u64 pm;            // lanes of this lane's collective whose members have a record
+  u32 fl;            // first such lane
+  u32 n, first, j;   // records of the collective, sorted position of its first record and of this record
+  u32 srow;          // the collective's row of the table
+  u32 comm;
+  u64 seq;           // operation counter
+};
+
+// table row of one collective (called by one lane)
+__device__ __forceinline__ void dense_put_row(const SegArgs& a, const DenseLane& L, u32 ninfl, bool complete, bool incons,
+                                              bool barrier, bool usable, u32 hop, u64 hb, i64 imin, u32 nd, i64 min_e,
+                                              i64 med_e, i64 max_e, i64 mad_e, i64 min_x, i64 med_x, i64 max_x, i64 mad_x,
+                                              i64 dmin, i64 dmax, u32 rmin, u32 rmax) {
+  const u32 srow = L.srow;
+  seg_put(a, CCLD_SEG_COMM, srow, (i64)L.comm);
+  seg_put(a, CCLD_SEG_SEQ, srow, (i64)L.seq);
+  seg_put(a, CCLD_SEG_N, srow, (i64)L.n);
+  seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
+  seg_put(a, CCLD_SEG_STATE, srow,
+          (complete ? CCLD_SEG_COMPLETE : 0) | (!incons ? CCLD_SEG_CONSISTENT : 0) |
+              (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+  seg_put(a, CCLD_SEG_OP, srow, (i64)hop);
+  seg_put(a, CCLD_SEG_BYTES, srow, (i64)hb);
+  seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
+  seg_put(a, CCLD_SEG_FIRST, srow, (i64)L.first);
+  seg_put_group(a, srow, usable, L.comm, hop, hb, dmax, dmin);
+  if (nd == 0) {
+    seg_put_empty_stats(a, srow);
+  } else {
+    seg_put(a, CCLD_SEG_ENTER_MIN, srow, min_e); seg_put(a, CCLD_SEG_ENTER_MED, srow, med_e);
+    seg_put(a, CCLD_SEG_ENTER_MAX, srow, max_e); seg_put(a, CCLD_SEG_ENTER_MAD, srow, mad_e);
+    seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
+    seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
+    seg_put(a, CCLD_SEG_DUR_MIN, srow, dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, dmax);
+    seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)rmax);
+  }
+}
+__device__ __forceinline__ void dense_put_record(const SegArgs& a, u32 j, u32 f, i64 le, i64 lx) {
+  a.rec_flag[j] = (uint8_t)f;
+  if (a.lag_e) a.lag_e[j] = le;
+  if (a.lag_x) a.lag_x[j] = lx;
+  if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
+}
+
+// Statistics of the collectives of one wavefront pass in 64-bit arithmetic (any spread of the times).
+template <int G>
+__device__ __forceinline__ void dense_pass64(const SegArgs& a, const DenseLane& L, u32 size, u32 lane, u32 gbase, u64 gmask) {
+  const i64 e = L.e, x = L.x;
+  const bool valid = L.valid;
+  const bool done = valid && x != T_INFLIGHT;
+  const u64 m_infl = ballot64(valid && !done);
+  const u32 nd = (u32)__popcll(ballot64(done) & gmask);
+  const u32 ninfl = (u32)__popcll(m_infl & gmask);
+  const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
+  const i64 se = sort_groups<G>(done ? e : T_INFLIGHT, lane);
+  const i64 sx = sort_groups<G>(done ? x : T_INFLIGHT, lane);
+  const i64 med_e = shfl_i64(se, gbase + km), med_x = shfl_i64(sx, gbase + km);
+  const i64 min_e = shfl_i64(se, gbase), max_e = shfl_i64(se, gbase + kl);
+  const i64 min_x = shfl_i64(sx, gbase), max_x = shfl_i64(sx, gbase + kl);
+  const i64 sde = sort_groups<G>(done ? (e >= med_e ? e - med_e : med_e - e) : T_INFLIGHT, lane);
+  const i64 sdx = sort_groups<G>(done ? (x >= med_x ? x - med_x : med_x - x) : T_INFLIGHT, lane);
+  const i64 mad_e = shfl_i64(sde, gbase + km), mad_x = shfl_i64(sdx, gbase + km);
+  i64 dmin = done ? x - e : INT64_MAX, dmax = done ? x - e : INT64_MIN;
+  u32 rmin = done ? L.rank : 0xFFFFFFFFu, rmax = rmin;
+  reduce_dur<G, false>(dmin, rmin);
+  reduce_dur<G, true>(dmax, rmax);
+  const u64 hb = shfl_u64(L.nb, (int)L.fl);
+  const u32 hop = __shfl(L.op, (int)L.fl, CCLD_WAVE);
+  const bool incons = (ballot64(valid && (L.nb != hb || L.op != hop)) & gmask) != 0;
+  i64 imin = T_INFLIGHT;
+  if (m_infl) imin = reduce_min<G>((valid && !done) ? e : T_INFLIGHT);
+  if (!valid) return;
+  const bool complete = L.n == size && ninfl == 0;
+  const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
+  const bool usable = complete && !incons && !barrier;
+  if (lane == L.fl)
+    dense_put_row(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, min_e, med_e, max_e, mad_e, min_x,
+                  med_x, max_x, mad_x, dmin, dmax, rmin, rmax);
+  i64 le = 0, lx = 0;
+  u32 f = 0;
+  if (usable) {
+    le = e - med_e; lx = x - med_x;
+    if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
+    if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
+  }
+  dense_put_record(a, L.j, f, le, lx);
+}
+
+// ---- the same statistics on 32-bit times relative to the collective's first record --------------------
+// Inside one collective the arrivals and completions lie within a second or so of each other, so they
+// are sorted, compared and subtracted as signed 32-bit offsets from the arrival of the collective's first
+// present member (half the instructions of the 64-bit form); the results are turned back into absolute
+// times where they are stored.  A pass in which some offset does not fit takes the 64-bit form.
+constexpr i32 REL_NONE = 0x7FFFFFFF;         // sorts behind every real offset (those stay below 2^30 in magnitude)
+
+template <int M>
+__device__ __forceinline__ i32 cmpx32(i32 v, u32 lane) {
+  const i32 p = (i32)xor_lane_u32<M>((u32)v);
+  const bool upper = (lane & high_bit(M)) != 0;
+  const i32 lo = p < v ? p : v, hi = p < v ? v : p;
+  return upper ? hi : lo;
+}
+template <int G>
+__device__ __forceinline__ i32 sort_groups32(i32 v, u32 lane) {
+  if constexpr (G >= 2) { v = cmpx32<1>(v, lane); }
+  if constexpr (G >= 4) { v = cmpx32<3>(v, lane); v = cmpx32<1>(v, lane); }
+  if constexpr (G >= 8) { v = cmpx32<7>(v, lane); v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane); }
+  if constexpr (G >= 16) { v = cmpx32<15>(v, lane); v = cmpx32<4>(v, lane); v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane); }
+  if constexpr (G >= 32) {
+    v = cmpx32<31>(v, lane); v = cmpx32<8>(v, lane); v = cmpx32<4>(v, lane); v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane);
+  }
+  if constexpr (G >= 64) {
+    v = cmpx32<63>(v, lane); v = cmpx32<16>(v, lane); v = cmpx32<8>(v, lane); v = cmpx32<4>(v, lane);
+    v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane);
+  }
+  return v;
+}
+// all-reduce of an unsigned 64-bit word inside a group
+template <int G, bool MAXIMUM>
+__device__ __forceinline__ u64 reduce_u64(u64 v) {
+#define CCLD_U64_STEP(M)                                                                         \
+  if constexpr (G > M) {                                                                         \
+    const u64 o = (u64)xor_lane_i64<M>((i64)v);                                                  \
+    v = MAXIMUM ? (o > v ? o : v) : (o < v ? o : v);                                             \
+  }
+  CCLD_U64_STEP(1) CCLD_U64_STEP(2) CCLD_U64_STEP(4) CCLD_U64_STEP(8) CCLD_U64_STEP(16) CCLD_U64_STEP(32)
+#undef CCLD_U64_STEP
+  return v;
+}
+// late iff lag > floor and lag * kden > knum * mad, with a 32-bit lag and a non-negative 32-bit mad
+__device__ __forceinline__ bool is_late32(i32 lag, i64 floor_ns, u32 knum, u32 kden, i32 mad) {
+  if (lag <= 0 || (i64)lag <= floor_ns) return false;       // a lag that is not positive never exceeds knum * mad >= 0
+  return (u64)(u32)lag * (u64)kden > (u64)knum * (u64)(u32)mad;
+}
+
+template <int G>
+__device__ __forceinline__ void dense_pass32(const SegArgs& a, const DenseLane& L, i64 ref, i32 er, i32 xr, u32 size,
+                                             u32 lane, u32 gbase, u64 gmask) {
+  const bool valid = L.valid;
+  const bool done = valid && L.x != T_INFLIGHT;
+  const u64 m_infl = ballot64(valid && !done);
+  const u32 nd = (u32)__popcll(ballot64(done) & gmask);
+  const u32 ninfl = (u32)__popcll(m_infl & gmask);
+  const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
+  const i32 se = sort_groups32<G>(done ? er : REL_NONE, lane);
+  const i32 sx = sort_groups32<G>(done ? xr : REL_NONE, lane);
+  const i32 med_e = __shfl(se, (int)(gbase + km), CCLD_WAVE), med_x = __shfl(sx, (int)(gbase + km), CCLD_WAVE);
+  const i32 min_e = __shfl(se, (int)gbase, CCLD_WAVE), max_e = __shfl(se, (int)(gbase + kl), CCLD_WAVE);
+  const i32 min_x = __shfl(sx, (int)gbase, CCLD_WAVE), max_x = __shfl(sx, (int)(gbase + kl), CCLD_WAVE);
+  const i32 de = er >= med_e ? er - med_e : med_e - er, dx = xr >= med_x ? xr - med_x : med_x - xr;
+  const i32 sde = sort_groups32<G>(done ? de : REL_NONE, lane);
+  const i32 sdx = sort_groups32<G>(done ? dx : REL_NONE, lane);
+  const i32 mad_e = __shfl(sde, (int)(gbase + km), CCLD_WAVE), mad_x = __shfl(sdx, (int)(gbase + km), CCLD_WAVE);
+  // T_min / T_max of the Duration Time with the ranks attaining them (ties: smallest rank): duration and rank
+  // travel as one 64-bit word
+  const u32 dur = (u32)(xr - er);
+  u64 wmin = done ? (((u64)dur << 32) | L.rank) : ~0ull;
+  u64 wmax = done ? (((u64)dur << 32) | (u32)~L.rank) : 0ull;
+  wmin = reduce_u64<G, false>(wmin);
+  wmax = reduce_u64<G, true>(wmax);
+  const u64 hb = shfl_u64(L.nb, (int)L.fl);
+  const u32 hop = __shfl(L.op, (int)L.fl, CCLD_WAVE);
+  const bool incons = (ballot64(valid && (L.nb != hb || L.op != hop)) & gmask) != 0;
+  i64 imin = T_INFLIGHT;
+  if (m_infl) imin = reduce_min<G>((valid && !done) ? L.e : T_INFLIGHT);
+  if (!valid) return;
+  const bool complete = L.n == size && ninfl == 0;
+  const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
+  const bool usable = complete && !incons && !barrier;
+  if (lane == L.fl)
+    dense_put_row(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, ref + min_e, ref + med_e, ref + max_e,
+                  (i64)mad_e, ref + min_x, ref + med_x, ref + max_x, (i64)mad_x, (i64)(wmin >> 32), (i64)(wmax >> 32),
+                  (u32)wmin, ~(u32)wmax);
+  i32 le = 0, lx = 0;
+  u32 f = 0;
+  if (usable) {
+    le = er - med_e; lx = xr - med_x;
+    if (is_late32(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
+    if (is_late32(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
+  }
+  dense_put_record(a, L.j, f, (i64)le, (i64)lx);
+}
 
 template <int G>
 __device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, const uint4* s_cell, const u32* s_pres,
@@ -811,93 +1000,48 @@ __device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, const uint4*
     const u32 k = b * SPW + q;
     const bool in = k < K && l < size;
     const u32 cell = k * size + l;
-    const bool valid = in && ((s_pres[cell >> 5] >> (cell & 31)) & 1u);
-    const u64 pm = ballot64(valid) & gmask;          // members of this lane's collective that have a record
-    const u32 n = (u32)__popcll(pm);
-    i64 e = 0, x = T_INFLIGHT;
-    u64 nb = 0;
-    u32 op = 0, ai = 0;
-    if (valid) {
+    DenseLane L;
+    L.valid = in && ((s_pres[cell >> 5] >> (cell & 31)) & 1u);
+    L.pm = ballot64(L.valid) & gmask;
+    L.n = (u32)__popcll(L.pm);
+    L.e = 0; L.x = T_INFLIGHT; L.nb = 0; L.op = 0; L.rank = rank; L.comm = comm;
+    u32 ai = 0;
+    if (L.valid) {
       const uint4 h0 = s_cell[2 * cell], h1 = s_cell[2 * cell + 1];
-      e = (i64)(((u64)h0.y << 32) | h0.x); x = (i64)(((u64)h0.w << 32) | h0.z);
-      nb = ((u64)h1.y << 32) | h1.x; op = h1.z & 15u; ai = h1.z >> 4;
+      L.e = (i64)(((u64)h0.y << 32) | h0.x); L.x = (i64)(((u64)h0.w << 32) | h0.z);
+      L.nb = ((u64)h1.y << 32) | h1.x; L.op = h1.z & 15u; ai = h1.z >> 4;
       ++mine;
     }
-    const u32 first = rec0 + (k < K ? s_pre[k] : 0u);          // sorted position of the collective's first record
-    const u32 j = first + (u32)__popcll(pm & below);
-    const u32 fl = pm ? (u32)__builtin_ctzll(pm) : gbase;      // lane of the first member present
-    const bool done = valid && x != T_INFLIGHT;
-    const u64 m_infl = ballot64(valid && !done);
-    const u32 nd = (u32)__popcll(ballot64(done) & gmask);
-    const u32 ninfl = (u32)__popcll(m_infl & gmask);
-    const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
-    const i64 se = sort_groups<G>(done ? e : T_INFLIGHT, lane);
-    const i64 sx = sort_groups<G>(done ? x : T_INFLIGHT, lane);
-    const i64 med_e = shfl_i64(se, gbase + km), med_x = shfl_i64(sx, gbase + km);
-    const i64 min_e = shfl_i64(se, gbase), max_e = shfl_i64(se, gbase + kl);
-    const i64 min_x = shfl_i64(sx, gbase), max_x = shfl_i64(sx, gbase + kl);
-    const i64 sde = sort_groups<G>(done ? (e >= med_e ? e - med_e : med_e - e) : T_INFLIGHT, lane);
-    const i64 sdx = sort_groups<G>(done ? (x >= med_x ? x - med_x : med_x - x) : T_INFLIGHT, lane);
-    const i64 mad_e = shfl_i64(sde, gbase + km), mad_x = shfl_i64(sdx, gbase + km);
-    i64 dmin = done ? x - e : INT64_MAX, dmax = done ? x - e : INT64_MIN;
-    u32 rmin = done ? rank : 0xFFFFFFFFu, rmax = rmin;
-    reduce_dur<G, false>(dmin, rmin);
-    reduce_dur<G, true>(dmax, rmax);
-    const u64 hb = shfl_u64(nb, (int)fl);
-    const u32 hop = __shfl(op, (int)fl, CCLD_WAVE);
-    const bool incons = (ballot64(valid && (nb != hb || op != hop)) & gmask) != 0;
-    i64 imin = T_INFLIGHT;
-    if (m_infl) imin = reduce_min<G>((valid && !done) ? e : T_INFLIGHT);
-    if (!valid) continue;
-    const bool complete = n == size && ninfl == 0;
-    const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
-    const bool usable = complete && !incons && !barrier;
+    L.first = rec0 + (k < K ? s_pre[k] : 0u);
+    L.j = L.first + (u32)__popcll(L.pm & below);
+    L.fl = L.pm ? (u32)__builtin_ctzll(L.pm) : gbase;
+    L.srow = srow0 + k;
     const u64 rel = rel0 + k;
-    if (lane == fl) {
-      const u32 srow = srow0 + k;
-      seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
-      seg_put(a, CCLD_SEG_SEQ, srow, (i64)(rel + a.sf.seq_base));
-      seg_put(a, CCLD_SEG_N, srow, (i64)n);
-      seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
-      seg_put(a, CCLD_SEG_STATE, srow,
-              (complete ? CCLD_SEG_COMPLETE : 0) | (!incons ? CCLD_SEG_CONSISTENT : 0) |
-                  (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
-      seg_put(a, CCLD_SEG_OP, srow, (i64)hop);
-      seg_put(a, CCLD_SEG_BYTES, srow, (i64)hb);
-      seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
-      seg_put(a, CCLD_SEG_FIRST, srow, (i64)first);
-      seg_put_group(a, srow, usable, comm, hop, hb, dmax, dmin);
-      if (nd == 0) {
-        seg_put_empty_stats(a, srow);
-      } else {
-        seg_put(a, CCLD_SEG_ENTER_MIN, srow, min_e); seg_put(a, CCLD_SEG_ENTER_MED, srow, med_e);
-        seg_put(a, CCLD_SEG_ENTER_MAX, srow, max_e); seg_put(a, CCLD_SEG_ENTER_MAD, srow, mad_e);
-        seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
-        seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
-        seg_put(a, CCLD_SEG_DUR_MIN, srow, dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, dmax);
-        seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)rmax);
-      }
+    L.seq = rel + a.sf.seq_base;
+    if (L.valid) {
+      skey[L.j] = ((u64)comm << (mb + a.sf.ws)) | (rel << mb) | (u64)l;
+      sidx[L.j] = row0 + ai;
     }
-    i64 le = 0, lx = 0;
-    u32 f = 0;
-    if (usable) {
-      le = e - med_e; lx = x - med_x;
-      if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
-      if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
-    }
-    skey[j] = ((u64)comm << (mb + a.sf.ws)) | (rel << mb) | (u64)l;
-    sidx[j] = row0 + ai;
-    a.rec_flag[j] = (uint8_t)f;
-    if (a.lag_e) a.lag_e[j] = le;
-    if (a.lag_x) a.lag_x[j] = lx;
-    if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
+    // offsets from the arrival of the collective's first present member
+    const i64 ref = shfl_i64(L.e, (int)L.fl);
+    const i64 oe = L.e - ref, ox = L.x - ref;
+    constexpr i64 LIM = (i64)1 << 30;
+    const bool wide = L.valid && (oe < -LIM || oe >= LIM || (L.x != T_INFLIGHT && (ox < -LIM || ox >= LIM)));
+    if (ballot64(wide) == 0) dense_pass32<G>(a, L, ref, (i32)oe, (i32)ox, size, lane, gbase, gmask);
+    else dense_pass64<G>(a, L, size, lane, gbase, gmask);
   }
   return mine;
 }
 
-__global__ __launch_bounds__(DENSE_THREADS) void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
+// Two workgroups of four wavefronts per compute unit (their LDS allows no more): while one of them waits
+// for its rows or at a barrier the other one computes.  Measured at the 4,096-rank trace: 512 threads with a
+// 128-register budget spill (3.3 ms), one workgroup of 512 or 768 threads per compute unit 2.4 - 2.6 ms, this
+// shape 2.2 ms; loading the next bucket's rows into registers one bucket ahead changed nothing.
+__global__ __launch_bounds__(DENSE_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
                                                                u32* __restrict__ sidx, i64* __restrict__ blame,
                                                                u32 n_ranks) {
+  constexpr int U = (DENSE_STRIDE + DENSE_THREADS - 1) / DENSE_THREADS;        // rows per thread
   __shared__ uint4 s_cell[2 * DENSE_B];
   __shared__ u32 s_pres[DENSE_B / 32];
   __shared__ unsigned short s_n[DENSE_B];
@@ -908,51 +1052,51 @@ __global__ __launch_bounds__(DENSE_THREADS) void k_dense_stats(SegArgs a, DenseA
   const u32 n_fine = d.hdr[DH_N_FINE];
   const uint4* __restrict__ rows4 = reinterpret_cast<const uint4*>(d.rows);
   unsigned long long* nrec = (unsigned long long*)(blame + (u64)CCLD_BLM_N_RECORDS * n_ranks);
-  for (u32 f = blockIdx.x; f < n_fine; f += gridDim.x) {
-    // the communicator whose fine buckets include f
-    u32 c;
-    {
-      u32 lo = 0, hi = d.n_comms;
-      while (lo < hi) { const u32 m = (lo + hi) >> 1; if (d.lay[m].fb_base <= f) lo = m + 1; else hi = m; }
-      c = lo - 1;
+  typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 h0[U], h1[U];
+  auto fetch = [&](u32 f, u32 cnt) {
+    const u64 row0 = (u64)f * DENSE_STRIDE;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u32 i = tid + u * DENSE_THREADS;
+      if (i < cnt) {
+        h0[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rows4 + 2 * (row0 + i)));
+        h1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rows4 + 2 * (row0 + i) + 1));
+      }
     }
-    const CommLayout L = d.lay[c];
-    const u32 size = d.comm_size[c];
-    const u32 r0 = (f - L.fb_base) * L.rpb;
-    const u32 K = (L.rounds - r0) < L.rpb ? (L.rounds - r0) : L.rpb;         // collectives in this bucket
-    const u32 rec0 = d.fill[f], cnt_raw = d.fill[f + 1] - rec0;
-    const u32 cnt = cnt_raw < DENSE_STRIDE ? cnt_raw : DENSE_STRIDE;
+  };
+  auto clamp = [](u32 c) { return c < DENSE_STRIDE ? c : DENSE_STRIDE; };
+  u32 f = blockIdx.x;
+  if (f >= n_fine) return;
+  // the descriptor of the next bucket is read one bucket ahead
+  FineDesc D = d.desc[f], Dn = D;
+  u32 fn = f + gridDim.x;
+  if (fn < n_fine) Dn = d.desc[fn];
+  while (true) {
+    const u32 c = D.comm, size = D.size, K = D.K, rec0 = D.rec0, cnt = clamp(D.cnt);
     const u32 row0 = f * DENSE_STRIDE;
     u32* s_pre = s_aux;
     u32* s_slot = s_aux + K;
+    fetch(f, cnt);                    // the rows are on their way while the bucket's LDS state is cleared
     for (u32 i = tid; i < DENSE_B / 32; i += DENSE_THREADS) s_pres[i] = 0;
     for (u32 i = tid; i < size; i += DENSE_THREADS) s_slot[i] = 0;
     __syncthreads();
     // 1. every row into its cell; a cell taken twice is a duplicate key
-    bool dup = cnt_raw > DENSE_STRIDE;
-    {
-      typedef u32 u32x4 __attribute__((ext_vector_type(4)));
-      u32x4 h0[4], h1[4];
+    bool dup = D.cnt > DENSE_STRIDE;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const u32 i = tid + u * DENSE_THREADS;
-        if (i < cnt) {
-          h0[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rows4 + 2ull * (row0 + i)));
-          h1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rows4 + 2ull * (row0 + i) + 1));
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const u32 i = tid + u * DENSE_THREADS;
-        if (i >= cnt) continue;
-        const u32 cell = (h1[u].z >> 4) & 0x7FFu;
-        if (cell >= K * size) { dup = true; continue; }
-        const u32 bit = 1u << (cell & 31);
-        if (atomicOr(&s_pres[cell >> 5], bit) & bit) { dup = true; continue; }
-        s_cell[2 * cell] = make_uint4(h0[u].x, h0[u].y, h0[u].z, h0[u].w);
-        s_cell[2 * cell + 1] = make_uint4(h1[u].x, h1[u].y, (h1[u].z & 15u) | (i << 4), h1[u].w);
-      }
+    for (int u = 0; u < U; ++u) {
+      const u32 i = tid + u * DENSE_THREADS;
+      if (i >= cnt) continue;
+      const u32 cell = (h1[u].z >> 4) & (DENSE_B - 1);
+      if (cell >= K * size) { dup = true; continue; }
+      const u32 bit = 1u << (cell & 31);
+      if (atomicOr(&s_pres[cell >> 5], bit) & bit) { dup = true; continue; }
+      s_cell[2 * cell] = make_uint4(h0[u].x, h0[u].y, h0[u].z, h0[u].w);
+      s_cell[2 * cell + 1] = make_uint4(h1[u].x, h1[u].y, (h1[u].z & 15u) | (i << 4), h1[u].w);
     }
+    const bool more = fn < n_fine;
+    FineDesc Dnn = Dn;
+    if (more && fn + gridDim.x < n_fine) Dnn = d.desc[fn + gridDim.x];
     __syncthreads();
     // 2. records per collective, their exclusive scan; a round without any record is a hole in the grid
     for (u32 k = tid; k < K; k += DENSE_THREADS) {
@@ -969,10 +1113,11 @@ __global__ __launch_bounds__(DENSE_THREADS) void k_dense_stats(SegArgs a, DenseA
     __syncthreads();
     bool gap = false;
     {
-      u32 v[4], sum = 0;
+      constexpr int PER = (DENSE_B + DENSE_THREADS - 1) / DENSE_THREADS;
+      u32 v[PER], sum = 0;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const u32 k = 4 * tid + i;
+      for (int i = 0; i < PER; ++i) {
+        const u32 k = PER * tid + i;
         v[i] = k < K ? s_n[k] : 0u;
         gap |= k < K && v[i] == 0;
         sum += v[i];
@@ -980,8 +1125,8 @@ __global__ __launch_bounds__(DENSE_THREADS) void k_dense_stats(SegArgs a, DenseA
       u32 tot;
       u32 ex = block_exclusive_sum<DENSE_THREADS>(sum, s_wave, &tot);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const u32 k = 4 * tid + i;
+      for (int i = 0; i < PER; ++i) {
+        const u32 k = PER * tid + i;
         if (k < K) s_pre[k] = ex;
         ex += v[i];
       }
@@ -989,8 +1134,8 @@ __global__ __launch_bounds__(DENSE_THREADS) void k_dense_stats(SegArgs a, DenseA
     __syncthreads();
     u64 bad = (dup ? (u64)DS_DUPLICATE : 0) | (gap ? (u64)DS_DENSE_FALLBACK : 0);
     // 3. the collectives
-    const u64 rel0 = L.seq_min + r0 - a.sf.seq_base;
-    const u32 srow0 = L.seg_base + r0;
+    const u64 rel0 = D.rel0;
+    const u32 srow0 = D.srow0;
     if (size <= (u32)SEG_WAVE_MAX) {
       u32 mine;
       if (size <= 2) mine = dense_wave_batches<2>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
@@ -1043,6 +1188,9 @@ __global__ __launch_bounds__(DENSE_THREADS) void k_dense_stats(SegArgs a, DenseA
         if (v) atomicAdd(&nrec[ms[sl]], (unsigned long long)v);
       }
     }
+    if (!more) break;
+    f = fn; fn += gridDim.x;
+    D = Dn; Dn = Dnn;
     __syncthreads();       // the LDS cells are reused by the next bucket
   }
 }

@@ -9,10 +9,10 @@ from tests.test_gpu_window import compare
 pytestmark = pytest.mark.gpu
 
 
-def _run(tr, seed):
+def _run(tr, seed, placement=0):
     import torch
     from paper_2605_04478_amd import ccld
-    an = ccld.Analyzer(tr.topo, max_window_records=tr.n)
+    an = ccld.Analyzer(tr.topo, max_window_records=tr.n, placement=placement)
     cols = an.to_device(tr.cols)
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
@@ -45,13 +45,19 @@ def test_config3_full_size_82m_records():
     tr = tg.generate(spec)
     assert tr.n == 81_920_000 and tr.topo.n_comms == 1088
     an, res, blame, order, now = _run(tr, 3)
-    assert res.status == "OK" and res.n_seg == 8_448_000
+    assert res.status == "OK" and res.n_seg == 8_448_000 and res.path == 0
     ref = orc.Oracle(tr.topo).analyze_window(tr.cols, now)
     compare(res, ref, blame, order, per_record=False, what="config3-full")
     slow = sorted(s.rank for s in spec.slow_ranks)
     nic = sorted(x for g in spec.slow_groups for x in g.ranks)
     assert set(order[:8].tolist()) == set(slow)                     # the 8 slow ranks lead the blame
     assert set(np.nonzero(blame["n_late_exit"] >= 20)[0].tolist()) == set(nic)
+    an.close()
+    del an, res
+    # the same trace by dense placement (no sort): the same tables
+    an, res, blame, order, now = _run(tr, 3, placement=1)
+    assert res.status == "OK" and res.path == 1
+    compare(res, ref, blame, order, per_record=False, what="config3-full dense placement")
     an.close()
 
 

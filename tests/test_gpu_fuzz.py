@@ -100,24 +100,28 @@ def run(seed):
     order = np.argsort(cols["t_enter"], kind="stable")
     cuts = [0] + sorted(int(x) for x in rng.integers(0, n + 1, n_win - 1)) + [n]
     from paper_2605_04478_amd import ccld
-    an = ccld.Analyzer(topo, max_window_records=n, **params)
+    # one context that sorts and one that tries the dense placement first, each with its own detection state
+    ans = [ccld.Analyzer(topo, max_window_records=n, placement=pl, **params) for pl in (0, 1)]
     o = orc.Oracle(topo, params)
     now = int(rng.choice([FAR, T0 + 10**6, T0 + 10**8]))
     for w in range(n_win):
         sel = order[cuts[w]:cuts[w + 1]]
         sel = sel[rng.permutation(len(sel))]
         sl = {k: v[sel] for k, v in cols.items()}
-        an.reset_window()
         on_dev = rng.random() < 0.7
-        an.ingest(an.to_device(sl) if on_dev else sl)
-        g = an.analyze_window(now, n_records=max(len(sel), 1), per_record=True, alert_cap=len(sel) + 1,
-                              cand_cap=max(65536, 8 * len(sel)))
         ref = o.analyze_window(sl, now)
-        blame = order_ = None
-        if ref.status == "OK":
-            blame, order_ = an.rank_blame()
-        compare(g, ref, blame, order_, what=f"seed{seed} window{w} n={len(sel)} status={ref.status}")
-    an.close()
+        for pl, an in enumerate(ans):
+            an.reset_window()
+            an.ingest(an.to_device(sl) if on_dev else sl)
+            g = an.analyze_window(now, n_records=max(len(sel), 1), per_record=True, alert_cap=len(sel) + 1,
+                                  cand_cap=max(65536, 8 * len(sel)))
+            blame = order_ = None
+            if ref.status == "OK":
+                blame, order_ = an.rank_blame()
+            compare(g, ref, blame, order_, what=f"seed{seed} window{w} n={len(sel)} status={ref.status} placement={pl}")
+            assert pl == 1 or g.path == 0
+    for an in ans:
+        an.close()
     return n
 
 

@@ -46,11 +46,11 @@ def compare(g, o, blame=None, order=None, per_record=True, what=""):
 
 def run_both(topo, cols, now=FAR, on_device=True, what="", expect_path=None, **params):
     """Both placements of the library (dense placement where the window allows it, and the sort) against
-    the oracle; returns the result of the automatic choice."""
+    the oracle; returns the result of the dense-placement context."""
     n = int(cols["rank"].shape[0])
     o = orc.Oracle(topo, params).analyze_window(cols, now)
     first = None
-    for placement in (0, 1):                   # CCLD_PLACEMENT_AUTO, CCLD_PLACEMENT_SORT
+    for placement in (1, 0):                   # CCLD_PLACEMENT_DENSE, CCLD_PLACEMENT_SORT
         an = _analyzer(topo, n, placement=placement, **params)
         an.ingest(an.to_device(cols) if on_device else cols)
         g = an.analyze_window(now, n_records=n, per_record=True)
@@ -58,7 +58,7 @@ def run_both(topo, cols, now=FAR, on_device=True, what="", expect_path=None, **p
         if o.status == "OK":
             blame, order = an.rank_blame()
         compare(g, o, blame, order, what=f"{what} placement={placement}")
-        if placement == 1:
+        if placement == 0:
             assert g.path == 0
         elif expect_path is not None and o.status == "OK":
             assert g.path == expect_path, (what, g.path)
@@ -471,7 +471,7 @@ def test_dense_placement_duplicates_and_small_sizes():
     from paper_2605_04478_amd import ccld
     keep = ~((cols["comm"] == 5) & (cols["seq"] == 1010))
     hole = {k: v[keep] for k, v in cols.items()}
-    an = ccld.Analyzer(topo, max_window_records=len(rows) + 1, tbase_init_ns=1000, lag_floor_ns=1000)
+    an = ccld.Analyzer(topo, max_window_records=len(rows) + 1, tbase_init_ns=1000, lag_floor_ns=1000, placement=1)
     orc_ = orc.Oracle(topo, dict(tbase_init_ns=1000, lag_floor_ns=1000))
     for step, w in enumerate((cols, dup, hole, cols)):
         an.reset_window()
@@ -484,3 +484,38 @@ def test_dense_placement_duplicates_and_small_sizes():
         compare(gg, oo, blame, order, what=f"state step {step}")
         assert gg.path == (0 if step == 2 else 1) or oo.status != "OK"
     an.close()
+
+
+def test_dense_placement_wide_spreads_take_the_64_bit_pass():
+    """Offsets inside a collective that do not fit 30 bits (members seconds apart, operations that run for
+    seconds, times near the ends of the int64 range) go through the 64-bit form of the statistics."""
+    topo = tg.make_topology(24, [list(range(8)), list(range(8, 24))])
+    rng = np.random.default_rng(5)
+    rows = []
+    for c, mem in enumerate(([*range(8)], [*range(8, 24)])):
+        for s in range(300):
+            t = T0 + s * 10_000_000_000
+            kind = s % 6
+            for r in mem:
+                te = t + int(rng.integers(0, 2000))
+                dur = 50_000 + int(rng.integers(0, 100))
+                if kind == 1 and r == mem[3]:
+                    te += 3_000_000_000                      # one member three seconds late
+                if kind == 2:
+                    dur += 2_500_000_000                     # everybody runs for seconds
+                if kind == 3 and r == mem[0]:
+                    te -= 1_100_000_000                      # the first member far ahead of the others
+                if kind == 4 and r == mem[-1]:
+                    dur = 2**31 + 5                          # just past 31 bits
+                if kind == 5 and r == mem[1]:
+                    dur = 2**30 - 1 - 2000                   # just inside the 32-bit form
+                rows.append((r, c, s, 0, 1 << 20, te, te + dur))
+    # times at the top of the range
+    big = 2**62
+    for r in range(8):
+        rows.append((r, 0, 300, 0, 1 << 20, big + r, big + r + 7 + (2**40 if r == 2 else 0)))
+    cols = toy_cols(rows)
+    p = rng.permutation(len(rows))
+    cols = {k: v[p] for k, v in cols.items()}
+    g, o = run_both(topo, cols, now=2**62 + 2**41, what="wide", expect_path=1, tbase_init_ns=1000)
+    assert g.n_flag > 100
