@@ -83,6 +83,8 @@ def main() -> int:
                     help="skip the secondary figure on the generator's record order (keeps a profile to the timed steps)")
     ap.add_argument("--cpu-cycles", type=int, default=2000, help="cycles of the trace given to the CPU oracle")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--placement", choices=("sort", "dense"), default="sort",
+                    help="how the timed steps bring a collective's records together (ccld_params.placement)")
     ap.add_argument("--host-batch", action="store_true",
                     help="also time two steps whose batch starts in pinned host memory (PCIe-inclusive rate)")
     ap.add_argument("--workload", choices=("trace", "stream", "hang", "rates", "frames"), default="trace",
@@ -122,7 +124,8 @@ def main() -> int:
     n = tr.n
     log(f"generated {n} records ({spec.layout.n_ranks} ranks, {tr.topo.n_comms} communicators) in {time.time() - t0:.1f}s")
 
-    an = ccld.Analyzer(tr.topo, max_window_records=n, device="cuda:0")
+    an = ccld.Analyzer(tr.topo, max_window_records=n, device="cuda:0",
+                       placement=ccld.PLACEMENT_DENSE if args.placement == "dense" else ccld.PLACEMENT_SORT)
     cols = an.to_device(tr.cols)
     cols_time_major = None
     if not args.no_shuffle:

@@ -168,6 +168,26 @@ typedef struct {
   int32_t path;        /* out (host): 0 the window was sorted, 1 it was analysed by dense placement     */
 } ccld_window_result;
 
+/* Root cause and secondary effects among the late entries (ccld_flag_chains).
+ * chain table: one row per row of the flag table, in the same order */
+enum { CCLD_CHN_PARENT,     /* row of the flag that caused this late entry, -1: none (a root flag, or a late exit) */
+       CCLD_CHN_ROOT,       /* first flag of the chain (the row itself for a root flag)                           */
+       CCLD_CHN_ROOT_RANK,  /* rank of that flag                                                                  */
+       CCLD_CHN_DEPTH,      /* links between the row and its root                                                 */
+       CCLD_CHN_NCOL };
+/* per rank: its late entries without / with a parent, and the late entries (of any rank) whose chain starts at
+ * one of its root flags */
+enum { CCLD_CHR_ROOT_ENTRIES, CCLD_CHR_SECONDARY_ENTRIES, CCLD_CHR_CAUSED, CCLD_CHR_NCOL };
+
+typedef struct {
+  uint64_t chain_cap;  /* in: rows                                                                   */
+  int64_t *chain;      /* device [CCLD_CHN_NCOL][chain_cap]                                           */
+  int64_t *per_rank;   /* device [CCLD_CHR_NCOL][n_ranks] or NULL                                     */
+  uint64_t n_chain;    /* out (host): rows the full table has = flags of the analysis                */
+  ccld_status status;  /* out (host)                                                                  */
+  int32_t reserved;
+} ccld_chain_result;
+
 /* hang location tables */
 /* roots, ordered by (rank, communicator) */
 enum { CCLD_HROOT_RANK, CCLD_HROOT_COMM, CCLD_HROOT_CLASS, CCLD_HROOT_NCOL };
@@ -275,6 +295,20 @@ ccld_status ccld_reset_window(ccld_ctx *ctx);
  * tree.  now_ns is the analyzer's clock.  Per-rank blame of this window is kept for
  * ccld_rank_blame.  Returns out->status. */
 ccld_status ccld_analyze_window(ccld_ctx *ctx, int64_t now_ns, ccld_window_result *out);
+
+/* Separates root cause from secondary effects among the late-entry flags of the most recent
+ * ccld_analyze_window (Section 4.2.2: in a large cluster an anomaly propagates across ranks, and the
+ * location step has to tell the rank that triggered it from the ranks that pass it on).  `analysed` is
+ * the result of that analysis (its collective table must hold every collective: n_seg <= seg_cap) and no
+ * other call on the context may lie in between (else CCLD_E_BAD_ARG).  Per late entry F of rank r: the
+ * operation r ran just before = r's completed record with the largest t_exit <= t_enter(F), on r's own
+ * clock (ties: larger t_enter, then larger communicator); among that operation's late entries the one
+ * with the largest lag (ties: smallest rank) ended it late and is F's parent, also when it is r's own;
+ * without a late entry there F is a root flag: r is late of its own.  Late exits have no parent.  Parents
+ * are followed to the chain's first flag.  A delay that a whole communicator carries in step for several
+ * operations leaves no late entry there, so a chain can end before it reaches the rank that injected the
+ * delay: the chains separate the direct consequences, not every later echo. */
+ccld_status ccld_flag_chains(ccld_ctx *ctx, const ccld_window_result *analysed, ccld_chain_result *out);
 
 /* Locates the root of a hang from progress-counter snapshots (Section 4.2.2, hang decision tree;
  * Section 4.1.2, SendCount / RecvCount; Section 4.2.1, ring vs tree comparison groups).  The n_rows

@@ -442,6 +442,86 @@ int orc_analyze_window(const int64_t *P, const orc_topology *T, uint64_t n,
 }
 
 /* ==================================================================================================
+ * Root cause and secondary effects among the late-entry flags (Section 4.2.2, first paragraph: an
+ * anomaly may propagate across ranks, and the location step separates the rank that triggered it
+ * from the ranks that merely pass it on).
+ *
+ * A rank enters a collective late either because it is slow itself or because the operation it ran
+ * just before ended late, which happens when another member of that operation arrived late there.
+ * For a late-entry flag F of rank r:
+ *   previous operation of r = r's completed record with the largest t_exit <= t_enter(F) (r's own
+ *     clock on both sides; ties: larger t_enter, then larger communicator, then larger counter;
+ *     the record of F itself is left out);
+ *   the member that ended that operation late = among its late-entry flags the one with the largest
+ *     lag (ties: smallest rank);
+ *   if there is such a member, F is a consequence of that member's late arrival and that flag is its
+ *     parent (when the member is r itself the chain goes on through r's own earlier flag); if the
+ *     previous operation has no late entry, F is a root flag: r is late of its own.
+ * Following parents ends at a root flag (a parent's collective ended before the child was entered);
+ * the output gives, per flag, its parent, its root, the root's rank and the depth, and per rank the
+ * numbers of its late entries without and with a parent and the number of late entries, of any rank,
+ * whose chain starts at one of its root flags.  Late-exit flags are a rank's own transfer and have no
+ * parent.  These rules are a reading made here ("parity unpinned" by the paper); the
+ * tests pin them on hand-built chains.
+ * ================================================================================================== */
+enum { CHN_PARENT, CHN_ROOT, CHN_ROOT_RANK, CHN_DEPTH, CHN_NCOL };
+enum { CHR_ROOT_ENTRIES, CHR_SECONDARY_ENTRIES, CHR_CAUSED, CHR_NCOL };
+
+int orc_flag_chains(uint64_t n, const uint32_t *rank, const uint32_t *comm, const uint64_t *seq,
+                    const int64_t *t_enter, const int64_t *t_exit, uint64_t n_flag, const int64_t *flag,
+                    uint32_t n_ranks, int64_t *chain, int64_t *per_rank) {
+  for (uint64_t k = 0; k < n_flag; ++k) {
+    const int64_t *F = flag + k * FLG_NCOL;
+    int64_t *C = chain + k * CHN_NCOL;
+    C[CHN_PARENT] = -1; C[CHN_ROOT] = (int64_t)k; C[CHN_ROOT_RANK] = F[FLG_RANK]; C[CHN_DEPTH] = 0;
+    if (!(F[FLG_KIND] & FLAG_LATE_ENTER)) continue;
+    /* the flag's own record */
+    uint64_t self = n;
+    for (uint64_t i = 0; i < n; ++i)
+      if (rank[i] == (uint32_t)F[FLG_RANK] && comm[i] == (uint32_t)F[FLG_COMM] && seq[i] == (uint64_t)F[FLG_SEQ]) { self = i; break; }
+    if (self == n) return ORC_E_BAD_ARG;
+    /* the operation this rank ran just before */
+    uint64_t prev = n;
+    for (uint64_t i = 0; i < n; ++i) {
+      if (i == self || rank[i] != rank[self] || t_exit[i] == ORC_INFLIGHT || t_exit[i] > t_enter[self]) continue;
+      if (prev == n) { prev = i; continue; }
+      if (t_exit[i] != t_exit[prev]) { if (t_exit[i] > t_exit[prev]) prev = i; continue; }
+      if (t_enter[i] != t_enter[prev]) { if (t_enter[i] > t_enter[prev]) prev = i; continue; }
+      if (comm[i] != comm[prev]) { if (comm[i] > comm[prev]) prev = i; continue; }
+      if (seq[i] > seq[prev]) prev = i;
+    }
+    if (prev == n) continue;
+    /* who ended it late */
+    int64_t best = -1;
+    for (uint64_t q = 0; q < n_flag; ++q) {
+      const int64_t *Q = flag + q * FLG_NCOL;
+      if (Q[FLG_COMM] != (int64_t)comm[prev] || Q[FLG_SEQ] != (int64_t)seq[prev] || !(Q[FLG_KIND] & FLAG_LATE_ENTER)) continue;
+      if (best < 0 || Q[FLG_LAG_ENTER] > flag[best * FLG_NCOL + FLG_LAG_ENTER] ||
+          (Q[FLG_LAG_ENTER] == flag[best * FLG_NCOL + FLG_LAG_ENTER] && Q[FLG_RANK] < flag[best * FLG_NCOL + FLG_RANK]))
+        best = (int64_t)q;
+    }
+    if (best >= 0) C[CHN_PARENT] = best;
+  }
+  for (uint64_t k = 0; k < n_flag; ++k) {
+    int64_t *C = chain + k * CHN_NCOL;
+    int64_t cur = (int64_t)k, depth = 0;
+    while (chain[cur * CHN_NCOL + CHN_PARENT] >= 0) {
+      cur = chain[cur * CHN_NCOL + CHN_PARENT];
+      if (++depth > (int64_t)n_flag) return ORC_E_BAD_ARG;      /* cannot happen: parents end earlier */
+    }
+    C[CHN_ROOT] = cur; C[CHN_ROOT_RANK] = flag[cur * FLG_NCOL + FLG_RANK]; C[CHN_DEPTH] = depth;
+  }
+  for (uint64_t i = 0; i < (uint64_t)n_ranks * CHR_NCOL; ++i) per_rank[i] = 0;
+  for (uint64_t k = 0; k < n_flag; ++k) {
+    const int64_t *F = flag + k * FLG_NCOL;
+    if (!(F[FLG_KIND] & FLAG_LATE_ENTER)) continue;
+    per_rank[F[FLG_RANK] * CHR_NCOL + (chain[k * CHN_NCOL + CHN_PARENT] < 0 ? CHR_ROOT_ENTRIES : CHR_SECONDARY_ENTRIES)] += 1;
+    per_rank[chain[k * CHN_NCOL + CHN_ROOT_RANK] * CHR_NCOL + CHR_CAUSED] += 1;
+  }
+  return ORC_OK;
+}
+
+/* ==================================================================================================
  * Hang location from progress-counter snapshots (Section 4.2.2, hang decision tree; Section 4.1.2,
  * SendCount / RecvCount per channel; Section 4.2.1, ring vs tree comparison groups).
  *

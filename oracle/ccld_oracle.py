@@ -41,6 +41,8 @@ GROUP_COLS = ("comm", "op", "cls", "n_usable", "rstar_seq", "tmax", "tmin", "tba
 ALERT_COLS = ("comm", "seq", "age", "class", "n_cand", "cand_off")
 BLAME_COLS = ("n_late_enter", "n_late_exit", "sum_lag_enter", "sum_lag_exit", "n_records")
 REC_COLS = ("lag_enter", "lag_exit", "flag")
+CHAIN_COLS = ("parent", "root", "root_rank", "depth")
+CHAIN_RANK_COLS = ("root_entries", "secondary_entries", "caused")
 SEG_COMPLETE, SEG_CONSISTENT, SEG_BARRIER, SEG_USABLE = 1, 2, 4, 8
 FLAG_LATE_ENTER, FLAG_LATE_EXIT = 1, 2
 
@@ -124,6 +126,9 @@ def lib() -> C.CDLL:
         L.orc_decode_frames.restype = C.c_int
         L.orc_decode_frames.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32] + \
             [C.c_void_p] * 7
+        L.orc_flag_chains.restype = C.c_int
+        L.orc_flag_chains.argtypes = [C.c_uint64] + [C.c_void_p] * 5 + [C.c_uint64, C.c_void_p, C.c_uint32,
+                                                                         C.c_void_p, C.c_void_p]
         L.orc_rate_result_free.argtypes = [C.c_void_p]
         L.orc_progress_rates.restype = C.c_int
         L.orc_progress_rates.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32] + [C.c_void_p] * 7 + \
@@ -228,6 +233,25 @@ class Oracle:
             return out
         finally:
             self.L.orc_window_result_free(C.addressof(res))
+
+    def flag_chains(self, cols: Dict[str, np.ndarray], res: WindowResult):
+        """Root cause and secondary effects among the late-entry flags of an analysed window:
+        -> ({parent, root, root_rank, depth} per flag, {root_entries, secondary_entries, caused} per rank)."""
+        rank = np.ascontiguousarray(cols["rank"], dtype=np.uint32)
+        comm = np.ascontiguousarray(cols["comm"], dtype=np.uint32)
+        seq = np.ascontiguousarray(cols["seq"], dtype=np.uint64)
+        te = np.ascontiguousarray(cols["t_enter"], dtype=np.int64)
+        tx = np.ascontiguousarray(cols["t_exit"], dtype=np.int64)
+        n_flag = int(res.flag["comm"].shape[0])
+        flag = np.ascontiguousarray(np.stack([res.flag[k] for k in FLAG_COLS], axis=1), dtype=np.int64) \
+            if n_flag else np.zeros((1, len(FLAG_COLS)), np.int64)
+        chain = np.zeros((max(n_flag, 1), len(CHAIN_COLS)), np.int64)
+        per_rank = np.zeros((max(self.n_ranks, 1), len(CHAIN_RANK_COLS)), np.int64)
+        st = self.L.orc_flag_chains(int(rank.shape[0]), _ptr(rank), _ptr(comm), _ptr(seq), _ptr(te), _ptr(tx),
+                                    n_flag, _ptr(flag), self.n_ranks, _ptr(chain), _ptr(per_rank))
+        if st != 0:
+            raise ValueError(STATUS[st])
+        return _cols(chain[:n_flag], CHAIN_COLS), _cols(per_rank[:self.n_ranks], CHAIN_RANK_COLS)
 
     def locate_hang(self, cols: Dict[str, np.ndarray], n_snapshots: int, n_channels: int) -> HangResult:
         dt = {"snap": np.uint32, "rank": np.uint32, "comm": np.uint32, "channel": np.uint32,

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libccld.so")
-SOURCES = ("radix_sort.hip", "window.hip", "segments.hip", "dense.hip", "hang.hip", "merge.hip", "api.hip")
+SOURCES = ("radix_sort.hip", "window.hip", "segments.hip", "dense.hip", "chains.hip", "hang.hip", "merge.hip", "api.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -71,6 +71,15 @@ class _WindowResult(C.Structure):
                 ("n_alert", C.c_uint64), ("n_cand", C.c_uint64), ("status", C.c_int32), ("path", C.c_int32)]
 
 
+class _ChainResult(C.Structure):
+    _fields_ = [("chain_cap", C.c_uint64), ("chain", C.c_void_p), ("per_rank", C.c_void_p), ("n_chain", C.c_uint64),
+                ("status", C.c_int32), ("reserved", C.c_int32)]
+
+
+CHAIN_COLS = ("parent", "root", "root_rank", "depth")
+CHAIN_RANK_COLS = ("root_entries", "secondary_entries", "caused")
+
+
 class _HangResult(C.Structure):
     _fields_ = [("root_cap", C.c_uint64), ("pair_cap", C.c_uint64), ("comm_cap", C.c_uint64),
                 ("root", C.c_void_p), ("pair", C.c_void_p), ("comm", C.c_void_p),
@@ -102,7 +111,8 @@ PLACEMENT_SORT, PLACEMENT_DENSE = 0, 1
 PROF_NCLASS = 16
 
 EXPORTS = ("ccld_profile_enable", "ccld_profile_read", "ccld_default_params", "ccld_query_workspace", "ccld_create", "ccld_destroy", "ccld_ingest",
-           "ccld_reset_window", "ccld_analyze_window", "ccld_rank_blame", "ccld_locate_hang", "ccld_locate_hang_static",
+           "ccld_reset_window", "ccld_analyze_window", "ccld_flag_chains", "ccld_rank_blame", "ccld_locate_hang",
+           "ccld_locate_hang_static",
            "ccld_progress_rates",
            "ccld_decode_frames", "ccld_reset_frames", "ccld_status_str")
 
@@ -124,6 +134,7 @@ def lib() -> C.CDLL:
         L.ccld_reset_window.argtypes = [vp]
         L.ccld_analyze_window.argtypes = [vp, C.c_int64, vp]
         L.ccld_rank_blame.argtypes = [vp, vp, vp]
+        L.ccld_flag_chains.argtypes = [vp, vp, vp]
         L.ccld_locate_hang.argtypes = [vp, vp, u64, vp]
         L.ccld_locate_hang_static.argtypes = [vp, vp, u64, vp]
         L.ccld_progress_rates.argtypes = [vp, vp, u64, vp]
@@ -175,6 +186,7 @@ class WindowResult:
     caps: Dict[str, int]
     dev: Dict[str, "object"] = field(repr=False, default_factory=dict)   # device tensors
     path: int = 0                    # 0: the window was sorted, 1: dense placement
+    raw: "object" = field(repr=False, default=None)                     # the C result structure of the call
 
     @property
     def seg(self): return _table(self.dev["seg"], SEG_COLS, self.caps["seg"], self.n_seg)
@@ -352,7 +364,23 @@ class Analyzer:
         if st in (-7, -11, -6):
             raise CcldError(st, "ccld_analyze_window")
         return WindowResult(STATUS.get(st, str(st)), r.n_records, r.n_seg, r.n_flag, r.n_group, r.n_alert,
-                            r.n_cand, caps, dev, int(r.path))
+                            r.n_cand, caps, dev, int(r.path), r)
+
+    def flag_chains(self, result: WindowResult):
+        """Root cause and secondary effects among the late entries of the analysis `result` (which must be
+        the context's most recent one): -> (status, {parent, root, root_rank, depth} per flag,
+        {root_entries, secondary_entries, caused} per rank)."""
+        t = self.torch
+        cap = max(int(result.n_flag), 1)
+        chain = t.empty(len(CHAIN_COLS) * cap, dtype=t.int64, device=self.device)
+        per_rank = t.empty(len(CHAIN_RANK_COLS) * self.n_ranks, dtype=t.int64, device=self.device)
+        o = _ChainResult(cap, chain.data_ptr(), per_rank.data_ptr())
+        st = self.L.ccld_flag_chains(self._ctx, C.addressof(result.raw), C.addressof(o))
+        if st not in (0, 1):
+            raise CcldError(st, "ccld_flag_chains")
+        n = int(o.n_chain)
+        return (STATUS.get(st, str(st)), _table(chain, CHAIN_COLS, cap, n),
+                _table(per_rank, CHAIN_RANK_COLS, self.n_ranks, self.n_ranks))
 
     def rank_blame(self, to_host: bool = True, buffers=None):
         """-> (blame columns, order).  to_host=False leaves both on the device (column-major int64 table

@@ -79,6 +79,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->alert_list = w.take<uint32_t>(NT);
   c->alert_ncand = w.take<uint32_t>(N + 2);
   c->gstate = w.take<GroupState>((uint64_t)n_comms * GROUP_SLOTS);
+  c->chain_first = w.take<uint32_t>((uint64_t)n_comms + 2);
   // the counters and the blame table are cleared together at the start of every analysis
   c->counters = w.take<uint64_t>(CNT_COUNT);
   c->blame = w.take<int64_t>((uint64_t)CCLD_BLM_NCOL * n_ranks);
@@ -240,6 +241,7 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   c->kf.mb = mb; c->kf.cb = cb; c->kf.sb = 64 - mb - cb;
   c->dense_capable = dense_capable(params, topo);
   c->last_path = 0;
+  c->chain_ready = false;
   c->max_comm_size = max_size;
   c->rank_bits = bits_for_host(topo->n_ranks - 1);
   c->head = 0; c->count = 0; c->next_slot = 0; c->total_ingested = 0;
@@ -362,6 +364,7 @@ ccld_status ccld_reset_window(ccld_ctx* c) {
   if (!c) return CCLD_E_NULL;
   c->head = 0; c->count = 0; c->batch_n.clear(); c->batch_slot.clear(); c->batch_seqno.clear();
   c->inc_ok = false;
+  c->chain_ready = false;
   return CCLD_OK;
 }
 
@@ -377,6 +380,7 @@ ccld_status ccld_ingest(ccld_ctx* c, const ccld_records* b, uint64_t n) {
     for (size_t i = 0; i < drop; ++i) { head = (head + c->batch_n[i]) % std::max<uint64_t>(c->cap, 1); count -= c->batch_n[i]; }
   }
   if (count + n > c->cap) return CCLD_E_CAPACITY;
+  c->chain_ready = false;
   IngestArgs a;
   std::memset(&a, 0, sizeof(a));
   const uint32_t slot = c->next_slot;
@@ -438,6 +442,7 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
   o->status = CCLD_OK;
   o->path = dense ? 1 : 0;
   *fallback = false;
+  c->chain_ready = false;
   c->blame_valid = false;
   if (!o->seg || o->seg_cap == 0) return o->status = CCLD_E_NULL;
   if ((o->flag_cap && !o->flag) || (o->group_cap && !o->group) || (o->alert_cap && !o->alert) ||
@@ -719,6 +724,9 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
   // the order of this window serves the next analysis (windows of several batches only)
   c->inc_ok = c->p.window_batches > 1 && !dense;
   c->last_path = dense ? 1 : 0;
+  c->chain_ready = true;
+  c->last_seg = o->seg; c->last_seg_cap = o->seg_cap; c->last_n_seg = o->n_seg; c->last_n_flag = o->n_flag;
+  c->last_rec_flag = sa.rec_flag; c->last_rows = rows;
   c->inc_sf = c->sf; c->inc_head = c->head; c->inc_count = n; c->inc_total = c->total_ingested;
   return o->status;
 }

@@ -166,6 +166,12 @@ struct ccld_ctx {
   void* d_desc;                       // [fine_cap] FineDesc
   uint32_t fine_cap;
   int last_path;                      // 1: the last analysis used the dense placement
+  // what ccld_flag_chains needs of the most recent analysis
+  bool chain_ready;                   // the sorted order, flag positions and lags of that analysis are still in the workspace
+  const int64_t* last_seg; uint64_t last_seg_cap, last_n_seg, last_n_flag;
+  const uint8_t* last_rec_flag;
+  const ccld::Row* last_rows;         // payload rows that the sorted row indices address
+  uint32_t* chain_first;              // [n_comms + 2] first table row of each communicator
   // last analysis
   int sorted_buf;                     // which ping-pong buffer holds the sorted window
   // the order of the last analysed window, kept for the next analysis of a window of several batches

@@ -760,6 +760,7 @@ extern "C" ccld_status ccld_locate_hang(ccld_ctx* c, const ccld_snapshots* sn, u
   if (s != CCLD_OK) return s;
   if (n_cell > c->snap_cap || n_rows > c->snap_cap) return o->status = CCLD_E_CAPACITY;
   c->inc_ok = false;            // the root list is sorted in the window's sort buffers
+  c->chain_ready = false;
   return locate_hang_on(c, scratch_of_context(c), sn, n_rows, n_cell, o);
 }
 

@@ -135,6 +135,195 @@ __device__ __forceinline__ i64 reduce_min(i64 v) {
   return v;
 }
 
+// What one lane knows about its record before the group-wide statistics.
+struct DenseLane {
+  i64 e, x;          // arrival, completion (T_INFLIGHT while the operation runs)
+  u64 nb;            // bytes
+  u32 op, rank;
+  bool valid;        // the lane's member has a record in this collective
+  u64 pm;            // lanes of this lane's collective whose members have a record
+  u32 fl;            // first such lane
+  u32 n, first, j;   // records of the collective, sorted position of its first record and of this record
+  u32 srow;          // the collective's row of the table
+  u32 comm;
+  u64 seq;           // operation counter
+};
+
+// table row of one collective (called by one lane)
+__device__ __forceinline__ void dense_put_row(const SegArgs& a, const DenseLane& L, u32 ninfl, bool complete, bool incons,
+                                              bool barrier, bool usable, u32 hop, u64 hb, i64 imin, u32 nd, i64 min_e,
+                                              i64 med_e, i64 max_e, i64 mad_e, i64 min_x, i64 med_x, i64 max_x, i64 mad_x,
+                                              i64 dmin, i64 dmax, u32 rmin, u32 rmax) {
+  const u32 srow = L.srow;
+  seg_put(a, CCLD_SEG_COMM, srow, (i64)L.comm);
+  seg_put(a, CCLD_SEG_SEQ, srow, (i64)L.seq);
+  seg_put(a, CCLD_SEG_N, srow, (i64)L.n);
+  seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
+  seg_put(a, CCLD_SEG_STATE, srow,
+          (complete ? CCLD_SEG_COMPLETE : 0) | (!incons ? CCLD_SEG_CONSISTENT : 0) |
+              (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+  seg_put(a, CCLD_SEG_OP, srow, (i64)hop);
+  seg_put(a, CCLD_SEG_BYTES, srow, (i64)hb);
+  seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
+  seg_put(a, CCLD_SEG_FIRST, srow, (i64)L.first);
+  seg_put_group(a, srow, usable, L.comm, hop, hb, dmax, dmin);
+  if (nd == 0) {
+    seg_put_empty_stats(a, srow);
+  } else {
+    seg_put(a, CCLD_SEG_ENTER_MIN, srow, min_e); seg_put(a, CCLD_SEG_ENTER_MED, srow, med_e);
+    seg_put(a, CCLD_SEG_ENTER_MAX, srow, max_e); seg_put(a, CCLD_SEG_ENTER_MAD, srow, mad_e);
+    seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
+    seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
+    seg_put(a, CCLD_SEG_DUR_MIN, srow, dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, dmax);
+    seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)rmax);
+  }
+}
+__device__ __forceinline__ void dense_put_record(const SegArgs& a, u32 j, u32 f, i64 le, i64 lx) {
+  a.rec_flag[j] = (uint8_t)f;
+  if (a.lag_e) a.lag_e[j] = le;
+  if (a.lag_x) a.lag_x[j] = lx;
+  if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
+}
+
+// Statistics of the collectives of one wavefront pass in 64-bit arithmetic (any spread of the times).
+template <int G>
+__device__ __forceinline__ void dense_pass64(const SegArgs& a, const DenseLane& L, u32 size, u32 lane, u32 gbase, u64 gmask) {
+  const i64 e = L.e, x = L.x;
+  const bool valid = L.valid;
+  const bool done = valid && x != T_INFLIGHT;
+  const u64 m_infl = ballot64(valid && !done);
+  const u32 nd = (u32)__popcll(ballot64(done) & gmask);
+  const u32 ninfl = (u32)__popcll(m_infl & gmask);
+  const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
+  const i64 se = sort_groups<G>(done ? e : T_INFLIGHT, lane);
+  const i64 sx = sort_groups<G>(done ? x : T_INFLIGHT, lane);
+  const i64 med_e = shfl_i64(se, gbase + km), med_x = shfl_i64(sx, gbase + km);
+  const i64 min_e = shfl_i64(se, gbase), max_e = shfl_i64(se, gbase + kl);
+  const i64 min_x = shfl_i64(sx, gbase), max_x = shfl_i64(sx, gbase + kl);
+  const i64 sde = sort_groups<G>(done ? (e >= med_e ? e - med_e : med_e - e) : T_INFLIGHT, lane);
+  const i64 sdx = sort_groups<G>(done ? (x >= med_x ? x - med_x : med_x - x) : T_INFLIGHT, lane);
+  const i64 mad_e = shfl_i64(sde, gbase + km), mad_x = shfl_i64(sdx, gbase + km);
+  i64 dmin = done ? x - e : INT64_MAX, dmax = done ? x - e : INT64_MIN;
+  u32 rmin = done ? L.rank : 0xFFFFFFFFu, rmax = rmin;
+  reduce_dur<G, false>(dmin, rmin);
+  reduce_dur<G, true>(dmax, rmax);
+  const u64 hb = shfl_u64(L.nb, (int)L.fl);
+  const u32 hop = __shfl(L.op, (int)L.fl, CCLD_WAVE);
+  const bool incons = (ballot64(valid && (L.nb != hb || L.op != hop)) & gmask) != 0;
+  i64 imin = T_INFLIGHT;
+  if (m_infl) imin = reduce_min<G>((valid && !done) ? e : T_INFLIGHT);
+  if (!valid) return;
+  const bool complete = L.n == size && ninfl == 0;
+  const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
+  const bool usable = complete && !incons && !barrier;
+  if (lane == L.fl)
+    dense_put_row(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, min_e, med_e, max_e, mad_e, min_x,
+                  med_x, max_x, mad_x, dmin, dmax, rmin, rmax);
+  i64 le = 0, lx = 0;
+  u32 f = 0;
+  if (usable) {
+    le = e - med_e; lx = x - med_x;
+    if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
+    if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
+  }
+  dense_put_record(a, L.j, f, le, lx);
+}
+
+// ---- the same statistics on 32-bit times relative to the collective's first record --------------------
+// Inside one collective the arrivals and completions lie within a second or so of each other, so they
+// are sorted, compared and subtracted as signed 32-bit offsets from the arrival of the collective's first
+// present member (half the instructions of the 64-bit form); the results are turned back into absolute
+// times where they are stored.  A pass in which some offset does not fit takes the 64-bit form.
+constexpr i32 REL_NONE = 0x7FFFFFFF;         // sorts behind every real offset (those stay below 2^30 in magnitude)
+
+template <int M>
+__device__ __forceinline__ i32 cmpx32(i32 v, u32 lane) {
+  const i32 p = (i32)xor_lane_u32<M>((u32)v);
+  const bool upper = (lane & high_bit(M)) != 0;
+  const i32 lo = p < v ? p : v, hi = p < v ? v : p;
+  return upper ? hi : lo;
+}
+template <int G>
+__device__ __forceinline__ i32 sort_groups32(i32 v, u32 lane) {
+  if constexpr (G >= 2) { v = cmpx32<1>(v, lane); }
+  if constexpr (G >= 4) { v = cmpx32<3>(v, lane); v = cmpx32<1>(v, lane); }
+  if constexpr (G >= 8) { v = cmpx32<7>(v, lane); v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane); }
+  if constexpr (G >= 16) { v = cmpx32<15>(v, lane); v = cmpx32<4>(v, lane); v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane); }
+  if constexpr (G >= 32) {
+    v = cmpx32<31>(v, lane); v = cmpx32<8>(v, lane); v = cmpx32<4>(v, lane); v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane);
+  }
+  if constexpr (G >= 64) {
+    v = cmpx32<63>(v, lane); v = cmpx32<16>(v, lane); v = cmpx32<8>(v, lane); v = cmpx32<4>(v, lane);
+    v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane);
+  }
+  return v;
+}
+// all-reduce of an unsigned 64-bit word inside a group
+template <int G, bool MAXIMUM>
+__device__ __forceinline__ u64 reduce_u64(u64 v) {
+#define CCLD_U64_STEP(M)                                                                         \
+  if constexpr (G > M) {                                                                         \
+    const u64 o = (u64)xor_lane_i64<M>((i64)v);                                                  \
+    v = MAXIMUM ? (o > v ? o : v) : (o < v ? o : v);                                             \
+  }
+  CCLD_U64_STEP(1) CCLD_U64_STEP(2) CCLD_U64_STEP(4) CCLD_U64_STEP(8) CCLD_U64_STEP(16) CCLD_U64_STEP(32)
+#undef CCLD_U64_STEP
+  return v;
+}
+// late iff lag > floor and lag * kden > knum * mad, with a 32-bit lag and a non-negative 32-bit mad
+__device__ __forceinline__ bool is_late32(i32 lag, i64 floor_ns, u32 knum, u32 kden, i32 mad) {
+  if (lag <= 0 || (i64)lag <= floor_ns) return false;       // a lag that is not positive never exceeds knum * mad >= 0
+  return (u64)(u32)lag * (u64)kden > (u64)knum * (u64)(u32)mad;
+}
+
+template <int G>
+__device__ __forceinline__ void dense_pass32(const SegArgs& a, const DenseLane& L, i64 ref, i32 er, i32 xr, u32 size,
+                                             u32 lane, u32 gbase, u64 gmask) {
+  const bool valid = L.valid;
+  const bool done = valid && L.x != T_INFLIGHT;
+  const u64 m_infl = ballot64(valid && !done);
+  const u32 nd = (u32)__popcll(ballot64(done) & gmask);
+  const u32 ninfl = (u32)__popcll(m_infl & gmask);
+  const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
+  const i32 se = sort_groups32<G>(done ? er : REL_NONE, lane);
+  const i32 sx = sort_groups32<G>(done ? xr : REL_NONE, lane);
+  const i32 med_e = __shfl(se, (int)(gbase + km), CCLD_WAVE), med_x = __shfl(sx, (int)(gbase + km), CCLD_WAVE);
+  const i32 min_e = __shfl(se, (int)gbase, CCLD_WAVE), max_e = __shfl(se, (int)(gbase + kl), CCLD_WAVE);
+  const i32 min_x = __shfl(sx, (int)gbase, CCLD_WAVE), max_x = __shfl(sx, (int)(gbase + kl), CCLD_WAVE);
+  const i32 de = er >= med_e ? er - med_e : med_e - er, dx = xr >= med_x ? xr - med_x : med_x - xr;
+  const i32 sde = sort_groups32<G>(done ? de : REL_NONE, lane);
+  const i32 sdx = sort_groups32<G>(done ? dx : REL_NONE, lane);
+  const i32 mad_e = __shfl(sde, (int)(gbase + km), CCLD_WAVE), mad_x = __shfl(sdx, (int)(gbase + km), CCLD_WAVE);
+  // T_min / T_max of the Duration Time with the ranks attaining them (ties: smallest rank): duration and rank
+  // travel as one 64-bit word
+  const u32 dur = (u32)(xr - er);
+  u64 wmin = done ? (((u64)dur << 32) | L.rank) : ~0ull;
+  u64 wmax = done ? (((u64)dur << 32) | (u32)~L.rank) : 0ull;
+  wmin = reduce_u64<G, false>(wmin);
+  wmax = reduce_u64<G, true>(wmax);
+  const u64 hb = shfl_u64(L.nb, (int)L.fl);
+  const u32 hop = __shfl(L.op, (int)L.fl, CCLD_WAVE);
+  const bool incons = (ballot64(valid && (L.nb != hb || L.op != hop)) & gmask) != 0;
+  i64 imin = T_INFLIGHT;
+  if (m_infl) imin = reduce_min<G>((valid && !done) ? L.e : T_INFLIGHT);
+  if (!valid) return;
+  const bool complete = L.n == size && ninfl == 0;
+  const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
+  const bool usable = complete && !incons && !barrier;
+  if (lane == L.fl)
+    dense_put_row(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, ref + min_e, ref + med_e, ref + max_e,
+                  (i64)mad_e, ref + min_x, ref + med_x, ref + max_x, (i64)mad_x, (i64)(wmin >> 32), (i64)(wmax >> 32),
+                  (u32)wmin, ~(u32)wmax);
+  i32 le = 0, lx = 0;
+  u32 f = 0;
+  if (usable) {
+    le = er - med_e; lx = xr - med_x;
+    if (is_late32(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
+    if (is_late32(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
+  }
+  dense_put_record(a, L.j, f, (i64)le, (i64)lx);
+}
+
 // ---- collectives of up to 64 records, 64/G of them per wavefront pass --------------------------
 template <int G>
 __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32 seg0, u32 nheads,
@@ -149,91 +338,34 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
     u32 a0 = 0, n = 0;
     if (sl < nheads) { a0 = s_head[sl]; n = (u32)s_head[sl + 1] - a0; }
     const bool small = n >= 1 && n <= (u32)SEG_WAVE_MAX;
-    const bool valid = small && l < n;
     if (n > (u32)SEG_WAVE_MAX && l == 0) {            // too long for a wavefront: leave it to k_seg_big
       const u64 slot = atomic_add_u64(&a.counters[CNT_NBIG], 1);
       a.big_list[3 * slot] = seg0 + sl;
       a.big_list[3 * slot + 1] = base + a0;
     }
-    u64 key = 0, nb = 0;
-    i64 e = 0, x = T_INFLIGHT;
-    u32 op = 0, j = 0, rank = 0;
-    if (valid) {
-      j = base + a0 + l;
-      key = a.key[j];
-      const Row rw = load_row(a, j);
+    DenseLane L;
+    L.valid = small && l < n;
+    L.e = 0; L.x = T_INFLIGHT; L.nb = 0; L.op = 0; L.rank = 0;
+    L.first = base + a0; L.j = L.first + l; L.fl = gbase; L.n = n; L.srow = seg0 + sl;
+    L.pm = 0;
+    u64 key = 0;
+    if (L.valid) {
+      key = a.key[L.j];
+      const Row rw = load_row(a, L.j);
       // the slot -> rank lookup overlaps the row gather
-      rank = a.members_sorted[a.member_off[(u32)(key >> (mb + a.sf.ws))] + (u32)(key & mmask)];
-      e = rw.t_enter; x = rw.t_exit; nb = rw.bytes; op = rw.op;
+      L.rank = a.members_sorted[a.member_off[(u32)(key >> (mb + a.sf.ws))] + (u32)(key & mmask)];
+      L.e = rw.t_enter; L.x = rw.t_exit; L.nb = rw.bytes; L.op = rw.op;
     }
-    const bool done = valid && x != T_INFLIGHT;
-    const u64 m_infl = ballot64(valid && !done);
-    const u32 nd = (u32)__popcll(ballot64(done) & gmask);
-    const u32 ninfl = (u32)__popcll(m_infl & gmask);
-    const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
-    // arrival and completion: sorted inside the group, lane k of the group holds the k-th smallest
-    const i64 se = sort_groups<G>(done ? e : T_INFLIGHT, lane);
-    const i64 sx = sort_groups<G>(done ? x : T_INFLIGHT, lane);
-    const i64 med_e = shfl_i64(se, gbase + km), med_x = shfl_i64(sx, gbase + km);
-    const i64 min_e = shfl_i64(se, gbase), max_e = shfl_i64(se, gbase + kl);
-    const i64 min_x = shfl_i64(sx, gbase), max_x = shfl_i64(sx, gbase + kl);
-    const i64 sde = sort_groups<G>(done ? (e >= med_e ? e - med_e : med_e - e) : T_INFLIGHT, lane);
-    const i64 sdx = sort_groups<G>(done ? (x >= med_x ? x - med_x : med_x - x) : T_INFLIGHT, lane);
-    const i64 mad_e = shfl_i64(sde, gbase + km), mad_x = shfl_i64(sdx, gbase + km);
-    // T_min / T_max of the Duration Time with the ranks attaining them (ties: smallest rank)
-    i64 dmin = done ? x - e : INT64_MAX, dmax = done ? x - e : INT64_MIN;
-    u32 rmin = done ? rank : 0xFFFFFFFFu, rmax = rmin;
-    reduce_dur<G, false>(dmin, rmin);
-    reduce_dur<G, true>(dmax, rmax);
-    // Operation Type Set must agree across the collective
-    const u64 hb = shfl_u64(nb, gbase);
-    const u32 hop = __shfl(op, gbase, CCLD_WAVE);
-    const bool incons = (ballot64(valid && (nb != hb || op != hop)) & gmask) != 0;
-    i64 imin = T_INFLIGHT;
-    if (m_infl) imin = reduce_min<G>((valid && !done) ? e : T_INFLIGHT);
-    const u32 comm = (u32)(key >> (mb + a.sf.ws));
-    bool usable = false;
-    if (valid) {
-      const bool complete = n == a.comm_size[comm] && ninfl == 0;
-      const bool barrier = op == CCLD_OP_ALLREDUCE && nb < (u64)a.barrier_bytes;
-      usable = complete && !incons && !barrier;
-      if (l == 0) {
-        const u32 srow = seg0 + sl;
-        seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
-        seg_put(a, CCLD_SEG_SEQ, srow, (i64)(((key >> mb) & smask) + a.sf.seq_base));
-        seg_put(a, CCLD_SEG_N, srow, (i64)n);
-        seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
-        seg_put(a, CCLD_SEG_STATE, srow,
-                (complete ? CCLD_SEG_COMPLETE : 0) | (!incons ? CCLD_SEG_CONSISTENT : 0) |
-                    (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
-        seg_put(a, CCLD_SEG_OP, srow, (i64)op);
-        seg_put(a, CCLD_SEG_BYTES, srow, (i64)nb);
-        seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
-        seg_put(a, CCLD_SEG_FIRST, srow, (i64)j);
-        seg_put_group(a, srow, usable, comm, op, nb, dmax, dmin);
-        if (nd == 0) {
-          seg_put_empty_stats(a, srow);
-        } else {
-          seg_put(a, CCLD_SEG_ENTER_MIN, srow, min_e); seg_put(a, CCLD_SEG_ENTER_MED, srow, med_e);
-          seg_put(a, CCLD_SEG_ENTER_MAX, srow, max_e); seg_put(a, CCLD_SEG_ENTER_MAD, srow, mad_e);
-          seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
-          seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
-          seg_put(a, CCLD_SEG_DUR_MIN, srow, dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, dmax);
-          seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)rmax);
-        }
-      }
-      i64 le = 0, lx = 0;
-      u32 f = 0;
-      if (usable) {
-        le = e - med_e; lx = x - med_x;
-        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
-        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
-      }
-      a.rec_flag[j] = (uint8_t)f;
-      if (a.lag_e) a.lag_e[j] = le;
-      if (a.lag_x) a.lag_x[j] = lx;
-      if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
-    }
+    L.comm = (u32)(key >> (mb + a.sf.ws));
+    L.seq = ((key >> mb) & smask) + a.sf.seq_base;
+    const u32 size = L.valid ? a.comm_size[L.comm] : 0u;
+    // offsets from the arrival of the collective's first record
+    const i64 ref = shfl_i64(L.e, (int)gbase);
+    const i64 oe = L.e - ref, ox = L.x - ref;
+    constexpr i64 LIM = (i64)1 << 30;
+    const bool wide = L.valid && (oe < -LIM || oe >= LIM || (L.x != T_INFLIGHT && (ox < -LIM || ox >= LIM)));
+    if (ballot64(wide) == 0) dense_pass32<G>(a, L, ref, (i32)oe, (i32)ox, size, lane, gbase, gmask);
+    else dense_pass64<G>(a, L, size, lane, gbase, gmask);
   }
 }
 
@@ -793,195 +925,6 @@ __global__ __launch_bounds__(256) void k_seg_group_listed(SegArgs a) {
 // indices in (communicator, counter, rank) order, which the flag, blame, group and alert stages read, and
 // adds the records per rank to the blame table.
 constexpr int DENSE_THREADS = 256;
-
-// What one lane knows about its record before the group-wide statistics.
-struct DenseLane {
-  i64 e, x;          // arrival, completion (T_INFLIGHT while the operation runs)
-  u64 nb;            // bytes
-  u32 op, rank;
-  bool valid;        // the lane's member has a record in this collective
-  u64 pm;            // lanes of this lane's collective whose members have a record
-  u32 fl;            // first such lane
-  u32 n, first, j;   // records of the collective, sorted position of its first record and of this record
-  u32 srow;          // the collective's row of the table
-  u32 comm;
-  u64 seq;           // operation counter
-};
-
-// table row of one collective (called by one lane)
-__device__ __forceinline__ void dense_put_row(const SegArgs& a, const DenseLane& L, u32 ninfl, bool complete, bool incons,
-                                              bool barrier, bool usable, u32 hop, u64 hb, i64 imin, u32 nd, i64 min_e,
-                                              i64 med_e, i64 max_e, i64 mad_e, i64 min_x, i64 med_x, i64 max_x, i64 mad_x,
-                                              i64 dmin, i64 dmax, u32 rmin, u32 rmax) {
-  const u32 srow = L.srow;
-  seg_put(a, CCLD_SEG_COMM, srow, (i64)L.comm);
-  seg_put(a, CCLD_SEG_SEQ, srow, (i64)L.seq);
-  seg_put(a, CCLD_SEG_N, srow, (i64)L.n);
-  seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
-  seg_put(a, CCLD_SEG_STATE, srow,
-          (complete ? CCLD_SEG_COMPLETE : 0) | (!incons ? CCLD_SEG_CONSISTENT : 0) |
-              (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
-  seg_put(a, CCLD_SEG_OP, srow, (i64)hop);
-  seg_put(a, CCLD_SEG_BYTES, srow, (i64)hb);
-  seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, imin);
-  seg_put(a, CCLD_SEG_FIRST, srow, (i64)L.first);
-  seg_put_group(a, srow, usable, L.comm, hop, hb, dmax, dmin);
-  if (nd == 0) {
-    seg_put_empty_stats(a, srow);
-  } else {
-    seg_put(a, CCLD_SEG_ENTER_MIN, srow, min_e); seg_put(a, CCLD_SEG_ENTER_MED, srow, med_e);
-    seg_put(a, CCLD_SEG_ENTER_MAX, srow, max_e); seg_put(a, CCLD_SEG_ENTER_MAD, srow, mad_e);
-    seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
-    seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
-    seg_put(a, CCLD_SEG_DUR_MIN, srow, dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, dmax);
-    seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)rmin); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)rmax);
-  }
-}
-__device__ __forceinline__ void dense_put_record(const SegArgs& a, u32 j, u32 f, i64 le, i64 lx) {
-  a.rec_flag[j] = (uint8_t)f;
-  if (a.lag_e) a.lag_e[j] = le;
-  if (a.lag_x) a.lag_x[j] = lx;
-  if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
-}
-
-// Statistics of the collectives of one wavefront pass in 64-bit arithmetic (any spread of the times).
-template <int G>
-__device__ __forceinline__ void dense_pass64(const SegArgs& a, const DenseLane& L, u32 size, u32 lane, u32 gbase, u64 gmask) {
-  const i64 e = L.e, x = L.x;
-  const bool valid = L.valid;
-  const bool done = valid && x != T_INFLIGHT;
-  const u64 m_infl = ballot64(valid && !done);
-  const u32 nd = (u32)__popcll(ballot64(done) & gmask);
-  const u32 ninfl = (u32)__popcll(m_infl & gmask);
-  const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
-  const i64 se = sort_groups<G>(done ? e : T_INFLIGHT, lane);
-  const i64 sx = sort_groups<G>(done ? x : T_INFLIGHT, lane);
-  const i64 med_e = shfl_i64(se, gbase + km), med_x = shfl_i64(sx, gbase + km);
-  const i64 min_e = shfl_i64(se, gbase), max_e = shfl_i64(se, gbase + kl);
-  const i64 min_x = shfl_i64(sx, gbase), max_x = shfl_i64(sx, gbase + kl);
-  const i64 sde = sort_groups<G>(done ? (e >= med_e ? e - med_e : med_e - e) : T_INFLIGHT, lane);
-  const i64 sdx = sort_groups<G>(done ? (x >= med_x ? x - med_x : med_x - x) : T_INFLIGHT, lane);
-  const i64 mad_e = shfl_i64(sde, gbase + km), mad_x = shfl_i64(sdx, gbase + km);
-  i64 dmin = done ? x - e : INT64_MAX, dmax = done ? x - e : INT64_MIN;
-  u32 rmin = done ? L.rank : 0xFFFFFFFFu, rmax = rmin;
-  reduce_dur<G, false>(dmin, rmin);
-  reduce_dur<G, true>(dmax, rmax);
-  const u64 hb = shfl_u64(L.nb, (int)L.fl);
-  const u32 hop = __shfl(L.op, (int)L.fl, CCLD_WAVE);
-  const bool incons = (ballot64(valid && (L.nb != hb || L.op != hop)) & gmask) != 0;
-  i64 imin = T_INFLIGHT;
-  if (m_infl) imin = reduce_min<G>((valid && !done) ? e : T_INFLIGHT);
-  if (!valid) return;
-  const bool complete = L.n == size && ninfl == 0;
-  const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
-  const bool usable = complete && !incons && !barrier;
-  if (lane == L.fl)
-    dense_put_row(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, min_e, med_e, max_e, mad_e, min_x,
-                  med_x, max_x, mad_x, dmin, dmax, rmin, rmax);
-  i64 le = 0, lx = 0;
-  u32 f = 0;
-  if (usable) {
-    le = e - med_e; lx = x - med_x;
-    if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
-    if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
-  }
-  dense_put_record(a, L.j, f, le, lx);
-}
-
-// ---- the same statistics on 32-bit times relative to the collective's first record --------------------
-// Inside one collective the arrivals and completions lie within a second or so of each other, so they
-// are sorted, compared and subtracted as signed 32-bit offsets from the arrival of the collective's first
-// present member (half the instructions of the 64-bit form); the results are turned back into absolute
-// times where they are stored.  A pass in which some offset does not fit takes the 64-bit form.
-constexpr i32 REL_NONE = 0x7FFFFFFF;         // sorts behind every real offset (those stay below 2^30 in magnitude)
-
-template <int M>
-__device__ __forceinline__ i32 cmpx32(i32 v, u32 lane) {
-  const i32 p = (i32)xor_lane_u32<M>((u32)v);
-  const bool upper = (lane & high_bit(M)) != 0;
-  const i32 lo = p < v ? p : v, hi = p < v ? v : p;
-  return upper ? hi : lo;
-}
-template <int G>
-__device__ __forceinline__ i32 sort_groups32(i32 v, u32 lane) {
-  if constexpr (G >= 2) { v = cmpx32<1>(v, lane); }
-  if constexpr (G >= 4) { v = cmpx32<3>(v, lane); v = cmpx32<1>(v, lane); }
-  if constexpr (G >= 8) { v = cmpx32<7>(v, lane); v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane); }
-  if constexpr (G >= 16) { v = cmpx32<15>(v, lane); v = cmpx32<4>(v, lane); v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane); }
-  if constexpr (G >= 32) {
-    v = cmpx32<31>(v, lane); v = cmpx32<8>(v, lane); v = cmpx32<4>(v, lane); v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane);
-  }
-  if constexpr (G >= 64) {
-    v = cmpx32<63>(v, lane); v = cmpx32<16>(v, lane); v = cmpx32<8>(v, lane); v = cmpx32<4>(v, lane);
-    v = cmpx32<2>(v, lane); v = cmpx32<1>(v, lane);
-  }
-  return v;
-}
-// all-reduce of an unsigned 64-bit word inside a group
-template <int G, bool MAXIMUM>
-__device__ __forceinline__ u64 reduce_u64(u64 v) {
-#define CCLD_U64_STEP(M)                                                                         \
-  if constexpr (G > M) {                                                                         \
-    const u64 o = (u64)xor_lane_i64<M>((i64)v);                                                  \
-    v = MAXIMUM ? (o > v ? o : v) : (o < v ? o : v);                                             \
-  }
-  CCLD_U64_STEP(1) CCLD_U64_STEP(2) CCLD_U64_STEP(4) CCLD_U64_STEP(8) CCLD_U64_STEP(16) CCLD_U64_STEP(32)
-#undef CCLD_U64_STEP
-  return v;
-}
-// late iff lag > floor and lag * kden > knum * mad, with a 32-bit lag and a non-negative 32-bit mad
-__device__ __forceinline__ bool is_late32(i32 lag, i64 floor_ns, u32 knum, u32 kden, i32 mad) {
-  if (lag <= 0 || (i64)lag <= floor_ns) return false;       // a lag that is not positive never exceeds knum * mad >= 0
-  return (u64)(u32)lag * (u64)kden > (u64)knum * (u64)(u32)mad;
-}
-
-template <int G>
-__device__ __forceinline__ void dense_pass32(const SegArgs& a, const DenseLane& L, i64 ref, i32 er, i32 xr, u32 size,
-                                             u32 lane, u32 gbase, u64 gmask) {
-  const bool valid = L.valid;
-  const bool done = valid && L.x != T_INFLIGHT;
-  const u64 m_infl = ballot64(valid && !done);
-  const u32 nd = (u32)__popcll(ballot64(done) & gmask);
-  const u32 ninfl = (u32)__popcll(m_infl & gmask);
-  const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
-  const i32 se = sort_groups32<G>(done ? er : REL_NONE, lane);
-  const i32 sx = sort_groups32<G>(done ? xr : REL_NONE, lane);
-  const i32 med_e = __shfl(se, (int)(gbase + km), CCLD_WAVE), med_x = __shfl(sx, (int)(gbase + km), CCLD_WAVE);
-  const i32 min_e = __shfl(se, (int)gbase, CCLD_WAVE), max_e = __shfl(se, (int)(gbase + kl), CCLD_WAVE);
-  const i32 min_x = __shfl(sx, (int)gbase, CCLD_WAVE), max_x = __shfl(sx, (int)(gbase + kl), CCLD_WAVE);
-  const i32 de = er >= med_e ? er - med_e : med_e - er, dx = xr >= med_x ? xr - med_x : med_x - xr;
-  const i32 sde = sort_groups32<G>(done ? de : REL_NONE, lane);
-  const i32 sdx = sort_groups32<G>(done ? dx : REL_NONE, lane);
-  const i32 mad_e = __shfl(sde, (int)(gbase + km), CCLD_WAVE), mad_x = __shfl(sdx, (int)(gbase + km), CCLD_WAVE);
-  // T_min / T_max of the Duration Time with the ranks attaining them (ties: smallest rank): duration and rank
-  // travel as one 64-bit word
-  const u32 dur = (u32)(xr - er);
-  u64 wmin = done ? (((u64)dur << 32) | L.rank) : ~0ull;
-  u64 wmax = done ? (((u64)dur << 32) | (u32)~L.rank) : 0ull;
-  wmin = reduce_u64<G, false>(wmin);
-  wmax = reduce_u64<G, true>(wmax);
-  const u64 hb = shfl_u64(L.nb, (int)L.fl);
-  const u32 hop = __shfl(L.op, (int)L.fl, CCLD_WAVE);
-  const bool incons = (ballot64(valid && (L.nb != hb || L.op != hop)) & gmask) != 0;
-  i64 imin = T_INFLIGHT;
-  if (m_infl) imin = reduce_min<G>((valid && !done) ? L.e : T_INFLIGHT);
-  if (!valid) return;
-  const bool complete = L.n == size && ninfl == 0;
-  const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
-  const bool usable = complete && !incons && !barrier;
-  if (lane == L.fl)
-    dense_put_row(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, ref + min_e, ref + med_e, ref + max_e,
-                  (i64)mad_e, ref + min_x, ref + med_x, ref + max_x, (i64)mad_x, (i64)(wmin >> 32), (i64)(wmax >> 32),
-                  (u32)wmin, ~(u32)wmax);
-  i32 le = 0, lx = 0;
-  u32 f = 0;
-  if (usable) {
-    le = er - med_e; lx = xr - med_x;
-    if (is_late32(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
-    if (is_late32(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
-  }
-  dense_put_record(a, L.j, f, (i64)le, (i64)lx);
-}
 
 template <int G>
 __device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, const uint4* s_cell, const u32* s_pres,
