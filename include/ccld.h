@@ -390,7 +390,7 @@ ccld_status ccld_rank_blame(ccld_ctx *ctx, int64_t *blame, uint32_t *order);
  * accumulated milliseconds and launch counts (host arrays of CCLD_PROF_NCLASS entries). */
 enum { CCLD_PROF_INGEST, CCLD_PROF_SORT_HIST, CCLD_PROF_SORT_SCAN, CCLD_PROF_SORT_SCATTER, CCLD_PROF_SEGMENTS,
        CCLD_PROF_FLAGS, CCLD_PROF_BLAME, CCLD_PROF_GROUPS, CCLD_PROF_ALERTS, CCLD_PROF_HANG,
-       CCLD_PROF_SEG_HEADS, CCLD_PROF_DENSE_PARTITION,
+       CCLD_PROF_SEG_HEADS, CCLD_PROF_DENSE_PARTITION, CCLD_PROF_HANG_PLACE, CCLD_PROF_FRAMES,
        CCLD_PROF_NCLASS = 16 };
 ccld_status ccld_profile_enable(ccld_ctx *ctx, int32_t on);
 ccld_status ccld_profile_read(ccld_ctx *ctx, double *ms, uint64_t *launches, uint64_t *sort_passes);

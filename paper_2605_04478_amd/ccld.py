@@ -106,7 +106,7 @@ class _RateResult(C.Structure):
 _lib: Optional[C.CDLL] = None
 
 PROF_CLASSES = ("ingest", "sort_hist", "sort_scan", "sort_scatter", "segments", "flags", "blame", "groups", "alerts",
-                "hang", "seg_heads", "dense_partition")
+                "hang", "seg_heads", "dense_partition", "hang_place", "frames")
 PLACEMENT_SORT, PLACEMENT_DENSE = 0, 1
 PROF_NCLASS = 16
 

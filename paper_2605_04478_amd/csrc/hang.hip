@@ -39,6 +39,12 @@ struct HangArgs {
   u64* layer_max;
   u64* counters;
   u32 stall_snapshots, fifo_depth;
+  // two-step placement of large grids: rows regrouped by region of 2^rb cells
+  ulonglong2* part_pay;   // [n_regions << rb] cell contents
+  u32* part_idx;          // [n_regions << rb] cell number inside the region
+  u32* part_fill;         // [n_regions] rows received
+  int rb;
+  u32 n_regions;
 };
 
 #define PAIR(a, col, p) (a.pair[(u64)(col) * a.n_members + (p)])
@@ -121,6 +127,155 @@ __global__ __launch_bounds__(256) void k_hang_place(HangArgs a) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) st |= shfl_xor_u64(st, m);
   if (lane_id() == 0 && st) atomicOr((unsigned long long*)&a.counters[CNT_STATUS], (unsigned long long)st);
+}
+
+// ---- placement of large grids in two steps ---------------------------------------------------------
+// Rows arrive in any order, so placing them directly sends one 16-byte store per row to a random line of a
+// grid that is far larger than the L2.  Here the rows are first regrouped by region of 2^rb cells (at most
+// PART_REGIONS regions; a round's rows of one region leave as one run), then every region's rows are placed
+// by workgroups that run side by side on one XCD, so that the eight cells of a line meet in that XCD's L2
+// and reach memory as whole lines.  A region takes at most 2^rb rows; more can only arrive with duplicate
+// cells, which the caller's exact pass reports.
+constexpr u32 PART_REGIONS = 256;
+constexpr int PART_THREADS = 512, PART_U = 4;
+constexpr u32 PART_CHUNK = PART_THREADS * PART_U;
+constexpr u32 PLACE_ROWS = 256;           // rows per workgroup of the second step (one per thread)
+
+__global__ __launch_bounds__(PART_THREADS) void k_hang_part(HangArgs a, u64 chunk) {
+  extern __shared__ ulonglong2 s_pay[];                    // [PART_CHUNK] contents | [PART_CHUNK] cell numbers | [PART_CHUNK] destinations
+  u32* s_idx = reinterpret_cast<u32*>(s_pay + PART_CHUNK);
+  u32* s_dst = s_idx + PART_CHUNK;
+  __shared__ u32 s_cnt[PART_REGIONS], s_pre[PART_REGIONS], s_base[PART_REGIONS], s_scan[PART_THREADS / CCLD_WAVE], s_total;
+  const u32 tid = threadIdx.x;
+  u64 status = 0;
+  const uint4* __restrict__ memb4 = reinterpret_cast<const uint4*>(a.T.rank_memb4);
+  const u32 mmask = a.mb < 32 ? (1u << a.mb) - 1 : ~0u;
+  const u32 cap = 1u << a.rb, kmask = cap - 1;
+  const u64 i_begin = chunk * blockIdx.x;
+  const u64 i_end = chunk * (blockIdx.x + 1) < a.n_rows ? chunk * (blockIdx.x + 1) : a.n_rows;
+  if (tid < PART_REGIONS) s_cnt[tid] = 0;
+  __syncthreads();
+  u32 c[PART_U], r[PART_U], ch[PART_U], sn[PART_U], se[PART_U], rv[PART_U];
+  u64 sq[PART_U];
+  u32 nc[PART_U], nr[PART_U], nch[PART_U], nsn[PART_U], nse[PART_U], nrv[PART_U];
+  u64 nsq[PART_U];
+  auto load_round = [&](u64 base, u32 (&C)[PART_U], u32 (&R)[PART_U], u32 (&CH)[PART_U], u32 (&SN)[PART_U], u64 (&SQ)[PART_U],
+                        u32 (&SE)[PART_U], u32 (&RV)[PART_U]) {
+#pragma unroll
+    for (int u = 0; u < PART_U; ++u) {
+      const u64 i = base + (u64)u * PART_THREADS + tid;
+      if (i < i_end) {
+        C[u] = __builtin_nontemporal_load(a.comm + i); R[u] = __builtin_nontemporal_load(a.rank + i);
+        CH[u] = __builtin_nontemporal_load(a.channel + i); SN[u] = __builtin_nontemporal_load(a.snap + i);
+        SQ[u] = __builtin_nontemporal_load(a.seq_posted + i);
+        SE[u] = __builtin_nontemporal_load(a.sent + i); RV[u] = __builtin_nontemporal_load(a.recv + i);
+      }
+    }
+  };
+  load_round(i_begin, c, r, ch, sn, sq, se, rv);
+  for (u64 base = i_begin; base < i_end; base += PART_CHUNK) {       // uniform over the workgroup
+    u32 at[PART_U], reg[PART_U], kin[PART_U];
+    bool on[PART_U];
+#pragma unroll
+    for (int u = 0; u < PART_U; ++u) on[u] = base + (u64)u * PART_THREADS + tid < i_end;
+    load_round(base + PART_CHUNK, nc, nr, nch, nsn, nsq, nse, nrv);     // the next round's columns are on their way meanwhile
+    uint4 m[PART_U];
+#pragma unroll
+    for (int u = 0; u < PART_U; ++u) {
+      m[u] = make_uint4(~0u, ~0u, ~0u, ~0u);
+      if (on[u] && memb4 && r[u] < a.T.n_ranks) m[u] = memb4[r[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < PART_U; ++u) {
+      if (!on[u]) continue;
+      on[u] = false;
+      if (c[u] >= a.T.n_comms) { status |= DS_UNKNOWN_COMM; continue; }
+      int slot = -1;
+      if (r[u] < a.T.n_ranks) {
+        if (memb4) {
+          const u32 w = c[u] == (m[u].x >> a.mb) ? m[u].x : c[u] == (m[u].y >> a.mb) ? m[u].y
+                      : c[u] == (m[u].z >> a.mb) ? m[u].z : m[u].w;
+          if (c[u] == (w >> a.mb)) slot = (int)a.T.sorted_slot[a.T.member_off[c[u]] + (w & mmask)];
+        } else {
+          slot = slot_of(a.T, c[u], r[u]);
+        }
+      }
+      if (slot < 0) { status |= DS_NOT_MEMBER; continue; }
+      if (ch[u] >= a.n_ch || sn[u] >= a.n_snap) { status |= DS_RANGE; continue; }
+      const u64 k = (((u64)a.T.member_off[c[u]] + (u32)slot) * a.n_ch + ch[u]) * a.n_snap + sn[u];
+      reg[u] = (u32)(k >> a.rb); kin[u] = (u32)k & kmask;
+      at[u] = atomicAdd(&s_cnt[reg[u]], 1u);
+      on[u] = true;
+    }
+    __syncthreads();
+    {
+      const u32 cnt = tid < a.n_regions ? s_cnt[tid] : 0u;
+      u32 tot;
+      const u32 ex = block_exclusive_sum<PART_THREADS>(cnt, s_scan, &tot);
+      if (tid < a.n_regions) {
+        s_pre[tid] = ex;
+        s_base[tid] = cnt ? atomicAdd(&a.part_fill[tid], cnt) : 0u;
+      }
+      if (tid == 0) s_total = tot;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < PART_U; ++u) {
+      if (!on[u]) continue;
+      const u32 q = s_pre[reg[u]] + at[u];
+      const u32 pos = s_base[reg[u]] + at[u];
+      if (pos >= cap) status |= DS_SUSPECT;              // more rows than cells: some cell is written twice
+      s_dst[q] = pos < cap ? ((reg[u] << a.rb) + pos) : ~0u;
+      s_idx[q] = kin[u];
+      s_pay[q] = make_ulonglong2(sq[u], (u64)se[u] | ((u64)rv[u] << 32));
+    }
+    __syncthreads();
+    const u32 total = s_total;
+    for (u32 i = tid; i < total; i += PART_THREADS) {
+      const u32 D = s_dst[i];
+      if (D == ~0u) continue;
+      // pieces of a line that this round writes completely leave with the streaming hint
+      const u32 o = D & 7;
+      const bool full = i >= o && i + 7 - o < total && s_dst[i - o] == D - o && s_dst[i + 7 - o] == D + 7 - o;
+      const ulonglong2 v = s_pay[i];
+      if (full) {
+        typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+        u64x2 vv = {v.x, v.y};
+        __builtin_nontemporal_store(vv, reinterpret_cast<u64x2*>(a.part_pay + D));
+      } else {
+        a.part_pay[D] = v;
+      }
+      a.part_idx[D] = s_idx[i];
+    }
+    if (tid < PART_REGIONS) s_cnt[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < PART_U; ++u) { c[u] = nc[u]; r[u] = nr[u]; ch[u] = nch[u]; sn[u] = nsn[u]; sq[u] = nsq[u]; se[u] = nse[u]; rv[u] = nrv[u]; }
+  }
+  u64 st = status;
+#pragma unroll
+  for (int m2 = 32; m2 >= 1; m2 >>= 1) st |= shfl_xor_u64(st, m2);
+  if (lane_id() == 0 && st) atomicOr((unsigned long long*)&a.counters[CNT_STATUS], (unsigned long long)st);
+}
+
+// Second step: workgroup i runs on XCD i % 8 (workgroups are dealt to the XCDs in turn); XCD x takes the regions
+// x, x + 8, ... one after the other, wpr consecutive workgroups of the XCD per region.
+__global__ __launch_bounds__(256) void k_hang_place_regions(HangArgs a, u32 wpr) {
+  const u32 xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const u32 reg = xcd + 8 * (j / wpr), part = j % wpr;
+  if (reg >= a.n_regions) return;
+  const u32 cap = 1u << a.rb;
+  const u32 have = a.part_fill[reg];
+  const u32 cnt = have < cap ? have : cap;
+  ulonglong2* __restrict__ cell2 = reinterpret_cast<ulonglong2*>(a.cell) + ((u64)reg << a.rb);
+  const ulonglong2* __restrict__ pay = a.part_pay + ((u64)reg << a.rb);
+  const u32* __restrict__ idx = a.part_idx + ((u64)reg << a.rb);
+  const u32 i = part * PLACE_ROWS + threadIdx.x;
+  if (i >= cnt) return;
+  typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+  const u32 k = __builtin_nontemporal_load(idx + i);                 // read once: streaming loads
+  const u64x2 t = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(pay + i));
+  cell2[k] = make_ulonglong2(t.x, t.y);
 }
 
 // ---- per (rank, communicator): stalled, operation counter, chunk totals, onset -------------------
@@ -616,7 +771,8 @@ struct HangScratch {
   SortBuffers sb;            // root list sort: n_members items
   uint64_t* keyC;            // [n_members]
   uint64_t sort_cap;
-  uint8_t* stage;            // [n_rows * 32] staging for host-resident rows, or null
+  uint8_t* stage;            // [stage_bytes] staging for host-resident rows, or null
+  uint64_t stage_bytes;
   bool fill_kernels;         // clear with fill kernels instead of hipMemsetAsync
 };
 
@@ -627,7 +783,7 @@ static HangScratch scratch_of_context(ccld_ctx* c) {
   S.tiles_a = c->tile_flags; S.tiles_b = c->tile_heads; S.comm_list = c->alert_list;
   S.sb.key[0] = c->sb.key[0]; S.sb.idx[0] = c->sb.idx[0]; S.sb.key[1] = c->sb.key[1]; S.sb.idx[1] = c->sb.idx[1];
   S.sb.table = c->table2; S.sb.totals = c->totals2;
-  S.keyC = c->keyC; S.sort_cap = c->sort_cap; S.stage = c->h_stage; S.fill_kernels = false;
+  S.keyC = c->keyC; S.sort_cap = c->sort_cap; S.stage = c->h_stage; S.stage_bytes = c->snap_cap * 32; S.fill_kernels = false;
   return S;
 }
 
@@ -661,17 +817,43 @@ static hipError_t place_snapshots(ccld_ctx* c, const HangScratch& S, const ccld_
   a.cand = S.cand; a.layer_max = S.layer_max; a.counters = S.counters;
   a.stall_snapshots = c->p.stall_snapshots; a.fifo_depth = c->p.fifo_depth;
 
-  c->prof.begin(CCLD_PROF_HANG);
+  c->prof.begin(CCLD_PROF_HANG_PLACE);
   if ((e = clear_bytes(st, S.counters, 0, sizeof(uint64_t) * CNT_COUNT, S.fill_kernels)) != hipSuccess) return e;
   a.exact = exact ? 1 : 0;
   if (exact) e = clear_bytes(st, S.cnt, 0, sizeof(uint32_t) * ((n_cell + 31) / 32), S.fill_kernels);
   else e = clear_bytes(st, S.cell, 0xFF, 16 * n_cell, S.fill_kernels);
   if (e != hipSuccess) return e;
-  if (n_rows) {
+  // large grids whose rows are already on the device (the staging area is free then) are placed in two steps
+  int rb = 16;
+  while ((n_cell >> rb) >= PART_REGIONS && rb < 31) ++rb;
+  const uint64_t n_regions = (n_cell + ((uint64_t)1 << rb) - 1) >> rb;
+  const bool two_step = !exact && sn->on_device && S.stage && n_rows >= ((uint64_t)1 << 20) && n_cell < ((uint64_t)1 << 31) &&
+                        (n_regions << rb) * 20 <= S.stage_bytes && n_regions <= PART_REGIONS;
+  if (n_rows && two_step) {
+    a.rb = rb; a.n_regions = (uint32_t)n_regions;
+    a.part_pay = reinterpret_cast<ulonglong2*>(S.stage);
+    a.part_idx = reinterpret_cast<uint32_t*>(S.stage + (n_regions << rb) * 16);
+    a.part_fill = S.cnt;                       // the presence bitmap is not in use in this mode
+    if ((e = clear_bytes(st, S.cnt, 0, sizeof(uint32_t) * PART_REGIONS, S.fill_kernels)) != hipSuccess) return e;
+    uint64_t g = (n_rows + PART_CHUNK - 1) / PART_CHUNK; if (g > 1024) g = 1024;
+    uint64_t chunk = (n_rows + g - 1) / g;
+    chunk = (chunk + PART_CHUNK - 1) / PART_CHUNK * PART_CHUNK;
+    static bool raised = false;       // more than 64 KB of dynamic LDS has to be asked for once
+    constexpr size_t part_lds = (size_t)PART_CHUNK * (16 + 4 + 4);
+    if (!raised) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hang_part), hipFuncAttributeMaxDynamicSharedMemorySize, (int)part_lds);
+      raised = true;
+    }
+    hipLaunchKernelGGL(k_hang_part, dim3((uint32_t)g), dim3(PART_THREADS), part_lds, st, a, chunk);
+    const uint32_t wpr = (uint32_t)((((uint64_t)1 << rb) + PLACE_ROWS - 1) / PLACE_ROWS);
+    const uint64_t g2 = 8 * ((n_regions + 7) / 8) * wpr;
+    hipLaunchKernelGGL(k_hang_place_regions, dim3((uint32_t)g2), dim3(256), 0, st, a, wpr);
+  } else if (n_rows) {
     uint64_t g = (n_rows + 255) / 256; if (g > 4096) g = 4096;
     if (exact) hipLaunchKernelGGL(k_hang_place<true>, dim3((uint32_t)g), dim3(256), 0, st, a);
     else hipLaunchKernelGGL(k_hang_place<false>, dim3((uint32_t)g), dim3(256), 0, st, a);
   }
+  c->prof.split(CCLD_PROF_HANG_PLACE, CCLD_PROF_HANG);
   return hipSuccess;
 }
 
@@ -840,6 +1022,7 @@ extern "C" ccld_status ccld_locate_hang_static(ccld_ctx* c, const ccld_snapshots
   S.keyC = w.take<uint64_t>(nm + 1);
   S.sort_cap = nm;
   S.stage = sn->on_device ? nullptr : w.take<uint8_t>(n_rows * 32);
+  S.stage_bytes = sn->on_device ? 0 : n_rows * 32;
   S.fill_kernels = true;
   if (w.off > CCLD_STATIC_SCRATCH_BYTES) return o->status = CCLD_E_CAPACITY;
   return locate_hang_on(c, S, sn, n_rows, n_cell, o);
@@ -927,7 +1110,7 @@ extern "C" ccld_status ccld_decode_frames(ccld_ctx* c, const ccld_frames* fr, co
   }
   a.n_frames = fr->n_frames; a.n_ch = fr->n_channels; a.snap = fr->snapshot; a.mb = c->kf.mb; a.T = c->topo;
   a.n_members = c->n_members; a.last = c->f_last; a.seen = c->f_seen; a.counters = c->counters;
-  c->prof.begin(CCLD_PROF_HANG);
+  c->prof.begin(CCLD_PROF_FRAMES);
   HIP_TRY(hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, st));
   HIP_TRY(hipMemsetAsync(c->f_seen, 0, sizeof(uint32_t) * (c->topo.n_ranks / 32 + 1), st));
   const uint32_t fblocks = (uint32_t)((fr->n_frames + 3) / 4);
@@ -935,10 +1118,10 @@ extern "C" ccld_status ccld_decode_frames(ccld_ctx* c, const ccld_frames* fr, co
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipMemcpyAsync(c->h_pinned, c->counters, sizeof(uint64_t) * CNT_COUNT, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
-  if (c->h_pinned[CNT_STATUS]) { c->prof.end(CCLD_PROF_HANG); c->prof.collect(); return hang_status(c->h_pinned[CNT_STATUS]); }
+  if (c->h_pinned[CNT_STATUS]) { c->prof.end(CCLD_PROF_FRAMES); c->prof.collect(); return hang_status(c->h_pinned[CNT_STATUS]); }
   if (fr->n_frames) hipLaunchKernelGGL(k_frames<false>, dim3(fblocks), dim3(256), 0, st, a);
   if (n_out) hipLaunchKernelGGL(k_frame_rows, dim3((uint32_t)((n_out + 255) / 256)), dim3(256), 0, st, a, *rows);
-  c->prof.end(CCLD_PROF_HANG);
+  c->prof.end(CCLD_PROF_FRAMES);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipStreamSynchronize(st));
   c->prof.collect();

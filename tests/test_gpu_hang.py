@@ -108,3 +108,37 @@ def test_a_row_that_holds_the_fill_pattern_is_still_a_row():
     state = lambda s, c, q, ch: full if (s == 2 and q == 1 and ch == 0) else (7 + (s > 4), 3 + s, 2 + s)
     g, o = run_both(topo, snap_rows(topo, 9, 2, state), 9, 2, what="all-ones-row", stall_snapshots=3)
     assert g.status == "OK"
+
+
+def test_large_grids_take_the_two_step_placement_with_the_same_results_and_statuses():
+    """Grids of a million cells and more are regrouped by region before they are placed; duplicates (a region
+    that receives more rows than it has cells, or a cell left at the fill) must still end in the exact pass."""
+    lay = tg.Layout3D(tp=4, pp=4, dp=32, world=True)                    # 512 ranks, 2,048 member slots
+    ht = tg.generate_hang(tg.config4(layout=lay, seed=5, n_channels=10, n_snapshots=60))
+    n = int(ht.cols["snap"].shape[0])
+    assert n == 2048 * 10 * 60 and n >= 1 << 20
+    g, o = run_both(ht.topo, ht.cols, 60, 10, what="large")
+    assert g.status == "OK" and list(g.root["rank"]) == [ht.root_rank]
+    rng = np.random.default_rng(1)
+    cases = {}
+    b = {k: v.copy() for k, v in ht.cols.items()}
+    i, j = rng.choice(n, 2, replace=False)
+    for k in b:
+        b[k][i] = b[k][j]                                              # one cell twice, one cell missing
+    cases["dup"] = (b, "E_DUPLICATE_KEY")
+    b = {k: v.copy() for k, v in ht.cols.items()}
+    first = np.nonzero((b["comm"] == b["comm"][0]) & (b["rank"] == b["rank"][0]) & (b["channel"] == b["channel"][0]))[0]
+    donors = rng.choice(n, 70_000, replace=False)                      # one region receives 70,000 rows more than it holds
+    for k in b:
+        b[k][donors] = b[k][first[0]]
+    cases["overflow"] = (b, "E_DUPLICATE_KEY")
+    b = {k: v.copy() for k, v in ht.cols.items()}
+    b["channel"][int(rng.integers(n))] = 10
+    cases["range"] = (b, "E_RANGE")
+    b = {k: v.copy() for k, v in ht.cols.items()}
+    b["comm"][int(rng.integers(n))] = ht.topo.n_comms
+    cases["comm"] = (b, "E_UNKNOWN_COMM")
+    cases["gap"] = ({k: v[:-1] for k, v in ht.cols.items()}, "E_SNAPSHOT_GAP")
+    for name, (c, want) in cases.items():
+        g, o = run_both(ht.topo, c, 60, 10, what=name)
+        assert g.status == want, (name, g.status)
