@@ -164,7 +164,7 @@ typedef struct {
   uint8_t *rec_flag;   /* device [n_records] or NULL: CCLD_FLAG_* bits, in sorted order          */
   uint32_t *perm;      /* device [n_records] or NULL: window index of the j-th record in (comm, seq, rank) order */
   uint64_t n_records, n_seg, n_flag, n_group, n_alert, n_cand;  /* out (host)                   */
-  ccld_status status;  /* out (host): CCLD_OK, a data error (no tables written), or CCLD_W_TRUNCATED */
+  ccld_status status;  /* out (host): CCLD_OK, a data error (counts are zero; table contents undefined), or CCLD_W_TRUNCATED */
   int32_t path;        /* out (host): 0 the window was sorted, 1 it was analysed by dense placement     */
 } ccld_window_result;
 

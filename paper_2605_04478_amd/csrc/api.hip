@@ -65,25 +65,29 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   const uint64_t seg_tiles = (NT + SEG_TILE - 1) / SEG_TILE, sel_tiles = (NT + SEL_TILE - 1) / SEL_TILE;
   c->tile_heads = w.take<uint32_t>(seg_tiles + 2);
   c->tile_flags = w.take<uint32_t>(sel_tiles + 2);
+  c->blame_list = w.take<uint32_t>(2ull * n_ranks);
+  c->blame_tiles = w.take<uint32_t>(n_ranks / SEL_TILE + 3);
+  c->blame_order = w.take<uint32_t>(n_ranks);
+  // per-record scratch of one analysis; nothing in it outlives the next ingest, so a batch that arrives in host
+  // memory is staged in the same bytes (48 per record of batch capacity)
+  c->stage = w.take<uint8_t>(0);
+  const uint64_t scratch_begin = w.off;
   c->rec_flag = w.take<uint8_t>(N);
   c->flag_pos = w.take<uint32_t>(N);
   c->flag_lag = w.take<int64_t>(2 * N);
   c->big_list = w.take<uint32_t>(3 * (N / 65 + 2));
   c->big_ex = w.take<int64_t>(2 * N);
   c->range_c = w.take<int64_t>(N);
-  c->blame_list = w.take<uint32_t>(2ull * n_ranks);
-  c->blame_tiles = w.take<uint32_t>(n_ranks / SEL_TILE + 3);
-  c->blame_order = w.take<uint32_t>(n_ranks);
   c->group_long = w.take<uint32_t>(N / GROUP_LONG_MIN + 2);
   c->group_first = w.take<uint32_t>(N + 1);
   c->alert_list = w.take<uint32_t>(NT);
   c->alert_ncand = w.take<uint32_t>(N + 2);
+  if (w.off - scratch_begin < B * 48) (void)w.take<uint8_t>(B * 48 - (w.off - scratch_begin));
   c->gstate = w.take<GroupState>((uint64_t)n_comms * GROUP_SLOTS);
   c->chain_first = w.take<uint32_t>((uint64_t)n_comms + 2);
   // the counters and the blame table are cleared together at the start of every analysis
   c->counters = w.take<uint64_t>(CNT_COUNT);
   c->blame = w.take<int64_t>((uint64_t)CCLD_BLM_NCOL * n_ranks);
-  c->stage = w.take<uint8_t>(B * 48);
   // dense placement: counter ranges, layout, fine-bucket fill counts and the partitioned rows (room for an
   // eighth more cells than records, and one partly filled fine bucket per communicator)
   c->fine_cap = 0;
@@ -465,7 +469,7 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
       bits |= m.status; max_seq = std::max(max_seq, m.max_seq); min_seq = std::min(min_seq, ~m.max_inv_seq);
     }
   }
-  if (bits) return o->status = data_status(bits);
+  if (bits) { c->inc_ok = false; return o->status = data_status(bits); }     // the kept order does not survive a bad batch
   o->n_records = n;
   {
     const size_t blame_bytes = sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)n_ranks;
@@ -734,12 +738,18 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
 ccld_status ccld_analyze_window(ccld_ctx* c, int64_t now_ns, ccld_window_result* o) {
   if (!c || !o) return CCLD_E_NULL;
   bool fallback = false;
+  ccld_status s = CCLD_OK;
   // a window of one batch is first tried by dense placement; one that does not fill a dense grid is sorted
-  if (c->dense_capable && c->batch_n.size() == 1 && c->count > 0) {
-    const ccld_status s = analyze_window_once(c, now_ns, o, true, &fallback);
-    if (!fallback) return s;
+  if (c->dense_capable && c->batch_n.size() == 1 && c->count > 0) s = analyze_window_once(c, now_ns, o, true, &fallback);
+  else fallback = true;
+  if (fallback) s = analyze_window_once(c, now_ns, o, false, &fallback);
+  if (s < 0) {       // an error return may have left work queued and timed spans open
+    (void)hipStreamSynchronize(c->stream);
+    (void)hipGetLastError();
+    c->prof.abandon();
+    c->inc_ok = false;
   }
-  return analyze_window_once(c, now_ns, o, false, &fallback);
+  return s;
 }
 
 ccld_status ccld_rank_blame(ccld_ctx* c, int64_t* blame, uint32_t* order) {

@@ -69,6 +69,8 @@ struct Profiler {
     }
     spans.clear(); used = 0;
   }
+  // after an error return: the recorded spans are dropped unread
+  void abandon() { spans.clear(); used = 0; open = false; }
   void destroy() { for (auto& e : pool) (void)hipEventDestroy(e); pool.clear(); on = false; }
 };
 

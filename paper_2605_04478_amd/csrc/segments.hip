@@ -9,10 +9,6 @@
 #include "dense.h"
 #include "device_utils.h"
 
-#ifndef CCLD_USE_DPP
-#define CCLD_USE_DPP 1
-#endif
-
 namespace ccld {
 
 constexpr i64 T_INFLIGHT = INT64_MAX;
@@ -62,7 +58,6 @@ __device__ __forceinline__ void seg_put_empty_stats(const SegArgs& a, u32 srow) 
 // value held by lane (lane ^ M)
 template <int M>
 __device__ __forceinline__ u32 xor_lane_u32(u32 v) {
-#if CCLD_USE_DPP
   const int s = (int)v;
   // every lane of these patterns reads a valid lane, so no previous value has to be kept: the plain
   // DPP move needs no copy of the destination first
@@ -77,8 +72,7 @@ __device__ __forceinline__ u32 xor_lane_u32(u32 v) {
     t = __builtin_amdgcn_update_dpp(t, s, 0x114, 0xF, 0xA, false);        // banks 1,3 read lane - 4 (row_shr:4)
     return (u32)t;
   } else
-#endif
-    return __shfl_xor(v, M, CCLD_WAVE);
+    return __shfl_xor(v, M, CCLD_WAVE);       // masks that cross a row of 16 lanes
 }
 template <int M>
 __device__ __forceinline__ i64 xor_lane_i64(i64 v) {

@@ -142,3 +142,18 @@ def test_large_grids_take_the_two_step_placement_with_the_same_results_and_statu
     for name, (c, want) in cases.items():
         g, o = run_both(ht.topo, c, 60, 10, what=name)
         assert g.status == want, (name, g.status)
+
+
+def test_tree_of_16384_members_parity():
+    """A binary tree over 16,384 ranks (heap order: contiguous layers): a clean stall, and one with two ranks of
+    one layer behind their peers by different amounts (only the one furthest behind is a root)."""
+    n = 16384
+    parent = [-1] + [(i - 1) // 2 for i in range(1, n)]
+    topo = tg.make_topology(n, [list(range(n))], algo=[tg.ALGO_TREE], tree_parent=[parent])
+    depth = np.floor(np.log2(np.arange(n) + 1)).astype(int)
+    ok = lambda s, c, q, ch: (3, 40 - 2 * int(depth[q]) + ch, 10 + int(depth[q]))
+    run_both(topo, snap_rows(topo, 6, 2, ok), 6, 2, what="tree16k-ok", stall_snapshots=3)
+    behind = {9000: 7, 12000: 3}
+    bad = lambda s, c, q, ch: (3, 40 - 2 * int(depth[q]) + ch - (behind.get(q, 0) if ch == 0 else 0), 10 + int(depth[q]))
+    g, _ = run_both(topo, snap_rows(topo, 6, 2, bad), 6, 2, what="tree16k-bad", stall_snapshots=3)
+    assert list(g.root["rank"]) == [9000]

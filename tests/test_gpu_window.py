@@ -147,7 +147,7 @@ def test_random_partial_rounds_with_ties(R, n_seq):
 
 
 @pytest.mark.parametrize("size,rounds", [(65, 6), (128, 6), (257, 9), (512, 4), (513, 4), (1500, 5), (2048, 3),
-                                         (2049, 3), (3000, 3)])
+                                         (2049, 3), (3000, 3), (16384, 3)])
 def test_large_communicators_cross_tiles(size, rounds):
     """Collectives at both edges of every size class: one wavefront in LDS (65-512), one workgroup
     in LDS (513-2048), counting selection (beyond), spanning tile boundaries."""
