@@ -549,7 +549,7 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
   }
   DenseArgs da;
   std::memset(&da, 0, sizeof(da));
-  uint32_t dense_n_seg = 0;
+  uint32_t dense_n_seg = 0, dense_n_fine = 0;
   if (dense) {
     // the grid's layout from the batch's counter ranges; its size comes back while the partition runs
     da.win_key = c->win_key; da.win_row = c->win_row; da.head = (uint32_t)c->head; da.cap = (uint32_t)cap; da.n = n;
@@ -576,6 +576,7 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
       return CCLD_OK;
     }
     dense_n_seg = h_hdr[DH_N_SEG];
+    dense_n_fine = h_hdr[DH_N_FINE];
     sorted = 0;
     c->sort_passes = 0;
   } else {
@@ -608,7 +609,7 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
     // every collective's row of the table is fixed by the layout; a duplicate key or a round without any
     // record shows in the status word at the end (the group stage leaves the detection state alone then)
     c->prof.split(CCLD_PROF_DENSE_PARTITION, CCLD_PROF_SEGMENTS);
-    launch_dense_stats(st, sa, da, c->sb.key[sorted], c->sb.idx[sorted], c->blame, n_ranks);
+    launch_dense_stats(st, sa, da, dense_n_fine, c->sb.key[sorted], c->sb.idx[sorted], c->blame, n_ranks);
     c->prof.split(CCLD_PROF_SEGMENTS, CCLD_PROF_FLAGS);
     o->n_seg = dense_n_seg;
   } else {

@@ -68,8 +68,9 @@ void launch_dense_layout(hipStream_t st, const DenseArgs& d);
 void launch_dense_partition(hipStream_t st, const DenseArgs& d);
 void launch_dense_desc(hipStream_t st, const DenseArgs& d);      // after the scan of fill
 // statistics of every collective from the partitioned rows (segments.hip); also writes the sorted keys
-// and row indices that the flag, blame, group and alert stages read
-void launch_dense_stats(hipStream_t st, const SegArgs& a, const DenseArgs& d, uint64_t* skey, uint32_t* sidx,
-                        int64_t* blame, uint32_t n_ranks);
+// and row indices that the flag, blame, group and alert stages read; n_fine: the fine buckets of the layout
+// (one workgroup each)
+void launch_dense_stats(hipStream_t st, const SegArgs& a, const DenseArgs& d, uint32_t n_fine, uint64_t* skey,
+                        uint32_t* sidx, int64_t* blame, uint32_t n_ranks);
 
 }  // namespace ccld

@@ -918,7 +918,7 @@ __global__ __launch_bounds__(256) void k_seg_group_listed(SegArgs a) {
 // 64 / G at a time exactly as k_seg_wave does.  The kernel also writes the records' squeezed keys and row
 // indices in (communicator, counter, rank) order, which the flag, blame, group and alert stages read, and
 // adds the records per rank to the blame table.
-constexpr int DENSE_THREADS = 256;
+constexpr int DENSE_THREADS = 512;
 
 template <int G>
 __device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, const uint4* s_cell, const u32* s_pres,
@@ -970,11 +970,12 @@ __device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, const uint4*
   return mine;
 }
 
-// Two workgroups of four wavefronts per compute unit (their LDS allows no more): while one of them waits
-// for its rows or at a barrier the other one computes.  Measured at the 4,096-rank trace: 512 threads with a
-// 128-register budget spill (3.3 ms), one workgroup of 512 or 768 threads per compute unit 2.4 - 2.6 ms, this
-// shape 2.2 ms; loading the next bucket's rows into registers one bucket ahead changed nothing.
-__global__ __launch_bounds__(DENSE_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// One workgroup per fine bucket, two workgroups of eight wavefronts per compute unit (their LDS allows no more):
+// while one of them waits for its rows or at a barrier the other one computes.  Measured at the 4,096-rank
+// trace: a grid-stride loop over the buckets makes the compiler keep the loop's invariants in some 230
+// registers (two wavefronts per SIMD, 2.2 ms; capped at 128 registers it spills, 3.3 ms); one bucket per
+// workgroup needs 97 registers, and 512 threads take 1.7 ms (256: 2.0, 384: 2.7, 640: 2.3, 1,024: 2.2 ms).
+__global__ __launch_bounds__(DENSE_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
                                                                u32* __restrict__ sidx, i64* __restrict__ blame,
                                                                u32 n_ranks) {
@@ -986,7 +987,8 @@ void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
   __shared__ u32 s_wave[DENSE_THREADS / CCLD_WAVE];
   if (d.hdr[DH_FEASIBLE] == 0) return;
   const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE;
-  const u32 n_fine = d.hdr[DH_N_FINE];
+  const u32 f = blockIdx.x;
+  if (f >= d.hdr[DH_N_FINE]) return;
   const uint4* __restrict__ rows4 = reinterpret_cast<const uint4*>(d.rows);
   unsigned long long* nrec = (unsigned long long*)(blame + (u64)CCLD_BLM_N_RECORDS * n_ranks);
   typedef u32 u32x4 __attribute__((ext_vector_type(4)));
@@ -1003,13 +1005,8 @@ void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
     }
   };
   auto clamp = [](u32 c) { return c < DENSE_STRIDE ? c : DENSE_STRIDE; };
-  u32 f = blockIdx.x;
-  if (f >= n_fine) return;
-  // the descriptor of the next bucket is read one bucket ahead
-  FineDesc D = d.desc[f], Dn = D;
-  u32 fn = f + gridDim.x;
-  if (fn < n_fine) Dn = d.desc[fn];
-  while (true) {
+  const FineDesc D = d.desc[f];
+  {
     const u32 c = D.comm, size = D.size, K = D.K, rec0 = D.rec0, cnt = clamp(D.cnt);
     const u32 row0 = f * DENSE_STRIDE;
     u32* s_pre = s_aux;
@@ -1031,9 +1028,6 @@ void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
       s_cell[2 * cell] = make_uint4(h0[u].x, h0[u].y, h0[u].z, h0[u].w);
       s_cell[2 * cell + 1] = make_uint4(h1[u].x, h1[u].y, (h1[u].z & 15u) | (i << 4), h1[u].w);
     }
-    const bool more = fn < n_fine;
-    FineDesc Dnn = Dn;
-    if (more && fn + gridDim.x < n_fine) Dnn = d.desc[fn + gridDim.x];
     __syncthreads();
     // 2. records per collective, their exclusive scan; a round without any record is a hole in the grid
     for (u32 k = tid; k < K; k += DENSE_THREADS) {
@@ -1125,10 +1119,6 @@ void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
         if (v) atomicAdd(&nrec[ms[sl]], (unsigned long long)v);
       }
     }
-    if (!more) break;
-    f = fn; fn += gridDim.x;
-    D = Dn; Dn = Dnn;
-    __syncthreads();       // the LDS cells are reused by the next bucket
   }
 }
 
@@ -1148,10 +1138,10 @@ static void launch_seg_listed(hipStream_t st, const SegArgs& a, bool with_short)
   if (m > (uint32_t)SEG_MULTI_MAX) hipLaunchKernelGGL(k_seg_group_listed, dim3(256), dim3(256), 0, st, a);
 }
 
-void launch_dense_stats(hipStream_t st, const SegArgs& a, const DenseArgs& d, uint64_t* skey, uint32_t* sidx,
-                        int64_t* blame, uint32_t n_ranks) {
-  if (a.n == 0) return;
-  hipLaunchKernelGGL(k_dense_stats, dim3(4096), dim3(DENSE_THREADS), 0, st, a, d, skey, sidx, blame, n_ranks);
+void launch_dense_stats(hipStream_t st, const SegArgs& a, const DenseArgs& d, uint32_t n_fine, uint64_t* skey,
+                        uint32_t* sidx, int64_t* blame, uint32_t n_ranks) {
+  if (a.n == 0 || n_fine == 0) return;
+  hipLaunchKernelGGL(k_dense_stats, dim3(n_fine), dim3(DENSE_THREADS), 0, st, a, d, skey, sidx, blame, n_ranks);
   launch_seg_listed(st, a, true);
 }
 
