@@ -87,14 +87,15 @@ def roofline(kernel, alg_bytes_per_launch, avg_ms, launches, traffic=None, **ext
 
 def traffic_from_counters(fetch_dir: str, write_dir: str) -> int:
     """Reads the counter CSVs of the two runs
-         rocprofv3 --pmc FETCH_SIZE --output-format csv -d <fetch_dir> -o run -- python3 bench.py --steps 1 --warmup 0 --no-cpu --no-time-major --calibrate-copy
-         rocprofv3 --pmc WRITE_SIZE --output-format csv -d <write_dir> -o run -- python3 bench.py --steps 1 --warmup 0 --no-cpu --no-time-major --calibrate-copy
+         rocprofv3 --pmc FETCH_SIZE --output-format csv -d <fetch_dir> -o run -- python3 bench.py --steps 1 --warmup 0 --no-cpu --no-time-major --no-dense --calibrate-copy
+         rocprofv3 --pmc WRITE_SIZE --output-format csv -d <write_dir> -o run -- python3 bench.py --steps 1 --warmup 0 --no-cpu --no-time-major --no-dense --calibrate-copy
     and writes profiles/window_config3_traffic.json: per kernel the bytes per launch (counter value in KiB x 1024 x scale),
     averaged over the launches of the kernel's largest grid; scale = what the 1 GiB -> 1 GiB calibration copy
     (__amd_rocclr_copyBuffer) should read or write over what the counter shows for it."""
     import csv
     import glob
     import re
+    STEPS_IN_RUN = 2          # --steps 1 --warmup 0: the timed step and the step of the per-class table
     per = {}
     scale = {}
     for d, counter in ((fetch_dir, "FETCH_SIZE"), (write_dir, "WRITE_SIZE")):
@@ -116,7 +117,7 @@ def traffic_from_counters(fetch_dir: str, write_dir: str) -> int:
         g = max(x[0] for x in c.get("FETCH_SIZE", [(0, 0)]) + c.get("WRITE_SIZE", [(0, 0)]))
         f = [v for gg, v in c.get("FETCH_SIZE", []) if gg == g]
         w = [v for gg, v in c.get("WRITE_SIZE", []) if gg == g]
-        kernels[k] = {"workgroups": g, "launches": max(len(f), len(w)),
+        kernels[k] = {"workgroups": g, "launches": max(len(f), len(w)) // STEPS_IN_RUN,      # per step
                       "fetch_bytes": int(sum(f) / max(len(f), 1) * 1024 * scale["FETCH_SIZE"]),
                       "write_bytes": int(sum(w) / max(len(w), 1) * 1024 * scale["WRITE_SIZE"])}
     rec = {"csrc_sha256": kernel_sources_digest(), "workload": "config 3, 81,920,000 records, shuffled, one step",
@@ -140,6 +141,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-time-major", action="store_true",
                     help="skip the secondary figure on the generator's record order (keeps a profile to the timed steps)")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="skip the secondary figure with the other placement (ccld_params.placement)")
     ap.add_argument("--cpu-cycles", type=int, default=1000,
                     help="cycles of the trace given to the CPU oracle (in a seeded random order, as the timed steps)")
     ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"), default=None,
@@ -269,6 +272,28 @@ def main() -> int:
             if timed:
                 time_major_ms = (time.perf_counter() - t_t) / 2 * 1e3
         assert r3.status == "OK" and int(r3.n_flag) == int(res.n_flag)
+    other_ms = None
+    if not args.no_dense:
+        # the same steps with the other placement (its own context and workspace)
+        other = "dense" if args.placement == "sort" else "sort"
+        an2 = ccld.Analyzer(tr.topo, max_window_records=n, device="cuda:0",
+                            placement=ccld.PLACEMENT_DENSE if other == "dense" else ccld.PLACEMENT_SORT)
+        for timed in (False, True):
+            torch.cuda.synchronize()
+            t_t = time.perf_counter()
+            for i in range(3):
+                w = dict(cols)
+                w["seq"] = seq_windows[i % n_windows]
+                an2.reset_window()
+                an2.ingest(w)
+                r4 = an2.analyze_window(now, buffers=buffers)
+                an2.rank_blame(to_host=False, buffers=blame_buffers)
+            torch.cuda.synchronize()
+            if timed:
+                other_ms = {"placement": other, "ms_per_step": (time.perf_counter() - t_t) / 3 * 1e3, "path_taken": int(r4.path)}
+        assert r4.status == "OK" and int(r4.n_flag) == int(res.n_flag) and int(r4.n_seg) == int(res.n_seg)
+        an2.close()
+        del an2
     pcie = None
     if args.host_batch:
         # the same batch handed over as host arrays (pinned): the library stages it over PCIe first
@@ -389,6 +414,7 @@ def main() -> int:
                    "records": n, "collectives": int(res.n_seg), "flags": int(res.n_flag),
                    "groups": int(res.n_group), "placement": "dense" if dense else "sort",
                    "pcie_inclusive_records_per_s": pcie, "time_major_order_ms_per_step": time_major_ms,
+                   "other_placement": other_ms,
                    "sort_passes": passes, "sort_key_bits": key_bits, "sort_packed_words": bool(packed)},
         "roofline": roofline(kname, alg[dominant] / launches_per_step, d_avg_ms, d_cnt, traffic,
                              layout_bytes_per_launch=layout[dominant] / launches_per_step,
