@@ -258,6 +258,14 @@ def main() -> int:
     prof, _ = an.profile_read()
     an.profile_enable(False)
     assert res is not None and res.status == "OK", res
+    # root-cause / secondary separation of the late entries of the last analysis (not part of the step)
+    torch.cuda.synchronize()
+    t_c = time.perf_counter()
+    for _ in range(3):
+        st_c, chain, _ = an.flag_chains(res)
+    torch.cuda.synchronize()
+    chains_ms = (time.perf_counter() - t_c) / 3 * 1e3
+    chains_info = {"ms": chains_ms, "with_parent": int((chain["parent"] >= 0).sum()), "max_depth": int(chain["depth"].max())}
     time_major_ms = None
     if cols_time_major is not None and not args.no_time_major:
         for timed in (False, True):
@@ -414,7 +422,7 @@ def main() -> int:
                    "records": n, "collectives": int(res.n_seg), "flags": int(res.n_flag),
                    "groups": int(res.n_group), "placement": "dense" if dense else "sort",
                    "pcie_inclusive_records_per_s": pcie, "time_major_order_ms_per_step": time_major_ms,
-                   "other_placement": other_ms,
+                   "other_placement": other_ms, "flag_chains": chains_info,
                    "sort_passes": passes, "sort_key_bits": key_bits, "sort_packed_words": bool(packed)},
         "roofline": roofline(kname, alg[dominant] / launches_per_step, d_avg_ms, d_cnt, traffic,
                              layout_bytes_per_launch=layout[dominant] / launches_per_step,

@@ -4,6 +4,7 @@ import pytest
 
 from oracle import ccld_oracle as orc
 from paper_2605_04478_amd import tracegen as tg
+from tests.chain_check import chains_by_definition
 from tests.test_gpu_window import compare
 
 pytestmark = pytest.mark.gpu
@@ -23,6 +24,19 @@ def _run(tr, seed, placement=0):
     res = an.analyze_window(now, n_records=tr.n, seg_cap=tr.n // 4 + 1024, flag_cap=tr.n // 8 + 1024)
     blame, order = an.rank_blame()
     return an, res, blame, order, now
+
+
+def _check_chains(an, res, tr, ref, what):
+    st, chain, per_rank = an.flag_chains(res)
+    assert st == "OK"
+    done = tr.cols["t_exit"] != tg.INFLIGHT
+    assert (tr.cols["t_exit"][done] > tr.cols["t_enter"][done]).all()
+    c2, p2 = chains_by_definition(tr.cols, ref.flag, tr.topo.n_ranks)
+    for k in c2:
+        assert np.array_equal(chain[k], c2[k]), (what, k, np.nonzero(chain[k] != c2[k])[0][:5])
+    for k in p2:
+        assert np.array_equal(per_rank[k], p2[k]), (what, k)
+    return chain
 
 
 def test_config2_full_size():
@@ -52,6 +66,8 @@ def test_config3_full_size_82m_records():
     nic = sorted(x for g in spec.slow_groups for x in g.ranks)
     assert set(order[:8].tolist()) == set(slow)                     # the 8 slow ranks lead the blame
     assert set(np.nonzero(blame["n_late_exit"] >= 20)[0].tolist()) == set(nic)
+    chain = _check_chains(an, res, tr, ref, "config3-full chains")
+    print(f"config 3: {res.n_flag} flags, {(chain['parent'] >= 0).sum()} with a parent, depth up to {chain['depth'].max()}", flush=True)
     an.close()
     del an, res
     # the same trace by dense placement (no sort): the same tables

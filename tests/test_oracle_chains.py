@@ -6,6 +6,7 @@ import numpy as np
 
 from oracle import ccld_oracle as orc
 from paper_2605_04478_amd import tracegen as tg
+from tests.chain_check import chains_by_definition
 from tests.helpers import T0, toy_cols
 
 MS = 1_000_000
@@ -235,3 +236,19 @@ def test_a_late_exit_after_a_late_round_still_has_no_parent():
     assert len(i) == 1 and r.flag["kind"][i[0]] == orc.FLAG_LATE_EXIT
     assert chain["parent"][i[0]] == -1 and chain["depth"][i[0]] == 0 and chain["root"][i[0]] == i[0]
     assert per_rank["root_entries"][2] == 0 and per_rank["secondary_entries"][2] == 0
+
+
+def test_chains_by_definition_agrees_with_the_oracle_where_both_run():
+    """The array form above against the oracle's loops on a propagating trace of 160,000 records."""
+    spec = tg.config2(n_cycles=20)
+    spec.same_size_per_kind = True
+    tr = tg.propagate(tg.generate(spec), gap_ns=2_000_000).shuffled(5)
+    o = orc.Oracle(tr.topo)
+    ref = o.analyze_window(tr.cols, int(tr.cols["t_exit"].max()) + 1)
+    chain, per_rank = o.flag_chains(tr.cols, ref)
+    c2, p2 = chains_by_definition(tr.cols, ref.flag, tr.topo.n_ranks)
+    assert (chain["parent"] >= 0).sum() > 300
+    for k in chain:
+        assert np.array_equal(chain[k], c2[k]), k
+    for k in per_rank:
+        assert np.array_equal(per_rank[k], p2[k]), k
