@@ -3,8 +3,8 @@
 // row operations wherever the lane pattern allows, which yields minimum, exact lower median
 // (order statistic floor((n-1)/2)), maximum, and then the median absolute deviation.  Collectives
 // of 65 to 512 records take a wavefront each with 2, 4 or 8 values per lane in registers, those of
-// up to 2,048 records a workgroup each with a bitonic sort in LDS, and longer ones the counting
-// selection of k_seg_big.
+// up to 16,384 records a workgroup each with a bitonic sort in LDS (k_seg_team, k_seg_large), and longer ones
+// the counting selection of k_seg_big.
 #include "window_kernels.h"
 #include "dense.h"
 #include "device_utils.h"
@@ -14,7 +14,8 @@ namespace ccld {
 constexpr i64 T_INFLIGHT = INT64_MAX;
 constexpr int SEG_WAVE_MAX = 64;     // longest collective handled inside one wavefront's registers
 constexpr int SEG_MULTI_MAX = 512;   // longest collective one wavefront sorts in registers (eight values per lane)
-constexpr int SEG_TEAM_MAX = 2048;   // longest collective a workgroup sorts in LDS
+constexpr int SEG_TEAM_MAX = 2048;   // longest collective a workgroup of 256 threads sorts in LDS (three arrays)
+constexpr int SEG_LARGE_MAX = 16384; // longest collective a workgroup of 1,024 threads sorts in LDS (one array of 128 KB)
 
 __device__ __forceinline__ u64 atomic_add_u64(u64* p, u64 v) {
   return atomicAdd((unsigned long long*)p, (unsigned long long)v);
@@ -617,7 +618,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_multi(SegArgs a) {
 }
 
 // ---- collectives of 65 to SEG_TEAM_MAX records -------------------------------------------------
-// length of every listed collective, capped at SEG_TEAM_MAX + 1: one wavefront per entry walks the
+// length of every listed collective, capped at SEG_LARGE_MAX + 1: one wavefront per entry walks the
 // sorted keys from the collective's first record until the (communicator, counter) prefix changes
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_lengths(SegArgs a) {
   const u32 nbig = (u32)a.counters[CNT_NBIG];
@@ -626,13 +627,13 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_lengths(SegArgs a) {
   for (u32 ent = blockIdx.x * nw + threadIdx.x / CCLD_WAVE; ent < nbig; ent += gridDim.x * nw) {
     const u32 a0 = a.big_list[3 * ent + 1];
     const u64 pref = a.key[a0] >> mb;
-    u32 len = SEG_TEAM_MAX + 1;
-    for (u32 o = 1; o <= (u32)SEG_TEAM_MAX + 1; o += CCLD_WAVE) {
+    u32 len = SEG_LARGE_MAX + 1;
+    for (u32 o = 1; o <= (u32)SEG_LARGE_MAX + 1; o += CCLD_WAVE) {
       const u64 j = (u64)a0 + o + lane;
       const u64 m = ballot64(j >= a.n || (a.key[j] >> mb) != pref);
       if (m) { len = o + (u32)__builtin_ctzll(m); break; }
     }
-    if (lane == 0) a.big_list[3 * ent + 2] = len < (u32)SEG_TEAM_MAX + 1 ? len : (u32)SEG_TEAM_MAX + 1;
+    if (lane == 0) a.big_list[3 * ent + 2] = len < (u32)SEG_LARGE_MAX + 1 ? len : (u32)SEG_LARGE_MAX + 1;
   }
 }
 
@@ -644,8 +645,9 @@ struct TeamAcc {
 
 // one compare-exchange step of the network over v[0, P): partner of i is i ^ M, the element whose
 // bit HB (the top bit of M) is clear keeps the smaller value
+template <u32 TT = SEG_THREADS>
 __device__ __forceinline__ void team_cmpx(i64* v, u32 P, u32 M, u32 HB, u32 t) {
-  for (u32 p = t; p < P / 2; p += SEG_THREADS) {
+  for (u32 p = t; p < P / 2; p += TT) {
     const u32 lo = p & (HB - 1), ia = ((p - lo) << 1) | lo, ib = ia ^ M;
     const i64 va = v[ia], vb = v[ib];
     if (vb < va) { v[ia] = vb; v[ib] = va; }
@@ -653,10 +655,11 @@ __device__ __forceinline__ void team_cmpx(i64* v, u32 P, u32 M, u32 HB, u32 t) {
   __syncthreads();
 }
 // ascending bitonic sort of v[0, P), P a power of two (same merges as sort_groups, in LDS)
+template <u32 TT = SEG_THREADS>
 __device__ __forceinline__ void team_sort(i64* v, u32 P, u32 t) {
   for (u32 k = 2; k <= P; k <<= 1) {
-    team_cmpx(v, P, k - 1, k >> 1, t);
-    for (u32 j = k >> 2; j; j >>= 1) team_cmpx(v, P, j, j, t);
+    team_cmpx<TT>(v, P, k - 1, k >> 1, t);
+    for (u32 j = k >> 2; j; j >>= 1) team_cmpx<TT>(v, P, j, j, t);
   }
 }
 
@@ -781,7 +784,130 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_team(SegArgs a) {
   }
 }
 
-// Collectives longer than SEG_TEAM_MAX records: one workgroup per collective, values staged in
+// One workgroup of 1,024 threads per collective of SEG_TEAM_MAX + 1 to SEG_LARGE_MAX records (a world communicator
+// of thousands of ranks): the times are staged in global scratch, and one LDS array of 128 KB is filled and sorted
+// four times (arrival, completion, and their absolute deviations from the medians).
+constexpr u32 LARGE_THREADS = 1024;
+__global__ __launch_bounds__(LARGE_THREADS) void k_seg_large(SegArgs a) {
+  extern __shared__ i64 s_large[];          // [SEG_LARGE_MAX]
+  __shared__ TeamAcc acc;
+  i64* V = s_large;
+  const u32 t = threadIdx.x;
+  const int mb = a.sf.mb;
+  const u64 mmask = ((u64)1 << mb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
+  i64* big_e = a.big_ex;
+  i64* big_x = a.big_ex + a.cap_n;
+  const u32 nbig = (u32)a.counters[CNT_NBIG];
+  for (u32 ent = blockIdx.x; ent < nbig; ent += gridDim.x) {
+    const u32 nn = a.big_list[3 * ent + 2];
+    if (nn <= (u32)SEG_TEAM_MAX || nn > (u32)SEG_LARGE_MAX) continue;
+    const u32 srow = a.big_list[3 * ent], a0 = a.big_list[3 * ent + 1];
+    const u64 k0 = a.key[a0];
+    const Row h = load_row(a, a0);
+    if (t == 0) {
+      acc.imin = (unsigned long long)T_INFLIGHT; acc.dmin = INT64_MAX; acc.dmax = INT64_MIN;
+      acc.ninfl = 0; acc.incons = 0; acc.rmin = 0xFFFFFFFFu; acc.rmax = 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    {
+      u32 ni = 0, rmin = 0xFFFFFFFFu, rmax = 0xFFFFFFFFu;
+      bool inc = false;
+      i64 imin = T_INFLIGHT, dmin = INT64_MAX, dmax = INT64_MIN;
+      for (u32 i = t; i < nn; i += LARGE_THREADS) {
+        const u32 j = a0 + i;
+        const Row rw = load_row(a, j);
+        big_e[j] = rw.t_enter; big_x[j] = rw.t_exit;
+        inc |= (rw.op != h.op || rw.bytes != h.bytes);
+        if (rw.t_exit == T_INFLIGHT) {
+          ++ni; imin = rw.t_enter < imin ? rw.t_enter : imin;
+        } else {
+          const i64 d = rw.t_exit - rw.t_enter;
+          const u32 rk = (u32)(a.key[j] & mmask);
+          if (d < dmin || (d == dmin && rk < rmin)) { dmin = d; rmin = rk; }
+          if (d > dmax || (d == dmax && rk < rmax)) { dmax = d; rmax = rk; }
+        }
+      }
+      if (ni) { atomicAdd(&acc.ninfl, ni); atomicMin(&acc.imin, (unsigned long long)imin); }
+      if (inc) atomicOr(&acc.incons, 1u);
+      if (rmin != 0xFFFFFFFFu) { atomicMin(&acc.dmin, (long long)dmin); atomicMax(&acc.dmax, (long long)dmax); }
+      __threadfence_block();
+      __syncthreads();
+      if (rmin != 0xFFFFFFFFu && dmin == (i64)acc.dmin) atomicMin(&acc.rmin, rmin);
+      if (rmax != 0xFFFFFFFFu && dmax == (i64)acc.dmax) atomicMin(&acc.rmax, rmax);
+    }
+    const u32 ninfl = acc.ninfl, nd = nn - ninfl;
+    const u32 km = nd ? (nd - 1) / 2 : 0, kl = nd ? nd - 1 : 0;
+    u32 P = 2;
+    while (P < nn) P <<= 1;
+    const i64* E = big_e + a0;
+    const i64* X = big_x + a0;
+    for (u32 i = t; i < P; i += LARGE_THREADS) V[i] = (i < nn && X[i] != T_INFLIGHT) ? E[i] : T_INFLIGHT;
+    __syncthreads();
+    team_sort<LARGE_THREADS>(V, P, t);
+    const i64 min_e = V[0], med_e = V[km], max_e = V[kl];
+    __syncthreads();
+    for (u32 i = t; i < P; i += LARGE_THREADS) V[i] = i < nn ? X[i] : T_INFLIGHT;
+    __syncthreads();
+    team_sort<LARGE_THREADS>(V, P, t);
+    const i64 min_x = V[0], med_x = V[km], max_x = V[kl];
+    __syncthreads();
+    for (u32 i = t; i < P; i += LARGE_THREADS) V[i] = (i < nn && X[i] != T_INFLIGHT) ? absdiff(E[i], med_e) : T_INFLIGHT;
+    __syncthreads();
+    team_sort<LARGE_THREADS>(V, P, t);
+    const i64 mad_e = V[km];
+    __syncthreads();
+    for (u32 i = t; i < P; i += LARGE_THREADS) V[i] = (i < nn && X[i] != T_INFLIGHT) ? absdiff(X[i], med_x) : T_INFLIGHT;
+    __syncthreads();
+    team_sort<LARGE_THREADS>(V, P, t);
+    const i64 mad_x = V[km];
+    const u32 comm = (u32)(k0 >> (mb + a.sf.ws));
+    const bool complete = nn == a.comm_size[comm] && ninfl == 0;
+    const bool consistent = acc.incons == 0;
+    const bool barrier = h.op == CCLD_OP_ALLREDUCE && h.bytes < (u64)a.barrier_bytes;
+    const bool usable = complete && consistent && !barrier;
+    if (t == 0) {
+      seg_put(a, CCLD_SEG_COMM, srow, (i64)comm);
+      seg_put(a, CCLD_SEG_SEQ, srow, (i64)(((k0 >> mb) & smask) + a.sf.seq_base));
+      seg_put(a, CCLD_SEG_N, srow, (i64)nn);
+      seg_put(a, CCLD_SEG_INFLIGHT, srow, (i64)ninfl);
+      seg_put(a, CCLD_SEG_STATE, srow,
+              (complete ? CCLD_SEG_COMPLETE : 0) | (consistent ? CCLD_SEG_CONSISTENT : 0) |
+                  (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+      seg_put(a, CCLD_SEG_OP, srow, (i64)h.op);
+      seg_put(a, CCLD_SEG_BYTES, srow, (i64)h.bytes);
+      seg_put(a, CCLD_SEG_INFLIGHT_ENTER_MIN, srow, (i64)acc.imin);
+      seg_put(a, CCLD_SEG_FIRST, srow, (i64)a0);
+      if (nd == 0) {
+        seg_put_empty_stats(a, srow);
+      } else {
+        seg_put(a, CCLD_SEG_ENTER_MIN, srow, min_e); seg_put(a, CCLD_SEG_ENTER_MED, srow, med_e);
+        seg_put(a, CCLD_SEG_ENTER_MAX, srow, max_e); seg_put(a, CCLD_SEG_ENTER_MAD, srow, mad_e);
+        seg_put(a, CCLD_SEG_EXIT_MIN, srow, min_x); seg_put(a, CCLD_SEG_EXIT_MED, srow, med_x);
+        seg_put(a, CCLD_SEG_EXIT_MAX, srow, max_x); seg_put(a, CCLD_SEG_EXIT_MAD, srow, mad_x);
+        seg_put(a, CCLD_SEG_DUR_MIN, srow, (i64)acc.dmin); seg_put(a, CCLD_SEG_DUR_MAX, srow, (i64)acc.dmax);
+        const u32* ms = a.members_sorted + a.member_off[comm];
+        seg_put(a, CCLD_SEG_ARGMIN_RANK, srow, (i64)ms[acc.rmin]); seg_put(a, CCLD_SEG_ARGMAX_RANK, srow, (i64)ms[acc.rmax]);
+      }
+    }
+    for (u32 i = t; i < nn; i += LARGE_THREADS) {
+      const u32 j = a0 + i;
+      i64 le = 0, lx = 0;
+      u32 f = 0;
+      if (usable) {
+        le = E[i] - med_e; lx = X[i] - med_x;
+        if (is_late(le, a.lag_floor, a.kmad_num, a.kmad_den, mad_e)) f |= CCLD_FLAG_LATE_ENTER;
+        if (is_late(lx, a.lag_floor, a.kmad_num, a.kmad_den, mad_x)) f |= CCLD_FLAG_LATE_EXIT;
+      }
+      a.rec_flag[j] = (uint8_t)f;
+      if (a.lag_e) a.lag_e[j] = le;
+      if (a.lag_x) a.lag_x[j] = lx;
+      if (f) { a.flag_lag[j] = le; a.flag_lag[a.cap_n + j] = lx; }
+    }
+    __syncthreads();     // the LDS array and the accumulator are reused by the next collective
+  }
+}
+
+// Collectives longer than SEG_LARGE_MAX records: one workgroup per collective, values staged in
 // global scratch, order statistics by counting with all reads broadcast across the workgroup.
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
   __shared__ u32 s_end, s_ninfl, s_incons;
@@ -794,7 +920,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_big(SegArgs a) {
   i64* big_x = a.big_ex + a.cap_n;
   const u32 nbig = (u32)a.counters[CNT_NBIG];
   for (u32 ent = blockIdx.x; ent < nbig; ent += gridDim.x) {
-    if (a.big_list[3 * ent + 2] <= (u32)SEG_TEAM_MAX) continue;    // a team kernel has taken it
+    if (a.big_list[3 * ent + 2] <= (u32)SEG_LARGE_MAX) continue;    // a workgroup kernel has taken it
     const u32 srow = a.big_list[3 * ent], a0 = a.big_list[3 * ent + 1];
     const u64 k0 = a.key[a0];
     const u64 pref = k0 >> mb;
@@ -1144,7 +1270,16 @@ static void launch_seg_listed(hipStream_t st, const SegArgs& a, bool with_short)
   if (m > 128) hipLaunchKernelGGL(k_seg_multi<4>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
   if (m > 256) hipLaunchKernelGGL(k_seg_multi<8>, dim3(2048), dim3(SEG_THREADS), 0, st, a);
   if (m > (uint32_t)SEG_MULTI_MAX) hipLaunchKernelGGL(k_seg_team, dim3(1024), dim3(SEG_THREADS), 0, st, a);
-  if (m > (uint32_t)SEG_TEAM_MAX) hipLaunchKernelGGL(k_seg_big, dim3(2048), dim3(SEG_THREADS), 0, st, a);
+  if (m > (uint32_t)SEG_TEAM_MAX) {
+    static bool raised = false;       // more than 64 KB of dynamic LDS has to be asked for once
+    constexpr size_t lds = sizeof(int64_t) * SEG_LARGE_MAX;
+    if (!raised) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_seg_large), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      raised = true;
+    }
+    hipLaunchKernelGGL(k_seg_large, dim3(512), dim3(LARGE_THREADS), lds, st, a);
+  }
+  if (m > (uint32_t)SEG_LARGE_MAX) hipLaunchKernelGGL(k_seg_big, dim3(2048), dim3(SEG_THREADS), 0, st, a);
   if (m > (uint32_t)SEG_MULTI_MAX) hipLaunchKernelGGL(k_seg_group_listed, dim3(256), dim3(256), 0, st, a);
 }
 

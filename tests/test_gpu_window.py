@@ -147,10 +147,11 @@ def test_random_partial_rounds_with_ties(R, n_seq):
 
 
 @pytest.mark.parametrize("size,rounds", [(65, 6), (128, 6), (257, 9), (512, 4), (513, 4), (1500, 5), (2048, 3),
-                                         (2049, 3), (3000, 3), (16384, 3)])
+                                         (2049, 3), (3000, 3), (16384, 3), (16385, 2), (20000, 2)])
 def test_large_communicators_cross_tiles(size, rounds):
-    """Collectives at both edges of every size class: one wavefront in LDS (65-512), one workgroup
-    in LDS (513-2048), counting selection (beyond), spanning tile boundaries."""
+    """Collectives at both edges of every size class: one wavefront with several values per lane (65-512), one
+    workgroup sorting in LDS (513-2,048 with 256 threads, up to 16,384 with 1,024), counting selection (beyond),
+    spanning tile boundaries."""
     rng = np.random.default_rng(size)
     topo = ring_topology(size, comms=[list(range(size)), [0, 1, 2, 3]])
     rows = []
