@@ -301,9 +301,49 @@ static void launch_scatter(hipStream_t stream, const KeySource& src, const u64* 
 
 static int host_bits(uint64_t v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
 
+// ---- sorts of at most SMALL_SORT_MAX pairs: one launch ------------------------------------------------------
+// One workgroup sorts composite words (key bits << 12 | position in the source) with a bitonic network in
+// LDS: equal keys keep their source order, as in the radix passes.  For key widths of at most 52 bits.
+constexpr u32 SMALL_SORT_MAX = 4096;
+constexpr int SMALL_SORT_BITS = 52;
+__global__ __launch_bounds__(1024) void k_small_sort(KeySource src, u32 n, int bits, u64* __restrict__ key_out,
+                                                     u32* __restrict__ idx_out) {
+  __shared__ u64 s_c[SMALL_SORT_MAX];
+  const u32 t = threadIdx.x;
+  u32 P = 2;
+  while (P < n) P <<= 1;
+  const u64 kmask = bits <= 0 ? 0ull : (((u64)1 << bits) - 1);
+  auto phys = [&](u32 j) -> u32 { u32 p = src.head + j; if (p >= src.cap) p -= src.cap; return p; };
+  for (u32 j = t; j < P; j += 1024)
+    s_c[j] = j < n ? (((squeeze_key(src, src.key[phys(j)]) & kmask) << 12) | (u64)j) : ~0ull;
+  __syncthreads();
+  for (u32 k = 2; k <= P; k <<= 1) {
+    for (u32 jj = k >> 1, first = 1; jj; jj >>= 1, first = 0) {
+      const u32 M = first ? k - 1 : jj;               // the merge's first step mirrors, the others halve the stride
+      for (u32 q = t; q < P / 2; q += 1024) {
+        const u32 lo = q & (jj - 1), ia = ((q - lo) << 1) | lo, ib = ia ^ M;
+        const u64 va = s_c[ia], vb = s_c[ib];
+        if (vb < va) { s_c[ia] = vb; s_c[ib] = va; }
+      }
+      __syncthreads();
+    }
+  }
+  for (u32 i = t; i < n; i += 1024) {
+    const u32 p = phys((u32)(s_c[i] & (SMALL_SORT_MAX - 1)));
+    key_out[i] = squeeze_key(src, src.key[p]);
+    idx_out[i] = p;
+  }
+}
+
 int radix_sort_pairs(hipStream_t stream, const KeySource& src_in, uint32_t n, const SortBuffers& buf, int bits,
                      Profiler* prof, int cls_hist, int cls_scan, int cls_scatter) {
   if (n == 0) return 0;
+  if (n <= SMALL_SORT_MAX && bits <= SMALL_SORT_BITS && src_in.key != buf.key[0]) {
+    if (prof) prof->begin(cls_scatter);
+    hipLaunchKernelGGL(k_small_sort, dim3(1), dim3(1024), 0, stream, src_in, n, bits, buf.key[0], buf.idx[0]);
+    if (prof) prof->end(cls_scatter);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+  }
   const KeySource& src = src_in;
   const u32 n_tiles = sort_tiles(n);
   const int passes = bits <= 0 ? 1 : (bits + SORT_RBITS - 1) / SORT_RBITS;
