@@ -71,6 +71,14 @@ def test_hand_packed_frame_and_carry_forward():
     assert st == "OK"
     assert rows_of(out, 0, 0) == [(0, 42, 1, 0), (1, 42, 1, 1)]                     # the later kernel wins
     assert rows_of(out, 0, 1) == [(0, 11, 1, 2), (1, 11, 3, 4)]                     # remembered
+    # two written blocks with the same operation counter on one communicator: the block further back in the frame
+    # is the later kernel
+    o3 = orc.Oracle(topo)
+    o3.frames_begin(2)
+    f3 = pack_frame([(1, 0, True, 50, [(1, 1), (1, 1)]), (6, 0, True, 50, [(2, 2), (2, 2)]), (3, 0, True, 50, [(3, 3), (3, 3)])],
+                    n_channels=2)
+    st, out3 = o3.decode_frames(np.stack([f3]), np.asarray([0]), 0)
+    assert st == "OK" and rows_of(out3, 0, 0) == [(0, 50, 2, 2), (1, 50, 2, 2)]
     # a stale frame (older operation) does not replace what is remembered
     st, out = o.decode_frames(np.stack([f0]), np.asarray([0]), 2)
     assert rows_of(out, 0, 0) == [(0, 42, 1, 0), (1, 42, 1, 1)]
@@ -98,6 +106,14 @@ def test_error_checks_leave_the_state_alone():
         assert st == want, (want, st)
     st, _ = o.decode_frames(np.stack([good, good]), np.asarray([1, 1]), 1)          # two frames of one rank
     assert st == "E_DUPLICATE_KEY"
+    # the largest count that fits 32 bits is allowed; a range error outranks two frames of one rank
+    edge = pack_frame([(0, 0, True, 5, [(2**32 - 1, 2**32 - 1), (2, 2)])], n_channels=2)
+    o2 = orc.Oracle(topo)
+    o2.frames_begin(2)
+    st, out2 = o2.decode_frames(np.stack([edge]), np.asarray([1]), 0)
+    assert st == "OK" and rows_of(out2, 1, 0)[0] == (0, 5, 2**32 - 1, 2**32 - 1)
+    nine = pack_frame([(0, 0, True, 6, [(1, 1)])], 9)
+    assert o.decode_frames(np.stack([nine, good, good]), np.asarray([0, 1, 1]), 1)[0] == "E_RANGE"
     st, out = o.decode_frames(np.zeros((0, G["frame_bytes"]), np.uint8), np.zeros(0, np.uint32), 2)
     assert st == "OK" and rows_of(out, 1, 0) == [(0, 5, 1, 1), (1, 5, 2, 2)]        # untouched by the failures
 

@@ -158,6 +158,19 @@ def test_statuses():
     assert locate(topo, bad, 3, 2).status == "E_RANGE"
     bad = {k: v.copy() for k, v in cols.items()}; bad["snap"][0] = 3
     assert locate(topo, bad, 3, 2).status == "E_RANGE"
+    # a non-member outranks a range error
+    bad = {k: v.copy() for k, v in cols.items()}; bad["channel"][0] = 2; bad["rank"][5] = 3
+    assert locate(topo, bad, 3, 2).status == "E_RANK_NOT_MEMBER"
+
+
+def test_the_operation_counter_of_a_member_is_the_largest_over_its_channels():
+    """Channels advance one after the other: a member whose first channel already shows operation 8 has entered
+    it, even though its second channel still shows 7; its peer, at 7 on both, has not."""
+    topo = ring_topology(2)
+    state = lambda s, c, q, ch: (8 if (q == 0 and ch == 0) else 7, 4, 4)
+    r = locate(topo, snap_rows(topo, 6, 2, state), 6, 2, stall_snapshots=3)
+    assert list(r.pair["seq"]) == [8, 7] and list(r.pair["entered"]) == [1, 0]
+    assert roots(r) == [(1, 0, 1)]                                    # H1: not entered
 
 
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])

@@ -336,6 +336,11 @@ def test_validation_statuses():
     assert analyze(topo, toy_cols(both[::-1]))[0].status == "E_UNKNOWN_COMM"
     empty, _ = analyze(topo, toy_cols([]))
     assert empty.status == "OK" and len(empty.seg["comm"]) == 0 and empty.blame["n_records"].sum() == 0
+    # a record before the epoch is out of range; a non-member outranks a range error, whatever the order
+    assert analyze(topo, toy_cols(ok + [(1, 0, 1, 0, 8, -1, T0)]))[0].status == "E_RANGE"
+    mixed = ok + [(1, 0, 1, 0, 8, T0 + 5, T0 + 4), (2, 0, 1, 0, 8, T0, T0 + 1)]
+    assert analyze(topo, toy_cols(mixed))[0].status == "E_RANK_NOT_MEMBER"
+    assert analyze(topo, toy_cols(mixed[::-1]))[0].status == "E_RANK_NOT_MEMBER"
 
 
 # --------------------------------------------------------------------------

@@ -191,3 +191,27 @@ def test_equal_rates_name_the_smaller_rank():
     r = rates(topo, series, 8)
     assert list(r.pair["ops_send"]) == [2, 1, 1, 1] and list(r.pair["changes_send"]) == [6, 3, 3, 2]
     assert r.comm["root_send"][0] == 0 and r.comm["root"][0] == 0
+
+
+def test_an_operation_without_any_change_is_not_an_observed_operation():
+    """Rank 0 sends in operations 5 and 7 but not in 6 (one change each, three runs): two observed operations, two
+    changes.  Counting the silent run as an operation would make it 3/2."""
+    topo = ring_topology(2)
+    series = {(0, 0, 0): [(5, 3, 0), (5, 3, 0), (6, 0, 0), (6, 0, 0), (7, 2, 0), (7, 2, 0), (8, 0, 0)],
+              (1, 0, 0): [(5, 1, 0), (5, 2, 0), (6, 1, 0), (6, 2, 0), (7, 1, 0), (7, 2, 0), (8, 0, 0)]}
+    r = rates(topo, series, 7)
+    assert list(r.pair["ops_send"]) == [2, 3] and list(r.pair["changes_send"]) == [2, 6]
+
+
+def test_the_root_is_the_member_whose_smaller_rate_is_minimal_send_or_receive():
+    """Rank 1 sends as fast as rank 0 but receives slowly: it is the RecvRate root and, its RecvRate being the
+    smallest rate of all, the communicator's root."""
+    topo = ring_topology(2)
+    fast = [1, 4, 4, 4]
+    slow = [1, 2, 3, 4]
+    series = {(0, 0, 0): [(3, s, v) for s, v in zip(fast, fast)] + [(4, 0, 0)],
+              (1, 0, 0): [(3, s, v) for s, v in zip(fast, slow)] + [(4, 0, 0)]}
+    r = rates(topo, series, 5)
+    assert list(r.pair["changes_send"]) == [2, 2] and list(r.pair["changes_recv"]) == [2, 4]
+    assert r.comm["root_send"][0] == 0 and r.comm["root_recv"][0] == 1 and r.comm["root"][0] == 1
+

@@ -1,4 +1,4 @@
-"""Every rule of the oracle is held by a pin: each entry below plants one mistake (a dropped term, a flipped
+"""Every rule of the oracle listed here is held by a pin: each entry below plants one mistake (a dropped term, a flipped
 comparison, a swapped tie rule) in a temporary copy of the oracle's C source, on the CPU, and the named pin file
 must fail against that copy.  The oracle under oracle/ is never touched."""
 import os
@@ -10,7 +10,8 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
-# (what is planted, the pin file that must notice, text in oracle/ccld_oracle.c, its replacement)
+# (what is planted, the pin file that notices it (None: some file of tests/test_oracle_*.py), text in
+# oracle/ccld_oracle.c, its replacement)
 MUTATIONS = [
     ('mad leg enter removed', 'test_oracle_chains.py',
      '(__int128)le * (__int128)P[P_KMAD_DEN] > (__int128)P[P_KMAD_NUM] * (__int128)S[SEG_ENTER_MAD])',
@@ -165,7 +166,91 @@ MUTATIONS = [
     ('chain caused by own rank', 'test_oracle_chains.py',
      'per_rank[chain[k * CHN_NCOL + CHN_ROOT_RANK] * CHR_NCOL + CHR_CAUSED] += 1;',
      'per_rank[F[FLG_RANK] * CHR_NCOL + CHR_CAUSED] += 1;'),
+    ('window: member error before unknown communicator', None,
+     '  if (bad_comm) { R->status = ORC_E_UNKNOWN_COMM; return R->status; }\n  if (bad_member) { R->status = ORC_E_RANK_NOT_MEMBER; return R->status; }',
+     '  if (bad_member) { R->status = ORC_E_RANK_NOT_MEMBER; return R->status; }\n  if (bad_comm) { R->status = ORC_E_UNKNOWN_COMM; return R->status; }'),
+    ('window: range error before member error', None,
+     '  if (bad_member) { R->status = ORC_E_RANK_NOT_MEMBER; return R->status; }\n  if (bad_range) { R->status = ORC_E_RANGE; return R->status; }',
+     '  if (bad_range) { R->status = ORC_E_RANGE; return R->status; }\n  if (bad_member) { R->status = ORC_E_RANK_NOT_MEMBER; return R->status; }'),
+    ('window: exit before enter allowed', None,
+     't_enter[i] == ORC_INFLIGHT || t_exit[i] < t_enter[i]) bad_range = 1;',
+     't_enter[i] == ORC_INFLIGHT) bad_range = 1;'),
+    ('window: op 16 allowed', None,
+     'if (op[i] >= OP_MAX || t_enter[i] < 0',
+     'if (op[i] > OP_MAX || t_enter[i] < 0'),
+    ('window: negative enter allowed', None,
+     'if (op[i] >= OP_MAX || t_enter[i] < 0 ||',
+     'if (op[i] >= OP_MAX ||'),
+    ('snapshots: range before member', None,
+     '  if (bad_member) return ORC_E_RANK_NOT_MEMBER;\n  if (bad_range) return ORC_E_RANGE;\n  cell_t *cell',
+     '  if (bad_range) return ORC_E_RANGE;\n  if (bad_member) return ORC_E_RANK_NOT_MEMBER;\n  cell_t *cell'),
+    ('snapshots: gap before duplicate', None,
+     '  if (dup) { free(cell); return ORC_E_DUPLICATE_KEY; }\n  if (gap) { free(cell); return ORC_E_SNAPSHOT_GAP; }',
+     '  if (gap) { free(cell); return ORC_E_SNAPSHOT_GAP; }\n  if (dup) { free(cell); return ORC_E_DUPLICATE_KEY; }'),
+    ('snapshots: channel == n_ch allowed', None,
+     'if (snap[i] >= n_snap || channel[i] >= n_ch) bad_range = 1;',
+     'if (snap[i] >= n_snap || channel[i] > n_ch) bad_range = 1;'),
+    ('rates: open run counted', None,
+     '        while (open > 0 && s[open - 1].seq == s[n_snap - 1].seq) --open;',
+     '        open = n_snap;'),
+    ('rates: first sample compared with the previous run', None,
+     '          uint32_t ps = 0, pr = 0;\n          int64_t cs = 0, cr = 0;',
+     '          uint32_t ps = t ? s[t - 1].sent : 0, pr = t ? s[t - 1].recv : 0;\n          int64_t cs = 0, cr = 0;'),
+    ('rates: run without change counted as operation', None,
+     '          if (cs) { Q[RATE_OPS_SEND] += 1; Q[RATE_CHG_SEND] += cs; }',
+     '          { Q[RATE_OPS_SEND] += 1; Q[RATE_CHG_SEND] += cs; }'),
+    ('rates: recv changes from sends', None,
+     '            if (s[t].recv != pr) ++cr;',
+     '            if (s[t].sent != ps) ++cr;'),
+    ('rates: root ignores recv', None,
+     '        if (H[RC_ROOT] == ORC_NO_RANK || rate_less(Q[RATE_OPS_RECV], Q[RATE_CHG_RECV], rk, bb[0], bb[1], H[RC_ROOT])) {',
+     '        if (0) {'),
+    ('rates: maximal rate', None,
+     '  if (l != r) return l < r;',
+     '  if (l != r) return l > r;'),
+    ('frames: smaller counter wins', None,
+     '        if (cnt2 > cnt || (cnt2 == cnt && b2 > b)) loses = 1;',
+     '        if (cnt2 < cnt || (cnt2 == cnt && b2 > b)) loses = 1;'),
+    ('frames: equal counters smaller block wins', None,
+     '        if (cnt2 > cnt || (cnt2 == cnt && b2 > b)) loses = 1;',
+     '        if (cnt2 > cnt || (cnt2 == cnt && b2 < b)) loses = 1;'),
+    ('frames: older frame overwrites', None,
+     '        if (cnt < L->seq) continue;                 /* what is remembered is newer */',
+     ''),
+    ('frames: unwritten blocks decoded', None,
+     '      if (!(rd_u32(B + 4) & 1u)) continue;\n      const uint32_t c = rd_u32(B);\n      const uint64_t cnt = rd_u64(B + 8);',
+     '      const uint32_t c = rd_u32(B);\n      const uint64_t cnt = rd_u64(B + 8);'),
+    ('frames: channels beyond the header keep counts', None,
+     '        L->sent = ch < nch ? (uint32_t)rd_u64(B + 16 + ch * 16) : 0;',
+     '        L->sent = (uint32_t)rd_u64(B + 16 + ch * 16);'),
+    ('frames: recv from send slot', None,
+     '        L->recv = ch < nch ? (uint32_t)rd_u64(B + 16 + ch * 16 + 8) : 0;',
+     '        L->recv = ch < nch ? (uint32_t)rd_u64(B + 16 + ch * 16) : 0;'),
+    ('frames: duplicate before range', None,
+     '  if (bad_range) return ORC_E_RANGE;\n  if (dup) return ORC_E_DUPLICATE_KEY;',
+     '  if (dup) return ORC_E_DUPLICATE_KEY;\n  if (bad_range) return ORC_E_RANGE;'),
+    ('frames: count limit off by one', None,
+     'if (rd_u64(B + 16 + ch * 16) > 0xFFFFFFFFull ||',
+     'if (rd_u64(B + 16 + ch * 16) >= 0xFFFFFFFFull ||'),
+    ('hang: seq is minimum over channels', None,
+     '        if (s[L].seq > seq) seq = s[L].seq;',
+     '        if (ch == 0 || s[L].seq < seq) seq = s[L].seq;'),
+    ('hang: entered means not behind by more than one', None,
+     '      PQ(q, PAIR_ENTERED) = ((uint64_t)PQ(q, PAIR_SEQ) == seq_max);',
+     '      PQ(q, PAIR_ENTERED) = ((uint64_t)PQ(q, PAIR_SEQ) + 1 >= seq_max);'),
+    ('hang: idle ignores recv', None,
+     '          if (PQ(r2, PAIR_SENT) != PQ(q, PAIR_SENT) || PQ(r2, PAIR_RECV) != PQ(q, PAIR_RECV)) idle_ok = 0;',
+     '          if (PQ(r2, PAIR_SENT) != PQ(q, PAIR_SENT)) idle_ok = 0;'),
+    ('hang: tree compared as ring', None,
+     '    if (T->algo[c] == 1 && T->tree_parent)\n      for (uint32_t q = 0; q < n; ++q) { int32_t par',
+     '    if (0)\n      for (uint32_t q = 0; q < n; ++q) { int32_t par'),
+    ('hang: sums over first channel only', None,
+     '        S += s[L].sent; Rv += s[L].recv;',
+     '        if (ch == 0) { S += s[L].sent; Rv += s[L].recv; }'),
 ]
+
+
+PIN_FILES = sorted(f for f in os.listdir(os.path.join(ROOT, "tests")) if f.startswith("test_oracle_") and f.endswith(".py"))
 
 
 def _sandbox(d):
@@ -195,7 +280,7 @@ def verdicts(tmp_path_factory):
         os.mkdir(d)
         _sandbox(d)
         open(os.path.join(d, "oracle", "ccld_oracle.c"), "w").write(src.replace(old, new))
-        p = _run_pins(d, [pin_file])
+        p = _run_pins(d, [pin_file] if pin_file else PIN_FILES)
         shutil.rmtree(d, ignore_errors=True)
         return ("ran", p.returncode, p.stdout[-600:], p.stderr[-300:])
 
@@ -214,5 +299,5 @@ def test_the_unchanged_copy_passes(tmp_path):
     """The sandbox itself is sound: with the oracle's own source every pin file passes there."""
     d = str(tmp_path)
     _sandbox(d)
-    p = _run_pins(d, sorted({m[1] for m in MUTATIONS}))
+    p = _run_pins(d, PIN_FILES)
     assert p.returncode == 0, (p.stdout[-800:], p.stderr[-400:])
