@@ -58,6 +58,20 @@ def test_hand_packed_frames_errors_and_carry_forward():
     an.reset_frames()
     o.frames_begin(2)
     both(an, o, np.stack([f2]), np.asarray([1]), 11, 2, what="after-reset")
+    # equal operation counters in three blocks (the block further back wins), the largest 32-bit count, and a range
+    # error that outranks two frames of one rank
+    an.reset_frames()
+    o.frames_begin(2)
+    f3 = pack_frame([(1, 0, True, 50, [(1, 1), (1, 1)]), (6, 0, True, 50, [(2, 2), (2, 2)]), (3, 0, True, 50, [(3, 3), (3, 3)])],
+                    n_channels=2)
+    edge = pack_frame([(0, 0, True, 51, [(2**32 - 1, 2**32 - 1), (2, 2)])], n_channels=2)
+    _, rows = both(an, o, np.stack([f3]), np.asarray([0]), 12, 2, what="equal counters")
+    m = (rows["rank"] == 0) & (rows["comm"] == 0)
+    assert list(rows["chunks_sent"][m]) == [2, 2]
+    both(an, o, np.stack([edge]), np.asarray([1]), 13, 2, on_device=True, what="largest count")
+    nine = pack_frame([(0, 0, True, 6, [(1, 1)])], 9)
+    st, _ = both(an, o, np.stack([nine, f2, f2]), np.asarray([0, 1, 1]), 14, 2, what="range+dup")
+    assert st == "E_RANGE"
     an.close()
 
 

@@ -86,8 +86,11 @@ def test_statuses_parity():
         b = {k: v.copy() for k, v in cols.items()}
         b[col][0] = val
         cases[name] = b
+    b = {k: v.copy() for k, v in cols.items()}
+    b["channel"][0] = 2; b["rank"][5] = 3
+    cases["member+range"] = b
     want = {"ok": "OK", "gap": "E_SNAPSHOT_GAP", "dup": "E_DUPLICATE_KEY", "comm": "E_UNKNOWN_COMM",
-            "member": "E_RANK_NOT_MEMBER", "chan": "E_RANGE", "snap": "E_RANGE"}
+            "member": "E_RANK_NOT_MEMBER", "chan": "E_RANGE", "snap": "E_RANGE", "member+range": "E_RANK_NOT_MEMBER"}
     for name, c in cases.items():
         g, o = run_both(topo, c, 3, 2, what=name)
         assert g.status == want[name]
@@ -157,3 +160,11 @@ def test_tree_of_16384_members_parity():
     bad = lambda s, c, q, ch: (3, 40 - 2 * int(depth[q]) + ch - (behind.get(q, 0) if ch == 0 else 0), 10 + int(depth[q]))
     g, _ = run_both(topo, snap_rows(topo, 6, 2, bad), 6, 2, what="tree16k-bad", stall_snapshots=3)
     assert list(g.root["rank"]) == [9000]
+
+
+def test_operation_counter_is_the_largest_over_the_channels_parity():
+    topo = ring_topology(2)
+    state = lambda s, c, q, ch: (8 if (q == 0 and ch == 0) else 7, 4, 4)
+    g, o = run_both(topo, snap_rows(topo, 6, 2, state), 6, 2, what="seq-over-channels", stall_snapshots=3)
+    assert list(g.pair["seq"]) == [8, 7] and list(g.root["rank"]) == [1]
+

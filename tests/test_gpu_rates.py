@@ -117,3 +117,17 @@ def test_communication_slow_root_follows_the_rate_pass():
         assert np.array_equal(g.group["root_s2"], w.group["root_s2"])
         assert g.group["root_s2"][0] == (3 if with_rates else NO_RANK)
     an.close()
+
+
+def test_silent_runs_and_the_receive_side_parity():
+    topo = ring_topology(2)
+    silent = {(0, 0, 0): [(5, 3, 0), (5, 3, 0), (6, 0, 0), (6, 0, 0), (7, 2, 0), (7, 2, 0), (8, 0, 0)],
+              (1, 0, 0): [(5, 1, 0), (5, 2, 0), (6, 1, 0), (6, 2, 0), (7, 1, 0), (7, 2, 0), (8, 0, 0)]}
+    g, o = run_both(topo, series_cols(silent), 7, 1, what="silent run")
+    assert list(g.pair["ops_send"]) == [2, 3] and list(g.pair["changes_send"]) == [2, 6]
+    fast, slow = [1, 4, 4, 4], [1, 2, 3, 4]
+    recv = {(0, 0, 0): [(3, s, v) for s, v in zip(fast, fast)] + [(4, 0, 0)],
+            (1, 0, 0): [(3, s, v) for s, v in zip(fast, slow)] + [(4, 0, 0)]}
+    g, o = run_both(topo, series_cols(recv), 5, 1, what="receive side")
+    assert g.comm["root_send"][0] == 0 and g.comm["root_recv"][0] == 1 and g.comm["root"][0] == 1
+

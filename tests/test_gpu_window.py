@@ -274,9 +274,13 @@ def test_validation_parity():
              "dup": ok + [(1, 0, 0, 0, 8, T0 + 5, T0 + 9)],
              "range": ok + [(1, 0, 1, 0, 8, T0 + 5, T0 + 4)],
              "op": ok + [(1, 0, 1, 16, 8, T0 + 5, T0 + 9)],
-             "both": ok + [(0, 2, 0, 0, 8, T0, T0 + 1), (2, 0, 1, 0, 8, T0, T0 + 1)]}
+             "both": ok + [(0, 2, 0, 0, 8, T0, T0 + 1), (2, 0, 1, 0, 8, T0, T0 + 1)],
+             "before-epoch": ok + [(1, 0, 1, 0, 8, -1, T0)],
+             "member+range": ok + [(1, 0, 1, 0, 8, T0 + 5, T0 + 4), (2, 0, 1, 0, 8, T0, T0 + 1)],
+             "range+member": ok + [(2, 0, 1, 0, 8, T0, T0 + 1), (1, 0, 1, 0, 8, T0 + 5, T0 + 4)]}
     want = {"unknown": "E_UNKNOWN_COMM", "member": "E_RANK_NOT_MEMBER", "dup": "E_DUPLICATE_KEY",
-            "range": "E_RANGE", "op": "E_RANGE", "both": "E_UNKNOWN_COMM"}
+            "range": "E_RANGE", "op": "E_RANGE", "both": "E_UNKNOWN_COMM", "before-epoch": "E_RANGE",
+            "member+range": "E_RANK_NOT_MEMBER", "range+member": "E_RANK_NOT_MEMBER"}
     for name, rows in cases.items():
         g, o = run_both(topo, toy_cols(rows), what=name)
         assert g.status == want[name] and g.n_seg == 0
