@@ -131,3 +131,26 @@ def test_silent_runs_and_the_receive_side_parity():
     g, o = run_both(topo, series_cols(recv), 5, 1, what="receive side")
     assert g.comm["root_send"][0] == 0 and g.comm["root_recv"][0] == 1 and g.comm["root"][0] == 1
 
+
+
+def test_location_needs_a_slow_window_and_the_rate_root_is_for_communication_only_parity():
+    from paper_2605_04478_amd import ccld
+    topo = ring_topology(2)
+    prm = dict(tbase_init_ns=1000, repeat_threshold=2)
+    an = ccld.Analyzer(topo, max_window_records=64, max_snapshot_rows=64, **prm)
+    o = orc.Oracle(topo, prm)
+    series = {(0, 0, 0): [(1, 0, 0), (1, 8, 8), (2, 0, 0)], (1, 0, 0): [(1, 2, 8), (1, 8, 8), (2, 0, 0)]}
+    assert an.progress_rates(series_cols(series), 3, 1).status == "OK"
+    o.progress_rates(series_cols(series), 3, 1)
+    want = [(1, 1, 0, 1), (1, 2, 1, 1), (0, 2, 0, 0)]                 # slow, repeats, locate, class per window
+    for s, durs in enumerate([[9000, 1000], [9000, 1000], [1200, 1100]]):
+        cols = toy_cols(rounds_with_durations([durs], seq0=s))
+        an.reset_window()
+        an.ingest(an.to_device(cols))
+        g = an.analyze_window(T0 + 10**12)
+        w = o.analyze_window(cols, T0 + 10**12)
+        for k in w.group:
+            assert np.array_equal(g.group[k], w.group[k]), (s, k)
+        assert (g.group["slow"][0], g.group["repeats"][0], g.group["locate"][0], g.group["class"][0]) == want[s]
+        assert g.group["root_s2"][0] == NO_RANK
+    an.close()

@@ -524,3 +524,29 @@ def test_dense_placement_wide_spreads_take_the_64_bit_pass():
     cols = {k: v[p] for k, v in cols.items()}
     g, o = run_both(topo, cols, now=2**62 + 2**41, what="wide", expect_path=1, tbase_init_ns=1000)
     assert g.n_flag > 100
+
+
+def test_barrier_operation_missing_member_and_warmup_origin_parity():
+    """An all-gather of three bytes is no barrier; a member without a record makes a hang alert of the first kind
+    also when other members have finished; the warm-up span of Eq. 1 starts at the first round's earliest entry."""
+    topo = ring_topology(2)
+    rows = (rounds_with_durations([[9000, 1000]], op=tg.OP_ALLREDUCE, nbytes=3, seq0=0)
+            + rounds_with_durations([[9000, 1000]], op=tg.OP_ALLGATHER, nbytes=3, seq0=1))
+    g, o = run_both(topo, toy_cols(rows), what="barrier-op", tbase_init_ns=1000)
+    assert list(g.group["op"]) == [tg.OP_ALLGATHER] and g.group["slow"][0] == 1
+    topo4 = ring_topology(4)
+    t = T0 + 1000
+    rows = [(r, 0, 6, 0, 4096, T0 + r, T0 + 100) for r in range(4)]
+    rows += [(0, 0, 7, 0, 4096, t, INFLIGHT), (1, 0, 7, 0, 4096, t + 1, INFLIGHT), (3, 0, 7, 0, 4096, t + 2, t + 90)]
+    g, o = run_both(topo4, toy_cols(rows), now=t + 10_000, what="missing+finished", hang_threshold_ns=5_000)
+    assert list(g.alert["class"]) == [1] and list(g.cand[:1]) == [2]
+    S = 1_000_000_000
+    for third_at, m in ((120 * S, 3), (120 * S + S // 2, 2)):
+        rows = []
+        for j, start in enumerate([0, 60 * S, third_at, 240 * S]):
+            for rk in range(2):
+                te = T0 + start + (S if (j == 0 and rk == 1) else 0)
+                rows.append((rk, 0, j, tg.OP_ALLREDUCE, 1 << 20, te, te + 10_000))
+        g, o = run_both(topo, toy_cols(rows), what=f"warmup{m}", tbase_init_ns=7)
+        assert g.group["m"][0] == m and g.group["frozen"][0] == 1
+

@@ -561,3 +561,62 @@ def test_eq1_round_exactly_at_the_end_of_the_warmup_span_still_counts():
         assert r.group["rstar_seq"][0] == 4
         assert r.group["frozen"][0] == 1 and r.group["m"][0] == m
         assert r.group["static"][0] == 0 and r.group["tbase"][0] == base
+
+
+def test_only_an_allreduce_of_a_few_bytes_is_a_barrier():
+    """The 4-byte all-reduce is the barrier (Section 4.2.1); an all-gather of the same size is an ordinary round."""
+    topo = ring_topology(2)
+    rows = (rounds_with_durations([[9000, 1000]], op=tg.OP_ALLREDUCE, nbytes=3, seq0=0)
+            + rounds_with_durations([[9000, 1000]], op=tg.OP_ALLGATHER, nbytes=3, seq0=1))
+    r, _ = analyze(topo, toy_cols(rows), tbase_init_ns=1000)
+    assert list(r.seg["state"] & orc.SEG_BARRIER) == [orc.SEG_BARRIER, 0]
+    assert list(r.seg["state"] & orc.SEG_USABLE) == [0, orc.SEG_USABLE]
+    assert list(r.group["op"]) == [tg.OP_ALLGATHER] and r.group["slow"][0] == 1
+
+
+def test_a_missing_member_means_not_entered_even_when_others_have_finished():
+    """Rank 2 never posted operation 7, rank 3 has already left it, ranks 0 and 1 are still inside: the member
+    without a record is the candidate (first branch of the hang decision tree), not the ranks that finished."""
+    topo = ring_topology(4)
+    t = T0 + 1000
+    rows = [(r, 0, 6, 0, 4096, T0 + r, T0 + 100) for r in range(4)]
+    rows += [(0, 0, 7, 0, 4096, t, INFLIGHT), (1, 0, 7, 0, 4096, t + 1, INFLIGHT), (3, 0, 7, 0, 4096, t + 2, t + 90)]
+    r, _ = analyze(topo, toy_cols(rows), now=t + 10_000, hang_threshold_ns=5_000)
+    assert list(r.alert["class"]) == [1]
+    assert list(r.cand[r.alert["cand_off"][0]: r.alert["cand_off"][0] + r.alert["n_cand"][0]]) == [2]
+
+
+def test_the_warmup_span_is_measured_between_earliest_entries():
+    """Rounds every 60 s, warm-up span 120 s; in the first round one rank enters 1 s after the other.  Measured
+    from the first round's earliest entry the round at 120 s still belongs to the baseline (Eq. 1); measured from
+    its latest entry the span would even reach a round at 121 s, which it must not."""
+    topo = ring_topology(2)
+    S = 1_000_000_000
+
+    def rounds(third_at):
+        rows = []
+        for j, start in enumerate([0, 60 * S, third_at, 240 * S]):
+            for rk in range(2):
+                te = T0 + start + (S if (j == 0 and rk == 1) else 0)
+                rows.append((rk, 0, j, tg.OP_ALLREDUCE, 1 << 20, te, te + 10 * US))
+        return rows
+    r, _ = analyze(topo, toy_cols(rounds(120 * S)), tbase_init_ns=7)
+    assert r.group["m"][0] == 3 and r.group["frozen"][0] == 1
+    r, _ = analyze(topo, toy_cols(rounds(120 * S + S // 2)), tbase_init_ns=7)
+    assert r.group["m"][0] == 2 and r.group["frozen"][0] == 1
+
+
+def test_location_needs_a_slow_window_and_the_rate_root_is_for_communication_only():
+    from tests.test_oracle_rates import series_cols
+    topo = ring_topology(2)
+    o = orc.Oracle(topo, dict(tbase_init_ns=1000, repeat_threshold=2))
+    series = {(0, 0, 0): [(1, 0, 0), (1, 8, 8), (2, 0, 0)], (1, 0, 0): [(1, 2, 8), (1, 8, 8), (2, 0, 0)]}
+    o.progress_rates(series_cols(series), 3, 1)                          # rank 1 has the minimal rate
+    for s in (0, 1):
+        r = o.analyze_window(toy_cols(rounds_with_durations([[9000, 1000]], seq0=s)), FAR)
+    assert r.group["repeats"][0] == 2 and r.group["locate"][0] == 1
+    # computation-slow (P = 1): the communication-side root stays empty although a rate pass has run
+    assert r.group["class"][0] == 1 and r.group["root_s1"][0] == 1 and r.group["root_s2"][0] == NO_RANK
+    # the next window is healthy: nothing to locate, whatever the counter says
+    r = o.analyze_window(toy_cols(rounds_with_durations([[1200, 1100]], seq0=2)), FAR)
+    assert r.group["slow"][0] == 0 and r.group["repeats"][0] == 2 and r.group["locate"][0] == 0
