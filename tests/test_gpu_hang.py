@@ -168,3 +168,35 @@ def test_operation_counter_is_the_largest_over_the_channels_parity():
     g, o = run_both(topo, snap_rows(topo, 6, 2, state), 6, 2, what="seq-over-channels", stall_snapshots=3)
     assert list(g.pair["seq"]) == [8, 7] and list(g.root["rank"]) == [1]
 
+
+def test_decision_tree_order_and_victim_filter_scope_parity():
+    topo = ring_topology(4)
+
+    def st(s, c, q, ch):
+        if q == 3:
+            return (6, 5, 5)
+        if q == 0:
+            return (7, 10 + s, 10 + s)
+        return (7, 2, 1)
+    g, o = run_both(topo, snap_rows(topo, 8, 1, st), 8, 1, what="not-entered first", stall_snapshots=3)
+    assert list(g.root["rank"]) == [3] and list(g.root["class"]) == [1]
+    topo3 = ring_topology(3)
+    g, o = run_both(topo3, snap_rows(topo3, 8, 1, lambda s, c, q, ch: (100 + s, 3 + q, 3)), 8, 1, what="healthy", stall_snapshots=3)
+    assert g.comm["root_by_count"][0] == 0xFFFFFFFF
+    topo = ring_topology(4, comms=[[0, 1], [0, 2, 3]])
+
+    def st1(s, c, q, ch):
+        if c == 0:
+            return (5, 3, 2) if q == 0 else (5, 5, 3)
+        return (8, 4, 4) if q == 2 else (9, 1, 1)
+    g, o = run_both(topo, snap_rows(topo, 8, 1, st1), 8, 1, what="hardware root stays", stall_snapshots=3)
+    assert list(zip(g.root["rank"], g.root["comm"], g.root["class"])) == [(0, 0, 3), (3, 1, 1)]
+    topo = ring_topology(3, comms=[[0, 1], [1, 2]])
+
+    def st2(s, c, q, ch):
+        if c == 0:
+            return (5, 1, 0) if q == 0 else (4, 6, 6)
+        return (7, 2, 2)
+    g, o = run_both(topo, snap_rows(topo, 8, 1, st2), 8, 1, what="idle communicator blocks nobody", stall_snapshots=3)
+    assert list(zip(g.root["rank"], g.root["comm"], g.root["class"])) == [(1, 0, 1)]
+

@@ -304,3 +304,50 @@ def test_victim_filter_needs_the_rank_inside_the_other_hung_communicator():
     r = locate(topo, snap_rows(topo, 8, 1, st(False)), 8, 1, stall_snapshots=3)
     assert list(r.comm["class"]) == [1, 1]
     assert roots(r) == [(2, 0, 1), (2, 1, 1)]
+
+
+def test_a_rank_that_has_not_entered_comes_before_ranks_that_still_progress():
+    """First question of the decision tree first: rank 3 never posted the operation, rank 0 still moves data,
+    ranks 1 and 2 are stuck.  Not-Entered-Hang with rank 3, not Inconsistent-Hang with rank 0."""
+    topo = ring_topology(4)
+
+    def st(s, c, q, ch):
+        if q == 3:
+            return (6, 5, 5)
+        if q == 0:
+            return (7, 10 + s, 10 + s)
+        return (7, 2, 1)
+    r = locate(topo, snap_rows(topo, 8, 1, st), 8, 1, stall_snapshots=3)
+    assert list(r.pair["stalled"]) == [0, 1, 1, 1] and list(r.pair["entered"]) == [1, 1, 1, 0]
+    assert r.comm["class"][0] == 1 and roots(r) == [(3, 0, 1)]
+
+
+def test_healthy_communicator_reports_no_rank_by_count():
+    topo = ring_topology(3)
+    r = locate(topo, snap_rows(topo, 8, 1, lambda s, c, q, ch: (100 + s, 3 + q, 3)), 8, 1, stall_snapshots=3)
+    assert r.comm["hung"][0] == 0 and r.comm["root_by_count"][0] == orc.NO_RANK and r.comm["n_cand"][0] == 0
+
+
+def test_victim_filter_applies_to_not_entered_candidates_of_hung_communicators_only():
+    # communicator 0 = ring {0, 1}: all entered, all stuck, rank 0 waits on nobody -> hardware root rank 0.
+    # communicator 1 = ring {0, 2, 3}: rank 3 never posted operation 9 -> not-entered root rank 3.
+    # Rank 0 has entered the hung communicator 1, but it is a hardware root, not a not-entered candidate: it stays.
+    topo = ring_topology(4, comms=[[0, 1], [0, 2, 3]])
+
+    def st(s, c, q, ch):
+        if c == 0:
+            return (5, 3, 2) if q == 0 else (5, 5, 3)
+        return (8, 4, 4) if q == 2 else (9, 1, 1)
+    r = locate(topo, snap_rows(topo, 8, 1, st), 8, 1, stall_snapshots=3)
+    assert list(r.comm["class"]) == [3, 1]
+    assert roots(r) == [(0, 0, 3), (3, 1, 1)]
+    # communicator 0 = ring {0, 1}: rank 1 never posted operation 5.  Communicator 1 = ring {1, 2} is finished and
+    # idle (equal counts): rank 1 counts as entered there, but an idle communicator blocks nobody: rank 1 stays.
+    topo = ring_topology(3, comms=[[0, 1], [1, 2]])
+
+    def st2(s, c, q, ch):
+        if c == 0:
+            return (5, 1, 0) if q == 0 else (4, 6, 6)
+        return (7, 2, 2)
+    r = locate(topo, snap_rows(topo, 8, 1, st2), 8, 1, stall_snapshots=3)
+    assert list(r.comm["hung"]) == [1, 0] and roots(r) == [(1, 0, 1)]
