@@ -109,6 +109,20 @@ __device__ __forceinline__ i64 sort_groups(i64 v, u32 lane) {
   return v;
 }
 
+// ascending sort of a sequence that falls and then rises inside every aligned group of G lanes (one bitonic
+// merge: halving strides).  The absolute deviations of sorted values from their median form such a sequence,
+// with the empty lanes' largest value at its end.
+template <int G>
+__device__ __forceinline__ i64 merge_groups(i64 v, u32 lane) {
+  if constexpr (G >= 64) v = cmpx<32>(v, lane);
+  if constexpr (G >= 32) v = cmpx<16>(v, lane);
+  if constexpr (G >= 16) v = cmpx<8>(v, lane);
+  if constexpr (G >= 8) v = cmpx<4>(v, lane);
+  if constexpr (G >= 4) v = cmpx<2>(v, lane);
+  if constexpr (G >= 2) v = cmpx<1>(v, lane);
+  return v;
+}
+
 // all-reduce inside a group: smallest (d, r) / largest d with the smallest r among equals
 template <int G, bool MAXIMUM>
 __device__ __forceinline__ void reduce_dur(i64& d, u32& r) {
@@ -205,8 +219,10 @@ __device__ __forceinline__ void dense_pass64(const SegArgs& a, const DenseLane& 
   const i64 med_e = shfl_i64(se, gbase + km), med_x = shfl_i64(sx, gbase + km);
   const i64 min_e = shfl_i64(se, gbase), max_e = shfl_i64(se, gbase + kl);
   const i64 min_x = shfl_i64(sx, gbase), max_x = shfl_i64(sx, gbase + kl);
-  const i64 sde = sort_groups<G>(done ? (e >= med_e ? e - med_e : med_e - e) : T_INFLIGHT, lane);
-  const i64 sdx = sort_groups<G>(done ? (x >= med_x ? x - med_x : med_x - x) : T_INFLIGHT, lane);
+  // deviations of the sorted values: the first nd lanes of a group hold its finished records
+  const bool held = lane - gbase < nd;
+  const i64 sde = merge_groups<G>(held ? absdiff(se, med_e) : T_INFLIGHT, lane);
+  const i64 sdx = merge_groups<G>(held ? absdiff(sx, med_x) : T_INFLIGHT, lane);
   const i64 mad_e = shfl_i64(sde, gbase + km), mad_x = shfl_i64(sdx, gbase + km);
   i64 dmin = done ? x - e : INT64_MAX, dmax = done ? x - e : INT64_MIN;
   u32 rmin = done ? L.rank : 0xFFFFFFFFu, rmax = rmin;
@@ -263,6 +279,16 @@ __device__ __forceinline__ i32 sort_groups32(i32 v, u32 lane) {
   }
   return v;
 }
+template <int G>
+__device__ __forceinline__ i32 merge_groups32(i32 v, u32 lane) {
+  if constexpr (G >= 64) v = cmpx32<32>(v, lane);
+  if constexpr (G >= 32) v = cmpx32<16>(v, lane);
+  if constexpr (G >= 16) v = cmpx32<8>(v, lane);
+  if constexpr (G >= 8) v = cmpx32<4>(v, lane);
+  if constexpr (G >= 4) v = cmpx32<2>(v, lane);
+  if constexpr (G >= 2) v = cmpx32<1>(v, lane);
+  return v;
+}
 // all-reduce of an unsigned 64-bit word inside a group
 template <int G, bool MAXIMUM>
 __device__ __forceinline__ u64 reduce_u64(u64 v) {
@@ -295,9 +321,11 @@ __device__ __forceinline__ void dense_pass32(const SegArgs& a, const DenseLane& 
   const i32 med_e = __shfl(se, (int)(gbase + km), CCLD_WAVE), med_x = __shfl(sx, (int)(gbase + km), CCLD_WAVE);
   const i32 min_e = __shfl(se, (int)gbase, CCLD_WAVE), max_e = __shfl(se, (int)(gbase + kl), CCLD_WAVE);
   const i32 min_x = __shfl(sx, (int)gbase, CCLD_WAVE), max_x = __shfl(sx, (int)(gbase + kl), CCLD_WAVE);
-  const i32 de = er >= med_e ? er - med_e : med_e - er, dx = xr >= med_x ? xr - med_x : med_x - xr;
-  const i32 sde = sort_groups32<G>(done ? de : REL_NONE, lane);
-  const i32 sdx = sort_groups32<G>(done ? dx : REL_NONE, lane);
+  // deviations of the sorted offsets (the first nd lanes of a group hold its finished records): they fall to zero
+  // at the median and rise again, so one merge sorts them
+  const bool held = lane - gbase < nd;
+  const i32 sde = merge_groups32<G>(held ? (se >= med_e ? se - med_e : med_e - se) : REL_NONE, lane);
+  const i32 sdx = merge_groups32<G>(held ? (sx >= med_x ? sx - med_x : med_x - sx) : REL_NONE, lane);
   const i32 mad_e = __shfl(sde, (int)(gbase + km), CCLD_WAVE), mad_x = __shfl(sdx, (int)(gbase + km), CCLD_WAVE);
   // T_min / T_max of the Duration Time with the ranks attaining them (ties: smallest rank): duration and rank
   // travel as one 64-bit word
