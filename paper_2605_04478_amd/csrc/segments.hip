@@ -25,15 +25,21 @@ __device__ __forceinline__ void seg_put(const SegArgs& a, int col, u32 srow, i64
   if (srow < a.seg_cap) a.seg[(u64)col * a.seg_cap + srow] = v;
 }
 // detection-group key and intra-round range T_max - T_min (Eq. 2) of one collective
-__device__ __forceinline__ void seg_put_group(const SegArgs& a, u32 srow, bool usable, u32 comm, u32 op, u64 nb,
-                                              i64 dmax, i64 dmin) {
-  u64 key = a.no_group;
-  i64 range = 0;
+__device__ __forceinline__ void seg_group_of(const SegArgs& a, bool usable, u32 comm, u32 op, u64 nb, i64 dmax, i64 dmin,
+                                             u64* key, i64* range) {
+  *key = a.no_group;
+  *range = 0;
   if (usable) {
     const u64 cls = 63 - __clzll((long long)(nb | 1));
-    key = ((u64)comm * CCLD_OP_MAX + op) * GROUP_CLS + cls;
-    range = dmax - dmin;
+    *key = ((u64)comm * CCLD_OP_MAX + op) * GROUP_CLS + cls;
+    *range = dmax - dmin;
   }
+}
+__device__ __forceinline__ void seg_put_group(const SegArgs& a, u32 srow, bool usable, u32 comm, u32 op, u64 nb,
+                                              i64 dmax, i64 dmin) {
+  u64 key;
+  i64 range;
+  seg_group_of(a, usable, comm, op, nb, dmax, dmin, &key, &range);
   a.gkey[srow] = key;
   a.range_c[srow] = range;
 }
@@ -144,6 +150,8 @@ __device__ __forceinline__ i64 reduce_min(i64 v) {
   return v;
 }
 
+typedef __attribute__((address_space(3))) i64 lds_i64;      // an LDS word: 32-bit addresses, ds instructions
+
 // What one lane knows about its record before the group-wide statistics.
 struct DenseLane {
   i64 e, x;          // arrival, completion (T_INFLIGHT while the operation runs)
@@ -156,7 +164,18 @@ struct DenseLane {
   u32 srow;          // the collective's row of the table
   u32 comm;
   u64 seq;           // operation counter
+  // LDS words that take the collective's table row (STAGE_COLS of them) when `staged`; otherwise the row goes
+  // straight to the table.  A flag and not a null pointer: LDS address 0 is a valid address (the first staged row).
+  lds_i64* stage;
+  bool staged;
 };
+// A staged table row: the 21 columns, then the detection-group key and the range T_max - T_min.  The rows of
+// consecutive collectives lie a multiple of 256 bytes apart; each starts STAGE_SKEW(k) words into its 32-word
+// region, so that the lanes that later read one column of 64 rows spread over eight bank pairs, and the columns
+// of one row keep constant offsets from the row's pointer.
+constexpr u32 STAGE_COLS = CCLD_SEG_NCOL + 2, STAGE_REGION = 32;
+__device__ __forceinline__ u32 stage_skew(u32 k) { return k & 7u; }
+static_assert(STAGE_COLS + 7 <= STAGE_REGION, "a skewed row fits its region");
 
 // Table rows of the collectives of one wavefront pass (called by the first lane of every collective; the rows of a
 // pass are consecutive).  The columns are written from one wavefront-uniform pointer that steps from column to column,
@@ -164,11 +183,35 @@ struct DenseLane {
 // not stay in scalar registers across the whole pass (212 spilled scalar registers become 20).  Storing G words of
 // a row per instruction from the G lanes of its group (3 instead of 23 store instructions at G = 8) was measured
 // too: the selects that bring each lane its word cost more than the stores save (2.18 -> 2.56 ms).
+enum { PUT_DIRECT = 0, PUT_STAGED = 1, PUT_EITHER = 2 };     // where a table row goes: known when compiled, or by L.staged
+template <int MODE>
 __device__ __forceinline__ void dense_put_row(const SegArgs& a, const DenseLane& L, u32 ninfl, bool complete, bool incons,
                                               bool barrier, bool usable, u32 hop, u64 hb, i64 imin, u32 nd, i64 min_e,
                                               i64 med_e, i64 max_e, i64 mad_e, i64 min_x, i64 med_x, i64 max_x, i64 mad_x,
                                               i64 dmin, i64 dmax, u32 rmin, u32 rmax) {
   const u32 srow = L.srow;
+  const bool none = nd == 0;            // no completed record: the statistics columns are empty
+  if (MODE == PUT_STAGED || (MODE == PUT_EITHER && L.staged)) {
+    // the row waits in LDS until the workgroup writes the table column by column, whole lines at a time
+    lds_i64* st = L.stage;
+    auto put = [&](u32 c, i64 v) { st[c] = v; };
+    u64 gk;
+    i64 gr;
+    seg_group_of(a, usable, L.comm, hop, hb, dmax, dmin, &gk, &gr);
+    put(CCLD_SEG_COMM, (i64)L.comm); put(CCLD_SEG_SEQ, (i64)L.seq); put(CCLD_SEG_N, (i64)L.n); put(CCLD_SEG_INFLIGHT, (i64)ninfl);
+    put(CCLD_SEG_STATE, (complete ? CCLD_SEG_COMPLETE : 0) | (!incons ? CCLD_SEG_CONSISTENT : 0) |
+                            (barrier ? CCLD_SEG_BARRIER : 0) | (usable ? CCLD_SEG_USABLE : 0));
+    put(CCLD_SEG_OP, (i64)hop); put(CCLD_SEG_BYTES, (i64)hb);
+    put(CCLD_SEG_ENTER_MIN, none ? 0 : min_e); put(CCLD_SEG_ENTER_MED, none ? 0 : med_e);
+    put(CCLD_SEG_ENTER_MAX, none ? 0 : max_e); put(CCLD_SEG_ENTER_MAD, none ? 0 : mad_e);
+    put(CCLD_SEG_EXIT_MIN, none ? 0 : min_x); put(CCLD_SEG_EXIT_MED, none ? 0 : med_x);
+    put(CCLD_SEG_EXIT_MAX, none ? 0 : max_x); put(CCLD_SEG_EXIT_MAD, none ? 0 : mad_x);
+    put(CCLD_SEG_DUR_MIN, none ? 0 : dmin); put(CCLD_SEG_DUR_MAX, none ? 0 : dmax);
+    put(CCLD_SEG_ARGMIN_RANK, none ? (i64)CCLD_NO_RANK : (i64)rmin); put(CCLD_SEG_ARGMAX_RANK, none ? (i64)CCLD_NO_RANK : (i64)rmax);
+    put(CCLD_SEG_INFLIGHT_ENTER_MIN, imin); put(CCLD_SEG_FIRST, (i64)L.first);
+    put(CCLD_SEG_NCOL, (i64)gk); put(CCLD_SEG_NCOL + 1, gr);
+    return;
+  }
   seg_put_group(a, srow, usable, L.comm, hop, hb, dmax, dmin);
   if (srow >= a.seg_cap) return;
   const u32 s0 = (u32)__builtin_amdgcn_readfirstlane((int)srow);      // the first of the pass's rows that fit the table
@@ -189,7 +232,6 @@ __device__ __forceinline__ void dense_put_row(const SegArgs& a, const DenseLane&
       (usable ? CCLD_SEG_USABLE : 0));
   put((i64)hop);
   put((i64)hb);
-  const bool none = nd == 0;            // no completed record: the statistics columns are empty
   put(none ? 0 : min_e); put(none ? 0 : med_e); put(none ? 0 : max_e); put(none ? 0 : mad_e);
   put(none ? 0 : min_x); put(none ? 0 : med_x); put(none ? 0 : max_x); put(none ? 0 : mad_x);
   put(none ? 0 : dmin); put(none ? 0 : dmax);
@@ -205,7 +247,7 @@ __device__ __forceinline__ void dense_put_record(const SegArgs& a, u32 j, u32 f,
 }
 
 // Statistics of the collectives of one wavefront pass in 64-bit arithmetic (any spread of the times).
-template <int G>
+template <int G, int MODE>
 __device__ __forceinline__ void dense_pass64(const SegArgs& a, const DenseLane& L, u32 size, u32 lane, u32 gbase, u64 gmask) {
   const i64 e = L.e, x = L.x;
   const bool valid = L.valid;
@@ -238,7 +280,7 @@ __device__ __forceinline__ void dense_pass64(const SegArgs& a, const DenseLane& 
   const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
   const bool usable = complete && !incons && !barrier;
   if (lane == L.fl)
-    dense_put_row(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, min_e, med_e, max_e, mad_e, min_x,
+    dense_put_row<MODE>(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, min_e, med_e, max_e, mad_e, min_x,
                   med_x, max_x, mad_x, dmin, dmax, rmin, rmax);
   i64 le = 0, lx = 0;
   u32 f = 0;
@@ -307,7 +349,7 @@ __device__ __forceinline__ bool is_late32(i32 lag, i64 floor_ns, u32 knum, u32 k
   return (u64)(u32)lag * (u64)kden > (u64)knum * (u64)(u32)mad;
 }
 
-template <int G>
+template <int G, int MODE>
 __device__ __forceinline__ void dense_pass32(const SegArgs& a, const DenseLane& L, i64 ref, i32 er, i32 xr, u32 size,
                                              u32 lane, u32 gbase, u64 gmask) {
   const bool valid = L.valid;
@@ -344,7 +386,7 @@ __device__ __forceinline__ void dense_pass32(const SegArgs& a, const DenseLane& 
   const bool barrier = hop == CCLD_OP_ALLREDUCE && hb < (u64)a.barrier_bytes;
   const bool usable = complete && !incons && !barrier;
   if (lane == L.fl)
-    dense_put_row(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, ref + min_e, ref + med_e, ref + max_e,
+    dense_put_row<MODE>(a, L, ninfl, complete, incons, barrier, usable, hop, hb, imin, nd, ref + min_e, ref + med_e, ref + max_e,
                   (i64)mad_e, ref + min_x, ref + med_x, ref + max_x, (i64)mad_x, (i64)(wmin >> 32), (i64)(wmax >> 32),
                   (u32)wmin, ~(u32)wmax);
   i32 le = 0, lx = 0;
@@ -358,9 +400,10 @@ __device__ __forceinline__ void dense_pass32(const SegArgs& a, const DenseLane& 
 }
 
 // ---- collectives of up to 64 records, 64/G of them per wavefront pass --------------------------
+constexpr u32 SEG_STAGE_ROWS = 144;      // table rows a tile stages in LDS (a tile of eight-member collectives has 128 or 129)
 template <int G>
 __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32 seg0, u32 nheads,
-                                                 const unsigned short* s_head, u32 lane, u32 wave) {
+                                                 const unsigned short* s_head, i64* s_stage, u32 lane, u32 wave) {
   constexpr int SPW = CCLD_WAVE / G, NW = SEG_THREADS / CCLD_WAVE;
   const int mb = a.sf.mb;
   const u64 mmask = ((u64)1 << mb) - 1, smask = ((u64)1 << a.sf.ws) - 1;
@@ -381,6 +424,9 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
     L.e = 0; L.x = T_INFLIGHT; L.nb = 0; L.op = 0; L.rank = 0;
     L.first = base + a0; L.j = L.first + l; L.fl = gbase; L.n = n; L.srow = seg0 + sl;
     L.pm = 0;
+    // rows beyond the staging area (a tile of many short collectives) go straight to the table
+    L.staged = sl < SEG_STAGE_ROWS;
+    L.stage = (lds_i64*)s_stage + sl * STAGE_COLS;
     u64 key = 0;
     if (L.valid) {
       key = a.key[L.j];
@@ -397,8 +443,8 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
     const i64 oe = L.e - ref, ox = L.x - ref;
     constexpr i64 LIM = (i64)1 << 30;
     const bool wide = L.valid && (oe < -LIM || oe >= LIM || (L.x != T_INFLIGHT && (ox < -LIM || ox >= LIM)));
-    if (ballot64(wide) == 0) dense_pass32<G>(a, L, ref, (i32)oe, (i32)ox, size, lane, gbase, gmask);
-    else dense_pass64<G>(a, L, size, lane, gbase, gmask);
+    if (ballot64(wide) == 0) dense_pass32<G, PUT_EITHER>(a, L, ref, (i32)oe, (i32)ox, size, lane, gbase, gmask);
+    else dense_pass64<G, PUT_EITHER>(a, L, size, lane, gbase, gmask);
   }
 }
 
@@ -410,6 +456,11 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
   __shared__ unsigned short s_head[SEG_TILE + 2];
   __shared__ u32 s_wave[NW];
   __shared__ u32 s_halo_head, s_gmax;
+  // Table rows of the tile's first SEG_STAGE_ROWS collectives wait here (STAGE_COLS words each: an odd stride, so
+  // the lanes that read one column of consecutive rows spread over the banks) and leave column by column at the
+  // end, consecutive lanes to consecutive rows: one store instruction per 64 rows and column instead of one per
+  // wavefront pass and column.
+  __shared__ i64 s_stage[SEG_STAGE_ROWS * STAGE_COLS];
   const u32 tid = threadIdx.x, lane = lane_id(), wave = tid / CCLD_WAVE;
   const u32 tile = blockIdx.x, base = tile * SEG_TILE;
   const u32 rem = a.n - base;                                     // records from the tile's start to the end
@@ -450,12 +501,25 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
   }
   __syncthreads();
   const u32 gmax = s_gmax, seg0 = a.tile_heads[tile];
-  if (gmax <= 2) seg_wave_batches<2>(a, base, seg0, nheads, s_head, lane, wave);
-  else if (gmax <= 4) seg_wave_batches<4>(a, base, seg0, nheads, s_head, lane, wave);
-  else if (gmax <= 8) seg_wave_batches<8>(a, base, seg0, nheads, s_head, lane, wave);
-  else if (gmax <= 16) seg_wave_batches<16>(a, base, seg0, nheads, s_head, lane, wave);
-  else if (gmax <= 32) seg_wave_batches<32>(a, base, seg0, nheads, s_head, lane, wave);
-  else seg_wave_batches<64>(a, base, seg0, nheads, s_head, lane, wave);
+  if (gmax <= 2) seg_wave_batches<2>(a, base, seg0, nheads, s_head, s_stage, lane, wave);
+  else if (gmax <= 4) seg_wave_batches<4>(a, base, seg0, nheads, s_head, s_stage, lane, wave);
+  else if (gmax <= 8) seg_wave_batches<8>(a, base, seg0, nheads, s_head, s_stage, lane, wave);
+  else if (gmax <= 16) seg_wave_batches<16>(a, base, seg0, nheads, s_head, s_stage, lane, wave);
+  else if (gmax <= 32) seg_wave_batches<32>(a, base, seg0, nheads, s_head, s_stage, lane, wave);
+  else seg_wave_batches<64>(a, base, seg0, nheads, s_head, s_stage, lane, wave);
+  __syncthreads();
+  const u32 staged = nheads < SEG_STAGE_ROWS ? nheads : SEG_STAGE_ROWS;
+  for (u32 col = wave; col < STAGE_COLS; col += NW) {
+    for (u32 sl = lane; sl < staged; sl += CCLD_WAVE) {
+      // a collective of more than 64 records is on the list of the kernels that take those: they write its row
+      if ((u32)s_head[sl + 1] - (u32)s_head[sl] > (u32)SEG_WAVE_MAX) continue;
+      const i64 v = s_stage[sl * STAGE_COLS + col];
+      const u32 srow = seg0 + sl;
+      if (col < (u32)CCLD_SEG_NCOL) { if (srow < a.seg_cap) a.seg[(u64)col * a.seg_cap + srow] = v; }
+      else if (col == (u32)CCLD_SEG_NCOL) a.gkey[srow] = (u64)v;
+      else a.range_c[srow] = v;
+    }
+  }
 }
 
 // ---- collectives of 65 to 512 records: E values per lane, sorted in registers ---------------------
@@ -1084,8 +1148,8 @@ __global__ __launch_bounds__(256) void k_seg_group_listed(SegArgs a) {
 // adds the records per rank to the blame table.
 constexpr int DENSE_THREADS = 512;
 
-template <int G>
-__device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, const uint4* s_cell, const u32* s_pres,
+template <int G, bool STAGED>
+__device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, uint4* s_cell, const u32* s_pres,
                                                   const u32* s_pre, u32 K, u32 size, u32 comm, u64 rel0, u32 srow0,
                                                   u32 rec0, u32 row0, u64* __restrict__ skey, u32* __restrict__ sidx,
                                                   u32 lane, u32 wave) {
@@ -1106,6 +1170,9 @@ __device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, const uint4*
     L.pm = ballot64(L.valid) & gmask;
     L.n = (u32)__popcll(L.pm);
     L.e = 0; L.x = T_INFLIGHT; L.nb = 0; L.op = 0; L.rank = rank; L.comm = comm;
+    // the collective's own cells (size x 32 bytes, at least one region) take its row once they are read
+    L.staged = STAGED;
+    L.stage = (lds_i64*)reinterpret_cast<i64*>(s_cell) + k * size * 4 + stage_skew(k);
     u32 ai = 0;
     if (L.valid) {
       const uint4 h0 = s_cell[2 * cell], h1 = s_cell[2 * cell + 1];
@@ -1128,8 +1195,8 @@ __device__ __forceinline__ u32 dense_wave_batches(const SegArgs& a, const uint4*
     const i64 oe = L.e - ref, ox = L.x - ref;
     constexpr i64 LIM = (i64)1 << 30;
     const bool wide = L.valid && (oe < -LIM || oe >= LIM || (L.x != T_INFLIGHT && (ox < -LIM || ox >= LIM)));
-    if (ballot64(wide) == 0) dense_pass32<G>(a, L, ref, (i32)oe, (i32)ox, size, lane, gbase, gmask);
-    else dense_pass64<G>(a, L, size, lane, gbase, gmask);
+    if (ballot64(wide) == 0) dense_pass32<G, STAGED ? PUT_STAGED : PUT_DIRECT>(a, L, ref, (i32)oe, (i32)ox, size, lane, gbase, gmask);
+    else dense_pass64<G, STAGED ? PUT_STAGED : PUT_DIRECT>(a, L, size, lane, gbase, gmask);
   }
   return mine;
 }
@@ -1233,12 +1300,14 @@ void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
     const u32 srow0 = D.srow0;
     if (size <= (u32)SEG_WAVE_MAX) {
       u32 mine;
-      if (size <= 2) mine = dense_wave_batches<2>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
-      else if (size <= 4) mine = dense_wave_batches<4>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
-      else if (size <= 8) mine = dense_wave_batches<8>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
-      else if (size <= 16) mine = dense_wave_batches<16>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
-      else if (size <= 32) mine = dense_wave_batches<32>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
-      else mine = dense_wave_batches<64>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      // from eight members on, a collective's cells are large enough to hold its table row
+      if (size <= 2) mine = dense_wave_batches<2, false>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else if (size <= 4) mine = dense_wave_batches<4, false>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else if (size < 8) mine = dense_wave_batches<8, false>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else if (size == 8) mine = dense_wave_batches<8, true>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else if (size <= 16) mine = dense_wave_batches<16, true>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else if (size <= 32) mine = dense_wave_batches<32, true>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
+      else mine = dense_wave_batches<64, true>(a, s_cell, s_pres, s_pre, K, size, c, rel0, srow0, rec0, row0, skey, sidx, lane, wave);
       // the lane's member slot is the same in every pass
       u32 G = 2; while (G < size) G <<= 1;
       if (mine) atomicAdd(&s_slot[lane % G], mine);
@@ -1275,6 +1344,20 @@ void k_dense_stats(SegArgs a, DenseArgs d, u64* __restrict__ skey,
     }
     if (bad) atomicOr((unsigned long long*)&a.counters[CNT_STATUS], (unsigned long long)bad);
     __syncthreads();
+    // the staged table rows: every wavefront writes whole columns, consecutive lanes to consecutive rows
+    if (size >= 8 && size <= (u32)SEG_WAVE_MAX) {
+      const i64* S = reinterpret_cast<const i64*>(s_cell);
+      for (u32 col = wave; col < STAGE_COLS; col += DENSE_THREADS / CCLD_WAVE) {
+        for (u32 k = lane; k < K; k += CCLD_WAVE) {
+          if (s_n[k] == 0) continue;                   // a round without any record has no row
+          const i64 v = S[k * size * 4 + stage_skew(k) + col];
+          const u32 srow = srow0 + k;
+          if (col < (u32)CCLD_SEG_NCOL) { if (srow < a.seg_cap) a.seg[(u64)col * a.seg_cap + srow] = v; }
+          else if (col == (u32)CCLD_SEG_NCOL) a.gkey[srow] = (u64)v;
+          else a.range_c[srow] = v;
+        }
+      }
+    }
     // 4. records per rank
     {
       const u32* __restrict__ ms = a.members_sorted + a.member_off[c];
