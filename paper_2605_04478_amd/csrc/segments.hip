@@ -454,7 +454,7 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
   constexpr int OWN = SEG_TILE / SEG_THREADS, NW = SEG_THREADS / CCLD_WAVE;
   __shared__ unsigned short s_head[SEG_TILE + 2];
-  __shared__ u32 s_wave[NW];
+  __shared__ u32 s_cnt[OWN * NW];
   __shared__ u32 s_halo_head, s_gmax;
   // Table rows of the tile's first SEG_STAGE_ROWS collectives wait here (STAGE_COLS words each: an odd stride, so
   // the lanes that read one column of consecutive rows spread over the banks) and leave column by column at the
@@ -467,23 +467,31 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
   const u32 own = rem < (u32)SEG_TILE ? rem : (u32)SEG_TILE;
   const int mb = a.sf.mb;
   if (tid == 0) { s_halo_head = rem <= (u32)(SEG_TILE + SEG_WAVE_MAX) ? rem : 0xFFFFu; s_gmax = 0; }
+  // Heads of the tile.  Position r * SEG_THREADS + tid ascends with (r, wavefront, lane), so a head's index is
+  // the number of heads in the (r, wavefront) blocks before its own (16 counts in LDS, one ballot each) plus
+  // the heads below its lane: no scan over the workgroup, one barrier.
   bool head[OWN];
+  u64 hm[OWN];
 #pragma unroll
   for (int r = 0; r < OWN; ++r) {
     const u32 pos = r * SEG_THREADS + tid, j = base + pos;
     head[r] = pos < own && (j == 0 || (a.key[j - 1] >> mb) != (a.key[j] >> mb));
+    hm[r] = ballot64(head[r]);
+    if (lane == 0) s_cnt[r * NW + wave] = (u32)__popcll(hm[r]);
   }
   __syncthreads();
-  u32 carry = 0;
+  u32 before[OWN], acc = 0;
 #pragma unroll
-  for (int r = 0; r < OWN; ++r) {
-    const u32 h = head[r] ? 1u : 0u;
-    u32 tot;
-    const u32 ex = block_exclusive_sum<SEG_THREADS>(h, s_wave, &tot);
-    if (h) s_head[carry + ex] = (unsigned short)(r * SEG_THREADS + tid);
-    carry += tot;
+  for (int r = 0; r < OWN; ++r) before[r] = 0;
+#pragma unroll
+  for (int bl = 0; bl < OWN * NW; ++bl) {
+    if ((u32)(bl % NW) == wave) before[bl / NW] = acc;
+    acc += s_cnt[bl];
   }
-  const u32 nheads = carry;
+  const u32 nheads = acc;
+#pragma unroll
+  for (int r = 0; r < OWN; ++r)
+    if (head[r]) s_head[before[r] + mbcnt64(hm[r])] = (unsigned short)(r * SEG_THREADS + tid);
   // where the tile's last collective ends: the first head within 64 records past the tile
   if (tid <= (u32)SEG_WAVE_MAX) {
     const u32 pos = SEG_TILE + tid;
@@ -493,10 +501,10 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_wave(SegArgs a) {
     }
   }
   __syncthreads();
-  if (tid == 0) s_head[nheads] = (unsigned short)s_halo_head;
-  __syncthreads();
+  const u32 halo = s_halo_head & 0xFFFFu;
+  if (tid == 0) s_head[nheads] = (unsigned short)halo;
   for (u32 s = tid; s < nheads; s += SEG_THREADS) {
-    const u32 n = (u32)s_head[s + 1] - (u32)s_head[s];
+    const u32 n = (s + 1 < nheads ? (u32)s_head[s + 1] : halo) - (u32)s_head[s];
     if (n <= (u32)SEG_WAVE_MAX) atomicMax(&s_gmax, n);
   }
   __syncthreads();
