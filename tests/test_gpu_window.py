@@ -550,3 +550,29 @@ def test_barrier_operation_missing_member_and_warmup_origin_parity():
         g, o = run_both(topo, toy_cols(rows), what=f"warmup{m}", tbase_init_ns=7)
         assert g.group["m"][0] == m and g.group["frozen"][0] == 1
 
+
+
+def test_tiles_of_many_short_collectives_beside_longer_ones():
+    # pairs: 512 collectives per tile of 1,024 sorted records, of which the statistics kernel stages the table rows
+    # of the first 144 and writes the others directly; after them eight-member rounds (128 per tile, all staged)
+    # and rounds of 5 (fewer than eight members: never staged by the dense placement); some members missing, one
+    # operation in flight, so that rows with empty statistics pass through both ways
+    rng = np.random.default_rng(11)
+    pairs = [[2 * i, 2 * i + 1] for i in range(24)]
+    comms = pairs + [list(range(48, 56)), list(range(56, 64)), [0, 9, 18, 27, 36], list(range(40, 48))]
+    topo = ring_topology(64, comms=comms)
+    rows = []
+    for c, members in enumerate(comms):
+        for s in range(130):
+            t = T0 + s * 1_000_000 + c * 1000
+            for r in members:
+                if rng.random() < 0.02:
+                    continue                                   # a member without a record
+                e = t + int(rng.integers(0, 5000))
+                rows.append((r, c, s, tg.OP_ALLREDUCE, 1 << 20, e, e + int(rng.integers(1000, 90000))))
+    cols = toy_cols(rows)
+    cols["t_exit"][rng.integers(0, len(rows), 40)] = INFLIGHT
+    perm = rng.permutation(len(rows))
+    cols = {k: v[perm] for k, v in cols.items()}
+    g, o = run_both(topo, cols, what="short-and-long", lag_floor_ns=1000, tbase_init_ns=1000)
+    assert g.n_seg > 24 * 130 and g.n_flag > 0
