@@ -140,6 +140,18 @@ __global__ __launch_bounds__(256) void k_chain_jump(const u32* anc_in, const u32
   anc_out[k] = a2;
   dist_out[k] = dist_in[k] + (a2 != a1 ? dist_in[a1] : 0u);
 }
+// column[idx] += 1 for every lane with `on`, one atomic per distinct idx in the wavefront: a faulty rank's thousands
+// of entries would otherwise queue up at one address.  Called by every active lane of the wavefront.
+__device__ __forceinline__ void wave_count_by_index(i64* column, u32 idx, bool on) {
+  u64 todo = ballot64(on);
+  while (todo) {
+    const u32 leader = (u32)__builtin_ctzll(todo);
+    const u32 v = (u32)__shfl((int)idx, (int)leader, CCLD_WAVE);
+    const u64 same = ballot64(on && idx == v);
+    if (lane_id() == leader) atomicAdd((unsigned long long*)&column[v], (unsigned long long)__popcll(same));
+    todo &= ~same;
+  }
+}
 __global__ __launch_bounds__(256) void k_chain_emit(ChainArgs a, const u32* anc, const u32* dist, i64* chain, u64 chain_cap,
                                                     i64* per_rank) {
   const u32 k = blockIdx.x * 256 + threadIdx.x;
@@ -158,11 +170,13 @@ __global__ __launch_bounds__(256) void k_chain_emit(ChainArgs a, const u32* anc,
     chain[(u64)CCLD_CHN_ROOT_RANK * chain_cap + k] = (i64)root_rank;
     chain[(u64)CCLD_CHN_DEPTH * chain_cap + k] = (i64)dist[k];
   }
-  if (per_rank && (a.rec_flag[a.flag_pos[k]] & CCLD_FLAG_LATE_ENTER)) {
+  if (per_rank) {
+    const bool on = (a.rec_flag[a.flag_pos[k]] & CCLD_FLAG_LATE_ENTER) != 0;
     const u32 n_ranks = a.T.n_ranks;
-    const u32 mine = rank_at(k);
-    atomicAdd((unsigned long long*)&per_rank[(u64)(p == ~0u ? CCLD_CHR_ROOT_ENTRIES : CCLD_CHR_SECONDARY_ENTRIES) * n_ranks + mine], 1ull);
-    atomicAdd((unsigned long long*)&per_rank[(u64)CCLD_CHR_CAUSED * n_ranks + root_rank], 1ull);
+    const u32 mine = on ? rank_at(k) : 0u;
+    wave_count_by_index(per_rank + (u64)CCLD_CHR_ROOT_ENTRIES * n_ranks, mine, on && p == ~0u);
+    wave_count_by_index(per_rank + (u64)CCLD_CHR_SECONDARY_ENTRIES * n_ranks, mine, on && p != ~0u);
+    wave_count_by_index(per_rank + (u64)CCLD_CHR_CAUSED * n_ranks, root_rank, on);
   }
 }
 
