@@ -43,6 +43,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->topo.rank_comms = w.take<uint32_t>(n_members);
   c->topo.rank_slots = w.take<uint32_t>(n_members);
   c->topo.rank_memb4 = w.take<uint32_t>(4ull * n_ranks);
+  c->topo.rank_cell4 = w.take<uint32_t>(4ull * n_ranks);
   // window
   c->win_key = w.take<uint64_t>(N);
   c->win_row = w.take<Row>(N);
@@ -310,6 +311,18 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
     for (uint32_t q = rc_off[r]; q < rc_off[r + 1]; ++q) rc4[4ull * r + (q - rc_off[r])] = (rc[q] << mb) | rs_slot[q];
   }
 
+  // the same rows with the member index (the row of the snapshot grid) in place of the sorted position: the
+  // snapshot placement then needs one lookup per row instead of three
+  const int pb = bits_for_host(n_members ? n_members - 1 : 0);
+  std::vector<uint32_t> rp4(4ull * topo->n_ranks, 0xFFFFFFFFu);
+  const bool fits_cell4 = fits4 && pb + cb <= 31;
+  for (uint32_t r = 0; fits_cell4 && r < topo->n_ranks; ++r)
+    for (uint32_t q = rc_off[r]; q < rc_off[r + 1]; ++q) {
+      const uint32_t k = rc[q], off = topo->member_off[k];
+      rp4[4ull * r + (q - rc_off[r])] = (k << pb) | (off + sslot[off + rs_slot[q]]);
+    }
+  c->topo.pb = pb;
+
   ccld_status rs = CCLD_OK;
   auto up = [&](const void* dst, const void* src, size_t bytes) {
     if (bytes && hipMemcpyAsync(const_cast<void*>(dst), src, bytes, hipMemcpyHostToDevice, c->stream) != hipSuccess)
@@ -327,6 +340,8 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   up(c->topo.rank_slots, rs_slot.data(), 4ull * n_members);
   up(c->topo.rank_memb4, rc4.data(), 4ull * rc4.size());
   if (!fits4) c->topo.rank_memb4 = nullptr;
+  up(c->topo.rank_cell4, rp4.data(), 4ull * rp4.size());
+  if (!fits_cell4) c->topo.rank_cell4 = nullptr;
   if (hipMemsetAsync(c->gstate, 0, sizeof(GroupState) * (uint64_t)topo->n_comms * GROUP_SLOTS, c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->batch_meta, 0, sizeof(BatchMeta) * ((uint64_t)c->p.window_batches + 2), c->stream) != hipSuccess) rs = CCLD_E_HIP;
   if (hipMemsetAsync(c->counters, 0, sizeof(uint64_t) * CNT_COUNT, c->stream) != hipSuccess) rs = CCLD_E_HIP;

@@ -48,6 +48,8 @@ struct DeviceTopology {
   const uint32_t* rank_comms;
   const uint32_t* rank_slots;       // parallel to rank_comms: the rank's position in members_sorted of that communicator
   const uint32_t* rank_memb4;       // [n_ranks][4] words comm << mb | position (padded with 0xFFFFFFFF); null if a rank is in more than four communicators or cb + mb > 31
+  const uint32_t* rank_cell4;       // [n_ranks][4] words comm << pb | member index (member_off[comm] + slot in members[]), padded alike; null if a rank is in more than four communicators or cb + pb > 31
+  int pb;                           // bits of the largest member index
 };
 
 // rank of the record whose key carries (comm, slot)

@@ -59,6 +59,31 @@ __device__ __forceinline__ int slot_of(const DeviceTopology& T, u32 c, u32 r) {
   return -1;
 }
 
+// Row of the snapshot grid (member index) of rank r in communicator c, or -1.  m: the rank's packed row of
+// rank_cell4 when that table exists (words comm << pb | member index), else of rank_memb4 (comm << mb | sorted
+// position), else unused.
+__device__ __forceinline__ i64 grid_row_of(const HangArgs& a, u32 c, u32 r, const uint4& m) {
+  if (r >= a.T.n_ranks) return -1;
+  if (a.T.rank_cell4) {
+    const int pb = a.T.pb;
+    const u32 w = c == (m.x >> pb) ? m.x : c == (m.y >> pb) ? m.y : c == (m.z >> pb) ? m.z : m.w;
+    return c == (w >> pb) ? (i64)(w & ((1u << pb) - 1u)) : -1;
+  }
+  int slot = -1;
+  if (a.T.rank_memb4) {
+    const u32 mmask = a.mb < 32 ? (1u << a.mb) - 1 : ~0u;
+    const u32 w = c == (m.x >> a.mb) ? m.x : c == (m.y >> a.mb) ? m.y : c == (m.z >> a.mb) ? m.z : m.w;
+    if (c == (w >> a.mb)) slot = (int)a.T.sorted_slot[a.T.member_off[c] + (w & mmask)];
+  } else {
+    slot = slot_of(a.T, c, r);
+  }
+  return slot < 0 ? -1 : (i64)a.T.member_off[c] + slot;
+}
+__device__ __forceinline__ uint4 grid_row_lookup(const HangArgs& a, u32 r) {
+  const uint4* __restrict__ t = reinterpret_cast<const uint4*>(a.T.rank_cell4 ? a.T.rank_cell4 : a.T.rank_memb4);
+  return (t && r < a.T.n_ranks) ? t[r] : make_uint4(~0u, ~0u, ~0u, ~0u);
+}
+
 // Status of one cell as the per-member passes read it.  With the bitmap: its bit.  Without: a cell that still
 // holds the all-ones fill was (almost certainly) never written; the caller then repeats the placement with the
 // bitmap, which tells a gap from a duplicate and from a row that really holds that pattern.
@@ -72,8 +97,6 @@ template <bool EXACT>
 __global__ __launch_bounds__(256) void k_hang_place(HangArgs a) {
   constexpr int U = 4;               // rows per thread in flight
   u64 status = 0;
-  const uint4* __restrict__ memb4 = reinterpret_cast<const uint4*>(a.T.rank_memb4);
-  const u32 mmask = a.mb < 32 ? (1u << a.mb) - 1 : ~0u;
   ulonglong2* __restrict__ cell2 = reinterpret_cast<ulonglong2*>(a.cell);
   const u64 stride = (u64)gridDim.x * 256;
   for (u64 i0 = (u64)blockIdx.x * 256 + threadIdx.x; i0 < a.n_rows; i0 += stride * U) {
@@ -94,27 +117,15 @@ __global__ __launch_bounds__(256) void k_hang_place(HangArgs a) {
     }
     uint4 m[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      m[u] = make_uint4(~0u, ~0u, ~0u, ~0u);
-      if (on[u] && memb4 && r[u] < a.T.n_ranks) m[u] = memb4[r[u]];
-    }
+    for (int u = 0; u < U; ++u) m[u] = on[u] ? grid_row_lookup(a, r[u]) : make_uint4(~0u, ~0u, ~0u, ~0u);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (!on[u]) continue;
       if (c[u] >= a.T.n_comms) { status |= DS_UNKNOWN_COMM; continue; }
-      int slot = -1;
-      if (r[u] < a.T.n_ranks) {
-        if (memb4) {      // the rank's packed (communicator, position among sorted members) words
-          const u32 w = c[u] == (m[u].x >> a.mb) ? m[u].x : c[u] == (m[u].y >> a.mb) ? m[u].y
-                      : c[u] == (m[u].z >> a.mb) ? m[u].z : m[u].w;
-          if (c[u] == (w >> a.mb)) slot = (int)a.T.sorted_slot[a.T.member_off[c[u]] + (w & mmask)];
-        } else {
-          slot = slot_of(a.T, c[u], r[u]);
-        }
-      }
-      if (slot < 0) { status |= DS_NOT_MEMBER; continue; }
+      const i64 p = grid_row_of(a, c[u], r[u], m[u]);
+      if (p < 0) { status |= DS_NOT_MEMBER; continue; }
       if (ch[u] >= a.n_ch || sn[u] >= a.n_snap) { status |= DS_RANGE; continue; }
-      const u64 k = (((u64)a.T.member_off[c[u]] + (u32)slot) * a.n_ch + ch[u]) * a.n_snap + sn[u];
+      const u64 k = ((u64)p * a.n_ch + ch[u]) * a.n_snap + sn[u];
       cell2[k] = make_ulonglong2(sq[u], (u64)se[u] | ((u64)rv[u] << 32));
       if (EXACT) {
         // presence bitmap (one bit per cell: small enough to stay in cache); a bit already set is a duplicate
@@ -148,8 +159,6 @@ __global__ __launch_bounds__(PART_THREADS) void k_hang_part(HangArgs a, u64 chun
   __shared__ u32 s_cnt[PART_REGIONS], s_pre[PART_REGIONS], s_base[PART_REGIONS], s_scan[PART_THREADS / CCLD_WAVE], s_total;
   const u32 tid = threadIdx.x;
   u64 status = 0;
-  const uint4* __restrict__ memb4 = reinterpret_cast<const uint4*>(a.T.rank_memb4);
-  const u32 mmask = a.mb < 32 ? (1u << a.mb) - 1 : ~0u;
   const u32 cap = 1u << a.rb, kmask = cap - 1;
   const u64 i_begin = chunk * blockIdx.x;
   const u64 i_end = chunk * (blockIdx.x + 1) < a.n_rows ? chunk * (blockIdx.x + 1) : a.n_rows;
@@ -181,28 +190,16 @@ __global__ __launch_bounds__(PART_THREADS) void k_hang_part(HangArgs a, u64 chun
     load_round(base + PART_CHUNK, nc, nr, nch, nsn, nsq, nse, nrv);     // the next round's columns are on their way meanwhile
     uint4 m[PART_U];
 #pragma unroll
-    for (int u = 0; u < PART_U; ++u) {
-      m[u] = make_uint4(~0u, ~0u, ~0u, ~0u);
-      if (on[u] && memb4 && r[u] < a.T.n_ranks) m[u] = memb4[r[u]];
-    }
+    for (int u = 0; u < PART_U; ++u) m[u] = on[u] ? grid_row_lookup(a, r[u]) : make_uint4(~0u, ~0u, ~0u, ~0u);
 #pragma unroll
     for (int u = 0; u < PART_U; ++u) {
       if (!on[u]) continue;
       on[u] = false;
       if (c[u] >= a.T.n_comms) { status |= DS_UNKNOWN_COMM; continue; }
-      int slot = -1;
-      if (r[u] < a.T.n_ranks) {
-        if (memb4) {
-          const u32 w = c[u] == (m[u].x >> a.mb) ? m[u].x : c[u] == (m[u].y >> a.mb) ? m[u].y
-                      : c[u] == (m[u].z >> a.mb) ? m[u].z : m[u].w;
-          if (c[u] == (w >> a.mb)) slot = (int)a.T.sorted_slot[a.T.member_off[c[u]] + (w & mmask)];
-        } else {
-          slot = slot_of(a.T, c[u], r[u]);
-        }
-      }
-      if (slot < 0) { status |= DS_NOT_MEMBER; continue; }
+      const i64 p = grid_row_of(a, c[u], r[u], m[u]);
+      if (p < 0) { status |= DS_NOT_MEMBER; continue; }
       if (ch[u] >= a.n_ch || sn[u] >= a.n_snap) { status |= DS_RANGE; continue; }
-      const u64 k = (((u64)a.T.member_off[c[u]] + (u32)slot) * a.n_ch + ch[u]) * a.n_snap + sn[u];
+      const u64 k = ((u64)p * a.n_ch + ch[u]) * a.n_snap + sn[u];
       reg[u] = (u32)(k >> a.rb); kin[u] = (u32)k & kmask;
       at[u] = atomicAdd(&s_cnt[reg[u]], 1u);
       on[u] = true;
