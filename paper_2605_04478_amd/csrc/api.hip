@@ -772,11 +772,7 @@ ccld_status ccld_rank_blame(ccld_ctx* c, int64_t* blame, uint32_t* order) {
   if (!c) return CCLD_E_NULL;
   if (!c->blame_valid) return CCLD_E_BAD_ARG;
   const uint32_t n_ranks = c->topo.n_ranks;
-  if (blame)
-    HIP_TRY(hipMemcpyAsync(blame, c->blame, sizeof(int64_t) * CCLD_BLM_NCOL * (uint64_t)n_ranks,
-                           hipMemcpyDeviceToDevice, c->stream));
-  if (order)
-    HIP_TRY(hipMemcpyAsync(order, c->blame_order, sizeof(uint32_t) * (uint64_t)n_ranks, hipMemcpyDeviceToDevice, c->stream));
+  launch_blame_out(c->stream, c->blame, c->blame_order, n_ranks, blame, order);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipStreamSynchronize(c->stream));
   return CCLD_OK;

@@ -748,6 +748,23 @@ void launch_blame_order(hipStream_t st, const int64_t* blame, uint32_t n_ranks, 
                      (const u32*)lists, (const u64*)counters, order);
 }
 
+// the blame table and its order handed to the caller: one launch for both
+__global__ __launch_bounds__(256) void k_blame_out(const i64* __restrict__ blame, const u32* __restrict__ order_in,
+                                                   u32 n_ranks, i64* __restrict__ table_out, u32* __restrict__ order_out) {
+  const u64 nt = (u64)CCLD_BLM_NCOL * n_ranks, stride = (u64)gridDim.x * 256;
+  for (u64 i = (u64)blockIdx.x * 256 + threadIdx.x; i < nt; i += stride) {
+    if (table_out) table_out[i] = blame[i];
+    if (order_out && i < n_ranks) order_out[i] = order_in[i];
+  }
+}
+void launch_blame_out(hipStream_t st, const int64_t* blame, const uint32_t* order_in, uint32_t n_ranks, int64_t* table_out,
+                      uint32_t* order_out) {
+  if (n_ranks == 0 || (!table_out && !order_out)) return;
+  const u64 nt = (u64)CCLD_BLM_NCOL * n_ranks;
+  const u32 blocks = (u32)std::min<u64>((nt + 255) / 256, 2048);
+  hipLaunchKernelGGL(k_blame_out, dim3(blocks), dim3(256), 0, st, blame, order_in, n_ranks, table_out, order_out);
+}
+
 // ------------------------------------------------------------------------------------------
 // The detection-group key of every collective was written with its statistics: (communicator, op,
 // floor(log2 bytes)) for a usable one, one value past every real key otherwise.  The table is in

@@ -106,6 +106,8 @@ struct GroupArgs {
   uint64_t group_cap;
   ccld_params p;
 };
+void launch_blame_out(hipStream_t st, const int64_t* blame, const uint32_t* order_in, uint32_t n_ranks, int64_t* table_out,
+                      uint32_t* order_out);
 void launch_group_heads(hipStream_t st, const uint64_t* skey, uint32_t n_rows, uint64_t no_group, uint32_t* tile_counts,
                         uint32_t* group_first, uint64_t* counters);
 void launch_group_eval(hipStream_t st, const GroupArgs& a, const uint64_t* skey, const uint32_t* sidx,
