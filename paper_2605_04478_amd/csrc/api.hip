@@ -44,6 +44,7 @@ void carve_all(ccld_ctx* c, Carver& w, uint32_t n_ranks, uint32_t n_comms, uint6
   c->topo.rank_slots = w.take<uint32_t>(n_members);
   c->topo.rank_memb4 = w.take<uint32_t>(4ull * n_ranks);
   c->topo.rank_cell4 = w.take<uint32_t>(4ull * n_ranks);
+  c->comm_info = w.take<uint2>(n_comms);
   // window
   c->win_key = w.take<uint64_t>(N);
   c->win_row = w.take<Row>(N);
@@ -340,6 +341,9 @@ ccld_status ccld_create(const ccld_params* params, const ccld_topology* topo, ui
   up(c->topo.rank_slots, rs_slot.data(), 4ull * n_members);
   up(c->topo.rank_memb4, rc4.data(), 4ull * rc4.size());
   if (!fits4) c->topo.rank_memb4 = nullptr;
+  std::vector<uint2> cinfo(topo->n_comms);
+  for (uint32_t k = 0; k < topo->n_comms; ++k) cinfo[k] = make_uint2(topo->member_off[k], topo->size[k]);
+  up(c->comm_info, cinfo.data(), sizeof(uint2) * cinfo.size());
   up(c->topo.rank_cell4, rp4.data(), 4ull * rp4.size());
   if (!fits_cell4) c->topo.rank_cell4 = nullptr;
   if (hipMemsetAsync(c->gstate, 0, sizeof(GroupState) * (uint64_t)topo->n_comms * GROUP_SLOTS, c->stream) != hipSuccess) rs = CCLD_E_HIP;
@@ -610,7 +614,7 @@ static ccld_status analyze_window_once(ccld_ctx* c, int64_t now_ns, ccld_window_
   SegArgs sa;
   std::memset(&sa, 0, sizeof(sa));
   sa.key = skey; sa.idx = sidx; sa.row = rows; sa.n = n; sa.sf = c->sf; sa.comm_size = c->topo.size;
-  sa.member_off = c->topo.member_off; sa.members_sorted = c->topo.members_sorted;
+  sa.member_off = c->topo.member_off; sa.members_sorted = c->topo.members_sorted; sa.comm_info = c->comm_info;
   sa.tile_heads = c->tile_heads; sa.seg = o->seg; sa.seg_cap = o->seg_cap;
   sa.rec_flag = o->rec_flag ? o->rec_flag : c->rec_flag;
   sa.lag_e = o->lag_enter; sa.lag_x = o->lag_exit; sa.flag_lag = c->flag_lag; sa.cap_n = c->cap;

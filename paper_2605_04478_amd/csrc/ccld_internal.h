@@ -135,6 +135,7 @@ struct ccld_ctx {
   uint32_t* group_first;              // [cap + 1]
   uint32_t* alert_list;               // [cap]
   uint32_t* alert_ncand;              // [cap + 1]
+  uint2* comm_info;                   // [n_comms] (first member index, members) of every communicator: one load for both
   ccld::GroupState* gstate;           // [n_comms][GROUP_SLOTS]
   uint64_t* counters;                 // [CNT_COUNT] device
   uint32_t max_comm_size;             // members of the largest communicator

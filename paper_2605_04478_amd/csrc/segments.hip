@@ -169,16 +169,18 @@ struct DenseLane {
   lds_i64* stage;
   bool staged;
 };
-// A staged table row: the 21 columns, then the detection-group key and the range T_max - T_min.  The rows of
-// consecutive collectives lie a multiple of 256 bytes apart; each starts STAGE_SKEW(k) words into its 32-word
-// region, so that the lanes that later read one column of 64 rows spread over eight bank pairs, and the columns
-// of one row keep constant offsets from the row's pointer.
+// A staged table row: the 21 columns, then the detection-group key and the range T_max - T_min, at constant
+// offsets from the row's pointer.  k_seg_wave keeps the rows STAGE_COLS words apart (an odd stride).  In
+// k_dense_stats a row lies in its collective's own cells, a multiple of 256 bytes from its neighbours, and
+// starts stage_skew(k) words into that region, so that the lanes that later read one column of 64 rows
+// spread over eight bank pairs.
 constexpr u32 STAGE_COLS = CCLD_SEG_NCOL + 2, STAGE_REGION = 32;
 __device__ __forceinline__ u32 stage_skew(u32 k) { return k & 7u; }
 static_assert(STAGE_COLS + 7 <= STAGE_REGION, "a skewed row fits its region");
 
 // Table rows of the collectives of one wavefront pass (called by the first lane of every collective; the rows of a
-// pass are consecutive).  The columns are written from one wavefront-uniform pointer that steps from column to column,
+// pass are consecutive).  A staged row goes to LDS and the workgroup writes it out later; a row that is not staged
+// is written here: the columns are written from one wavefront-uniform pointer that steps from column to column,
 // plus a 32-bit byte offset per lane: no 64-bit address arithmetic per lane and column, and the kernel arguments need
 // not stay in scalar registers across the whole pass (212 spilled scalar registers become 20).  Storing G words of
 // a row per instruction from the G lanes of its group (3 instead of 23 store instructions at G = 8) was measured
@@ -428,16 +430,18 @@ __device__ __forceinline__ void seg_wave_batches(const SegArgs& a, u32 base, u32
     L.staged = sl < SEG_STAGE_ROWS;
     L.stage = (lds_i64*)s_stage + sl * STAGE_COLS;
     u64 key = 0;
+    u32 size = 0;
     if (L.valid) {
       key = a.key[L.j];
       const Row rw = load_row(a, L.j);
-      // the slot -> rank lookup overlaps the row gather
-      L.rank = a.members_sorted[a.member_off[(u32)(key >> (mb + a.sf.ws))] + (u32)(key & mmask)];
+      // first member and size of the communicator in one load; the slot -> rank lookup overlaps the row gather
+      const uint2 ci = a.comm_info[(u32)(key >> (mb + a.sf.ws))];
+      L.rank = a.members_sorted[ci.x + (u32)(key & mmask)];
+      size = ci.y;
       L.e = rw.t_enter; L.x = rw.t_exit; L.nb = rw.bytes; L.op = rw.op;
     }
     L.comm = (u32)(key >> (mb + a.sf.ws));
     L.seq = ((key >> mb) & smask) + a.sf.seq_base;
-    const u32 size = L.valid ? a.comm_size[L.comm] : 0u;
     // offsets from the arrival of the collective's first record
     const i64 ref = shfl_i64(L.e, (int)gbase);
     const i64 oe = L.e - ref, ox = L.x - ref;

@@ -41,6 +41,7 @@ struct SegArgs {
   SqueezedFormat sf;
   const uint32_t* comm_size;
   const uint32_t *member_off, *members_sorted;   // key slot -> rank
+  const uint2* comm_info;    // [n_comms] (member_off, comm_size) side by side
   uint32_t* tile_heads;      // [tiles + 1] head counts, then (after the scan) first segment ordinal of each tile
   int64_t* seg;
   uint64_t seg_cap;
